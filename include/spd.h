@@ -1,0 +1,162 @@
+/*
+ * spd.h - C ABI of the Secure Partitioned Decoding (SPD) decode-attention library for AMD MI355X (gfx950).
+ *
+ * SPD splits the attention of one decode step between two owners of the KV cache
+ * (paper section 4, protocol step 3; section 4.2, Theorem 1):
+ *
+ *   - each user's process holds that user's *private* KV cache (the prompt) and answers a query with a
+ *     partial attention over it                                   -> spd_partial_attn_private
+ *   - the service process holds the *public* KV cache (generated tokens) of all users and computes the
+ *     same kind of partial for every user in one batch            -> spd_partial_attn_public_batched
+ *   - the service merges the two partials so that the result equals softmax attention over the
+ *     concatenated cache (Theorem 1, stabilised as in the last paragraph of section 4.2)
+ *                                                                  -> spd_lse_merge
+ *
+ * A partial is the pair (A, lse): A = softmax(s) V over the owner's tokens and lse = ln sum_i exp(s_i),
+ * with scores s_i = scale * <q, k_i>.  In the paper's notation lse = m + ln(gamma); carrying lse instead of
+ * (m, gamma) keeps the merge free of the overflow that alpha = exp(m_out - m_in) has in fp32.
+ *
+ * Conventions common to all calls
+ *   - Every pointer marked DEVICE is memory of the HIP device the context was created on; HOST pointers are
+ *     ordinary host memory read during the call only.  The library keeps no caller pointer after a call returns
+ *     (it may keep *copies* of the small host arrays to recognise a repeated view, see below).
+ *   - The caller owns all tensors and the stream.  Calls validate on the host, enqueue work on `hip_stream`
+ *     (a hipStream_t passed as void*; NULL is the default stream) and return without synchronising.
+ *   - Query head h reads KV head h / (n_q_heads / n_kv_heads).  The head_dim axis is unit stride everywhere.
+ *   - Outputs are fp32 and fully overwritten.  An owner that holds no token for a user returns A = 0 and
+ *     lse = -inf for that user's rows; this is legal, not an error.
+ *   - Return value: SPD_OK or a negative error code; on any validation error nothing is launched.
+ *   - Calls on one context that use the same entry point must not overlap in time (they share scratch memory);
+ *     the private and the public call may run concurrently on two streams.
+ */
+#ifndef SPD_H
+#define SPD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SPD_OK 0
+#define SPD_ERR_NULL (-1)      /* a required pointer is NULL                                         */
+#define SPD_ERR_SHAPE (-2)     /* unsupported dtype / head counts / head_dim / block size            */
+#define SPD_ERR_LEN (-3)       /* negative count or length, or a paged length beyond max_blocks      */
+#define SPD_ERR_ALIGN (-4)     /* a base pointer or stride breaks the 16-byte row alignment          */
+#define SPD_ERR_WORKSPACE (-5) /* scratch memory could not be (re)allocated                          */
+#define SPD_ERR_HIP (-6)       /* a HIP runtime call failed; see spd_last_hip_error                  */
+#define SPD_ERR_NOMEM (-7)     /* host allocation failed                                             */
+
+enum { SPD_F32 = 0, SPD_BF16 = 1 };
+
+/* Opaque library context: device id, scratch memory for split partials, cached schedules. */
+typedef struct spd_ctx spd_ctx;
+
+/* Attention shape shared by q, K and V of one call. */
+typedef struct spd_shape {
+    int32_t dtype;      /* SPD_F32 or SPD_BF16: element type of q, K and V                            */
+    int32_t n_q_heads;  /* Hq                                                                         */
+    int32_t n_kv_heads; /* Hkv, must divide Hq; Hq / Hkv in {1,2,4,8} (fp32) or 1..16 (bf16)          */
+    int32_t head_dim;   /* d: 128 for SPD_BF16; 64 or 128 for SPD_F32                                 */
+    float scale;        /* multiplies <q,k> before the softmax; 1/sqrt(d) in the usual case           */
+} spd_shape;
+
+/*
+ * One owner's KV cache for n_users users.
+ *
+ * Contiguous mode (block_size == 0): user u's K and V start at k_ptrs[u] / v_ptrs[u]; element (token i, KV head j,
+ * channel c) is at offset i*token_stride + j*head_stride + c (in elements).  Buffers of different users may be
+ * separate allocations.  A user with lens[u] == 0 may have NULL pointers.
+ *
+ * Paged mode (block_size == 16): element (token i, head j, channel c) of user u is at
+ * pool + block_table[u*max_blocks + i/16]*block_stride + j*head_stride + (i%16)*token_stride + c.
+ * The table lives on the device and only entries [0, ceil(lens[u]/16)) of each row are read; they must name
+ * pages inside the pool (the library cannot check device-resident entries).
+ */
+typedef struct spd_kv_view {
+    int32_t n_users;
+    const int32_t *lens;        /* HOST [n_users] tokens held per user, >= 0                              */
+    const void *const *k_ptrs;  /* HOST array [n_users] of DEVICE pointers (contiguous mode)              */
+    const void *const *v_ptrs;  /* HOST array [n_users] of DEVICE pointers (contiguous mode)              */
+    int64_t token_stride;       /* elements, multiple of 16 bytes                                         */
+    int64_t head_stride;        /* elements, multiple of 16 bytes                                         */
+    const void *k_pool;         /* DEVICE (paged mode)                                                    */
+    const void *v_pool;         /* DEVICE (paged mode)                                                    */
+    int32_t block_size;         /* 0 = contiguous, 16 = paged                                             */
+    const int32_t *block_table; /* DEVICE [n_users][max_blocks] (paged mode)                              */
+    int32_t max_blocks;
+    int64_t block_stride;       /* elements between pages, multiple of 16 bytes                           */
+} spd_kv_view;
+
+/* Create a context on HIP device `hip_device` (host call; allocates a small amount of device memory). */
+int spd_create(spd_ctx **out, int hip_device);
+
+/* Synchronise the device and free everything the context owns. */
+int spd_destroy(spd_ctx *ctx);
+
+/* Static description of an error code. */
+const char *spd_strerror(int code);
+
+/* hipError_t of the last failed HIP call made through this context (0 if none). */
+int spd_last_hip_error(const spd_ctx *ctx);
+
+/*
+ * Private partial attention (protocol step 3b; A_in of Theorem 1): for every user u of `priv` and query head h,
+ *   out[u][h][:] = softmax(scale * q[u][h] . K_in[u]^T) V_in[u],   lse[u][h] = ln sum_i exp(scale * <q[u][h], k_i>).
+ * A user's rows depend only on that user's q row and buffers, so n_users == 1 is the paper's per-process call and
+ * n_users > 1 computes many users' private partials in one launch.
+ *   q    DEVICE [n_users][Hq][d], shape->dtype, 16-byte aligned
+ *   out  DEVICE [n_users][Hq][d] fp32        lse  DEVICE [n_users][Hq] fp32
+ * Long caches are split into chunks internally; chunk partials are combined with the n-way form of Theorem 1.
+ */
+int spd_partial_attn_private(spd_ctx *ctx, const spd_shape *shape, const void *q, const spd_kv_view *priv,
+                             float *out, float *lse, void *hip_stream);
+
+/*
+ * Public batched partial attention (protocol step 3c; A_out of Theorem 1): the same quantity over the service's
+ * output-token cache, for all users in one batch.  Arguments as for spd_partial_attn_private.
+ */
+int spd_partial_attn_public_batched(spd_ctx *ctx, const spd_shape *shape, const void *q, const spd_kv_view *pub,
+                                    float *out, float *lse, void *hip_stream);
+
+/*
+ * Merge two partials row by row (Theorem 1 with the coefficients of section 4.2 rewritten on log-sum-exps):
+ *   lse = logaddexp(lse0, lse1); w0 = exp(lse0 - lse); w1 = exp(lse1 - lse); y = w0*a0 + w1*a1.
+ * A row whose lse is -inf on one side takes the other side unchanged; -inf on both sides gives y = 0, lse = -inf,
+ * w0 = 0.  n_rows = n_users * Hq.  All arrays DEVICE fp32: a0, a1, y [n_rows][head_dim]; lse0, lse1 [n_rows];
+ * lse_out and w0_out ([n_rows], the merged log-sum-exp and the weight of side 0) may be NULL.  y may alias a0 or a1.
+ * head_dim must be a multiple of 4 and at most 1024.
+ */
+int spd_lse_merge(spd_ctx *ctx, int32_t n_rows, int32_t head_dim, const float *a0, const float *lse0,
+                  const float *a1, const float *lse1, float *y, float *lse_out, float *w0_out, void *hip_stream);
+
+/* ------------------------------------------------------------------------------------------------------------
+ * Host-only helpers (no GPU needed): the argument checks and the split schedule the calls above use.
+ */
+
+/* The validation every partial-attention call performs first.  Returns SPD_OK or the error the call would return. */
+int spd_validate_partial(const spd_shape *shape, const void *q, const spd_kv_view *view, const float *out,
+                         const float *lse);
+
+/* One unit of split work: tokens [t_begin, t_end) of one (user, KV head); `slot` indexes the partial it writes. */
+typedef struct spd_work_item {
+    int32_t user, kv_head, t_begin, t_end;
+    int32_t slot;      /* partial index: row_first_slot + chunk                                             */
+    int32_t n_chunks;  /* chunks of this (user, KV head); 1 means the item writes the final result itself    */
+    int32_t chunk;     /* index of this chunk within its row                                                */
+    int32_t reserved;
+} spd_work_item;
+
+/*
+ * Build the split schedule for `lens` (HOST, [n_users]) on a device with `n_compute_units` CUs.
+ * Every token of every (user, KV head) is covered by exactly one item; chunk boundaries are multiples of 32 tokens.
+ * items may be NULL to query the count.  On return *n_items is the number of items (written only if it fits
+ * `capacity`, else SPD_ERR_WORKSPACE) and *chunk_tokens the target chunk length chosen.
+ */
+int spd_build_schedule(const spd_shape *shape, int32_t n_users, const int32_t *lens, int32_t n_compute_units,
+                       spd_work_item *items, int64_t capacity, int64_t *n_items, int32_t *chunk_tokens);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPD_H */

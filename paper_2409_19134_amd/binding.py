@@ -1,0 +1,222 @@
+"""Thin ctypes binding of the C ABI in include/spd.h (argument marshalling only).
+
+Every step of the path runs in the HIP library; there is no Python or CPU fallback.  Importing this
+module without the built library raises, and so does any call without a GPU.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libspd_hip.so")
+
+SPD_OK = 0
+SPD_ERR_NULL, SPD_ERR_SHAPE, SPD_ERR_LEN, SPD_ERR_ALIGN = -1, -2, -3, -4
+SPD_ERR_WORKSPACE, SPD_ERR_HIP, SPD_ERR_NOMEM = -5, -6, -7
+SPD_F32, SPD_BF16 = 0, 1
+
+EXPORTED_SYMBOLS = (
+    "spd_create", "spd_destroy", "spd_strerror", "spd_last_hip_error",
+    "spd_partial_attn_private", "spd_partial_attn_public_batched", "spd_lse_merge",
+    "spd_validate_partial", "spd_build_schedule",
+)
+
+
+class SpdError(RuntimeError):
+    def __init__(self, code: int, where: str, hip: int = 0):
+        self.code = code
+        msg = f"{where}: {spd_strerror(code)} (code {code})"
+        if hip:
+            msg += f", hipError {hip}"
+        super().__init__(msg)
+
+
+class spd_shape(C.Structure):
+    _fields_ = [("dtype", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("scale", C.c_float)]
+
+
+class spd_kv_view(C.Structure):
+    _fields_ = [("n_users", C.c_int32), ("lens", C.POINTER(C.c_int32)),
+                ("k_ptrs", C.POINTER(C.c_void_p)), ("v_ptrs", C.POINTER(C.c_void_p)),
+                ("token_stride", C.c_int64), ("head_stride", C.c_int64),
+                ("k_pool", C.c_void_p), ("v_pool", C.c_void_p), ("block_size", C.c_int32),
+                ("block_table", C.c_void_p), ("max_blocks", C.c_int32), ("block_stride", C.c_int64)]
+
+
+class spd_work_item(C.Structure):
+    _fields_ = [("user", C.c_int32), ("kv_head", C.c_int32), ("t_begin", C.c_int32), ("t_end", C.c_int32),
+                ("slot", C.c_int32), ("n_chunks", C.c_int32), ("chunk", C.c_int32), ("reserved", C.c_int32)]
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'` "
+                          "(the SPD path has no fallback)")
+    lib = C.CDLL(LIB_PATH)
+    vp, fp = C.c_void_p, C.c_void_p
+    lib.spd_create.restype = C.c_int
+    lib.spd_create.argtypes = [C.POINTER(vp), C.c_int]
+    lib.spd_destroy.restype = C.c_int
+    lib.spd_destroy.argtypes = [vp]
+    lib.spd_strerror.restype = C.c_char_p
+    lib.spd_strerror.argtypes = [C.c_int]
+    lib.spd_last_hip_error.restype = C.c_int
+    lib.spd_last_hip_error.argtypes = [vp]
+    for name in ("spd_partial_attn_private", "spd_partial_attn_public_batched"):
+        fn = getattr(lib, name)
+        fn.restype = C.c_int
+        fn.argtypes = [vp, C.POINTER(spd_shape), vp, C.POINTER(spd_kv_view), fp, fp, vp]
+    lib.spd_lse_merge.restype = C.c_int
+    lib.spd_lse_merge.argtypes = [vp, C.c_int32, C.c_int32, fp, fp, fp, fp, fp, fp, fp, vp]
+    lib.spd_validate_partial.restype = C.c_int
+    lib.spd_validate_partial.argtypes = [C.POINTER(spd_shape), vp, C.POINTER(spd_kv_view), fp, fp]
+    lib.spd_build_schedule.restype = C.c_int
+    lib.spd_build_schedule.argtypes = [C.POINTER(spd_shape), C.c_int32, C.POINTER(C.c_int32), C.c_int32,
+                                       C.POINTER(spd_work_item), C.c_int64, C.POINTER(C.c_int64),
+                                       C.POINTER(C.c_int32)]
+    return lib
+
+
+lib = _load()
+
+
+def spd_strerror(code: int) -> str:
+    return lib.spd_strerror(int(code)).decode()
+
+
+def make_shape(dtype, n_q_heads: int, n_kv_heads: int, head_dim: int, scale: float) -> spd_shape:
+    if isinstance(dtype, torch.dtype):
+        dtype = {torch.float32: SPD_F32, torch.bfloat16: SPD_BF16}[dtype]
+    return spd_shape(int(dtype), int(n_q_heads), int(n_kv_heads), int(head_dim), float(scale))
+
+
+class KVView:
+    """Marshalled spd_kv_view; keeps the host arrays (and the tensors they point into) alive."""
+
+    def __init__(self, lens, token_stride: int, head_stride: int, k: Optional[Sequence[torch.Tensor]] = None,
+                 v: Optional[Sequence[torch.Tensor]] = None, k_pool: Optional[torch.Tensor] = None,
+                 v_pool: Optional[torch.Tensor] = None, block_table: Optional[torch.Tensor] = None,
+                 block_size: int = 0, block_stride: int = 0, max_blocks: Optional[int] = None):
+        self.lens = np.ascontiguousarray(lens, dtype=np.int32)
+        n = int(self.lens.shape[0])
+        self._keep = (k, v, k_pool, v_pool, block_table)
+        st = spd_kv_view()
+        st.n_users = n
+        st.lens = self.lens.ctypes.data_as(C.POINTER(C.c_int32))
+        st.token_stride, st.head_stride = int(token_stride), int(head_stride)
+        st.block_size, st.block_stride = int(block_size), int(block_stride)
+        if block_size == 0:
+            assert k is not None and v is not None and len(k) == n == len(v)
+            self._kp = (C.c_void_p * max(1, n))(*[t.data_ptr() if t.numel() else None for t in k])
+            self._vp = (C.c_void_p * max(1, n))(*[t.data_ptr() if t.numel() else None for t in v])
+            st.k_ptrs = C.cast(self._kp, C.POINTER(C.c_void_p))
+            st.v_ptrs = C.cast(self._vp, C.POINTER(C.c_void_p))
+        else:
+            st.k_pool, st.v_pool = k_pool.data_ptr(), v_pool.data_ptr()
+            st.block_table = block_table.data_ptr()
+            st.max_blocks = int(block_table.shape[1] if max_blocks is None else max_blocks)
+        self.struct = st
+
+    @classmethod
+    def from_side(cls, side) -> "KVView":
+        """From a workloads.KVSide (tensors already on the GPU)."""
+        if side.paged:
+            return cls(side.lens, side.token_stride, side.head_stride, k_pool=side.k_pool, v_pool=side.v_pool,
+                       block_table=side.block_table, block_size=16, block_stride=side.block_stride)
+        return cls(side.lens, side.token_stride, side.head_stride, k=side.k, v=side.v)
+
+
+def _stream_ptr(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+class Context:
+    """Owns an spd_ctx on one device."""
+
+    def __init__(self, device: int = 0):
+        h = C.c_void_p()
+        rc = lib.spd_create(C.byref(h), int(device))
+        if rc != SPD_OK:
+            raise SpdError(rc, "spd_create")
+        self.handle = h
+        self.device = int(device)
+
+    def close(self):
+        if self.handle:
+            lib.spd_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc: int, where: str):
+        if rc != SPD_OK:
+            raise SpdError(rc, where, lib.spd_last_hip_error(self.handle) if rc == SPD_ERR_HIP else 0)
+
+    def _partial(self, fn, name, shape: spd_shape, q: torch.Tensor, view: KVView, out, lse, stream):
+        n, Hq, d = view.struct.n_users, shape.n_q_heads, shape.head_dim
+        if out is None:
+            out = torch.empty((n, Hq, d), device=q.device, dtype=torch.float32)
+        if lse is None:
+            lse = torch.empty((n, Hq), device=q.device, dtype=torch.float32)
+        assert q.is_contiguous() and out.is_contiguous() and lse.is_contiguous()
+        assert tuple(q.shape) == (n, Hq, d) and tuple(out.shape) == (n, Hq, d) and tuple(lse.shape) == (n, Hq)
+        assert out.dtype == torch.float32 and lse.dtype == torch.float32
+        rc = fn(self.handle, C.byref(shape), q.data_ptr(), C.byref(view.struct), out.data_ptr(), lse.data_ptr(),
+                _stream_ptr(stream))
+        self._check(rc, name)
+        return out, lse
+
+    def spd_partial_attn_private(self, shape, q, view, out=None, lse=None, stream=None):
+        return self._partial(lib.spd_partial_attn_private, "spd_partial_attn_private", shape, q, view, out, lse, stream)
+
+    def spd_partial_attn_public_batched(self, shape, q, view, out=None, lse=None, stream=None):
+        return self._partial(lib.spd_partial_attn_public_batched, "spd_partial_attn_public_batched", shape, q, view,
+                             out, lse, stream)
+
+    def spd_lse_merge(self, a0, lse0, a1, lse1, y=None, lse_out=None, w0_out=None, stream=None):
+        n_rows = lse0.numel()
+        d = a0.shape[-1]
+        if y is None:
+            y = torch.empty_like(a0)
+        for t in (a0, a1, y, lse0, lse1):
+            assert t.is_contiguous() and t.dtype == torch.float32
+        assert a0.numel() == n_rows * d == a1.numel() == y.numel() and lse1.numel() == n_rows
+        rc = lib.spd_lse_merge(self.handle, n_rows, d, a0.data_ptr(), lse0.data_ptr(), a1.data_ptr(), lse1.data_ptr(),
+                               y.data_ptr(), None if lse_out is None else lse_out.data_ptr(),
+                               None if w0_out is None else w0_out.data_ptr(), _stream_ptr(stream))
+        self._check(rc, "spd_lse_merge")
+        return y
+
+
+def spd_validate_partial(shape: spd_shape, q_ptr, view: spd_kv_view, out_ptr, lse_ptr) -> int:
+    return int(lib.spd_validate_partial(C.byref(shape), q_ptr, C.byref(view), out_ptr, lse_ptr))
+
+
+def spd_build_schedule(shape: spd_shape, lens, n_compute_units: int):
+    """Host-only: the split schedule for `lens`.  Returns (list of item dicts, chunk_tokens)."""
+    lens = np.ascontiguousarray(lens, dtype=np.int32)
+    n = C.c_int64(0)
+    chunk = C.c_int32(0)
+    lp = lens.ctypes.data_as(C.POINTER(C.c_int32))
+    rc = lib.spd_build_schedule(C.byref(shape), len(lens), lp, n_compute_units, None, 0, C.byref(n), C.byref(chunk))
+    if rc != SPD_OK:
+        raise SpdError(rc, "spd_build_schedule")
+    items = (spd_work_item * max(1, n.value))()
+    rc = lib.spd_build_schedule(C.byref(shape), len(lens), lp, n_compute_units, items, n.value, C.byref(n),
+                                C.byref(chunk))
+    if rc != SPD_OK:
+        raise SpdError(rc, "spd_build_schedule")
+    fields = [f[0] for f in spd_work_item._fields_]
+    return [{f: getattr(items[i], f) for f in fields} for i in range(n.value)], int(chunk.value)

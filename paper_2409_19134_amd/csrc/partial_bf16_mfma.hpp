@@ -1,0 +1,251 @@
+// Partial attention over one chunk of one (user, KV head): bf16 K/V, head_dim 128, MFMA path.
+//
+// What it computes (paper section 4.2): for each of the G query heads that share this KV head,
+//   A = softmax(s) V and lse = ln sum exp(s) over the chunk's tokens, s_i = scale * <q, k_i>,
+// i.e. one owner's term of Theorem 1 restricted to a token range.  Chunks of one row are later
+// combined with the n-way form of the same theorem (combine.hpp).
+//
+// Mapping onto a 64-lane wave (r = lane % 16, grp = lane / 16), 32 tokens per step:
+//   S^T = K . Q^T   two v_mfma_f32_16x16x32_bf16 chains (4 MFMAs each, 128 channels):
+//                   the A operand is K as loaded (lane reads 16 B = 8 channels of token row r),
+//                   the B operand is Q (head r, rows >= G are zero).  The result lands with
+//                   head = r and tokens tb + grp*8 + e (e = 0..7) in each lane.
+//   softmax         online (running max m, running sum l) per lane; the max is made uniform across the
+//                   four lane groups of a head with two cross-lane exchanges per step.
+//   O^T += V^T P^T  eight MFMA pairs (one per channel phase cc): the A operand V^T needs 8 tokens of one
+//                   channel per lane; the lane loaded 8 channels of 8 tokens (16 B each, full 256 B rows
+//                   per 16 lanes), so the operand is formed in registers with v_perm_b32 (no LDS).
+//                   P is split into bf16 hi + lo so the product keeps ~16 mantissa bits.
+//                   The B operand P^T is exactly the lane's own 8 probabilities.
+// Every K/V byte is read once per KV head (all G heads share the tile) with 16-byte loads.
+// The four waves of a workgroup take interleaved 32-token steps and are combined through LDS.
+#pragma once
+#include "common.hpp"
+
+namespace spd {
+
+struct TileRegs {
+    u32x4 k[2][4];  // [S tile a][channel block kk]: token row r of tile a, channels kk*32 + grp*8 .. +8
+    u32x4 v[8];     // [e]: token tb + grp*8 + e, channels r*8 .. +8
+};
+
+struct LaneConst {
+    int r, grp;
+    const char *k_base;  // contiguous: user's K + head offset; paged: pool + head offset
+    const char *v_base;
+    const int32_t *bt_row;
+    int64_t token_stride, block_stride;
+};
+
+template <bool PAGED>
+__device__ __forceinline__ void load_tile(TileRegs &T, const LaneConst &L, int tb, int t_last)
+{
+    const int gk = tb + (L.r >> 2) * 8;  // first token of the 8-token group this lane's K rows fall in
+    const int gv = tb + L.grp * 8;       // first token of the group this lane's V rows fall in
+    const char *kp = L.k_base, *vp = L.v_base;
+    if (PAGED) {
+        // an 8-token group never straddles a 16-token page; clamping keeps the lookup inside the user's pages
+        kp += (int64_t)L.bt_row[min(gk, t_last) >> 4] * L.block_stride;
+        vp += (int64_t)L.bt_row[min(gv, t_last) >> 4] * L.block_stride;
+    }
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+        const int t = min(gk + a * 4 + (L.r & 3), t_last);  // rows past the chunk re-read its last token (masked later)
+        const char *p = kp + (int64_t)(PAGED ? (t & 15) : t) * L.token_stride + L.grp * 16;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+            T.k[a][kk] = *reinterpret_cast<const u32x4 *>(p + kk * 64);
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const int t = min(gv + e, t_last);
+        const char *p = vp + (int64_t)(PAGED ? (t & 15) : t) * L.token_stride + L.r * 16;
+        T.v[e] = *reinterpret_cast<const u32x4 *>(p);
+    }
+}
+
+__device__ __forceinline__ void compute_tile(const TileRegs &T, const bf16x8 (&qB)[4], int tb, int grp, int t_end,
+                                             float c, float &m, float &l, f32x4 (&acc)[8])
+{
+    f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+        s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, T.k[0][kk]), qB[kk], s0, 0, 0, 0);
+        s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, T.k[1][kk]), qB[kk], s1, 0, 0, 0);
+    }
+    // scores in log2 units; tokens past the chunk end get -inf
+    const int t0 = tb + grp * 8;
+    float x[8];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        x[e] = (t0 + e < t_end) ? s0[e] * c : -INFINITY;
+        x[4 + e] = (t0 + 4 + e < t_end) ? s1[e] * c : -INFINITY;
+    }
+    float mt = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+    mt = wave_xor_max(mt, 16);
+    mt = wave_xor_max(mt, 32);
+    const float m_new = fmaxf(m, mt);  // finite: every step holds at least one token of the chunk
+    const float alpha = fast_exp2(m - m_new);
+    float p[8], ps = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        p[e] = fast_exp2(x[e] - m_new);
+        ps += p[e];
+    }
+    l = l * alpha + ps;
+    m = m_new;
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {  // wave-uniform: rescale only when some max moved
+#pragma unroll
+        for (int cc = 0; cc < 8; ++cc)
+            acc[cc] *= alpha;
+    }
+    bf16x8 ph, pl;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        ph[e] = (__bf16)p[e];
+        pl[e] = (__bf16)(p[e] - (float)ph[e]);
+    }
+#pragma unroll
+    for (int cc = 0; cc < 8; ++cc) {
+        const int w = cc >> 1;
+        const unsigned sel = (cc & 1) ? 0x07060302u : 0x05040100u;  // odd channel: high halves, even: low halves
+        u32x4 vt;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            vt[j] = __builtin_amdgcn_perm(T.v[2 * j + 1][w], T.v[2 * j][w], sel);  // (token 2j, token 2j+1) of channel cc
+        const bf16x8 va = __builtin_bit_cast(bf16x8, vt);
+        acc[cc] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, ph, acc[cc], 0, 0, 0);
+        acc[cc] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pl, acc[cc], 0, 0, 0);
+    }
+}
+
+constexpr int kOStride = 132;  // LDS row stride (floats) of one head's 128 channels: bank = 4*r + grp, conflict free
+
+// items: one workgroup each.  q: [U][Hq][128] bf16.  Rows with one chunk write out/lse directly,
+// others write part_o[slot][G][128] / part_lse[slot][G].
+template <bool PAGED>
+__global__ __launch_bounds__(kThreads, 2) void partial_bf16_d128_kernel(
+    const spd_work_item *__restrict__ items, KvAddr kv, const uint16_t *__restrict__ q, int Hq, int G,
+    float scale_log2e, float *__restrict__ part_o, float *__restrict__ part_lse, float *__restrict__ out,
+    float *__restrict__ lse)
+{
+    __shared__ float sm_m[kWaves][16];
+    __shared__ float sm_l[kWaves][16];
+    __shared__ float sm_o[kWaves][kMaxGroup * kOStride];
+
+    const spd_work_item it = items[blockIdx.x];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+
+    LaneConst L;
+    L.r = lane & 15;
+    L.grp = lane >> 4;
+    L.token_stride = kv.token_stride;
+    L.block_stride = kv.block_stride;
+    if (PAGED) {
+        L.k_base = kv.k_pool + (int64_t)it.kv_head * kv.head_stride;
+        L.v_base = kv.v_pool + (int64_t)it.kv_head * kv.head_stride;
+        L.bt_row = kv.block_table + (int64_t)it.user * kv.max_blocks;
+    } else {
+        L.k_base = kv.k_ptrs[it.user] + (int64_t)it.kv_head * kv.head_stride;
+        L.v_base = kv.v_ptrs[it.user] + (int64_t)it.kv_head * kv.head_stride;
+        L.bt_row = nullptr;
+    }
+
+    // Q as the B operand: head r (zero beyond G), channels kk*32 + grp*8 .. +8
+    bf16x8 qB[4];
+    {
+        const uint16_t *qrow = q + ((int64_t)it.user * Hq + (int64_t)it.kv_head * G + L.r) * 128 + L.grp * 8;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            u32x4 w = {0u, 0u, 0u, 0u};
+            if (L.r < G)
+                w = *reinterpret_cast<const u32x4 *>(qrow + kk * 32);
+            qB[kk] = __builtin_bit_cast(bf16x8, w);
+        }
+    }
+
+    float m = -INFINITY, l = 0.f;
+    f32x4 acc[8];
+#pragma unroll
+    for (int cc = 0; cc < 8; ++cc)
+        acc[cc] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const int t_last = it.t_end - 1;
+    constexpr int kStep = 32 * kWaves;
+    int tb = it.t_begin + wave * 32;
+    if (tb < it.t_end) {
+        TileRegs T0, T1;
+        load_tile<PAGED>(T0, L, tb, t_last);
+        while (true) {
+            const int tb1 = tb + kStep;
+            const bool more1 = tb1 < it.t_end;
+            if (more1)
+                load_tile<PAGED>(T1, L, tb1, t_last);
+            compute_tile(T0, qB, tb, L.grp, it.t_end, scale_log2e, m, l, acc);
+            if (!more1)
+                break;
+            const int tb2 = tb1 + kStep;
+            const bool more2 = tb2 < it.t_end;
+            if (more2)
+                load_tile<PAGED>(T0, L, tb2, t_last);
+            compute_tile(T1, qB, tb1, L.grp, it.t_end, scale_log2e, m, l, acc);
+            if (!more2)
+                break;
+            tb = tb2;
+        }
+    }
+
+    // ---- combine the lane groups (sum of l) and the four waves (LDS) ----
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+    if (L.grp == 0) {
+        sm_m[wave][L.r] = m;
+        sm_l[wave][L.r] = l;
+    }
+    __syncthreads();
+    float M = sm_m[0][L.r];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w)
+        M = fmaxf(M, sm_m[w][L.r]);
+    const float f = fast_exp2(m - M);  // wave 0 always holds tokens, so M is finite; an idle wave has m = -inf, f = 0
+    if (L.r < G) {
+        float *dst = &sm_o[wave][L.r * kOStride + L.grp * 32];
+#pragma unroll
+        for (int cc = 0; cc < 8; ++cc)
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                dst[v * 8 + cc] = acc[cc][v] * f;  // channel (4*grp + v)*8 + cc
+    }
+    __syncthreads();
+
+    const bool direct = it.n_chunks == 1;
+    const int64_t head0 = (int64_t)it.user * Hq + (int64_t)it.kv_head * G;
+    for (int idx = threadIdx.x; idx < G * 128; idx += kThreads) {
+        const int g = idx >> 7, ch = idx & 127;
+        float Mg = sm_m[0][g];
+#pragma unroll
+        for (int w = 1; w < kWaves; ++w)
+            Mg = fmaxf(Mg, sm_m[w][g]);
+        float o = 0.f, lt = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            o += sm_o[w][g * kOStride + ch];
+            lt += sm_l[w][g] * fast_exp2(sm_m[w][g] - Mg);
+        }
+        const float a = o / lt;
+        if (direct)
+            out[(head0 + g) * 128 + ch] = a;
+        else
+            part_o[((int64_t)it.slot * G + g) * 128 + ch] = a;
+        if (ch == 0) {
+            const float ls = Mg * kLn2 + logf(lt);
+            if (direct)
+                lse[head0 + g] = ls;
+            else
+                part_lse[(int64_t)it.slot * G + g] = ls;
+        }
+    }
+}
+
+}  // namespace spd

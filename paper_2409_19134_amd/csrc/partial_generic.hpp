@@ -1,0 +1,161 @@
+// Partial attention over one chunk of one (user, KV head): vector-ALU path for fp32 inputs
+// (head_dim 64 or 128) where products must be formed in fp32 and the tile is too thin for MFMA.
+//
+// Computes the same quantity as the MFMA kernel (paper section 4.2: A = softmax(s) V and
+// lse = ln sum exp(s) over a token range).  A row of D channels is covered by LPR = D/4 lanes (16 bytes each),
+// so one wave reads 64/LPR full rows per load; every lane group keeps its own online-softmax state
+// (m, l, acc) for the G query heads of the KV head and the groups are merged at the end with the
+// n-way form of Theorem 1 (first across lane groups by cross-lane exchanges, then across waves in LDS).
+#pragma once
+#include "common.hpp"
+
+namespace spd {
+
+template <int D, int G>
+__global__ __launch_bounds__(kThreads) void partial_f32_kernel(
+    const spd_work_item *__restrict__ items, KvAddr kv, const float *__restrict__ q, int Hq, float scale_log2e,
+    float *__restrict__ part_o, float *__restrict__ part_lse, float *__restrict__ out, float *__restrict__ lse)
+{
+    constexpr int EPL = 4;          // fp32 elements per 16-byte lane load
+    constexpr int LPR = D / EPL;    // lanes per row: 16 (D=64) or 32 (D=128)
+    constexpr int RPW = 64 / LPR;   // rows per wave per step
+    __shared__ float sm_m[kWaves][G];
+    __shared__ float sm_l[kWaves][G];
+    __shared__ float sm_o[kWaves][G][D];
+
+    const spd_work_item it = items[blockIdx.x];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int cl = lane % LPR;      // which 4-channel slice of the row
+    const int rs = lane / LPR;      // which row of the step
+
+    const bool paged = kv.block_table != nullptr;
+    const char *k_base, *v_base;
+    const int32_t *bt_row = nullptr;
+    if (paged) {
+        k_base = kv.k_pool + (int64_t)it.kv_head * kv.head_stride;
+        v_base = kv.v_pool + (int64_t)it.kv_head * kv.head_stride;
+        bt_row = kv.block_table + (int64_t)it.user * kv.max_blocks;
+    } else {
+        k_base = kv.k_ptrs[it.user] + (int64_t)it.kv_head * kv.head_stride;
+        v_base = kv.v_ptrs[it.user] + (int64_t)it.kv_head * kv.head_stride;
+    }
+
+    float qr[G][EPL];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const f32x4 w = *reinterpret_cast<const f32x4 *>(
+            q + ((int64_t)it.user * Hq + (int64_t)it.kv_head * G + g) * D + cl * EPL);
+#pragma unroll
+        for (int e = 0; e < EPL; ++e)
+            qr[g][e] = w[e];
+    }
+
+    float m[G], l[G], acc[G][EPL];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        m[g] = -INFINITY;
+        l[g] = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e)
+            acc[g][e] = 0.f;
+    }
+
+    const int t_last = it.t_end - 1;
+    for (int tb = it.t_begin + wave * RPW; tb < it.t_end; tb += RPW * kWaves) {
+        const int t = tb + rs;
+        const int tc = min(t, t_last);
+        int64_t off;
+        if (paged)
+            off = (int64_t)bt_row[tc >> 4] * kv.block_stride + (int64_t)(tc & 15) * kv.token_stride;
+        else
+            off = (int64_t)tc * kv.token_stride;
+        off += cl * 16;
+        const f32x4 kk = *reinterpret_cast<const f32x4 *>(k_base + off);
+        const f32x4 vv = *reinterpret_cast<const f32x4 *>(v_base + off);
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            float s = qr[g][0] * kk[0];
+            s = fmaf(qr[g][1], kk[1], s);
+            s = fmaf(qr[g][2], kk[2], s);
+            s = fmaf(qr[g][3], kk[3], s);
+#pragma unroll
+            for (int o = 1; o < LPR; o <<= 1)
+                s += __shfl_xor(s, o);          // all LPR lanes of the row end up with the full dot product
+            if (t < it.t_end) {
+                const float x = s * scale_log2e;
+                const float m_new = fmaxf(m[g], x);
+                const float alpha = fast_exp2(m[g] - m_new);
+                const float p = fast_exp2(x - m_new);
+                l[g] = l[g] * alpha + p;
+#pragma unroll
+                for (int e = 0; e < EPL; ++e)
+                    acc[g][e] = fmaf(p, vv[e], acc[g][e] * alpha);
+                m[g] = m_new;
+            }
+        }
+    }
+
+    // merge the RPW lane groups of the wave (they hold disjoint token subsets)
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        float mw = m[g];
+#pragma unroll
+        for (int o = LPR; o < 64; o <<= 1)
+            mw = fmaxf(mw, __shfl_xor(mw, o));
+        const float f = (mw == -INFINITY) ? 0.f : fast_exp2(m[g] - mw);
+        float lw = l[g] * f;
+        float a[EPL];
+#pragma unroll
+        for (int e = 0; e < EPL; ++e)
+            a[e] = acc[g][e] * f;
+#pragma unroll
+        for (int o = LPR; o < 64; o <<= 1) {
+            lw += __shfl_xor(lw, o);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e)
+                a[e] += __shfl_xor(a[e], o);
+        }
+        if (rs == 0) {
+            if (cl == 0) {
+                sm_m[wave][g] = mw;
+                sm_l[wave][g] = lw;
+            }
+#pragma unroll
+            for (int e = 0; e < EPL; ++e)
+                sm_o[wave][g][cl * EPL + e] = a[e];
+        }
+    }
+    __syncthreads();
+
+    const bool direct = it.n_chunks == 1;
+    const int64_t head0 = (int64_t)it.user * Hq + (int64_t)it.kv_head * G;
+    for (int idx = threadIdx.x; idx < G * D; idx += kThreads) {
+        const int g = idx / D, ch = idx % D;
+        float Mg = sm_m[0][g];
+#pragma unroll
+        for (int w = 1; w < kWaves; ++w)
+            Mg = fmaxf(Mg, sm_m[w][g]);
+        float o = 0.f, lt = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            const float f = (sm_m[w][g] == -INFINITY) ? 0.f : fast_exp2(sm_m[w][g] - Mg);
+            o += sm_o[w][g][ch] * f;
+            lt += sm_l[w][g] * f;
+        }
+        const float a = o / lt;
+        if (direct)
+            out[(head0 + g) * D + ch] = a;
+        else
+            part_o[((int64_t)it.slot * G + g) * D + ch] = a;
+        if (ch == 0) {
+            const float ls = Mg * kLn2 + logf(lt);
+            if (direct)
+                lse[head0 + g] = ls;
+            else
+                part_lse[(int64_t)it.slot * G + g] = ls;
+        }
+    }
+}
+
+}  // namespace spd

@@ -1,0 +1,40 @@
+"""One SPD decode step for one layer: private partial, public batched partial, merge (paper section 4, step 3).
+
+Pure call sequencing over the C ABI; holds the output buffers so a step allocates nothing.
+"""
+from __future__ import annotations
+
+import torch
+
+from .binding import Context, KVView, make_shape
+
+
+class DecodeStep:
+    def __init__(self, ctx: Context, dtype, n_q_heads: int, n_kv_heads: int, head_dim: int, scale: float,
+                 private: KVView, public: KVView, device="cuda:0"):
+        self.ctx = ctx
+        self.shape = make_shape(dtype, n_q_heads, n_kv_heads, head_dim, scale)
+        self.private, self.public = private, public
+        n = private.struct.n_users
+        assert public.struct.n_users == n
+        f32 = dict(device=device, dtype=torch.float32)
+        self.a_in = torch.empty((n, n_q_heads, head_dim), **f32)
+        self.a_out = torch.empty((n, n_q_heads, head_dim), **f32)
+        self.y = torch.empty((n, n_q_heads, head_dim), **f32)
+        self.lse_in = torch.empty((n, n_q_heads), **f32)
+        self.lse_out = torch.empty((n, n_q_heads), **f32)
+        self.lse = torch.empty((n, n_q_heads), **f32)
+        self.w_in = torch.empty((n, n_q_heads), **f32)
+
+    @classmethod
+    def from_workload(cls, ctx: Context, wl) -> "DecodeStep":
+        return cls(ctx, wl.dtype, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.scale,
+                   KVView.from_side(wl.private), KVView.from_side(wl.public), device=wl.q.device)
+
+    def run(self, q: torch.Tensor, stream=None):
+        """Enqueue the three calls on `stream` (default: torch's current stream).  No synchronisation."""
+        c = self.ctx
+        c.spd_partial_attn_private(self.shape, q, self.private, self.a_in, self.lse_in, stream)
+        c.spd_partial_attn_public_batched(self.shape, q, self.public, self.a_out, self.lse_out, stream)
+        c.spd_lse_merge(self.a_in, self.lse_in, self.a_out, self.lse_out, self.y, self.lse, self.w_in, stream)
+        return self.y

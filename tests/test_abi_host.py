@@ -1,0 +1,148 @@
+"""Host-only checks of the C ABI: exported symbols, argument validation, the split schedule.  No GPU needed."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2409_19134_amd as spd
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "spd.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(spd_[a-z_]+)\s*\(", header))
+    assert declared == set(spd.EXPORTED_SYMBOLS)
+    for name in declared:
+        assert hasattr(spd.lib, name), name
+
+
+def test_strerror_is_distinct_per_code():
+    msgs = {spd.spd_strerror(c) for c in range(0, -8, -1)}
+    assert len(msgs) == 8 and spd.spd_strerror(-99) == "unknown error code"
+
+
+def _view(lens, token_stride=1024, head_stride=128, k=None, v=None, block_size=0, **kw):
+    lens = np.asarray(lens, dtype=np.int32)
+    n = len(lens)
+    st = spd.spd_kv_view()
+    st.n_users = n
+    st.lens = lens.ctypes.data_as(C.POINTER(C.c_int32))
+    st.token_stride, st.head_stride, st.block_size = token_stride, head_stride, block_size
+    kp = (C.c_void_p * max(1, n))(*(k if k is not None else [0x10000] * n))
+    vp = (C.c_void_p * max(1, n))(*(v if v is not None else [0x20000] * n))
+    st.k_ptrs = C.cast(kp, C.POINTER(C.c_void_p))
+    st.v_ptrs = C.cast(vp, C.POINTER(C.c_void_p))
+    for key, val in kw.items():
+        setattr(st, key, val)
+    st._keep = (lens, kp, vp)
+    return st
+
+
+Q, OUT, LSE = 0x1000, 0x2000, 0x3000   # fake device addresses: validation never dereferences them
+
+
+def _check(shape, view, q=Q, out=OUT, lse=LSE):
+    return spd.spd_validate_partial(shape, q, view, out, lse)
+
+
+def test_validation_accepts_good_arguments():
+    sh = spd.make_shape(spd.SPD_BF16, 32, 8, 128, 0.0884)
+    assert _check(sh, _view([5, 0, 9])) == spd.SPD_OK
+    assert _check(sh, _view([0, 0], k=[0, 0], v=[0, 0])) == spd.SPD_OK          # empty users may have NULL buffers
+    assert _check(sh, _view([])) == spd.SPD_OK
+    paged = _view([40, 1], token_stride=128, head_stride=2048, block_size=16, k_pool=0x100000, v_pool=0x200000,
+                  block_table=0x300000, max_blocks=3, block_stride=16384)
+    assert _check(sh, paged) == spd.SPD_OK
+    assert _check(spd.make_shape(spd.SPD_F32, 8, 8, 64, 0.125), _view([128], token_stride=512, head_stride=64)) == spd.SPD_OK
+
+
+@pytest.mark.parametrize("args,code", [
+    (dict(dtype=7), spd.SPD_ERR_SHAPE),
+    (dict(Hq=30), spd.SPD_ERR_SHAPE),                   # Hq % Hkv != 0
+    (dict(d=96), spd.SPD_ERR_SHAPE),
+    (dict(Hq=256, Hkv=8), spd.SPD_ERR_SHAPE),           # group of 32 heads
+    (dict(scale=float("nan")), spd.SPD_ERR_SHAPE),
+])
+def test_validation_rejects_bad_shapes(args, code):
+    a = dict(dtype=spd.SPD_BF16, Hq=32, Hkv=8, d=128, scale=0.1)
+    a.update(args)
+    sh = spd.make_shape(a["dtype"], a["Hq"], a["Hkv"], a["d"], a["scale"])
+    assert _check(sh, _view([5])) == code
+
+
+def test_validation_rejects_bad_views_and_pointers():
+    sh = spd.make_shape(spd.SPD_BF16, 32, 8, 128, 0.1)
+    assert _check(sh, _view([5, -1])) == spd.SPD_ERR_LEN
+    assert _check(sh, _view([5]), q=0) == spd.SPD_ERR_NULL
+    assert _check(sh, _view([5]), out=0) == spd.SPD_ERR_NULL
+    assert _check(sh, _view([5]), lse=0) == spd.SPD_ERR_NULL
+    assert _check(sh, _view([5]), q=Q + 2) == spd.SPD_ERR_ALIGN
+    assert _check(sh, _view([5], k=[0])) == spd.SPD_ERR_NULL
+    assert _check(sh, _view([5], v=[0x20008])) == spd.SPD_ERR_ALIGN
+    assert _check(sh, _view([5], token_stride=1028)) == spd.SPD_ERR_ALIGN       # rows no longer 16-byte aligned
+    assert _check(sh, _view([5], token_stride=64)) == spd.SPD_ERR_ALIGN         # rows would overlap
+    assert _check(sh, _view([5], head_stride=100)) == spd.SPD_ERR_ALIGN
+    assert _check(sh, _view([5], block_size=32)) == spd.SPD_ERR_SHAPE
+    paged = dict(token_stride=128, head_stride=2048, block_size=16, k_pool=0x100000, v_pool=0x200000,
+                 block_table=0x300000, max_blocks=3, block_stride=16384)
+    assert _check(sh, _view([49], **paged)) == spd.SPD_ERR_LEN                   # needs 4 pages, table has 3
+    assert _check(sh, _view([48], **dict(paged, block_table=0))) == spd.SPD_ERR_NULL
+    assert _check(sh, _view([48], **dict(paged, block_stride=0))) == spd.SPD_ERR_ALIGN
+    null_shape = C.POINTER(spd.spd_shape)()
+    assert spd.lib.spd_validate_partial(null_shape, Q, C.byref(_view([5])), OUT, LSE) == spd.SPD_ERR_NULL
+
+
+def test_calls_reject_null_context_without_touching_the_gpu():
+    sh = spd.make_shape(spd.SPD_BF16, 32, 8, 128, 0.1)
+    v = _view([5])
+    assert spd.lib.spd_partial_attn_private(None, C.byref(sh), Q, C.byref(v), OUT, LSE, None) == spd.SPD_ERR_NULL
+    assert spd.lib.spd_partial_attn_public_batched(None, C.byref(sh), Q, C.byref(v), OUT, LSE, None) == spd.SPD_ERR_NULL
+    assert spd.lib.spd_lse_merge(None, 4, 128, Q, Q, Q, Q, Q, None, None, None) == spd.SPD_ERR_NULL
+    assert spd.lib.spd_destroy(None) == spd.SPD_ERR_NULL
+
+
+@pytest.mark.parametrize("lens", [
+    [0], [1], [31, 32, 33], [128, 129, 4096, 0, 513], list(range(0, 700, 37)),
+    [131072, 5, 40000], [2304] * 16,
+])
+@pytest.mark.parametrize("n_cus", [1, 256])
+def test_schedule_covers_every_token_once(lens, n_cus):
+    Hkv = 8
+    sh = spd.make_shape(spd.SPD_BF16, 32, Hkv, 128, 0.1)
+    items, chunk = spd.spd_build_schedule(sh, lens, n_cus)
+    assert chunk % 128 == 0 and chunk >= 128
+    seen = {}
+    slots = set()
+    for it in items:
+        assert 0 <= it["t_begin"] < it["t_end"] <= lens[it["user"]]
+        assert it["t_begin"] % 32 == 0
+        assert it["t_end"] - it["t_begin"] <= chunk
+        seen.setdefault((it["user"], it["kv_head"]), []).append(it)
+        assert it["slot"] not in slots
+        slots.add(it["slot"])
+    for u, L in enumerate(lens):
+        for h in range(Hkv):
+            row = sorted(seen.get((u, h), []), key=lambda x: x["t_begin"])
+            if L == 0:
+                assert not row
+                continue
+            assert row[0]["t_begin"] == 0 and row[-1]["t_end"] == L
+            for a, b in zip(row, row[1:]):
+                assert a["t_end"] == b["t_begin"]
+            assert all(it["n_chunks"] == len(row) for it in row)
+            assert [it["chunk"] for it in row] == list(range(len(row)))
+            assert [it["slot"] for it in row] == list(range(row[0]["slot"], row[0]["slot"] + len(row)))
+    sizes = [it["t_end"] - it["t_begin"] for it in items]
+    assert sizes == sorted(sizes, reverse=True)          # longest first
+
+
+def test_schedule_fills_the_machine_for_the_headline_workload():
+    import workloads
+    lp, lo = workloads.draw_lengths(2, 16)
+    sh = spd.make_shape(spd.SPD_BF16, 32, 8, 128, 0.1)
+    items, chunk = spd.spd_build_schedule(sh, lp, 256)
+    assert 512 <= len(items) <= 1536            # a few workgroups per CU, one resident wave of them

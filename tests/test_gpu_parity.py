@@ -1,0 +1,257 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 CPU oracle on the same seeded inputs.
+
+Tolerances are the ones the benchmark contract states: max abs error <= 1e-5 for fp32 inputs and <= 2e-3 for
+bf16 inputs with fp32 accumulation (on A_in, A_out, Y and on the log-sum-exps).
+"""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from oracle import spd_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+TOL = {torch.float32: 1e-5, torch.bfloat16: 2e-3}
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    import paper_2409_19134_amd as spd
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    c = spd.Context(0)
+    yield c
+    torch.cuda.synchronize()
+    c.close()
+
+
+def run_step(ctx, wl):
+    import paper_2409_19134_amd as spd
+    step = spd.DecodeStep.from_workload(ctx, wl)
+    step.run(wl.q)
+    torch.cuda.synchronize()
+    return step
+
+
+def maxerr(got: torch.Tensor, want: np.ndarray) -> float:
+    g = got.detach().cpu().double().numpy().reshape(want.shape)
+    both_inf = np.isinf(g) & np.isinf(want) & (np.sign(g) == np.sign(want))
+    diff = np.where(both_inf, 0.0, np.abs(g - want))
+    assert not np.isnan(g).any(), "NaN in GPU result"
+    return float(diff.max()) if diff.size else 0.0
+
+
+def check_against_oracle(ctx, wl, rows=None, tol=None):
+    tol = TOL[wl.dtype] if tol is None else tol
+    step = run_step(ctx, wl)
+    hw = orc.from_workload(wl)
+    Y, lse = orc.attention(hw, rows=rows)
+    A_in, m_in, g_in = orc.partial(hw, hw.private, rows=rows)
+    A_out, m_out, g_out = orc.partial(hw, hw.public, rows=rows)
+    _, _, _, w_in = orc.merge(A_in, m_in, g_in, A_out, m_out, g_out)
+    if rows is None:
+        sel = slice(None)
+    else:
+        r = np.asarray(rows)
+        sel = torch.as_tensor(r[:, 0] * wl.n_q_heads + r[:, 1], device=DEV)
+    flat = lambda t: t.reshape(wl.n_users * wl.n_q_heads, -1)[sel]
+    errs = {
+        "A_in": maxerr(flat(step.a_in), A_in), "A_out": maxerr(flat(step.a_out), A_out),
+        "Y": maxerr(flat(step.y), Y),
+        "lse_in": maxerr(flat(step.lse_in), orc.lse_of(m_in, g_in)[:, None]),
+        "lse_out": maxerr(flat(step.lse_out), orc.lse_of(m_out, g_out)[:, None]),
+        "lse": maxerr(flat(step.lse), lse[:, None]),
+        "w_in": maxerr(flat(step.w_in), w_in[:, None]),
+    }
+    bad = {k: v for k, v in errs.items() if not v <= tol}
+    assert not bad, f"beyond tolerance {tol}: {bad} (all: {errs})"
+    return step, errs
+
+
+# ---------------------------------------------------------------------------
+# the five benchmark configurations at oracle-sized lengths (several tiles, ragged tails)
+
+
+def test_config1_fp32_full_size(ctx):
+    check_against_oracle(ctx, workloads.make_workload(1, DEV))
+
+
+@pytest.mark.parametrize("cfg,len_div,n_users", [(2, 4, None), (3, 64, 12), (4, 8, 48), (5, 128, 6)])
+def test_configs_reduced_lengths(ctx, cfg, len_div, n_users):
+    check_against_oracle(ctx, workloads.make_workload(cfg, DEV, len_div=len_div, n_users=n_users))
+
+
+def test_config2_full_size_all_rows(ctx):
+    """The headline workload at its real size; the oracle still finishes in seconds."""
+    check_against_oracle(ctx, workloads.make_workload(2, DEV))
+
+
+# ---------------------------------------------------------------------------
+# full-size workloads, sampled output rows
+
+
+def _sample_rows(wl, n, seed):
+    rng = np.random.default_rng(seed)
+    tot = wl.private.lens.astype(np.int64) + wl.public.lens
+    users = {int(np.argmax(tot)), int(np.argmin(tot))}
+    while len(users) < min(n, wl.n_users):
+        users.add(int(rng.integers(wl.n_users)))
+    return [(u, int(rng.integers(wl.n_q_heads))) for u in sorted(users)]
+
+
+@pytest.mark.parametrize("cfg,n", [(3, 4), (4, 8), (5, 3)])
+def test_full_size_sampled_rows(ctx, cfg, n):
+    wl = workloads.make_workload(cfg, DEV)
+    check_against_oracle(ctx, wl, rows=_sample_rows(wl, n, cfg))
+
+
+# ---------------------------------------------------------------------------
+# edge cases
+
+
+@pytest.mark.parametrize("lp,lo", [
+    ([0], [0]), ([1], [0]), ([0], [1]), ([1], [1]),
+    ([31], [33]), ([32], [32]), ([127, 128, 129], [0, 1, 2]),
+    ([0, 0, 700], [5, 0, 0]), ([513, 1025, 2049], [95, 96, 97]),
+])
+@pytest.mark.parametrize("layout,paged", [("nhd", False), ("hnd", False), ("nhd", True)])
+def test_bf16_edge_lengths(ctx, lp, lo, layout, paged):
+    wl = workloads.random_case(101, torch.bfloat16, len(lp), 32, 8, 128, lp, lo, device=DEV, layout=layout, paged=paged)
+    step, _ = check_against_oracle(ctx, wl)
+    for u in range(len(lp)):     # empty parts are exact: zeros and -inf
+        if lp[u] == 0:
+            assert (step.a_in[u] == 0).all() and torch.isneginf(step.lse_in[u]).all()
+            assert (step.w_in[u] == 0).all()
+        if lo[u] == 0:
+            assert (step.a_out[u] == 0).all() and torch.isneginf(step.lse_out[u]).all()
+        if lp[u] == 0 and lo[u] == 0:
+            assert (step.y[u] == 0).all() and torch.isneginf(step.lse[u]).all()
+        elif lo[u] == 0:
+            assert torch.equal(step.y[u], step.a_in[u])       # merging with an empty part is the identity
+        elif lp[u] == 0:
+            assert torch.equal(step.y[u], step.a_out[u])
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(8, 8), (16, 8), (64, 8), (16, 1), (12, 4)])
+def test_bf16_head_groupings(ctx, Hq, Hkv):
+    wl = workloads.random_case(103, torch.bfloat16, 3, Hq, Hkv, 128, [300, 77, 1500], [40, 0, 65], device=DEV)
+    check_against_oracle(ctx, wl)
+
+
+@pytest.mark.parametrize("d,Hq,Hkv", [(64, 8, 8), (64, 8, 2), (128, 8, 1), (128, 4, 4), (64, 16, 2)])
+@pytest.mark.parametrize("paged", [False, True])
+def test_fp32_shapes(ctx, d, Hq, Hkv, paged):
+    wl = workloads.random_case(107, torch.float32, 4, Hq, Hkv, d, [128, 0, 1000, 3], [16, 5, 0, 77], device=DEV, paged=paged)
+    check_against_oracle(ctx, wl)
+
+
+def test_peaked_softmax_and_large_score_gap(ctx):
+    """Scores spread far beyond the fp32 exp range between the two parts: weights saturate, nothing overflows."""
+    wl = workloads.random_case(109, torch.bfloat16, 2, 32, 8, 128, [256, 256], [64, 64], device=DEV, scale=1.0)
+    wl.private.k[0].mul_(6.0)        # user 0: private scores ~ N(0, 70): the max dominates
+    wl.public.k[1].mul_(8.0)         # user 1: public side dominates
+    check_against_oracle(ctx, wl)
+
+
+def test_single_user_call_equals_batched_call(ctx):
+    """A user's rows depend only on that user's buffers: the per-process call gives the same bits."""
+    import paper_2409_19134_amd as spd
+    wl = workloads.random_case(113, torch.bfloat16, 5, 32, 8, 128, [900, 31, 0, 2500, 128], [10, 300, 7, 0, 64], device=DEV)
+    step = run_step(ctx, wl)
+    sh = spd.make_shape(wl.dtype, 32, 8, 128, wl.scale)
+    for u in range(5):
+        v = spd.KVView(wl.private.lens[u:u + 1], wl.private.token_stride, wl.private.head_stride,
+                       k=[wl.private.k[u]], v=[wl.private.v[u]])
+        a, l = ctx.spd_partial_attn_private(sh, wl.q[u:u + 1].contiguous(), v)
+        torch.cuda.synchronize()
+        # the split of a user's tokens depends on the batch's total work, so compare to tolerance, not bits
+        assert (a[0] - step.a_in[u]).abs().max().item() <= 1e-5
+        fin = torch.isfinite(l[0])
+        assert torch.equal(fin, torch.isfinite(step.lse_in[u]))
+        assert (l[0][fin] - step.lse_in[u][fin]).abs().max().item() <= 1e-5 if fin.any() else True
+
+
+def test_run_to_run_determinism_and_user_permutation(ctx):
+    wl = workloads.random_case(127, torch.bfloat16, 6, 32, 8, 128, [1500, 40, 700, 0, 3000, 64], [9, 100, 0, 50, 512, 1], device=DEV)
+    s1 = run_step(ctx, wl)
+    y1, l1 = s1.y.clone(), s1.lse.clone()
+    s2 = run_step(ctx, wl)
+    assert torch.equal(s2.y, y1) and torch.equal(s2.lse, l1)
+    # permuting users permutes outputs (same chunking: total work unchanged)
+    perm = [3, 0, 5, 1, 4, 2]
+    import copy
+    wp = copy.copy(wl)
+    wp.q = wl.q[perm].contiguous()
+    for name in ("private", "public"):
+        side = copy.copy(getattr(wl, name))
+        side.lens = side.lens[perm].copy()
+        side.k = [side.k[i] for i in perm]
+        side.v = [side.v[i] for i in perm]
+        setattr(wp, name, side)
+    s3 = run_step(ctx, wp)
+    assert torch.equal(s3.y, y1[perm]) and torch.equal(s3.lse, l1[perm])
+
+
+def test_token_permutation_invariance(ctx):
+    """A decode query attends to a set of tokens: shuffling a cache's tokens (K and V together) changes nothing
+    beyond rounding."""
+    wl = workloads.random_case(131, torch.bfloat16, 1, 32, 8, 128, [777], [100], device=DEV)
+    s1 = run_step(ctx, wl)
+    y1 = s1.y.clone()
+    p = torch.randperm(777, generator=torch.Generator().manual_seed(1)).to(DEV)
+    wl.private.k[0] = wl.private.k[0][p].contiguous()
+    wl.private.v[0] = wl.private.v[0][p].contiguous()
+    s2 = run_step(ctx, wl)
+    assert (s2.y - y1).abs().max().item() <= 1e-5
+
+
+def test_merge_standalone_against_oracle(ctx):
+    rng = np.random.default_rng(7)
+    n, d = 257, 128
+    A0 = rng.standard_normal((n, d)); A1 = rng.standard_normal((n, d))
+    l0 = rng.normal(0, 30, n); l1 = rng.normal(0, 30, n)
+    l0[:5] = -np.inf; A0[:5] = 0
+    l1[3:9] = -np.inf; A1[3:9] = 0
+    l0[10], l1[10] = 500.0, -500.0
+    l0[11], l1[11] = -3000.0, 2000.0
+    l0[12] = l1[12] = 1.25
+    t = lambda a: torch.tensor(a, dtype=torch.float32, device=DEV)
+    a0, a1, t0, t1 = t(A0), t(A1), t(l0), t(l1)
+    lse = torch.empty(n, device=DEV); w = torch.empty(n, device=DEV)
+    y = ctx.spd_lse_merge(a0, t0, a1, t1, lse_out=lse, w0_out=w)
+    torch.cuda.synchronize()
+    # oracle in the paper's (m, gamma) form: m = lse, gamma = 1 (or 0 for an empty side), on the fp32-rounded inputs
+    f64 = lambda x: x.cpu().double().numpy()
+    g0 = np.where(np.isinf(f64(t0)), 0.0, 1.0); g1 = np.where(np.isinf(f64(t1)), 0.0, 1.0)
+    Y, m, g, w0 = orc.merge(f64(a0), f64(t0), g0, f64(a1), f64(t1), g1)
+    assert maxerr(y, Y) <= 1e-5
+    assert maxerr(w, w0) <= 1e-6
+    assert maxerr(lse, orc.lse_of(m, g)) <= 3e-4      # |lse| up to 3000 in fp32
+    # in-place on either input and swapped operands
+    y2 = ctx.spd_lse_merge(a1, t1, a0, t0)
+    torch.cuda.synchronize()
+    assert torch.equal(y2, y)
+    a0c = a0.clone()
+    ctx.spd_lse_merge(a0c, t0, a1, t1, y=a0c)
+    torch.cuda.synchronize()
+    assert torch.equal(a0c, y)
+
+
+def test_error_codes_from_device_calls(ctx):
+    import paper_2409_19134_amd as spd
+    wl = workloads.random_case(137, torch.bfloat16, 1, 32, 8, 128, [64], [8], device=DEV)
+    sh = spd.make_shape(wl.dtype, 32, 8, 128, wl.scale)
+    v = spd.KVView.from_side(wl.private)
+    out = torch.full((1, 32, 128), 7.0, device=DEV)
+    lse = torch.full((1, 32), 7.0, device=DEV)
+    bad = spd.make_shape(wl.dtype, 30, 8, 128, wl.scale)
+    with pytest.raises(spd.SpdError) as ei:
+        ctx._partial(spd.lib.spd_partial_attn_private, "x", bad, wl.q[:, :30].contiguous(), v,
+                     out[:, :30].contiguous(), lse[:, :30].contiguous(), None)
+    assert ei.value.code == spd.SPD_ERR_SHAPE
+    torch.cuda.synchronize()
+    assert (out == 7.0).all()           # nothing was launched
+    ctx.spd_partial_attn_private(sh, wl.q, v, out, lse)
+    torch.cuda.synchronize()
+    assert not (out == 7.0).any()
