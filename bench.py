@@ -1,0 +1,182 @@
+#!/usr/bin/env python3
+"""Benchmark of the SPD decode-attention hot path on one MI355X.
+
+A "step" is one pass of the whole path for one layer and one decode position: private partial attention for all
+users, public batched partial attention, and the merge.  Inputs are synthetic (seeded N(0,1) caches of the named
+workload) and already resident in HBM when the timed region starts.  Several copies of the KV set at distinct
+addresses are cycled through so that consecutive steps do not re-read the same lines from the 256 MB last-level
+cache.
+
+Prints ONE JSON line: whole-step KV-read throughput (algorithmic K/V bytes of both owners / time per step), the
+roofline position of the dominant kernel (the private partial-attention kernel) from HIP-event timing, and the fp64
+CPU oracle timed on the host cores as a reported baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0     # MI355X published HBM3E peak
+
+
+def clone_side(side):
+    import copy
+    c = copy.copy(side)
+    if side.paged:
+        c.k_pool, c.v_pool = side.k_pool.clone(), side.v_pool.clone()
+        c.block_table = side.block_table.clone()
+    else:
+        c.k = [t.clone() for t in side.k]
+        c.v = [t.clone() for t in side.v]
+    return c
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (2 = Llama-3-8B shape, 16 users: the headline)")
+    ap.add_argument("--copies", type=int, default=0, help="KV set copies cycled through (0 = enough for > 1 GB, at most 8)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-check", action="store_true", help="skip the parity check against the oracle")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="bound on the oracle timing leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+
+    import numpy as np
+    import torch
+    import paper_2409_19134_amd as spd
+    import workloads
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    wl = workloads.make_workload(args.config, dev)
+    kv_bytes = wl.kv_bytes
+    elt = 4 if wl.dtype == torch.float32 else 2
+    per_token = 2 * wl.n_kv_heads * wl.head_dim * elt
+    priv_bytes = wl.private.n_tokens * per_token
+    pub_bytes = wl.public.n_tokens * per_token
+
+    copies = args.copies or int(min(8, max(1, -(-1_200_000_000 // max(1, kv_bytes)))))
+    ctx = spd.Context(0)
+    steps_objs = []
+    for i in range(copies):
+        w = wl if i == 0 else None
+        if w is None:
+            import copy
+            w = copy.copy(wl)
+            w.private, w.public = clone_side(wl.private), clone_side(wl.public)
+        steps_objs.append(spd.DecodeStep.from_workload(ctx, w))
+    q = wl.q
+
+    def run(n, start=0):
+        for i in range(n):
+            steps_objs[(start + i) % copies].run(q)
+
+    # warm-up: builds and uploads every copy's schedule, grows scratch memory
+    run(max(args.warmup, copies))
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly K steps between two synchronisations ----
+    K = args.steps
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(K)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / K
+    value = kv_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # ---- the same K steps again with HIP events around the partial kernels (on the launch stream) ----
+    ctx.spd_set_kernel_timing(K)
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    run(K)
+    torch.cuda.synchronize()
+    t3 = time.perf_counter()
+    n_priv, priv_mean_us, priv_min_us = ctx.spd_get_kernel_timing(0)
+    n_pub, pub_mean_us, pub_min_us = ctx.spd_get_kernel_timing(1)
+    ctx.spd_set_kernel_timing(0)
+    ms_per_step_timed = (t3 - t2) * 1e3 / K
+    achieved = priv_bytes / (priv_mean_us * 1e-6) / 1e9 if n_priv else 0.0
+
+    out = {
+        "metric": "kv_read_hbm_GBps_per_spd_decode_step",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 6),
+        "us_per_step": round(ms_per_step * 1e3, 2),
+        "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if wl.dtype == torch.float32 else "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"config{args.config}:{wl.name}", "n_users": wl.n_users, "n_q_heads": wl.n_q_heads,
+                   "n_kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim,
+                   "private_tokens": wl.private.n_tokens, "public_tokens": wl.public.n_tokens,
+                   "kv_bytes_per_step": kv_bytes, "kv_copies_cycled": copies,
+                   "layout": "paged16" if wl.private.paged else wl.private.layout,
+                   "seeds": wl.seeds},
+        "roofline": {"bound": "hbm", "kernel": "partial_bf16_d128_kernel (private call)" if elt == 2 else "partial_f32_kernel (private call)",
+                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "bytes_per_launch": priv_bytes, "launches_timed": n_priv,
+                     "mean_us": round(priv_mean_us, 2), "min_us": round(priv_min_us, 2),
+                     "public_kernel": {"bytes_per_launch": pub_bytes, "mean_us": round(pub_mean_us, 2),
+                                       "GBps": round(pub_bytes / (pub_mean_us * 1e-6) / 1e9, 1) if n_pub else 0.0},
+                     "us_per_step_while_timed": round(ms_per_step_timed * 1e3, 2)},
+    }
+
+    if not args.no_check or not args.no_cpu_baseline:
+        from oracle import spd_oracle as orc
+        hw = orc.from_workload(wl)
+        full = args.config in (1, 2)
+        if full:
+            rows = None
+        else:   # big workloads: a bounded sample of output rows
+            rng = np.random.default_rng(args.config)
+            rows = [(int(rng.integers(wl.n_users)), int(rng.integers(wl.n_q_heads))) for _ in range(4)]
+        if not args.no_check:
+            Y, _ = orc.attention(hw, rows=rows)
+            y = steps_objs[0].y.cpu().double().numpy().reshape(wl.n_users * wl.n_q_heads, -1)
+            if rows is not None:
+                y = y[[u * wl.n_q_heads + h for u, h in rows]]
+            err = float(np.abs(y - Y).max())
+            tol = 1e-5 if elt == 4 else 2e-3
+            out["parity"] = {"max_abs_err_vs_fp64_oracle": err, "tolerance": tol, "ok": bool(err <= tol),
+                             "rows_checked": "all" if rows is None else len(rows)}
+        if not args.no_cpu_baseline:
+            # the oracle as it stands, on the host cores of this machine, on a bounded sample of the same workload
+            if full:
+                sample_rows, sample_desc = None, "whole workload, all rows"
+                sample_bytes = kv_bytes
+            else:
+                sample_rows = rows
+                # a row's share of the algorithmic bytes: its (user, kv head) K/V stream divided among the G query
+                # heads that share it (the whole job is U*Hq rows and reads every stream once)
+                toks = sum(int(wl.private.lens[u]) + int(wl.public.lens[u]) for u, _ in rows)
+                sample_bytes = toks * 2 * wl.head_dim * elt // (wl.n_q_heads // wl.n_kv_heads)
+                sample_desc = f"{len(rows)} sampled (user, head) rows; bytes = their share of the K/V streams"
+            times = []
+            t_begin = time.perf_counter()
+            while len(times) < 5 and (time.perf_counter() - t_begin) < args.cpu_seconds:
+                a = time.perf_counter()
+                orc.attention(hw, rows=sample_rows)
+                times.append(time.perf_counter() - a)
+            med = float(np.median(times))
+            out["cpu_baseline"] = {"value": round(sample_bytes / med / 1e9, 4), "unit": "GB/s", "cores": orc.threads(),
+                                   "kind": "oracle", "sample": f"{sample_desc}; median of {len(times)} passes",
+                                   "seconds_per_pass": round(med, 4)}
+    print(json.dumps(out))
+    ctx.close()
+
+
+if __name__ == "__main__":
+    main()

@@ -130,6 +130,16 @@ int spd_partial_attn_public_batched(spd_ctx *ctx, const spd_shape *shape, const 
 int spd_lse_merge(spd_ctx *ctx, int32_t n_rows, int32_t head_dim, const float *a0, const float *lse0,
                   const float *a1, const float *lse1, float *y, float *lse_out, float *w0_out, void *hip_stream);
 
+/*
+ * Built-in timing of the partial-attention kernel (the HBM-streaming kernel of both partial calls), measured with HIP
+ * events on the stream each call launches on.  spd_set_kernel_timing(ctx, n) arms timing for the next n launches of
+ * each entry point (n = 0 disarms); while armed, every partial call records an event before and after its partial
+ * kernel.  spd_get_kernel_timing waits for the recorded launches of one entry point (0 = private, 1 = public batched),
+ * returns their count and mean / minimum duration in microseconds, and clears them.
+ */
+int spd_set_kernel_timing(spd_ctx *ctx, int32_t max_launches);
+int spd_get_kernel_timing(spd_ctx *ctx, int32_t entry_point, int32_t *n_launches, double *mean_us, double *min_us);
+
 /* ------------------------------------------------------------------------------------------------------------
  * Host-only helpers (no GPU needed): the argument checks and the split schedule the calls above use.
  */

@@ -23,7 +23,7 @@ SPD_F32, SPD_BF16 = 0, 1
 EXPORTED_SYMBOLS = (
     "spd_create", "spd_destroy", "spd_strerror", "spd_last_hip_error",
     "spd_partial_attn_private", "spd_partial_attn_public_batched", "spd_lse_merge",
-    "spd_validate_partial", "spd_build_schedule",
+    "spd_validate_partial", "spd_build_schedule", "spd_set_kernel_timing", "spd_get_kernel_timing",
 )
 
 
@@ -74,6 +74,11 @@ def _load() -> C.CDLL:
         fn.argtypes = [vp, C.POINTER(spd_shape), vp, C.POINTER(spd_kv_view), fp, fp, vp]
     lib.spd_lse_merge.restype = C.c_int
     lib.spd_lse_merge.argtypes = [vp, C.c_int32, C.c_int32, fp, fp, fp, fp, fp, fp, fp, vp]
+    lib.spd_set_kernel_timing.restype = C.c_int
+    lib.spd_set_kernel_timing.argtypes = [vp, C.c_int32]
+    lib.spd_get_kernel_timing.restype = C.c_int
+    lib.spd_get_kernel_timing.argtypes = [vp, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_double),
+                                          C.POINTER(C.c_double)]
     lib.spd_validate_partial.restype = C.c_int
     lib.spd_validate_partial.argtypes = [C.POINTER(spd_shape), vp, C.POINTER(spd_kv_view), fp, fp]
     lib.spd_build_schedule.restype = C.c_int
@@ -177,6 +182,16 @@ class Context:
                 _stream_ptr(stream))
         self._check(rc, name)
         return out, lse
+
+    def spd_set_kernel_timing(self, max_launches: int):
+        self._check(lib.spd_set_kernel_timing(self.handle, int(max_launches)), "spd_set_kernel_timing")
+
+    def spd_get_kernel_timing(self, entry_point: int):
+        """(n_launches, mean_us, min_us) of the partial kernel of entry point 0 (private) or 1 (public)."""
+        n, mean, mn = C.c_int32(0), C.c_double(0), C.c_double(0)
+        self._check(lib.spd_get_kernel_timing(self.handle, entry_point, C.byref(n), C.byref(mean), C.byref(mn)),
+                    "spd_get_kernel_timing")
+        return int(n.value), float(mean.value), float(mn.value)
 
     def spd_partial_attn_private(self, shape, q, view, out=None, lse=None, stream=None):
         return self._partial(lib.spd_partial_attn_private, "spd_partial_attn_private", shape, q, view, out, lse, stream)

@@ -203,6 +203,9 @@ struct Owner {
     float *part_o = nullptr;
     float *part_lse = nullptr;
     size_t part_o_cap = 0, part_lse_cap = 0;  // floats
+    // optional timing of the partial kernel: a ring of event pairs recorded around its launch
+    std::vector<hipEvent_t> ev_start, ev_stop;
+    int ev_used = 0;
 };
 
 }  // namespace
@@ -212,6 +215,7 @@ struct spd_ctx {
     int n_cus = 0;
     int last_hip = 0;
     uint64_t tick = 0;
+    bool timing = false;
     Owner owner[2];
 };
 
@@ -415,6 +419,9 @@ int partial_attention(spd_ctx *ctx, int which, const spd_shape *s, const void *q
     const float c = s->scale * spd::kLog2e;
 
     if (e->n_items > 0) {
+        const bool timed = ctx->timing && own.ev_used < (int)own.ev_start.size();
+        if (timed)
+            SPD_HIP(ctx, hipEventRecord(own.ev_start[own.ev_used], stream));
         if (s->dtype == SPD_BF16) {
             if (v->block_size)
                 hipLaunchKernelGGL((spd::partial_bf16_d128_kernel<true>), dim3((unsigned)e->n_items),
@@ -432,6 +439,8 @@ int partial_attention(spd_ctx *ctx, int which, const spd_shape *s, const void *q
             launch_f32_g<128>(G, *e, kv, q, s, c, own, out, lse, stream);
         }
         SPD_HIP(ctx, hipGetLastError());
+        if (timed)
+            SPD_HIP(ctx, hipEventRecord(own.ev_stop[own.ev_used++], stream));
     }
     if (e->need_combine) {
         const RowInfo *rows = reinterpret_cast<const RowInfo *>(e->dev + e->off_rows);
@@ -501,6 +510,10 @@ int spd_destroy(spd_ctx *ctx)
             (void)hipFree(own.part_o);
         if (own.part_lse)
             (void)hipFree(own.part_lse);
+        for (auto ev : own.ev_start)
+            (void)hipEventDestroy(ev);
+        for (auto ev : own.ev_stop)
+            (void)hipEventDestroy(ev);
     }
     delete ctx;
     return SPD_OK;
@@ -549,6 +562,49 @@ int spd_build_schedule(const spd_shape *shape, int32_t n_users, const int32_t *l
             return SPD_ERR_WORKSPACE;
         std::memcpy(items, S.items.data(), S.items.size() * sizeof(spd_work_item));
     }
+    return SPD_OK;
+}
+
+int spd_set_kernel_timing(spd_ctx *ctx, int32_t max_launches)
+{
+    if (!ctx)
+        return SPD_ERR_NULL;
+    if (max_launches < 0)
+        return SPD_ERR_LEN;
+    SPD_HIP(ctx, hipSetDevice(ctx->device));
+    for (auto &own : ctx->owner) {
+        while ((int)own.ev_start.size() < max_launches) {
+            hipEvent_t a, b;
+            SPD_HIP(ctx, hipEventCreate(&a));
+            own.ev_start.push_back(a);
+            SPD_HIP(ctx, hipEventCreate(&b));
+            own.ev_stop.push_back(b);
+        }
+        own.ev_used = 0;
+    }
+    ctx->timing = max_launches > 0;
+    return SPD_OK;
+}
+
+int spd_get_kernel_timing(spd_ctx *ctx, int32_t entry_point, int32_t *n_launches, double *mean_us, double *min_us)
+{
+    if (!ctx || !n_launches || !mean_us || !min_us)
+        return SPD_ERR_NULL;
+    if (entry_point != 0 && entry_point != 1)
+        return SPD_ERR_SHAPE;
+    Owner &own = ctx->owner[entry_point];
+    double sum = 0.0, mn = 0.0;
+    for (int i = 0; i < own.ev_used; ++i) {
+        SPD_HIP(ctx, hipEventSynchronize(own.ev_stop[i]));
+        float ms = 0.f;
+        SPD_HIP(ctx, hipEventElapsedTime(&ms, own.ev_start[i], own.ev_stop[i]));
+        sum += ms;
+        mn = (i == 0 || ms < mn) ? ms : mn;
+    }
+    *n_launches = own.ev_used;
+    *mean_us = own.ev_used ? 1e3 * sum / own.ev_used : 0.0;
+    *min_us = 1e3 * mn;
+    own.ev_used = 0;
     return SPD_OK;
 }
 
