@@ -43,6 +43,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (2 = Llama-3-8B shape, 16 users: the headline)")
     ap.add_argument("--copies", type=int, default=0, help="KV set copies cycled through (0 = enough for > 1 GB, at most 8)")
+    ap.add_argument("--mode", default="fused", choices=["fused", "calls"],
+                    help="fused: spd_decode_step (public beside private on two streams, one closing kernel); "
+                         "calls: the three entry points in sequence on one stream")
+    ap.add_argument("--layout", default=None, choices=["hnd", "nhd"], help="contiguous KV layout override")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true", help="skip the parity check against the oracle")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="bound on the oracle timing leg")
@@ -57,7 +61,7 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
-    wl = workloads.make_workload(args.config, dev)
+    wl = workloads.make_workload(args.config, dev, layout=args.layout)
     kv_bytes = wl.kv_bytes
     elt = 4 if wl.dtype == torch.float32 else 2
     per_token = 2 * wl.n_kv_heads * wl.head_dim * elt
@@ -76,9 +80,19 @@ def main():
         steps_objs.append(spd.DecodeStep.from_workload(ctx, w))
     q = wl.q
 
+    stream_ptr = torch.cuda.current_stream().cuda_stream
+    for so in steps_objs:
+        so.prepare(q, stream_ptr)
+
+    fused = args.mode == "fused"
+
     def run(n, start=0):
         for i in range(n):
-            steps_objs[(start + i) % copies].run(q)
+            so = steps_objs[(start + i) % copies]
+            if fused:
+                so.run_prepared_fused()
+            else:
+                so.run_prepared()
 
     # warm-up: builds and uploads every copy's schedule, grows scratch memory
     run(max(args.warmup, copies))
@@ -105,7 +119,9 @@ def main():
     n_pub, pub_mean_us, pub_min_us = ctx.spd_get_kernel_timing(1)
     ctx.spd_set_kernel_timing(0)
     ms_per_step_timed = (t3 - t2) * 1e3 / K
-    achieved = priv_bytes / (priv_mean_us * 1e-6) / 1e9 if n_priv else 0.0
+    # fused mode: one launch streams both owners' caches; calls mode: the private call's kernel is the dominant one
+    launch_bytes = kv_bytes if fused else priv_bytes
+    achieved = launch_bytes / (priv_mean_us * 1e-6) / 1e9 if n_priv else 0.0
 
     out = {
         "metric": "kv_read_hbm_GBps_per_spd_decode_step",
@@ -121,16 +137,18 @@ def main():
         "config": {"workload": f"config{args.config}:{wl.name}", "n_users": wl.n_users, "n_q_heads": wl.n_q_heads,
                    "n_kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim,
                    "private_tokens": wl.private.n_tokens, "public_tokens": wl.public.n_tokens,
-                   "kv_bytes_per_step": kv_bytes, "kv_copies_cycled": copies,
+                   "kv_bytes_per_step": kv_bytes, "kv_copies_cycled": copies, "mode": args.mode,
                    "layout": "paged16" if wl.private.paged else wl.private.layout,
                    "seeds": wl.seeds},
-        "roofline": {"bound": "hbm", "kernel": "partial_bf16_d128_kernel (private call)" if elt == 2 else "partial_f32_kernel (private call)",
+        "roofline": {"bound": "hbm",
+                     "kernel": ("partial_bf16_d128_kernel" if elt == 2 else "partial_f32_kernel")
+                               + (" (both owners, spd_decode_step)" if fused else " (private call)"),
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
-                     "bytes_per_launch": priv_bytes, "launches_timed": n_priv,
+                     "bytes_per_launch": launch_bytes, "launches_timed": n_priv,
                      "mean_us": round(priv_mean_us, 2), "min_us": round(priv_min_us, 2),
-                     "public_kernel": {"bytes_per_launch": pub_bytes, "mean_us": round(pub_mean_us, 2),
-                                       "GBps": round(pub_bytes / (pub_mean_us * 1e-6) / 1e9, 1) if n_pub else 0.0},
+                     "public_kernel": ({"bytes_per_launch": pub_bytes, "mean_us": round(pub_mean_us, 2),
+                                        "GBps": round(pub_bytes / (pub_mean_us * 1e-6) / 1e9, 1)} if n_pub else None),
                      "us_per_step_while_timed": round(ms_per_step_timed * 1e3, 2)},
     }
 

@@ -131,11 +131,28 @@ int spd_lse_merge(spd_ctx *ctx, int32_t n_rows, int32_t head_dim, const float *a
                   const float *a1, const float *lse1, float *y, float *lse_out, float *w0_out, void *hip_stream);
 
 /*
+ * One whole decode step of one layer for a caller that holds both owners' caches in one process (section 4, step 3).
+ * The paper's prototype overlaps the users' private computation with the service's public one; here both owners'
+ * work is placed in one launch (the public owner's short pieces run beside the private owner's long streams on the
+ * same compute units) and a single closing kernel combines whatever rows either owner had to split and merges the
+ * two owners.  Results are those of the three calls above made in sequence, all of them still delivered:
+ *   a_in, lse_in   = spd_partial_attn_private(q, priv)            [n_users][Hq][d], [n_users][Hq]
+ *   a_out, lse_out = spd_partial_attn_public_batched(q, pub)
+ *   y, lse, w_in   = spd_lse_merge(a_in, lse_in, a_out, lse_out)   (all three required here)
+ * priv and pub must describe the same users.  Uses the scratch memory of both partial entry points: it must not
+ * overlap in time with any other call on the same context.
+ */
+int spd_decode_step(spd_ctx *ctx, const spd_shape *shape, const void *q, const spd_kv_view *priv,
+                    const spd_kv_view *pub, float *a_in, float *lse_in, float *a_out, float *lse_out, float *y,
+                    float *lse, float *w_in, void *hip_stream);
+
+/*
  * Built-in timing of the partial-attention kernel (the HBM-streaming kernel of both partial calls), measured with HIP
  * events on the stream each call launches on.  spd_set_kernel_timing(ctx, n) arms timing for the next n launches of
  * each entry point (n = 0 disarms); while armed, every partial call records an event before and after its partial
  * kernel.  spd_get_kernel_timing waits for the recorded launches of one entry point (0 = private, 1 = public batched),
- * returns their count and mean / minimum duration in microseconds, and clears them.
+ * returns their count and mean / minimum duration in microseconds, and clears them.  spd_decode_step's single
+ * two-owner launch is booked under entry point 0.
  */
 int spd_set_kernel_timing(spd_ctx *ctx, int32_t max_launches);
 int spd_get_kernel_timing(spd_ctx *ctx, int32_t entry_point, int32_t *n_launches, double *mean_us, double *min_us);
@@ -148,20 +165,24 @@ int spd_get_kernel_timing(spd_ctx *ctx, int32_t entry_point, int32_t *n_launches
 int spd_validate_partial(const spd_shape *shape, const void *q, const spd_kv_view *view, const float *out,
                          const float *lse);
 
-/* One unit of split work: tokens [t_begin, t_end) of one (user, KV head); `slot` indexes the partial it writes. */
+/*
+ * One segment of split work: tokens [t_begin, t_end) of one (user, KV head) row.  A workgroup processes a *piece*:
+ * consecutive segments with the same `piece` index (a piece that crosses a row boundary has one segment per row).
+ */
 typedef struct spd_work_item {
     int32_t user, kv_head, t_begin, t_end;
-    int32_t slot;      /* partial index: row_first_slot + chunk                                             */
-    int32_t n_chunks;  /* chunks of this (user, KV head); 1 means the item writes the final result itself    */
-    int32_t chunk;     /* index of this chunk within its row                                                */
-    int32_t reserved;
+    int32_t slot;      /* index of the partial this segment writes when its row has several segments            */
+    int32_t n_chunks;  /* segments of this (user, KV head) row; 1 means the segment writes the final result      */
+    int32_t chunk;     /* index of this segment within its row                                                  */
+    int32_t piece;     /* workgroup that processes this segment                                                  */
 } spd_work_item;
 
 /*
- * Build the split schedule for `lens` (HOST, [n_users]) on a device with `n_compute_units` CUs.
- * Every token of every (user, KV head) is covered by exactly one item; chunk boundaries are multiples of 32 tokens.
- * items may be NULL to query the count.  On return *n_items is the number of items (written only if it fits
- * `capacity`, else SPD_ERR_WORKSPACE) and *chunk_tokens the target chunk length chosen.
+ * Build the split schedule for `lens` (HOST, [n_users]) on a device with `n_compute_units` CUs.  The 32-token steps
+ * of all rows, laid end to end, are cut into pieces of equal length (+-1 step).  Every token of every (user, KV head)
+ * is covered by exactly one segment; segment boundaries inside a row are multiples of 32 tokens.
+ * items may be NULL to query the count.  On return *n_items is the number of segments (written only if it fits
+ * `capacity`, else SPD_ERR_WORKSPACE) and *chunk_tokens the tokens per piece (rounded up to 32).
  */
 int spd_build_schedule(const spd_shape *shape, int32_t n_users, const int32_t *lens, int32_t n_compute_units,
                        spd_work_item *items, int64_t capacity, int64_t *n_items, int32_t *chunk_tokens);

@@ -13,7 +13,7 @@ import numpy as np
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libspd_hip.so")
+LIB_PATH = os.environ.get("SPD_HIP_LIBRARY") or os.path.join(_PKG, "libspd_hip.so")
 
 SPD_OK = 0
 SPD_ERR_NULL, SPD_ERR_SHAPE, SPD_ERR_LEN, SPD_ERR_ALIGN = -1, -2, -3, -4
@@ -24,6 +24,7 @@ EXPORTED_SYMBOLS = (
     "spd_create", "spd_destroy", "spd_strerror", "spd_last_hip_error",
     "spd_partial_attn_private", "spd_partial_attn_public_batched", "spd_lse_merge",
     "spd_validate_partial", "spd_build_schedule", "spd_set_kernel_timing", "spd_get_kernel_timing",
+    "spd_decode_step",
 )
 
 
@@ -51,7 +52,7 @@ class spd_kv_view(C.Structure):
 
 class spd_work_item(C.Structure):
     _fields_ = [("user", C.c_int32), ("kv_head", C.c_int32), ("t_begin", C.c_int32), ("t_end", C.c_int32),
-                ("slot", C.c_int32), ("n_chunks", C.c_int32), ("chunk", C.c_int32), ("reserved", C.c_int32)]
+                ("slot", C.c_int32), ("n_chunks", C.c_int32), ("chunk", C.c_int32), ("piece", C.c_int32)]
 
 
 def _load() -> C.CDLL:
@@ -74,6 +75,9 @@ def _load() -> C.CDLL:
         fn.argtypes = [vp, C.POINTER(spd_shape), vp, C.POINTER(spd_kv_view), fp, fp, vp]
     lib.spd_lse_merge.restype = C.c_int
     lib.spd_lse_merge.argtypes = [vp, C.c_int32, C.c_int32, fp, fp, fp, fp, fp, fp, fp, vp]
+    lib.spd_decode_step.restype = C.c_int
+    lib.spd_decode_step.argtypes = [vp, C.POINTER(spd_shape), vp, C.POINTER(spd_kv_view), C.POINTER(spd_kv_view),
+                                    fp, fp, fp, fp, fp, fp, fp, vp]
     lib.spd_set_kernel_timing.restype = C.c_int
     lib.spd_set_kernel_timing.argtypes = [vp, C.c_int32]
     lib.spd_get_kernel_timing.restype = C.c_int
@@ -199,6 +203,19 @@ class Context:
     def spd_partial_attn_public_batched(self, shape, q, view, out=None, lse=None, stream=None):
         return self._partial(lib.spd_partial_attn_public_batched, "spd_partial_attn_public_batched", shape, q, view,
                              out, lse, stream)
+
+    def spd_decode_step(self, shape, q, private, public, a_in, lse_in, a_out, lse_out, y, lse, w_in, stream=None):
+        n, Hq, d = private.struct.n_users, shape.n_q_heads, shape.head_dim
+        for t in (a_in, a_out, y):
+            assert t.is_contiguous() and t.dtype == torch.float32 and tuple(t.shape) == (n, Hq, d)
+        for t in (lse_in, lse_out, lse, w_in):
+            assert t.is_contiguous() and t.dtype == torch.float32 and tuple(t.shape) == (n, Hq)
+        assert q.is_contiguous() and tuple(q.shape) == (n, Hq, d)
+        rc = lib.spd_decode_step(self.handle, C.byref(shape), q.data_ptr(), C.byref(private.struct),
+                                 C.byref(public.struct), a_in.data_ptr(), lse_in.data_ptr(), a_out.data_ptr(),
+                                 lse_out.data_ptr(), y.data_ptr(), lse.data_ptr(), w_in.data_ptr(), _stream_ptr(stream))
+        self._check(rc, "spd_decode_step")
+        return y
 
     def spd_lse_merge(self, a0, lse0, a1, lse1, y=None, lse_out=None, w0_out=None, stream=None):
         n_rows = lse0.numel()

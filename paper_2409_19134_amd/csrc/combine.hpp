@@ -2,8 +2,11 @@
 //
 //   combine_chunks_kernel  n-way form, used inside one owner's call: the chunks c of a (user, KV head) row each hold
 //                          (A_c, lse_c); lse = logsumexp_c lse_c and A = sum_c exp(lse_c - lse) A_c.
-//                          Rows with no token get A = 0, lse = -inf; rows with one chunk were already written by the
-//                          partial kernel and are skipped.
+//                          A separate launch, not a last-workgroup-reduces scheme inside the partial kernel: on this
+//                          multi-die GPU a device-scope release/acquire writes back and invalidates a whole L2, which
+//                          cost more than the extra launch when every workgroup had to issue one.
+//   finalize_step_kernel   last kernel of the fused step: combines whichever rows were split, for both owners, and
+//                          merges the owners, in one launch
 //   lse_merge_kernel       the two-owner merge itself: Y = w0 A_in + w1 A_out with w_x = exp(lse_x - lse).
 //                          With lse_x = m_x + ln gamma_x these weights equal the paper's
 //                          gamma_in / (gamma_in + alpha gamma_out) and gamma_out / (alpha^-1 gamma_in + gamma_out),
@@ -14,60 +17,145 @@
 
 namespace spd {
 
-// grid: U * Hkv blocks of D threads (thread = channel), D in {64, 128}.  Chunks are read in index order, so the
-// result does not depend on which workgroup finished first.
+constexpr int kCombineStage = 512;  // chunk weights staged in LDS per pass
+
+// n-way form for one (row, query head), executed by a workgroup of D threads (thread = channel): returns this
+// thread's channel of A = sum_c exp(lse_c - lse) A_c and lse = logsumexp_c lse_c.  The chunk weights are staged in
+// LDS by all threads in parallel, then every thread streams its channel of the chunks' partial vectors with
+// independent loads, in chunk order (so the result does not depend on the order in which the partial workgroups
+// ran).  sm_w: kCombineStage floats, sm_red: D floats.  n_chunks >= 1; chunks are never empty, so lse is finite.
 template <int D>
-__global__ __launch_bounds__(D) void combine_chunks_kernel(const RowInfo *__restrict__ rows, int Hkv, int Hq, int G,
+__device__ __forceinline__ void combine_row(const float *__restrict__ pl, const float *__restrict__ po, int n_chunks,
+                                            int G, float *sm_w, float *sm_red, float &a_out, float &lse_out)
+{
+    const int tid = threadIdx.x;
+    float mloc = -INFINITY;
+    for (int c = tid; c < n_chunks; c += D)
+        mloc = fmaxf(mloc, pl[(int64_t)c * G]);
+    __syncthreads();  // earlier readers of the LDS arrays are done
+    sm_red[tid] = mloc;
+    __syncthreads();
+    for (int s = D / 2; s > 0; s >>= 1) {
+        if (tid < s)
+            sm_red[tid] = fmaxf(sm_red[tid], sm_red[tid + s]);
+        __syncthreads();
+    }
+    const float M = sm_red[0];
+    float o = 0.f, den = 0.f;
+    for (int c0 = 0; c0 < n_chunks; c0 += kCombineStage) {
+        const int nc = min(kCombineStage, n_chunks - c0);
+        __syncthreads();
+        for (int c = tid; c < nc; c += D)
+            sm_w[c] = expf(pl[(int64_t)(c0 + c) * G] - M);
+        __syncthreads();
+#pragma unroll 8
+        for (int c = 0; c < nc; ++c) {
+            den += sm_w[c];
+            o = fmaf(sm_w[c], po[(int64_t)(c0 + c) * G * D], o);
+        }
+    }
+    a_out = o / den;
+    lse_out = M + logf(den);
+}
+
+// One workgroup of D threads per (split row, query head).
+template <int D>
+__global__ __launch_bounds__(D) void combine_chunks_kernel(const CombineRow *__restrict__ rows, int Hq, int G,
                                                            const float *__restrict__ part_o,
                                                            const float *__restrict__ part_lse,
                                                            float *__restrict__ out, float *__restrict__ lse)
 {
-    const RowInfo ri = rows[blockIdx.x];
-    if (ri.n_chunks == 1)
+    __shared__ float sm_w[kCombineStage];
+    __shared__ float sm_red[D];
+    const CombineRow r = rows[blockIdx.x / G];
+    const int g = blockIdx.x % G;
+    const int64_t row = (int64_t)r.user * Hq + (int64_t)r.kv_head * G + g;
+    float a, ls;
+    combine_row<D>(part_lse + (int64_t)r.first_slot * G + g,
+                   part_o + ((int64_t)r.first_slot * G + g) * D + threadIdx.x, r.n_chunks, G, sm_w, sm_red, a, ls);
+    out[row * D + threadIdx.x] = a;
+    if (threadIdx.x == 0)
+        lse[row] = ls;
+}
+
+// Two-owner weights of Theorem 1 on log-sum-exps; a side with lse = -inf gets weight exactly 0.
+__device__ __forceinline__ void merge_weights(float l0, float l1, float &w0, float &w1, float &ls)
+{
+    const float M = fmaxf(l0, l1);
+    if (M == -INFINITY) {  // both owners hold no token for this row
+        w0 = 0.f, w1 = 0.f, ls = -INFINITY;
         return;
-    const int user = blockIdx.x / Hkv, kvh = blockIdx.x % Hkv;
-    const int ch = threadIdx.x;
-    for (int g = 0; g < G; ++g) {
-        const int64_t row = (int64_t)user * Hq + (int64_t)kvh * G + g;
-        float M = -INFINITY;
-        for (int c = 0; c < ri.n_chunks; ++c)
-            M = fmaxf(M, part_lse[(int64_t)(ri.first_slot + c) * G + g]);
-        float o = 0.f, den = 0.f;
-        for (int c = 0; c < ri.n_chunks; ++c) {
-            const int64_t s = (int64_t)(ri.first_slot + c) * G + g;
-            const float w = expf(part_lse[s] - M);   // chunks are never empty, so M is finite here
-            den += w;
-            o = fmaf(w, part_o[s * D + ch], o);
-        }
-        const bool empty = ri.n_chunks == 0;
-        out[row * D + ch] = empty ? 0.f : o / den;
-        if (ch == 0)
-            lse[row] = empty ? -INFINITY : M + logf(den);
+    }
+    const float e0 = expf(l0 - M), e1 = expf(l1 - M);  // the larger one is exactly 1
+    const float den = e0 + e1;
+    w0 = e0 / den;
+    w1 = e1 / den;
+    ls = M + logf(den);
+}
+
+// Last kernel of a fused decode step: one workgroup of D threads per (user, query head).  For each owner, a row
+// that was split is combined here (and its A / lse written, so the caller still gets both partials); unsplit and
+// empty rows were already written by the partial kernels and are read back.  Then the two owners are merged.
+template <int D>
+__global__ __launch_bounds__(D) void finalize_step_kernel(const RowInfo *__restrict__ rows_in,
+                                                          const RowInfo *__restrict__ rows_out, int Hkv, int Hq, int G,
+                                                          const float *__restrict__ part_o_in,
+                                                          const float *__restrict__ part_lse_in,
+                                                          const float *__restrict__ part_o_out,
+                                                          const float *__restrict__ part_lse_out, float *a_in,
+                                                          float *lse_in, float *a_out, float *lse_out,
+                                                          float *__restrict__ y, float *__restrict__ lse,
+                                                          float *__restrict__ w_in)
+{
+    __shared__ float sm_w[kCombineStage];
+    __shared__ float sm_red[D];
+    const int64_t row = blockIdx.x;  // user * Hq + head
+    const int user = (int)(row / Hq), h = (int)(row % Hq);
+    const int kvh = h / G, g = h % G;
+    const int tid = threadIdx.x;
+    const RowInfo ri = rows_in[user * Hkv + kvh], ro = rows_out[user * Hkv + kvh];
+    float x0, l0, x1, l1;
+    if (ri.n_chunks > 1) {
+        combine_row<D>(part_lse_in + (int64_t)ri.first_slot * G + g,
+                       part_o_in + ((int64_t)ri.first_slot * G + g) * D + tid, ri.n_chunks, G, sm_w, sm_red, x0, l0);
+        a_in[row * D + tid] = x0;
+        if (tid == 0)
+            lse_in[row] = l0;
+    } else {
+        x0 = a_in[row * D + tid];
+        l0 = lse_in[row];
+    }
+    if (ro.n_chunks > 1) {
+        combine_row<D>(part_lse_out + (int64_t)ro.first_slot * G + g,
+                       part_o_out + ((int64_t)ro.first_slot * G + g) * D + tid, ro.n_chunks, G, sm_w, sm_red, x1, l1);
+        a_out[row * D + tid] = x1;
+        if (tid == 0)
+            lse_out[row] = l1;
+    } else {
+        x1 = a_out[row * D + tid];
+        l1 = lse_out[row];
+    }
+    float w0, w1, ls;
+    merge_weights(l0, l1, w0, w1, ls);
+    y[row * D + tid] = (w0 == 0.f ? 0.f : w0 * x0) + (w1 == 0.f ? 0.f : w1 * x1);
+    if (tid == 0) {
+        lse[row] = ls;
+        w_in[row] = w0;
     }
 }
 
 // one thread per 4 channels of one row
-__global__ __launch_bounds__(256) void lse_merge_kernel(int64_t n_vec, int vec_per_row, const float *__restrict__ a0,
-                                                         const float *__restrict__ lse0, const float *__restrict__ a1,
-                                                         const float *__restrict__ lse1, float *__restrict__ y,
+__global__ __launch_bounds__(256) void lse_merge_kernel(int64_t n_vec, int vec_per_row, const float *a0,
+                                                         const float *__restrict__ lse0, const float *a1,
+                                                         const float *__restrict__ lse1, float *y,
                                                          float *__restrict__ lse_out, float *__restrict__ w0_out)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n_vec)
         return;
     const int64_t row = i / vec_per_row;
-    const float l0 = lse0[row], l1 = lse1[row];
-    const float M = fmaxf(l0, l1);
     float w0, w1, ls;
-    if (M == -INFINITY) {  // both owners hold no token for this row
-        w0 = 0.f, w1 = 0.f, ls = -INFINITY;
-    } else {
-        const float e0 = expf(l0 - M), e1 = expf(l1 - M);  // the larger one is exactly 1
-        const float den = e0 + e1;
-        w0 = e0 / den;
-        w1 = e1 / den;
-        ls = M + logf(den);
-    }
+    merge_weights(lse0[row], lse1[row], w0, w1, ls);
     const f32x4 x0 = reinterpret_cast<const f32x4 *>(a0)[i];
     const f32x4 x1 = reinterpret_cast<const f32x4 *>(a1)[i];
     f32x4 r;

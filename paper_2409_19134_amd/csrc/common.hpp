@@ -17,27 +17,70 @@ constexpr int kMaxGroup = 16;        // query heads per KV head the MFMA tile ca
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
-// Addressing of one owner's cache; all strides in BYTES.
+// Addressing of one owner's cache; all strides in BYTES.  Base pointers travel in the work items.
 struct KvAddr {
-    const char *const *k_ptrs;   // contiguous mode: device array of per-user base pointers
-    const char *const *v_ptrs;
-    const char *k_pool;          // paged mode
-    const char *v_pool;
-    const int32_t *block_table;
+    const int32_t *block_table;  // paged mode only, else nullptr
     int32_t max_blocks;
     int64_t block_stride;
     int64_t token_stride;
-    int64_t head_stride;
 };
 
-// first partial slot and chunk count of one (user, KV head) row
-struct RowInfo {
-    int32_t first_slot;
-    int32_t n_chunks;
+// One segment of work as the kernels read it: tokens [t_begin, t_end) of one (user, KV head) row.  A workgroup
+// processes a *piece*: a short list of segments linked by `next` (a piece that crosses a row boundary has one
+// segment per row it touches).  k_base / v_base point at channel 0 of token 0 of the row (contiguous mode) or at the
+// KV head's offset inside the pool (paged mode).  n_chunks == 0 marks a row without tokens: the workgroup only
+// writes A = 0, lse = -inf.
+struct DevItem {
+    const char *k_base;
+    const char *v_base;
+    int32_t user, kv_head, t_begin, t_end;
+    int32_t slot;      // where this segment's partial goes when the row has several segments
+    int32_t n_chunks;  // segments of the row; 1: the segment writes the final result itself
+    int32_t next;      // index of the piece's next segment, -1 if none
+    int32_t rot;       // 32-token steps the piece has already handed out (mod 4): keeps the four waves evenly loaded
 };
+
+// 16-byte load of K/V data that is read exactly once: the non-temporal hint keeps the stream from displacing
+// other lines in L2 (measured: plain streaming reads reach ~6.3 TB/s on this GPU, non-temporal ones ~7.1 TB/s).
+__device__ __forceinline__ u32x4 stream_load16(const char *p)
+{
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+}
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 __device__ __forceinline__ float wave_xor_max(float v, int mask) { return fmaxf(v, __shfl_xor(v, mask)); }
+
+// Rows without tokens (Theorem 1 with an empty part): A = 0, lse = -inf for the G heads of the row.
+template <int D>
+__device__ __forceinline__ void write_empty_row(const DevItem &it, int G, int Hq, float *out, float *lse)
+{
+    const int64_t head0 = (int64_t)it.user * Hq + (int64_t)it.kv_head * G;
+    for (int idx = threadIdx.x; idx < G * D; idx += blockDim.x)
+        out[head0 * D + idx] = 0.f;
+    if ((int)threadIdx.x < G)
+        lse[head0 + threadIdx.x] = -INFINITY;
+}
+
+// Everything a partial kernel needs to know about one owner's call.  A launch serves one owner, or - for the fused
+// decode step - both at once: workgroups [0, n0) take owner 0's pieces, the rest owner 1's.
+struct OwnerArgs {
+    const DevItem *items;
+    KvAddr kv;
+    float *part_o;    // [slots][G][D] chunk partials of split rows
+    float *part_lse;  // [slots][G]
+    float *out;       // [U][Hq][D]
+    float *lse;       // [U][Hq]
+};
+
+// A row (user, KV head) whose tokens were split into several chunks.
+struct CombineRow {
+    int32_t first_slot, n_chunks, user, kv_head;
+};
+
+// Chunk bookkeeping of every (user, KV head) row, indexed user * Hkv + kv_head.
+struct RowInfo {
+    int32_t first_slot, n_chunks;
+};
 
 }  // namespace spd

@@ -54,13 +54,13 @@ __device__ __forceinline__ void load_tile(TileRegs &T, const LaneConst &L, int t
         const char *p = kp + (int64_t)(PAGED ? (t & 15) : t) * L.token_stride + L.grp * 16;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk)
-            T.k[a][kk] = *reinterpret_cast<const u32x4 *>(p + kk * 64);
+            T.k[a][kk] = stream_load16(p + kk * 64);
     }
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         const int t = min(gv + e, t_last);
         const char *p = vp + (int64_t)(PAGED ? (t & 15) : t) * L.token_stride + L.r * 16;
-        T.v[e] = *reinterpret_cast<const u32x4 *>(p);
+        T.v[e] = stream_load16(p);
     }
 }
 
@@ -121,130 +121,150 @@ __device__ __forceinline__ void compute_tile(const TileRegs &T, const bf16x8 (&q
 
 constexpr int kOStride = 132;  // LDS row stride (floats) of one head's 128 channels: bank = 4*r + grp, conflict free
 
-// items: one workgroup each.  q: [U][Hq][128] bf16.  Rows with one chunk write out/lse directly,
-// others write part_o[slot][G][128] / part_lse[slot][G].
-template <bool PAGED>
-__global__ __launch_bounds__(kThreads, 2) void partial_bf16_d128_kernel(
-    const spd_work_item *__restrict__ items, KvAddr kv, const uint16_t *__restrict__ q, int Hq, int G,
-    float scale_log2e, float *__restrict__ part_o, float *__restrict__ part_lse, float *__restrict__ out,
-    float *__restrict__ lse)
+// One workgroup per piece (see DevItem); q: [U][Hq][128] bf16.  A segment that is its row's only one writes out/lse
+// directly; otherwise it writes part_o[slot][G][128] / part_lse[slot][G], which combine_chunks_kernel then reduces.
+//
+// PREFETCH = true keeps two 32-token steps of loads in flight per wave (231 VGPRs, two workgroups per CU): best when a
+// launch runs many waves of workgroups.  PREFETCH = false holds one step (166 VGPRs, three workgroups per CU): as fast
+// when the whole launch is one resident wave, and it leaves room on every CU for the other owner's kernel to run
+// beside this one.
+template <bool PAGED, bool PREFETCH>
+__global__ __launch_bounds__(kThreads, PREFETCH ? 2 : 3) void partial_bf16_d128_kernel(
+    OwnerArgs a0, OwnerArgs a1, int n0, const uint16_t *__restrict__ q, int Hq, int G, float scale_log2e)
 {
+    const bool second = (int)blockIdx.x >= n0;  // workgroup-uniform: which owner this workgroup serves
+    const DevItem *__restrict__ items = second ? a1.items : a0.items;
+    const KvAddr kv = second ? a1.kv : a0.kv;
+    float *__restrict__ part_o = second ? a1.part_o : a0.part_o;
+    float *__restrict__ part_lse = second ? a1.part_lse : a0.part_lse;
+    float *__restrict__ out = second ? a1.out : a0.out;
+    float *__restrict__ lse = second ? a1.lse : a0.lse;
     __shared__ float sm_m[kWaves][16];
     __shared__ float sm_l[kWaves][16];
     __shared__ float sm_o[kWaves][kMaxGroup * kOStride];
 
-    const spd_work_item it = items[blockIdx.x];
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-
     LaneConst L;
     L.r = lane & 15;
     L.grp = lane >> 4;
     L.token_stride = kv.token_stride;
     L.block_stride = kv.block_stride;
-    if (PAGED) {
-        L.k_base = kv.k_pool + (int64_t)it.kv_head * kv.head_stride;
-        L.v_base = kv.v_pool + (int64_t)it.kv_head * kv.head_stride;
-        L.bt_row = kv.block_table + (int64_t)it.user * kv.max_blocks;
-    } else {
-        L.k_base = kv.k_ptrs[it.user] + (int64_t)it.kv_head * kv.head_stride;
-        L.v_base = kv.v_ptrs[it.user] + (int64_t)it.kv_head * kv.head_stride;
-        L.bt_row = nullptr;
-    }
 
-    // Q as the B operand: head r (zero beyond G), channels kk*32 + grp*8 .. +8
-    bf16x8 qB[4];
-    {
-        const uint16_t *qrow = q + ((int64_t)it.user * Hq + (int64_t)it.kv_head * G + L.r) * 128 + L.grp * 8;
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            u32x4 w = {0u, 0u, 0u, 0u};
-            if (L.r < G)
-                w = *reinterpret_cast<const u32x4 *>(qrow + kk * 32);
-            qB[kk] = __builtin_bit_cast(bf16x8, w);
+    for (int seg = second ? (int)blockIdx.x - n0 : (int)blockIdx.x;;) {
+        const DevItem it = items[seg];
+        if (it.n_chunks == 0) {  // a row without tokens is a piece of its own
+            write_empty_row<128>(it, G, Hq, out, lse);
+            return;
         }
-    }
+        L.k_base = it.k_base;
+        L.v_base = it.v_base;
+        L.bt_row = PAGED ? kv.block_table + (int64_t)it.user * kv.max_blocks : nullptr;
 
-    float m = -INFINITY, l = 0.f;
-    f32x4 acc[8];
+        // Q as the B operand: head r (zero beyond G), channels kk*32 + grp*8 .. +8
+        bf16x8 qB[4];
+        {
+            const uint16_t *qrow = q + ((int64_t)it.user * Hq + (int64_t)it.kv_head * G + L.r) * 128 + L.grp * 8;
 #pragma unroll
-    for (int cc = 0; cc < 8; ++cc)
-        acc[cc] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    const int t_last = it.t_end - 1;
-    constexpr int kStep = 32 * kWaves;
-    int tb = it.t_begin + wave * 32;
-    if (tb < it.t_end) {
-        TileRegs T0, T1;
-        load_tile<PAGED>(T0, L, tb, t_last);
-        while (true) {
-            const int tb1 = tb + kStep;
-            const bool more1 = tb1 < it.t_end;
-            if (more1)
-                load_tile<PAGED>(T1, L, tb1, t_last);
-            compute_tile(T0, qB, tb, L.grp, it.t_end, scale_log2e, m, l, acc);
-            if (!more1)
-                break;
-            const int tb2 = tb1 + kStep;
-            const bool more2 = tb2 < it.t_end;
-            if (more2)
-                load_tile<PAGED>(T0, L, tb2, t_last);
-            compute_tile(T1, qB, tb1, L.grp, it.t_end, scale_log2e, m, l, acc);
-            if (!more2)
-                break;
-            tb = tb2;
+            for (int kk = 0; kk < 4; ++kk) {
+                u32x4 w = {0u, 0u, 0u, 0u};
+                if (L.r < G)
+                    w = *reinterpret_cast<const u32x4 *>(qrow + kk * 32);
+                qB[kk] = __builtin_bit_cast(bf16x8, w);
+            }
         }
-    }
 
-    // ---- combine the lane groups (sum of l) and the four waves (LDS) ----
-    l += __shfl_xor(l, 16);
-    l += __shfl_xor(l, 32);
-    if (L.grp == 0) {
-        sm_m[wave][L.r] = m;
-        sm_l[wave][L.r] = l;
-    }
-    __syncthreads();
-    float M = sm_m[0][L.r];
-#pragma unroll
-    for (int w = 1; w < kWaves; ++w)
-        M = fmaxf(M, sm_m[w][L.r]);
-    const float f = fast_exp2(m - M);  // wave 0 always holds tokens, so M is finite; an idle wave has m = -inf, f = 0
-    if (L.r < G) {
-        float *dst = &sm_o[wave][L.r * kOStride + L.grp * 32];
+        float m = -INFINITY, l = 0.f;
+        f32x4 acc[8];
 #pragma unroll
         for (int cc = 0; cc < 8; ++cc)
-#pragma unroll
-            for (int v = 0; v < 4; ++v)
-                dst[v * 8 + cc] = acc[cc][v] * f;  // channel (4*grp + v)*8 + cc
-    }
-    __syncthreads();
+            acc[cc] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const bool direct = it.n_chunks == 1;
-    const int64_t head0 = (int64_t)it.user * Hq + (int64_t)it.kv_head * G;
-    for (int idx = threadIdx.x; idx < G * 128; idx += kThreads) {
-        const int g = idx >> 7, ch = idx & 127;
-        float Mg = sm_m[0][g];
+        const int t_last = it.t_end - 1;
+        constexpr int kStep = 32 * kWaves;
+        int tb = it.t_begin + ((wave - it.rot) & (kWaves - 1)) * 32;  // the waves take interleaved 32-token steps
+        if (!PREFETCH) {
+            for (; tb < it.t_end; tb += kStep) {
+                TileRegs T0;
+                load_tile<PAGED>(T0, L, tb, t_last);
+                compute_tile(T0, qB, tb, L.grp, it.t_end, scale_log2e, m, l, acc);
+            }
+        } else if (tb < it.t_end) {
+            TileRegs T0, T1;
+            load_tile<PAGED>(T0, L, tb, t_last);
+            while (true) {
+                const int tb1 = tb + kStep;
+                const bool more1 = tb1 < it.t_end;
+                if (more1)
+                    load_tile<PAGED>(T1, L, tb1, t_last);
+                compute_tile(T0, qB, tb, L.grp, it.t_end, scale_log2e, m, l, acc);
+                if (!more1)
+                    break;
+                const int tb2 = tb1 + kStep;
+                const bool more2 = tb2 < it.t_end;
+                if (more2)
+                    load_tile<PAGED>(T0, L, tb2, t_last);
+                compute_tile(T1, qB, tb1, L.grp, it.t_end, scale_log2e, m, l, acc);
+                if (!more2)
+                    break;
+                tb = tb2;
+            }
+        }
+
+        // ---- combine the lane groups (sum of l) and the four waves (LDS) ----
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+        if (L.grp == 0) {
+            sm_m[wave][L.r] = m;
+            sm_l[wave][L.r] = l;
+        }
+        __syncthreads();
+        float M = sm_m[0][L.r];
 #pragma unroll
         for (int w = 1; w < kWaves; ++w)
-            Mg = fmaxf(Mg, sm_m[w][g]);
-        float o = 0.f, lt = 0.f;
+            M = fmaxf(M, sm_m[w][L.r]);
+        const float f = fast_exp2(m - M);  // some wave holds tokens, so M is finite; an idle wave has m = -inf, f = 0
+        if (L.r < G) {
+            float *dst = &sm_o[wave][L.r * kOStride + L.grp * 32];
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
-            o += sm_o[w][g * kOStride + ch];
-            lt += sm_l[w][g] * fast_exp2(sm_m[w][g] - Mg);
+            for (int cc = 0; cc < 8; ++cc)
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    dst[v * 8 + cc] = acc[cc][v] * f;  // channel (4*grp + v)*8 + cc
         }
-        const float a = o / lt;
-        if (direct)
-            out[(head0 + g) * 128 + ch] = a;
-        else
-            part_o[((int64_t)it.slot * G + g) * 128 + ch] = a;
-        if (ch == 0) {
-            const float ls = Mg * kLn2 + logf(lt);
+        __syncthreads();
+
+        const bool direct = it.n_chunks == 1;
+        const int64_t head0 = (int64_t)it.user * Hq + (int64_t)it.kv_head * G;
+        for (int idx = threadIdx.x; idx < G * 128; idx += kThreads) {
+            const int g = idx >> 7, ch = idx & 127;
+            float Mg = sm_m[0][g];
+#pragma unroll
+            for (int w = 1; w < kWaves; ++w)
+                Mg = fmaxf(Mg, sm_m[w][g]);
+            float o = 0.f, lt = 0.f;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) {
+                o += sm_o[w][g * kOStride + ch];
+                lt += sm_l[w][g] * fast_exp2(sm_m[w][g] - Mg);
+            }
+            const float a = o / lt;
             if (direct)
-                lse[head0 + g] = ls;
+                out[(head0 + g) * 128 + ch] = a;
             else
-                part_lse[(int64_t)it.slot * G + g] = ls;
+                part_o[((int64_t)it.slot * G + g) * 128 + ch] = a;
+            if (ch == 0) {
+                const float ls = Mg * kLn2 + logf(lt);
+                if (direct)
+                    lse[head0 + g] = ls;
+                else
+                    part_lse[(int64_t)it.slot * G + g] = ls;
+            }
         }
+        if (it.next < 0)
+            return;
+        seg = it.next;
+        __syncthreads();  // the LDS staging arrays are reused by the next segment
     }
 }
 

@@ -13,9 +13,15 @@ namespace spd {
 
 template <int D, int G>
 __global__ __launch_bounds__(kThreads) void partial_f32_kernel(
-    const spd_work_item *__restrict__ items, KvAddr kv, const float *__restrict__ q, int Hq, float scale_log2e,
-    float *__restrict__ part_o, float *__restrict__ part_lse, float *__restrict__ out, float *__restrict__ lse)
+    OwnerArgs a0, OwnerArgs a1, int n0, const float *__restrict__ q, int Hq, float scale_log2e)
 {
+    const bool second = (int)blockIdx.x >= n0;  // workgroup-uniform: which owner this workgroup serves
+    const DevItem *__restrict__ items = second ? a1.items : a0.items;
+    const KvAddr kv = second ? a1.kv : a0.kv;
+    float *__restrict__ part_o = second ? a1.part_o : a0.part_o;
+    float *__restrict__ part_lse = second ? a1.part_lse : a0.part_lse;
+    float *__restrict__ out = second ? a1.out : a0.out;
+    float *__restrict__ lse = second ? a1.lse : a0.lse;
     constexpr int EPL = 4;          // fp32 elements per 16-byte lane load
     constexpr int LPR = D / EPL;    // lanes per row: 16 (D=64) or 32 (D=128)
     constexpr int RPW = 64 / LPR;   // rows per wave per step
@@ -23,23 +29,20 @@ __global__ __launch_bounds__(kThreads) void partial_f32_kernel(
     __shared__ float sm_l[kWaves][G];
     __shared__ float sm_o[kWaves][G][D];
 
-    const spd_work_item it = items[blockIdx.x];
+  for (int seg = second ? (int)blockIdx.x - n0 : (int)blockIdx.x;;) {
+    const DevItem it = items[seg];
+    if (it.n_chunks == 0) {  // a row without tokens is a piece of its own
+        write_empty_row<D>(it, G, Hq, out, lse);
+        return;
+    }
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int cl = lane % LPR;      // which 4-channel slice of the row
     const int rs = lane / LPR;      // which row of the step
 
     const bool paged = kv.block_table != nullptr;
-    const char *k_base, *v_base;
-    const int32_t *bt_row = nullptr;
-    if (paged) {
-        k_base = kv.k_pool + (int64_t)it.kv_head * kv.head_stride;
-        v_base = kv.v_pool + (int64_t)it.kv_head * kv.head_stride;
-        bt_row = kv.block_table + (int64_t)it.user * kv.max_blocks;
-    } else {
-        k_base = kv.k_ptrs[it.user] + (int64_t)it.kv_head * kv.head_stride;
-        v_base = kv.v_ptrs[it.user] + (int64_t)it.kv_head * kv.head_stride;
-    }
+    const char *k_base = it.k_base, *v_base = it.v_base;
+    const int32_t *bt_row = paged ? kv.block_table + (int64_t)it.user * kv.max_blocks : nullptr;
 
     float qr[G][EPL];
 #pragma unroll
@@ -130,6 +133,7 @@ __global__ __launch_bounds__(kThreads) void partial_f32_kernel(
 
     const bool direct = it.n_chunks == 1;
     const int64_t head0 = (int64_t)it.user * Hq + (int64_t)it.kv_head * G;
+    const int64_t slot = it.slot;
     for (int idx = threadIdx.x; idx < G * D; idx += kThreads) {
         const int g = idx / D, ch = idx % D;
         float Mg = sm_m[0][g];
@@ -147,15 +151,20 @@ __global__ __launch_bounds__(kThreads) void partial_f32_kernel(
         if (direct)
             out[(head0 + g) * D + ch] = a;
         else
-            part_o[((int64_t)it.slot * G + g) * D + ch] = a;
+            part_o[(slot * G + g) * D + ch] = a;
         if (ch == 0) {
             const float ls = Mg * kLn2 + logf(lt);
             if (direct)
                 lse[head0 + g] = ls;
             else
-                part_lse[(int64_t)it.slot * G + g] = ls;
+                part_lse[slot * G + g] = ls;
         }
     }
+    if (it.next < 0)
+        return;
+    seg = it.next;
+    __syncthreads();  // the LDS staging arrays are reused by the next segment
+  }
 }
 
 }  // namespace spd

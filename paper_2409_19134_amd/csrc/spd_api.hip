@@ -16,14 +16,19 @@
 
 namespace {
 
+using spd::CombineRow;
+using spd::DevItem;
 using spd::KvAddr;
+using spd::OwnerArgs;
 using spd::RowInfo;
 
 constexpr int kCacheEntries = 8;     // remembered schedules per entry point
 constexpr int kChunkAlign = 32;      // chunk boundaries are multiples of the MFMA kernel's 32-token step
-constexpr int kChunkMin = 128;       // one step for each of the four waves
-constexpr int kChunkMaxDefault = 1024;
-constexpr int kTargetWgPerCuDefault = 3;
+constexpr int kChunkMin = 128;       // one 32-token step for each of the four waves
+constexpr int kChunkMaxDefault = 4096;     // tokens per piece when the work exceeds one resident wave
+constexpr int kNoSplitMaxDefault = 768;     // rows this short are never split: the work is latency-bound and a
+                                            // whole row per workgroup saves the combine launch
+constexpr int kTargetWgPerCuDefault = 2;   // workgroups of the MFMA kernel resident per CU (2 waves per SIMD)
 
 int env_int(const char *name, int dflt)
 {
@@ -112,66 +117,102 @@ int validate_view(const spd_shape *s, const spd_kv_view *v)
     return SPD_OK;
 }
 
-// Target chunk length (tokens) for a total of `tokens` per KV head over all users.
-int pick_chunk(int64_t tokens, int n_kv_heads, int n_cus)
-{
-    const int64_t target_items = (int64_t)std::max(1, n_cus) * env_int("SPD_TARGET_WG_PER_CU", kTargetWgPerCuDefault);
-    const int chunk_max = std::max(kChunkMin, env_int("SPD_CHUNK_MAX", kChunkMaxDefault) / kChunkMin * kChunkMin);
-    int64_t c = (tokens * n_kv_heads + target_items - 1) / target_items;
-    c = (c + kChunkMin - 1) / kChunkMin * kChunkMin;
-    return (int)std::min<int64_t>(std::max<int64_t>(c, kChunkMin), chunk_max);
-}
-
+// The split schedule ("stream-K" over tokens).  Every (user, KV head) row with tokens is cut into 32-token steps;
+// the steps of all rows, laid end to end, are divided into n_pieces runs of equal length (+-1 step), one workgroup
+// each.  A piece that crosses a row boundary consists of several segments.  Equal pieces matter because the path is
+// HBM-bound: a launch lasts as long as its longest workgroup.
+//   - if no row is longer than a few hundred tokens, every row is one piece: nothing to combine afterwards;
+//   - work that fits one resident wave of workgroups (2 per CU) gets exactly that many pieces;
+//   - larger work gets pieces of at most `piece_max` tokens, their number rounded up to a multiple of the resident
+//     wave, and relies on the hardware's dynamic workgroup dispatch.
 struct Schedule {
-    std::vector<spd_work_item> items;
-    std::vector<RowInfo> rows;   // [U * Hkv]
+    std::vector<spd_work_item> items;  // segments in piece order (rows with tokens only)
+    std::vector<int32_t> piece_first;  // [n_pieces + 1] first segment of each piece
     int64_t n_slots = 0;
-    int chunk_tokens = 0;
-    bool need_combine = false;   // some row has zero or several chunks
+    int chunk_tokens = 0;              // tokens per piece (rounded up)
 };
 
 void build_schedule(int Hkv, int n_users, const int32_t *lens, int n_cus, Schedule &S)
 {
-    int64_t tokens = 0;
-    for (int u = 0; u < n_users; ++u)
-        tokens += lens[u];
-    const int C = pick_chunk(tokens, Hkv, n_cus);
-    S.chunk_tokens = C;
     S.items.clear();
-    S.rows.assign((size_t)n_users * Hkv, RowInfo{0, 0});
+    S.piece_first.assign(1, 0);
     S.n_slots = 0;
-    S.need_combine = false;
+    S.chunk_tokens = 0;
+    int64_t T = 0;  // total 32-token steps
+    int max_len = 0;
     for (int u = 0; u < n_users; ++u) {
-        const int L = lens[u];
-        int n_c = 0, per = 0;
-        if (L > 0) {
-            n_c = (L + C - 1) / C;
-            per = ((L + n_c - 1) / n_c + kChunkAlign - 1) / kChunkAlign * kChunkAlign;  // balanced, 32-aligned
-            n_c = (L + per - 1) / per;
-        }
-        if (n_c != 1)
-            S.need_combine = true;
-        for (int h = 0; h < Hkv; ++h) {
-            S.rows[(size_t)u * Hkv + h] = RowInfo{(int32_t)S.n_slots, n_c};
-            for (int c = 0; c < n_c; ++c) {
+        T += (int64_t)((lens[u] + kChunkAlign - 1) / kChunkAlign) * Hkv;
+        max_len = std::max(max_len, lens[u]);
+    }
+    if (T == 0)
+        return;
+    if (max_len <= env_int("SPD_NO_SPLIT_MAX", kNoSplitMaxDefault)) {
+        for (int u = 0; u < n_users; ++u) {
+            if (lens[u] == 0)
+                continue;
+            for (int h = 0; h < Hkv; ++h) {
                 spd_work_item it;
                 it.user = u;
                 it.kv_head = h;
-                it.t_begin = c * per;
-                it.t_end = std::min(L, (c + 1) * per);
-                it.slot = (int32_t)(S.n_slots + c);
-                it.n_chunks = n_c;
-                it.chunk = c;
-                it.reserved = 0;
+                it.t_begin = 0;
+                it.t_end = lens[u];
+                it.slot = (int32_t)S.n_slots++;
+                it.n_chunks = 1;
+                it.chunk = 0;
+                it.piece = (int32_t)S.items.size();
                 S.items.push_back(it);
+                S.piece_first.push_back((int32_t)S.items.size());
             }
-            S.n_slots += n_c;
+        }
+        S.chunk_tokens = (max_len + kChunkAlign - 1) / kChunkAlign * kChunkAlign;
+        return;
+    }
+    const int64_t slots = (int64_t)std::max(1, n_cus) * env_int("SPD_TARGET_WG_PER_CU", kTargetWgPerCuDefault);
+    const int64_t piece_max = std::max(kChunkMin, env_int("SPD_CHUNK_MAX", kChunkMaxDefault)) / kChunkAlign;  // steps
+    int64_t W;
+    if (T <= slots * piece_max)
+        W = std::min<int64_t>(slots, (T + spd::kWaves - 1) / spd::kWaves);  // at least one step per wave
+    else
+        W = slots * ((T + slots * piece_max - 1) / (slots * piece_max));
+    S.chunk_tokens = (int)((T + W - 1) / W) * kChunkAlign;
+
+    int64_t g0 = 0;  // global step index of the current row's first step
+    int64_t p = 0;   // current piece
+    auto piece_end = [&](int64_t i) { return T * (i + 1) / W; };
+    std::vector<int32_t> row_first_item;
+    for (int u = 0; u < n_users; ++u) {
+        const int L = lens[u];
+        if (L == 0)
+            continue;
+        const int64_t steps = (L + kChunkAlign - 1) / kChunkAlign;
+        for (int h = 0; h < Hkv; ++h) {
+            const size_t first_item = S.items.size();
+            int64_t s = 0;
+            while (s < steps) {
+                while (piece_end(p) <= g0 + s) {  // the current piece is used up: close it
+                    ++p;
+                    S.piece_first.push_back((int32_t)S.items.size());
+                }
+                const int64_t e = std::min(steps, piece_end(p) - g0);
+                spd_work_item it;
+                it.user = u;
+                it.kv_head = h;
+                it.t_begin = (int32_t)(s * kChunkAlign);
+                it.t_end = (int32_t)std::min<int64_t>(L, e * kChunkAlign);
+                it.slot = (int32_t)S.n_slots++;
+                it.n_chunks = 0;  // filled below
+                it.chunk = (int32_t)(S.items.size() - first_item);
+                it.piece = (int32_t)p;
+                S.items.push_back(it);
+                s = e;
+            }
+            const int32_t n_c = (int32_t)(S.items.size() - first_item);
+            for (size_t i = first_item; i < S.items.size(); ++i)
+                S.items[i].n_chunks = n_c;
+            g0 += steps;
         }
     }
-    // longest first, so the last workgroups to start are the short ones
-    std::stable_sort(S.items.begin(), S.items.end(), [](const spd_work_item &a, const spd_work_item &b) {
-        return (a.t_end - a.t_begin) > (b.t_end - b.t_begin);
-    });
+    S.piece_first.push_back((int32_t)S.items.size());
 }
 
 uint64_t fnv1a(const uint8_t *p, size_t n)
@@ -190,12 +231,11 @@ struct CachedSchedule {
     uint64_t hash = 0, last_use = 0;
     std::vector<uint8_t> key;
     int64_t n_items = 0, n_slots = 0;
-    int n_rows = 0;
-    bool need_combine = false;
-    char *dev = nullptr;     // items | rows | k_ptrs | v_ptrs
+    int n_split_rows = 0;    // rows with several chunks: CombineRow[n_split_rows] follows the items
+    size_t off_rows = 0, off_info = 0;
+    char *dev = nullptr;     // DevItem[n_items] | CombineRow[n_split_rows] | RowInfo[n_users * Hkv]
     char *pinned = nullptr;  // host staging copy of the same blob
     size_t capacity = 0;
-    size_t off_rows = 0, off_kptrs = 0, off_vptrs = 0;
 };
 
 struct Owner {
@@ -249,6 +289,11 @@ void make_key(const spd_shape *s, const spd_kv_view *v, std::vector<uint8_t> &ke
     const int32_t head[5] = {s->dtype, s->n_q_heads, s->n_kv_heads, v->n_users, v->block_size};
     put(head, sizeof head);
     put(v->lens, sizeof(int32_t) * (size_t)v->n_users);
+    put(&v->head_stride, sizeof v->head_stride);  // the items carry row base pointers: everything they depend on
+    if (v->block_size != 0) {
+        put(&v->k_pool, sizeof v->k_pool);
+        put(&v->v_pool, sizeof v->v_pool);
+    }
     if (v->block_size == 0) {
         for (int u = 0; u < v->n_users; ++u) {  // pointers of empty users are never read: normalise them
             const void *kp = v->lens[u] ? v->k_ptrs[u] : nullptr;
@@ -284,12 +329,88 @@ int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view
     Schedule S;
     build_schedule(s->n_kv_heads, v->n_users, v->lens, ctx->n_cus, S);
 
-    const size_t b_items = S.items.size() * sizeof(spd_work_item);
-    const size_t b_rows = S.rows.size() * sizeof(RowInfo);
-    const size_t b_ptrs = v->block_size == 0 ? sizeof(void *) * (size_t)v->n_users : 0;
-    auto up = [](size_t x) { return (x + 255) / 256 * 256; };
-    const size_t off_rows = up(b_items), off_k = off_rows + up(b_rows), off_v = off_k + up(b_ptrs);
-    const size_t total = off_v + up(b_ptrs) + 256;
+    // device items: the first segment of every piece (index = workgroup id), then one per row without tokens (it only
+    // writes A = 0, lse = -inf), then the continuation segments, linked through `next`
+    const int es = elt_size(s->dtype);
+    const int Hkv = s->n_kv_heads;
+    const int64_t n_pieces = (int64_t)S.piece_first.size() - 1;
+    int64_t n_empty_rows = 0;
+    for (int u = 0; u < v->n_users; ++u)
+        n_empty_rows += v->lens[u] == 0 ? Hkv : 0;
+    const int64_t n_groups = n_pieces + n_empty_rows;  // launched workgroups
+    std::vector<DevItem> dev_items((size_t)n_groups);
+    dev_items.reserve((size_t)n_groups + S.items.size());
+    auto row_base = [&](int u, int h, bool is_v) -> const char * {
+        const char *base = v->block_size ? static_cast<const char *>(is_v ? v->v_pool : v->k_pool)
+                                         : static_cast<const char *>(is_v ? v->v_ptrs[u] : v->k_ptrs[u]);
+        return base + (int64_t)h * v->head_stride * es;
+    };
+    auto to_dev = [&](const spd_work_item &w, int rot) {
+        DevItem d;
+        d.k_base = row_base(w.user, w.kv_head, false);
+        d.v_base = row_base(w.user, w.kv_head, true);
+        d.user = w.user;
+        d.kv_head = w.kv_head;
+        d.t_begin = w.t_begin;
+        d.t_end = w.t_end;
+        d.slot = w.slot;
+        d.n_chunks = w.n_chunks;
+        d.next = -1;
+        d.rot = rot & (spd::kWaves - 1);
+        return d;
+    };
+    for (int64_t pc = 0; pc < n_pieces; ++pc) {
+        int rot = 0;
+        size_t prev = 0;
+        for (int32_t i = S.piece_first[(size_t)pc]; i < S.piece_first[(size_t)pc + 1]; ++i) {
+            const spd_work_item &w = S.items[(size_t)i];
+            const DevItem d = to_dev(w, rot);
+            size_t at;
+            if (i == S.piece_first[(size_t)pc]) {
+                at = (size_t)pc;
+                dev_items[at] = d;
+            } else {
+                at = dev_items.size();
+                dev_items.push_back(d);
+                dev_items[prev].next = (int32_t)at;
+            }
+            prev = at;
+            rot += (w.t_end - w.t_begin + kChunkAlign - 1) / kChunkAlign;
+        }
+    }
+    {
+        size_t at = (size_t)n_pieces;
+        for (int u = 0; u < v->n_users; ++u) {
+            if (v->lens[u] != 0)
+                continue;
+            for (int h = 0; h < Hkv; ++h) {
+                DevItem d;
+                d.k_base = d.v_base = nullptr;
+                d.user = u;
+                d.kv_head = h;
+                d.t_begin = d.t_end = 0;
+                d.slot = d.n_chunks = d.rot = 0;
+                d.next = -1;
+                dev_items[at++] = d;
+            }
+        }
+    }
+    std::vector<CombineRow> split_rows;
+    for (size_t i = 0; i < S.items.size(); ++i) {
+        const spd_work_item &w = S.items[i];
+        if (w.chunk == 0 && w.n_chunks > 1)
+            split_rows.push_back(CombineRow{w.slot, w.n_chunks, w.user, w.kv_head});
+    }
+    std::vector<RowInfo> row_info((size_t)v->n_users * Hkv, RowInfo{0, 0});
+    for (const spd_work_item &w : S.items)
+        if (w.chunk == 0)
+            row_info[(size_t)w.user * Hkv + w.kv_head] = RowInfo{w.slot, w.n_chunks};
+    const size_t b_items = dev_items.size() * sizeof(DevItem);
+    const size_t b_rows = split_rows.size() * sizeof(CombineRow);
+    const size_t b_info = row_info.size() * sizeof(RowInfo);
+    const size_t off_rows = (b_items + 255) / 256 * 256;
+    const size_t off_info = off_rows + (b_rows + 255) / 256 * 256;
+    const size_t total = off_info + (b_info + 255) / 256 * 256 + 256;
 
     CachedSchedule &e = *victim;
     if (e.valid || e.capacity < total) {
@@ -305,29 +426,21 @@ int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view
     }
     std::memset(e.pinned, 0, total);
     if (b_items)
-        std::memcpy(e.pinned, S.items.data(), b_items);
+        std::memcpy(e.pinned, dev_items.data(), b_items);
     if (b_rows)
-        std::memcpy(e.pinned + off_rows, S.rows.data(), b_rows);
-    if (b_ptrs) {
-        const void **kp = reinterpret_cast<const void **>(e.pinned + off_k);
-        const void **vp = reinterpret_cast<const void **>(e.pinned + off_v);
-        for (int u = 0; u < v->n_users; ++u) {
-            kp[u] = v->lens[u] ? v->k_ptrs[u] : nullptr;
-            vp[u] = v->lens[u] ? v->v_ptrs[u] : nullptr;
-        }
-    }
+        std::memcpy(e.pinned + off_rows, split_rows.data(), b_rows);
+    if (b_info)
+        std::memcpy(e.pinned + off_info, row_info.data(), b_info);
     SPD_HIP(ctx, hipMemcpyAsync(e.dev, e.pinned, total, hipMemcpyHostToDevice, stream));
     e.valid = true;
     e.hash = h;
     e.key.swap(key);
     e.last_use = ctx->tick;
-    e.n_items = (int64_t)S.items.size();
+    e.n_items = n_groups;
     e.n_slots = S.n_slots;
-    e.n_rows = (int)S.rows.size();
-    e.need_combine = S.need_combine;
+    e.n_split_rows = (int)split_rows.size();
     e.off_rows = off_rows;
-    e.off_kptrs = off_k;
-    e.off_vptrs = off_v;
+    e.off_info = off_info;
     *out = &e;
     return SPD_OK;
 }
@@ -362,24 +475,127 @@ int ensure_scratch(spd_ctx *ctx, Owner &own, size_t o_floats, size_t lse_floats)
 }
 
 template <int D, int G>
-void launch_f32(const CachedSchedule &e, const KvAddr &kv, const void *q, const spd_shape *s, float c, Owner &own,
-                float *out, float *lse, hipStream_t stream)
+void launch_f32(dim3 grid, hipStream_t stream, const OwnerArgs &a0, const OwnerArgs &a1, int n0, const void *q, int Hq,
+                float c)
 {
-    hipLaunchKernelGGL((spd::partial_f32_kernel<D, G>), dim3((unsigned)e.n_items), dim3(spd::kThreads), 0, stream,
-                       reinterpret_cast<const spd_work_item *>(e.dev), kv, static_cast<const float *>(q),
-                       s->n_q_heads, c, own.part_o, own.part_lse, out, lse);
+    hipLaunchKernelGGL((spd::partial_f32_kernel<D, G>), grid, dim3(spd::kThreads), 0, stream, a0, a1, n0,
+                       static_cast<const float *>(q), Hq, c);
 }
 
 template <int D>
-void launch_f32_g(int G, const CachedSchedule &e, const KvAddr &kv, const void *q, const spd_shape *s, float c,
-                  Owner &own, float *out, float *lse, hipStream_t stream)
+void launch_f32_g(int G, dim3 grid, hipStream_t stream, const OwnerArgs &a0, const OwnerArgs &a1, int n0,
+                  const void *q, int Hq, float c)
 {
     switch (G) {
-    case 1: launch_f32<D, 1>(e, kv, q, s, c, own, out, lse, stream); break;
-    case 2: launch_f32<D, 2>(e, kv, q, s, c, own, out, lse, stream); break;
-    case 4: launch_f32<D, 4>(e, kv, q, s, c, own, out, lse, stream); break;
-    default: launch_f32<D, 8>(e, kv, q, s, c, own, out, lse, stream); break;
+    case 1: launch_f32<D, 1>(grid, stream, a0, a1, n0, q, Hq, c); break;
+    case 2: launch_f32<D, 2>(grid, stream, a0, a1, n0, q, Hq, c); break;
+    case 4: launch_f32<D, 4>(grid, stream, a0, a1, n0, q, Hq, c); break;
+    default: launch_f32<D, 8>(grid, stream, a0, a1, n0, q, Hq, c); break;
     }
+}
+
+// Validation, schedule lookup and scratch growth of one partial-attention call.
+int prepare_partial(spd_ctx *ctx, int which, const spd_shape *s, const void *q, const spd_kv_view *v, float *out,
+                    float *lse, hipStream_t stream, CachedSchedule **e)
+{
+    const int rc = spd_validate_partial(s, q, v, out, lse);
+    if (rc != SPD_OK)
+        return rc;
+    *e = nullptr;
+    if (v->n_users == 0)
+        return SPD_OK;
+    Owner &own = ctx->owner[which];
+    const int rs = get_schedule(ctx, own, s, v, stream, e);
+    if (rs != SPD_OK)
+        return rs;
+    const int G = s->n_q_heads / s->n_kv_heads;
+    return ensure_scratch(ctx, own, (size_t)(*e)->n_slots * G * s->head_dim + 4, (size_t)(*e)->n_slots * G + 4);
+}
+
+OwnerArgs owner_args(const Owner &own, const CachedSchedule *e, const spd_shape *s, const spd_kv_view *v, float *out,
+                     float *lse)
+{
+    const int es = elt_size(s->dtype);
+    OwnerArgs a;
+    a.items = reinterpret_cast<const DevItem *>(e->dev);
+    a.kv.block_table = v->block_size ? v->block_table : nullptr;
+    a.kv.max_blocks = v->max_blocks;
+    a.kv.block_stride = v->block_stride * es;
+    a.kv.token_stride = v->token_stride * es;
+    a.part_o = own.part_o;
+    a.part_lse = own.part_lse;
+    a.out = out;
+    a.lse = lse;
+    return a;
+}
+
+// The partial kernel: every piece's workgroup writes final rows or chunk partials.  One owner per launch
+// (e1 == nullptr), or both owners' pieces in one grid (the fused step; both views in the same storage mode).
+int launch_partial(spd_ctx *ctx, int which, const CachedSchedule *e0, const spd_kv_view *v0, float *out0, float *lse0,
+                   const CachedSchedule *e1, const spd_kv_view *v1, float *out1, float *lse1, const spd_shape *s,
+                   const void *q, hipStream_t stream)
+{
+    const int64_t n0 = e0->n_items, n1 = e1 ? e1->n_items : 0;
+    if (n0 + n1 == 0)
+        return SPD_OK;
+    Owner &own0 = ctx->owner[which];
+    const OwnerArgs a0 = owner_args(own0, e0, s, v0, out0, lse0);
+    const OwnerArgs a1 = e1 ? owner_args(ctx->owner[1 - which], e1, s, v1, out1, lse1) : a0;
+    const int G = s->n_q_heads / s->n_kv_heads;
+    const float c = s->scale * spd::kLog2e;
+    Owner &town = ctx->owner[e1 ? 0 : which];  // a two-owner launch is booked under entry point 0
+    const bool timed = ctx->timing && town.ev_used < (int)town.ev_start.size();
+    if (timed)
+        SPD_HIP(ctx, hipEventRecord(town.ev_start[town.ev_used], stream));
+    const dim3 grid((unsigned)(n0 + n1)), block(spd::kThreads);
+    if (s->dtype == SPD_BF16) {
+        const uint16_t *qh = static_cast<const uint16_t *>(q);
+        // more pieces than the three-per-CU kernel can hold at once: use the prefetching two-per-CU kernel
+        const bool prefetch = n0 + n1 > (int64_t)std::max(1, ctx->n_cus) * 3;
+#define SPD_LAUNCH_BF16(PAGED, PREFETCH)                                                                              \
+    hipLaunchKernelGGL((spd::partial_bf16_d128_kernel<PAGED, PREFETCH>), grid, block, 0, stream, a0, a1, (int)n0, qh,    \
+                       s->n_q_heads, G, c)
+        if (v0->block_size) {
+            if (prefetch)
+                SPD_LAUNCH_BF16(true, true);
+            else
+                SPD_LAUNCH_BF16(true, false);
+        } else {
+            if (prefetch)
+                SPD_LAUNCH_BF16(false, true);
+            else
+                SPD_LAUNCH_BF16(false, false);
+        }
+#undef SPD_LAUNCH_BF16
+    } else if (s->head_dim == 64) {
+        launch_f32_g<64>(G, grid, stream, a0, a1, (int)n0, q, s->n_q_heads, c);
+    } else {
+        launch_f32_g<128>(G, grid, stream, a0, a1, (int)n0, q, s->n_q_heads, c);
+    }
+    SPD_HIP(ctx, hipGetLastError());
+    if (timed)
+        SPD_HIP(ctx, hipEventRecord(town.ev_stop[town.ev_used++], stream));
+    return SPD_OK;
+}
+
+// The n-way combine of the rows that were split (a separate launch, see combine.hpp).
+int launch_combine(spd_ctx *ctx, int which, const CachedSchedule *e, const spd_shape *s, float *out, float *lse,
+                   hipStream_t stream)
+{
+    if (e->n_split_rows == 0)
+        return SPD_OK;
+    Owner &own = ctx->owner[which];
+    const int G = s->n_q_heads / s->n_kv_heads;
+    const CombineRow *rows = reinterpret_cast<const CombineRow *>(e->dev + e->off_rows);
+    const unsigned grid = (unsigned)e->n_split_rows * (unsigned)G;
+    if (s->head_dim == 64)
+        hipLaunchKernelGGL((spd::combine_chunks_kernel<64>), dim3(grid), dim3(64), 0, stream, rows, s->n_q_heads, G,
+                           own.part_o, own.part_lse, out, lse);
+    else
+        hipLaunchKernelGGL((spd::combine_chunks_kernel<128>), dim3(grid), dim3(128), 0, stream, rows, s->n_q_heads, G,
+                           own.part_o, own.part_lse, out, lse);
+    SPD_HIP(ctx, hipGetLastError());
+    return SPD_OK;
 }
 
 int partial_attention(spd_ctx *ctx, int which, const spd_shape *s, const void *q, const spd_kv_view *v, float *out,
@@ -387,72 +603,16 @@ int partial_attention(spd_ctx *ctx, int which, const spd_shape *s, const void *q
 {
     if (!ctx)
         return SPD_ERR_NULL;
-    const int rc = spd_validate_partial(s, q, v, out, lse);
-    if (rc != SPD_OK)
-        return rc;
-    if (v->n_users == 0)
-        return SPD_OK;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     SPD_HIP(ctx, hipSetDevice(ctx->device));
-    Owner &own = ctx->owner[which];
     CachedSchedule *e = nullptr;
-    const int rs = get_schedule(ctx, own, s, v, stream, &e);
-    if (rs != SPD_OK)
-        return rs;
-    const int G = s->n_q_heads / s->n_kv_heads;
-    const int d = s->head_dim;
-    const int rw = ensure_scratch(ctx, own, (size_t)e->n_slots * G * d + 4, (size_t)e->n_slots * G + 4);
-    if (rw != SPD_OK)
-        return rw;
-
-    const int es = elt_size(s->dtype);
-    KvAddr kv;
-    kv.k_ptrs = reinterpret_cast<const char *const *>(e->dev + e->off_kptrs);
-    kv.v_ptrs = reinterpret_cast<const char *const *>(e->dev + e->off_vptrs);
-    kv.k_pool = static_cast<const char *>(v->k_pool);
-    kv.v_pool = static_cast<const char *>(v->v_pool);
-    kv.block_table = v->block_size ? v->block_table : nullptr;
-    kv.max_blocks = v->max_blocks;
-    kv.block_stride = v->block_stride * es;
-    kv.token_stride = v->token_stride * es;
-    kv.head_stride = v->head_stride * es;
-    const float c = s->scale * spd::kLog2e;
-
-    if (e->n_items > 0) {
-        const bool timed = ctx->timing && own.ev_used < (int)own.ev_start.size();
-        if (timed)
-            SPD_HIP(ctx, hipEventRecord(own.ev_start[own.ev_used], stream));
-        if (s->dtype == SPD_BF16) {
-            if (v->block_size)
-                hipLaunchKernelGGL((spd::partial_bf16_d128_kernel<true>), dim3((unsigned)e->n_items),
-                                   dim3(spd::kThreads), 0, stream, reinterpret_cast<const spd_work_item *>(e->dev), kv,
-                                   static_cast<const uint16_t *>(q), s->n_q_heads, G, c, own.part_o, own.part_lse, out,
-                                   lse);
-            else
-                hipLaunchKernelGGL((spd::partial_bf16_d128_kernel<false>), dim3((unsigned)e->n_items),
-                                   dim3(spd::kThreads), 0, stream, reinterpret_cast<const spd_work_item *>(e->dev), kv,
-                                   static_cast<const uint16_t *>(q), s->n_q_heads, G, c, own.part_o, own.part_lse, out,
-                                   lse);
-        } else if (d == 64) {
-            launch_f32_g<64>(G, *e, kv, q, s, c, own, out, lse, stream);
-        } else {
-            launch_f32_g<128>(G, *e, kv, q, s, c, own, out, lse, stream);
-        }
-        SPD_HIP(ctx, hipGetLastError());
-        if (timed)
-            SPD_HIP(ctx, hipEventRecord(own.ev_stop[own.ev_used++], stream));
-    }
-    if (e->need_combine) {
-        const RowInfo *rows = reinterpret_cast<const RowInfo *>(e->dev + e->off_rows);
-        if (d == 64)
-            hipLaunchKernelGGL((spd::combine_chunks_kernel<64>), dim3((unsigned)e->n_rows), dim3(64), 0, stream, rows,
-                               s->n_kv_heads, s->n_q_heads, G, own.part_o, own.part_lse, out, lse);
-        else
-            hipLaunchKernelGGL((spd::combine_chunks_kernel<128>), dim3((unsigned)e->n_rows), dim3(128), 0, stream,
-                               rows, s->n_kv_heads, s->n_q_heads, G, own.part_o, own.part_lse, out, lse);
-        SPD_HIP(ctx, hipGetLastError());
-    }
-    return SPD_OK;
+    int rc = prepare_partial(ctx, which, s, q, v, out, lse, stream, &e);
+    if (rc != SPD_OK || !e)
+        return rc;
+    rc = launch_partial(ctx, which, e, v, out, lse, nullptr, nullptr, nullptr, nullptr, s, q, stream);
+    if (rc != SPD_OK)
+        return rc;
+    return launch_combine(ctx, which, e, s, out, lse, stream);
 }
 
 }  // namespace
@@ -618,6 +778,69 @@ int spd_partial_attn_public_batched(spd_ctx *ctx, const spd_shape *shape, const 
                                     float *out, float *lse, void *hip_stream)
 {
     return partial_attention(ctx, 1, shape, q, pub, out, lse, hip_stream);
+}
+
+int spd_decode_step(spd_ctx *ctx, const spd_shape *shape, const void *q, const spd_kv_view *priv,
+                    const spd_kv_view *pub, float *a_in, float *lse_in, float *a_out, float *lse_out, float *y,
+                    float *lse, float *w_in, void *hip_stream)
+{
+    if (!ctx)
+        return SPD_ERR_NULL;
+    if (!priv || !pub)
+        return SPD_ERR_NULL;
+    if (priv->n_users != pub->n_users)
+        return SPD_ERR_LEN;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    SPD_HIP(ctx, hipSetDevice(ctx->device));
+    // validate everything before anything is enqueued
+    int rc = spd_validate_partial(shape, q, priv, a_in, lse_in);
+    if (rc == SPD_OK)
+        rc = spd_validate_partial(shape, q, pub, a_out, lse_out);
+    if (rc != SPD_OK)
+        return rc;
+    if (priv->n_users == 0)
+        return SPD_OK;
+    if (!y || !lse || !w_in)
+        return SPD_ERR_NULL;
+    if (!aligned16(y))
+        return SPD_ERR_ALIGN;
+    CachedSchedule *ep = nullptr, *eo = nullptr;
+    rc = prepare_partial(ctx, 0, shape, q, priv, a_in, lse_in, stream, &ep);
+    if (rc != SPD_OK)
+        return rc;
+    rc = prepare_partial(ctx, 1, shape, q, pub, a_out, lse_out, stream, &eo);  // an upload, if any, stays on `stream`
+    if (rc != SPD_OK)
+        return rc;
+    // one grid for both owners, the private owner's long streams first (measured faster than public first): the
+    // public owner's short, latency-bound pieces then run beside them on the workgroup slots that remain
+    if ((priv->block_size != 0) == (pub->block_size != 0)) {
+        rc = launch_partial(ctx, 0, ep, priv, a_in, lse_in, eo, pub, a_out, lse_out, shape, q, stream);
+        if (rc != SPD_OK)
+            return rc;
+    } else {  // different storage modes need different kernel instances
+        rc = launch_partial(ctx, 1, eo, pub, a_out, lse_out, nullptr, nullptr, nullptr, nullptr, shape, q, stream);
+        if (rc != SPD_OK)
+            return rc;
+        rc = launch_partial(ctx, 0, ep, priv, a_in, lse_in, nullptr, nullptr, nullptr, nullptr, shape, q, stream);
+        if (rc != SPD_OK)
+            return rc;
+    }
+    // join: one kernel combines whichever rows were split and merges the owners
+    const int G = shape->n_q_heads / shape->n_kv_heads;
+    const RowInfo *ri = reinterpret_cast<const RowInfo *>(ep->dev + ep->off_info);
+    const RowInfo *ro = reinterpret_cast<const RowInfo *>(eo->dev + eo->off_info);
+    const unsigned grid = (unsigned)priv->n_users * (unsigned)shape->n_q_heads;
+    const Owner &op = ctx->owner[0], &oo = ctx->owner[1];
+    if (shape->head_dim == 64)
+        hipLaunchKernelGGL((spd::finalize_step_kernel<64>), dim3(grid), dim3(64), 0, stream, ri, ro, shape->n_kv_heads,
+                           shape->n_q_heads, G, op.part_o, op.part_lse, oo.part_o, oo.part_lse, a_in, lse_in, a_out,
+                           lse_out, y, lse, w_in);
+    else
+        hipLaunchKernelGGL((spd::finalize_step_kernel<128>), dim3(grid), dim3(128), 0, stream, ri, ro,
+                           shape->n_kv_heads, shape->n_q_heads, G, op.part_o, op.part_lse, oo.part_o, oo.part_lse, a_in,
+                           lse_in, a_out, lse_out, y, lse, w_in);
+    SPD_HIP(ctx, hipGetLastError());
+    return SPD_OK;
 }
 
 int spd_lse_merge(spd_ctx *ctx, int32_t n_rows, int32_t head_dim, const float *a0, const float *lse0, const float *a1,

@@ -38,3 +38,46 @@ class DecodeStep:
         c.spd_partial_attn_public_batched(self.shape, q, self.public, self.a_out, self.lse_out, stream)
         c.spd_lse_merge(self.a_in, self.lse_in, self.a_out, self.lse_out, self.y, self.lse, self.w_in, stream)
         return self.y
+
+    def run_fused(self, q: torch.Tensor, stream=None):
+        """The same step through spd_decode_step: public beside private on two streams, one closing kernel."""
+        return self.ctx.spd_decode_step(self.shape, q, self.private, self.public, self.a_in, self.lse_in, self.a_out,
+                                        self.lse_out, self.y, self.lse, self.w_in, stream)
+
+    def prepare(self, q: torch.Tensor, stream_ptr: int):
+        """Marshal the three calls' arguments once; `run_prepared` then only makes the three C calls.
+        For loops that reuse the same q buffer and stream (serving loops, benchmarks)."""
+        import ctypes as C
+        from .binding import lib
+        n, Hq, d = self.private.struct.n_users, self.shape.n_q_heads, self.shape.head_dim
+        assert q.is_contiguous() and tuple(q.shape) == (n, Hq, d)
+        h, sp, st = self.ctx.handle, C.byref(self.shape), C.c_void_p(stream_ptr)
+        self._keep_q = q
+        self._calls = (
+            (lib.spd_partial_attn_private, (h, sp, q.data_ptr(), C.byref(self.private.struct),
+                                            self.a_in.data_ptr(), self.lse_in.data_ptr(), st)),
+            (lib.spd_partial_attn_public_batched, (h, sp, q.data_ptr(), C.byref(self.public.struct),
+                                                   self.a_out.data_ptr(), self.lse_out.data_ptr(), st)),
+            (lib.spd_lse_merge, (h, n * Hq, d, self.a_in.data_ptr(), self.lse_in.data_ptr(), self.a_out.data_ptr(),
+                                 self.lse_out.data_ptr(), self.y.data_ptr(), self.lse.data_ptr(),
+                                 self.w_in.data_ptr(), st)),
+        )
+
+        self._fused = (lib.spd_decode_step, (h, sp, q.data_ptr(), C.byref(self.private.struct),
+                                             C.byref(self.public.struct), self.a_in.data_ptr(),
+                                             self.lse_in.data_ptr(), self.a_out.data_ptr(), self.lse_out.data_ptr(),
+                                             self.y.data_ptr(), self.lse.data_ptr(), self.w_in.data_ptr(), st))
+
+    def run_prepared_fused(self):
+        fn, args = self._fused
+        rc = fn(*args)
+        if rc != 0:
+            self.ctx._check(rc, "spd_decode_step")
+        return self.y
+
+    def run_prepared(self):
+        for fn, args in self._calls:
+            rc = fn(*args)
+            if rc != 0:
+                self.ctx._check(rc, fn.__name__)
+        return self.y

@@ -107,20 +107,20 @@ def test_calls_reject_null_context_without_touching_the_gpu():
 
 @pytest.mark.parametrize("lens", [
     [0], [1], [31, 32, 33], [128, 129, 4096, 0, 513], list(range(0, 700, 37)),
-    [131072, 5, 40000], [2304] * 16,
+    [131072, 5, 40000], [2304] * 16, [100000] * 64,
 ])
 @pytest.mark.parametrize("n_cus", [1, 256])
 def test_schedule_covers_every_token_once(lens, n_cus):
     Hkv = 8
     sh = spd.make_shape(spd.SPD_BF16, 32, Hkv, 128, 0.1)
     items, chunk = spd.spd_build_schedule(sh, lens, n_cus)
-    assert chunk % 128 == 0 and chunk >= 128
+    assert chunk % 32 == 0
     seen = {}
     slots = set()
     for it in items:
         assert 0 <= it["t_begin"] < it["t_end"] <= lens[it["user"]]
         assert it["t_begin"] % 32 == 0
-        assert it["t_end"] - it["t_begin"] <= chunk
+        assert it["t_end"] % 32 == 0 or it["t_end"] == lens[it["user"]]
         seen.setdefault((it["user"], it["kv_head"]), []).append(it)
         assert it["slot"] not in slots
         slots.add(it["slot"])
@@ -136,8 +136,22 @@ def test_schedule_covers_every_token_once(lens, n_cus):
             assert all(it["n_chunks"] == len(row) for it in row)
             assert [it["chunk"] for it in row] == list(range(len(row)))
             assert [it["slot"] for it in row] == list(range(row[0]["slot"], row[0]["slot"] + len(row)))
-    sizes = [it["t_end"] - it["t_begin"] for it in items]
-    assert sizes == sorted(sizes, reverse=True)          # longest first
+    # pieces: consecutive, equal to within one 32-token step, and no more than fit the machine at once
+    # unless each already carries the maximum piece length
+    pieces = [it["piece"] for it in items]
+    assert pieces == sorted(pieces)
+    if items:
+        steps = {}
+        for it in items:
+            steps[it["piece"]] = steps.get(it["piece"], 0) + -(-(it["t_end"] - it["t_begin"]) // 32)
+        assert sorted(steps) == list(range(len(steps)))
+        if max(lens) <= 768:      # short rows are never split: one piece per row
+            assert all(it["n_chunks"] == 1 for it in items)
+            return
+        assert max(steps.values()) - min(steps.values()) <= 1
+        assert max(steps.values()) * 32 <= max(chunk, 128)
+        if len(steps) > 2 * n_cus:
+            assert len(steps) % (2 * n_cus) == 0 and max(steps.values()) * 32 <= 4096
 
 
 def test_schedule_fills_the_machine_for_the_headline_workload():
@@ -145,4 +159,4 @@ def test_schedule_fills_the_machine_for_the_headline_workload():
     lp, lo = workloads.draw_lengths(2, 16)
     sh = spd.make_shape(spd.SPD_BF16, 32, 8, 128, 0.1)
     items, chunk = spd.spd_build_schedule(sh, lp, 256)
-    assert 512 <= len(items) <= 1536            # a few workgroups per CU, one resident wave of them
+    assert len({it["piece"] for it in items}) == 512      # the 2 workgroups per CU that are resident at once

@@ -26,10 +26,16 @@ def ctx():
     c.close()
 
 
-def run_step(ctx, wl):
+def run_step(ctx, wl, fused=False):
+    """One decode step: the three C-ABI calls in sequence, or the fused spd_decode_step."""
     import paper_2409_19134_amd as spd
     step = spd.DecodeStep.from_workload(ctx, wl)
-    step.run(wl.q)
+    for t in (step.a_in, step.a_out, step.y, step.lse_in, step.lse_out, step.lse, step.w_in):
+        t.fill_(float("nan"))          # every output must be overwritten
+    if fused:
+        step.run_fused(wl.q)
+    else:
+        step.run(wl.q)
     torch.cuda.synchronize()
     return step
 
@@ -43,9 +49,18 @@ def maxerr(got: torch.Tensor, want: np.ndarray) -> float:
 
 
 def check_against_oracle(ctx, wl, rows=None, tol=None):
-    tol = TOL[wl.dtype] if tol is None else tol
-    step = run_step(ctx, wl)
+    """Both ways of running a step (three calls; fused call) against the oracle.  Returns the three-call step."""
     hw = orc.from_workload(wl)
+    first = None
+    for fused in (False, True):
+        step, errs = _check_one(ctx, wl, hw, rows, tol, fused)
+        first = first or (step, errs)
+    return first
+
+
+def _check_one(ctx, wl, hw, rows, tol, fused):
+    tol = TOL[wl.dtype] if tol is None else tol
+    step = run_step(ctx, wl, fused)
     Y, lse = orc.attention(hw, rows=rows)
     A_in, m_in, g_in = orc.partial(hw, hw.private, rows=rows)
     A_out, m_out, g_out = orc.partial(hw, hw.public, rows=rows)
@@ -65,7 +80,7 @@ def check_against_oracle(ctx, wl, rows=None, tol=None):
         "w_in": maxerr(flat(step.w_in), w_in[:, None]),
     }
     bad = {k: v for k, v in errs.items() if not v <= tol}
-    assert not bad, f"beyond tolerance {tol}: {bad} (all: {errs})"
+    assert not bad, f"fused={fused}: beyond tolerance {tol}: {bad} (all: {errs})"
     return step, errs
 
 
