@@ -36,6 +36,23 @@ def clone_side(side):
     return c
 
 
+def measured_traffic(config: int, kernel_prefix: str):
+    """HBM bytes per launch of the streaming kernel from the committed rocprofv3 --pmc summary of this workload
+    (scaled FETCH_SIZE + WRITE_SIZE), or None if no summary is there.  The summary names the command that made it."""
+    import re
+    path = os.path.join(ROOT, "profiles", f"partial_kernel_config{config}_pmc_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    total = 0.0
+    found = 0
+    for line in open(path):
+        m = re.search(r"^\s+spd::(\S+).*->\s+([0-9.]+) MB scaled", line)
+        if m and m.group(1).startswith(kernel_prefix):
+            total += float(m.group(2)) * 1e6
+            found += 1
+    return int(total) if found == 2 else None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -50,6 +67,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true", help="skip the parity check against the oracle")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="bound on the oracle timing leg")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy, so that a rocprofv3 --pmc run has a dispatch of known "
+                         "traffic to scale FETCH_SIZE / WRITE_SIZE by")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -93,6 +113,14 @@ def main():
                 so.run_prepared_fused()
             else:
                 so.run_prepared()
+
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(3)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)          # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     # warm-up: builds and uploads every copy's schedule, grows scratch memory
     run(max(args.warmup, copies))
@@ -144,7 +172,9 @@ def main():
                      "kernel": ("partial_bf16_d128_kernel" if elt == 2 else "partial_f32_kernel")
                                + (" (both owners, spd_decode_step)" if fused else " (private call)"),
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "traffic": measured_traffic(args.config, "partial_bf16_d128_kernel" if elt == 2 else "partial_f32_kernel")
+                                if fused else None,
                      "bytes_per_launch": launch_bytes, "launches_timed": n_priv,
                      "mean_us": round(priv_mean_us, 2), "min_us": round(priv_min_us, 2),
                      "public_kernel": ({"bytes_per_launch": pub_bytes, "mean_us": round(pub_mean_us, 2),
