@@ -58,6 +58,36 @@ __device__ __forceinline__ void combine_row(const float *__restrict__ pl, const 
     lse_out = M + logf(den);
 }
 
+// The same for rows of at most MAXC chunks, without LDS or barriers: every load is issued at once (one memory round
+// trip), same arithmetic and chunk order as combine_row.
+template <int D, int MAXC>
+__device__ __forceinline__ void combine_row_small(const float *__restrict__ pl, const float *__restrict__ po,
+                                                  int n_chunks, int G, float &a_out, float &lse_out)
+{
+    float l[MAXC], x[MAXC];
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) {
+        const bool on = c < n_chunks;
+        l[c] = on ? pl[(int64_t)c * G] : -INFINITY;
+        x[c] = on ? po[(int64_t)c * G * D] : 0.f;
+    }
+    float M = l[0];
+#pragma unroll
+    for (int c = 1; c < MAXC; ++c)
+        M = fmaxf(M, l[c]);
+    float o = 0.f, den = 0.f;
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) {
+        if (c < n_chunks) {
+            const float w = expf(l[c] - M);
+            den += w;
+            o = fmaf(w, x[c], o);
+        }
+    }
+    a_out = o / den;
+    lse_out = M + logf(den);
+}
+
 // One workgroup of D threads per (split row, query head).
 template <int D>
 __global__ __launch_bounds__(D) void combine_chunks_kernel(const CombineRow *__restrict__ rows, int Hq, int G,
@@ -114,8 +144,15 @@ __global__ __launch_bounds__(D) void finalize_step_kernel(const RowInfo *__restr
     const int kvh = h / G, g = h % G;
     const int tid = threadIdx.x;
     const RowInfo ri = rows_in[user * Hkv + kvh], ro = rows_out[user * Hkv + kvh];
+    constexpr int kSmall = 8;
     float x0, l0, x1, l1;
-    if (ri.n_chunks > 1) {
+    if (ri.n_chunks > 1 && ri.n_chunks <= kSmall) {
+        combine_row_small<D, kSmall>(part_lse_in + (int64_t)ri.first_slot * G + g,
+                                     part_o_in + ((int64_t)ri.first_slot * G + g) * D + tid, ri.n_chunks, G, x0, l0);
+        a_in[row * D + tid] = x0;
+        if (tid == 0)
+            lse_in[row] = l0;
+    } else if (ri.n_chunks > 1) {
         combine_row<D>(part_lse_in + (int64_t)ri.first_slot * G + g,
                        part_o_in + ((int64_t)ri.first_slot * G + g) * D + tid, ri.n_chunks, G, sm_w, sm_red, x0, l0);
         a_in[row * D + tid] = x0;
@@ -125,7 +162,13 @@ __global__ __launch_bounds__(D) void finalize_step_kernel(const RowInfo *__restr
         x0 = a_in[row * D + tid];
         l0 = lse_in[row];
     }
-    if (ro.n_chunks > 1) {
+    if (ro.n_chunks > 1 && ro.n_chunks <= kSmall) {
+        combine_row_small<D, kSmall>(part_lse_out + (int64_t)ro.first_slot * G + g,
+                                     part_o_out + ((int64_t)ro.first_slot * G + g) * D + tid, ro.n_chunks, G, x1, l1);
+        a_out[row * D + tid] = x1;
+        if (tid == 0)
+            lse_out[row] = l1;
+    } else if (ro.n_chunks > 1) {
         combine_row<D>(part_lse_out + (int64_t)ro.first_slot * G + g,
                        part_o_out + ((int64_t)ro.first_slot * G + g) * D + tid, ro.n_chunks, G, sm_w, sm_red, x1, l1);
         a_out[row * D + tid] = x1;

@@ -42,9 +42,12 @@ struct DevItem {
 
 // 16-byte load of K/V data that is read exactly once: the non-temporal hint keeps the stream from displacing
 // other lines in L2 (measured: plain streaming reads reach ~6.3 TB/s on this GPU, non-temporal ones ~7.1 TB/s).
+// The pointer is cast to the global address space: base pointers arrive through memory (the work items), where the
+// compiler cannot see the address space and would otherwise emit slower FLAT loads that also tie up the LDS counter.
+typedef const u32x4 __attribute__((address_space(1))) *global_u32x4_ptr;
 __device__ __forceinline__ u32x4 stream_load16(const char *p)
 {
-    return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+    return __builtin_nontemporal_load((global_u32x4_ptr)(uintptr_t)p);
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }

@@ -62,6 +62,9 @@ __device__ __forceinline__ void load_tile(TileRegs &T, const LaneConst &L, int t
         const char *p = vp + (int64_t)(PAGED ? (t & 15) : t) * L.token_stride + L.r * 16;
         T.v[e] = stream_load16(p);
     }
+    // all 16 loads of the step are issued before anything that follows: without this the compiler sinks the V loads
+    // below the K wait to shorten live ranges, which serialises two memory round trips per step
+    __builtin_amdgcn_sched_barrier(0);
 }
 
 __device__ __forceinline__ void compute_tile(const TileRegs &T, const bf16x8 (&qB)[4], int tb, int grp, int t_end,

@@ -22,7 +22,7 @@ using spd::KvAddr;
 using spd::OwnerArgs;
 using spd::RowInfo;
 
-constexpr int kCacheEntries = 8;     // remembered schedules per entry point
+constexpr int kCacheEntries = 16;    // remembered schedules per entry point
 constexpr int kChunkAlign = 32;      // chunk boundaries are multiples of the MFMA kernel's 32-token step
 constexpr int kChunkMin = 128;       // one 32-token step for each of the four waves
 constexpr int kChunkMaxDefault = 4096;     // tokens per piece when the work exceeds one resident wave
@@ -117,11 +117,15 @@ int validate_view(const spd_shape *s, const spd_kv_view *v)
     return SPD_OK;
 }
 
-// The split schedule ("stream-K" over tokens).  Every (user, KV head) row with tokens is cut into 32-token steps;
-// the steps of all rows, laid end to end, are divided into n_pieces runs of equal length (+-1 step), one workgroup
-// each.  A piece that crosses a row boundary consists of several segments.  Equal pieces matter because the path is
-// HBM-bound: a launch lasts as long as its longest workgroup.
-//   - if no row is longer than a few hundred tokens, every row is one piece: nothing to combine afterwards;
+// The split schedule ("stream-K" over tokens).  All KV heads of a user hold the same tokens, so the schedule is laid
+// out on token steps (32 tokens) per user and replicated over the KV heads: the steps of all users, laid end to end,
+// are divided into groups of equal length (+-1 step), and every group becomes one piece (one workgroup) per KV head.
+// The pieces of a group are adjacent in launch order, so with token-major storage the heads that share DRAM pages
+// stream them at the same time.  A group that crosses a user boundary gives pieces with several segments.
+// Equal pieces matter because the path is HBM-bound: a launch lasts as long as its longest workgroup.
+//   - if no user is longer than a few hundred tokens the work is latency-bound: a standalone call then takes one
+//     whole row per workgroup (nothing to combine afterwards: saves the combine launch), the fused step, whose
+//     closing kernel combines anyway, takes chunks of 128 tokens (one step per wave: one memory round trip);
 //   - work that fits one resident wave of workgroups (2 per CU) gets exactly that many pieces;
 //   - larger work gets pieces of at most `piece_max` tokens, their number rounded up to a multiple of the resident
 //     wave, and relies on the hardware's dynamic workgroup dispatch.
@@ -132,87 +136,96 @@ struct Schedule {
     int chunk_tokens = 0;              // tokens per piece (rounded up)
 };
 
-void build_schedule(int Hkv, int n_users, const int32_t *lens, int n_cus, Schedule &S)
+void build_schedule(int Hkv, int n_users, const int32_t *lens, int n_cus, bool fused, Schedule &S)
 {
     S.items.clear();
     S.piece_first.assign(1, 0);
     S.n_slots = 0;
     S.chunk_tokens = 0;
-    int64_t T = 0;  // total 32-token steps
+    int64_t T = 0;  // total 32-token steps per KV head
     int max_len = 0;
     for (int u = 0; u < n_users; ++u) {
-        T += (int64_t)((lens[u] + kChunkAlign - 1) / kChunkAlign) * Hkv;
+        T += (lens[u] + kChunkAlign - 1) / kChunkAlign;
         max_len = std::max(max_len, lens[u]);
     }
     if (T == 0)
         return;
-    if (max_len <= env_int("SPD_NO_SPLIT_MAX", kNoSplitMaxDefault)) {
-        for (int u = 0; u < n_users; ++u) {
-            if (lens[u] == 0)
-                continue;
-            for (int h = 0; h < Hkv; ++h) {
-                spd_work_item it;
-                it.user = u;
-                it.kv_head = h;
-                it.t_begin = 0;
-                it.t_end = lens[u];
-                it.slot = (int32_t)S.n_slots++;
-                it.n_chunks = 1;
-                it.chunk = 0;
-                it.piece = (int32_t)S.items.size();
-                S.items.push_back(it);
-                S.piece_first.push_back((int32_t)S.items.size());
-            }
-        }
-        S.chunk_tokens = (max_len + kChunkAlign - 1) / kChunkAlign * kChunkAlign;
-        return;
-    }
-    const int64_t slots = (int64_t)std::max(1, n_cus) * env_int("SPD_TARGET_WG_PER_CU", kTargetWgPerCuDefault);
-    const int64_t piece_max = std::max(kChunkMin, env_int("SPD_CHUNK_MAX", kChunkMaxDefault)) / kChunkAlign;  // steps
-    int64_t W;
-    if (T <= slots * piece_max)
-        W = std::min<int64_t>(slots, (T + spd::kWaves - 1) / spd::kWaves);  // at least one step per wave
-    else
-        W = slots * ((T + slots * piece_max - 1) / (slots * piece_max));
-    S.chunk_tokens = (int)((T + W - 1) / W) * kChunkAlign;
 
-    int64_t g0 = 0;  // global step index of the current row's first step
-    int64_t p = 0;   // current piece
-    auto piece_end = [&](int64_t i) { return T * (i + 1) / W; };
-    std::vector<int32_t> row_first_item;
-    for (int u = 0; u < n_users; ++u) {
-        const int L = lens[u];
-        if (L == 0)
-            continue;
-        const int64_t steps = (L + kChunkAlign - 1) / kChunkAlign;
-        for (int h = 0; h < Hkv; ++h) {
-            const size_t first_item = S.items.size();
+    // a group: user-local step ranges; cut[g] lists (user, first step, end step)
+    struct Cut {
+        int user;
+        int64_t s0, s1;
+    };
+    std::vector<std::vector<Cut>> groups;
+    if (max_len <= env_int("SPD_NO_SPLIT_MAX", kNoSplitMaxDefault)) {
+        const int64_t per = fused ? spd::kWaves : (int64_t)1 << 40;  // steps per chunk
+        for (int u = 0; u < n_users; ++u) {
+            const int64_t steps = (lens[u] + kChunkAlign - 1) / kChunkAlign;
+            for (int64_t s0 = 0; s0 < steps; s0 += per)
+                groups.push_back({Cut{u, s0, std::min(steps, s0 + per)}});
+        }
+        S.chunk_tokens = fused ? spd::kWaves * kChunkAlign : (max_len + kChunkAlign - 1) / kChunkAlign * kChunkAlign;
+    } else {
+        const int64_t slots = (int64_t)std::max(1, n_cus) * env_int("SPD_TARGET_WG_PER_CU", kTargetWgPerCuDefault);
+        const int64_t wg = std::max<int64_t>(1, slots / Hkv);  // groups per resident wave of workgroups
+        const int64_t piece_max = std::max(kChunkMin, env_int("SPD_CHUNK_MAX", kChunkMaxDefault)) / kChunkAlign;
+        int64_t W;
+        if (T <= wg * piece_max)
+            W = std::min<int64_t>(wg, (T + spd::kWaves - 1) / spd::kWaves);  // at least one step per wave
+        else
+            W = wg * ((T + wg * piece_max - 1) / (wg * piece_max));
+        S.chunk_tokens = (int)((T + W - 1) / W) * kChunkAlign;
+        groups.resize((size_t)W);
+        int64_t g0 = 0;  // global step index of the current user's first step
+        int64_t g = 0;
+        auto group_end = [&](int64_t i) { return T * (i + 1) / W; };
+        for (int u = 0; u < n_users; ++u) {
+            const int64_t steps = (lens[u] + kChunkAlign - 1) / kChunkAlign;
             int64_t s = 0;
             while (s < steps) {
-                while (piece_end(p) <= g0 + s) {  // the current piece is used up: close it
-                    ++p;
-                    S.piece_first.push_back((int32_t)S.items.size());
-                }
-                const int64_t e = std::min(steps, piece_end(p) - g0);
-                spd_work_item it;
-                it.user = u;
-                it.kv_head = h;
-                it.t_begin = (int32_t)(s * kChunkAlign);
-                it.t_end = (int32_t)std::min<int64_t>(L, e * kChunkAlign);
-                it.slot = (int32_t)S.n_slots++;
-                it.n_chunks = 0;  // filled below
-                it.chunk = (int32_t)(S.items.size() - first_item);
-                it.piece = (int32_t)p;
-                S.items.push_back(it);
+                while (group_end(g) <= g0 + s)
+                    ++g;
+                const int64_t e = std::min(steps, group_end(g) - g0);
+                groups[(size_t)g].push_back(Cut{u, s, e});
                 s = e;
             }
-            const int32_t n_c = (int32_t)(S.items.size() - first_item);
-            for (size_t i = first_item; i < S.items.size(); ++i)
-                S.items[i].n_chunks = n_c;
             g0 += steps;
         }
     }
-    S.piece_first.push_back((int32_t)S.items.size());
+
+    // chunks per user (same for all its KV heads) and the first partial slot of every row
+    std::vector<int32_t> n_chunks((size_t)n_users, 0), seen((size_t)n_users, 0);
+    for (const auto &grp : groups)
+        for (const Cut &c : grp)
+            ++n_chunks[(size_t)c.user];
+    std::vector<int64_t> user_slot0((size_t)n_users, 0);
+    for (int u = 0; u < n_users; ++u) {
+        user_slot0[(size_t)u] = S.n_slots;
+        S.n_slots += (int64_t)n_chunks[(size_t)u] * Hkv;
+    }
+    int32_t piece = 0;
+    for (const auto &grp : groups) {
+        if (grp.empty())
+            continue;
+        for (int h = 0; h < Hkv; ++h) {
+            for (const Cut &c : grp) {
+                spd_work_item it;
+                it.user = c.user;
+                it.kv_head = h;
+                it.t_begin = (int32_t)(c.s0 * kChunkAlign);
+                it.t_end = (int32_t)std::min<int64_t>(lens[c.user], c.s1 * kChunkAlign);
+                it.n_chunks = n_chunks[(size_t)c.user];
+                it.chunk = seen[(size_t)c.user];
+                it.slot = (int32_t)(user_slot0[(size_t)c.user] + (int64_t)h * it.n_chunks + it.chunk);
+                it.piece = piece;
+                S.items.push_back(it);
+            }
+            ++piece;
+            S.piece_first.push_back((int32_t)S.items.size());
+        }
+        for (const Cut &c : grp)
+            ++seen[(size_t)c.user];
+    }
 }
 
 uint64_t fnv1a(const uint8_t *p, size_t n)
@@ -279,14 +292,14 @@ void free_entry(CachedSchedule &e)
     e = CachedSchedule();
 }
 
-void make_key(const spd_shape *s, const spd_kv_view *v, std::vector<uint8_t> &key)
+void make_key(const spd_shape *s, const spd_kv_view *v, bool fused, std::vector<uint8_t> &key)
 {
     key.clear();
     auto put = [&key](const void *p, size_t n) {
         const uint8_t *b = static_cast<const uint8_t *>(p);
         key.insert(key.end(), b, b + n);
     };
-    const int32_t head[5] = {s->dtype, s->n_q_heads, s->n_kv_heads, v->n_users, v->block_size};
+    const int32_t head[6] = {s->dtype, s->n_q_heads, s->n_kv_heads, v->n_users, v->block_size, fused ? 1 : 0};
     put(head, sizeof head);
     put(v->lens, sizeof(int32_t) * (size_t)v->n_users);
     put(&v->head_stride, sizeof v->head_stride);  // the items carry row base pointers: everything they depend on
@@ -305,11 +318,11 @@ void make_key(const spd_shape *s, const spd_kv_view *v, std::vector<uint8_t> &ke
 }
 
 // Find or build the device-resident schedule for this view.  Uploads are enqueued on `stream`.
-int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view *v, hipStream_t stream,
+int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view *v, bool fused, hipStream_t stream,
                  CachedSchedule **out)
 {
     std::vector<uint8_t> key;
-    make_key(s, v, key);
+    make_key(s, v, fused, key);
     const uint64_t h = fnv1a(key.data(), key.size());
     ++ctx->tick;
     CachedSchedule *victim = &own.cache[0];
@@ -327,7 +340,7 @@ int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view
         }
     }
     Schedule S;
-    build_schedule(s->n_kv_heads, v->n_users, v->lens, ctx->n_cus, S);
+    build_schedule(s->n_kv_heads, v->n_users, v->lens, ctx->n_cus, fused, S);
 
     // device items: the first segment of every piece (index = workgroup id), then one per row without tokens (it only
     // writes A = 0, lse = -inf), then the continuation segments, linked through `next`
@@ -496,7 +509,7 @@ void launch_f32_g(int G, dim3 grid, hipStream_t stream, const OwnerArgs &a0, con
 
 // Validation, schedule lookup and scratch growth of one partial-attention call.
 int prepare_partial(spd_ctx *ctx, int which, const spd_shape *s, const void *q, const spd_kv_view *v, float *out,
-                    float *lse, hipStream_t stream, CachedSchedule **e)
+                    float *lse, bool fused, hipStream_t stream, CachedSchedule **e)
 {
     const int rc = spd_validate_partial(s, q, v, out, lse);
     if (rc != SPD_OK)
@@ -505,7 +518,7 @@ int prepare_partial(spd_ctx *ctx, int which, const spd_shape *s, const void *q, 
     if (v->n_users == 0)
         return SPD_OK;
     Owner &own = ctx->owner[which];
-    const int rs = get_schedule(ctx, own, s, v, stream, e);
+    const int rs = get_schedule(ctx, own, s, v, fused, stream, e);
     if (rs != SPD_OK)
         return rs;
     const int G = s->n_q_heads / s->n_kv_heads;
@@ -606,7 +619,7 @@ int partial_attention(spd_ctx *ctx, int which, const spd_shape *s, const void *q
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     SPD_HIP(ctx, hipSetDevice(ctx->device));
     CachedSchedule *e = nullptr;
-    int rc = prepare_partial(ctx, which, s, q, v, out, lse, stream, &e);
+    int rc = prepare_partial(ctx, which, s, q, v, out, lse, false, stream, &e);
     if (rc != SPD_OK || !e)
         return rc;
     rc = launch_partial(ctx, which, e, v, out, lse, nullptr, nullptr, nullptr, nullptr, s, q, stream);
@@ -713,7 +726,7 @@ int spd_build_schedule(const spd_shape *shape, int32_t n_users, const int32_t *l
         if (lens[u] < 0)
             return SPD_ERR_LEN;
     Schedule S;
-    build_schedule(shape->n_kv_heads, n_users, lens, n_compute_units, S);
+    build_schedule(shape->n_kv_heads, n_users, lens, n_compute_units, false, S);
     *n_items = (int64_t)S.items.size();
     if (chunk_tokens)
         *chunk_tokens = S.chunk_tokens;
@@ -805,10 +818,10 @@ int spd_decode_step(spd_ctx *ctx, const spd_shape *shape, const void *q, const s
     if (!aligned16(y))
         return SPD_ERR_ALIGN;
     CachedSchedule *ep = nullptr, *eo = nullptr;
-    rc = prepare_partial(ctx, 0, shape, q, priv, a_in, lse_in, stream, &ep);
+    rc = prepare_partial(ctx, 0, shape, q, priv, a_in, lse_in, true, stream, &ep);
     if (rc != SPD_OK)
         return rc;
-    rc = prepare_partial(ctx, 1, shape, q, pub, a_out, lse_out, stream, &eo);  // an upload, if any, stays on `stream`
+    rc = prepare_partial(ctx, 1, shape, q, pub, a_out, lse_out, true, stream, &eo);  // an upload, if any, stays on `stream`
     if (rc != SPD_OK)
         return rc;
     // one grid for both owners, the private owner's long streams first (measured faster than public first): the
