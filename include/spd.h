@@ -149,8 +149,8 @@ int spd_decode_step(spd_ctx *ctx, const spd_shape *shape, const void *q, const s
 /*
  * Built-in timing of the partial-attention kernel (the HBM-streaming kernel of both partial calls), measured with HIP
  * events on the stream each call launches on.  spd_set_kernel_timing(ctx, n) arms timing for the next n launches of
- * each entry point (n = 0 disarms); while armed, every partial call records an event before and after its partial
- * kernel.  spd_get_kernel_timing waits for the recorded launches of one entry point (0 = private, 1 = public batched),
+ * each entry point (n = 0 disarms); while armed, every partial call launches its partial kernel with a start and a stop
+ * event attached to the dispatch itself (hipExtLaunchKernel), so the pair measures the kernel alone.  spd_get_kernel_timing waits for the recorded launches of one entry point (0 = private, 1 = public batched),
  * returns their count and mean / minimum duration in microseconds, and clears them.  spd_decode_step's single
  * two-owner launch is booked under entry point 0.
  */

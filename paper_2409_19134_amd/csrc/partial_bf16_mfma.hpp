@@ -144,7 +144,8 @@ __global__ __launch_bounds__(kThreads, PREFETCH ? 2 : 3) void partial_bf16_d128_
     float *__restrict__ lse = second ? a1.lse : a0.lse;
     __shared__ float sm_m[kWaves][16];
     __shared__ float sm_l[kWaves][16];
-    __shared__ float sm_o[kWaves][kMaxGroup * kOStride];
+    extern __shared__ float sm_o[];  // [kWaves][G * kOStride], sized by the launch: only G heads are staged
+    const int o_wave_stride = G * kOStride;
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -228,7 +229,7 @@ __global__ __launch_bounds__(kThreads, PREFETCH ? 2 : 3) void partial_bf16_d128_
             M = fmaxf(M, sm_m[w][L.r]);
         const float f = fast_exp2(m - M);  // some wave holds tokens, so M is finite; an idle wave has m = -inf, f = 0
         if (L.r < G) {
-            float *dst = &sm_o[wave][L.r * kOStride + L.grp * 32];
+            float *dst = &sm_o[wave * o_wave_stride + L.r * kOStride + L.grp * 32];
 #pragma unroll
             for (int cc = 0; cc < 8; ++cc)
 #pragma unroll
@@ -248,7 +249,7 @@ __global__ __launch_bounds__(kThreads, PREFETCH ? 2 : 3) void partial_bf16_d128_
             float o = 0.f, lt = 0.f;
 #pragma unroll
             for (int w = 0; w < kWaves; ++w) {
-                o += sm_o[w][g * kOStride + ch];
+                o += sm_o[w * o_wave_stride + g * kOStride + ch];
                 lt += sm_l[w][g] * fast_exp2(sm_m[w][g] - Mg);
             }
             const float a = o / lt;

@@ -1,6 +1,7 @@
 // Host side of the SPD decode-attention library: C ABI, argument validation, split schedule, launches.
 // The calls follow the paper's decode protocol (section 4, step 3b/3c) and Theorem 1 (section 4.2).
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <algorithm>
 #include <cmath>
@@ -487,23 +488,24 @@ int ensure_scratch(spd_ctx *ctx, Owner &own, size_t o_floats, size_t lse_floats)
     return SPD_OK;
 }
 
+// ev0 / ev1 (both null unless timing is armed) receive the kernel's own start and stop time stamps.
 template <int D, int G>
-void launch_f32(dim3 grid, hipStream_t stream, const OwnerArgs &a0, const OwnerArgs &a1, int n0, const void *q, int Hq,
-                float c)
+void launch_f32(dim3 grid, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1, const OwnerArgs &a0,
+                const OwnerArgs &a1, int n0, const void *q, int Hq, float c)
 {
-    hipLaunchKernelGGL((spd::partial_f32_kernel<D, G>), grid, dim3(spd::kThreads), 0, stream, a0, a1, n0,
-                       static_cast<const float *>(q), Hq, c);
+    hipExtLaunchKernelGGL((spd::partial_f32_kernel<D, G>), grid, dim3(spd::kThreads), 0, stream, ev0, ev1, 0, a0, a1, n0,
+                          static_cast<const float *>(q), Hq, c);
 }
 
 template <int D>
-void launch_f32_g(int G, dim3 grid, hipStream_t stream, const OwnerArgs &a0, const OwnerArgs &a1, int n0,
-                  const void *q, int Hq, float c)
+void launch_f32_g(int G, dim3 grid, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1, const OwnerArgs &a0,
+                  const OwnerArgs &a1, int n0, const void *q, int Hq, float c)
 {
     switch (G) {
-    case 1: launch_f32<D, 1>(grid, stream, a0, a1, n0, q, Hq, c); break;
-    case 2: launch_f32<D, 2>(grid, stream, a0, a1, n0, q, Hq, c); break;
-    case 4: launch_f32<D, 4>(grid, stream, a0, a1, n0, q, Hq, c); break;
-    default: launch_f32<D, 8>(grid, stream, a0, a1, n0, q, Hq, c); break;
+    case 1: launch_f32<D, 1>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
+    case 2: launch_f32<D, 2>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
+    case 4: launch_f32<D, 4>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
+    default: launch_f32<D, 8>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
     }
 }
 
@@ -558,16 +560,18 @@ int launch_partial(spd_ctx *ctx, int which, const CachedSchedule *e0, const spd_
     const float c = s->scale * spd::kLog2e;
     Owner &town = ctx->owner[e1 ? 0 : which];  // a two-owner launch is booked under entry point 0
     const bool timed = ctx->timing && town.ev_used < (int)town.ev_start.size();
-    if (timed)
-        SPD_HIP(ctx, hipEventRecord(town.ev_start[town.ev_used], stream));
+    const hipEvent_t ev0 = timed ? town.ev_start[town.ev_used] : nullptr;
+    const hipEvent_t ev1 = timed ? town.ev_stop[town.ev_used] : nullptr;
     const dim3 grid((unsigned)(n0 + n1)), block(spd::kThreads);
     if (s->dtype == SPD_BF16) {
         const uint16_t *qh = static_cast<const uint16_t *>(q);
-        // more pieces than the three-per-CU kernel can hold at once: use the prefetching two-per-CU kernel
-        const bool prefetch = n0 + n1 > (int64_t)std::max(1, ctx->n_cus) * 3;
+        const size_t lds = sizeof(float) * spd::kWaves * (size_t)G * spd::kOStride;  // cross-wave staging, G heads
+        // clearly more pieces than the three-per-CU kernel holds at once (a few left over just start a little
+        // later): use the prefetching two-per-CU kernel
+        const bool prefetch = n0 + n1 > (int64_t)std::max(1, ctx->n_cus) * 4;
 #define SPD_LAUNCH_BF16(PAGED, PREFETCH)                                                                              \
-    hipLaunchKernelGGL((spd::partial_bf16_d128_kernel<PAGED, PREFETCH>), grid, block, 0, stream, a0, a1, (int)n0, qh,    \
-                       s->n_q_heads, G, c)
+    hipExtLaunchKernelGGL((spd::partial_bf16_d128_kernel<PAGED, PREFETCH>), grid, block, (uint32_t)lds, stream, ev0,    \
+                          ev1, 0, a0, a1, (int)n0, qh, s->n_q_heads, G, c)
         if (v0->block_size) {
             if (prefetch)
                 SPD_LAUNCH_BF16(true, true);
@@ -581,13 +585,13 @@ int launch_partial(spd_ctx *ctx, int which, const CachedSchedule *e0, const spd_
         }
 #undef SPD_LAUNCH_BF16
     } else if (s->head_dim == 64) {
-        launch_f32_g<64>(G, grid, stream, a0, a1, (int)n0, q, s->n_q_heads, c);
+        launch_f32_g<64>(G, grid, stream, ev0, ev1, a0, a1, (int)n0, q, s->n_q_heads, c);
     } else {
-        launch_f32_g<128>(G, grid, stream, a0, a1, (int)n0, q, s->n_q_heads, c);
+        launch_f32_g<128>(G, grid, stream, ev0, ev1, a0, a1, (int)n0, q, s->n_q_heads, c);
     }
     SPD_HIP(ctx, hipGetLastError());
     if (timed)
-        SPD_HIP(ctx, hipEventRecord(town.ev_stop[town.ev_used++], stream));
+        ++town.ev_used;
     return SPD_OK;
 }
 
