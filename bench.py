@@ -63,7 +63,7 @@ def main():
     ap.add_argument("--mode", default="fused", choices=["fused", "calls"],
                     help="fused: spd_decode_step (public beside private on two streams, one closing kernel); "
                          "calls: the three entry points in sequence on one stream")
-    ap.add_argument("--layout", default=None, choices=["hnd", "nhd"], help="contiguous KV layout override")
+    ap.add_argument("--layout", default=None, choices=["hnd", "hnd_exact", "nhd"], help="contiguous KV layout override")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true", help="skip the parity check against the oracle")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="bound on the oracle timing leg")

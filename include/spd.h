@@ -65,8 +65,8 @@ typedef struct spd_shape {
  * One owner's KV cache for n_users users.
  *
  * Contiguous mode (block_size == 0): user u's K and V start at k_ptrs[u] / v_ptrs[u]; element (token i, KV head j,
- * channel c) is at offset i*token_stride + j*head_stride + c (in elements).  Buffers of different users may be
- * separate allocations.  A user with lens[u] == 0 may have NULL pointers.
+ * channel c) is at offset i*token_stride + j*head_stride + c (in elements; head_strides[u] instead of head_stride if
+ * that array is given).  Buffers of different users may be separate allocations.  A user with lens[u] == 0 may have NULL pointers.
  *
  * Paged mode (block_size == 16): element (token i, head j, channel c) of user u is at
  * pool + block_table[u*max_blocks + i/16]*block_stride + j*head_stride + (i%16)*token_stride + c.
@@ -80,6 +80,9 @@ typedef struct spd_kv_view {
     const void *const *v_ptrs;  /* HOST array [n_users] of DEVICE pointers (contiguous mode)              */
     int64_t token_stride;       /* elements, multiple of 16 bytes                                         */
     int64_t head_stride;        /* elements, multiple of 16 bytes                                         */
+    const int64_t *head_strides; /* HOST [n_users] or NULL: per-user head stride (contiguous mode), replacing
+                                    head_stride; lets exactly sized head-major buffers [Hkv][len][d] of different
+                                    lengths share one view                                                   */
     const void *k_pool;         /* DEVICE (paged mode)                                                    */
     const void *v_pool;         /* DEVICE (paged mode)                                                    */
     int32_t block_size;         /* 0 = contiguous, 16 = paged                                             */

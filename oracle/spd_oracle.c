@@ -52,6 +52,7 @@ typedef struct {
     const void *const *v_ptrs;
     int64_t token_stride;         /* elements between consecutive tokens              */
     int64_t head_stride;          /* elements between consecutive KV heads            */
+    const int64_t *head_strides;  /* [n_users] per-user head stride, or NULL (contiguous mode only) */
     /* paged mode (block_size > 0): one pool per tensor and a block table             */
     const void *k_pool;
     const void *v_pool;
@@ -76,7 +77,7 @@ static int64_t row_offset(const orc_view *w, int is_v, int u, int64_t i, int kv,
 {
     if (w->block_size == 0) {
         *base = is_v ? w->v_ptrs[u] : w->k_ptrs[u];
-        return i * w->token_stride + (int64_t)kv * w->head_stride;
+        return i * w->token_stride + (int64_t)kv * (w->head_strides ? w->head_strides[u] : w->head_stride);
     }
     int64_t page = w->block_table[(int64_t)u * w->max_blocks + i / w->block_size];
     *base = is_v ? w->v_pool : w->k_pool;

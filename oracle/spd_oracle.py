@@ -34,7 +34,7 @@ class _View(C.Structure):
     _fields_ = [
         ("n_users", C.c_int32), ("lens", C.POINTER(C.c_int32)),
         ("k_ptrs", C.POINTER(C.c_void_p)), ("v_ptrs", C.POINTER(C.c_void_p)),
-        ("token_stride", C.c_int64), ("head_stride", C.c_int64),
+        ("token_stride", C.c_int64), ("head_stride", C.c_int64), ("head_strides", C.POINTER(C.c_int64)),
         ("k_pool", C.c_void_p), ("v_pool", C.c_void_p), ("block_size", C.c_int32),
         ("block_table", C.POINTER(C.c_int32)), ("max_blocks", C.c_int32), ("block_stride", C.c_int64),
     ]
@@ -72,7 +72,7 @@ class HostView:
     def __init__(self, lens, token_stride, head_stride, k: Optional[Sequence[np.ndarray]] = None,
                  v: Optional[Sequence[np.ndarray]] = None, k_pool: Optional[np.ndarray] = None,
                  v_pool: Optional[np.ndarray] = None, block_size: int = 0,
-                 block_table: Optional[np.ndarray] = None, block_stride: int = 0):
+                 block_table: Optional[np.ndarray] = None, block_stride: int = 0, head_strides=None):
         self.lens = np.ascontiguousarray(lens, dtype=np.int32)
         self.n_users = int(self.lens.shape[0])
         self.k, self.v, self.k_pool, self.v_pool = k, v, k_pool, v_pool
@@ -83,6 +83,11 @@ class HostView:
         st.lens = self.lens.ctypes.data_as(C.POINTER(C.c_int32))
         st.token_stride, st.head_stride = self.token_stride, self.head_stride
         st.block_size, st.block_stride = self.block_size, self.block_stride
+        self.head_strides = None
+        if head_strides is not None:
+            self.head_strides = np.ascontiguousarray(head_strides, dtype=np.int64)
+            assert self.head_strides.shape == (self.n_users,)
+            st.head_strides = self.head_strides.ctypes.data_as(C.POINTER(C.c_int64))
         if self.block_size == 0:
             assert k is not None and v is not None and len(k) == self.n_users == len(v)
             for a in list(k) + list(v):
@@ -134,7 +139,7 @@ def from_workload(wl) -> HostWorkload:
                             v_pool=host_array(s.v_pool), block_size=PAGE_TOKENS,
                             block_table=s.block_table.cpu().numpy(), block_stride=s.block_stride)
         return HostView(s.lens, s.token_stride, s.head_stride, k=[host_array(t) for t in s.k],
-                        v=[host_array(t) for t in s.v])
+                        v=[host_array(t) for t in s.v], head_strides=getattr(s, "head_strides", None))
 
     dt = F32 if wl.dtype == torch.float32 else BF16
     return HostWorkload(dt, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.scale, host_array(wl.q),

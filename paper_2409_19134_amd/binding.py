@@ -45,7 +45,7 @@ class spd_shape(C.Structure):
 class spd_kv_view(C.Structure):
     _fields_ = [("n_users", C.c_int32), ("lens", C.POINTER(C.c_int32)),
                 ("k_ptrs", C.POINTER(C.c_void_p)), ("v_ptrs", C.POINTER(C.c_void_p)),
-                ("token_stride", C.c_int64), ("head_stride", C.c_int64),
+                ("token_stride", C.c_int64), ("head_stride", C.c_int64), ("head_strides", C.POINTER(C.c_int64)),
                 ("k_pool", C.c_void_p), ("v_pool", C.c_void_p), ("block_size", C.c_int32),
                 ("block_table", C.c_void_p), ("max_blocks", C.c_int32), ("block_stride", C.c_int64)]
 
@@ -111,7 +111,8 @@ class KVView:
     def __init__(self, lens, token_stride: int, head_stride: int, k: Optional[Sequence[torch.Tensor]] = None,
                  v: Optional[Sequence[torch.Tensor]] = None, k_pool: Optional[torch.Tensor] = None,
                  v_pool: Optional[torch.Tensor] = None, block_table: Optional[torch.Tensor] = None,
-                 block_size: int = 0, block_stride: int = 0, max_blocks: Optional[int] = None):
+                 block_size: int = 0, block_stride: int = 0, max_blocks: Optional[int] = None,
+                 head_strides=None):
         self.lens = np.ascontiguousarray(lens, dtype=np.int32)
         n = int(self.lens.shape[0])
         self._keep = (k, v, k_pool, v_pool, block_table)
@@ -120,6 +121,10 @@ class KVView:
         st.lens = self.lens.ctypes.data_as(C.POINTER(C.c_int32))
         st.token_stride, st.head_stride = int(token_stride), int(head_stride)
         st.block_size, st.block_stride = int(block_size), int(block_stride)
+        if head_strides is not None:
+            self.head_strides = np.ascontiguousarray(head_strides, dtype=np.int64)
+            assert self.head_strides.shape == (n,)
+            st.head_strides = self.head_strides.ctypes.data_as(C.POINTER(C.c_int64))
         if block_size == 0:
             assert k is not None and v is not None and len(k) == n == len(v)
             self._kp = (C.c_void_p * max(1, n))(*[t.data_ptr() if t.numel() else None for t in k])
@@ -138,7 +143,8 @@ class KVView:
         if side.paged:
             return cls(side.lens, side.token_stride, side.head_stride, k_pool=side.k_pool, v_pool=side.v_pool,
                        block_table=side.block_table, block_size=16, block_stride=side.block_stride)
-        return cls(side.lens, side.token_stride, side.head_stride, k=side.k, v=side.v)
+        return cls(side.lens, side.token_stride, side.head_stride, k=side.k, v=side.v,
+                   head_strides=getattr(side, "head_strides", None))
 
 
 def _stream_ptr(stream) -> Optional[int]:

@@ -89,6 +89,10 @@ int validate_view(const spd_shape *s, const spd_kv_view *v)
         return any ? SPD_ERR_ALIGN : SPD_OK;
     if (v->head_stride < 0 || (v->head_stride * es) % 16 != 0)
         return any ? SPD_ERR_ALIGN : SPD_OK;
+    if (v->head_strides && v->block_size == 0)
+        for (int u = 0; u < v->n_users; ++u)
+            if (v->lens[u] > 0 && (v->head_strides[u] < 0 || (v->head_strides[u] * es) % 16 != 0))
+                return SPD_ERR_ALIGN;
     if (v->block_size == 0) {
         if (any && (!v->k_ptrs || !v->v_ptrs))
             return SPD_ERR_NULL;
@@ -304,6 +308,8 @@ void make_key(const spd_shape *s, const spd_kv_view *v, bool fused, std::vector<
     put(head, sizeof head);
     put(v->lens, sizeof(int32_t) * (size_t)v->n_users);
     put(&v->head_stride, sizeof v->head_stride);  // the items carry row base pointers: everything they depend on
+    if (v->head_strides && v->block_size == 0)
+        put(v->head_strides, sizeof(int64_t) * (size_t)v->n_users);
     if (v->block_size != 0) {
         put(&v->k_pool, sizeof v->k_pool);
         put(&v->v_pool, sizeof v->v_pool);
@@ -357,7 +363,8 @@ int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view
     auto row_base = [&](int u, int h, bool is_v) -> const char * {
         const char *base = v->block_size ? static_cast<const char *>(is_v ? v->v_pool : v->k_pool)
                                          : static_cast<const char *>(is_v ? v->v_ptrs[u] : v->k_ptrs[u]);
-        return base + (int64_t)h * v->head_stride * es;
+        const int64_t hs = (v->head_strides && v->block_size == 0) ? v->head_strides[u] : v->head_stride;
+        return base + (int64_t)h * hs * es;
     };
     auto to_dev = [&](const spd_work_item &w, int rot) {
         DevItem d;

@@ -92,9 +92,10 @@ def test_config1_fp32_full_size(ctx):
     check_against_oracle(ctx, workloads.make_workload(1, DEV))
 
 
-@pytest.mark.parametrize("cfg,len_div,n_users", [(2, 4, None), (3, 64, 12), (4, 8, 48), (5, 128, 6)])
-def test_configs_reduced_lengths(ctx, cfg, len_div, n_users):
-    check_against_oracle(ctx, workloads.make_workload(cfg, DEV, len_div=len_div, n_users=n_users))
+@pytest.mark.parametrize("cfg,len_div,n_users,layout", [(2, 4, None, None), (3, 64, 12, None), (4, 8, 48, None),
+                                                        (4, 8, 48, "nhd"), (2, 8, None, "nhd"), (5, 128, 6, None)])
+def test_configs_reduced_lengths(ctx, cfg, len_div, n_users, layout):
+    check_against_oracle(ctx, workloads.make_workload(cfg, DEV, len_div=len_div, n_users=n_users, layout=layout))
 
 
 def test_config2_full_size_all_rows(ctx):
@@ -130,7 +131,7 @@ def test_full_size_sampled_rows(ctx, cfg, n):
     ([31], [33]), ([32], [32]), ([127, 128, 129], [0, 1, 2]),
     ([0, 0, 700], [5, 0, 0]), ([513, 1025, 2049], [95, 96, 97]),
 ])
-@pytest.mark.parametrize("layout,paged", [("nhd", False), ("hnd", False), ("nhd", True)])
+@pytest.mark.parametrize("layout,paged", [("nhd", False), ("hnd", False), ("hnd_exact", False), ("nhd", True)])
 def test_bf16_edge_lengths(ctx, lp, lo, layout, paged):
     wl = workloads.random_case(101, torch.bfloat16, len(lp), 32, 8, 128, lp, lo, device=DEV, layout=layout, paged=paged)
     step, _ = check_against_oracle(ctx, wl)
@@ -177,7 +178,8 @@ def test_single_user_call_equals_batched_call(ctx):
     sh = spd.make_shape(wl.dtype, 32, 8, 128, wl.scale)
     for u in range(5):
         v = spd.KVView(wl.private.lens[u:u + 1], wl.private.token_stride, wl.private.head_stride,
-                       k=[wl.private.k[u]], v=[wl.private.v[u]])
+                       k=[wl.private.k[u]], v=[wl.private.v[u]],
+                       head_strides=None if wl.private.head_strides is None else wl.private.head_strides[u:u + 1])
         a, l = ctx.spd_partial_attn_private(sh, wl.q[u:u + 1].contiguous(), v)
         torch.cuda.synchronize()
         # the split of a user's tokens depends on the batch's total work, so compare to tolerance, not bits
@@ -201,6 +203,8 @@ def test_run_to_run_determinism_and_user_permutation(ctx):
     for name in ("private", "public"):
         side = copy.copy(getattr(wl, name))
         side.lens = side.lens[perm].copy()
+        if side.head_strides is not None:
+            side.head_strides = side.head_strides[perm].copy()
         side.k = [side.k[i] for i in perm]
         side.v = [side.v[i] for i in perm]
         setattr(wp, name, side)

@@ -33,7 +33,7 @@ def _rows_as_float64(wl, side, u, kv):
     else:
         L = int(side.lens[u])
         kt, vt = side.k[u], side.v[u]
-        if side.layout == "hnd":
+        if side.layout in ("hnd", "hnd_exact"):
             k, v = kt[kv, :L], vt[kv, :L]
         else:                                      # nhd
             k, v = kt[:L, kv], vt[:L, kv]
@@ -79,7 +79,7 @@ def test_brute_force_naive_exponentials(dtype, Hq, Hkv):
 # 2. library routines: scipy softmax/logsumexp and torch fp64 scaled_dot_product_attention
 
 
-@pytest.mark.parametrize("layout,paged", [("nhd", False), ("hnd", False), ("nhd", True)])
+@pytest.mark.parametrize("layout,paged", [("nhd", False), ("hnd", False), ("hnd_exact", False), ("nhd", True)])
 def test_against_library_softmax(layout, paged):
     from scipy.special import logsumexp, softmax
     U, Hq, Hkv, d = 4, 8, 2, 64

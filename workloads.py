@@ -14,7 +14,8 @@ The five workloads follow the benchmark configurations of this repository
   3  bf16, 64 users, same heads, private U[8192,32768], public U[0,1024],
      21 of the 1024 (kv_head, channel) pairs of K scaled by 20
   4  bf16, 256 users, same heads, private lognormal(median 1024, sigma 1)
-     clipped to [16,32768], public U[0,2048], separately allocated buffers
+     clipped to [16,32768], public U[0,2048], separately allocated, exactly
+     sized head-major buffers [Hkv][len][d] (a different head stride per user)
   5  bf16, 32 users, Hq=64/Hkv=8, d=128, private U[32768,131072],
      public U[1,4096], 16-token pages with a shuffled block table
 
@@ -48,7 +49,8 @@ class KVSide:
     """One owner's KV cache for all users.
 
     Contiguous mode: ``k[u]``/``v[u]`` are separately allocated tensors, one
-    pair per user, shaped [Hkv, L, d] ("hnd") or [L, Hkv, d] ("nhd");
+    pair per user, shaped [Hkv, cap, d] ("hnd"), [Hkv, L, d] ("hnd_exact", per-user
+    ``head_strides``) or [L, Hkv, d] ("nhd");
     ``token_stride``/``head_stride`` are in elements and the channel axis is
     unit stride.  Paged mode: ``k_pool``/``v_pool`` are
     [n_blocks, Hkv, PAGE_TOKENS, d] and ``block_table`` is int32
@@ -66,6 +68,7 @@ class KVSide:
     block_table: Optional[torch.Tensor] = None
     block_stride: int = 0
     max_blocks: int = 0
+    head_strides: Optional[np.ndarray] = None   # per-user head stride (layout "hnd_exact"), else None
     layout: str = "nhd"      # contiguous mode: "nhd" or "hnd"; paged pools are [block, head, token, d]
 
     @property
@@ -144,7 +147,8 @@ def _randn(shape, gen, device, dtype):
 def _make_contig(lens, Hkv, d, dtype, device, seed_k, seed_v, layout, ch_scale):
     """Per-user buffers.  'nhd': [L, Hkv, d] (token_stride = Hkv*d, head_stride = d).
     'hnd': [Hkv, cap, d] with a common capacity cap = max(lens) rounded up to 64
-    tokens (token_stride = d, head_stride = cap*d), so one stride pair serves all users."""
+    tokens (token_stride = d, head_stride = cap*d), so one stride pair serves all users.
+    'hnd_exact': [Hkv, L, d] exactly sized per user (token_stride = d, per-user head stride L*d)."""
     gk = torch.Generator(device=device).manual_seed(seed_k)
     gv = torch.Generator(device=device).manual_seed(seed_v)
     ks, vs = [], []
@@ -153,6 +157,8 @@ def _make_contig(lens, Hkv, d, dtype, device, seed_k, seed_v, layout, ch_scale):
     elif layout == "hnd":
         cap = max(64, int(-(-int(lens.max(initial=0)) // 64) * 64))
         token_stride, head_stride = d, cap * d
+    elif layout == "hnd_exact":
+        token_stride, head_stride = d, 0
     else:
         raise ValueError(layout)
     for L in lens.tolist():
@@ -161,6 +167,11 @@ def _make_contig(lens, Hkv, d, dtype, device, seed_k, seed_v, layout, ch_scale):
             v = _randn((L, Hkv, d), gv, device, dtype)
             if ch_scale is not None and L > 0:
                 k = (k.float() * ch_scale.view(1, Hkv, d)).to(dtype)
+        elif layout == "hnd_exact":
+            k = _randn((Hkv, L, d), gk, device, dtype)
+            v = _randn((Hkv, L, d), gv, device, dtype)
+            if ch_scale is not None and L > 0:
+                k = (k.float() * ch_scale.view(Hkv, 1, d)).to(dtype)
         else:
             k = torch.zeros((Hkv, cap, d), device=device, dtype=dtype)
             v = torch.zeros((Hkv, cap, d), device=device, dtype=dtype)
@@ -172,8 +183,9 @@ def _make_contig(lens, Hkv, d, dtype, device, seed_k, seed_v, layout, ch_scale):
                 v[:, :L] = _randn((Hkv, L, d), gv, device, dtype)
         ks.append(k)
         vs.append(v)
+    hs = (lens.astype(np.int64) * d) if layout == "hnd_exact" else None
     return KVSide(lens=lens, paged=False, token_stride=token_stride, head_stride=head_stride, k=ks, v=vs,
-                  layout=layout)
+                  layout=layout, head_strides=hs)
 
 
 def _make_paged(lens, Hkv, d, dtype, device, seed_k, seed_v, seed_t, ch_scale, spare_blocks=3):
@@ -211,7 +223,7 @@ def make_workload(cfg: int, device="cpu", len_div: int = 1, n_users: Optional[in
 
     ``len_div`` divides every drawn length (for CPU-sized parity cases);
     ``n_users`` overrides the user count; ``layout`` overrides the contiguous
-    layout ("hnd" for configs 1-3, "nhd" for config 4 by default; config 5 is paged).
+    layout ("hnd" for configs 1-3, "hnd_exact" for config 4 by default; config 5 is paged).
     """
     sh = _SHAPES[cfg]
     U = sh["U"] if n_users is None else n_users
@@ -237,7 +249,7 @@ def make_workload(cfg: int, device="cpu", len_div: int = 1, n_users: Optional[in
         pub = _make_paged(lo, Hkv, d, dtype, device, seeds["k_public"], seeds["v_public"],
                           seeds["table_public"], ch_scale)
     else:
-        lay = layout or ("nhd" if cfg == 4 else "hnd")
+        lay = layout or ("hnd_exact" if cfg == 4 else "hnd")
         priv = _make_contig(lp, Hkv, d, dtype, device, seeds["k_private"], seeds["v_private"], lay, ch_scale)
         pub = _make_contig(lo, Hkv, d, dtype, device, seeds["k_public"], seeds["v_public"], lay, ch_scale)
 
