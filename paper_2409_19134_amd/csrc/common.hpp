@@ -50,6 +50,40 @@ __device__ __forceinline__ u32x4 stream_load16(const char *p)
     return __builtin_nontemporal_load((global_u32x4_ptr)(uintptr_t)p);
 }
 
+// Wave-uniform values (work item fields arrive through vector loads): tell the compiler, so that address arithmetic
+// and the block-table lookups go to the scalar unit.
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ const char *uniform(const char *p)
+{
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const char *>(((uint64_t)hi << 32) | lo);
+}
+__device__ __forceinline__ DevItem uniform(const DevItem &it)
+{
+    DevItem u;
+    u.k_base = uniform(it.k_base);
+    u.v_base = uniform(it.v_base);
+    u.user = uniform(it.user);
+    u.kv_head = uniform(it.kv_head);
+    u.t_begin = uniform(it.t_begin);
+    u.t_end = uniform(it.t_end);
+    u.slot = uniform(it.slot);
+    u.n_chunks = uniform(it.n_chunks);
+    u.next = uniform(it.next);
+    u.rot = uniform(it.rot);
+    return u;
+}
+
+// Block-table entry read through the scalar cache (the table is constant during a launch and the index is
+// wave-uniform): it neither waits behind the vector loads of the K/V stream nor delays them.
+typedef const int32_t __attribute__((address_space(4))) *const_i32_ptr;
+__device__ __forceinline__ int scalar_load_i32(const int32_t *p, int idx)
+{
+    return ((const_i32_ptr)(uintptr_t)p)[idx];
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 __device__ __forceinline__ float wave_xor_max(float v, int mask) { return fmaxf(v, __shfl_xor(v, mask)); }

@@ -44,9 +44,14 @@ __device__ __forceinline__ void load_tile(TileRegs &T, const LaneConst &L, int t
     const int gv = tb + L.grp * 8;       // first token of the group this lane's V rows fall in
     const char *kp = L.k_base, *vp = L.v_base;
     if (PAGED) {
-        // an 8-token group never straddles a 16-token page; clamping keeps the lookup inside the user's pages
-        kp += (int64_t)L.bt_row[min(gk, t_last) >> 4] * L.block_stride;
-        vp += (int64_t)L.bt_row[min(gv, t_last) >> 4] * L.block_stride;
+        // A 32-token step touches two 16-token pages; their ids are wave-uniform and come through the scalar cache.
+        // Clamping keeps the lookups inside the user's pages; rows past the chunk re-read its last token, which lies
+        // in the page the clamped lookup names (an 8-token group never straddles a page).
+        const int tbu = uniform(tb);
+        const int64_t p0 = scalar_load_i32(L.bt_row, min(tbu, t_last) >> 4);
+        const int64_t p1 = scalar_load_i32(L.bt_row, min(tbu + 16, t_last) >> 4);
+        kp += ((gk - tb) >= 16 ? p1 : p0) * L.block_stride;
+        vp += ((gv - tb) >= 16 ? p1 : p0) * L.block_stride;
     }
 #pragma unroll
     for (int a = 0; a < 2; ++a) {
@@ -156,7 +161,7 @@ __global__ __launch_bounds__(kThreads, PREFETCH ? 2 : 3) void partial_bf16_d128_
     L.block_stride = kv.block_stride;
 
     for (int seg = second ? (int)blockIdx.x - n0 : (int)blockIdx.x;;) {
-        const DevItem it = items[seg];
+        const DevItem it = uniform(items[seg]);
         if (it.n_chunks == 0) {  // a row without tokens is a piece of its own
             write_empty_row<128>(it, G, Hq, out, lse);
             return;
@@ -186,7 +191,7 @@ __global__ __launch_bounds__(kThreads, PREFETCH ? 2 : 3) void partial_bf16_d128_
 
         const int t_last = it.t_end - 1;
         constexpr int kStep = 32 * kWaves;
-        int tb = it.t_begin + ((wave - it.rot) & (kWaves - 1)) * 32;  // the waves take interleaved 32-token steps
+        int tb = it.t_begin + ((uniform(wave) - it.rot) & (kWaves - 1)) * 32;  // the waves take interleaved 32-token steps
         if (!PREFETCH) {
             for (; tb < it.t_end; tb += kStep) {
                 TileRegs T0;
