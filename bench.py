@@ -63,6 +63,9 @@ def main():
     ap.add_argument("--mode", default="fused", choices=["fused", "calls"],
                     help="fused: spd_decode_step (public beside private on two streams, one closing kernel); "
                          "calls: the three entry points in sequence on one stream")
+    ap.add_argument("--append", action="store_true",
+                    help="fused mode only: also append one new token per user to the public cache in the same launch "
+                         "(its slot is the cache's last token, rewritten every step)")
     ap.add_argument("--layout", default=None, choices=["hnd", "hnd_exact", "nhd"], help="contiguous KV layout override")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true", help="skip the parity check against the oracle")
@@ -101,8 +104,14 @@ def main():
     q = wl.q
 
     stream_ptr = torch.cuda.current_stream().cuda_stream
+    k_new = v_new = None
+    if args.append:
+        assert args.mode == "fused" and int(wl.public.lens.min()) >= 1, "--append needs --mode fused and no empty public part"
+        gen = torch.Generator(device=dev).manual_seed(1000 * args.config + 10)
+        k_new = torch.randn((wl.n_users, wl.n_kv_heads, wl.head_dim), generator=gen, device=dev).to(wl.dtype)
+        v_new = torch.randn((wl.n_users, wl.n_kv_heads, wl.head_dim), generator=gen, device=dev).to(wl.dtype)
     for so in steps_objs:
-        so.prepare(q, stream_ptr)
+        so.prepare(q, stream_ptr, k_new, v_new)
 
     fused = args.mode == "fused"
 
@@ -165,7 +174,7 @@ def main():
         "config": {"workload": f"config{args.config}:{wl.name}", "n_users": wl.n_users, "n_q_heads": wl.n_q_heads,
                    "n_kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim,
                    "private_tokens": wl.private.n_tokens, "public_tokens": wl.public.n_tokens,
-                   "kv_bytes_per_step": kv_bytes, "kv_copies_cycled": copies, "mode": args.mode,
+                   "kv_bytes_per_step": kv_bytes, "kv_copies_cycled": copies, "mode": args.mode, "kv_append": bool(args.append),
                    "layout": "paged16" if wl.private.paged else wl.private.layout,
                    "seeds": wl.seeds},
         "roofline": {"bound": "hbm",

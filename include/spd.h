@@ -123,6 +123,20 @@ int spd_partial_attn_public_batched(spd_ctx *ctx, const spd_shape *shape, const 
                                     float *out, float *lse, void *hip_stream);
 
 /*
+ * KV append fused into the public partial (protocol step 3a followed by 3c; Figure 3 steps 2 and 3): the new token's
+ * K and V rows, k_new / v_new DEVICE [n_users][Hkv][d] in shape->dtype, become token lens[u] - 1 of every user's
+ * public cache - `pub->lens` already counts the new token, so every length must be >= 1 - and the partial is
+ * computed over the cache including it.  The same launch writes the rows into the cache (contiguous: the buffer must
+ * have room for lens[u] tokens; paged: the block table must already name the page of position lens[u] - 1) and reads
+ * them from k_new / v_new, so no separate copy kernel and no ordering between the two is needed.  The cache memory
+ * behind `pub` is written by this call although the view type is const.  Other arguments as for
+ * spd_partial_attn_public_batched.
+ */
+int spd_partial_attn_public_batched_append(spd_ctx *ctx, const spd_shape *shape, const void *q, const void *k_new,
+                                           const void *v_new, const spd_kv_view *pub, float *out, float *lse,
+                                           void *hip_stream);
+
+/*
  * Merge two partials row by row (Theorem 1 with the coefficients of section 4.2 rewritten on log-sum-exps):
  *   lse = logaddexp(lse0, lse1); w0 = exp(lse0 - lse); w1 = exp(lse1 - lse); y = w0*a0 + w1*a1.
  * A row whose lse is -inf on one side takes the other side unchanged; -inf on both sides gives y = 0, lse = -inf,
@@ -142,12 +156,13 @@ int spd_lse_merge(spd_ctx *ctx, int32_t n_rows, int32_t head_dim, const float *a
  *   a_in, lse_in   = spd_partial_attn_private(q, priv)            [n_users][Hq][d], [n_users][Hq]
  *   a_out, lse_out = spd_partial_attn_public_batched(q, pub)
  *   y, lse, w_in   = spd_lse_merge(a_in, lse_in, a_out, lse_out)   (all three required here)
+ * With k_new and v_new non-NULL (both or neither) the public part is spd_partial_attn_public_batched_append.
  * priv and pub must describe the same users.  Uses the scratch memory of both partial entry points: it must not
  * overlap in time with any other call on the same context.
  */
 int spd_decode_step(spd_ctx *ctx, const spd_shape *shape, const void *q, const spd_kv_view *priv,
-                    const spd_kv_view *pub, float *a_in, float *lse_in, float *a_out, float *lse_out, float *y,
-                    float *lse, float *w_in, void *hip_stream);
+                    const spd_kv_view *pub, const void *k_new, const void *v_new, float *a_in, float *lse_in,
+                    float *a_out, float *lse_out, float *y, float *lse, float *w_in, void *hip_stream);
 
 /*
  * Built-in timing of the partial-attention kernel (the HBM-streaming kernel of both partial calls), measured with HIP

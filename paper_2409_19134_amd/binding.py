@@ -24,7 +24,7 @@ EXPORTED_SYMBOLS = (
     "spd_create", "spd_destroy", "spd_strerror", "spd_last_hip_error",
     "spd_partial_attn_private", "spd_partial_attn_public_batched", "spd_lse_merge",
     "spd_validate_partial", "spd_build_schedule", "spd_set_kernel_timing", "spd_get_kernel_timing",
-    "spd_decode_step",
+    "spd_decode_step", "spd_partial_attn_public_batched_append",
 )
 
 
@@ -77,7 +77,10 @@ def _load() -> C.CDLL:
     lib.spd_lse_merge.argtypes = [vp, C.c_int32, C.c_int32, fp, fp, fp, fp, fp, fp, fp, vp]
     lib.spd_decode_step.restype = C.c_int
     lib.spd_decode_step.argtypes = [vp, C.POINTER(spd_shape), vp, C.POINTER(spd_kv_view), C.POINTER(spd_kv_view),
-                                    fp, fp, fp, fp, fp, fp, fp, vp]
+                                    vp, vp, fp, fp, fp, fp, fp, fp, fp, vp]
+    lib.spd_partial_attn_public_batched_append.restype = C.c_int
+    lib.spd_partial_attn_public_batched_append.argtypes = [vp, C.POINTER(spd_shape), vp, vp, vp,
+                                                           C.POINTER(spd_kv_view), fp, fp, vp]
     lib.spd_set_kernel_timing.restype = C.c_int
     lib.spd_set_kernel_timing.argtypes = [vp, C.c_int32]
     lib.spd_get_kernel_timing.restype = C.c_int
@@ -210,15 +213,35 @@ class Context:
         return self._partial(lib.spd_partial_attn_public_batched, "spd_partial_attn_public_batched", shape, q, view,
                              out, lse, stream)
 
-    def spd_decode_step(self, shape, q, private, public, a_in, lse_in, a_out, lse_out, y, lse, w_in, stream=None):
+    def spd_partial_attn_public_batched_append(self, shape, q, k_new, v_new, view, out=None, lse=None, stream=None):
+        n, Hq, d = view.struct.n_users, shape.n_q_heads, shape.head_dim
+        if out is None:
+            out = torch.empty((n, Hq, d), device=q.device, dtype=torch.float32)
+        if lse is None:
+            lse = torch.empty((n, Hq), device=q.device, dtype=torch.float32)
+        for t in (k_new, v_new):
+            assert t.is_contiguous() and t.dtype == q.dtype and tuple(t.shape) == (n, shape.n_kv_heads, d)
+        assert q.is_contiguous() and tuple(q.shape) == (n, Hq, d)
+        rc = lib.spd_partial_attn_public_batched_append(self.handle, C.byref(shape), q.data_ptr(), k_new.data_ptr(),
+                                                        v_new.data_ptr(), C.byref(view.struct), out.data_ptr(),
+                                                        lse.data_ptr(), _stream_ptr(stream))
+        self._check(rc, "spd_partial_attn_public_batched_append")
+        return out, lse
+
+    def spd_decode_step(self, shape, q, private, public, a_in, lse_in, a_out, lse_out, y, lse, w_in, stream=None,
+                        k_new=None, v_new=None):
         n, Hq, d = private.struct.n_users, shape.n_q_heads, shape.head_dim
         for t in (a_in, a_out, y):
             assert t.is_contiguous() and t.dtype == torch.float32 and tuple(t.shape) == (n, Hq, d)
         for t in (lse_in, lse_out, lse, w_in):
             assert t.is_contiguous() and t.dtype == torch.float32 and tuple(t.shape) == (n, Hq)
         assert q.is_contiguous() and tuple(q.shape) == (n, Hq, d)
+        for t in (k_new, v_new):
+            assert t is None or (t.is_contiguous() and t.dtype == q.dtype and tuple(t.shape) == (n, shape.n_kv_heads, d))
         rc = lib.spd_decode_step(self.handle, C.byref(shape), q.data_ptr(), C.byref(private.struct),
-                                 C.byref(public.struct), a_in.data_ptr(), lse_in.data_ptr(), a_out.data_ptr(),
+                                 C.byref(public.struct), None if k_new is None else k_new.data_ptr(),
+                                 None if v_new is None else v_new.data_ptr(),
+                                 a_in.data_ptr(), lse_in.data_ptr(), a_out.data_ptr(),
                                  lse_out.data_ptr(), y.data_ptr(), lse.data_ptr(), w_in.data_ptr(), _stream_ptr(stream))
         self._check(rc, "spd_decode_step")
         return y

@@ -37,8 +37,10 @@ struct DevItem {
     int32_t slot;      // where this segment's partial goes when the row has several segments
     int32_t n_chunks;  // segments of the row; 1: the segment writes the final result itself
     int32_t next;      // index of the piece's next segment, -1 if none
-    int32_t rot;       // 32-token steps the piece has already handed out (mod 4): keeps the four waves evenly loaded
+    int32_t rot;       // bits 0-1: 32-token steps the piece has already handed out (mod 4), keeps the four waves
+                       // evenly loaded; bit 8 (kEndsRow): the segment ends at the last token of its row
 };
+constexpr int kEndsRow = 0x100;
 
 // 16-byte load of K/V data that is read exactly once: the non-temporal hint keeps the stream from displacing
 // other lines in L2 (measured: plain streaming reads reach ~6.3 TB/s on this GPU, non-temporal ones ~7.1 TB/s).
@@ -84,6 +86,11 @@ __device__ __forceinline__ int scalar_load_i32(const int32_t *p, int idx)
     return ((const_i32_ptr)(uintptr_t)p)[idx];
 }
 
+__device__ __forceinline__ void copy16(char *dst, const char *src)
+{
+    *reinterpret_cast<u32x4 *>(dst) = *reinterpret_cast<const u32x4 *>(src);
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 __device__ __forceinline__ float wave_xor_max(float v, int mask) { return fmaxf(v, __shfl_xor(v, mask)); }
@@ -108,6 +115,10 @@ struct OwnerArgs {
     float *part_lse;  // [slots][G]
     float *out;       // [U][Hq][D]
     float *lse;       // [U][Hq]
+    // KV append (protocol step 3a), or nullptr: [U][Hkv][D] rows of the new token's K and V.  The row's last token
+    // (position lens[u] - 1) is then taken from here, and the segment that ends the row also writes it to the cache.
+    const char *k_new;
+    const char *v_new;
 };
 
 // A row (user, KV head) whose tokens were split into several chunks.

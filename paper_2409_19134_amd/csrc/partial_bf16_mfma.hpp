@@ -35,6 +35,8 @@ struct LaneConst {
     const char *v_base;
     const int32_t *bt_row;
     int64_t token_stride, block_stride;
+    const char *k_new_row;  // KV append: this (user, KV head)'s new K / V row if the segment ends its row, else nullptr
+    const char *v_new_row;
 };
 
 template <bool PAGED>
@@ -57,6 +59,8 @@ __device__ __forceinline__ void load_tile(TileRegs &T, const LaneConst &L, int t
     for (int a = 0; a < 2; ++a) {
         const int t = min(gk + a * 4 + (L.r & 3), t_last);  // rows past the chunk re-read its last token (masked later)
         const char *p = kp + (int64_t)(PAGED ? (t & 15) : t) * L.token_stride + L.grp * 16;
+        if (L.k_new_row && t == t_last)  // the appended token is read from the caller's buffer, not from the cache
+            p = L.k_new_row + L.grp * 16;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk)
             T.k[a][kk] = stream_load16(p + kk * 64);
@@ -65,6 +69,8 @@ __device__ __forceinline__ void load_tile(TileRegs &T, const LaneConst &L, int t
     for (int e = 0; e < 8; ++e) {
         const int t = min(gv + e, t_last);
         const char *p = vp + (int64_t)(PAGED ? (t & 15) : t) * L.token_stride + L.r * 16;
+        if (L.v_new_row && t == t_last)
+            p = L.v_new_row + L.r * 16;
         T.v[e] = stream_load16(p);
     }
     // all 16 loads of the step are issued before anything that follows: without this the compiler sinks the V loads
@@ -147,6 +153,8 @@ __global__ __launch_bounds__(kThreads, PREFETCH ? 2 : 3) void partial_bf16_d128_
     float *__restrict__ part_lse = second ? a1.part_lse : a0.part_lse;
     float *__restrict__ out = second ? a1.out : a0.out;
     float *__restrict__ lse = second ? a1.lse : a0.lse;
+    const char *k_new = second ? a1.k_new : a0.k_new;
+    const char *v_new = second ? a1.v_new : a0.v_new;
     __shared__ float sm_m[kWaves][16];
     __shared__ float sm_l[kWaves][16];
     extern __shared__ float sm_o[];  // [kWaves][G * kOStride], sized by the launch: only G heads are staged
@@ -169,6 +177,25 @@ __global__ __launch_bounds__(kThreads, PREFETCH ? 2 : 3) void partial_bf16_d128_
         L.k_base = it.k_base;
         L.v_base = it.v_base;
         L.bt_row = PAGED ? kv.block_table + (int64_t)it.user * kv.max_blocks : nullptr;
+        const int t_last = it.t_end - 1;
+        L.k_new_row = L.v_new_row = nullptr;
+        if (k_new && (it.rot & kEndsRow)) {
+            // KV append: this segment holds the row's last token, which is the new one.  Wave 0 copies its K and V
+            // rows into the cache (lanes 0-15: K, 16-31: V); every reader of that token takes it from the caller's
+            // buffer instead, so nothing waits for the copy.
+            const int64_t row = ((int64_t)it.user * (Hq / G) + it.kv_head) * 256;
+            L.k_new_row = k_new + row;
+            L.v_new_row = v_new + row;
+            if (wave == 0 && lane < 32) {
+                int64_t off = (int64_t)(PAGED ? (t_last & 15) : t_last) * kv.token_stride + (lane & 15) * 16;
+                if (PAGED)
+                    off += (int64_t)scalar_load_i32(L.bt_row, t_last >> 4) * kv.block_stride;
+                if (lane < 16)
+                    copy16(const_cast<char *>(it.k_base) + off, L.k_new_row + lane * 16);
+                else
+                    copy16(const_cast<char *>(it.v_base) + off, L.v_new_row + (lane - 16) * 16);
+            }
+        }
 
         // Q as the B operand: head r (zero beyond G), channels kk*32 + grp*8 .. +8
         bf16x8 qB[4];
@@ -189,9 +216,8 @@ __global__ __launch_bounds__(kThreads, PREFETCH ? 2 : 3) void partial_bf16_d128_
         for (int cc = 0; cc < 8; ++cc)
             acc[cc] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-        const int t_last = it.t_end - 1;
         constexpr int kStep = 32 * kWaves;
-        int tb = it.t_begin + ((uniform(wave) - it.rot) & (kWaves - 1)) * 32;  // the waves take interleaved 32-token steps
+        int tb = it.t_begin + ((uniform(wave) - (it.rot & 3)) & (kWaves - 1)) * 32;  // the waves take interleaved 32-token steps
         if (!PREFETCH) {
             for (; tb < it.t_end; tb += kStep) {
                 TileRegs T0;

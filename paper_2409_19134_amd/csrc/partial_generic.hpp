@@ -22,6 +22,8 @@ __global__ __launch_bounds__(kThreads) void partial_f32_kernel(
     float *__restrict__ part_lse = second ? a1.part_lse : a0.part_lse;
     float *__restrict__ out = second ? a1.out : a0.out;
     float *__restrict__ lse = second ? a1.lse : a0.lse;
+    const char *k_new = second ? a1.k_new : a0.k_new;
+    const char *v_new = second ? a1.v_new : a0.v_new;
     constexpr int EPL = 4;          // fp32 elements per 16-byte lane load
     constexpr int LPR = D / EPL;    // lanes per row: 16 (D=64) or 32 (D=128)
     constexpr int RPW = 64 / LPR;   // rows per wave per step
@@ -65,6 +67,23 @@ __global__ __launch_bounds__(kThreads) void partial_f32_kernel(
     }
 
     const int t_last = it.t_end - 1;
+    // KV append: the row's last token is the new one; it is read from the caller's buffer and wave 0 copies it into
+    // the cache (lanes [0, LPR): K, [LPR, 2*LPR): V; 2*LPR <= 64)
+    const char *k_new_row = nullptr, *v_new_row = nullptr;
+    if (k_new && (it.rot & kEndsRow)) {
+        const int64_t row = ((int64_t)it.user * (Hq / G) + it.kv_head) * D * 4;
+        k_new_row = k_new + row;
+        v_new_row = v_new + row;
+        if (wave == 0 && lane < 2 * LPR) {
+            int64_t off = paged ? (int64_t)bt_row[t_last >> 4] * kv.block_stride + (int64_t)(t_last & 15) * kv.token_stride
+                                : (int64_t)t_last * kv.token_stride;
+            off += (lane % LPR) * 16;
+            if (lane < LPR)
+                copy16(const_cast<char *>(k_base) + off, k_new_row + (lane % LPR) * 16);
+            else
+                copy16(const_cast<char *>(v_base) + off, v_new_row + (lane % LPR) * 16);
+        }
+    }
     for (int tb = it.t_begin + wave * RPW; tb < it.t_end; tb += RPW * kWaves) {
         const int t = tb + rs;
         const int tc = min(t, t_last);
@@ -74,8 +93,9 @@ __global__ __launch_bounds__(kThreads) void partial_f32_kernel(
         else
             off = (int64_t)tc * kv.token_stride;
         off += cl * 16;
-        const f32x4 kk = *reinterpret_cast<const f32x4 *>(k_base + off);
-        const f32x4 vv = *reinterpret_cast<const f32x4 *>(v_base + off);
+        const bool is_new = k_new_row && tc == t_last;
+        const f32x4 kk = *reinterpret_cast<const f32x4 *>(is_new ? k_new_row + cl * 16 : k_base + off);
+        const f32x4 vv = *reinterpret_cast<const f32x4 *>(is_new ? v_new_row + cl * 16 : v_base + off);
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             float s = qr[g][0] * kk[0];

@@ -377,7 +377,7 @@ int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view
         d.slot = w.slot;
         d.n_chunks = w.n_chunks;
         d.next = -1;
-        d.rot = rot & (spd::kWaves - 1);
+        d.rot = (rot & (spd::kWaves - 1)) | (w.t_end == v->lens[w.user] ? spd::kEndsRow : 0);
         return d;
     };
     for (int64_t pc = 0; pc < n_pieces; ++pc) {
@@ -535,7 +535,7 @@ int prepare_partial(spd_ctx *ctx, int which, const spd_shape *s, const void *q, 
 }
 
 OwnerArgs owner_args(const Owner &own, const CachedSchedule *e, const spd_shape *s, const spd_kv_view *v, float *out,
-                     float *lse)
+                     float *lse, const void *k_new, const void *v_new)
 {
     const int es = elt_size(s->dtype);
     OwnerArgs a;
@@ -548,21 +548,30 @@ OwnerArgs owner_args(const Owner &own, const CachedSchedule *e, const spd_shape 
     a.part_lse = own.part_lse;
     a.out = out;
     a.lse = lse;
+    a.k_new = static_cast<const char *>(k_new);
+    a.v_new = static_cast<const char *>(v_new);
     return a;
 }
 
 // The partial kernel: every piece's workgroup writes final rows or chunk partials.  One owner per launch
 // (e1 == nullptr), or both owners' pieces in one grid (the fused step; both views in the same storage mode).
+struct NewToken {  // KV append for the public owner (protocol step 3a); both null if none
+    const void *k = nullptr, *v = nullptr;
+};
+
 int launch_partial(spd_ctx *ctx, int which, const CachedSchedule *e0, const spd_kv_view *v0, float *out0, float *lse0,
                    const CachedSchedule *e1, const spd_kv_view *v1, float *out1, float *lse1, const spd_shape *s,
-                   const void *q, hipStream_t stream)
+                   const void *q, NewToken nt, hipStream_t stream)
 {
     const int64_t n0 = e0->n_items, n1 = e1 ? e1->n_items : 0;
     if (n0 + n1 == 0)
         return SPD_OK;
     Owner &own0 = ctx->owner[which];
-    const OwnerArgs a0 = owner_args(own0, e0, s, v0, out0, lse0);
-    const OwnerArgs a1 = e1 ? owner_args(ctx->owner[1 - which], e1, s, v1, out1, lse1) : a0;
+    // the public owner is entry point 1: the new token, if any, belongs to whichever of the two that is
+    const OwnerArgs a0 = owner_args(own0, e0, s, v0, out0, lse0, which == 1 ? nt.k : nullptr, which == 1 ? nt.v : nullptr);
+    const OwnerArgs a1 = e1 ? owner_args(ctx->owner[1 - which], e1, s, v1, out1, lse1, which == 0 ? nt.k : nullptr,
+                                         which == 0 ? nt.v : nullptr)
+                            : a0;
     const int G = s->n_q_heads / s->n_kv_heads;
     const float c = s->scale * spd::kLog2e;
     Owner &town = ctx->owner[e1 ? 0 : which];  // a two-owner launch is booked under entry point 0
@@ -622,18 +631,38 @@ int launch_combine(spd_ctx *ctx, int which, const CachedSchedule *e, const spd_s
     return SPD_OK;
 }
 
+// An append needs both rows, 16-byte aligned, and at least the new token itself in every user's length.
+int validate_new_token(const spd_kv_view *v, NewToken nt)
+{
+    if (!nt.k && !nt.v)
+        return SPD_OK;
+    if (!nt.k || !nt.v)
+        return SPD_ERR_NULL;
+    if (!aligned16(nt.k) || !aligned16(nt.v))
+        return SPD_ERR_ALIGN;
+    for (int u = 0; u < v->n_users; ++u)
+        if (v->lens[u] < 1)
+            return SPD_ERR_LEN;
+    return SPD_OK;
+}
+
 int partial_attention(spd_ctx *ctx, int which, const spd_shape *s, const void *q, const spd_kv_view *v, float *out,
-                      float *lse, void *hip_stream)
+                      float *lse, NewToken nt, void *hip_stream)
 {
     if (!ctx)
         return SPD_ERR_NULL;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     SPD_HIP(ctx, hipSetDevice(ctx->device));
     CachedSchedule *e = nullptr;
-    int rc = prepare_partial(ctx, which, s, q, v, out, lse, false, stream, &e);
+    int rc = spd_validate_partial(s, q, v, out, lse);
+    if (rc == SPD_OK)
+        rc = validate_new_token(v, nt);
+    if (rc != SPD_OK)
+        return rc;
+    rc = prepare_partial(ctx, which, s, q, v, out, lse, false, stream, &e);
     if (rc != SPD_OK || !e)
         return rc;
-    rc = launch_partial(ctx, which, e, v, out, lse, nullptr, nullptr, nullptr, nullptr, s, q, stream);
+    rc = launch_partial(ctx, which, e, v, out, lse, nullptr, nullptr, nullptr, nullptr, s, q, nt, stream);
     if (rc != SPD_OK)
         return rc;
     return launch_combine(ctx, which, e, s, out, lse, stream);
@@ -795,19 +824,34 @@ int spd_get_kernel_timing(spd_ctx *ctx, int32_t entry_point, int32_t *n_launches
 int spd_partial_attn_private(spd_ctx *ctx, const spd_shape *shape, const void *q, const spd_kv_view *priv, float *out,
                              float *lse, void *hip_stream)
 {
-    return partial_attention(ctx, 0, shape, q, priv, out, lse, hip_stream);
+    return partial_attention(ctx, 0, shape, q, priv, out, lse, NewToken(), hip_stream);
 }
 
 int spd_partial_attn_public_batched(spd_ctx *ctx, const spd_shape *shape, const void *q, const spd_kv_view *pub,
                                     float *out, float *lse, void *hip_stream)
 {
-    return partial_attention(ctx, 1, shape, q, pub, out, lse, hip_stream);
+    return partial_attention(ctx, 1, shape, q, pub, out, lse, NewToken(), hip_stream);
+}
+
+int spd_partial_attn_public_batched_append(spd_ctx *ctx, const spd_shape *shape, const void *q, const void *k_new,
+                                           const void *v_new, const spd_kv_view *pub, float *out, float *lse,
+                                           void *hip_stream)
+{
+    if (!k_new || !v_new)
+        return SPD_ERR_NULL;
+    NewToken nt;
+    nt.k = k_new;
+    nt.v = v_new;
+    return partial_attention(ctx, 1, shape, q, pub, out, lse, nt, hip_stream);
 }
 
 int spd_decode_step(spd_ctx *ctx, const spd_shape *shape, const void *q, const spd_kv_view *priv,
-                    const spd_kv_view *pub, float *a_in, float *lse_in, float *a_out, float *lse_out, float *y,
-                    float *lse, float *w_in, void *hip_stream)
+                    const spd_kv_view *pub, const void *k_new, const void *v_new, float *a_in, float *lse_in,
+                    float *a_out, float *lse_out, float *y, float *lse, float *w_in, void *hip_stream)
 {
+    NewToken nt;
+    nt.k = k_new;
+    nt.v = v_new;
     if (!ctx)
         return SPD_ERR_NULL;
     if (!priv || !pub)
@@ -820,6 +864,8 @@ int spd_decode_step(spd_ctx *ctx, const spd_shape *shape, const void *q, const s
     int rc = spd_validate_partial(shape, q, priv, a_in, lse_in);
     if (rc == SPD_OK)
         rc = spd_validate_partial(shape, q, pub, a_out, lse_out);
+    if (rc == SPD_OK)
+        rc = validate_new_token(pub, nt);
     if (rc != SPD_OK)
         return rc;
     if (priv->n_users == 0)
@@ -838,14 +884,14 @@ int spd_decode_step(spd_ctx *ctx, const spd_shape *shape, const void *q, const s
     // one grid for both owners, the private owner's long streams first (measured faster than public first): the
     // public owner's short, latency-bound pieces then run beside them on the workgroup slots that remain
     if ((priv->block_size != 0) == (pub->block_size != 0)) {
-        rc = launch_partial(ctx, 0, ep, priv, a_in, lse_in, eo, pub, a_out, lse_out, shape, q, stream);
+        rc = launch_partial(ctx, 0, ep, priv, a_in, lse_in, eo, pub, a_out, lse_out, shape, q, nt, stream);
         if (rc != SPD_OK)
             return rc;
     } else {  // different storage modes need different kernel instances
-        rc = launch_partial(ctx, 1, eo, pub, a_out, lse_out, nullptr, nullptr, nullptr, nullptr, shape, q, stream);
+        rc = launch_partial(ctx, 1, eo, pub, a_out, lse_out, nullptr, nullptr, nullptr, nullptr, shape, q, nt, stream);
         if (rc != SPD_OK)
             return rc;
-        rc = launch_partial(ctx, 0, ep, priv, a_in, lse_in, nullptr, nullptr, nullptr, nullptr, shape, q, stream);
+        rc = launch_partial(ctx, 0, ep, priv, a_in, lse_in, nullptr, nullptr, nullptr, nullptr, shape, q, NewToken(), stream);
         if (rc != SPD_OK)
             return rc;
     }

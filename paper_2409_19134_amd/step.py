@@ -39,12 +39,13 @@ class DecodeStep:
         c.spd_lse_merge(self.a_in, self.lse_in, self.a_out, self.lse_out, self.y, self.lse, self.w_in, stream)
         return self.y
 
-    def run_fused(self, q: torch.Tensor, stream=None):
-        """The same step through spd_decode_step: public beside private on two streams, one closing kernel."""
+    def run_fused(self, q: torch.Tensor, stream=None, k_new=None, v_new=None):
+        """The same step through spd_decode_step: one launch for both owners, one closing kernel.  With k_new / v_new
+        the new token is appended to the public cache in the same launch (the view's lengths already count it)."""
         return self.ctx.spd_decode_step(self.shape, q, self.private, self.public, self.a_in, self.lse_in, self.a_out,
-                                        self.lse_out, self.y, self.lse, self.w_in, stream)
+                                        self.lse_out, self.y, self.lse, self.w_in, stream, k_new, v_new)
 
-    def prepare(self, q: torch.Tensor, stream_ptr: int):
+    def prepare(self, q: torch.Tensor, stream_ptr: int, k_new=None, v_new=None):
         """Marshal the three calls' arguments once; `run_prepared` then only makes the three C calls.
         For loops that reuse the same q buffer and stream (serving loops, benchmarks)."""
         import ctypes as C
@@ -52,7 +53,7 @@ class DecodeStep:
         n, Hq, d = self.private.struct.n_users, self.shape.n_q_heads, self.shape.head_dim
         assert q.is_contiguous() and tuple(q.shape) == (n, Hq, d)
         h, sp, st = self.ctx.handle, C.byref(self.shape), C.c_void_p(stream_ptr)
-        self._keep_q = q
+        self._keep_q = (q, k_new, v_new)
         self._calls = (
             (lib.spd_partial_attn_private, (h, sp, q.data_ptr(), C.byref(self.private.struct),
                                             self.a_in.data_ptr(), self.lse_in.data_ptr(), st)),
@@ -64,7 +65,9 @@ class DecodeStep:
         )
 
         self._fused = (lib.spd_decode_step, (h, sp, q.data_ptr(), C.byref(self.private.struct),
-                                             C.byref(self.public.struct), self.a_in.data_ptr(),
+                                             C.byref(self.public.struct),
+                                             None if k_new is None else k_new.data_ptr(),
+                                             None if v_new is None else v_new.data_ptr(), self.a_in.data_ptr(),
                                              self.lse_in.data_ptr(), self.a_out.data_ptr(), self.lse_out.data_ptr(),
                                              self.y.data_ptr(), self.lse.data_ptr(), self.w_in.data_ptr(), st))
 
