@@ -1,0 +1,129 @@
+"""Runtime behaviour of the library on the GPU: schedule cache eviction, scratch growth, streams, several contexts."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from oracle import spd_oracle as orc
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _oracle_y(wl):
+    return orc.attention(orc.from_workload(wl))[0]
+
+
+def _err(step, Y):
+    return float(np.abs(step.y.cpu().double().numpy().reshape(Y.shape) - Y).max())
+
+
+def test_more_views_than_cache_entries_and_scratch_growth():
+    """40 distinct views (the cache remembers 16 per entry point), sizes going up and down: every result stays right,
+    also when an evicted view comes back."""
+    import paper_2409_19134_amd as spd
+    ctx = spd.Context(0)
+    rng = np.random.default_rng(3)
+    cases = []
+    for i in range(40):
+        U = int(rng.integers(1, 5))
+        lp = rng.integers(0, 3000 if i % 7 else 20000, size=U).tolist()
+        lo = rng.integers(0, 300, size=U).tolist()
+        wl = workloads.random_case(300 + i, torch.bfloat16, U, 32, 8, 128, lp, lo, device=DEV,
+                                   layout=("nhd", "hnd", "hnd_exact")[i % 3], paged=(i % 5 == 0))
+        cases.append((wl, spd.DecodeStep.from_workload(ctx, wl), _oracle_y(wl)))
+    for rnd in range(2):
+        for j, (wl, step, Y) in enumerate(cases):
+            if (j + rnd) % 2:
+                step.run_fused(wl.q)
+            else:
+                step.run(wl.q)
+        torch.cuda.synchronize()      # all 40 were enqueued back to back: evictions happened with work in flight
+        for wl, step, Y in cases:
+            assert _err(step, Y) <= 2e-3
+    ctx.close()
+
+
+def test_private_and_public_calls_on_two_streams():
+    """The two partial calls use separate scratch memory and may overlap on two streams; the merge waits for both."""
+    import paper_2409_19134_amd as spd
+    ctx = spd.Context(0)
+    wl = workloads.random_case(401, torch.bfloat16, 6, 32, 8, 128, [5000, 100, 0, 900, 2500, 64], [300, 900, 5, 0, 64, 1],
+                               device=DEV)
+    step = spd.DecodeStep.from_workload(ctx, wl)
+    Y = _oracle_y(wl)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    for _ in range(5):
+        ctx.spd_partial_attn_private(step.shape, wl.q, step.private, step.a_in, step.lse_in, stream=s1)
+        ctx.spd_partial_attn_public_batched(step.shape, wl.q, step.public, step.a_out, step.lse_out, stream=s2)
+        s1.wait_stream(s2)
+        ctx.spd_lse_merge(step.a_in, step.lse_in, step.a_out, step.lse_out, step.y, step.lse, step.w_in, stream=s1)
+        s2.wait_stream(s1)
+    torch.cuda.synchronize()
+    assert _err(step, Y) <= 2e-3
+    ctx.close()
+
+
+def test_two_contexts_and_non_default_stream():
+    import paper_2409_19134_amd as spd
+    a, b = spd.Context(0), spd.Context(0)
+    wl = workloads.make_workload(2, DEV, len_div=8)
+    Y = _oracle_y(wl)
+    sa, sb = spd.DecodeStep.from_workload(a, wl), spd.DecodeStep.from_workload(b, wl)
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        sa.run_fused(wl.q)          # binding picks up torch's current stream
+    sb.run(wl.q)
+    torch.cuda.synchronize()
+    assert _err(sa, Y) <= 2e-3 and _err(sb, Y) <= 2e-3
+    a.close()
+    b.close()
+
+
+def test_kernel_timing_counts_launches():
+    import paper_2409_19134_amd as spd
+    ctx = spd.Context(0)
+    wl = workloads.make_workload(2, DEV, len_div=8)
+    step = spd.DecodeStep.from_workload(ctx, wl)
+    step.run(wl.q)
+    ctx.spd_set_kernel_timing(3)
+    for _ in range(5):
+        step.run(wl.q)              # only the first three launches of each entry point are timed
+    n0, mean0, min0 = ctx.spd_get_kernel_timing(0)
+    n1, mean1, min1 = ctx.spd_get_kernel_timing(1)
+    assert (n0, n1) == (3, 3) and 0 < min0 <= mean0 < 1e4 and 0 < min1 <= mean1 < 1e4
+    assert ctx.spd_get_kernel_timing(0)[0] == 0      # reading clears
+    ctx.spd_set_kernel_timing(0)
+    step.run_fused(wl.q)
+    torch.cuda.synchronize()
+    assert ctx.spd_get_kernel_timing(0)[0] == 0
+    ctx.close()
+
+
+def test_zero_users_and_decode_step_validation():
+    import ctypes as C
+    import paper_2409_19134_amd as spd
+    ctx = spd.Context(0)
+    wl = workloads.random_case(409, torch.bfloat16, 2, 32, 8, 128, [10, 20], [3, 4], device=DEV)
+    step = spd.DecodeStep.from_workload(ctx, wl)
+    empty = spd.KVView([], 1024, 128, k=[], v=[])
+    q0 = torch.empty((0, 32, 128), device=DEV, dtype=torch.bfloat16)
+    out0 = torch.empty((0, 32, 128), device=DEV)
+    lse0 = torch.empty((0, 32), device=DEV)
+    rc = spd.lib.spd_partial_attn_private(ctx.handle, C.byref(step.shape), None, C.byref(empty.struct), None, None, None)
+    assert rc == spd.SPD_OK                          # nothing to do is not an error
+    one = spd.KVView(wl.public.lens[:1], wl.public.token_stride, wl.public.head_stride, k=wl.public.k[:1], v=wl.public.v[:1])
+    rc = spd.lib.spd_decode_step(ctx.handle, C.byref(step.shape), wl.q.data_ptr(), C.byref(step.private.struct),
+                                 C.byref(one.struct), None, None, step.a_in.data_ptr(), step.lse_in.data_ptr(),
+                                 step.a_out.data_ptr(), step.lse_out.data_ptr(), step.y.data_ptr(), step.lse.data_ptr(),
+                                 step.w_in.data_ptr(), None)
+    assert rc == spd.SPD_ERR_LEN                     # the two owners must describe the same users
+    rc = spd.lib.spd_decode_step(ctx.handle, C.byref(step.shape), wl.q.data_ptr(), C.byref(step.private.struct),
+                                 C.byref(step.public.struct), None, None, step.a_in.data_ptr(), step.lse_in.data_ptr(),
+                                 step.a_out.data_ptr(), step.lse_out.data_ptr(), None, step.lse.data_ptr(),
+                                 step.w_in.data_ptr(), None)
+    assert rc == spd.SPD_ERR_NULL
+    assert spd.lib.spd_lse_merge(ctx.handle, 4, 130, step.a_in.data_ptr(), step.lse_in.data_ptr(), step.a_out.data_ptr(),
+                                 step.lse_out.data_ptr(), step.y.data_ptr(), None, None, None) == spd.SPD_ERR_SHAPE
+    ctx.close()
