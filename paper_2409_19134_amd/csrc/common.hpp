@@ -78,6 +78,27 @@ __device__ __forceinline__ DevItem uniform(const DevItem &it)
     return u;
 }
 
+// A work item read through the scalar cache (items are constant during a launch, the index is wave-uniform): the
+// fields land in scalar registers and cost no vector registers while they wait to be used.
+typedef const uint32_t __attribute__((address_space(4))) *const_u32_ptr;
+__device__ __forceinline__ DevItem scalar_load_item(const DevItem *items, int idx)
+{
+    static_assert(sizeof(DevItem) == 48, "DevItem is read as 12 dwords");
+    const const_u32_ptr w = (const_u32_ptr)(uintptr_t)(items + idx);
+    DevItem it;
+    it.k_base = reinterpret_cast<const char *>(((uint64_t)w[1] << 32) | w[0]);
+    it.v_base = reinterpret_cast<const char *>(((uint64_t)w[3] << 32) | w[2]);
+    it.user = (int32_t)w[4];
+    it.kv_head = (int32_t)w[5];
+    it.t_begin = (int32_t)w[6];
+    it.t_end = (int32_t)w[7];
+    it.slot = (int32_t)w[8];
+    it.n_chunks = (int32_t)w[9];
+    it.next = (int32_t)w[10];
+    it.rot = (int32_t)w[11];
+    return it;
+}
+
 // Block-table entry read through the scalar cache (the table is constant during a launch and the index is
 // wave-uniform): it neither waits behind the vector loads of the K/V stream nor delays them.
 typedef const int32_t __attribute__((address_space(4))) *const_i32_ptr;

@@ -162,18 +162,16 @@ __global__ __launch_bounds__(kThreads, PREFETCH ? 2 : 3) void partial_bf16_d128_
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    LaneConst L;
-    L.r = lane & 15;
-    L.grp = lane >> 4;
-    L.token_stride = kv.token_stride;
-    L.block_stride = kv.block_stride;
+    constexpr int kStep = 32 * kWaves;
 
-    for (int seg = second ? (int)blockIdx.x - n0 : (int)blockIdx.x;;) {
-        const DevItem it = uniform(items[seg]);
-        if (it.n_chunks == 0) {  // a row without tokens is a piece of its own
-            write_empty_row<128>(it, G, Hq, out, lse);
-            return;
-        }
+    // Everything a segment needs before its first MFMA: addresses, the KV append copy, Q, and the loads of the wave's
+    // first 32-token step.  Issued for the *next* segment before the current one's epilogue, so that the barriers
+    // and the result stores of the epilogue overlap the memory round trip instead of preceding it.
+    auto begin_segment = [&](const DevItem &it, LaneConst &L, bf16x8 (&qB)[4], int &tb, TileRegs &T0) {
+        L.r = lane & 15;
+        L.grp = lane >> 4;
+        L.token_stride = kv.token_stride;
+        L.block_stride = kv.block_stride;
         L.k_base = it.k_base;
         L.v_base = it.v_base;
         L.bt_row = PAGED ? kv.block_table + (int64_t)it.user * kv.max_blocks : nullptr;
@@ -196,19 +194,38 @@ __global__ __launch_bounds__(kThreads, PREFETCH ? 2 : 3) void partial_bf16_d128_
                     copy16(const_cast<char *>(it.v_base) + off, L.v_new_row + (lane - 16) * 16);
             }
         }
-
         // Q as the B operand: head r (zero beyond G), channels kk*32 + grp*8 .. +8
-        bf16x8 qB[4];
-        {
-            const uint16_t *qrow = q + ((int64_t)it.user * Hq + (int64_t)it.kv_head * G + L.r) * 128 + L.grp * 8;
+        const uint16_t *qrow = q + ((int64_t)it.user * Hq + (int64_t)it.kv_head * G + L.r) * 128 + L.grp * 8;
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                u32x4 w = {0u, 0u, 0u, 0u};
-                if (L.r < G)
-                    w = *reinterpret_cast<const u32x4 *>(qrow + kk * 32);
-                qB[kk] = __builtin_bit_cast(bf16x8, w);
-            }
+        for (int kk = 0; kk < 4; ++kk) {
+            u32x4 w = {0u, 0u, 0u, 0u};
+            if (L.r < G)
+                w = *reinterpret_cast<const u32x4 *>(qrow + kk * 32);
+            qB[kk] = __builtin_bit_cast(bf16x8, w);
         }
+        // the waves take interleaved 32-token steps
+        tb = it.t_begin + ((uniform(wave) - (it.rot & 3)) & (kWaves - 1)) * 32;
+        if (PREFETCH && tb < it.t_end)
+            load_tile<PAGED>(T0, L, tb, t_last);
+    };
+
+    DevItem it = scalar_load_item(items, second ? (int)blockIdx.x - n0 : (int)blockIdx.x);
+    if (it.n_chunks == 0) {  // a row without tokens is a piece of its own
+        write_empty_row<128>(it, G, Hq, out, lse);
+        return;
+    }
+    LaneConst L;
+    bf16x8 qB[4];
+    int tb;
+    TileRegs T0;
+    begin_segment(it, L, qB, tb, T0);
+    for (;;) {
+        // the piece's next segment is fetched (scalar cache) long before it is looked at: with tens of MB of loads in
+        // flight a dependent round trip costs microseconds, so none may sit between two segments
+        DevItem nx = it;
+        if (it.next >= 0)
+            nx = scalar_load_item(items, it.next);
+        const int t_last = it.t_end - 1;
 
         float m = -INFINITY, l = 0.f;
         f32x4 acc[8];
@@ -216,51 +233,55 @@ __global__ __launch_bounds__(kThreads, PREFETCH ? 2 : 3) void partial_bf16_d128_
         for (int cc = 0; cc < 8; ++cc)
             acc[cc] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-        constexpr int kStep = 32 * kWaves;
-        int tb = it.t_begin + ((uniform(wave) - (it.rot & 3)) & (kWaves - 1)) * 32;  // the waves take interleaved 32-token steps
         if (!PREFETCH) {
             for (; tb < it.t_end; tb += kStep) {
-                TileRegs T0;
-                load_tile<PAGED>(T0, L, tb, t_last);
-                compute_tile(T0, qB, tb, L.grp, it.t_end, scale_log2e, m, l, acc);
+                TileRegs T;
+                load_tile<PAGED>(T, L, tb, t_last);
+                compute_tile(T, qB, tb, L.grp, it.t_end, scale_log2e, m, l, acc);
             }
-        } else if (tb < it.t_end) {
-            TileRegs T0, T1;
-            load_tile<PAGED>(T0, L, tb, t_last);
-            while (true) {
-                const int tb1 = tb + kStep;
-                const bool more1 = tb1 < it.t_end;
-                if (more1)
-                    load_tile<PAGED>(T1, L, tb1, t_last);
-                compute_tile(T0, qB, tb, L.grp, it.t_end, scale_log2e, m, l, acc);
-                if (!more1)
-                    break;
-                const int tb2 = tb1 + kStep;
-                const bool more2 = tb2 < it.t_end;
-                if (more2)
-                    load_tile<PAGED>(T0, L, tb2, t_last);
-                compute_tile(T1, qB, tb1, L.grp, it.t_end, scale_log2e, m, l, acc);
-                if (!more2)
-                    break;
-                tb = tb2;
+        } else if (tb < it.t_end) {  // T0 already holds (the loads of) step tb
+            {
+                TileRegs T1;
+                for (;;) {
+                    const int tb1 = tb + kStep;
+                    const bool more1 = tb1 < it.t_end;
+                    if (more1)
+                        load_tile<PAGED>(T1, L, tb1, t_last);
+                    compute_tile(T0, qB, tb, L.grp, it.t_end, scale_log2e, m, l, acc);
+                    if (!more1)
+                        break;
+                    const int tb2 = tb1 + kStep;
+                    const bool more2 = tb2 < it.t_end;
+                    if (more2)
+                        load_tile<PAGED>(T0, L, tb2, t_last);
+                    compute_tile(T1, qB, tb1, L.grp, it.t_end, scale_log2e, m, l, acc);
+                    if (!more2)
+                        break;
+                    tb = tb2;
+                }
             }
         }
+
+        const int grp = L.grp, r = L.r;
+        // the two-per-CU kernel has the registers to let the next segment's loads fly during the epilogue below
+        if (PREFETCH && it.next >= 0)
+            begin_segment(nx, L, qB, tb, T0);
 
         // ---- combine the lane groups (sum of l) and the four waves (LDS) ----
         l += __shfl_xor(l, 16);
         l += __shfl_xor(l, 32);
-        if (L.grp == 0) {
-            sm_m[wave][L.r] = m;
-            sm_l[wave][L.r] = l;
+        if (grp == 0) {
+            sm_m[wave][r] = m;
+            sm_l[wave][r] = l;
         }
         __syncthreads();
-        float M = sm_m[0][L.r];
+        float M = sm_m[0][r];
 #pragma unroll
         for (int w = 1; w < kWaves; ++w)
-            M = fmaxf(M, sm_m[w][L.r]);
+            M = fmaxf(M, sm_m[w][r]);
         const float f = fast_exp2(m - M);  // some wave holds tokens, so M is finite; an idle wave has m = -inf, f = 0
-        if (L.r < G) {
-            float *dst = &sm_o[wave * o_wave_stride + L.r * kOStride + L.grp * 32];
+        if (r < G) {
+            float *dst = &sm_o[wave * o_wave_stride + r * kOStride + grp * 32];
 #pragma unroll
             for (int cc = 0; cc < 8; ++cc)
 #pragma unroll
@@ -298,7 +319,9 @@ __global__ __launch_bounds__(kThreads, PREFETCH ? 2 : 3) void partial_bf16_d128_
         }
         if (it.next < 0)
             return;
-        seg = it.next;
+        if (!PREFETCH)
+            begin_segment(nx, L, qB, tb, T0);
+        it = nx;
         __syncthreads();  // the LDS staging arrays are reused by the next segment
     }
 }

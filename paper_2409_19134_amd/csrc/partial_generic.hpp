@@ -31,8 +31,11 @@ __global__ __launch_bounds__(kThreads) void partial_f32_kernel(
     __shared__ float sm_l[kWaves][G];
     __shared__ float sm_o[kWaves][G][D];
 
-    for (int seg = second ? (int)blockIdx.x - n0 : (int)blockIdx.x;;) {
-        const DevItem it = items[seg];
+    DevItem fetched = items[second ? (int)blockIdx.x - n0 : (int)blockIdx.x];
+    for (;;) {
+        const DevItem it = fetched;
+        if (it.next >= 0)  // fetch the piece's next segment early; it is looked at only when this one is done
+            fetched = items[it.next];
         if (it.n_chunks == 0) {  // a row without tokens is a piece of its own
             write_empty_row<D>(it, G, Hq, out, lse);
             return;
@@ -182,7 +185,6 @@ __global__ __launch_bounds__(kThreads) void partial_f32_kernel(
         }
         if (it.next < 0)
             return;
-        seg = it.next;
         __syncthreads();  // the LDS staging arrays are reused by the next segment
     }
 }
