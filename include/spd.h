@@ -104,6 +104,14 @@ const char *spd_strerror(int code);
 int spd_last_hip_error(const spd_ctx *ctx);
 
 /*
+ * How often a call had to build and upload a split schedule (`builds`) and how often it found the one it needed among
+ * those it remembers (`hits`).  A schedule is determined by the lengths, the storage mode and strides and, in
+ * contiguous mode, the per-user base pointers - not by q, the outputs, the block table or the pools; so the layers of
+ * a model that share lengths and a block table share one schedule per decode step.
+ */
+int spd_get_schedule_stats(const spd_ctx *ctx, int64_t *builds, int64_t *hits);
+
+/*
  * Private partial attention (protocol step 3b; A_in of Theorem 1): for every user u of `priv` and query head h,
  *   out[u][h][:] = softmax(scale * q[u][h] . K_in[u]^T) V_in[u],   lse[u][h] = ln sum_i exp(scale * <q[u][h], k_i>).
  * A user's rows depend only on that user's q row and buffers, so n_users == 1 is the paper's per-process call and

@@ -24,7 +24,7 @@ EXPORTED_SYMBOLS = (
     "spd_create", "spd_destroy", "spd_strerror", "spd_last_hip_error",
     "spd_partial_attn_private", "spd_partial_attn_public_batched", "spd_lse_merge",
     "spd_validate_partial", "spd_build_schedule", "spd_set_kernel_timing", "spd_get_kernel_timing",
-    "spd_decode_step", "spd_partial_attn_public_batched_append",
+    "spd_decode_step", "spd_partial_attn_public_batched_append", "spd_get_schedule_stats",
 )
 
 
@@ -81,6 +81,8 @@ def _load() -> C.CDLL:
     lib.spd_partial_attn_public_batched_append.restype = C.c_int
     lib.spd_partial_attn_public_batched_append.argtypes = [vp, C.POINTER(spd_shape), vp, vp, vp,
                                                            C.POINTER(spd_kv_view), fp, fp, vp]
+    lib.spd_get_schedule_stats.restype = C.c_int
+    lib.spd_get_schedule_stats.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
     lib.spd_set_kernel_timing.restype = C.c_int
     lib.spd_set_kernel_timing.argtypes = [vp, C.c_int32]
     lib.spd_get_kernel_timing.restype = C.c_int
@@ -195,6 +197,12 @@ class Context:
                 _stream_ptr(stream))
         self._check(rc, name)
         return out, lse
+
+    def spd_get_schedule_stats(self):
+        """(builds, hits) of the split-schedule cache."""
+        b, h = C.c_int64(0), C.c_int64(0)
+        self._check(lib.spd_get_schedule_stats(self.handle, C.byref(b), C.byref(h)), "spd_get_schedule_stats")
+        return int(b.value), int(h.value)
 
     def spd_set_kernel_timing(self, max_launches: int):
         self._check(lib.spd_set_kernel_timing(self.handle, int(max_launches)), "spd_set_kernel_timing")

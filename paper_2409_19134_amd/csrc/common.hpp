@@ -28,7 +28,7 @@ struct KvAddr {
 // One segment of work as the kernels read it: tokens [t_begin, t_end) of one (user, KV head) row.  A workgroup
 // processes a *piece*: a short list of segments linked by `next` (a piece that crosses a row boundary has one
 // segment per row it touches).  k_base / v_base point at channel 0 of token 0 of the row (contiguous mode) or at the
-// KV head's offset inside the pool (paged mode).  n_chunks == 0 marks a row without tokens: the workgroup only
+// KV head's offset inside the pool (paged mode: a byte offset stored as a pointer, the pool base travels in OwnerArgs).  n_chunks == 0 marks a row without tokens: the workgroup only
 // writes A = 0, lse = -inf.
 struct DevItem {
     const char *k_base;
@@ -131,6 +131,8 @@ __device__ __forceinline__ void write_empty_row(const DevItem &it, int G, int Hq
 // decode step - both at once: workgroups [0, n0) take owner 0's pieces, the rest owner 1's.
 struct OwnerArgs {
     const DevItem *items;
+    const char *k_pool;  // paged mode: the items' k_base / v_base are byte offsets inside these; else nullptr
+    const char *v_pool;
     KvAddr kv;
     float *part_o;    // [slots][G][D] chunk partials of split rows
     float *part_lse;  // [slots][G]

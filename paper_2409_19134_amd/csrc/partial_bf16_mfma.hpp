@@ -149,6 +149,8 @@ __global__ __launch_bounds__(kThreads, PREFETCH ? 2 : 3) void partial_bf16_d128_
     const bool second = (int)blockIdx.x >= n0;  // workgroup-uniform: which owner this workgroup serves
     const DevItem *__restrict__ items = second ? a1.items : a0.items;
     const KvAddr kv = second ? a1.kv : a0.kv;
+    const uintptr_t k_pool = reinterpret_cast<uintptr_t>(second ? a1.k_pool : a0.k_pool);  // 0 unless paged
+    const uintptr_t v_pool = reinterpret_cast<uintptr_t>(second ? a1.v_pool : a0.v_pool);
     float *__restrict__ part_o = second ? a1.part_o : a0.part_o;
     float *__restrict__ part_lse = second ? a1.part_lse : a0.part_lse;
     float *__restrict__ out = second ? a1.out : a0.out;
@@ -172,8 +174,8 @@ __global__ __launch_bounds__(kThreads, PREFETCH ? 2 : 3) void partial_bf16_d128_
         L.grp = lane >> 4;
         L.token_stride = kv.token_stride;
         L.block_stride = kv.block_stride;
-        L.k_base = it.k_base;
-        L.v_base = it.v_base;
+        L.k_base = it.k_base + k_pool;
+        L.v_base = it.v_base + v_pool;
         L.bt_row = PAGED ? kv.block_table + (int64_t)it.user * kv.max_blocks : nullptr;
         const int t_last = it.t_end - 1;
         L.k_new_row = L.v_new_row = nullptr;
@@ -189,9 +191,9 @@ __global__ __launch_bounds__(kThreads, PREFETCH ? 2 : 3) void partial_bf16_d128_
                 if (PAGED)
                     off += (int64_t)scalar_load_i32(L.bt_row, t_last >> 4) * kv.block_stride;
                 if (lane < 16)
-                    copy16(const_cast<char *>(it.k_base) + off, L.k_new_row + lane * 16);
+                    copy16(const_cast<char *>(L.k_base) + off, L.k_new_row + lane * 16);
                 else
-                    copy16(const_cast<char *>(it.v_base) + off, L.v_new_row + (lane - 16) * 16);
+                    copy16(const_cast<char *>(L.v_base) + off, L.v_new_row + (lane - 16) * 16);
             }
         }
         // Q as the B operand: head r (zero beyond G), channels kk*32 + grp*8 .. +8

@@ -265,6 +265,8 @@ struct CachedSchedule {
     char *dev = nullptr;     // DevItem[n_items] | CombineRow[n_split_rows] | RowInfo[n_users * Hkv]
     char *pinned = nullptr;  // host staging copy of the same blob
     size_t capacity = 0;
+    hipStream_t last_stream = nullptr;  // stream of the latest call that used this entry
+    hipEvent_t uploaded = nullptr;      // completes when the latest upload has left the staging copy
 };
 
 struct Owner {
@@ -284,6 +286,7 @@ struct spd_ctx {
     int n_cus = 0;
     int last_hip = 0;
     uint64_t tick = 0;
+    int64_t schedule_builds = 0, schedule_hits = 0;
     bool timing = false;
     Owner owner[2];
 };
@@ -305,6 +308,8 @@ void free_entry(CachedSchedule &e)
         (void)hipFree(e.dev);
     if (e.pinned)
         (void)hipHostFree(e.pinned);
+    if (e.uploaded)
+        (void)hipEventDestroy(e.uploaded);
     e = CachedSchedule();
 }
 
@@ -318,13 +323,12 @@ void make_key(const spd_shape *s, const spd_kv_view *v, bool fused, std::vector<
     const int32_t head[6] = {s->dtype, s->n_q_heads, s->n_kv_heads, v->n_users, v->block_size, fused ? 1 : 0};
     put(head, sizeof head);
     put(v->lens, sizeof(int32_t) * (size_t)v->n_users);
-    put(&v->head_stride, sizeof v->head_stride);  // the items carry row base pointers: everything they depend on
+    // the items carry row base addresses (contiguous mode) or row offsets inside the pools (paged mode): the key holds
+    // everything those depend on.  The pools themselves are not part of it, so the layers of a model, which share
+    // lengths and block table but have a pool each, share one schedule.
+    put(&v->head_stride, sizeof v->head_stride);
     if (v->head_strides && v->block_size == 0)
         put(v->head_strides, sizeof(int64_t) * (size_t)v->n_users);
-    if (v->block_size != 0) {
-        put(&v->k_pool, sizeof v->k_pool);
-        put(&v->v_pool, sizeof v->v_pool);
-    }
     if (v->block_size == 0) {
         for (int u = 0; u < v->n_users; ++u) {  // pointers of empty users are never read: normalise them
             const void *kp = v->lens[u] ? v->k_ptrs[u] : nullptr;
@@ -347,6 +351,8 @@ int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view
     for (auto &e : own.cache) {
         if (e.valid && e.hash == h && e.key == key) {
             e.last_use = ctx->tick;
+            e.last_stream = stream;
+            ++ctx->schedule_hits;
             *out = &e;
             return SPD_OK;
         }
@@ -372,7 +378,7 @@ int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view
     std::vector<DevItem> dev_items((size_t)n_groups);
     dev_items.reserve((size_t)n_groups + S.items.size());
     auto row_base = [&](int u, int h, bool is_v) -> const char * {
-        const char *base = v->block_size ? static_cast<const char *>(is_v ? v->v_pool : v->k_pool)
+        const char *base = v->block_size ? nullptr  // paged: an offset, the kernel adds the pool
                                          : static_cast<const char *>(is_v ? v->v_ptrs[u] : v->k_ptrs[u]);
         const int64_t hs = (v->head_strides && v->block_size == 0) ? v->head_strides[u] : v->head_stride;
         return base + (int64_t)h * hs * es;
@@ -445,17 +451,24 @@ int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view
     const size_t total = off_info + (b_info + 255) / 256 * 256 + 256;
 
     CachedSchedule &e = *victim;
-    if (e.valid || e.capacity < total) {
-        if (e.valid)
-            SPD_HIP(ctx, hipDeviceSynchronize());  // a kernel or copy in flight may still read the evicted blob
-        const size_t cap = std::max(total, e.capacity);
-        if (e.capacity < total) {
-            free_entry(e);
-            SPD_HIP(ctx, hipMalloc(reinterpret_cast<void **>(&e.dev), cap));
-            SPD_HIP(ctx, hipHostMalloc(reinterpret_cast<void **>(&e.pinned), cap, hipHostMallocDefault));
-            e.capacity = cap;
-        }
+    ++ctx->schedule_builds;
+    if (e.valid) {
+        // Reusing an entry: work in flight may still read its device blob, and its last upload may still read the
+        // staging copy.  On the same stream the new upload is ordered behind that work anyway; another stream is
+        // waited for.  The staging copy is only rewritten once its last upload has completed.
+        if (e.last_stream != stream)
+            SPD_HIP(ctx, hipStreamSynchronize(e.last_stream));
+        SPD_HIP(ctx, hipEventSynchronize(e.uploaded));
     }
+    if (e.capacity < total) {
+        const size_t cap = std::max(total, e.capacity);
+        free_entry(e);  // hipFree waits for the device
+        SPD_HIP(ctx, hipMalloc(reinterpret_cast<void **>(&e.dev), cap));
+        SPD_HIP(ctx, hipHostMalloc(reinterpret_cast<void **>(&e.pinned), cap, hipHostMallocDefault));
+        e.capacity = cap;
+    }
+    if (!e.uploaded)
+        SPD_HIP(ctx, hipEventCreateWithFlags(&e.uploaded, hipEventDisableTiming));
     std::memset(e.pinned, 0, total);
     if (b_items)
         std::memcpy(e.pinned, dev_items.data(), b_items);
@@ -464,6 +477,8 @@ int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view
     if (b_info)
         std::memcpy(e.pinned + off_info, row_info.data(), b_info);
     SPD_HIP(ctx, hipMemcpyAsync(e.dev, e.pinned, total, hipMemcpyHostToDevice, stream));
+    SPD_HIP(ctx, hipEventRecord(e.uploaded, stream));
+    e.last_stream = stream;
     e.valid = true;
     e.hash = h;
     e.key.swap(key);
@@ -551,6 +566,8 @@ OwnerArgs owner_args(const Owner &own, const CachedSchedule *e, const spd_shape 
     const int es = elt_size(s->dtype);
     OwnerArgs a;
     a.items = reinterpret_cast<const DevItem *>(e->dev);
+    a.k_pool = v->block_size ? static_cast<const char *>(v->k_pool) : nullptr;
+    a.v_pool = v->block_size ? static_cast<const char *>(v->v_pool) : nullptr;
     a.kv.block_table = v->block_size ? v->block_table : nullptr;
     a.kv.max_blocks = v->max_blocks;
     a.kv.block_stride = v->block_stride * es;
@@ -744,6 +761,15 @@ int spd_destroy(spd_ctx *ctx)
 }
 
 int spd_last_hip_error(const spd_ctx *ctx) { return ctx ? ctx->last_hip : 0; }
+
+int spd_get_schedule_stats(const spd_ctx *ctx, int64_t *builds, int64_t *hits)
+{
+    if (!ctx || !builds || !hits)
+        return SPD_ERR_NULL;
+    *builds = ctx->schedule_builds;
+    *hits = ctx->schedule_hits;
+    return SPD_OK;
+}
 
 int spd_validate_partial(const spd_shape *shape, const void *q, const spd_kv_view *view, const float *out,
                          const float *lse)

@@ -127,3 +127,46 @@ def test_zero_users_and_decode_step_validation():
     assert spd.lib.spd_lse_merge(ctx.handle, 4, 130, step.a_in.data_ptr(), step.lse_in.data_ptr(), step.a_out.data_ptr(),
                                  step.lse_out.data_ptr(), step.y.data_ptr(), None, None, None) == spd.SPD_ERR_SHAPE
     ctx.close()
+
+
+def test_layers_share_one_schedule_per_step_in_paged_mode():
+    """A model's layers share lengths and block table and own a pool each: one schedule per owner serves them all.
+    Three decode steps over four layers, each step appending one token per user to every layer's public cache."""
+    import copy
+    import paper_2409_19134_amd as spd
+    ctx = spd.Context(0)
+    U, Hq, Hkv, d, n_layers, n_steps = 3, 32, 8, 128, 4, 3
+    lp, lo0 = [700, 40, 2100], [30, 1, 200]
+    cap = [x + n_steps for x in lo0]          # pages for the tokens that will be appended exist from the start
+    base = workloads.random_case(500, torch.bfloat16, U, Hq, Hkv, d, lp, cap, device=DEV, paged=True)
+    layers = []
+    for i in range(n_layers):                  # same tables, another pool (other values) per layer
+        w = copy.copy(base)
+        w.private, w.public = copy.copy(base.private), copy.copy(base.public)
+        for side in (w.private, w.public):
+            g = torch.Generator(device=DEV).manual_seed(600 + i)
+            side.k_pool = torch.randn(side.k_pool.shape, generator=g, device=DEV).to(torch.bfloat16)
+            side.v_pool = torch.randn(side.v_pool.shape, generator=g, device=DEV).to(torch.bfloat16)
+        layers.append(w)
+    g = torch.Generator(device=DEV).manual_seed(7)
+    builds0, _ = ctx.spd_get_schedule_stats()
+    for s in range(n_steps):
+        lens_now = np.asarray([x + s + 1 for x in lo0], dtype=np.int32)     # counts the token appended in this step
+        outs = []
+        for w in layers:
+            w.public.lens = lens_now
+            q = torch.randn((U, Hq, d), generator=g, device=DEV).to(torch.bfloat16)
+            kn = torch.randn((U, Hkv, d), generator=g, device=DEV).to(torch.bfloat16)
+            vn = torch.randn((U, Hkv, d), generator=g, device=DEV).to(torch.bfloat16)
+            w.q = q
+            step = spd.DecodeStep.from_workload(ctx, w)
+            step.run_fused(q, k_new=kn, v_new=vn)
+            outs.append(step)
+        torch.cuda.synchronize()
+        builds, hits = ctx.spd_get_schedule_stats()
+        # the private schedule is built once (step 0), the public one once per step; every other call is a hit
+        assert builds - builds0 == (s + 1) + 1
+        for w, step in zip(layers, outs):
+            assert _err(step, _oracle_y(w)) <= 2e-3
+    assert hits == 2 * n_layers * n_steps - (n_steps + 1)
+    ctx.close()
