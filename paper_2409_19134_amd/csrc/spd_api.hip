@@ -810,7 +810,8 @@ int spd_build_schedule(const spd_shape *shape, int32_t n_users, const int32_t *l
     if (items) {
         if (capacity < (int64_t)S.items.size())
             return SPD_ERR_WORKSPACE;
-        std::memcpy(items, S.items.data(), S.items.size() * sizeof(spd_work_item));
+        if (!S.items.empty())
+            std::memcpy(items, S.items.data(), S.items.size() * sizeof(spd_work_item));
     }
     return SPD_OK;
 }

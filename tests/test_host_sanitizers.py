@@ -1,0 +1,37 @@
+"""The host side of the library (schedule builder, argument checks) under AddressSanitizer and UBSan.
+Host code only: the GPU pass is compiled without sanitizers and no device call is made."""
+import os
+import shutil
+import subprocess
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+
+
+@pytest.mark.skipif(not os.path.exists(HIPCC), reason="hipcc not found")
+def test_schedule_and_validation_under_asan_ubsan(tmp_path):
+    exe = str(tmp_path / "schedule_fuzz")
+    cmd = [HIPCC, "--offload-arch=gfx950", "-O1", "-g", "-std=c++17",
+           "-Xarch_host", "-fsanitize=address,undefined", "-Xarch_host", "-fno-sanitize-recover=undefined",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-o", exe, os.path.join(ROOT, "tests", "host", "schedule_fuzz.cpp"),
+           os.path.join(ROOT, "paper_2409_19134_amd", "csrc", "spd_api.hip")]
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    assert res.returncode == 0, res.stdout[-3000:]
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    run = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, env=env, timeout=300)
+    assert run.returncode == 0 and run.stdout.strip().endswith("ok 400"), run.stdout[-3000:]
+
+
+def test_oracle_under_asan_ubsan(tmp_path):
+    """The C oracle itself: small random inputs in every storage mode, with AddressSanitizer and UBSan."""
+    exe = str(tmp_path / "oracle_sanitize")
+    cmd = ["gcc", "-O1", "-g", "-std=c99", "-fopenmp", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+           "-o", exe, os.path.join(ROOT, "tests", "host", "oracle_sanitize.c"), "-lm"]
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    assert res.returncode == 0, res.stdout[-3000:]
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1", OMP_NUM_THREADS="4")
+    run = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, env=env, timeout=300)
+    assert run.returncode == 0 and run.stdout.strip().endswith("ok 60"), run.stdout[-3000:]
