@@ -23,6 +23,7 @@ struct KvAddr {
     int32_t max_blocks;
     int64_t block_stride;
     int64_t token_stride;
+    int64_t head_stride;  // used by the head-per-wave kernel only (token-major storage: the same for every user)
 };
 
 // One segment of work as the kernels read it: tokens [t_begin, t_end) of one (user, KV head) row.  A workgroup
@@ -34,7 +35,8 @@ struct DevItem {
     const char *k_base;
     const char *v_base;
     int32_t user, kv_head, t_begin, t_end;
-    int32_t slot;      // where this segment's partial goes when the row has several segments
+    int32_t slot;      // where this segment's partial goes when the row has several segments (head-per-wave pieces:
+                       // the slot of KV head 0; head h writes slot + h * n_chunks)
     int32_t n_chunks;  // segments of the row; 1: the segment writes the final result itself
     int32_t next;      // index of the piece's next segment, -1 if none
     int32_t rot;       // bits 0-1: 32-token steps the piece has already handed out (mod 4), keeps the four waves

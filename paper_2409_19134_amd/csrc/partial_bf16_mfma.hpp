@@ -138,12 +138,18 @@ constexpr int kOStride = 132;  // LDS row stride (floats) of one head's 128 chan
 // One workgroup per piece (see DevItem); q: [U][Hq][128] bf16.  A segment that is its row's only one writes out/lse
 // directly; otherwise it writes part_o[slot][G][128] / part_lse[slot][G], which combine_chunks_kernel then reduces.
 //
-// PREFETCH = true keeps two 32-token steps of loads in flight per wave (231 VGPRs, two workgroups per CU): best when a
-// launch runs many waves of workgroups.  PREFETCH = false holds one step (166 VGPRs, three workgroups per CU): as fast
-// when the whole launch is one resident wave, and it leaves room on every CU for the other owner's kernel to run
-// beside this one.
-template <bool PAGED, bool PREFETCH>
-__global__ __launch_bounds__(kThreads, PREFETCH ? 2 : 3) void partial_bf16_d128_kernel(
+// PREFETCH = true keeps two 32-token steps of loads in flight per wave (~245 VGPRs, two waves per SIMD): best when a
+// launch runs many waves of workgroups.  PREFETCH = false holds one step (~165 VGPRs, three waves per SIMD): as fast
+// when the whole launch is one resident wave, and it leaves room on every CU for the other owner's pieces.
+//
+// HPW ("head per wave") is the mapping for contiguous token-major storage, where the KV heads of a token are adjacent
+// in memory ([token][head][d]).  A piece is then a token range of a *user* (all KV heads), the workgroup
+// has one wave per KV head, and all waves walk the same tokens: together they read whole, consecutive DRAM pages,
+// where one workgroup per head would touch every page eight times at different moments.  Each wave owns its head's
+// result, so there is no cross-wave combine, no LDS and no barrier.  Without HPW (head-major storage: one contiguous
+// stream per head) a piece is a token range of one (user, KV head) row and its four waves take interleaved steps.
+template <bool PAGED, bool PREFETCH, bool HPW>
+__global__ __launch_bounds__(HPW ? 512 : kThreads, PREFETCH ? 2 : 3) void partial_bf16_d128_kernel(
     OwnerArgs a0, OwnerArgs a1, int n0, const uint16_t *__restrict__ q, int Hq, int G, float scale_log2e)
 {
     const bool second = (int)blockIdx.x >= n0;  // workgroup-uniform: which owner this workgroup serves
@@ -164,7 +170,7 @@ __global__ __launch_bounds__(kThreads, PREFETCH ? 2 : 3) void partial_bf16_d128_
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    constexpr int kStep = 32 * kWaves;
+    constexpr int kStep = HPW ? 32 : 32 * kWaves;
 
     // Everything a segment needs before its first MFMA: addresses, the KV append copy, Q, and the loads of the wave's
     // first 32-token step.  Issued for the *next* segment before the current one's epilogue, so that the barriers
@@ -174,8 +180,9 @@ __global__ __launch_bounds__(kThreads, PREFETCH ? 2 : 3) void partial_bf16_d128_
         L.grp = lane >> 4;
         L.token_stride = kv.token_stride;
         L.block_stride = kv.block_stride;
-        L.k_base = it.k_base + k_pool;
-        L.v_base = it.v_base + v_pool;
+        const int kv_head = HPW ? uniform(wave) : it.kv_head;
+        L.k_base = it.k_base + k_pool + (HPW ? (int64_t)kv_head * kv.head_stride : 0);
+        L.v_base = it.v_base + v_pool + (HPW ? (int64_t)kv_head * kv.head_stride : 0);
         L.bt_row = PAGED ? kv.block_table + (int64_t)it.user * kv.max_blocks : nullptr;
         const int t_last = it.t_end - 1;
         L.k_new_row = L.v_new_row = nullptr;
@@ -183,10 +190,10 @@ __global__ __launch_bounds__(kThreads, PREFETCH ? 2 : 3) void partial_bf16_d128_
             // KV append: this segment holds the row's last token, which is the new one.  Wave 0 copies its K and V
             // rows into the cache (lanes 0-15: K, 16-31: V); every reader of that token takes it from the caller's
             // buffer instead, so nothing waits for the copy.
-            const int64_t row = ((int64_t)it.user * (Hq / G) + it.kv_head) * 256;
+            const int64_t row = ((int64_t)it.user * (Hq / G) + kv_head) * 256;
             L.k_new_row = k_new + row;
             L.v_new_row = v_new + row;
-            if (wave == 0 && lane < 32) {
+            if ((HPW || wave == 0) && lane < 32) {
                 int64_t off = (int64_t)(PAGED ? (t_last & 15) : t_last) * kv.token_stride + (lane & 15) * 16;
                 if (PAGED)
                     off += (int64_t)scalar_load_i32(L.bt_row, t_last >> 4) * kv.block_stride;
@@ -197,7 +204,7 @@ __global__ __launch_bounds__(kThreads, PREFETCH ? 2 : 3) void partial_bf16_d128_
             }
         }
         // Q as the B operand: head r (zero beyond G), channels kk*32 + grp*8 .. +8
-        const uint16_t *qrow = q + ((int64_t)it.user * Hq + (int64_t)it.kv_head * G + L.r) * 128 + L.grp * 8;
+        const uint16_t *qrow = q + ((int64_t)it.user * Hq + (int64_t)kv_head * G + L.r) * 128 + L.grp * 8;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             u32x4 w = {0u, 0u, 0u, 0u};
@@ -205,15 +212,23 @@ __global__ __launch_bounds__(kThreads, PREFETCH ? 2 : 3) void partial_bf16_d128_
                 w = *reinterpret_cast<const u32x4 *>(qrow + kk * 32);
             qB[kk] = __builtin_bit_cast(bf16x8, w);
         }
-        // the waves take interleaved 32-token steps
-        tb = it.t_begin + ((uniform(wave) - (it.rot & 3)) & (kWaves - 1)) * 32;
+        // head-major: the four waves take interleaved 32-token steps; token-major: every wave takes every step
+        tb = HPW ? it.t_begin : it.t_begin + ((uniform(wave) - (it.rot & 3)) & (kWaves - 1)) * 32;
         if (PREFETCH && tb < it.t_end)
             load_tile<PAGED>(T0, L, tb, t_last);
     };
 
     DevItem it = scalar_load_item(items, second ? (int)blockIdx.x - n0 : (int)blockIdx.x);
-    if (it.n_chunks == 0) {  // a row without tokens is a piece of its own
-        write_empty_row<128>(it, G, Hq, out, lse);
+    if (it.n_chunks == 0) {  // a row without tokens (head-per-wave: a user without tokens) is a piece of its own
+        if (HPW) {
+            const int64_t head0 = (int64_t)it.user * Hq + (int64_t)wave * G;
+            for (int idx = lane; idx < G * 128; idx += 64)
+                out[head0 * 128 + idx] = 0.f;
+            if (lane < G)
+                lse[head0 + lane] = -INFINITY;
+        } else {
+            write_empty_row<128>(it, G, Hq, out, lse);
+        }
         return;
     }
     LaneConst L;
@@ -247,6 +262,10 @@ __global__ __launch_bounds__(kThreads, PREFETCH ? 2 : 3) void partial_bf16_d128_
                 for (;;) {
                     const int tb1 = tb + kStep;
                     const bool more1 = tb1 < it.t_end;
+                    // head per wave: the waves stay in step (they all run the same trip counts), so that together they
+                    // ask for whole consecutive token rows at about the same time
+                    if (HPW)
+                        __builtin_amdgcn_s_barrier();
                     if (more1)
                         load_tile<PAGED>(T1, L, tb1, t_last);
                     compute_tile(T0, qB, tb, L.grp, it.t_end, scale_log2e, m, l, acc);
@@ -254,6 +273,8 @@ __global__ __launch_bounds__(kThreads, PREFETCH ? 2 : 3) void partial_bf16_d128_
                         break;
                     const int tb2 = tb1 + kStep;
                     const bool more2 = tb2 < it.t_end;
+                    if (HPW)
+                        __builtin_amdgcn_s_barrier();
                     if (more2)
                         load_tile<PAGED>(T0, L, tb2, t_last);
                     compute_tile(T1, qB, tb1, L.grp, it.t_end, scale_log2e, m, l, acc);
@@ -269,9 +290,43 @@ __global__ __launch_bounds__(kThreads, PREFETCH ? 2 : 3) void partial_bf16_d128_
         if (PREFETCH && it.next >= 0)
             begin_segment(nx, L, qB, tb, T0);
 
-        // ---- combine the lane groups (sum of l) and the four waves (LDS) ----
+        // ---- combine the lane groups (sum of l) ... ----
         l += __shfl_xor(l, 16);
         l += __shfl_xor(l, 32);
+        const bool direct = it.n_chunks == 1;
+        if (HPW) {
+            // ... and that is all: the wave owns head `wave` of this token range.  Lane (r < G, grp) holds channels
+            // (4*grp + v)*8 + cc of query head r: eight consecutive floats per v.
+            const int kvh = uniform(wave);
+            const int64_t head0 = (int64_t)it.user * Hq + (int64_t)kvh * G;
+            const int64_t slot = (int64_t)it.slot + (int64_t)kvh * it.n_chunks;
+            if (r < G) {
+                const float inv = 1.f / l;  // l > 0: the segment holds at least one token
+                float *dst = (direct ? out + (head0 + r) * 128 : part_o + (slot * G + r) * 128) + grp * 32;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    f32x4 lo = {acc[0][v] * inv, acc[1][v] * inv, acc[2][v] * inv, acc[3][v] * inv};
+                    f32x4 hi = {acc[4][v] * inv, acc[5][v] * inv, acc[6][v] * inv, acc[7][v] * inv};
+                    *reinterpret_cast<f32x4 *>(dst + v * 8) = lo;
+                    *reinterpret_cast<f32x4 *>(dst + v * 8 + 4) = hi;
+                }
+                if (grp == 0) {
+                    const float ls = m * kLn2 + logf(l);
+                    if (direct)
+                        lse[head0 + r] = ls;
+                    else
+                        part_lse[slot * G + r] = ls;
+                }
+            }
+            if (it.next < 0)
+                return;
+            if (!PREFETCH)
+                begin_segment(nx, L, qB, tb, T0);
+            it = nx;
+            continue;
+        }
+
+        // ---- ... and the four waves (LDS) ----
         if (grp == 0) {
             sm_m[wave][r] = m;
             sm_l[wave][r] = l;
@@ -292,7 +347,6 @@ __global__ __launch_bounds__(kThreads, PREFETCH ? 2 : 3) void partial_bf16_d128_
         }
         __syncthreads();
 
-        const bool direct = it.n_chunks == 1;
         const int64_t head0 = (int64_t)it.user * Hq + (int64_t)it.kv_head * G;
         for (int idx = threadIdx.x; idx < G * 128; idx += kThreads) {
             const int g = idx >> 7, ch = idx & 127;

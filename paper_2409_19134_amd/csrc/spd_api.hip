@@ -30,6 +30,7 @@ constexpr int kChunkMaxDefault = 4096;     // tokens per piece when the work exc
 constexpr int kNoSplitMaxDefault = 768;     // rows this short are never split: the work is latency-bound and a
                                             // whole row per workgroup saves the combine launch
 constexpr int kTargetWgPerCuDefault = 2;   // workgroups of the MFMA kernel resident per CU (2 waves per SIMD)
+constexpr int kHeadPerWaveMinSteps = 8;    // 32-token steps per CU from which the head-per-wave mapping is used
 
 int env_int(const char *name, int dflt)
 {
@@ -141,7 +142,11 @@ struct Schedule {
     int chunk_tokens = 0;              // tokens per piece (rounded up)
 };
 
-void build_schedule(int Hkv, int n_users, const int32_t *lens, int n_cus, bool fused, Schedule &S)
+// hpw: pieces for the head-per-wave kernel (token-major storage).  A piece then covers all KV heads of its token
+// range: one item per cut (kv_head = 0, slot = the slot of head 0) and one resident workgroup per CU.  The same
+// token limit per piece measured best (2048 and 4096 within 1 %, 1024 4 % slower), although every wave now walks
+// the whole range instead of a quarter of it.
+void build_schedule(int Hkv, int n_users, const int32_t *lens, int n_cus, bool fused, bool hpw, Schedule &S)
 {
     S.items.clear();
     S.piece_first.assign(1, 0);
@@ -163,21 +168,24 @@ void build_schedule(int Hkv, int n_users, const int32_t *lens, int n_cus, bool f
     };
     std::vector<std::vector<Cut>> groups;
     if (max_len <= env_int("SPD_NO_SPLIT_MAX", kNoSplitMaxDefault)) {
-        const int64_t per = fused ? spd::kWaves : (int64_t)1 << 40;  // steps per chunk
+        // steps per chunk (every wave of a head-per-wave piece walks all of them: two round trips with its prefetch)
+        const int64_t per = fused ? spd::kWaves : (int64_t)1 << 40;
         for (int u = 0; u < n_users; ++u) {
             const int64_t steps = (lens[u] + kChunkAlign - 1) / kChunkAlign;
             for (int64_t s0 = 0; s0 < steps; s0 += per)
                 groups.push_back({Cut{u, s0, std::min(steps, s0 + per)}});
         }
-        S.chunk_tokens = fused ? spd::kWaves * kChunkAlign : (max_len + kChunkAlign - 1) / kChunkAlign * kChunkAlign;
+        S.chunk_tokens = (int)std::min<int64_t>(per, (max_len + kChunkAlign - 1) / kChunkAlign) * kChunkAlign;
     } else {
         const int64_t slots = (int64_t)std::max(1, n_cus) * env_int("SPD_TARGET_WG_PER_CU", kTargetWgPerCuDefault);
-        const int64_t wg = std::max<int64_t>(1, slots / Hkv);  // groups per resident wave of workgroups
+        // groups per resident wave of workgroups
+        const int64_t wg = hpw ? std::max(1, n_cus) : std::max<int64_t>(1, slots / Hkv);
         const int64_t piece_max = std::max(kChunkMin, env_int("SPD_CHUNK_MAX", kChunkMaxDefault)) / kChunkAlign;
         // group boundaries (cumulative step counts)
         std::vector<int64_t> ends;
         if (T <= wg * piece_max) {
-            const int64_t W = std::min<int64_t>(wg, (T + spd::kWaves - 1) / spd::kWaves);  // >= one step per wave
+            // at least one step per wave
+            const int64_t W = std::min<int64_t>(wg, hpw ? T : (T + spd::kWaves - 1) / spd::kWaves);
             for (int64_t i = 0; i < W; ++i)
                 ends.push_back(T * (i + 1) / W);
         } else {
@@ -223,7 +231,7 @@ void build_schedule(int Hkv, int n_users, const int32_t *lens, int n_cus, bool f
     for (const auto &grp : groups) {
         if (grp.empty())
             continue;
-        for (int h = 0; h < Hkv; ++h) {
+        for (int h = 0; h < (hpw ? 1 : Hkv); ++h) {
             for (const Cut &c : grp) {
                 spd_work_item it;
                 it.user = c.user;
@@ -260,6 +268,7 @@ struct CachedSchedule {
     uint64_t hash = 0, last_use = 0;
     std::vector<uint8_t> key;
     int64_t n_items = 0, n_slots = 0;
+    bool hpw = false;        // pieces are for the head-per-wave kernel
     int n_split_rows = 0;    // rows with several chunks: CombineRow[n_split_rows] follows the items
     size_t off_rows = 0, off_info = 0;
     char *dev = nullptr;     // DevItem[n_items] | CombineRow[n_split_rows] | RowInfo[n_users * Hkv]
@@ -313,14 +322,44 @@ void free_entry(CachedSchedule &e)
     e = CachedSchedule();
 }
 
-void make_key(const spd_shape *s, const spd_kv_view *v, bool fused, std::vector<uint8_t> &key)
+// Contiguous token-major storage (the KV heads of a token adjacent in memory) can take the head-per-wave kernel: one
+// wave per KV head, all waves on the same tokens.  (Token-major pages gained nothing from it when measured.)
+bool head_per_wave_layout(const spd_shape *s, const spd_kv_view *v)
+{
+    return s->dtype == SPD_BF16 && s->n_kv_heads > 1 && s->n_kv_heads <= 8 && v->block_size == 0 &&
+           !v->head_strides && v->head_stride == s->head_dim &&
+           v->token_stride >= (int64_t)s->n_kv_heads * s->head_dim;
+}
+
+int64_t total_steps(const spd_kv_view *v)
+{
+    int64_t T = 0;
+    for (int u = 0; u < v->n_users; ++u)
+        T += (v->lens[u] + kChunkAlign - 1) / kChunkAlign;
+    return T;
+}
+
+// The mapping pays once the launch is bandwidth-bound, i.e. every one-per-CU workgroup gets several 32-token steps;
+// below that the four interleaving waves of the head-major mapping finish a short piece sooner.
+// SPD_HEAD_PER_WAVE=0 / 1 in the environment overrides the rule (never / whenever the layout allows): for tests and
+// measurements.
+bool head_per_wave_pays(const spd_ctx *ctx, int64_t steps)
+{
+    const char *force = std::getenv("SPD_HEAD_PER_WAVE");
+    if (force && (force[0] == '0' || force[0] == '1'))
+        return force[0] == '1';
+    return steps >= (int64_t)std::max(1, ctx->n_cus) * kHeadPerWaveMinSteps;
+}
+
+void make_key(const spd_shape *s, const spd_kv_view *v, bool fused, bool hpw, std::vector<uint8_t> &key)
 {
     key.clear();
     auto put = [&key](const void *p, size_t n) {
         const uint8_t *b = static_cast<const uint8_t *>(p);
         key.insert(key.end(), b, b + n);
     };
-    const int32_t head[6] = {s->dtype, s->n_q_heads, s->n_kv_heads, v->n_users, v->block_size, fused ? 1 : 0};
+    const int32_t head[6] = {s->dtype, s->n_q_heads, s->n_kv_heads, v->n_users, v->block_size,
+                             (fused ? 1 : 0) | (hpw ? 2 : 0)};
     put(head, sizeof head);
     put(v->lens, sizeof(int32_t) * (size_t)v->n_users);
     // the items carry row base addresses (contiguous mode) or row offsets inside the pools (paged mode): the key holds
@@ -339,12 +378,13 @@ void make_key(const spd_shape *s, const spd_kv_view *v, bool fused, std::vector<
     }
 }
 
-// Find or build the device-resident schedule for this view.  Uploads are enqueued on `stream`.
-int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view *v, bool fused, hipStream_t stream,
-                 CachedSchedule **out)
+// Find or build the device-resident schedule for this view (hpw: pieces for the head-per-wave kernel).  Uploads are
+// enqueued on `stream`.
+int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view *v, bool fused, bool hpw,
+                 hipStream_t stream, CachedSchedule **out)
 {
     std::vector<uint8_t> key;
-    make_key(s, v, fused, key);
+    make_key(s, v, fused, hpw, key);
     const uint64_t h = fnv1a(key.data(), key.size());
     ++ctx->tick;
     CachedSchedule *victim = &own.cache[0];
@@ -364,16 +404,16 @@ int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view
         }
     }
     Schedule S;
-    build_schedule(s->n_kv_heads, v->n_users, v->lens, ctx->n_cus, fused, S);
+    build_schedule(s->n_kv_heads, v->n_users, v->lens, ctx->n_cus, fused, hpw, S);
 
     // device items: the first segment of every piece (index = workgroup id), then one per row without tokens (it only
     // writes A = 0, lse = -inf), then the continuation segments, linked through `next`
     const int es = elt_size(s->dtype);
     const int Hkv = s->n_kv_heads;
     const int64_t n_pieces = (int64_t)S.piece_first.size() - 1;
-    int64_t n_empty_rows = 0;
+    int64_t n_empty_rows = 0;  // workgroups that only write A = 0, lse = -inf (head-per-wave: one per empty user)
     for (int u = 0; u < v->n_users; ++u)
-        n_empty_rows += v->lens[u] == 0 ? Hkv : 0;
+        n_empty_rows += v->lens[u] == 0 ? (hpw ? 1 : Hkv) : 0;
     const int64_t n_groups = n_pieces + n_empty_rows;  // launched workgroups
     std::vector<DevItem> dev_items((size_t)n_groups);
     dev_items.reserve((size_t)n_groups + S.items.size());
@@ -381,7 +421,7 @@ int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view
         const char *base = v->block_size ? nullptr  // paged: an offset, the kernel adds the pool
                                          : static_cast<const char *>(is_v ? v->v_ptrs[u] : v->k_ptrs[u]);
         const int64_t hs = (v->head_strides && v->block_size == 0) ? v->head_strides[u] : v->head_stride;
-        return base + (int64_t)h * hs * es;
+        return base + (hpw ? 0 : (int64_t)h * hs * es);  // head-per-wave: every wave adds its own head's offset
     };
     auto to_dev = [&](const spd_work_item &w, int rot) {
         DevItem d;
@@ -421,7 +461,7 @@ int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view
         for (int u = 0; u < v->n_users; ++u) {
             if (v->lens[u] != 0)
                 continue;
-            for (int h = 0; h < Hkv; ++h) {
+            for (int h = 0; h < (hpw ? 1 : Hkv); ++h) {
                 DevItem d;
                 d.k_base = d.v_base = nullptr;
                 d.user = u;
@@ -437,12 +477,14 @@ int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view
     for (size_t i = 0; i < S.items.size(); ++i) {
         const spd_work_item &w = S.items[i];
         if (w.chunk == 0 && w.n_chunks > 1)
-            split_rows.push_back(CombineRow{w.slot, w.n_chunks, w.user, w.kv_head});
+            for (int h = 0; h < (hpw ? Hkv : 1); ++h)  // a head-per-wave item stands for all KV heads
+                split_rows.push_back(CombineRow{w.slot + h * w.n_chunks, w.n_chunks, w.user, w.kv_head + h});
     }
     std::vector<RowInfo> row_info((size_t)v->n_users * Hkv, RowInfo{0, 0});
     for (const spd_work_item &w : S.items)
         if (w.chunk == 0)
-            row_info[(size_t)w.user * Hkv + w.kv_head] = RowInfo{w.slot, w.n_chunks};
+            for (int h = 0; h < (hpw ? Hkv : 1); ++h)
+                row_info[(size_t)w.user * Hkv + w.kv_head + h] = RowInfo{w.slot + h * w.n_chunks, w.n_chunks};
     const size_t b_items = dev_items.size() * sizeof(DevItem);
     const size_t b_rows = split_rows.size() * sizeof(CombineRow);
     const size_t b_info = row_info.size() * sizeof(RowInfo);
@@ -484,6 +526,7 @@ int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view
     e.key.swap(key);
     e.last_use = ctx->tick;
     e.n_items = n_groups;
+    e.hpw = hpw;
     e.n_slots = S.n_slots;
     e.n_split_rows = (int)split_rows.size();
     e.off_rows = off_rows;
@@ -544,7 +587,7 @@ void launch_f32_g(int G, dim3 grid, hipStream_t stream, hipEvent_t ev0, hipEvent
 
 // Validation, schedule lookup and scratch growth of one partial-attention call.
 int prepare_partial(spd_ctx *ctx, int which, const spd_shape *s, const void *q, const spd_kv_view *v, float *out,
-                    float *lse, bool fused, hipStream_t stream, CachedSchedule **e)
+                    float *lse, bool fused, int mapping, hipStream_t stream, CachedSchedule **e)
 {
     const int rc = spd_validate_partial(s, q, v, out, lse);
     if (rc != SPD_OK)
@@ -553,7 +596,9 @@ int prepare_partial(spd_ctx *ctx, int which, const spd_shape *s, const void *q, 
     if (v->n_users == 0)
         return SPD_OK;
     Owner &own = ctx->owner[which];
-    const int rs = get_schedule(ctx, own, s, v, fused, stream, e);
+    // mapping: 1 = head per wave, 0 = head-major, -1 = whatever suits this view on its own
+    const bool hpw = mapping >= 0 ? mapping != 0 : head_per_wave_layout(s, v) && head_per_wave_pays(ctx, total_steps(v));
+    const int rs = get_schedule(ctx, own, s, v, fused, hpw, stream, e);
     if (rs != SPD_OK)
         return rs;
     const int G = s->n_q_heads / s->n_kv_heads;
@@ -572,6 +617,7 @@ OwnerArgs owner_args(const Owner &own, const CachedSchedule *e, const spd_shape 
     a.kv.max_blocks = v->max_blocks;
     a.kv.block_stride = v->block_stride * es;
     a.kv.token_stride = v->token_stride * es;
+    a.kv.head_stride = v->head_stride * es;
     a.part_o = own.part_o;
     a.part_lse = own.part_lse;
     a.out = out;
@@ -606,26 +652,30 @@ int launch_partial(spd_ctx *ctx, int which, const CachedSchedule *e0, const spd_
     const bool timed = ctx->timing && town.ev_used < (int)town.ev_start.size();
     const hipEvent_t ev0 = timed ? town.ev_start[town.ev_used] : nullptr;
     const hipEvent_t ev1 = timed ? town.ev_stop[town.ev_used] : nullptr;
-    const dim3 grid((unsigned)(n0 + n1)), block(spd::kThreads);
+    const dim3 grid((unsigned)(n0 + n1));
     if (s->dtype == SPD_BF16) {
         const uint16_t *qh = static_cast<const uint16_t *>(q);
-        const size_t lds = sizeof(float) * spd::kWaves * (size_t)G * spd::kOStride;  // cross-wave staging, G heads
+        const bool hpw = e0->hpw;  // a two-owner launch needs the same mapping on both sides (checked by the caller)
+        const size_t lds = hpw ? 0 : sizeof(float) * spd::kWaves * (size_t)G * spd::kOStride;  // cross-wave staging
+        const dim3 blk(hpw ? 64u * (unsigned)s->n_kv_heads : (unsigned)spd::kThreads);
         // clearly more pieces than the three-per-CU kernel holds at once (a few left over just start a little
-        // later): use the prefetching two-per-CU kernel
-        const bool prefetch = n0 + n1 > (int64_t)std::max(1, ctx->n_cus) * 4;
-#define SPD_LAUNCH_BF16(PAGED, PREFETCH)                                                                              \
-    hipExtLaunchKernelGGL((spd::partial_bf16_d128_kernel<PAGED, PREFETCH>), grid, block, (uint32_t)lds, stream, ev0,    \
-                          ev1, 0, a0, a1, (int)n0, qh, s->n_q_heads, G, c)
+        // later): use the prefetching two-per-CU kernel.  Head-per-wave workgroups fit one per CU either way.
+        const bool prefetch = hpw || n0 + n1 > (int64_t)std::max(1, ctx->n_cus) * 4;
+#define SPD_LAUNCH_BF16(PAGED, PREFETCH, HPW)                                                                         \
+    hipExtLaunchKernelGGL((spd::partial_bf16_d128_kernel<PAGED, PREFETCH, HPW>), grid, blk, (uint32_t)lds, stream,      \
+                          ev0, ev1, 0, a0, a1, (int)n0, qh, s->n_q_heads, G, c)
         if (v0->block_size) {
             if (prefetch)
-                SPD_LAUNCH_BF16(true, true);
+                SPD_LAUNCH_BF16(true, true, false);
             else
-                SPD_LAUNCH_BF16(true, false);
+                SPD_LAUNCH_BF16(true, false, false);
         } else {
-            if (prefetch)
-                SPD_LAUNCH_BF16(false, true);
+            if (hpw)
+                SPD_LAUNCH_BF16(false, true, true);
+            else if (prefetch)
+                SPD_LAUNCH_BF16(false, true, false);
             else
-                SPD_LAUNCH_BF16(false, false);
+                SPD_LAUNCH_BF16(false, false, false);
         }
 #undef SPD_LAUNCH_BF16
     } else if (s->head_dim == 64) {
@@ -687,7 +737,7 @@ int partial_attention(spd_ctx *ctx, int which, const spd_shape *s, const void *q
         rc = validate_new_token(v, nt);
     if (rc != SPD_OK)
         return rc;
-    rc = prepare_partial(ctx, which, s, q, v, out, lse, false, stream, &e);
+    rc = prepare_partial(ctx, which, s, q, v, out, lse, false, -1, stream, &e);
     if (rc != SPD_OK || !e)
         return rc;
     rc = launch_partial(ctx, which, e, v, out, lse, nullptr, nullptr, nullptr, nullptr, s, q, nt, stream);
@@ -803,7 +853,7 @@ int spd_build_schedule(const spd_shape *shape, int32_t n_users, const int32_t *l
         if (lens[u] < 0)
             return SPD_ERR_LEN;
     Schedule S;
-    build_schedule(shape->n_kv_heads, n_users, lens, n_compute_units, false, S);
+    build_schedule(shape->n_kv_heads, n_users, lens, n_compute_units, false, false, S);
     *n_items = (int64_t)S.items.size();
     if (chunk_tokens)
         *chunk_tokens = S.chunk_tokens;
@@ -913,10 +963,14 @@ int spd_decode_step(spd_ctx *ctx, const spd_shape *shape, const void *q, const s
     if (!aligned16(y))
         return SPD_ERR_ALIGN;
     CachedSchedule *ep = nullptr, *eo = nullptr;
-    rc = prepare_partial(ctx, 0, shape, q, priv, a_in, lse_in, true, stream, &ep);
+    // both owners share one launch, so they share the mapping: head per wave if both layouts allow it and the two
+    // together are bandwidth-bound
+    const int hpw = head_per_wave_layout(shape, priv) && head_per_wave_layout(shape, pub) &&
+                    head_per_wave_pays(ctx, total_steps(priv) + total_steps(pub));
+    rc = prepare_partial(ctx, 0, shape, q, priv, a_in, lse_in, true, hpw, stream, &ep);
     if (rc != SPD_OK)
         return rc;
-    rc = prepare_partial(ctx, 1, shape, q, pub, a_out, lse_out, true, stream, &eo);  // an upload, if any, stays on `stream`
+    rc = prepare_partial(ctx, 1, shape, q, pub, a_out, lse_out, true, hpw, stream, &eo);  // an upload, if any, stays on `stream`
     if (rc != SPD_OK)
         return rc;
     // one grid for both owners, the private owner's long streams first (measured faster than public first): the

@@ -10,3 +10,16 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+
+
+@pytest.fixture
+def mapping_of(monkeypatch):
+    """Layout names ending in "_hpw" force the library's head-per-wave kernel mapping (it is otherwise chosen only for
+    large token-major inputs) through its SPD_HEAD_PER_WAVE override; returns the plain layout name."""
+    def apply(layout):
+        if layout is not None and layout.endswith("_hpw"):
+            monkeypatch.setenv("SPD_HEAD_PER_WAVE", "1")
+            return layout[:-4]
+        monkeypatch.delenv("SPD_HEAD_PER_WAVE", raising=False)
+        return layout
+    return apply

@@ -28,8 +28,12 @@ def _set_last_token(side, u, k_row, v_row):
     t = int(side.lens[u]) - 1
     if side.paged:
         page = int(side.block_table[u, t // workloads.PAGE_TOKENS])
-        side.k_pool[page, :, t % workloads.PAGE_TOKENS] = k_row
-        side.v_pool[page, :, t % workloads.PAGE_TOKENS] = v_row
+        if side.page_token_major:
+            side.k_pool[page, t % workloads.PAGE_TOKENS] = k_row
+            side.v_pool[page, t % workloads.PAGE_TOKENS] = v_row
+        else:
+            side.k_pool[page, :, t % workloads.PAGE_TOKENS] = k_row
+            side.v_pool[page, :, t % workloads.PAGE_TOKENS] = v_row
     elif side.layout == "nhd":
         side.k[u][t] = k_row
         side.v[u][t] = v_row
@@ -54,10 +58,14 @@ def _all_bytes(side):
 
 CASES = [
     (torch.bfloat16, 32, 8, 128, [40, 1, 700, 33], [1, 16, 17, 250], "nhd", False),
+    (torch.bfloat16, 32, 8, 128, [40, 1, 700, 33], [1, 16, 17, 250], "nhd_hpw", False),
+    (torch.bfloat16, 16, 4, 128, [2000, 10, 0], [1500, 3000, 1], "nhd_hpw", False),
     (torch.bfloat16, 32, 8, 128, [40, 1, 700, 33], [1, 16, 17, 250], "hnd", False),
     (torch.bfloat16, 64, 8, 128, [300, 0, 5000], [32, 1, 4097], "hnd_exact", False),
     (torch.bfloat16, 32, 8, 128, [40, 1, 700, 33], [1, 16, 17, 250], "nhd", True),
     (torch.bfloat16, 32, 8, 128, [2000, 10], [1500, 3000], "nhd", True),
+    (torch.bfloat16, 32, 8, 128, [2000, 10, 0], [1500, 3000, 1], "nhd", "token_major"),
+    (torch.bfloat16, 16, 4, 128, [40, 1, 700, 33], [1, 16, 17, 250], "nhd", "token_major"),
     (torch.float32, 8, 8, 64, [128, 5], [16, 1], "nhd", False),
     (torch.float32, 8, 2, 128, [128, 5, 9], [33, 1, 900], "nhd", True),
 ]
@@ -65,7 +73,8 @@ CASES = [
 
 @pytest.mark.parametrize("dtype,Hq,Hkv,d,lp,lo,layout,paged", CASES)
 @pytest.mark.parametrize("fused", [False, True])
-def test_append_then_attend(ctx, dtype, Hq, Hkv, d, lp, lo, layout, paged, fused):
+def test_append_then_attend(ctx, mapping_of, dtype, Hq, Hkv, d, lp, lo, layout, paged, fused):
+    layout = mapping_of(layout)
     import paper_2409_19134_amd as spd
     U = len(lp)
     wl = workloads.random_case(211, dtype, U, Hq, Hkv, d, lp, lo, device=DEV, layout=layout, paged=paged)

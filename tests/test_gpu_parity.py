@@ -94,8 +94,12 @@ def test_config1_fp32_full_size(ctx):
 
 
 @pytest.mark.parametrize("cfg,len_div,n_users,layout", [(2, 4, None, None), (3, 64, 12, None), (4, 8, 48, None),
-                                                        (4, 8, 48, "nhd"), (2, 8, None, "nhd"), (5, 128, 6, None)])
-def test_configs_reduced_lengths(ctx, cfg, len_div, n_users, layout):
+                                                        (4, 8, 48, "nhd"), (2, 8, None, "nhd"), (5, 128, 6, None),
+                                                        (5, 128, 6, "nhd"), (3, 64, 12, "nhd"),
+                                                        (4, 8, 48, "nhd_hpw"), (2, 8, None, "nhd_hpw"),
+                                                        (3, 64, 12, "nhd_hpw")])
+def test_configs_reduced_lengths(ctx, mapping_of, cfg, len_div, n_users, layout):
+    layout = mapping_of(layout)
     check_against_oracle(ctx, workloads.make_workload(cfg, DEV, len_div=len_div, n_users=n_users, layout=layout))
 
 
@@ -117,9 +121,10 @@ def _sample_rows(wl, n, seed):
     return [(u, int(rng.integers(wl.n_q_heads))) for u in sorted(users)]
 
 
-@pytest.mark.parametrize("cfg,n", [(3, 4), (4, 8), (5, 3)])
-def test_full_size_sampled_rows(ctx, cfg, n):
-    wl = workloads.make_workload(cfg, DEV)
+@pytest.mark.parametrize("cfg,n,layout", [(3, 4, None), (4, 8, None), (5, 3, None),
+                                          (4, 8, "nhd")])     # large and token-major: the head-per-wave mapping
+def test_full_size_sampled_rows(ctx, cfg, n, layout):
+    wl = workloads.make_workload(cfg, DEV, layout=layout)
     check_against_oracle(ctx, wl, rows=_sample_rows(wl, n, cfg))
 
 
@@ -132,8 +137,10 @@ def test_full_size_sampled_rows(ctx, cfg, n):
     ([31], [33]), ([32], [32]), ([127, 128, 129], [0, 1, 2]),
     ([0, 0, 700], [5, 0, 0]), ([513, 1025, 2049], [95, 96, 97]),
 ])
-@pytest.mark.parametrize("layout,paged", [("nhd", False), ("hnd", False), ("hnd_exact", False), ("nhd", True)])
-def test_bf16_edge_lengths(ctx, lp, lo, layout, paged):
+@pytest.mark.parametrize("layout,paged", [("nhd", False), ("nhd_hpw", False), ("hnd", False), ("hnd_exact", False),
+                                          ("nhd", True), ("nhd", "token_major")])
+def test_bf16_edge_lengths(ctx, mapping_of, lp, lo, layout, paged):
+    layout = mapping_of(layout)
     wl = workloads.random_case(101, torch.bfloat16, len(lp), 32, 8, 128, lp, lo, device=DEV, layout=layout, paged=paged)
     step, _ = check_against_oracle(ctx, wl)
     for u in range(len(lp)):     # empty parts are exact: zeros and -inf
@@ -150,9 +157,12 @@ def test_bf16_edge_lengths(ctx, lp, lo, layout, paged):
             assert torch.equal(step.y[u], step.a_out[u])
 
 
-@pytest.mark.parametrize("Hq,Hkv", [(8, 8), (16, 8), (64, 8), (16, 1), (12, 4)])
-def test_bf16_head_groupings(ctx, Hq, Hkv):
-    wl = workloads.random_case(103, torch.bfloat16, 3, Hq, Hkv, 128, [300, 77, 1500], [40, 0, 65], device=DEV)
+@pytest.mark.parametrize("Hq,Hkv", [(8, 8), (16, 8), (64, 8), (16, 1), (12, 4), (32, 2), (48, 16)])
+@pytest.mark.parametrize("layout", ["nhd", "nhd_hpw", "hnd"])   # nhd_hpw: one wave per KV head where Hkv is in 2..8
+def test_bf16_head_groupings(ctx, mapping_of, Hq, Hkv, layout):
+    layout = mapping_of(layout)
+    wl = workloads.random_case(103, torch.bfloat16, 3, Hq, Hkv, 128, [300, 77, 1500], [40, 0, 65], device=DEV,
+                               layout=layout)
     check_against_oracle(ctx, wl)
 
 

@@ -28,8 +28,12 @@ def _rows_as_float64(wl, side, u, kv):
         L = int(side.lens[u])
         n = -(-L // workloads.PAGE_TOKENS)
         pages = side.block_table[u, :n].long()
-        k = side.k_pool[pages, kv].reshape(-1, wl.head_dim)[:L]
-        v = side.v_pool[pages, kv].reshape(-1, wl.head_dim)[:L]
+        if side.page_token_major:
+            k = side.k_pool[pages][:, :, kv].reshape(-1, wl.head_dim)[:L]
+            v = side.v_pool[pages][:, :, kv].reshape(-1, wl.head_dim)[:L]
+        else:
+            k = side.k_pool[pages, kv].reshape(-1, wl.head_dim)[:L]
+            v = side.v_pool[pages, kv].reshape(-1, wl.head_dim)[:L]
     else:
         L = int(side.lens[u])
         kt, vt = side.k[u], side.v[u]
@@ -79,7 +83,8 @@ def test_brute_force_naive_exponentials(dtype, Hq, Hkv):
 # 2. library routines: scipy softmax/logsumexp and torch fp64 scaled_dot_product_attention
 
 
-@pytest.mark.parametrize("layout,paged", [("nhd", False), ("hnd", False), ("hnd_exact", False), ("nhd", True)])
+@pytest.mark.parametrize("layout,paged", [("nhd", False), ("hnd", False), ("hnd_exact", False), ("nhd", True),
+                                          ("nhd", "token_major")])
 def test_against_library_softmax(layout, paged):
     from scipy.special import logsumexp, softmax
     U, Hq, Hkv, d = 4, 8, 2, 64

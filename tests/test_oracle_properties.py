@@ -16,7 +16,7 @@ def cases(draw):
     d = draw(st.sampled_from([4, 8, 16]))
     lp = [draw(st.integers(0, 40)) for _ in range(U)]
     lo = [draw(st.integers(0, 20)) for _ in range(U)]
-    layout = draw(st.sampled_from(["nhd", "hnd", "hnd_exact", "paged"]))
+    layout = draw(st.sampled_from(["nhd", "hnd", "hnd_exact", "paged", "paged_tm"]))
     dtype = draw(st.sampled_from([torch.float32, torch.bfloat16]))
     seed = draw(st.integers(0, 10_000))
     scale = draw(st.sampled_from([1.0, 0.25, 2.0]))
@@ -28,8 +28,12 @@ def _rows(wl, side, u, kv):
     if side.paged:
         n = -(-L // workloads.PAGE_TOKENS)
         pg = side.block_table[u, :n].long()
-        k = side.k_pool[pg, kv].reshape(-1, wl.head_dim)[:L]
-        v = side.v_pool[pg, kv].reshape(-1, wl.head_dim)[:L]
+        if side.page_token_major:
+            k = side.k_pool[pg][:, :, kv].reshape(-1, wl.head_dim)[:L]
+            v = side.v_pool[pg][:, :, kv].reshape(-1, wl.head_dim)[:L]
+        else:
+            k = side.k_pool[pg, kv].reshape(-1, wl.head_dim)[:L]
+            v = side.v_pool[pg, kv].reshape(-1, wl.head_dim)[:L]
     elif side.layout == "nhd":
         k, v = side.k[u][:L, kv], side.v[u][:L, kv]
     else:
@@ -42,8 +46,9 @@ def _rows(wl, side, u, kv):
 def test_oracle_matches_library_softmax_and_theorem1(case):
     U, Hkv, G, d, lp, lo, layout, dtype, seed, scale = case
     Hq = Hkv * G
-    wl = workloads.random_case(seed, dtype, U, Hq, Hkv, d, lp, lo, layout="nhd" if layout == "paged" else layout,
-                               paged=layout == "paged", scale=scale)
+    paged = {"paged": True, "paged_tm": "token_major"}.get(layout, False)
+    wl = workloads.random_case(seed, dtype, U, Hq, Hkv, d, lp, lo, layout="nhd" if paged else layout,
+                               paged=paged, scale=scale)
     hw = orc.from_workload(wl)
     Y, lse = orc.attention(hw)
     A0, m0, g0 = orc.partial(hw, hw.private)

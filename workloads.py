@@ -53,7 +53,8 @@ class KVSide:
     ``head_strides``) or [L, Hkv, d] ("nhd");
     ``token_stride``/``head_stride`` are in elements and the channel axis is
     unit stride.  Paged mode: ``k_pool``/``v_pool`` are
-    [n_blocks, Hkv, PAGE_TOKENS, d] and ``block_table`` is int32
+    [n_blocks, Hkv, PAGE_TOKENS, d] (or [n_blocks, PAGE_TOKENS, Hkv, d] with
+    ``page_token_major``) and ``block_table`` is int32
     [U, max_blocks]; entries past a user's last page are 0 (a valid page that
     is never read).
     """
@@ -69,6 +70,7 @@ class KVSide:
     block_stride: int = 0
     max_blocks: int = 0
     head_strides: Optional[np.ndarray] = None   # per-user head stride (layout "hnd_exact"), else None
+    page_token_major: bool = False              # paged pools are [block, token, head, d] instead of [block, head, token, d]
     layout: str = "nhd"      # contiguous mode: "nhd" or "hnd"; paged pools are [block, head, token, d]
 
     @property
@@ -188,8 +190,9 @@ def _make_contig(lens, Hkv, d, dtype, device, seed_k, seed_v, layout, ch_scale):
                   layout=layout, head_strides=hs)
 
 
-def _make_paged(lens, Hkv, d, dtype, device, seed_k, seed_v, seed_t, ch_scale, spare_blocks=3):
-    """One pool per tensor; each user's pages are drawn from a seeded shuffle of the pool."""
+def _make_paged(lens, Hkv, d, dtype, device, seed_k, seed_v, seed_t, ch_scale, spare_blocks=3, token_major=False):
+    """One pool per tensor; each user's pages are drawn from a seeded shuffle of the pool.  Pages are
+    [Hkv, PAGE_TOKENS, d] (head-major) or, with token_major, [PAGE_TOKENS, Hkv, d]."""
     gk = torch.Generator(device=device).manual_seed(seed_k)
     gv = torch.Generator(device=device).manual_seed(seed_v)
     n_pages = [-(-int(L) // PAGE_TOKENS) for L in lens.tolist()]
@@ -201,20 +204,23 @@ def _make_paged(lens, Hkv, d, dtype, device, seed_k, seed_v, seed_t, ch_scale, s
     for u, n in enumerate(n_pages):
         table[u, :n] = perm[at:at + n]
         at += n
-    k_pool = torch.empty((n_blocks, Hkv, PAGE_TOKENS, d), device=device, dtype=dtype)
-    v_pool = torch.empty((n_blocks, Hkv, PAGE_TOKENS, d), device=device, dtype=dtype)
+    shape = (n_blocks, PAGE_TOKENS, Hkv, d) if token_major else (n_blocks, Hkv, PAGE_TOKENS, d)
+    k_pool = torch.empty(shape, device=device, dtype=dtype)
+    v_pool = torch.empty(shape, device=device, dtype=dtype)
     step = 4096  # pages per draw, bounds the fp32 staging buffer
     for b0 in range(0, n_blocks, step):
         b1 = min(n_blocks, b0 + step)
-        kk = _randn((b1 - b0, Hkv, PAGE_TOKENS, d), gk, device, dtype)
+        kk = _randn((b1 - b0,) + shape[1:], gk, device, dtype)
         if ch_scale is not None:
-            kk = (kk.float() * ch_scale.view(1, Hkv, 1, d)).to(dtype)
+            cs = ch_scale.view(1, 1, Hkv, d) if token_major else ch_scale.view(1, Hkv, 1, d)
+            kk = (kk.float() * cs).to(dtype)
         k_pool[b0:b1] = kk
-        v_pool[b0:b1] = _randn((b1 - b0, Hkv, PAGE_TOKENS, d), gv, device, dtype)
-    return KVSide(lens=lens, paged=True, token_stride=d, head_stride=PAGE_TOKENS * d,
+        v_pool[b0:b1] = _randn((b1 - b0,) + shape[1:], gv, device, dtype)
+    return KVSide(lens=lens, paged=True, token_stride=Hkv * d if token_major else d,
+                  head_stride=d if token_major else PAGE_TOKENS * d,
                   k_pool=k_pool, v_pool=v_pool,
                   block_table=torch.from_numpy(table).to(device),
-                  block_stride=Hkv * PAGE_TOKENS * d, max_blocks=max_blocks)
+                  block_stride=Hkv * PAGE_TOKENS * d, max_blocks=max_blocks, page_token_major=token_major)
 
 
 def make_workload(cfg: int, device="cpu", len_div: int = 1, n_users: Optional[int] = None,
@@ -244,10 +250,11 @@ def make_workload(cfg: int, device="cpu", len_div: int = 1, n_users: Optional[in
         ch_scale = torch.from_numpy(cs).to(device).view(Hkv, d)
 
     if cfg == 5:
+        tm = layout == "nhd"      # token-major pages [block, token, head, d]
         priv = _make_paged(lp, Hkv, d, dtype, device, seeds["k_private"], seeds["v_private"],
-                           seeds["table_private"], ch_scale)
+                           seeds["table_private"], ch_scale, token_major=tm)
         pub = _make_paged(lo, Hkv, d, dtype, device, seeds["k_public"], seeds["v_public"],
-                          seeds["table_public"], ch_scale)
+                          seeds["table_public"], ch_scale, token_major=tm)
     else:
         lay = layout or ("hnd_exact" if cfg == 4 else "hnd")
         priv = _make_contig(lp, Hkv, d, dtype, device, seeds["k_private"], seeds["v_private"], lay, ch_scale)
@@ -259,16 +266,18 @@ def make_workload(cfg: int, device="cpu", len_div: int = 1, n_users: Optional[in
 
 
 def random_case(seed: int, dtype, U: int, Hq: int, Hkv: int, d: int, lens_private, lens_public,
-                device="cpu", layout: str = "nhd", paged: bool = False, scale: Optional[float] = None) -> Workload:
-    """A free-form seeded case for edge-case tests (explicit shapes and lengths)."""
+                device="cpu", layout: str = "nhd", paged=False, scale: Optional[float] = None) -> Workload:
+    """A free-form seeded case for edge-case tests (explicit shapes and lengths).  paged: False, True
+    (head-major pages) or "token_major"."""
     lp = np.asarray(lens_private, dtype=np.int32)
     lo = np.asarray(lens_public, dtype=np.int32)
     assert lp.shape == (U,) and lo.shape == (U,)
     gq = torch.Generator(device=device).manual_seed(seed)
     q = _randn((U, Hq, d), gq, device, dtype)
     if paged:
-        priv = _make_paged(lp, Hkv, d, dtype, device, seed + 1, seed + 2, seed + 5, None)
-        pub = _make_paged(lo, Hkv, d, dtype, device, seed + 3, seed + 4, seed + 6, None)
+        tm = paged == "token_major"
+        priv = _make_paged(lp, Hkv, d, dtype, device, seed + 1, seed + 2, seed + 5, None, token_major=tm)
+        pub = _make_paged(lo, Hkv, d, dtype, device, seed + 3, seed + 4, seed + 6, None, token_major=tm)
     else:
         priv = _make_contig(lp, Hkv, d, dtype, device, seed + 1, seed + 2, layout, None)
         pub = _make_contig(lo, Hkv, d, dtype, device, seed + 3, seed + 4, layout, None)
