@@ -60,9 +60,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (2 = Llama-3-8B shape, 16 users: the headline)")
     ap.add_argument("--copies", type=int, default=0, help="KV set copies cycled through (0 = enough for > 1 GB, at most 8)")
-    ap.add_argument("--mode", default="fused", choices=["fused", "calls"],
-                    help="fused: spd_decode_step (public beside private on two streams, one closing kernel); "
-                         "calls: the three entry points in sequence on one stream")
+    ap.add_argument("--mode", default="fused", choices=["fused", "calls", "calls_public_first", "streams"],
+                    help="fused: spd_decode_step (both owners' pieces in one launch, one closing kernel); "
+                         "calls: the three entry points in sequence on one stream (private, public, merge); "
+                         "calls_public_first: the same with the public call first; "
+                         "streams: private and public calls on two streams of equal priority, joined before the merge "
+                         "(the last three are the orderings of the paper's overlap study, section 5)")
     ap.add_argument("--append", action="store_true",
                     help="fused mode only: also append one new token per user to the public cache in the same launch "
                          "(its slot is the cache's last token, rewritten every step)")
@@ -116,13 +119,17 @@ def main():
 
     fused = args.mode == "fused"
 
+    side = torch.cuda.Stream() if args.mode == "streams" else None     # default priority
+
     def run(n, start=0):
         for i in range(n):
             so = steps_objs[(start + i) % copies]
             if fused:
                 so.run_prepared_fused()
+            elif side is not None:
+                so.run_streams(q, side)
             else:
-                so.run_prepared()
+                so.run_prepared(public_first=args.mode == "calls_public_first")
 
     if args.calibrate_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(3)

@@ -173,6 +173,19 @@ int spd_decode_step(spd_ctx *ctx, const spd_shape *shape, const void *q, const s
                     float *a_out, float *lse_out, float *y, float *lse, float *w_in, void *hip_stream);
 
 /*
+ * Running statistics of the private part's attention mass (sections 2.4 and 7.1: a user's process can notice a
+ * prompt-leakage injection by watching how much attention its prompt still receives; Theorem 1's weight of A_in,
+ * w_in = gamma_in / (gamma_in + gamma_out), is that share, and spd_lse_merge / spd_decode_step emit it).
+ * One call folds one decode step's masses into the statistics, row by row:
+ *   mass_min[i] = min(mass_min[i], w_in[i]);  mass_sum[i] += w_in[i];  n_below[i] += (w_in[i] < threshold).
+ * All arrays DEVICE, [n_rows] (w_in, mass_min, mass_sum fp32; n_below int32).  The caller owns and initialises the
+ * statistics (mass_min = 1, the others 0) and divides mass_sum by its own step count for the mean; any of the
+ * three may be NULL.  The comparison with `threshold` is made on the fp32 values as stored.
+ */
+int spd_attention_mass_track(spd_ctx *ctx, int32_t n_rows, const float *w_in, float threshold, float *mass_min,
+                             float *mass_sum, int32_t *n_below, void *hip_stream);
+
+/*
  * Built-in timing of the partial-attention kernel (the HBM-streaming kernel of both partial calls), measured with HIP
  * events on the stream each call launches on.  spd_set_kernel_timing(ctx, n) arms timing for the next n launches of
  * each entry point (n = 0 disarms); while armed, every partial call launches its partial kernel with a start and a stop

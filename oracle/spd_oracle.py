@@ -226,3 +226,25 @@ def lse_of(m, gamma):
     with np.errstate(divide="ignore", invalid="ignore"):
         out = m + np.log(gamma)
     return np.where(gamma == 0.0, -np.inf, out)
+
+
+def attention_mass_track(w_steps, threshold: float):
+    """Running statistics of the private part's attention mass w_in = gamma_in / (gamma_in + gamma_out) (the weight
+    of A_in in Theorem 1) over a sequence of decode steps: the quantity a user's process would watch to notice that
+    generation has stopped attending to its prompt (the attention-based detection discussed in sections 2.4 and 7.1).
+
+    w_steps: [n_steps, n_rows] masses in [0, 1].  Returns, per row: the minimum over the steps, the sum over the steps
+    (mean = sum / n_steps) and the number of steps whose mass lies strictly below ``threshold``.  An empty sequence
+    gives (1, 0, 0): 1 is the largest value a mass can take.
+    """
+    w = np.asarray(w_steps, dtype=np.float64)
+    assert w.ndim == 2
+    n_rows = w.shape[1]
+    mn = np.ones(n_rows, dtype=np.float64)
+    sm = np.zeros(n_rows, dtype=np.float64)
+    below = np.zeros(n_rows, dtype=np.int64)
+    for step in range(w.shape[0]):          # one decode step after the other, as the statistic is kept
+        mn = np.minimum(mn, w[step])
+        sm = sm + w[step]
+        below = below + (w[step] < float(threshold))
+    return mn, sm, below

@@ -25,6 +25,7 @@ EXPORTED_SYMBOLS = (
     "spd_partial_attn_private", "spd_partial_attn_public_batched", "spd_lse_merge",
     "spd_validate_partial", "spd_build_schedule", "spd_set_kernel_timing", "spd_get_kernel_timing",
     "spd_decode_step", "spd_partial_attn_public_batched_append", "spd_get_schedule_stats",
+    "spd_attention_mass_track",
 )
 
 
@@ -75,6 +76,8 @@ def _load() -> C.CDLL:
         fn.argtypes = [vp, C.POINTER(spd_shape), vp, C.POINTER(spd_kv_view), fp, fp, vp]
     lib.spd_lse_merge.restype = C.c_int
     lib.spd_lse_merge.argtypes = [vp, C.c_int32, C.c_int32, fp, fp, fp, fp, fp, fp, fp, vp]
+    lib.spd_attention_mass_track.restype = C.c_int
+    lib.spd_attention_mass_track.argtypes = [vp, C.c_int32, fp, C.c_float, fp, fp, vp, vp]
     lib.spd_decode_step.restype = C.c_int
     lib.spd_decode_step.argtypes = [vp, C.POINTER(spd_shape), vp, C.POINTER(spd_kv_view), C.POINTER(spd_kv_view),
                                     vp, vp, fp, fp, fp, fp, fp, fp, fp, vp]
@@ -253,6 +256,17 @@ class Context:
                                  lse_out.data_ptr(), y.data_ptr(), lse.data_ptr(), w_in.data_ptr(), _stream_ptr(stream))
         self._check(rc, "spd_decode_step")
         return y
+
+    def spd_attention_mass_track(self, w_in, threshold, mass_min=None, mass_sum=None, n_below=None, stream=None):
+        n = w_in.numel()
+        for t in (w_in, mass_min, mass_sum):
+            assert t is None or (t.is_contiguous() and t.dtype == torch.float32 and t.numel() == n)
+        assert n_below is None or (n_below.is_contiguous() and n_below.dtype == torch.int32 and n_below.numel() == n)
+        ptr = lambda t: None if t is None else t.data_ptr()
+        rc = lib.spd_attention_mass_track(self.handle, n, w_in.data_ptr(), float(threshold), ptr(mass_min), ptr(mass_sum),
+                                          ptr(n_below),
+                                          _stream_ptr(stream))
+        self._check(rc, "spd_attention_mass_track")
 
     def spd_lse_merge(self, a0, lse0, a1, lse1, y=None, lse_out=None, w0_out=None, stream=None):
         n_rows = lse0.numel()

@@ -214,4 +214,21 @@ __global__ __launch_bounds__(256) void lse_merge_kernel(int64_t n_vec, int vec_p
     }
 }
 
+// Folds one decode step's private attention masses into running per-row statistics (minimum, sum, count below a
+// threshold); any of the three outputs may be null.
+__global__ __launch_bounds__(256) void mass_track_kernel(int n_rows, const float *__restrict__ w_in, float threshold,
+                                                          float *mass_min, float *mass_sum, int32_t *n_below)
+{
+    const int i = (int)(blockIdx.x * blockDim.x + threadIdx.x);
+    if (i >= n_rows)
+        return;
+    const float w = w_in[i];
+    if (mass_min)
+        mass_min[i] = fminf(mass_min[i], w);
+    if (mass_sum)
+        mass_sum[i] += w;
+    if (n_below && w < threshold)
+        n_below[i] += 1;
+}
+
 }  // namespace spd

@@ -1005,6 +1005,24 @@ int spd_decode_step(spd_ctx *ctx, const spd_shape *shape, const void *q, const s
     return SPD_OK;
 }
 
+int spd_attention_mass_track(spd_ctx *ctx, int32_t n_rows, const float *w_in, float threshold, float *mass_min,
+                             float *mass_sum, int32_t *n_below, void *hip_stream)
+{
+    if (!ctx)
+        return SPD_ERR_NULL;
+    if (n_rows < 0)
+        return SPD_ERR_LEN;
+    if (n_rows == 0)
+        return SPD_OK;
+    if (!w_in)
+        return SPD_ERR_NULL;
+    SPD_HIP(ctx, hipSetDevice(ctx->device));
+    hipLaunchKernelGGL(spd::mass_track_kernel, dim3((unsigned)((n_rows + 255) / 256)), dim3(256), 0,
+                       static_cast<hipStream_t>(hip_stream), n_rows, w_in, threshold, mass_min, mass_sum, n_below);
+    SPD_HIP(ctx, hipGetLastError());
+    return SPD_OK;
+}
+
 int spd_lse_merge(spd_ctx *ctx, int32_t n_rows, int32_t head_dim, const float *a0, const float *lse0, const float *a1,
                   const float *lse1, float *y, float *lse_out, float *w0_out, void *hip_stream)
 {

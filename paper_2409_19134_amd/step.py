@@ -78,9 +78,30 @@ class DecodeStep:
             self.ctx._check(rc, "spd_decode_step")
         return self.y
 
-    def run_prepared(self):
-        for fn, args in self._calls:
+    def run_prepared(self, public_first: bool = False):
+        """The three calls in sequence on the prepared stream; public_first swaps the two partial calls (the order
+        in which the paper's service runs its own attention before it hears from the user processes)."""
+        order = (1, 0, 2) if public_first else (0, 1, 2)
+        for i in order:
+            fn, args = self._calls[i]
             rc = fn(*args)
             if rc != 0:
                 self.ctx._check(rc, fn.__name__)
+        return self.y
+
+    def run_streams(self, q: torch.Tensor, side: "torch.cuda.Stream"):
+        """The two owners on two HIP streams of equal priority: the private call on torch's current stream, the public
+        call on `side`, joined by events before the merge (the paper's "start the private computation as soon as Q
+        exists" schedule, section 5, with streams standing in for processes).  No host synchronisation."""
+        c = self.ctx
+        main = torch.cuda.current_stream()
+        fork = torch.cuda.Event()
+        fork.record(main)          # everything already queued on main (the previous merge reads a_out) comes first
+        side.wait_event(fork)
+        c.spd_partial_attn_public_batched(self.shape, q, self.public, self.a_out, self.lse_out, side)
+        join = torch.cuda.Event()
+        join.record(side)
+        c.spd_partial_attn_private(self.shape, q, self.private, self.a_in, self.lse_in, main)
+        main.wait_event(join)
+        c.spd_lse_merge(self.a_in, self.lse_in, self.a_out, self.lse_out, self.y, self.lse, self.w_in, main)
         return self.y

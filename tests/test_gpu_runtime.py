@@ -65,6 +65,35 @@ def test_private_and_public_calls_on_two_streams():
     ctx.close()
 
 
+def test_step_orderings_give_the_same_result():
+    """The orderings of the overlap study (private first, public first, two streams, one fused launch) are the same
+    computation: identical partials bit for bit where the same kernels run (the three unfused orderings)."""
+    import paper_2409_19134_amd as spd
+    ctx = spd.Context(0)
+    wl = workloads.random_case(402, torch.bfloat16, 5, 32, 8, 128, [3000, 100, 0, 900, 64], [300, 900, 5, 0, 1], device=DEV)
+    step = spd.DecodeStep.from_workload(ctx, wl)
+    Y = _oracle_y(wl)
+    step.prepare(wl.q, torch.cuda.current_stream().cuda_stream)
+    outs = []
+    side = torch.cuda.Stream()
+    for mode in ("calls", "public_first", "streams", "streams", "fused"):
+        step.y.zero_()
+        if mode == "calls":
+            step.run_prepared()
+        elif mode == "public_first":
+            step.run_prepared(public_first=True)
+        elif mode == "streams":
+            step.run_streams(wl.q, side)
+        else:
+            step.run_prepared_fused()
+        torch.cuda.synchronize()
+        assert _err(step, Y) <= 2e-3
+        outs.append(step.y.clone())
+    for o in outs[1:4]:
+        assert torch.equal(o, outs[0])
+    ctx.close()
+
+
 def test_two_contexts_and_non_default_stream():
     import paper_2409_19134_amd as spd
     a, b = spd.Context(0), spd.Context(0)
@@ -169,4 +198,73 @@ def test_layers_share_one_schedule_per_step_in_paged_mode():
         for w, step in zip(layers, outs):
             assert _err(step, _oracle_y(w)) <= 2e-3
     assert hits == 2 * n_layers * n_steps - (n_steps + 1)
+    ctx.close()
+
+
+def test_attention_mass_track_against_oracle():
+    """Seeded masses (some exactly on the threshold, zeros, ones) folded step by step; then the masses of real decode
+    steps with KV append, against the oracle's w_in."""
+    import paper_2409_19134_amd as spd
+    ctx = spd.Context(0)
+    n_rows, steps, thr = 1000, 9, 0.375
+    g = torch.Generator().manual_seed(611)
+    w = torch.rand((steps, n_rows), generator=g, dtype=torch.float32)
+    w[2, ::7] = thr
+    w[3, ::11] = 0.0
+    w[4, ::13] = 1.0
+    mn = torch.ones(n_rows, device=DEV)
+    sm = torch.zeros(n_rows, device=DEV)
+    below = torch.zeros(n_rows, device=DEV, dtype=torch.int32)
+    wd = w.to(DEV)
+    for s in range(steps):
+        ctx.spd_attention_mass_track(wd[s], thr, mn, sm, below)
+    only_min = torch.ones(n_rows, device=DEV)
+    ctx.spd_attention_mass_track(wd[0], thr, mass_min=only_min)          # the other two statistics left out
+    torch.cuda.synchronize()
+    o_mn, o_sm, o_below = orc.attention_mass_track(w.double().numpy(), thr)
+    assert np.array_equal(mn.cpu().double().numpy(), o_mn)               # a minimum of fp32 values is exact
+    assert np.array_equal(below.cpu().numpy().astype(np.int64), o_below)
+    assert np.abs(sm.cpu().double().numpy() - o_sm).max() <= steps * 6e-7
+    assert torch.equal(only_min.cpu(), w[0])
+
+    # three decode steps of a growing public cache: w_in of the step against the oracle's merge weight
+    lp, lo0 = [300, 40, 0, 2000], [1, 5, 3, 0]
+    U, Hq, Hkv, d = 4, 32, 8, 128
+    cap = 8
+    wl = workloads.random_case(612, torch.bfloat16, U, Hq, Hkv, d, lp, [l + cap for l in lo0], device=DEV, layout="hnd")
+    mn = torch.ones(U * Hq, device=DEV)
+    sm = torch.zeros(U * Hq, device=DEV)
+    masses = []
+    for s in range(3):
+        wl.public.lens = np.asarray([l + s + 1 for l in lo0], dtype=np.int32)     # the step appends one token
+        step = spd.DecodeStep.from_workload(ctx, wl)
+        gq = torch.Generator(device=DEV).manual_seed(620 + s)
+        q = torch.randn((U, Hq, d), generator=gq, device=DEV).to(torch.bfloat16)
+        k_new = torch.randn((U, Hkv, d), generator=gq, device=DEV).to(torch.bfloat16)
+        v_new = torch.randn((U, Hkv, d), generator=gq, device=DEV).to(torch.bfloat16)
+        step.run_fused(q, k_new=k_new, v_new=v_new)
+        ctx.spd_attention_mass_track(step.w_in, 0.5, mn, sm)
+        torch.cuda.synchronize()
+        wl.q = q                                   # the cache now holds the new rows: the oracle reads it as it is
+        hw = orc.from_workload(wl)
+        A0, m0, g0 = orc.partial(hw, hw.private)
+        A1, m1, g1 = orc.partial(hw, hw.public)
+        masses.append(orc.merge(A0, m0, g0, A1, m1, g1)[3])
+        assert np.abs(step.w_in.cpu().double().numpy().reshape(-1) - masses[-1]).max() <= 2e-3
+    o_mn, o_sm, _ = orc.attention_mass_track(np.stack(masses), 0.5)
+    assert np.abs(mn.cpu().double().numpy() - o_mn).max() <= 2e-3
+    assert np.abs(sm.cpu().double().numpy() - o_sm).max() <= 3 * 2e-3
+    assert (mn.cpu().numpy().reshape(U, Hq)[2] == 0).all()               # user 2 has no private part
+    ctx.close()
+
+
+def test_attention_mass_track_argument_errors():
+    import paper_2409_19134_amd as spd
+    from paper_2409_19134_amd import binding as b
+    ctx = spd.Context(0)
+    w = torch.zeros(4, device=DEV)
+    assert b.lib.spd_attention_mass_track(ctx.handle, -1, w.data_ptr(), 0.5, None, None, None, None) == b.SPD_ERR_LEN
+    assert b.lib.spd_attention_mass_track(ctx.handle, 4, None, 0.5, None, None, None, None) == b.SPD_ERR_NULL
+    assert b.lib.spd_attention_mass_track(None, 4, w.data_ptr(), 0.5, None, None, None, None) == b.SPD_ERR_NULL
+    assert b.lib.spd_attention_mass_track(ctx.handle, 0, None, 0.5, None, None, None, None) == b.SPD_OK
     ctx.close()

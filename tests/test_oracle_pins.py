@@ -290,6 +290,45 @@ def test_naive_gammas_of_the_proof_match_stabilised_coefficients():
         assert 1 - w[h] == pytest.approx(g1[h] / (g0[h] / alpha + g1[h]), rel=1e-13)
 
 
+def test_attention_mass_is_the_softmax_mass_on_the_private_tokens():
+    """w_in of the merge is the share of the unsplit softmax that falls on the private tokens (library softmax)."""
+    from scipy.special import softmax
+    wl, hw = _case(43, torch.float32, 2, 4, 2, 16, [9, 3], [4, 11], layout="hnd")
+    A0, m0, g0 = orc.partial(hw, hw.private)
+    A1, m1, g1 = orc.partial(hw, hw.public)
+    _, _, _, w = orc.merge(A0, m0, g0, A1, m1, g1)
+    for u in range(2):
+        for h in range(4):
+            K, _ = _concat_rows(wl, u, h // 2)
+            p = softmax((K @ wl.q[u, h].double().numpy()) * wl.scale)
+            assert w[u * 4 + h] == pytest.approx(p[:int(wl.private.lens[u])].sum(), rel=1e-13)
+
+
+def test_attention_mass_track_closed_forms():
+    # row 0: an arithmetic ramp 0.1 .. 1.0; row 1: constant; row 2: alternating 0 and 1
+    steps = 10
+    w = np.stack([np.linspace(0.1, 1.0, steps), np.full(steps, 0.25), np.arange(steps) % 2.0], axis=1)
+    mn, sm, below = orc.attention_mass_track(w, 0.35)
+    np.testing.assert_allclose(mn, [0.1, 0.25, 0.0], rtol=0, atol=0)
+    np.testing.assert_allclose(sm, [steps * (0.1 + 1.0) / 2, 0.25 * steps, steps // 2], rtol=1e-14)
+    assert below.tolist() == [3, steps, steps // 2]           # 0.1, 0.2, 0.3 | all | the zeros
+    # strictly below: a mass equal to the threshold does not count; nothing to fold gives the neutral element
+    assert orc.attention_mass_track(np.array([[0.5]]), 0.5)[2].tolist() == [0]
+    mn0, sm0, b0 = orc.attention_mass_track(np.zeros((0, 2)), 0.5)
+    assert mn0.tolist() == [1, 1] and sm0.tolist() == [0, 0] and b0.tolist() == [0, 0]
+    # folding a sequence in two halves, carrying the state by hand, is folding it at once
+    rng = np.random.default_rng(5)
+    w = rng.random((7, 4))
+    a = orc.attention_mass_track(w[:3], 0.4)
+    b = orc.attention_mass_track(w[3:], 0.4)
+    full = orc.attention_mass_track(w, 0.4)
+    np.testing.assert_array_equal(np.minimum(a[0], b[0]), full[0])
+    np.testing.assert_allclose(a[1] + b[1], full[1], rtol=1e-15)
+    np.testing.assert_array_equal(a[2] + b[2], full[2])
+    np.testing.assert_array_equal(full[0], w.min(axis=0))
+    np.testing.assert_array_equal(full[2], (w < 0.4).sum(axis=0))
+
+
 def test_merge_extreme_score_gap_stays_finite():
     """m_out - m_in far beyond the fp32 exp range (config 3 style outliers): weights saturate, no NaN."""
     d = 4
