@@ -39,21 +39,34 @@ struct LaneConst {
     const char *v_new_row;
 };
 
+// The two 16-token pages a 32-token step at tb touches.  The ids are wave-uniform and come through the scalar cache.
+// Clamping keeps the lookups inside the user's pages; rows past the chunk re-read its last token, which lies in the
+// page the clamped lookup names (an 8-token group never straddles a page).
+struct PagePair {
+    int p0, p1;
+};
+
+__device__ __forceinline__ PagePair load_pages(const LaneConst &L, int tb, int t_last)
+{
+    const int tbu = uniform(tb);
+    PagePair P;
+    P.p0 = scalar_load_i32(L.bt_row, min(tbu, t_last) >> 4);
+    P.p1 = scalar_load_i32(L.bt_row, min(tbu + 16, t_last) >> 4);
+    return P;
+}
+
+// Issues the 16 loads of the step at tb.  Paged: P holds that step's page ids on entry and the following step's
+// (tb + step) on return: the lookup is issued behind the data loads, one whole step before it is needed, so that no
+// wave ever waits for a block-table entry before it can ask for data.
 template <bool PAGED>
-__device__ __forceinline__ void load_tile(TileRegs &T, const LaneConst &L, int tb, int t_last)
+__device__ __forceinline__ void load_tile(TileRegs &T, const LaneConst &L, int tb, int t_last, PagePair &P, int step)
 {
     const int gk = tb + (L.r >> 2) * 8;  // first token of the 8-token group this lane's K rows fall in
     const int gv = tb + L.grp * 8;       // first token of the group this lane's V rows fall in
     const char *kp = L.k_base, *vp = L.v_base;
     if (PAGED) {
-        // A 32-token step touches two 16-token pages; their ids are wave-uniform and come through the scalar cache.
-        // Clamping keeps the lookups inside the user's pages; rows past the chunk re-read its last token, which lies
-        // in the page the clamped lookup names (an 8-token group never straddles a page).
-        const int tbu = uniform(tb);
-        const int64_t p0 = scalar_load_i32(L.bt_row, min(tbu, t_last) >> 4);
-        const int64_t p1 = scalar_load_i32(L.bt_row, min(tbu + 16, t_last) >> 4);
-        kp += ((gk - tb) >= 16 ? p1 : p0) * L.block_stride;
-        vp += ((gv - tb) >= 16 ? p1 : p0) * L.block_stride;
+        kp += (int64_t)((gk - tb) >= 16 ? P.p1 : P.p0) * L.block_stride;
+        vp += (int64_t)((gv - tb) >= 16 ? P.p1 : P.p0) * L.block_stride;
     }
 #pragma unroll
     for (int a = 0; a < 2; ++a) {
@@ -73,6 +86,8 @@ __device__ __forceinline__ void load_tile(TileRegs &T, const LaneConst &L, int t
             p = L.v_new_row + L.r * 16;
         T.v[e] = stream_load16(p);
     }
+    if (PAGED)
+        P = load_pages(L, tb + step, t_last);
     // all 16 loads of the step are issued before anything that follows: without this the compiler sinks the V loads
     // below the K wait to shorten live ranges, which serialises two memory round trips per step
     __builtin_amdgcn_sched_barrier(0);
@@ -175,7 +190,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, PREFETCH ? 2 : 3) void partia
     // Everything a segment needs before its first MFMA: addresses, the KV append copy, Q, and the loads of the wave's
     // first 32-token step.  Issued for the *next* segment before the current one's epilogue, so that the barriers
     // and the result stores of the epilogue overlap the memory round trip instead of preceding it.
-    auto begin_segment = [&](const DevItem &it, LaneConst &L, bf16x8 (&qB)[4], int &tb, TileRegs &T0) {
+    auto begin_segment = [&](const DevItem &it, LaneConst &L, bf16x8 (&qB)[4], int &tb, TileRegs &T0, PagePair &P) {
         L.r = lane & 15;
         L.grp = lane >> 4;
         L.token_stride = kv.token_stride;
@@ -214,8 +229,10 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, PREFETCH ? 2 : 3) void partia
         }
         // head-major: the four waves take interleaved 32-token steps; token-major: every wave takes every step
         tb = HPW ? it.t_begin : it.t_begin + ((uniform(wave) - (it.rot & 3)) & (kWaves - 1)) * 32;
+        if (PAGED)
+            P = load_pages(L, tb, t_last);
         if (PREFETCH && tb < it.t_end)
-            load_tile<PAGED>(T0, L, tb, t_last);
+            load_tile<PAGED>(T0, L, tb, t_last, P, kStep);
     };
 
     DevItem it = scalar_load_item(items, second ? (int)blockIdx.x - n0 : (int)blockIdx.x);
@@ -235,7 +252,8 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, PREFETCH ? 2 : 3) void partia
     bf16x8 qB[4];
     int tb;
     TileRegs T0;
-    begin_segment(it, L, qB, tb, T0);
+    PagePair P = {0, 0};
+    begin_segment(it, L, qB, tb, T0, P);
     for (;;) {
         // the piece's next segment is fetched (scalar cache) long before it is looked at: with tens of MB of loads in
         // flight a dependent round trip costs microseconds, so none may sit between two segments
@@ -253,7 +271,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, PREFETCH ? 2 : 3) void partia
         if (!PREFETCH) {
             for (; tb < it.t_end; tb += kStep) {
                 TileRegs T;
-                load_tile<PAGED>(T, L, tb, t_last);
+                load_tile<PAGED>(T, L, tb, t_last, P, kStep);
                 compute_tile(T, qB, tb, L.grp, it.t_end, scale_log2e, m, l, acc);
             }
         } else if (tb < it.t_end) {  // T0 already holds (the loads of) step tb
@@ -267,7 +285,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, PREFETCH ? 2 : 3) void partia
                     if (HPW)
                         __builtin_amdgcn_s_barrier();
                     if (more1)
-                        load_tile<PAGED>(T1, L, tb1, t_last);
+                        load_tile<PAGED>(T1, L, tb1, t_last, P, kStep);
                     compute_tile(T0, qB, tb, L.grp, it.t_end, scale_log2e, m, l, acc);
                     if (!more1)
                         break;
@@ -276,7 +294,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, PREFETCH ? 2 : 3) void partia
                     if (HPW)
                         __builtin_amdgcn_s_barrier();
                     if (more2)
-                        load_tile<PAGED>(T0, L, tb2, t_last);
+                        load_tile<PAGED>(T0, L, tb2, t_last, P, kStep);
                     compute_tile(T1, qB, tb1, L.grp, it.t_end, scale_log2e, m, l, acc);
                     if (!more2)
                         break;
@@ -288,7 +306,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, PREFETCH ? 2 : 3) void partia
         const int grp = L.grp, r = L.r;
         // the two-per-CU kernel has the registers to let the next segment's loads fly during the epilogue below
         if (PREFETCH && it.next >= 0)
-            begin_segment(nx, L, qB, tb, T0);
+            begin_segment(nx, L, qB, tb, T0, P);
 
         // ---- combine the lane groups (sum of l) ... ----
         l += __shfl_xor(l, 16);
@@ -321,7 +339,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, PREFETCH ? 2 : 3) void partia
             if (it.next < 0)
                 return;
             if (!PREFETCH)
-                begin_segment(nx, L, qB, tb, T0);
+                begin_segment(nx, L, qB, tb, T0, P);
             it = nx;
             continue;
         }
@@ -376,7 +394,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, PREFETCH ? 2 : 3) void partia
         if (it.next < 0)
             return;
         if (!PREFETCH)
-            begin_segment(nx, L, qB, tb, T0);
+            begin_segment(nx, L, qB, tb, T0, P);
         it = nx;
         __syncthreads();  // the LDS staging arrays are reused by the next segment
     }

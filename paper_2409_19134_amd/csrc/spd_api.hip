@@ -26,7 +26,9 @@ using spd::RowInfo;
 constexpr int kCacheEntries = 16;    // remembered schedules per entry point
 constexpr int kChunkAlign = 32;      // chunk boundaries are multiples of the MFMA kernel's 32-token step
 constexpr int kChunkMin = 128;       // one 32-token step for each of the four waves
-constexpr int kChunkMaxDefault = 4096;     // tokens per piece when the work exceeds one resident wave
+constexpr int kChunkMaxDefault = 16384;    // tokens per piece when the work exceeds one resident wave: a new
+                                            // workgroup costs a few microseconds of an idle slot, more than the longer
+                                            // tail of bigger pieces (4096: 3 % slower on the longest workload)
 constexpr int kNoSplitMaxDefault = 768;     // rows this short are never split: the work is latency-bound and a
                                             // whole row per workgroup saves the combine launch
 constexpr int kTargetWgPerCuDefault = 2;   // workgroups of the MFMA kernel resident per CU (2 waves per SIMD)
@@ -144,8 +146,8 @@ struct Schedule {
 
 // hpw: pieces for the head-per-wave kernel (token-major storage).  A piece then covers all KV heads of its token
 // range: one item per cut (kv_head = 0, slot = the slot of head 0) and one resident workgroup per CU.  The same
-// token limit per piece measured best (2048 and 4096 within 1 %, 1024 4 % slower), although every wave now walks
-// the whole range instead of a quarter of it.
+// token limit per piece serves both mappings (smaller pieces measured slower here too), although every wave now
+// walks the whole range instead of a quarter of it.
 void build_schedule(int Hkv, int n_users, const int32_t *lens, int n_cus, bool fused, bool hpw, Schedule &S)
 {
     S.items.clear();
