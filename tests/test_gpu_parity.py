@@ -166,6 +166,36 @@ def test_bf16_head_groupings(ctx, mapping_of, Hq, Hkv, layout):
     check_against_oracle(ctx, wl)
 
 
+def _random_case_spec(rng):
+    """Shape, lengths, storage and mapping of one randomised case, drawn from the given numpy generator."""
+    bf16 = rng.random() < 0.7
+    Hkv = int(rng.choice([1, 2, 4, 8] if bf16 else [1, 2, 4]))
+    G = int(rng.choice([1, 2, 3, 4, 8, 16] if bf16 else [1, 2, 4, 8]))
+    d = 128 if bf16 else int(rng.choice([64, 128]))
+    U = int(rng.integers(1, 7))
+    kinds = [lambda: 0, lambda: int(rng.integers(1, 40)), lambda: int(rng.integers(40, 800)),
+             lambda: int(rng.integers(800, 6000)), lambda: int(rng.choice([32, 64, 128, 512, 1024]))]
+    weights = [0.1, 0.25, 0.3, 0.2, 0.15]
+    lens = lambda: [kinds[int(rng.choice(len(kinds), p=weights))]() for _ in range(U)]
+    storage = str(rng.choice(["nhd", "nhd_hpw", "hnd", "hnd_exact", "paged", "paged_tm"]))
+    return dict(dtype=torch.bfloat16 if bf16 else torch.float32, U=U, Hq=Hkv * G, Hkv=Hkv, d=d, lp=lens(), lo=lens(),
+                storage=storage, scale=float(rng.choice([d ** -0.5, 0.02, 0.3])))
+
+
+@pytest.mark.parametrize("block", range(4))
+def test_randomised_cases(ctx, mapping_of, block):
+    """Seeded random shapes, lengths, storage modes and kernel mappings; every case through both step variants."""
+    rng = np.random.default_rng(9000 + block)
+    for i in range(10):
+        c = _random_case_spec(rng)
+        print(f"randomised case {block}.{i}: {c}", flush=True)       # names the case if the GPU run ends badly
+        paged = {"paged": True, "paged_tm": "token_major"}.get(c["storage"], False)
+        layout = mapping_of("nhd" if paged else c["storage"])
+        wl = workloads.random_case(9100 + 16 * block + i, c["dtype"], c["U"], c["Hq"], c["Hkv"], c["d"], c["lp"], c["lo"],
+                                   device=DEV, layout=layout, paged=paged, scale=c["scale"])
+        check_against_oracle(ctx, wl)
+
+
 @pytest.mark.parametrize("d,Hq,Hkv", [(64, 8, 8), (64, 8, 2), (128, 8, 1), (128, 4, 4), (64, 16, 2)])
 @pytest.mark.parametrize("paged", [False, True])
 def test_fp32_shapes(ctx, d, Hq, Hkv, paged):
