@@ -1,0 +1,161 @@
+// The split schedule of a partial-attention launch (host only, no HIP calls).
+#pragma once
+#include <algorithm>
+#include <cstdint>
+#include <cstdlib>
+#include <vector>
+
+#include "../../include/spd.h"
+#include "common.hpp"
+
+namespace spd::host {
+
+constexpr int kChunkAlign = 32;      // chunk boundaries are multiples of the MFMA kernel's 32-token step
+constexpr int kChunkMin = 128;       // one 32-token step for each of the four waves
+constexpr int kChunkMaxDefault = 16384;    // tokens per piece when the work exceeds one resident wave: a new
+                                            // workgroup costs a few microseconds of an idle slot, more than the longer
+                                            // tail of bigger pieces (4096: 3 % slower on the longest workload)
+constexpr int kNoSplitMaxDefault = 768;     // rows this short are never split: the work is latency-bound and a
+                                            // whole row per workgroup saves the combine launch
+constexpr int kTargetWgPerCuDefault = 2;   // workgroups of the MFMA kernel resident per CU (2 waves per SIMD)
+constexpr int kHeadPerWaveMinSteps = 8;    // 32-token steps per CU from which the head-per-wave mapping is used
+
+inline int env_int(const char *name, int dflt)
+{
+    const char *s = std::getenv(name);
+    if (!s || !*s)
+        return dflt;
+    const long v = std::strtol(s, nullptr, 10);
+    return v > 0 ? (int)v : dflt;
+}
+
+// The split schedule ("stream-K" over tokens).  All KV heads of a user hold the same tokens, so the schedule is laid
+// out on token steps (32 tokens) per user and replicated over the KV heads: the steps of all users, laid end to end,
+// are divided into groups of equal length (+-1 step), and every group becomes one piece (one workgroup) per KV head.
+// The pieces of a group are adjacent in launch order, so with token-major storage the heads that share DRAM pages
+// stream them at the same time.  A group that crosses a user boundary gives pieces with several segments.
+// Equal pieces matter because the path is HBM-bound: a launch lasts as long as its longest workgroup.
+//   - if no user is longer than a few hundred tokens the work is latency-bound: a standalone call then takes one
+//     whole row per workgroup (nothing to combine afterwards: saves the combine launch), the fused step, whose
+//     closing kernel combines anyway, takes chunks of 128 tokens (one step per wave: one memory round trip);
+//   - work that fits one resident wave of workgroups (2 per CU) gets exactly that many pieces;
+//   - larger work gets pieces of at most `piece_max` tokens, their number rounded up to a multiple of the resident
+//     wave, and relies on the hardware's dynamic workgroup dispatch.
+struct Schedule {
+    std::vector<spd_work_item> items;  // segments in piece order (rows with tokens only)
+    std::vector<int32_t> piece_first;  // [n_pieces + 1] first segment of each piece
+    int64_t n_slots = 0;
+    int chunk_tokens = 0;              // tokens per piece (rounded up)
+};
+
+// hpw: pieces for the head-per-wave kernel (token-major storage).  A piece then covers all KV heads of its token
+// range: one item per cut (kv_head = 0, slot = the slot of head 0) and one resident workgroup per CU.  The same
+// token limit per piece serves both mappings (smaller pieces measured slower here too), although every wave now
+// walks the whole range instead of a quarter of it.
+inline void build_schedule(int Hkv, int n_users, const int32_t *lens, int n_cus, bool fused, bool hpw, Schedule &S)
+{
+    S.items.clear();
+    S.piece_first.assign(1, 0);
+    S.n_slots = 0;
+    S.chunk_tokens = 0;
+    int64_t T = 0;  // total 32-token steps per KV head
+    int max_len = 0;
+    for (int u = 0; u < n_users; ++u) {
+        T += (lens[u] + kChunkAlign - 1) / kChunkAlign;
+        max_len = std::max(max_len, lens[u]);
+    }
+    if (T == 0)
+        return;
+
+    // a group: user-local step ranges; cut[g] lists (user, first step, end step)
+    struct Cut {
+        int user;
+        int64_t s0, s1;
+    };
+    std::vector<std::vector<Cut>> groups;
+    if (max_len <= env_int("SPD_NO_SPLIT_MAX", kNoSplitMaxDefault)) {
+        // steps per chunk (every wave of a head-per-wave piece walks all of them: two round trips with its prefetch)
+        const int64_t per = fused ? spd::kWaves : (int64_t)1 << 40;
+        for (int u = 0; u < n_users; ++u) {
+            const int64_t steps = (lens[u] + kChunkAlign - 1) / kChunkAlign;
+            for (int64_t s0 = 0; s0 < steps; s0 += per)
+                groups.push_back({Cut{u, s0, std::min(steps, s0 + per)}});
+        }
+        S.chunk_tokens = (int)std::min<int64_t>(per, (max_len + kChunkAlign - 1) / kChunkAlign) * kChunkAlign;
+    } else {
+        const int64_t slots = (int64_t)std::max(1, n_cus) * env_int("SPD_TARGET_WG_PER_CU", kTargetWgPerCuDefault);
+        // groups per resident wave of workgroups
+        const int64_t wg = hpw ? std::max(1, n_cus) : std::max<int64_t>(1, slots / Hkv);
+        const int64_t piece_max = std::max(kChunkMin, env_int("SPD_CHUNK_MAX", kChunkMaxDefault)) / kChunkAlign;
+        // group boundaries (cumulative step counts)
+        std::vector<int64_t> ends;
+        if (T <= wg * piece_max) {
+            // at least one step per wave
+            const int64_t W = std::min<int64_t>(wg, hpw ? T : (T + spd::kWaves - 1) / spd::kWaves);
+            for (int64_t i = 0; i < W; ++i)
+                ends.push_back(T * (i + 1) / W);
+        } else {
+            // several resident waves of equal pieces; the hardware hands them out in launch order.  (Cutting the last
+            // wave's share finer to shorten the tail was measured and lost 1-3 %: short pieces cost more than the tail.)
+            const int64_t W = wg * ((T + wg * piece_max - 1) / (wg * piece_max));
+            for (int64_t i = 0; i < W; ++i)
+                ends.push_back(T * (i + 1) / W);
+        }
+        const int64_t W = (int64_t)ends.size();
+        int64_t longest = ends[0];
+        for (size_t i = 1; i < ends.size(); ++i)
+            longest = std::max(longest, ends[i] - ends[i - 1]);
+        S.chunk_tokens = (int)longest * kChunkAlign;
+        groups.resize((size_t)W);
+        int64_t g0 = 0;  // global step index of the current user's first step
+        int64_t g = 0;
+        for (int u = 0; u < n_users; ++u) {
+            const int64_t steps = (lens[u] + kChunkAlign - 1) / kChunkAlign;
+            int64_t s = 0;
+            while (s < steps) {
+                while (ends[(size_t)g] <= g0 + s)
+                    ++g;
+                const int64_t e = std::min(steps, ends[(size_t)g] - g0);
+                groups[(size_t)g].push_back(Cut{u, s, e});
+                s = e;
+            }
+            g0 += steps;
+        }
+    }
+
+    // chunks per user (same for all its KV heads) and the first partial slot of every row
+    std::vector<int32_t> n_chunks((size_t)n_users, 0), seen((size_t)n_users, 0);
+    for (const auto &grp : groups)
+        for (const Cut &c : grp)
+            ++n_chunks[(size_t)c.user];
+    std::vector<int64_t> user_slot0((size_t)n_users, 0);
+    for (int u = 0; u < n_users; ++u) {
+        user_slot0[(size_t)u] = S.n_slots;
+        S.n_slots += (int64_t)n_chunks[(size_t)u] * Hkv;
+    }
+    int32_t piece = 0;
+    for (const auto &grp : groups) {
+        if (grp.empty())
+            continue;
+        for (int h = 0; h < (hpw ? 1 : Hkv); ++h) {
+            for (const Cut &c : grp) {
+                spd_work_item it;
+                it.user = c.user;
+                it.kv_head = h;
+                it.t_begin = (int32_t)(c.s0 * kChunkAlign);
+                it.t_end = (int32_t)std::min<int64_t>(lens[c.user], c.s1 * kChunkAlign);
+                it.n_chunks = n_chunks[(size_t)c.user];
+                it.chunk = seen[(size_t)c.user];
+                it.slot = (int32_t)(user_slot0[(size_t)c.user] + (int64_t)h * it.n_chunks + it.chunk);
+                it.piece = piece;
+                S.items.push_back(it);
+            }
+            ++piece;
+            S.piece_first.push_back((int32_t)S.items.size());
+        }
+        for (const Cut &c : grp)
+            ++seen[(size_t)c.user];
+    }
+}
+
+}  // namespace spd::host

@@ -1,4 +1,5 @@
-// Host side of the SPD decode-attention library: C ABI, argument validation, split schedule, launches.
+// Host side of the SPD decode-attention library: C ABI, schedule cache, scratch memory, launches
+// (argument validation: host_checks.hpp; the split schedule itself: schedule.hpp).
 // The calls follow the paper's decode protocol (section 4, step 3b/3c) and Theorem 1 (section 4.2).
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>
@@ -12,8 +13,10 @@
 
 #include "combine.hpp"
 #include "common.hpp"
+#include "host_checks.hpp"
 #include "partial_bf16_mfma.hpp"
 #include "partial_generic.hpp"
+#include "schedule.hpp"
 
 namespace {
 
@@ -22,237 +25,9 @@ using spd::DevItem;
 using spd::KvAddr;
 using spd::OwnerArgs;
 using spd::RowInfo;
+using namespace spd::host;
 
 constexpr int kCacheEntries = 16;    // remembered schedules per entry point
-constexpr int kChunkAlign = 32;      // chunk boundaries are multiples of the MFMA kernel's 32-token step
-constexpr int kChunkMin = 128;       // one 32-token step for each of the four waves
-constexpr int kChunkMaxDefault = 16384;    // tokens per piece when the work exceeds one resident wave: a new
-                                            // workgroup costs a few microseconds of an idle slot, more than the longer
-                                            // tail of bigger pieces (4096: 3 % slower on the longest workload)
-constexpr int kNoSplitMaxDefault = 768;     // rows this short are never split: the work is latency-bound and a
-                                            // whole row per workgroup saves the combine launch
-constexpr int kTargetWgPerCuDefault = 2;   // workgroups of the MFMA kernel resident per CU (2 waves per SIMD)
-constexpr int kHeadPerWaveMinSteps = 8;    // 32-token steps per CU from which the head-per-wave mapping is used
-
-int env_int(const char *name, int dflt)
-{
-    const char *s = std::getenv(name);
-    if (!s || !*s)
-        return dflt;
-    const long v = std::strtol(s, nullptr, 10);
-    return v > 0 ? (int)v : dflt;
-}
-
-int elt_size(int dtype) { return dtype == SPD_F32 ? 4 : 2; }
-
-int validate_shape(const spd_shape *s)
-{
-    if (!s)
-        return SPD_ERR_NULL;
-    if (s->dtype != SPD_F32 && s->dtype != SPD_BF16)
-        return SPD_ERR_SHAPE;
-    if (s->n_q_heads <= 0 || s->n_kv_heads <= 0 || s->n_q_heads % s->n_kv_heads != 0)
-        return SPD_ERR_SHAPE;
-    const int G = s->n_q_heads / s->n_kv_heads;
-    if (s->dtype == SPD_BF16) {
-        if (s->head_dim != 128 || G > spd::kMaxGroup)
-            return SPD_ERR_SHAPE;
-    } else {
-        if (s->head_dim != 64 && s->head_dim != 128)
-            return SPD_ERR_SHAPE;
-        if (G != 1 && G != 2 && G != 4 && G != 8)
-            return SPD_ERR_SHAPE;
-    }
-    if (!std::isfinite(s->scale))
-        return SPD_ERR_SHAPE;
-    return SPD_OK;
-}
-
-bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
-
-int validate_view(const spd_shape *s, const spd_kv_view *v)
-{
-    if (!v)
-        return SPD_ERR_NULL;
-    if (v->n_users < 0)
-        return SPD_ERR_LEN;
-    if (v->n_users > 0 && !v->lens)
-        return SPD_ERR_NULL;
-    const int es = elt_size(s->dtype);
-    if (v->block_size != 0 && v->block_size != 16)
-        return SPD_ERR_SHAPE;
-    bool any = false;
-    for (int u = 0; u < v->n_users; ++u) {
-        if (v->lens[u] < 0)
-            return SPD_ERR_LEN;
-        any = any || v->lens[u] > 0;
-    }
-    // rows are read with 16-byte loads: strides must keep every row 16-byte aligned and rows must not overlap
-    if (v->token_stride < s->head_dim || (v->token_stride * es) % 16 != 0)
-        return any ? SPD_ERR_ALIGN : SPD_OK;
-    if (v->head_stride < 0 || (v->head_stride * es) % 16 != 0)
-        return any ? SPD_ERR_ALIGN : SPD_OK;
-    if (v->head_strides && v->block_size == 0)
-        for (int u = 0; u < v->n_users; ++u)
-            if (v->lens[u] > 0 && (v->head_strides[u] < 0 || (v->head_strides[u] * es) % 16 != 0))
-                return SPD_ERR_ALIGN;
-    if (v->block_size == 0) {
-        if (any && (!v->k_ptrs || !v->v_ptrs))
-            return SPD_ERR_NULL;
-        for (int u = 0; u < v->n_users; ++u) {
-            if (v->lens[u] == 0)
-                continue;
-            if (!v->k_ptrs[u] || !v->v_ptrs[u])
-                return SPD_ERR_NULL;
-            if (!aligned16(v->k_ptrs[u]) || !aligned16(v->v_ptrs[u]))
-                return SPD_ERR_ALIGN;
-        }
-    } else {
-        if (v->max_blocks < 0)
-            return SPD_ERR_LEN;
-        for (int u = 0; u < v->n_users; ++u)
-            if (((int64_t)v->lens[u] + 15) / 16 > v->max_blocks)
-                return SPD_ERR_LEN;
-        if (any) {
-            if (!v->k_pool || !v->v_pool || !v->block_table)
-                return SPD_ERR_NULL;
-            if (!aligned16(v->k_pool) || !aligned16(v->v_pool) || (reinterpret_cast<uintptr_t>(v->block_table) & 3u))
-                return SPD_ERR_ALIGN;
-            if (v->block_stride <= 0 || (v->block_stride * es) % 16 != 0)
-                return SPD_ERR_ALIGN;
-        }
-    }
-    return SPD_OK;
-}
-
-// The split schedule ("stream-K" over tokens).  All KV heads of a user hold the same tokens, so the schedule is laid
-// out on token steps (32 tokens) per user and replicated over the KV heads: the steps of all users, laid end to end,
-// are divided into groups of equal length (+-1 step), and every group becomes one piece (one workgroup) per KV head.
-// The pieces of a group are adjacent in launch order, so with token-major storage the heads that share DRAM pages
-// stream them at the same time.  A group that crosses a user boundary gives pieces with several segments.
-// Equal pieces matter because the path is HBM-bound: a launch lasts as long as its longest workgroup.
-//   - if no user is longer than a few hundred tokens the work is latency-bound: a standalone call then takes one
-//     whole row per workgroup (nothing to combine afterwards: saves the combine launch), the fused step, whose
-//     closing kernel combines anyway, takes chunks of 128 tokens (one step per wave: one memory round trip);
-//   - work that fits one resident wave of workgroups (2 per CU) gets exactly that many pieces;
-//   - larger work gets pieces of at most `piece_max` tokens, their number rounded up to a multiple of the resident
-//     wave, and relies on the hardware's dynamic workgroup dispatch.
-struct Schedule {
-    std::vector<spd_work_item> items;  // segments in piece order (rows with tokens only)
-    std::vector<int32_t> piece_first;  // [n_pieces + 1] first segment of each piece
-    int64_t n_slots = 0;
-    int chunk_tokens = 0;              // tokens per piece (rounded up)
-};
-
-// hpw: pieces for the head-per-wave kernel (token-major storage).  A piece then covers all KV heads of its token
-// range: one item per cut (kv_head = 0, slot = the slot of head 0) and one resident workgroup per CU.  The same
-// token limit per piece serves both mappings (smaller pieces measured slower here too), although every wave now
-// walks the whole range instead of a quarter of it.
-void build_schedule(int Hkv, int n_users, const int32_t *lens, int n_cus, bool fused, bool hpw, Schedule &S)
-{
-    S.items.clear();
-    S.piece_first.assign(1, 0);
-    S.n_slots = 0;
-    S.chunk_tokens = 0;
-    int64_t T = 0;  // total 32-token steps per KV head
-    int max_len = 0;
-    for (int u = 0; u < n_users; ++u) {
-        T += (lens[u] + kChunkAlign - 1) / kChunkAlign;
-        max_len = std::max(max_len, lens[u]);
-    }
-    if (T == 0)
-        return;
-
-    // a group: user-local step ranges; cut[g] lists (user, first step, end step)
-    struct Cut {
-        int user;
-        int64_t s0, s1;
-    };
-    std::vector<std::vector<Cut>> groups;
-    if (max_len <= env_int("SPD_NO_SPLIT_MAX", kNoSplitMaxDefault)) {
-        // steps per chunk (every wave of a head-per-wave piece walks all of them: two round trips with its prefetch)
-        const int64_t per = fused ? spd::kWaves : (int64_t)1 << 40;
-        for (int u = 0; u < n_users; ++u) {
-            const int64_t steps = (lens[u] + kChunkAlign - 1) / kChunkAlign;
-            for (int64_t s0 = 0; s0 < steps; s0 += per)
-                groups.push_back({Cut{u, s0, std::min(steps, s0 + per)}});
-        }
-        S.chunk_tokens = (int)std::min<int64_t>(per, (max_len + kChunkAlign - 1) / kChunkAlign) * kChunkAlign;
-    } else {
-        const int64_t slots = (int64_t)std::max(1, n_cus) * env_int("SPD_TARGET_WG_PER_CU", kTargetWgPerCuDefault);
-        // groups per resident wave of workgroups
-        const int64_t wg = hpw ? std::max(1, n_cus) : std::max<int64_t>(1, slots / Hkv);
-        const int64_t piece_max = std::max(kChunkMin, env_int("SPD_CHUNK_MAX", kChunkMaxDefault)) / kChunkAlign;
-        // group boundaries (cumulative step counts)
-        std::vector<int64_t> ends;
-        if (T <= wg * piece_max) {
-            // at least one step per wave
-            const int64_t W = std::min<int64_t>(wg, hpw ? T : (T + spd::kWaves - 1) / spd::kWaves);
-            for (int64_t i = 0; i < W; ++i)
-                ends.push_back(T * (i + 1) / W);
-        } else {
-            // several resident waves of equal pieces; the hardware hands them out in launch order.  (Cutting the last
-            // wave's share finer to shorten the tail was measured and lost 1-3 %: short pieces cost more than the tail.)
-            const int64_t W = wg * ((T + wg * piece_max - 1) / (wg * piece_max));
-            for (int64_t i = 0; i < W; ++i)
-                ends.push_back(T * (i + 1) / W);
-        }
-        const int64_t W = (int64_t)ends.size();
-        int64_t longest = ends[0];
-        for (size_t i = 1; i < ends.size(); ++i)
-            longest = std::max(longest, ends[i] - ends[i - 1]);
-        S.chunk_tokens = (int)longest * kChunkAlign;
-        groups.resize((size_t)W);
-        int64_t g0 = 0;  // global step index of the current user's first step
-        int64_t g = 0;
-        for (int u = 0; u < n_users; ++u) {
-            const int64_t steps = (lens[u] + kChunkAlign - 1) / kChunkAlign;
-            int64_t s = 0;
-            while (s < steps) {
-                while (ends[(size_t)g] <= g0 + s)
-                    ++g;
-                const int64_t e = std::min(steps, ends[(size_t)g] - g0);
-                groups[(size_t)g].push_back(Cut{u, s, e});
-                s = e;
-            }
-            g0 += steps;
-        }
-    }
-
-    // chunks per user (same for all its KV heads) and the first partial slot of every row
-    std::vector<int32_t> n_chunks((size_t)n_users, 0), seen((size_t)n_users, 0);
-    for (const auto &grp : groups)
-        for (const Cut &c : grp)
-            ++n_chunks[(size_t)c.user];
-    std::vector<int64_t> user_slot0((size_t)n_users, 0);
-    for (int u = 0; u < n_users; ++u) {
-        user_slot0[(size_t)u] = S.n_slots;
-        S.n_slots += (int64_t)n_chunks[(size_t)u] * Hkv;
-    }
-    int32_t piece = 0;
-    for (const auto &grp : groups) {
-        if (grp.empty())
-            continue;
-        for (int h = 0; h < (hpw ? 1 : Hkv); ++h) {
-            for (const Cut &c : grp) {
-                spd_work_item it;
-                it.user = c.user;
-                it.kv_head = h;
-                it.t_begin = (int32_t)(c.s0 * kChunkAlign);
-                it.t_end = (int32_t)std::min<int64_t>(lens[c.user], c.s1 * kChunkAlign);
-                it.n_chunks = n_chunks[(size_t)c.user];
-                it.chunk = seen[(size_t)c.user];
-                it.slot = (int32_t)(user_slot0[(size_t)c.user] + (int64_t)h * it.n_chunks + it.chunk);
-                it.piece = piece;
-                S.items.push_back(it);
-            }
-            ++piece;
-            S.piece_first.push_back((int32_t)S.items.size());
-        }
-        for (const Cut &c : grp)
-            ++seen[(size_t)c.user];
-    }
-}
 
 uint64_t fnv1a(const uint8_t *p, size_t n)
 {
