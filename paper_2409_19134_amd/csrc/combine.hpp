@@ -88,6 +88,74 @@ __device__ __forceinline__ void combine_row_small(const float *__restrict__ pl, 
     lse_out = M + logf(den);
 }
 
+// One owner's side of a row as combine_chunks_kernel reads it: up to MAXC (lse, value) pairs, all loaded at once.
+// A row that was not split (or holds no token) is one pair read from the caller's own A / lse arrays.
+template <int MAXC>
+struct RowLoads {
+    float l[MAXC], x[MAXC];
+    int n;  // pairs held; 0 if the row has more chunks than MAXC (then combine_row takes it)
+};
+
+template <int D, int MAXC>
+__device__ __forceinline__ RowLoads<MAXC> load_row(const RowInfo ri, int G, int g, int64_t row, const float *part_o,
+                                                   const float *part_lse, const float *a, const float *lse)
+{
+    const bool split = ri.n_chunks > 1;
+    const float *pl = split ? part_lse + (int64_t)ri.first_slot * G + g : lse + row;
+    const float *po = split ? part_o + ((int64_t)ri.first_slot * G + g) * D + threadIdx.x : a + row * D + threadIdx.x;
+    RowLoads<MAXC> r;
+    r.n = split ? (ri.n_chunks <= MAXC ? ri.n_chunks : 0) : 1;
+    const int GD = G * D;  // 32-bit offsets: at most MAXC * 16 * 128 floats from the row's first pair
+    // groups of four pairs: a wave-uniform branch per group, unconditional loads inside it (a pair past the end re-reads
+    // the row's first pair; reduce_row ignores it), so the loads leave back to back and few are redundant
+    static_assert(MAXC % 4 == 0, "pairs are loaded in groups of four");
+#pragma unroll
+    for (int c0 = 0; c0 < MAXC; c0 += 4) {
+        if (c0 < r.n) {
+#pragma unroll
+            for (int c = c0; c < c0 + 4; ++c) {
+                const int ce = c < r.n ? c : 0;
+                r.l[c] = pl[ce * G];  // masked where it is used: nothing here waits for a load
+                r.x[c] = po[ce * GD];
+            }
+        } else {
+#pragma unroll
+            for (int c = c0; c < c0 + 4; ++c) {
+                r.l[c] = -INFINITY;
+                r.x[c] = 0.f;
+            }
+        }
+    }
+    return r;
+}
+
+// n-way form over the loaded pairs, same arithmetic and chunk order as combine_row; a single pair passes through
+// unchanged (it may be an empty row: value 0, lse -inf).
+template <int MAXC>
+__device__ __forceinline__ void reduce_row(const RowLoads<MAXC> &r, float &a_out, float &lse_out)
+{
+    if (r.n == 1) {
+        a_out = r.x[0];
+        lse_out = r.l[0];
+        return;
+    }
+    float M = r.l[0];
+#pragma unroll
+    for (int c = 1; c < MAXC; ++c)
+        M = fmaxf(M, c < r.n ? r.l[c] : -INFINITY);
+    float o = 0.f, den = 0.f;
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) {
+        if (c < r.n) {
+            const float w = expf(r.l[c] - M);
+            den += w;
+            o = fmaf(w, r.x[c], o);
+        }
+    }
+    a_out = o / den;
+    lse_out = M + logf(den);
+}
+
 // One workgroup of D threads per (split row, query head).
 template <int D>
 __global__ __launch_bounds__(D) void combine_chunks_kernel(const CombineRow *__restrict__ rows, int Hq, int G,
@@ -101,8 +169,12 @@ __global__ __launch_bounds__(D) void combine_chunks_kernel(const CombineRow *__r
     const int g = blockIdx.x % G;
     const int64_t row = (int64_t)r.user * Hq + (int64_t)r.kv_head * G + g;
     float a, ls;
-    combine_row<D>(part_lse + (int64_t)r.first_slot * G + g,
-                   part_o + ((int64_t)r.first_slot * G + g) * D + threadIdx.x, r.n_chunks, G, sm_w, sm_red, a, ls);
+    constexpr int kSmall = 16;
+    if (r.n_chunks <= kSmall)  // every load at once: one memory round trip
+        reduce_row(load_row<D, kSmall>(RowInfo{r.first_slot, r.n_chunks}, G, g, row, part_o, part_lse, out, lse), a, ls);
+    else
+        combine_row<D>(part_lse + (int64_t)r.first_slot * G + g,
+                       part_o + ((int64_t)r.first_slot * G + g) * D + threadIdx.x, r.n_chunks, G, sm_w, sm_red, a, ls);
     out[row * D + threadIdx.x] = a;
     if (threadIdx.x == 0)
         lse[row] = ls;
@@ -144,11 +216,19 @@ __global__ __launch_bounds__(D) void finalize_step_kernel(const RowInfo *__restr
     const int kvh = h / G, g = h % G;
     const int tid = threadIdx.x;
     const RowInfo ri = rows_in[user * Hkv + kvh], ro = rows_out[user * Hkv + kvh];
-    constexpr int kSmall = 8;
+    // Measured on this kernel (4 us, pure latency): the 8-wide straight-line form is the fastest for rows of up to 8
+    // chunks; loading both owners' pairs in one go, or 16-wide for everything, made it 1.3-2.3 us slower.
+    constexpr int kSmall = 8, kMedium = 16;
     float x0, l0, x1, l1;
     if (ri.n_chunks > 1 && ri.n_chunks <= kSmall) {
         combine_row_small<D, kSmall>(part_lse_in + (int64_t)ri.first_slot * G + g,
                                      part_o_in + ((int64_t)ri.first_slot * G + g) * D + tid, ri.n_chunks, G, x0, l0);
+        a_in[row * D + tid] = x0;
+        if (tid == 0)
+            lse_in[row] = l0;
+    } else if (ri.n_chunks > 1 && ri.n_chunks <= kMedium) {
+        combine_row_small<D, kMedium>(part_lse_in + (int64_t)ri.first_slot * G + g,
+                                      part_o_in + ((int64_t)ri.first_slot * G + g) * D + tid, ri.n_chunks, G, x0, l0);
         a_in[row * D + tid] = x0;
         if (tid == 0)
             lse_in[row] = l0;
