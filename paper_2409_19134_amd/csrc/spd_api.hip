@@ -436,8 +436,11 @@ int launch_partial(spd_ctx *ctx, int which, const CachedSchedule *e0, const spd_
         const size_t lds = hpw ? 0 : sizeof(float) * spd::kWaves * (size_t)G * spd::kOStride;  // cross-wave staging
         const dim3 blk(hpw ? 64u * (unsigned)s->n_kv_heads : (unsigned)spd::kThreads);
         // clearly more pieces than the three-per-CU kernel holds at once (a few left over just start a little
-        // later): use the prefetching two-per-CU kernel.  Head-per-wave workgroups fit one per CU either way.
-        const bool prefetch = hpw || n0 + n1 > (int64_t)std::max(1, ctx->n_cus) * 4;
+        // later): use the prefetching two-per-CU kernel.  Also when all pieces fit two per CU anyway: a wave then
+        // needs half as many dependent memory round trips (short rows taken whole are latency-bound).
+        // Head-per-wave workgroups fit one per CU either way.
+        const int64_t cus = std::max(1, ctx->n_cus);
+        const bool prefetch = hpw || n0 + n1 > cus * 4 || n0 + n1 <= cus * 2;
 #define SPD_LAUNCH_BF16(PAGED, PREFETCH, HPW)                                                                         \
     hipExtLaunchKernelGGL((spd::partial_bf16_d128_kernel<PAGED, PREFETCH, HPW>), grid, blk, (uint32_t)lds, stream,      \
                           ev0, ev1, 0, a0, a1, (int)n0, qh, s->n_q_heads, G, c)
