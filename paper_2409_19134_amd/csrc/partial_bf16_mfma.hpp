@@ -58,7 +58,7 @@ __device__ __forceinline__ PagePair load_pages(const LaneConst &L, int tb, int t
 // Issues the 16 loads of the step at tb.  Paged: P holds that step's page ids on entry and the following step's
 // (tb + step) on return: the lookup is issued behind the data loads, one whole step before it is needed, so that no
 // wave ever waits for a block-table entry before it can ask for data.
-template <bool PAGED>
+template <bool PAGED, bool APPEND>
 __device__ __forceinline__ void load_tile(TileRegs &T, const LaneConst &L, int tb, int t_last, PagePair &P, int step)
 {
     const int gk = tb + (L.r >> 2) * 8;  // first token of the 8-token group this lane's K rows fall in
@@ -72,7 +72,7 @@ __device__ __forceinline__ void load_tile(TileRegs &T, const LaneConst &L, int t
     for (int a = 0; a < 2; ++a) {
         const int t = min(gk + a * 4 + (L.r & 3), t_last);  // rows past the chunk re-read its last token (masked later)
         const char *p = kp + (int64_t)(PAGED ? (t & 15) : t) * L.token_stride + L.grp * 16;
-        if (L.k_new_row && t == t_last)  // the appended token is read from the caller's buffer, not from the cache
+        if (APPEND && L.k_new_row && t == t_last)  // the appended token is read from the caller's buffer, not the cache
             p = L.k_new_row + L.grp * 16;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk)
@@ -82,7 +82,7 @@ __device__ __forceinline__ void load_tile(TileRegs &T, const LaneConst &L, int t
     for (int e = 0; e < 8; ++e) {
         const int t = min(gv + e, t_last);
         const char *p = vp + (int64_t)(PAGED ? (t & 15) : t) * L.token_stride + L.r * 16;
-        if (L.v_new_row && t == t_last)
+        if (APPEND && L.v_new_row && t == t_last)
             p = L.v_new_row + L.r * 16;
         T.v[e] = stream_load16(p);
     }
@@ -163,7 +163,9 @@ constexpr int kOStride = 132;  // LDS row stride (floats) of one head's 128 chan
 // where one workgroup per head would touch every page eight times at different moments.  Each wave owns its head's
 // result, so there is no cross-wave combine, no LDS and no barrier.  Without HPW (head-major storage: one contiguous
 // stream per head) a piece is a token range of one (user, KV head) row and its four waves take interleaved steps.
-template <bool PAGED, bool PREFETCH, bool HPW>
+//
+// APPEND = true adds the KV append (the address substitution costs ~1 % when nothing is appended, hence a flag).
+template <bool PAGED, bool PREFETCH, bool HPW, bool APPEND>
 __global__ __launch_bounds__(HPW ? 512 : kThreads, PREFETCH ? 2 : 3) void partial_bf16_d128_kernel(
     OwnerArgs a0, OwnerArgs a1, int n0, const uint16_t *__restrict__ q, int Hq, int G, float scale_log2e)
 {
@@ -201,7 +203,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, PREFETCH ? 2 : 3) void partia
         L.bt_row = PAGED ? kv.block_table + (int64_t)it.user * kv.max_blocks : nullptr;
         const int t_last = it.t_end - 1;
         L.k_new_row = L.v_new_row = nullptr;
-        if (k_new && (it.rot & kEndsRow)) {
+        if (APPEND && k_new && (it.rot & kEndsRow)) {
             // KV append: this segment holds the row's last token, which is the new one.  Wave 0 copies its K and V
             // rows into the cache (lanes 0-15: K, 16-31: V); every reader of that token takes it from the caller's
             // buffer instead, so nothing waits for the copy.
@@ -232,7 +234,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, PREFETCH ? 2 : 3) void partia
         if (PAGED)
             P = load_pages(L, tb, t_last);
         if (PREFETCH && tb < it.t_end)
-            load_tile<PAGED>(T0, L, tb, t_last, P, kStep);
+            load_tile<PAGED, APPEND>(T0, L, tb, t_last, P, kStep);
     };
 
     DevItem it = scalar_load_item(items, second ? (int)blockIdx.x - n0 : (int)blockIdx.x);
@@ -271,7 +273,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, PREFETCH ? 2 : 3) void partia
         if (!PREFETCH) {
             for (; tb < it.t_end; tb += kStep) {
                 TileRegs T;
-                load_tile<PAGED>(T, L, tb, t_last, P, kStep);
+                load_tile<PAGED, APPEND>(T, L, tb, t_last, P, kStep);
                 compute_tile(T, qB, tb, L.grp, it.t_end, scale_log2e, m, l, acc);
             }
         } else if (tb < it.t_end) {  // T0 already holds (the loads of) step tb
@@ -285,7 +287,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, PREFETCH ? 2 : 3) void partia
                     if (HPW)
                         __builtin_amdgcn_s_barrier();
                     if (more1)
-                        load_tile<PAGED>(T1, L, tb1, t_last, P, kStep);
+                        load_tile<PAGED, APPEND>(T1, L, tb1, t_last, P, kStep);
                     compute_tile(T0, qB, tb, L.grp, it.t_end, scale_log2e, m, l, acc);
                     if (!more1)
                         break;
@@ -294,7 +296,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, PREFETCH ? 2 : 3) void partia
                     if (HPW)
                         __builtin_amdgcn_s_barrier();
                     if (more2)
-                        load_tile<PAGED>(T0, L, tb2, t_last, P, kStep);
+                        load_tile<PAGED, APPEND>(T0, L, tb2, t_last, P, kStep);
                     compute_tile(T1, qB, tb1, L.grp, it.t_end, scale_log2e, m, l, acc);
                     if (!more2)
                         break;

@@ -441,9 +441,16 @@ int launch_partial(spd_ctx *ctx, int which, const CachedSchedule *e0, const spd_
         // Head-per-wave workgroups fit one per CU either way.
         const int64_t cus = std::max(1, ctx->n_cus);
         const bool prefetch = hpw || n0 + n1 > cus * 4 || n0 + n1 <= cus * 2;
+#define SPD_LAUNCH_BF16_A(PAGED, PREFETCH, HPW, APPEND)                                                              \
+    hipExtLaunchKernelGGL((spd::partial_bf16_d128_kernel<PAGED, PREFETCH, HPW, APPEND>), grid, blk, (uint32_t)lds,     \
+                          stream, ev0, ev1, 0, a0, a1, (int)n0, qh, s->n_q_heads, G, c)
 #define SPD_LAUNCH_BF16(PAGED, PREFETCH, HPW)                                                                         \
-    hipExtLaunchKernelGGL((spd::partial_bf16_d128_kernel<PAGED, PREFETCH, HPW>), grid, blk, (uint32_t)lds, stream,      \
-                          ev0, ev1, 0, a0, a1, (int)n0, qh, s->n_q_heads, G, c)
+    do {                                                                                                             \
+        if (nt.k)                                                                                                    \
+            SPD_LAUNCH_BF16_A(PAGED, PREFETCH, HPW, true);                                                           \
+        else                                                                                                         \
+            SPD_LAUNCH_BF16_A(PAGED, PREFETCH, HPW, false);                                                          \
+    } while (0)
         if (v0->block_size) {
             if (prefetch)
                 SPD_LAUNCH_BF16(true, true, false);
@@ -457,6 +464,7 @@ int launch_partial(spd_ctx *ctx, int which, const CachedSchedule *e0, const spd_
             else
                 SPD_LAUNCH_BF16(false, false, false);
         }
+#undef SPD_LAUNCH_BF16_A
 #undef SPD_LAUNCH_BF16
     } else if (s->head_dim == 64) {
         launch_f32_g<64>(G, grid, stream, ev0, ev1, a0, a1, (int)n0, q, s->n_q_heads, c);
