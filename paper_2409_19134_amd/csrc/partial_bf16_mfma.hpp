@@ -150,6 +150,11 @@ __device__ __forceinline__ void compute_tile(const TileRegs &T, const bf16x8 (&q
 
 constexpr int kOStride = 132;  // LDS row stride (floats) of one head's 128 channels: bank = 4*r + grp, conflict free
 
+// LDS bytes of the result staging tiles of a workgroup of `waves` waves, and whether the head-per-wave mapping can have
+// them (kernel and launch use the same rule; 64 KB is what a workgroup may ask for without special attributes).
+__host__ __device__ constexpr size_t staging_bytes(int waves, int G) { return sizeof(float) * (size_t)waves * G * kOStride; }
+__host__ __device__ constexpr bool staging_fits(int waves, int G) { return staging_bytes(waves, G) <= 64 * 1024; }
+
 // One workgroup per piece (see DevItem); q: [U][Hq][128] bf16.  A segment that is its row's only one writes out/lse
 // directly; otherwise it writes part_o[slot][G][128] / part_lse[slot][G], which combine_chunks_kernel then reduces.
 //
@@ -182,8 +187,10 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, PREFETCH ? 2 : 3) void partia
     const char *v_new = second ? a1.v_new : a0.v_new;
     __shared__ float sm_m[kWaves][16];
     __shared__ float sm_l[kWaves][16];
-    extern __shared__ float sm_o[];  // [kWaves][G * kOStride], sized by the launch: only G heads are staged
+    extern __shared__ float sm_o[];  // [waves][G * kOStride], sized by the launch: only G heads are staged
     const int o_wave_stride = G * kOStride;
+    // head-per-wave results go through a wave-private tile if the launch gave the room
+    const bool staged = HPW && staging_fits((int)(blockDim.x >> 6), G);
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -320,15 +327,38 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, PREFETCH ? 2 : 3) void partia
             const int kvh = uniform(wave);
             const int64_t head0 = (int64_t)it.user * Hq + (int64_t)kvh * G;
             const int64_t slot = (int64_t)it.slot + (int64_t)kvh * it.n_chunks;
-            if (r < G) {
-                const float inv = 1.f / l;  // l > 0: the segment holds at least one token
-                float *dst = (direct ? out + (head0 + r) * 128 : part_o + (slot * G + r) * 128) + grp * 32;
+            const float inv = 1.f / l;  // l > 0: the segment holds at least one token
+            float *res = direct ? out + head0 * 128 : part_o + slot * G * 128;  // [G][128], contiguous
+            if (staged) {
+                // Through a wave-private LDS tile, so that the wave stores whole rows with consecutive lanes (storing
+                // straight from the accumulator layout puts 16 bytes per lane into 16 different cache lines per
+                // instruction; measured 2-3 % of the kernel on long token-major workloads).
+                float *stage = sm_o + wave * o_wave_stride;
+                if (r < G) {
+                    float *dst = stage + r * kOStride + grp * 32;
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    f32x4 lo = {acc[0][v] * inv, acc[1][v] * inv, acc[2][v] * inv, acc[3][v] * inv};
-                    f32x4 hi = {acc[4][v] * inv, acc[5][v] * inv, acc[6][v] * inv, acc[7][v] * inv};
-                    *reinterpret_cast<f32x4 *>(dst + v * 8) = lo;
-                    *reinterpret_cast<f32x4 *>(dst + v * 8 + 4) = hi;
+                    for (int cc = 0; cc < 8; ++cc)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v)
+                            dst[v * 8 + cc] = acc[cc][v] * inv;  // channel (4*grp + v)*8 + cc
+                }
+                __builtin_amdgcn_wave_barrier();  // same wave: LDS executes its writes before its reads
+                for (int i = lane * 4; i < G * 128; i += 256) {
+                    const f32x4 w = *reinterpret_cast<const f32x4 *>(stage + (i >> 7) * kOStride + (i & 127));
+                    *reinterpret_cast<f32x4 *>(res + i) = w;
+                }
+                __builtin_amdgcn_wave_barrier();
+            }
+            if (r < G) {
+                if (!staged) {
+                    float *dst = res + r * 128 + grp * 32;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        f32x4 lo = {acc[0][v] * inv, acc[1][v] * inv, acc[2][v] * inv, acc[3][v] * inv};
+                        f32x4 hi = {acc[4][v] * inv, acc[5][v] * inv, acc[6][v] * inv, acc[7][v] * inv};
+                        *reinterpret_cast<f32x4 *>(dst + v * 8) = lo;
+                        *reinterpret_cast<f32x4 *>(dst + v * 8 + 4) = hi;
+                    }
                 }
                 if (grp == 0) {
                     const float ls = m * kLn2 + logf(l);

@@ -433,7 +433,9 @@ int launch_partial(spd_ctx *ctx, int which, const CachedSchedule *e0, const spd_
     if (s->dtype == SPD_BF16) {
         const uint16_t *qh = static_cast<const uint16_t *>(q);
         const bool hpw = e0->hpw;  // a two-owner launch needs the same mapping on both sides (checked by the caller)
-        const size_t lds = hpw ? 0 : sizeof(float) * spd::kWaves * (size_t)G * spd::kOStride;  // cross-wave staging
+        const int waves = hpw ? s->n_kv_heads : spd::kWaves;
+        // cross-wave staging; head-per-wave stages its per-wave results too if that fits (the kernel applies the same rule)
+        const size_t lds = (hpw && !spd::staging_fits(waves, G)) ? 0 : spd::staging_bytes(waves, G);
         const dim3 blk(hpw ? 64u * (unsigned)s->n_kv_heads : (unsigned)spd::kThreads);
         // clearly more pieces than the three-per-CU kernel holds at once (a few left over just start a little
         // later): use the prefetching two-per-CU kernel.  Also when all pieces fit two per CU anyway: a wave then
