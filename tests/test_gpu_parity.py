@@ -196,6 +196,26 @@ def test_randomised_cases(ctx, mapping_of, block):
         check_against_oracle(ctx, wl)
 
 
+def test_many_users_with_short_rows(ctx):
+    """Thousands of workgroups that each take a whole short row (or only write an empty one)."""
+    rng = np.random.default_rng(77)
+    U = 1500
+    lp = rng.integers(0, 300, U).tolist()
+    lo = rng.integers(0, 40, U).tolist()
+    wl = workloads.random_case(104, torch.bfloat16, U, 16, 8, 128, lp, lo, device=DEV, layout="hnd_exact")
+    check_against_oracle(ctx, wl)
+
+
+@pytest.mark.parametrize("chunk_max", [None, 128])
+def test_one_very_long_row(ctx, monkeypatch, chunk_max):
+    """A single KV head with a quarter of a million tokens: the row is cut into 512 chunks (one per resident workgroup);
+    with the piece limit forced down to 128 tokens into ~2000, more than one staging pass of the combine holds."""
+    if chunk_max:
+        monkeypatch.setenv("SPD_CHUNK_MAX", str(chunk_max))
+    wl = workloads.random_case(105, torch.bfloat16, 1, 4, 1, 128, [200_003], [70_001], device=DEV, layout="hnd")
+    check_against_oracle(ctx, wl)
+
+
 @pytest.mark.parametrize("d,Hq,Hkv", [(64, 8, 8), (64, 8, 2), (128, 8, 1), (128, 4, 4), (64, 16, 2)])
 @pytest.mark.parametrize("paged", [False, True])
 def test_fp32_shapes(ctx, d, Hq, Hkv, paged):
