@@ -166,3 +166,23 @@ def test_schedule_fills_the_machine_for_the_headline_workload():
     sh = spd.make_shape(spd.SPD_BF16, 32, 8, 128, 0.1)
     items, chunk = spd.spd_build_schedule(sh, lp, 256)
     assert len({it["piece"] for it in items}) == 512      # the 2 workgroups per CU that are resident at once
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU only: the benchmark says so instead of starting ranks."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert res.returncode != 0
+    assert "one GPU" in res.stderr
+
+
+def test_product_package_does_not_reach_the_oracle():
+    """The oracle is test infrastructure: nothing under the package imports or loads it."""
+    pkg = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "paper_2409_19134_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hpp", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower() or f == "build.py", f"{f} mentions the oracle"
