@@ -15,8 +15,8 @@ constexpr int kChunkMin = 128;       // one 32-token step for each of the four w
 constexpr int kChunkMaxDefault = 16384;    // tokens per piece when the work exceeds one resident wave: a new
                                             // workgroup costs a few microseconds of an idle slot, more than the longer
                                             // tail of bigger pieces (4096: 3 % slower on the longest workload)
-constexpr int kNoSplitMaxDefault = 768;     // rows this short are never split: the work is latency-bound and a
-                                            // whole row per workgroup saves the combine launch
+constexpr int kNoSplitMaxDefault = 768;     // if no row is longer than this the work is latency-bound: every row
+                                            // is cut into chunks of one step per wave
 constexpr int kTargetWgPerCuDefault = 2;   // workgroups of the MFMA kernel resident per CU (2 waves per SIMD)
 constexpr int kHeadPerWaveMinSteps = 8;    // 32-token steps per CU from which the head-per-wave mapping is used
 
@@ -35,9 +35,9 @@ inline int env_int(const char *name, int dflt)
 // The pieces of a group are adjacent in launch order, so with token-major storage the heads that share DRAM pages
 // stream them at the same time.  A group that crosses a user boundary gives pieces with several segments.
 // Equal pieces matter because the path is HBM-bound: a launch lasts as long as its longest workgroup.
-//   - if no user is longer than a few hundred tokens the work is latency-bound: a standalone call then takes one
-//     whole row per workgroup (nothing to combine afterwards: saves the combine launch), the fused step, whose
-//     closing kernel combines anyway, takes chunks of 128 tokens (one step per wave: one memory round trip);
+//   - if no user is longer than a few hundred tokens the work is latency-bound: every row is cut into chunks of 128
+//     tokens (one step per wave: one memory round trip).  That also holds for a standalone call, although it then
+//     needs the combine launch: whole rows of up to 512 tokens per workgroup measured 2.4 us slower;
 //   - work that fits one resident wave of workgroups (2 per CU) gets exactly that many pieces;
 //   - larger work gets pieces of at most `piece_max` tokens, their number rounded up to a multiple of the resident
 //     wave, and relies on the hardware's dynamic workgroup dispatch.
@@ -52,7 +52,7 @@ struct Schedule {
 // range: one item per cut (kv_head = 0, slot = the slot of head 0) and one resident workgroup per CU.  The same
 // token limit per piece serves both mappings (smaller pieces measured slower here too), although every wave now
 // walks the whole range instead of a quarter of it.
-inline void build_schedule(int Hkv, int n_users, const int32_t *lens, int n_cus, bool fused, bool hpw, Schedule &S)
+inline void build_schedule(int Hkv, int n_users, const int32_t *lens, int n_cus, bool hpw, Schedule &S)
 {
     S.items.clear();
     S.piece_first.assign(1, 0);
@@ -74,8 +74,7 @@ inline void build_schedule(int Hkv, int n_users, const int32_t *lens, int n_cus,
     };
     std::vector<std::vector<Cut>> groups;
     if (max_len <= env_int("SPD_NO_SPLIT_MAX", kNoSplitMaxDefault)) {
-        // steps per chunk (every wave of a head-per-wave piece walks all of them: two round trips with its prefetch)
-        const int64_t per = fused ? spd::kWaves : (int64_t)1 << 40;
+        const int64_t per = spd::kWaves;  // steps per chunk
         for (int u = 0; u < n_users; ++u) {
             const int64_t steps = (lens[u] + kChunkAlign - 1) / kChunkAlign;
             for (int64_t s0 = 0; s0 < steps; s0 += per)

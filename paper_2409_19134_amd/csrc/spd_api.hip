@@ -128,7 +128,7 @@ bool head_per_wave_pays(const spd_ctx *ctx, int64_t steps)
     return steps >= (int64_t)std::max(1, ctx->n_cus) * kHeadPerWaveMinSteps;
 }
 
-void make_key(const spd_shape *s, const spd_kv_view *v, bool fused, bool hpw, std::vector<uint8_t> &key)
+void make_key(const spd_shape *s, const spd_kv_view *v, bool hpw, std::vector<uint8_t> &key)
 {
     key.clear();
     auto put = [&key](const void *p, size_t n) {
@@ -136,7 +136,7 @@ void make_key(const spd_shape *s, const spd_kv_view *v, bool fused, bool hpw, st
         key.insert(key.end(), b, b + n);
     };
     const int32_t head[6] = {s->dtype, s->n_q_heads, s->n_kv_heads, v->n_users, v->block_size,
-                             (fused ? 1 : 0) | (hpw ? 2 : 0)};
+                             hpw ? 1 : 0};
     put(head, sizeof head);
     put(v->lens, sizeof(int32_t) * (size_t)v->n_users);
     // the items carry row base addresses (contiguous mode) or row offsets inside the pools (paged mode): the key holds
@@ -157,11 +157,11 @@ void make_key(const spd_shape *s, const spd_kv_view *v, bool fused, bool hpw, st
 
 // Find or build the device-resident schedule for this view (hpw: pieces for the head-per-wave kernel).  Uploads are
 // enqueued on `stream`.
-int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view *v, bool fused, bool hpw,
+int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view *v, bool hpw,
                  hipStream_t stream, CachedSchedule **out)
 {
     std::vector<uint8_t> key;
-    make_key(s, v, fused, hpw, key);
+    make_key(s, v, hpw, key);
     const uint64_t h = fnv1a(key.data(), key.size());
     ++ctx->tick;
     CachedSchedule *victim = &own.cache[0];
@@ -181,7 +181,7 @@ int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view
         }
     }
     Schedule S;
-    build_schedule(s->n_kv_heads, v->n_users, v->lens, ctx->n_cus, fused, hpw, S);
+    build_schedule(s->n_kv_heads, v->n_users, v->lens, ctx->n_cus, hpw, S);
 
     // device items: the first segment of every piece (index = workgroup id), then one per row without tokens (it only
     // writes A = 0, lse = -inf), then the continuation segments, linked through `next`
@@ -364,7 +364,7 @@ void launch_f32_g(int G, dim3 grid, hipStream_t stream, hipEvent_t ev0, hipEvent
 
 // Validation, schedule lookup and scratch growth of one partial-attention call.
 int prepare_partial(spd_ctx *ctx, int which, const spd_shape *s, const void *q, const spd_kv_view *v, float *out,
-                    float *lse, bool fused, int mapping, hipStream_t stream, CachedSchedule **e)
+                    float *lse, int mapping, hipStream_t stream, CachedSchedule **e)
 {
     const int rc = spd_validate_partial(s, q, v, out, lse);
     if (rc != SPD_OK)
@@ -375,7 +375,7 @@ int prepare_partial(spd_ctx *ctx, int which, const spd_shape *s, const void *q, 
     Owner &own = ctx->owner[which];
     // mapping: 1 = head per wave, 0 = head-major, -1 = whatever suits this view on its own
     const bool hpw = mapping >= 0 ? mapping != 0 : head_per_wave_layout(s, v) && head_per_wave_pays(ctx, total_steps(v));
-    const int rs = get_schedule(ctx, own, s, v, fused, hpw, stream, e);
+    const int rs = get_schedule(ctx, own, s, v, hpw, stream, e);
     if (rs != SPD_OK)
         return rs;
     const int G = s->n_q_heads / s->n_kv_heads;
@@ -527,7 +527,7 @@ int partial_attention(spd_ctx *ctx, int which, const spd_shape *s, const void *q
         rc = validate_new_token(v, nt);
     if (rc != SPD_OK)
         return rc;
-    rc = prepare_partial(ctx, which, s, q, v, out, lse, false, -1, stream, &e);
+    rc = prepare_partial(ctx, which, s, q, v, out, lse, -1, stream, &e);
     if (rc != SPD_OK || !e)
         return rc;
     rc = launch_partial(ctx, which, e, v, out, lse, nullptr, nullptr, nullptr, nullptr, s, q, nt, stream);
@@ -643,7 +643,7 @@ int spd_build_schedule(const spd_shape *shape, int32_t n_users, const int32_t *l
         if (lens[u] < 0)
             return SPD_ERR_LEN;
     Schedule S;
-    build_schedule(shape->n_kv_heads, n_users, lens, n_compute_units, false, false, S);
+    build_schedule(shape->n_kv_heads, n_users, lens, n_compute_units, false, S);
     *n_items = (int64_t)S.items.size();
     if (chunk_tokens)
         *chunk_tokens = S.chunk_tokens;
@@ -757,10 +757,10 @@ int spd_decode_step(spd_ctx *ctx, const spd_shape *shape, const void *q, const s
     // together are bandwidth-bound
     const int hpw = head_per_wave_layout(shape, priv) && head_per_wave_layout(shape, pub) &&
                     head_per_wave_pays(ctx, total_steps(priv) + total_steps(pub));
-    rc = prepare_partial(ctx, 0, shape, q, priv, a_in, lse_in, true, hpw, stream, &ep);
+    rc = prepare_partial(ctx, 0, shape, q, priv, a_in, lse_in, hpw, stream, &ep);
     if (rc != SPD_OK)
         return rc;
-    rc = prepare_partial(ctx, 1, shape, q, pub, a_out, lse_out, true, hpw, stream, &eo);  // an upload, if any, stays on `stream`
+    rc = prepare_partial(ctx, 1, shape, q, pub, a_out, lse_out, hpw, stream, &eo);  // an upload, if any, stays on `stream`
     if (rc != SPD_OK)
         return rc;
     // one grid for both owners, the private owner's long streams first (measured faster than public first): the

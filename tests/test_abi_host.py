@@ -149,8 +149,9 @@ def test_schedule_covers_every_token_once(lens, n_cus):
         for it in items:
             steps[it["piece"]] = steps.get(it["piece"], 0) + -(-(it["t_end"] - it["t_begin"]) // 32)
         assert sorted(steps) == list(range(len(steps)))
-        if max(lens) <= 768:      # short rows are never split: one piece per row
-            assert all(it["n_chunks"] == 1 for it in items)
+        if max(lens) <= 768:      # short rows: chunks of 128 tokens, one per piece
+            assert all(it["t_end"] - it["t_begin"] <= 128 for it in items)
+            assert len(steps) == len(items)
             return
         sizes = [steps[i] for i in range(len(steps))]
         assert max(sizes) * 32 <= max(chunk, 128) and max(sizes) * 32 <= 16384
