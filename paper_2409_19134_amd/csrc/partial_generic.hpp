@@ -89,37 +89,47 @@ __global__ __launch_bounds__(kThreads) void partial_f32_kernel(
                     copy16(const_cast<char *>(v_base) + off, v_new_row + (lane % LPR) * 16);
             }
         }
-        for (int tb = it.t_begin + wave * RPW; tb < it.t_end; tb += RPW * kWaves) {
-            const int t = tb + rs;
-            const int tc = min(t, t_last);
-            int64_t off;
-            if (paged)
-                off = (int64_t)bt_row[tc >> 4] * kv.block_stride + (int64_t)(tc & 15) * kv.token_stride;
-            else
-                off = (int64_t)tc * kv.token_stride;
-            off += cl * 16;
-            const bool is_new = k_new_row && tc == t_last;
-            const f32x4 kk = *reinterpret_cast<const f32x4 *>(is_new ? k_new_row + cl * 16 : k_base + off);
-            const f32x4 vv = *reinterpret_cast<const f32x4 *>(is_new ? v_new_row + cl * 16 : v_base + off);
+        // kUnroll steps of loads are issued before the first is used: the workloads that take this kernel are small and
+        // latency-bound, so what counts is the number of dependent memory round trips per wave
+        constexpr int kUnroll = 4;
+        for (int tb = it.t_begin + wave * RPW; tb < it.t_end; tb += RPW * kWaves * kUnroll) {
+            f32x4 kk[kUnroll], vv[kUnroll];
 #pragma unroll
-            for (int g = 0; g < G; ++g) {
-                float s = qr[g][0] * kk[0];
-                s = fmaf(qr[g][1], kk[1], s);
-                s = fmaf(qr[g][2], kk[2], s);
-                s = fmaf(qr[g][3], kk[3], s);
+            for (int u = 0; u < kUnroll; ++u) {
+                const int tc = min(tb + u * RPW * kWaves + rs, t_last);  // rows past the chunk re-read its last token
+                int64_t off;
+                if (paged)
+                    off = (int64_t)bt_row[tc >> 4] * kv.block_stride + (int64_t)(tc & 15) * kv.token_stride;
+                else
+                    off = (int64_t)tc * kv.token_stride;
+                off += cl * 16;
+                const bool is_new = k_new_row && tc == t_last;
+                kk[u] = *reinterpret_cast<const f32x4 *>(is_new ? k_new_row + cl * 16 : k_base + off);
+                vv[u] = *reinterpret_cast<const f32x4 *>(is_new ? v_new_row + cl * 16 : v_base + off);
+            }
 #pragma unroll
-                for (int o = 1; o < LPR; o <<= 1)
-                    s += __shfl_xor(s, o);          // all LPR lanes of the row end up with the full dot product
-                if (t < it.t_end) {
-                    const float x = s * scale_log2e;
-                    const float m_new = fmaxf(m[g], x);
-                    const float alpha = fast_exp2(m[g] - m_new);
-                    const float p = fast_exp2(x - m_new);
-                    l[g] = l[g] * alpha + p;
+            for (int u = 0; u < kUnroll; ++u) {
+                const int t = tb + u * RPW * kWaves + rs;
 #pragma unroll
-                    for (int e = 0; e < EPL; ++e)
-                        acc[g][e] = fmaf(p, vv[e], acc[g][e] * alpha);
-                    m[g] = m_new;
+                for (int g = 0; g < G; ++g) {
+                    float s = qr[g][0] * kk[u][0];
+                    s = fmaf(qr[g][1], kk[u][1], s);
+                    s = fmaf(qr[g][2], kk[u][2], s);
+                    s = fmaf(qr[g][3], kk[u][3], s);
+#pragma unroll
+                    for (int o = 1; o < LPR; o <<= 1)
+                        s += __shfl_xor(s, o);          // all LPR lanes of the row end up with the full dot product
+                    if (t < it.t_end) {
+                        const float x = s * scale_log2e;
+                        const float m_new = fmaxf(m[g], x);
+                        const float alpha = fast_exp2(m[g] - m_new);
+                        const float p = fast_exp2(x - m_new);
+                        l[g] = l[g] * alpha + p;
+#pragma unroll
+                        for (int e = 0; e < EPL; ++e)
+                            acc[g][e] = fmaf(p, vv[u][e], acc[g][e] * alpha);
+                        m[g] = m_new;
+                    }
                 }
             }
         }
