@@ -70,6 +70,9 @@ def main():
                     help="fused mode only: also append one new token per user to the public cache in the same launch "
                          "(its slot is the cache's last token, rewritten every step)")
     ap.add_argument("--layout", default=None, choices=["hnd", "hnd_exact", "nhd"], help="contiguous KV layout override")
+    ap.add_argument("--pointer-tables", action="store_true",
+                    help="contiguous layouts: also pass the per-user pointers in device arrays (address-independent "
+                         "schedules, shared by the layers of a model; one more dependent scalar load per segment)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true", help="skip the parity check against the oracle")
     ap.add_argument("--cpu-seconds", type=float, default=1.5,
@@ -104,7 +107,7 @@ def main():
             import copy
             w = copy.copy(wl)
             w.private, w.public = clone_side(wl.private), clone_side(wl.public)
-        steps_objs.append(spd.DecodeStep.from_workload(ctx, w))
+        steps_objs.append(spd.DecodeStep.from_workload(ctx, w, device_pointer_tables=args.pointer_tables))
     q = wl.q
 
     stream_ptr = torch.cuda.current_stream().cuda_stream
@@ -201,6 +204,7 @@ def main():
                    "private_tokens": wl.private.n_tokens, "public_tokens": wl.public.n_tokens,
                    "kv_bytes_per_step": kv_bytes, "kv_copies_cycled": copies, "mode": args.mode, "kv_append": bool(args.append),
                    "layout": "paged16" if wl.private.paged else wl.private.layout,
+                   "device_pointer_tables": bool(args.pointer_tables and not wl.private.paged),
                    "seeds": wl.seeds},
         "roofline": {"bound": "hbm",
                      "kernel": ("partial_bf16_d128_kernel" if elt == 2 else "partial_f32_kernel")

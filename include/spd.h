@@ -89,6 +89,11 @@ typedef struct spd_kv_view {
     const int32_t *block_table; /* DEVICE [n_users][max_blocks] (paged mode)                              */
     int32_t max_blocks;
     int64_t block_stride;       /* elements between pages, multiple of 16 bytes                           */
+    const void *const *k_ptrs_dev; /* optional, DEVICE copies [n_users] of k_ptrs / v_ptrs (contiguous mode; both */
+    const void *const *v_ptrs_dev; /* or neither): with them the split schedule does not depend on the buffers'
+                                      addresses - views that differ only in their buffers, such as the layers of
+                                      a model, share one cached schedule - and the kernels read each user's base
+                                      pointer from these arrays.  k_ptrs / v_ptrs are still required (validation) */
 } spd_kv_view;
 
 /* Create a context on HIP device `hip_device` (host call; allocates a small amount of device memory). */
@@ -106,8 +111,9 @@ int spd_last_hip_error(const spd_ctx *ctx);
 /*
  * How often a call had to build and upload a split schedule (`builds`) and how often it found the one it needed among
  * those it remembers (`hits`).  A schedule is determined by the lengths, the storage mode and strides and, in
- * contiguous mode, the per-user base pointers - not by q, the outputs, the block table or the pools; so the layers of
- * a model that share lengths and a block table share one schedule per decode step.
+ * contiguous mode without device pointer arrays, the per-user base pointers - not by q, the outputs, the block table
+ * or the pools; so the layers of a model that share lengths (and a block table, or pass k_ptrs_dev / v_ptrs_dev) share
+ * one schedule per decode step.
  */
 int spd_get_schedule_stats(const spd_ctx *ctx, int64_t *builds, int64_t *hits);
 

@@ -48,7 +48,8 @@ class spd_kv_view(C.Structure):
                 ("k_ptrs", C.POINTER(C.c_void_p)), ("v_ptrs", C.POINTER(C.c_void_p)),
                 ("token_stride", C.c_int64), ("head_stride", C.c_int64), ("head_strides", C.POINTER(C.c_int64)),
                 ("k_pool", C.c_void_p), ("v_pool", C.c_void_p), ("block_size", C.c_int32),
-                ("block_table", C.c_void_p), ("max_blocks", C.c_int32), ("block_stride", C.c_int64)]
+                ("block_table", C.c_void_p), ("max_blocks", C.c_int32), ("block_stride", C.c_int64),
+                ("k_ptrs_dev", C.c_void_p), ("v_ptrs_dev", C.c_void_p)]
 
 
 class spd_work_item(C.Structure):
@@ -120,7 +121,9 @@ class KVView:
                  v: Optional[Sequence[torch.Tensor]] = None, k_pool: Optional[torch.Tensor] = None,
                  v_pool: Optional[torch.Tensor] = None, block_table: Optional[torch.Tensor] = None,
                  block_size: int = 0, block_stride: int = 0, max_blocks: Optional[int] = None,
-                 head_strides=None):
+                 head_strides=None, device_pointer_tables: bool = False):
+        """device_pointer_tables (contiguous mode): also hand the per-user pointers over in device arrays, which makes
+        the split schedule independent of the buffers' addresses (views of different layers then share one)."""
         self.lens = np.ascontiguousarray(lens, dtype=np.int32)
         n = int(self.lens.shape[0])
         self._keep = (k, v, k_pool, v_pool, block_table)
@@ -139,6 +142,11 @@ class KVView:
             self._vp = (C.c_void_p * max(1, n))(*[t.data_ptr() if t.numel() else None for t in v])
             st.k_ptrs = C.cast(self._kp, C.POINTER(C.c_void_p))
             st.v_ptrs = C.cast(self._vp, C.POINTER(C.c_void_p))
+            if device_pointer_tables and n:
+                dev = k[0].device
+                self._kp_dev = torch.tensor([t.data_ptr() if t.numel() else 0 for t in k], dtype=torch.int64, device=dev)
+                self._vp_dev = torch.tensor([t.data_ptr() if t.numel() else 0 for t in v], dtype=torch.int64, device=dev)
+                st.k_ptrs_dev, st.v_ptrs_dev = self._kp_dev.data_ptr(), self._vp_dev.data_ptr()
         else:
             st.k_pool, st.v_pool = k_pool.data_ptr(), v_pool.data_ptr()
             st.block_table = block_table.data_ptr()
@@ -146,13 +154,13 @@ class KVView:
         self.struct = st
 
     @classmethod
-    def from_side(cls, side) -> "KVView":
+    def from_side(cls, side, device_pointer_tables: bool = False) -> "KVView":
         """From a workloads.KVSide (tensors already on the GPU)."""
         if side.paged:
             return cls(side.lens, side.token_stride, side.head_stride, k_pool=side.k_pool, v_pool=side.v_pool,
                        block_table=side.block_table, block_size=16, block_stride=side.block_stride)
         return cls(side.lens, side.token_stride, side.head_stride, k=side.k, v=side.v,
-                   head_strides=getattr(side, "head_strides", None))
+                   head_strides=getattr(side, "head_strides", None), device_pointer_tables=device_pointer_tables)
 
 
 def _stream_ptr(stream) -> Optional[int]:

@@ -109,6 +109,14 @@ __device__ __forceinline__ int scalar_load_i32(const int32_t *p, int idx)
     return ((const_i32_ptr)(uintptr_t)p)[idx];
 }
 
+// A user's base pointer from a device pointer table, as an integer to add to the item's offset (0 without a table).
+// Scalar cache: the table is constant during a launch and the index wave-uniform.
+typedef const uint64_t __attribute__((address_space(4))) *const_u64_ptr;
+__device__ __forceinline__ uintptr_t user_base(const char *const *table, int user)
+{
+    return table ? (uintptr_t)((const_u64_ptr)(uintptr_t)table)[user] : 0;
+}
+
 __device__ __forceinline__ void copy16(char *dst, const char *src)
 {
     *reinterpret_cast<u32x4 *>(dst) = *reinterpret_cast<const u32x4 *>(src);
@@ -135,6 +143,10 @@ struct OwnerArgs {
     const DevItem *items;
     const char *k_pool;  // paged mode: the items' k_base / v_base are byte offsets inside these; else nullptr
     const char *v_pool;
+    // contiguous mode with device pointer tables: the items' k_base / v_base are byte offsets from k_ptrs[user] /
+    // v_ptrs[user] (so that the schedule does not depend on the buffers' addresses); else nullptr
+    const char *const *k_ptrs;
+    const char *const *v_ptrs;
     KvAddr kv;
     float *part_o;    // [slots][G][D] chunk partials of split rows
     float *part_lse;  // [slots][G]

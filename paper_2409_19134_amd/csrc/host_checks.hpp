@@ -66,6 +66,10 @@ inline int validate_view(const spd_shape *s, const spd_kv_view *v)
     if (v->block_size == 0) {
         if (any && (!v->k_ptrs || !v->v_ptrs))
             return SPD_ERR_NULL;
+        if ((v->k_ptrs_dev != nullptr) != (v->v_ptrs_dev != nullptr))  // device pointer tables: both or neither
+            return SPD_ERR_NULL;
+        if ((reinterpret_cast<uintptr_t>(v->k_ptrs_dev) | reinterpret_cast<uintptr_t>(v->v_ptrs_dev)) & 7u)
+            return SPD_ERR_ALIGN;
         for (int u = 0; u < v->n_users; ++u) {
             if (v->lens[u] == 0)
                 continue;

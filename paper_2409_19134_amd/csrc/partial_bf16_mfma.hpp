@@ -179,6 +179,8 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, PREFETCH ? 2 : 3) void partia
     const KvAddr kv = second ? a1.kv : a0.kv;
     const uintptr_t k_pool = reinterpret_cast<uintptr_t>(second ? a1.k_pool : a0.k_pool);  // 0 unless paged
     const uintptr_t v_pool = reinterpret_cast<uintptr_t>(second ? a1.v_pool : a0.v_pool);
+    const char *const *k_ptrs = second ? a1.k_ptrs : a0.k_ptrs;  // null unless the view brought device pointer tables
+    const char *const *v_ptrs = second ? a1.v_ptrs : a0.v_ptrs;
     float *__restrict__ part_o = second ? a1.part_o : a0.part_o;
     float *__restrict__ part_lse = second ? a1.part_lse : a0.part_lse;
     float *__restrict__ out = second ? a1.out : a0.out;
@@ -205,8 +207,8 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, PREFETCH ? 2 : 3) void partia
         L.token_stride = kv.token_stride;
         L.block_stride = kv.block_stride;
         const int kv_head = HPW ? uniform(wave) : it.kv_head;
-        L.k_base = it.k_base + k_pool + (HPW ? (int64_t)kv_head * kv.head_stride : 0);
-        L.v_base = it.v_base + v_pool + (HPW ? (int64_t)kv_head * kv.head_stride : 0);
+        L.k_base = it.k_base + k_pool + (PAGED ? 0 : user_base(k_ptrs, it.user)) + (HPW ? (int64_t)kv_head * kv.head_stride : 0);
+        L.v_base = it.v_base + v_pool + (PAGED ? 0 : user_base(v_ptrs, it.user)) + (HPW ? (int64_t)kv_head * kv.head_stride : 0);
         L.bt_row = PAGED ? kv.block_table + (int64_t)it.user * kv.max_blocks : nullptr;
         const int t_last = it.t_end - 1;
         L.k_new_row = L.v_new_row = nullptr;

@@ -20,6 +20,8 @@ __global__ __launch_bounds__(kThreads) void partial_f32_kernel(
     const KvAddr kv = second ? a1.kv : a0.kv;
     const uintptr_t k_pool = reinterpret_cast<uintptr_t>(second ? a1.k_pool : a0.k_pool);  // 0 unless paged
     const uintptr_t v_pool = reinterpret_cast<uintptr_t>(second ? a1.v_pool : a0.v_pool);
+    const char *const *k_ptrs = second ? a1.k_ptrs : a0.k_ptrs;  // null unless the view brought device pointer tables
+    const char *const *v_ptrs = second ? a1.v_ptrs : a0.v_ptrs;
     float *__restrict__ part_o = second ? a1.part_o : a0.part_o;
     float *__restrict__ part_lse = second ? a1.part_lse : a0.part_lse;
     float *__restrict__ out = second ? a1.out : a0.out;
@@ -48,7 +50,8 @@ __global__ __launch_bounds__(kThreads) void partial_f32_kernel(
         const int rs = lane / LPR;      // which row of the step
 
         const bool paged = kv.block_table != nullptr;
-        const char *k_base = it.k_base + k_pool, *v_base = it.v_base + v_pool;
+        const char *k_base = it.k_base + k_pool + user_base(k_ptrs, it.user);
+        const char *v_base = it.v_base + v_pool + user_base(v_ptrs, it.user);
         const int32_t *bt_row = paged ? kv.block_table + (int64_t)it.user * kv.max_blocks : nullptr;
 
         float qr[G][EPL];

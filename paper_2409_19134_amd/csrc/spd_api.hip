@@ -142,10 +142,12 @@ void make_key(const spd_shape *s, const spd_kv_view *v, bool hpw, std::vector<ui
     // the items carry row base addresses (contiguous mode) or row offsets inside the pools (paged mode): the key holds
     // everything those depend on.  The pools themselves are not part of it, so the layers of a model, which share
     // lengths and block table but have a pool each, share one schedule.
+    const int32_t tables = (v->block_size == 0 && v->k_ptrs_dev) ? 1 : 0;  // the items then hold offsets, not addresses
+    put(&tables, sizeof tables);
     put(&v->head_stride, sizeof v->head_stride);
     if (v->head_strides && v->block_size == 0)
         put(v->head_strides, sizeof(int64_t) * (size_t)v->n_users);
-    if (v->block_size == 0) {
+    if (v->block_size == 0 && !tables) {
         for (int u = 0; u < v->n_users; ++u) {  // pointers of empty users are never read: normalise them
             const void *kp = v->lens[u] ? v->k_ptrs[u] : nullptr;
             const void *vp = v->lens[u] ? v->v_ptrs[u] : nullptr;
@@ -195,7 +197,7 @@ int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view
     std::vector<DevItem> dev_items((size_t)n_groups);
     dev_items.reserve((size_t)n_groups + S.items.size());
     auto row_base = [&](int u, int h, bool is_v) -> const char * {
-        const char *base = v->block_size ? nullptr  // paged: an offset, the kernel adds the pool
+        const char *base = (v->block_size || v->k_ptrs_dev) ? nullptr  // an offset: the kernel adds the pool / the user's pointer
                                          : static_cast<const char *>(is_v ? v->v_ptrs[u] : v->k_ptrs[u]);
         const int64_t hs = (v->head_strides && v->block_size == 0) ? v->head_strides[u] : v->head_stride;
         return base + (hpw ? 0 : (int64_t)h * hs * es);  // head-per-wave: every wave adds its own head's offset
@@ -390,6 +392,8 @@ OwnerArgs owner_args(const Owner &own, const CachedSchedule *e, const spd_shape 
     a.items = reinterpret_cast<const DevItem *>(e->dev);
     a.k_pool = v->block_size ? static_cast<const char *>(v->k_pool) : nullptr;
     a.v_pool = v->block_size ? static_cast<const char *>(v->v_pool) : nullptr;
+    a.k_ptrs = v->block_size ? nullptr : reinterpret_cast<const char *const *>(v->k_ptrs_dev);
+    a.v_ptrs = v->block_size ? nullptr : reinterpret_cast<const char *const *>(v->v_ptrs_dev);
     a.kv.block_table = v->block_size ? v->block_table : nullptr;
     a.kv.max_blocks = v->max_blocks;
     a.kv.block_stride = v->block_stride * es;

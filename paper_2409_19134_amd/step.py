@@ -27,9 +27,10 @@ class DecodeStep:
         self.w_in = torch.empty((n, n_q_heads), **f32)
 
     @classmethod
-    def from_workload(cls, ctx: Context, wl) -> "DecodeStep":
+    def from_workload(cls, ctx: Context, wl, device_pointer_tables: bool = False) -> "DecodeStep":
         return cls(ctx, wl.dtype, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.scale,
-                   KVView.from_side(wl.private), KVView.from_side(wl.public), device=wl.q.device)
+                   KVView.from_side(wl.private, device_pointer_tables), KVView.from_side(wl.public, device_pointer_tables),
+                   device=wl.q.device)
 
     def run(self, q: torch.Tensor, stream=None):
         """Enqueue the three calls on `stream` (default: torch's current stream).  No synchronisation."""

@@ -187,3 +187,24 @@ def test_product_package_does_not_reach_the_oracle():
             if f.endswith((".py", ".hpp", ".hip", ".h")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in text.lower() or f == "build.py", f"{f} mentions the oracle"
+
+
+def test_device_pointer_tables_come_in_pairs_and_aligned():
+    sh = spd.make_shape(spd.SPD_BF16, 8, 8, 128, 0.1)
+    lens = np.asarray([5], dtype=np.int32)
+    kp = (C.c_void_p * 1)(0x1000)
+    st = spd.spd_kv_view()
+    st.n_users, st.lens = 1, lens.ctypes.data_as(C.POINTER(C.c_int32))
+    st.k_ptrs = C.cast(kp, C.POINTER(C.c_void_p))
+    st.v_ptrs = C.cast(kp, C.POINTER(C.c_void_p))
+    st.token_stride, st.head_stride = 1024, 128
+    q = C.c_void_p(0x2000)
+    out = C.c_void_p(0x3000)
+    args = (C.byref(sh), q, C.byref(st), out, out)
+    assert spd.lib.spd_validate_partial(*args) == spd.SPD_OK
+    st.k_ptrs_dev = 0x4000
+    assert spd.lib.spd_validate_partial(*args) == spd.SPD_ERR_NULL        # one table without the other
+    st.v_ptrs_dev = 0x5004
+    assert spd.lib.spd_validate_partial(*args) == spd.SPD_ERR_ALIGN       # pointers are 8 bytes
+    st.v_ptrs_dev = 0x5008
+    assert spd.lib.spd_validate_partial(*args) == spd.SPD_OK

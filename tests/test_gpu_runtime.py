@@ -201,6 +201,59 @@ def test_layers_share_one_schedule_per_step_in_paged_mode():
     ctx.close()
 
 
+@pytest.mark.parametrize("layout", ["hnd", "nhd", "hnd_exact"])
+def test_layers_share_one_schedule_with_device_pointer_tables(layout):
+    """Contiguous per-user buffers: with the pointers also handed over in device arrays the schedule does not depend
+    on the buffers' addresses, so the layers of a model (a set of buffers each, same lengths) share one per owner and
+    decode step.  Without the tables every layer builds its own.  Three steps over four layers, appending a token."""
+    import paper_2409_19134_amd as spd
+    ctx = spd.Context(0)
+    U, Hq, Hkv, d, n_layers, n_steps = 3, 32, 8, 128, 4, 3
+    lp, lo0 = [700, 40, 2100], [30, 1, 200]
+    cap = [x + n_steps for x in lo0]          # room for the tokens that will be appended
+    layers = [workloads.random_case(520 + i, torch.bfloat16, U, Hq, Hkv, d, lp, cap, device=DEV, layout=layout)
+              for i in range(n_layers)]
+    g = torch.Generator(device=DEV).manual_seed(8)
+    for tables in (True, False):
+        builds0, hits0 = ctx.spd_get_schedule_stats()
+        for s in range(n_steps):
+            lens_now = np.asarray([x + s + 1 for x in lo0], dtype=np.int32)
+            outs = []
+            for w in layers:
+                w.public.lens = lens_now
+                if layout == "hnd_exact":      # the buffers keep the head stride they were allocated with
+                    w.public.head_strides = np.asarray(cap, dtype=np.int64) * d
+                q = torch.randn((U, Hq, d), generator=g, device=DEV).to(torch.bfloat16)
+                kn = torch.randn((U, Hkv, d), generator=g, device=DEV).to(torch.bfloat16)
+                vn = torch.randn((U, Hkv, d), generator=g, device=DEV).to(torch.bfloat16)
+                w.q = q
+                step = spd.DecodeStep.from_workload(ctx, w, device_pointer_tables=tables)
+                step.run_fused(q, k_new=kn, v_new=vn)
+                outs.append(step)
+            torch.cuda.synchronize()
+            for w, step in zip(layers, outs):
+                assert _err(step, _oracle_y(w)) <= 2e-3
+        builds, hits = ctx.spd_get_schedule_stats()
+        if tables:   # private: one build in all; public: one per step
+            assert builds - builds0 == 1 + n_steps
+            assert hits - hits0 == 2 * n_layers * n_steps - (1 + n_steps)
+        else:        # private: one per layer; public: one per layer and step
+            assert builds - builds0 == n_layers + n_layers * n_steps
+    ctx.close()
+
+
+def test_device_pointer_tables_three_call_path_and_fp32():
+    import paper_2409_19134_amd as spd
+    ctx = spd.Context(0)
+    for dtype, Hq, Hkv, d in ((torch.bfloat16, 16, 4, 128), (torch.float32, 8, 2, 64)):
+        wl = workloads.random_case(530, dtype, 4, Hq, Hkv, d, [3000, 0, 65, 900], [5, 700, 0, 128], device=DEV, layout="hnd")
+        step = spd.DecodeStep.from_workload(ctx, wl, device_pointer_tables=True)
+        step.run(wl.q)
+        torch.cuda.synchronize()
+        assert _err(step, _oracle_y(wl)) <= (2e-3 if dtype == torch.bfloat16 else 1e-5)
+    ctx.close()
+
+
 def test_attention_mass_track_against_oracle():
     """Seeded masses (some exactly on the threshold, zeros, ones) folded step by step; then the masses of real decode
     steps with KV append, against the oracle's w_in."""
