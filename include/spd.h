@@ -27,7 +27,8 @@
  *     lse = -inf for that user's rows; this is legal, not an error.
  *   - Return value: SPD_OK or a negative error code; on any validation error nothing is launched.
  *   - Calls on one context that use the same entry point must not overlap in time (they share scratch memory);
- *     the private and the public call may run concurrently on two streams.
+ *     the private and the public call may run concurrently on two streams.  A context is not thread-safe: its
+ *     calls must come from one host thread at a time (use a context per thread).
  */
 #ifndef SPD_H
 #define SPD_H
