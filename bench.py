@@ -177,8 +177,12 @@ def main():
     run(K)
     torch.cuda.synchronize()
     t3 = time.perf_counter()
-    n_priv, priv_mean_us, priv_min_us = ctx.spd_get_kernel_timing(0)
-    n_pub, pub_mean_us, pub_min_us = ctx.spd_get_kernel_timing(1)
+    def stats(samples):
+        a = np.asarray(samples, dtype=np.float64)
+        return (len(a), float(a.mean()), float(a.min()), [float(np.percentile(a, p)) for p in (10, 50, 90)]) if len(a) \
+            else (0, 0.0, 0.0, [0.0, 0.0, 0.0])
+    n_priv, priv_mean_us, priv_min_us, priv_pct = stats(ctx.spd_get_kernel_timing_samples(0))
+    n_pub, pub_mean_us, pub_min_us, _ = stats(ctx.spd_get_kernel_timing_samples(1))
     ctx.spd_set_kernel_timing(0)
     ms_per_step_timed = (t3 - t2) * 1e3 / K
     # fused mode: one launch streams both owners' caches; calls mode: the private call's kernel is the dominant one
@@ -215,6 +219,7 @@ def main():
                                 if fused else None,
                      "bytes_per_launch": launch_bytes, "launches_timed": n_priv,
                      "mean_us": round(priv_mean_us, 2), "min_us": round(priv_min_us, 2),
+                     "p10_p50_p90_us": [round(v, 2) for v in priv_pct],
                      "public_kernel": ({"bytes_per_launch": pub_bytes, "mean_us": round(pub_mean_us, 2),
                                         "GBps": round(pub_bytes / (pub_mean_us * 1e-6) / 1e9, 1)} if n_pub else None),
                      "us_per_step_while_timed": round(ms_per_step_timed * 1e3, 2)},

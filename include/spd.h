@@ -202,6 +202,9 @@ int spd_attention_mass_track(spd_ctx *ctx, int32_t n_rows, const float *w_in, fl
  */
 int spd_set_kernel_timing(spd_ctx *ctx, int32_t max_launches);
 int spd_get_kernel_timing(spd_ctx *ctx, int32_t entry_point, int32_t *n_launches, double *mean_us, double *min_us);
+/* The same, handing out every recorded duration (microseconds, in launch order) instead of their mean and minimum:
+ * the first min(*n_launches, capacity) of them are written to us (HOST [capacity]); also clears the record. */
+int spd_get_kernel_timing_samples(spd_ctx *ctx, int32_t entry_point, int32_t capacity, float *us, int32_t *n_launches);
 
 /* ------------------------------------------------------------------------------------------------------------
  * Host-only helpers (no GPU needed): the argument checks and the split schedule the calls above use.

@@ -25,7 +25,7 @@ EXPORTED_SYMBOLS = (
     "spd_partial_attn_private", "spd_partial_attn_public_batched", "spd_lse_merge",
     "spd_validate_partial", "spd_build_schedule", "spd_set_kernel_timing", "spd_get_kernel_timing",
     "spd_decode_step", "spd_partial_attn_public_batched_append", "spd_get_schedule_stats",
-    "spd_attention_mass_track",
+    "spd_attention_mass_track", "spd_get_kernel_timing_samples",
 )
 
 
@@ -92,6 +92,8 @@ def _load() -> C.CDLL:
     lib.spd_get_kernel_timing.restype = C.c_int
     lib.spd_get_kernel_timing.argtypes = [vp, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_double),
                                           C.POINTER(C.c_double)]
+    lib.spd_get_kernel_timing_samples.restype = C.c_int
+    lib.spd_get_kernel_timing_samples.argtypes = [vp, C.c_int32, C.c_int32, C.POINTER(C.c_float), C.POINTER(C.c_int32)]
     lib.spd_validate_partial.restype = C.c_int
     lib.spd_validate_partial.argtypes = [C.POINTER(spd_shape), vp, C.POINTER(spd_kv_view), fp, fp]
     lib.spd_build_schedule.restype = C.c_int
@@ -214,6 +216,14 @@ class Context:
         b, h = C.c_int64(0), C.c_int64(0)
         self._check(lib.spd_get_schedule_stats(self.handle, C.byref(b), C.byref(h)), "spd_get_schedule_stats")
         return int(b.value), int(h.value)
+
+    def spd_get_kernel_timing_samples(self, entry_point: int, capacity: int = 1 << 16):
+        """Durations (us) of the recorded launches of one entry point, in launch order; clears the record."""
+        buf = (C.c_float * max(1, capacity))()
+        n = C.c_int32(0)
+        self._check(lib.spd_get_kernel_timing_samples(self.handle, int(entry_point), int(capacity), buf, C.byref(n)),
+                    "spd_get_kernel_timing_samples")
+        return [float(buf[i]) for i in range(min(int(n.value), capacity))]
 
     def spd_set_kernel_timing(self, max_launches: int):
         self._check(lib.spd_set_kernel_timing(self.handle, int(max_launches)), "spd_set_kernel_timing")

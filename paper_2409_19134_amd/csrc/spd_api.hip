@@ -681,25 +681,44 @@ int spd_set_kernel_timing(spd_ctx *ctx, int32_t max_launches)
     return SPD_OK;
 }
 
+int spd_get_kernel_timing_samples(spd_ctx *ctx, int32_t entry_point, int32_t capacity, float *us, int32_t *n_launches)
+{
+    if (!ctx || !n_launches || (capacity > 0 && !us))
+        return SPD_ERR_NULL;
+    if (entry_point != 0 && entry_point != 1)
+        return SPD_ERR_SHAPE;
+    if (capacity < 0)
+        return SPD_ERR_LEN;
+    Owner &own = ctx->owner[entry_point];
+    for (int i = 0; i < own.ev_used; ++i) {
+        SPD_HIP(ctx, hipEventSynchronize(own.ev_stop[i]));
+        float ms = 0.f;
+        SPD_HIP(ctx, hipEventElapsedTime(&ms, own.ev_start[i], own.ev_stop[i]));
+        if (i < capacity)
+            us[i] = 1e3f * ms;
+    }
+    *n_launches = own.ev_used;
+    own.ev_used = 0;
+    return SPD_OK;
+}
+
 int spd_get_kernel_timing(spd_ctx *ctx, int32_t entry_point, int32_t *n_launches, double *mean_us, double *min_us)
 {
     if (!ctx || !n_launches || !mean_us || !min_us)
         return SPD_ERR_NULL;
     if (entry_point != 0 && entry_point != 1)
         return SPD_ERR_SHAPE;
-    Owner &own = ctx->owner[entry_point];
+    std::vector<float> us((size_t)ctx->owner[entry_point].ev_used);
+    const int rc = spd_get_kernel_timing_samples(ctx, entry_point, (int32_t)us.size(), us.data(), n_launches);
+    if (rc != SPD_OK)
+        return rc;
     double sum = 0.0, mn = 0.0;
-    for (int i = 0; i < own.ev_used; ++i) {
-        SPD_HIP(ctx, hipEventSynchronize(own.ev_stop[i]));
-        float ms = 0.f;
-        SPD_HIP(ctx, hipEventElapsedTime(&ms, own.ev_start[i], own.ev_stop[i]));
-        sum += ms;
-        mn = (i == 0 || ms < mn) ? ms : mn;
+    for (size_t i = 0; i < us.size(); ++i) {
+        sum += us[i];
+        mn = (i == 0 || us[i] < mn) ? us[i] : mn;
     }
-    *n_launches = own.ev_used;
-    *mean_us = own.ev_used ? 1e3 * sum / own.ev_used : 0.0;
-    *min_us = 1e3 * mn;
-    own.ev_used = 0;
+    *mean_us = us.empty() ? 0.0 : sum / (double)us.size();
+    *min_us = mn;
     return SPD_OK;
 }
 

@@ -123,6 +123,15 @@ def test_kernel_timing_counts_launches():
     n1, mean1, min1 = ctx.spd_get_kernel_timing(1)
     assert (n0, n1) == (3, 3) and 0 < min0 <= mean0 < 1e4 and 0 < min1 <= mean1 < 1e4
     assert ctx.spd_get_kernel_timing(0)[0] == 0      # reading clears
+    ctx.spd_set_kernel_timing(4)
+    for _ in range(2):
+        step.run_fused(wl.q)        # the two-owner launch is booked under entry point 0
+    samples = ctx.spd_get_kernel_timing_samples(0)
+    assert len(samples) == 2 and all(0 < s < 1e4 for s in samples)
+    assert ctx.spd_get_kernel_timing_samples(1) == [] and ctx.spd_get_kernel_timing_samples(0) == []
+    for _ in range(2):
+        step.run_fused(wl.q)
+    assert len(ctx.spd_get_kernel_timing_samples(0, capacity=1)) == 1      # more recorded than asked for
     ctx.spd_set_kernel_timing(0)
     step.run_fused(wl.q)
     torch.cuda.synchronize()
