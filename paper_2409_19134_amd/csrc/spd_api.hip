@@ -29,13 +29,20 @@ using namespace spd::host;
 
 constexpr int kCacheEntries = 16;    // remembered schedules per entry point
 
-uint64_t fnv1a(const uint8_t *p, size_t n)
+// Hash of a schedule key, eight bytes at a time (keys grow with the number of users and are hashed on every call).
+// Only a filter: a hit is confirmed by comparing the keys themselves.
+uint64_t hash_key(const uint8_t *p, size_t n)
 {
-    uint64_t h = 1469598103934665603ull;
-    for (size_t i = 0; i < n; ++i) {
-        h ^= p[i];
-        h *= 1099511628211ull;
+    uint64_t h = 1469598103934665603ull ^ n;
+    size_t i = 0;
+    for (; i + 8 <= n; i += 8) {
+        uint64_t w;
+        std::memcpy(&w, p + i, 8);
+        h = (h ^ w) * 0x9E3779B97F4A7C15ull;
+        h ^= h >> 29;
     }
+    for (; i < n; ++i)
+        h = (h ^ p[i]) * 1099511628211ull;
     return h;
 }
 
@@ -74,6 +81,7 @@ struct spd_ctx {
     uint64_t tick = 0;
     int64_t schedule_builds = 0, schedule_hits = 0;
     bool timing = false;
+    std::vector<uint8_t> key_scratch;
     Owner owner[2];
 };
 
@@ -162,9 +170,9 @@ void make_key(const spd_shape *s, const spd_kv_view *v, bool hpw, std::vector<ui
 int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view *v, bool hpw,
                  hipStream_t stream, CachedSchedule **out)
 {
-    std::vector<uint8_t> key;
+    std::vector<uint8_t> &key = ctx->key_scratch;  // reused from call to call: no allocation on the hit path
     make_key(s, v, hpw, key);
-    const uint64_t h = fnv1a(key.data(), key.size());
+    const uint64_t h = hash_key(key.data(), key.size());
     ++ctx->tick;
     CachedSchedule *victim = &own.cache[0];
     for (auto &e : own.cache) {
@@ -302,7 +310,7 @@ int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view
     e.last_stream = stream;
     e.valid = true;
     e.hash = h;
-    e.key.swap(key);
+    e.key = key;
     e.last_use = ctx->tick;
     e.n_items = n_groups;
     e.hpw = hpw;
