@@ -158,16 +158,18 @@ __host__ __device__ constexpr bool staging_fits(int waves, int G) { return stagi
 // One workgroup per piece (see DevItem); q: [U][Hq][128] bf16.  A segment that is its row's only one writes out/lse
 // directly; otherwise it writes part_o[slot][G][128] / part_lse[slot][G], which combine_chunks_kernel then reduces.
 //
-// PREFETCH = true keeps two 32-token steps of loads in flight per wave (~245 VGPRs, two waves per SIMD): best when a
-// launch runs many waves of workgroups.  PREFETCH = false holds one step (~165 VGPRs, three waves per SIMD): as fast
-// when the whole launch is one resident wave, and it leaves room on every CU for the other owner's pieces.
+// PREFETCH = true keeps two 32-token steps of loads in flight per wave (~245 VGPRs, two waves per SIMD): for launches
+// that run several rounds of workgroups, and for small ones that fit two per CU anyway (half as many dependent round
+// trips per wave).  PREFETCH = false holds one step (~160 VGPRs, three waves per SIMD): as fast when the private
+// owner's pieces are one resident round, and it leaves room on every CU for the other owner's pieces.
 //
 // HPW ("head per wave") is the mapping for contiguous token-major storage, where the KV heads of a token are adjacent
 // in memory ([token][head][d]).  A piece is then a token range of a *user* (all KV heads), the workgroup
 // has one wave per KV head, and all waves walk the same tokens: together they read whole, consecutive DRAM pages,
-// where one workgroup per head would touch every page eight times at different moments.  Each wave owns its head's
-// result, so there is no cross-wave combine, no LDS and no barrier.  Without HPW (head-major storage: one contiguous
-// stream per head) a piece is a token range of one (user, KV head) row and its four waves take interleaved steps.
+// where one workgroup per head would touch every page eight times at different moments (a barrier per step keeps
+// the waves together).  Each wave owns its head's result, so there is no cross-wave combine; the wave stores its
+// result through an LDS tile of its own.  Without HPW (head-major storage: one contiguous stream per head) a piece is
+// a token range of one (user, KV head) row and its four waves take interleaved steps.
 //
 // APPEND = true adds the KV append (the address substitution costs ~1 % when nothing is appended, hence a flag).
 template <bool PAGED, bool PREFETCH, bool HPW, bool APPEND>
