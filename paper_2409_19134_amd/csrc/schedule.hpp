@@ -90,11 +90,11 @@ inline void build_schedule(int Hkv, int n_users, const int32_t *lens, int n_cus,
         std::vector<int64_t> ends;
         if (T <= wg * piece_max) {
             // at least one step per wave
+            // (measured on the headline workload: fewer, round-aligned pieces or more pieces than fit at once are
+            // both slower - 55 groups of 20 steps +2 us, 80 groups +1.5 us against 64 groups of 17-18 steps)
             const int64_t W = std::min<int64_t>(wg, hpw ? T : (T + spd::kWaves - 1) / spd::kWaves);
-            // EXPERIMENT: the workgroups dispatched first (first half of the pieces) get `bonus` steps more each
-            const int64_t bonus = (W == wg && W % 2 == 0 && T / W >= 16) ? env_int("SPD_FIRST_HALF_BONUS", 0) : 0;
             for (int64_t i = 0; i < W; ++i)
-                ends.push_back(T * (i + 1) / W + bonus * std::min<int64_t>(i + 1, W - i - 1));
+                ends.push_back(T * (i + 1) / W);
         } else {
             // several resident waves of equal pieces; the hardware hands them out in launch order.  (Cutting the last
             // wave's share finer to shorten the tail was measured and lost 1-3 %: short pieces cost more than the tail.)
