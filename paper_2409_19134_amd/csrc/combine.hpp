@@ -19,6 +19,11 @@ namespace spd {
 
 constexpr int kCombineStage = 512;  // chunk weights staged in LDS per pass
 
+// e^x through the hardware's 2^x (one instruction after the scaling; the library expf is a dozen, and these kernels
+// are a few microseconds of pure latency in which every thread computes the same few weights).  fast_exp(0) is
+// exactly 1 and fast_exp(-inf) exactly 0, which the merge relies on.
+__device__ __forceinline__ float fast_exp(float x) { return fast_exp2(x * kLog2e); }
+
 // n-way form for one (row, query head), executed by a workgroup of D threads (thread = channel): returns this
 // thread's channel of A = sum_c exp(lse_c - lse) A_c and lse = logsumexp_c lse_c.  The chunk weights are staged in
 // LDS by all threads in parallel, then every thread streams its channel of the chunks' partial vectors with
@@ -46,7 +51,7 @@ __device__ __forceinline__ void combine_row(const float *__restrict__ pl, const 
         const int nc = min(kCombineStage, n_chunks - c0);
         __syncthreads();
         for (int c = tid; c < nc; c += D)
-            sm_w[c] = expf(pl[(int64_t)(c0 + c) * G] - M);
+            sm_w[c] = fast_exp(pl[(int64_t)(c0 + c) * G] - M);
         __syncthreads();
 #pragma unroll 8
         for (int c = 0; c < nc; ++c) {
@@ -79,7 +84,7 @@ __device__ __forceinline__ void combine_row_small(const float *__restrict__ pl, 
 #pragma unroll
     for (int c = 0; c < MAXC; ++c) {
         if (c < n_chunks) {
-            const float w = expf(l[c] - M);
+            const float w = fast_exp(l[c] - M);
             den += w;
             o = fmaf(w, x[c], o);
         }
@@ -147,7 +152,7 @@ __device__ __forceinline__ void reduce_row(const RowLoads<MAXC> &r, float &a_out
 #pragma unroll
     for (int c = 0; c < MAXC; ++c) {
         if (c < r.n) {
-            const float w = expf(r.l[c] - M);
+            const float w = fast_exp(r.l[c] - M);
             den += w;
             o = fmaf(w, r.x[c], o);
         }
@@ -188,7 +193,7 @@ __device__ __forceinline__ void merge_weights(float l0, float l1, float &w0, flo
         w0 = 0.f, w1 = 0.f, ls = -INFINITY;
         return;
     }
-    const float e0 = expf(l0 - M), e1 = expf(l1 - M);  // the larger one is exactly 1
+    const float e0 = fast_exp(l0 - M), e1 = fast_exp(l1 - M);  // the larger one is exactly 1
     const float den = e0 + e1;
     w0 = e0 / den;
     w1 = e1 / den;
