@@ -23,6 +23,9 @@ constexpr int kCombineStage = 512;  // chunk weights staged in LDS per pass
 // are a few microseconds of pure latency in which every thread computes the same few weights).  fast_exp(0) is
 // exactly 1 and fast_exp(-inf) exactly 0, which the merge relies on.
 __device__ __forceinline__ float fast_exp(float x) { return fast_exp2(x * kLog2e); }
+// 1/x and ln x through the hardware's reciprocal and log2 (1 ulp each), for the same reason
+__device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
+__device__ __forceinline__ float fast_log(float x) { return __builtin_amdgcn_logf(x) * kLn2; }
 
 // n-way form for one (row, query head), executed by a workgroup of D threads (thread = channel): returns this
 // thread's channel of A = sum_c exp(lse_c - lse) A_c and lse = logsumexp_c lse_c.  The chunk weights are staged in
@@ -59,8 +62,8 @@ __device__ __forceinline__ void combine_row(const float *__restrict__ pl, const 
             o = fmaf(sm_w[c], po[(int64_t)(c0 + c) * G * D], o);
         }
     }
-    a_out = o / den;
-    lse_out = M + logf(den);
+    a_out = o * fast_rcp(den);
+    lse_out = M + fast_log(den);
 }
 
 // The same for rows of at most MAXC chunks, without LDS or barriers: every load is issued at once (one memory round
@@ -89,8 +92,8 @@ __device__ __forceinline__ void combine_row_small(const float *__restrict__ pl, 
             o = fmaf(w, x[c], o);
         }
     }
-    a_out = o / den;
-    lse_out = M + logf(den);
+    a_out = o * fast_rcp(den);
+    lse_out = M + fast_log(den);
 }
 
 // One owner's side of a row as combine_chunks_kernel reads it: up to MAXC (lse, value) pairs, all loaded at once.
@@ -157,8 +160,8 @@ __device__ __forceinline__ void reduce_row(const RowLoads<MAXC> &r, float &a_out
             o = fmaf(w, r.x[c], o);
         }
     }
-    a_out = o / den;
-    lse_out = M + logf(den);
+    a_out = o * fast_rcp(den);
+    lse_out = M + fast_log(den);
 }
 
 // One workgroup of D threads per (split row, query head).
@@ -195,9 +198,10 @@ __device__ __forceinline__ void merge_weights(float l0, float l1, float &w0, flo
     }
     const float e0 = fast_exp(l0 - M), e1 = fast_exp(l1 - M);  // the larger one is exactly 1
     const float den = e0 + e1;
-    w0 = e0 / den;
-    w1 = e1 / den;
-    ls = M + logf(den);
+    const float inv = fast_rcp(den);
+    w0 = e0 * inv;
+    w1 = e1 * inv;
+    ls = M + fast_log(den);
 }
 
 // Last kernel of a fused decode step: one workgroup of D threads per (user, query head).  For each owner, a row
