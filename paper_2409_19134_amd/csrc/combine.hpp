@@ -23,9 +23,8 @@ constexpr int kCombineStage = 512;  // chunk weights staged in LDS per pass
 // are a few microseconds of pure latency in which every thread computes the same few weights).  fast_exp(0) is
 // exactly 1 and fast_exp(-inf) exactly 0, which the merge relies on.
 __device__ __forceinline__ float fast_exp(float x) { return fast_exp2(x * kLog2e); }
-// 1/x and ln x through the hardware's reciprocal and log2 (1 ulp each), for the same reason
-__device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
-__device__ __forceinline__ float fast_log(float x) { return __builtin_amdgcn_logf(x) * kLn2; }
+// ln x through the hardware's log2 (1 ulp), for the same reason
+__device__ __forceinline__ float fast_log(float x) { return fast_log2(x) * kLn2; }
 
 // n-way form for one (row, query head), executed by a workgroup of D threads (thread = channel): returns this
 // thread's channel of A = sum_c exp(lse_c - lse) A_c and lse = logsumexp_c lse_c.  The chunk weights are staged in

@@ -123,6 +123,9 @@ __device__ __forceinline__ void copy16(char *dst, const char *src)
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+// hardware log2 and reciprocal (1 ulp): the epilogues are latency, every library call in them is a dozen instructions
+__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+__device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
 
 __device__ __forceinline__ float wave_xor_max(float v, int mask) { return fmaxf(v, __shfl_xor(v, mask)); }
 

@@ -331,7 +331,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, PREFETCH ? 2 : 3) void partia
             const int kvh = uniform(wave);
             const int64_t head0 = (int64_t)it.user * Hq + (int64_t)kvh * G;
             const int64_t slot = (int64_t)it.slot + (int64_t)kvh * it.n_chunks;
-            const float inv = 1.f / l;  // l > 0: the segment holds at least one token
+            const float inv = fast_rcp(l);  // l > 0: the segment holds at least one token
             float *res = direct ? out + head0 * 128 : part_o + slot * G * 128;  // [G][128], contiguous
             if (staged) {
                 // Through a wave-private LDS tile, so that the wave stores whole rows with consecutive lanes (storing
@@ -365,7 +365,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, PREFETCH ? 2 : 3) void partia
                     }
                 }
                 if (grp == 0) {
-                    const float ls = m * kLn2 + logf(l);
+                    const float ls = (m + fast_log2(l)) * kLn2;  // m is in log2 units
                     if (direct)
                         lse[head0 + r] = ls;
                     else
@@ -414,13 +414,13 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, PREFETCH ? 2 : 3) void partia
                 o += sm_o[w * o_wave_stride + g * kOStride + ch];
                 lt += sm_l[w][g] * fast_exp2(sm_m[w][g] - Mg);
             }
-            const float a = o / lt;
+            const float a = o * fast_rcp(lt);
             if (direct)
                 out[(head0 + g) * 128 + ch] = a;
             else
                 part_o[((int64_t)it.slot * G + g) * 128 + ch] = a;
             if (ch == 0) {
-                const float ls = Mg * kLn2 + logf(lt);
+                const float ls = (Mg + fast_log2(lt)) * kLn2;  // Mg is in log2 units
                 if (direct)
                     lse[head0 + g] = ls;
                 else

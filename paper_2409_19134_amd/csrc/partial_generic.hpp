@@ -185,13 +185,13 @@ __global__ __launch_bounds__(kThreads) void partial_f32_kernel(
                 o += sm_o[w][g][ch] * f;
                 lt += sm_l[w][g] * f;
             }
-            const float a = o / lt;
+            const float a = o * fast_rcp(lt);
             if (direct)
                 out[(head0 + g) * D + ch] = a;
             else
                 part_o[(slot * G + g) * D + ch] = a;
             if (ch == 0) {
-                const float ls = Mg * kLn2 + logf(lt);
+                const float ls = (Mg + fast_log2(lt)) * kLn2;  // Mg is in log2 units
                 if (direct)
                     lse[head0 + g] = ls;
                 else
