@@ -163,7 +163,7 @@ __device__ __forceinline__ void reduce_row(const RowLoads<MAXC> &r, float &a_out
     lse_out = M + fast_log(den);
 }
 
-// One workgroup of D threads per (split row, query head).
+// One workgroup of D threads per (split row, query head); grid (split rows, G).
 template <int D>
 __global__ __launch_bounds__(D) void combine_chunks_kernel(const CombineRow *__restrict__ rows, int Hq, int G,
                                                            const float *__restrict__ part_o,
@@ -172,8 +172,8 @@ __global__ __launch_bounds__(D) void combine_chunks_kernel(const CombineRow *__r
 {
     __shared__ float sm_w[kCombineStage];
     __shared__ float sm_red[D];
-    const CombineRow r = rows[blockIdx.x / G];
-    const int g = blockIdx.x % G;
+    const CombineRow r = rows[blockIdx.x];  // grid: (split rows, G) - no integer division on a latency-bound path
+    const int g = blockIdx.y;
     const int64_t row = (int64_t)r.user * Hq + (int64_t)r.kv_head * G + g;
     float a, ls;
     constexpr int kSmall = 16;
@@ -203,7 +203,7 @@ __device__ __forceinline__ void merge_weights(float l0, float l1, float &w0, flo
     ls = M + fast_log(den);
 }
 
-// Last kernel of a fused decode step: one workgroup of D threads per (user, query head).  For each owner, a row
+// Last kernel of a fused decode step: one workgroup of D threads per (user, query head), grid (users, Hkv, G).  For each owner, a row
 // that was split is combined here (and its A / lse written, so the caller still gets both partials); unsplit and
 // empty rows were already written by the partial kernels and are read back.  Then the two owners are merged.
 template <int D>
@@ -219,9 +219,10 @@ __global__ __launch_bounds__(D) void finalize_step_kernel(const RowInfo *__restr
 {
     __shared__ float sm_w[kCombineStage];
     __shared__ float sm_red[D];
-    const int64_t row = blockIdx.x;  // user * Hq + head
-    const int user = (int)(row / Hq), h = (int)(row % Hq);
-    const int kvh = h / G, g = h % G;
+    // grid (users, Hkv, G): the indices come as they are (a 64-bit division here was ~150 dependent scalar instructions
+    // in front of a kernel that lasts 4 us)
+    const int user = blockIdx.x, kvh = blockIdx.y, g = blockIdx.z;
+    const int64_t row = (int64_t)user * Hq + kvh * G + g;
     const int tid = threadIdx.x;
     const RowInfo ri = rows_in[user * Hkv + kvh], ro = rows_out[user * Hkv + kvh];
     // Measured on this kernel (4 us, pure latency): the 8-wide straight-line form is the fastest for rows of up to 8
@@ -275,16 +276,16 @@ __global__ __launch_bounds__(D) void finalize_step_kernel(const RowInfo *__restr
     }
 }
 
-// one thread per 4 channels of one row
-__global__ __launch_bounds__(256) void lse_merge_kernel(int64_t n_vec, int vec_per_row, const float *a0,
+// one thread per 4 channels of one row; block (vec_per_row, rows per block)
+__global__ __launch_bounds__(256) void lse_merge_kernel(int n_rows, int vec_per_row, const float *a0,
                                                          const float *__restrict__ lse0, const float *a1,
                                                          const float *__restrict__ lse1, float *y,
                                                          float *__restrict__ lse_out, float *__restrict__ w0_out)
 {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n_vec)
+    const int64_t row = (int64_t)blockIdx.x * blockDim.y + threadIdx.y;
+    if (row >= n_rows)
         return;
-    const int64_t row = i / vec_per_row;
+    const int64_t i = row * vec_per_row + threadIdx.x;
     float w0, w1, ls;
     merge_weights(lse0[row], lse1[row], w0, w1, ls);
     const f32x4 x0 = reinterpret_cast<const f32x4 *>(a0)[i];
@@ -294,7 +295,7 @@ __global__ __launch_bounds__(256) void lse_merge_kernel(int64_t n_vec, int vec_p
     for (int e = 0; e < 4; ++e)
         r[e] = (w0 == 0.f ? 0.f : w0 * x0[e]) + (w1 == 0.f ? 0.f : w1 * x1[e]);  // a zero weight ignores its side entirely
     reinterpret_cast<f32x4 *>(y)[i] = r;
-    if (i % vec_per_row == 0) {
+    if (threadIdx.x == 0) {
         if (lse_out)
             lse_out[row] = ls;
         if (w0_out)

@@ -20,6 +20,8 @@ inline int validate_shape(const spd_shape *s)
         return SPD_ERR_SHAPE;
     if (s->n_q_heads <= 0 || s->n_kv_heads <= 0 || s->n_q_heads % s->n_kv_heads != 0)
         return SPD_ERR_SHAPE;
+    if (s->n_kv_heads > 65535)  // a grid dimension of the closing kernel
+        return SPD_ERR_SHAPE;
     const int G = s->n_q_heads / s->n_kv_heads;
     if (s->dtype == SPD_BF16) {
         if (s->head_dim != 128 || G > spd::kMaxGroup)

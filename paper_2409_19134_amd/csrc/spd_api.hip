@@ -500,12 +500,12 @@ int launch_combine(spd_ctx *ctx, int which, const CachedSchedule *e, const spd_s
     Owner &own = ctx->owner[which];
     const int G = s->n_q_heads / s->n_kv_heads;
     const CombineRow *rows = reinterpret_cast<const CombineRow *>(e->dev + e->off_rows);
-    const unsigned grid = (unsigned)e->n_split_rows * (unsigned)G;
+    const dim3 grid((unsigned)e->n_split_rows, (unsigned)G);
     if (s->head_dim == 64)
-        hipLaunchKernelGGL((spd::combine_chunks_kernel<64>), dim3(grid), dim3(64), 0, stream, rows, s->n_q_heads, G,
+        hipLaunchKernelGGL((spd::combine_chunks_kernel<64>), grid, dim3(64), 0, stream, rows, s->n_q_heads, G,
                            own.part_o, own.part_lse, out, lse);
     else
-        hipLaunchKernelGGL((spd::combine_chunks_kernel<128>), dim3(grid), dim3(128), 0, stream, rows, s->n_q_heads, G,
+        hipLaunchKernelGGL((spd::combine_chunks_kernel<128>), grid, dim3(128), 0, stream, rows, s->n_q_heads, G,
                            own.part_o, own.part_lse, out, lse);
     SPD_HIP(ctx, hipGetLastError());
     return SPD_OK;
@@ -812,14 +812,14 @@ int spd_decode_step(spd_ctx *ctx, const spd_shape *shape, const void *q, const s
     const int G = shape->n_q_heads / shape->n_kv_heads;
     const RowInfo *ri = reinterpret_cast<const RowInfo *>(ep->dev + ep->off_info);
     const RowInfo *ro = reinterpret_cast<const RowInfo *>(eo->dev + eo->off_info);
-    const unsigned grid = (unsigned)priv->n_users * (unsigned)shape->n_q_heads;
+    const dim3 grid((unsigned)priv->n_users, (unsigned)shape->n_kv_heads, (unsigned)G);
     const Owner &op = ctx->owner[0], &oo = ctx->owner[1];
     if (shape->head_dim == 64)
-        hipLaunchKernelGGL((spd::finalize_step_kernel<64>), dim3(grid), dim3(64), 0, stream, ri, ro, shape->n_kv_heads,
+        hipLaunchKernelGGL((spd::finalize_step_kernel<64>), grid, dim3(64), 0, stream, ri, ro, shape->n_kv_heads,
                            shape->n_q_heads, G, op.part_o, op.part_lse, oo.part_o, oo.part_lse, a_in, lse_in, a_out,
                            lse_out, y, lse, w_in);
     else
-        hipLaunchKernelGGL((spd::finalize_step_kernel<128>), dim3(grid), dim3(128), 0, stream, ri, ro,
+        hipLaunchKernelGGL((spd::finalize_step_kernel<128>), grid, dim3(128), 0, stream, ri, ro,
                            shape->n_kv_heads, shape->n_q_heads, G, op.part_o, op.part_lse, oo.part_o, oo.part_lse, a_in,
                            lse_in, a_out, lse_out, y, lse, w_in);
     SPD_HIP(ctx, hipGetLastError());
@@ -860,11 +860,11 @@ int spd_lse_merge(spd_ctx *ctx, int32_t n_rows, int32_t head_dim, const float *a
     if (!aligned16(a0) || !aligned16(a1) || !aligned16(y))
         return SPD_ERR_ALIGN;
     SPD_HIP(ctx, hipSetDevice(ctx->device));
-    const int vpr = head_dim / 4;
-    const int64_t n_vec = (int64_t)n_rows * vpr;
-    const unsigned blocks = (unsigned)((n_vec + 255) / 256);
-    hipLaunchKernelGGL(spd::lse_merge_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream), n_vec,
-                       vpr, a0, lse0, a1, lse1, y, lse_out, w0_out);
+    const int vpr = head_dim / 4;              // at most 256
+    const int rows_per_block = std::max(1, 256 / vpr);
+    const unsigned blocks = (unsigned)(((int64_t)n_rows + rows_per_block - 1) / rows_per_block);
+    hipLaunchKernelGGL(spd::lse_merge_kernel, dim3(blocks), dim3((unsigned)vpr, (unsigned)rows_per_block), 0,
+                       static_cast<hipStream_t>(hip_stream), n_rows, vpr, a0, lse0, a1, lse1, y, lse_out, w0_out);
     SPD_HIP(ctx, hipGetLastError());
     return SPD_OK;
 }
