@@ -107,12 +107,12 @@ void free_entry(CachedSchedule &e)
     e = CachedSchedule();
 }
 
-// Contiguous token-major storage (the KV heads of a token adjacent in memory) can take the head-per-wave kernel: one
-// wave per KV head, all waves on the same tokens.  (Token-major pages gained nothing from it when measured.)
+// Token-major storage (the KV heads of a token adjacent in memory, plain or inside pages) can take the head-per-wave
+// kernel: one wave per KV head, all waves on the same tokens.
 bool head_per_wave_layout(const spd_shape *s, const spd_kv_view *v)
 {
-    return s->dtype == SPD_BF16 && s->n_kv_heads > 1 && s->n_kv_heads <= 8 && v->block_size == 0 &&
-           !v->head_strides && v->head_stride == s->head_dim &&
+    return s->dtype == SPD_BF16 && s->n_kv_heads > 1 && s->n_kv_heads <= 8 &&
+           !(v->head_strides && v->block_size == 0) && v->head_stride == s->head_dim &&
            v->token_stride >= (int64_t)s->n_kv_heads * s->head_dim;
 }
 
@@ -466,7 +466,9 @@ int launch_partial(spd_ctx *ctx, int which, const CachedSchedule *e0, const spd_
             SPD_LAUNCH_BF16_A(PAGED, PREFETCH, HPW, false);                                                          \
     } while (0)
         if (v0->block_size) {
-            if (prefetch)
+            if (hpw)
+                SPD_LAUNCH_BF16(true, true, true);
+            else if (prefetch)
                 SPD_LAUNCH_BF16(true, true, false);
             else
                 SPD_LAUNCH_BF16(true, false, false);

@@ -97,7 +97,7 @@ def test_config1_fp32_full_size(ctx):
                                                         (4, 8, 48, "nhd"), (2, 8, None, "nhd"), (5, 128, 6, None),
                                                         (5, 128, 6, "nhd"), (3, 64, 12, "nhd"),
                                                         (4, 8, 48, "nhd_hpw"), (2, 8, None, "nhd_hpw"),
-                                                        (3, 64, 12, "nhd_hpw")])
+                                                        (3, 64, 12, "nhd_hpw"), (5, 128, 6, "nhd_hpw")])
 def test_configs_reduced_lengths(ctx, mapping_of, cfg, len_div, n_users, layout):
     layout = mapping_of(layout)
     check_against_oracle(ctx, workloads.make_workload(cfg, DEV, len_div=len_div, n_users=n_users, layout=layout))
@@ -122,7 +122,7 @@ def _sample_rows(wl, n, seed):
 
 
 @pytest.mark.parametrize("cfg,n,layout", [(3, 4, None), (4, 8, None), (5, 3, None),
-                                          (4, 8, "nhd")])     # large and token-major: the head-per-wave mapping
+                                          (4, 8, "nhd"), (5, 3, "nhd")])   # large and token-major: head per wave
 def test_full_size_sampled_rows(ctx, cfg, n, layout):
     wl = workloads.make_workload(cfg, DEV, layout=layout)
     check_against_oracle(ctx, wl, rows=_sample_rows(wl, n, cfg))
@@ -138,7 +138,7 @@ def test_full_size_sampled_rows(ctx, cfg, n, layout):
     ([0, 0, 700], [5, 0, 0]), ([513, 1025, 2049], [95, 96, 97]),
 ])
 @pytest.mark.parametrize("layout,paged", [("nhd", False), ("nhd_hpw", False), ("hnd", False), ("hnd_exact", False),
-                                          ("nhd", True), ("nhd", "token_major")])
+                                          ("nhd", True), ("nhd", "token_major"), ("nhd_hpw", "token_major")])
 def test_bf16_edge_lengths(ctx, mapping_of, lp, lo, layout, paged):
     layout = mapping_of(layout)
     wl = workloads.random_case(101, torch.bfloat16, len(lp), 32, 8, 128, lp, lo, device=DEV, layout=layout, paged=paged)
@@ -177,7 +177,7 @@ def _random_case_spec(rng):
              lambda: int(rng.integers(800, 6000)), lambda: int(rng.choice([32, 64, 128, 512, 1024]))]
     weights = [0.1, 0.25, 0.3, 0.2, 0.15]
     lens = lambda: [kinds[int(rng.choice(len(kinds), p=weights))]() for _ in range(U)]
-    storage = str(rng.choice(["nhd", "nhd_hpw", "hnd", "hnd_exact", "paged", "paged_tm"]))
+    storage = str(rng.choice(["nhd", "nhd_hpw", "hnd", "hnd_exact", "paged", "paged_tm", "paged_tm_hpw"]))
     return dict(dtype=torch.bfloat16 if bf16 else torch.float32, U=U, Hq=Hkv * G, Hkv=Hkv, d=d, lp=lens(), lo=lens(),
                 storage=storage, scale=float(rng.choice([d ** -0.5, 0.02, 0.3])))
 
@@ -189,8 +189,9 @@ def test_randomised_cases(ctx, mapping_of, block):
     for i in range(10):
         c = _random_case_spec(rng)
         print(f"randomised case {block}.{i}: {c}", flush=True)       # names the case if the GPU run ends badly
-        paged = {"paged": True, "paged_tm": "token_major"}.get(c["storage"], False)
-        layout = mapping_of("nhd" if paged else c["storage"])
+        storage = mapping_of(c["storage"])
+        paged = {"paged": True, "paged_tm": "token_major"}.get(storage, False)
+        layout = "nhd" if paged else storage
         wl = workloads.random_case(9100 + 16 * block + i, c["dtype"], c["U"], c["Hq"], c["Hkv"], c["d"], c["lp"], c["lo"],
                                    device=DEV, layout=layout, paged=paged, scale=c["scale"])
         check_against_oracle(ctx, wl)
