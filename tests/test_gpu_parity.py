@@ -197,6 +197,41 @@ def test_randomised_cases(ctx, mapping_of, block):
         check_against_oracle(ctx, wl)
 
 
+def _pad_contiguous(side, Hkv, d, pad_tokens, pad_channels, token_major):
+    """Re-house every user's K and V in buffers with unused channels after each row and unused rows after each head
+    (head-major) or unused channels after each token's heads (token-major); fills the padding with a large value."""
+    for name in ("k", "v"):
+        out = []
+        for t in getattr(side, name):
+            if token_major:                                   # [L, Hkv, d] -> rows of Hkv*d + pad_channels elements
+                L = t.shape[0]
+                big = torch.full((max(L, 1), Hkv * d + pad_channels), 777.0, device=t.device, dtype=t.dtype)
+                big[:L, :Hkv * d] = t.reshape(L, Hkv * d)
+            else:                                             # [Hkv, cap, d] -> [Hkv, cap + pad_tokens, d + pad_channels]
+                cap = t.shape[1]
+                big = torch.full((Hkv, cap + pad_tokens, d + pad_channels), 777.0, device=t.device, dtype=t.dtype)
+                big[:, :cap, :d] = t
+            out.append(big)
+        setattr(side, name, out)
+    if token_major:
+        side.token_stride = Hkv * d + pad_channels
+    else:
+        side.token_stride = d + pad_channels
+        side.head_stride = (side.k[0].shape[1]) * (d + pad_channels)
+
+
+@pytest.mark.parametrize("layout", ["hnd", "nhd", "nhd_hpw"])
+@pytest.mark.parametrize("dtype,d", [(torch.bfloat16, 128), (torch.float32, 64)])
+def test_padded_strides(ctx, mapping_of, layout, dtype, d):
+    """Token and head strides larger than the data they step over (rows and heads with unused space behind them)."""
+    layout = mapping_of(layout)
+    Hkv = 4
+    wl = workloads.random_case(106, dtype, 3, 8, Hkv, d, [700, 33, 1500], [40, 0, 129], device=DEV, layout=layout)
+    for side in (wl.private, wl.public):
+        _pad_contiguous(side, Hkv, d, pad_tokens=3, pad_channels=32, token_major=layout == "nhd")
+    check_against_oracle(ctx, wl)
+
+
 def test_many_users_with_short_rows(ctx):
     """Thousands of workgroups that each take a whole short row (or only write an empty one)."""
     rng = np.random.default_rng(77)
