@@ -195,10 +195,11 @@ int spd_attention_mass_track(spd_ctx *ctx, int32_t n_rows, const float *w_in, fl
 /*
  * Built-in timing of the partial-attention kernel (the HBM-streaming kernel of both partial calls), measured with HIP
  * events on the stream each call launches on.  spd_set_kernel_timing(ctx, n) arms timing for the next n launches of
- * each entry point (n = 0 disarms); while armed, every partial call launches its partial kernel with a start and a stop
- * event attached to the dispatch itself (hipExtLaunchKernel), so the pair measures the kernel alone.  spd_get_kernel_timing waits for the recorded launches of one entry point (0 = private, 1 = public batched),
- * returns their count and mean / minimum duration in microseconds, and clears them.  spd_decode_step's single
- * two-owner launch is booked under entry point 0.
+ * each entry point (n = 0 disarms); while armed, every partial call launches its partial kernel with a start and a
+ * stop event attached to the dispatch itself (hipExtLaunchKernel), so the pair measures the kernel alone.
+ * spd_get_kernel_timing waits for the recorded launches of one entry point (0 = private, 1 = public batched), returns
+ * their count and mean / minimum duration in microseconds, and clears them.  spd_decode_step's single two-owner
+ * launch is booked under entry point 0.
  */
 int spd_set_kernel_timing(spd_ctx *ctx, int32_t max_launches);
 int spd_get_kernel_timing(spd_ctx *ctx, int32_t entry_point, int32_t *n_launches, double *mean_us, double *min_us);
