@@ -550,6 +550,18 @@ int partial_attention(spd_ctx *ctx, int which, const spd_shape *s, const void *q
     return launch_combine(ctx, which, e, s, out, lse, stream);
 }
 
+// No C++ exception leaves the library: a failed host allocation (the schedule builder and the cache use std::vector)
+// becomes SPD_ERR_NOMEM.
+template <class F>
+int no_throw(F &&body)
+{
+    try {
+        return body();
+    } catch (...) {
+        return SPD_ERR_NOMEM;
+    }
+}
+
 }  // namespace
 
 extern "C" {
@@ -645,7 +657,7 @@ int spd_validate_partial(const spd_shape *shape, const void *q, const spd_kv_vie
 
 int spd_build_schedule(const spd_shape *shape, int32_t n_users, const int32_t *lens, int32_t n_compute_units,
                        spd_work_item *items, int64_t capacity, int64_t *n_items, int32_t *chunk_tokens)
-{
+try {
     const int rc = validate_shape(shape);
     if (rc != SPD_OK)
         return rc;
@@ -668,10 +680,12 @@ int spd_build_schedule(const spd_shape *shape, int32_t n_users, const int32_t *l
             std::memcpy(items, S.items.data(), S.items.size() * sizeof(spd_work_item));
     }
     return SPD_OK;
+} catch (...) {  // a failed host allocation (std::vector): no C++ exception leaves the library
+    return SPD_ERR_NOMEM;
 }
 
 int spd_set_kernel_timing(spd_ctx *ctx, int32_t max_launches)
-{
+try {
     if (!ctx)
         return SPD_ERR_NULL;
     if (max_launches < 0)
@@ -689,6 +703,8 @@ int spd_set_kernel_timing(spd_ctx *ctx, int32_t max_launches)
     }
     ctx->timing = max_launches > 0;
     return SPD_OK;
+} catch (...) {  // a failed host allocation (std::vector): no C++ exception leaves the library
+    return SPD_ERR_NOMEM;
 }
 
 int spd_get_kernel_timing_samples(spd_ctx *ctx, int32_t entry_point, int32_t capacity, float *us, int32_t *n_launches)
@@ -713,7 +729,7 @@ int spd_get_kernel_timing_samples(spd_ctx *ctx, int32_t entry_point, int32_t cap
 }
 
 int spd_get_kernel_timing(spd_ctx *ctx, int32_t entry_point, int32_t *n_launches, double *mean_us, double *min_us)
-{
+try {
     if (!ctx || !n_launches || !mean_us || !min_us)
         return SPD_ERR_NULL;
     if (entry_point != 0 && entry_point != 1)
@@ -730,18 +746,20 @@ int spd_get_kernel_timing(spd_ctx *ctx, int32_t entry_point, int32_t *n_launches
     *mean_us = us.empty() ? 0.0 : sum / (double)us.size();
     *min_us = mn;
     return SPD_OK;
+} catch (...) {  // a failed host allocation (std::vector): no C++ exception leaves the library
+    return SPD_ERR_NOMEM;
 }
 
 int spd_partial_attn_private(spd_ctx *ctx, const spd_shape *shape, const void *q, const spd_kv_view *priv, float *out,
                              float *lse, void *hip_stream)
 {
-    return partial_attention(ctx, 0, shape, q, priv, out, lse, NewToken(), hip_stream);
+    return no_throw([&] { return partial_attention(ctx, 0, shape, q, priv, out, lse, NewToken(), hip_stream); });
 }
 
 int spd_partial_attn_public_batched(spd_ctx *ctx, const spd_shape *shape, const void *q, const spd_kv_view *pub,
                                     float *out, float *lse, void *hip_stream)
 {
-    return partial_attention(ctx, 1, shape, q, pub, out, lse, NewToken(), hip_stream);
+    return no_throw([&] { return partial_attention(ctx, 1, shape, q, pub, out, lse, NewToken(), hip_stream); });
 }
 
 int spd_partial_attn_public_batched_append(spd_ctx *ctx, const spd_shape *shape, const void *q, const void *k_new,
@@ -753,13 +771,13 @@ int spd_partial_attn_public_batched_append(spd_ctx *ctx, const spd_shape *shape,
     NewToken nt;
     nt.k = k_new;
     nt.v = v_new;
-    return partial_attention(ctx, 1, shape, q, pub, out, lse, nt, hip_stream);
+    return no_throw([&] { return partial_attention(ctx, 1, shape, q, pub, out, lse, nt, hip_stream); });
 }
 
 int spd_decode_step(spd_ctx *ctx, const spd_shape *shape, const void *q, const spd_kv_view *priv,
                     const spd_kv_view *pub, const void *k_new, const void *v_new, float *a_in, float *lse_in,
                     float *a_out, float *lse_out, float *y, float *lse, float *w_in, void *hip_stream)
-{
+try {
     NewToken nt;
     nt.k = k_new;
     nt.v = v_new;
@@ -826,6 +844,8 @@ int spd_decode_step(spd_ctx *ctx, const spd_shape *shape, const void *q, const s
                            lse_in, a_out, lse_out, y, lse, w_in);
     SPD_HIP(ctx, hipGetLastError());
     return SPD_OK;
+} catch (...) {  // a failed host allocation (std::vector): no C++ exception leaves the library
+    return SPD_ERR_NOMEM;
 }
 
 int spd_attention_mass_track(spd_ctx *ctx, int32_t n_rows, const float *w_in, float threshold, float *mass_min,
