@@ -208,3 +208,17 @@ def test_device_pointer_tables_come_in_pairs_and_aligned():
     assert spd.lib.spd_validate_partial(*args) == spd.SPD_ERR_ALIGN       # pointers are 8 bytes
     st.v_ptrs_dev = 0x5008
     assert spd.lib.spd_validate_partial(*args) == spd.SPD_OK
+
+
+def test_header_is_c99_and_library_links_from_c(tmp_path):
+    """include/spd.h compiled by a C99 compiler with warnings as errors; the program links the library and calls the
+    host-only entry points."""
+    import subprocess
+    lib_dir = os.path.join(ROOT, "paper_2409_19134_amd")
+    exe = str(tmp_path / "abi_c99")
+    subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"),
+                           os.path.join(ROOT, "tests", "host", "abi_c99.c"), "-o", exe,
+                           "-L", lib_dir, "-l:libspd_hip.so", "-Wl,-rpath," + lib_dir])
+    res = subprocess.run([exe], capture_output=True, text=True)
+    assert res.returncode == 0, (res.returncode, res.stdout, res.stderr)
+    assert "c99 ok" in res.stdout
