@@ -164,8 +164,8 @@ __host__ __device__ constexpr bool staging_fits(int waves, int G) { return stagi
 // owner's pieces are one resident round, and it leaves room on every CU for the other owner's pieces.
 //
 // HPW ("head per wave") is the mapping for contiguous token-major storage, where the KV heads of a token are adjacent
-// in memory ([token][head][d]).  A piece is then a token range of a *user* (all KV heads), the workgroup
-// has one wave per KV head, and all waves walk the same tokens: together they read whole, consecutive DRAM pages,
+// in memory ([token][head][d]).  A piece is then a token range of a *user* for a group of up to eight KV heads (all
+// of them if Hkv <= 8), the workgroup has one wave per KV head of the group, and all waves walk the same tokens: together they read whole, consecutive DRAM pages,
 // where one workgroup per head would touch every page eight times at different moments (a barrier per step keeps
 // the waves together).  Each wave owns its head's result, so there is no cross-wave combine; the wave stores its
 // result through an LDS tile of its own.  Without HPW (head-major storage: one contiguous stream per head) a piece is
@@ -208,7 +208,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, PREFETCH ? 2 : 3) void partia
         L.grp = lane >> 4;
         L.token_stride = kv.token_stride;
         L.block_stride = kv.block_stride;
-        const int kv_head = HPW ? uniform(wave) : it.kv_head;
+        const int kv_head = HPW ? it.kv_head + uniform(wave) : it.kv_head;  // head per wave: the group's first head + wave
         L.k_base = it.k_base + k_pool + (PAGED ? 0 : user_base(k_ptrs, it.user)) + (HPW ? (int64_t)kv_head * kv.head_stride : 0);
         L.v_base = it.v_base + v_pool + (PAGED ? 0 : user_base(v_ptrs, it.user)) + (HPW ? (int64_t)kv_head * kv.head_stride : 0);
         L.bt_row = PAGED ? kv.block_table + (int64_t)it.user * kv.max_blocks : nullptr;
@@ -251,7 +251,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, PREFETCH ? 2 : 3) void partia
     DevItem it = scalar_load_item(items, second ? (int)blockIdx.x - n0 : (int)blockIdx.x);
     if (it.n_chunks == 0) {  // a row without tokens (head-per-wave: a user without tokens) is a piece of its own
         if (HPW) {
-            const int64_t head0 = (int64_t)it.user * Hq + (int64_t)wave * G;
+            const int64_t head0 = (int64_t)it.user * Hq + (int64_t)(it.kv_head + wave) * G;
             for (int idx = lane; idx < G * 128; idx += 64)
                 out[head0 * 128 + idx] = 0.f;
             if (lane < G)
@@ -328,9 +328,9 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, PREFETCH ? 2 : 3) void partia
         if (HPW) {
             // ... and that is all: the wave owns head `wave` of this token range.  Lane (r < G, grp) holds channels
             // (4*grp + v)*8 + cc of query head r: eight consecutive floats per v.
-            const int kvh = uniform(wave);
+            const int kvh = it.kv_head + uniform(wave);
             const int64_t head0 = (int64_t)it.user * Hq + (int64_t)kvh * G;
-            const int64_t slot = (int64_t)it.slot + (int64_t)kvh * it.n_chunks;
+            const int64_t slot = (int64_t)it.slot + (int64_t)uniform(wave) * it.n_chunks;  // it.slot: the group's first head
             const float inv = fast_rcp(l);  // l > 0: the segment holds at least one token
             float *res = direct ? out + head0 * 128 : part_o + slot * G * 128;  // [G][128], contiguous
             if (staged) {

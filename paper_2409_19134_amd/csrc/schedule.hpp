@@ -49,11 +49,24 @@ struct Schedule {
 };
 
 // hpw: pieces for the head-per-wave kernel (token-major storage).  A piece then covers all KV heads of its token
-// range: one item per cut (kv_head = 0, slot = the slot of head 0) and one resident workgroup per CU.  The same
+// range (a group of up to eight of them, see head_per_wave_waves): one item per cut and group (kv_head and slot are
+// those of the group's first head) and one resident workgroup per CU.  The same
 // token limit per piece serves both mappings (smaller pieces measured slower here too), although every wave now
 // walks the whole range instead of a quarter of it.
+// Waves (KV heads) per workgroup of the head-per-wave mapping: the largest divisor of Hkv that is at most 8 (two waves
+// per SIMD is what the kernel's registers allow); Hkv / that many head groups share a token range.
+inline int head_per_wave_waves(int Hkv)
+{
+    for (int w = std::min(Hkv, 8); w >= 1; --w)
+        if (Hkv % w == 0)
+            return w;
+    return 1;
+}
+
 inline void build_schedule(int Hkv, int n_users, const int32_t *lens, int n_cus, bool hpw, Schedule &S)
 {
+    const int hpw_waves = hpw ? head_per_wave_waves(Hkv) : 1;
+    const int hpw_groups = hpw ? Hkv / hpw_waves : 1;
     S.items.clear();
     S.piece_first.assign(1, 0);
     S.n_slots = 0;
@@ -84,7 +97,9 @@ inline void build_schedule(int Hkv, int n_users, const int32_t *lens, int n_cus,
     } else {
         const int64_t slots = (int64_t)std::max(1, n_cus) * env_int("SPD_TARGET_WG_PER_CU", kTargetWgPerCuDefault);
         // groups per resident wave of workgroups
-        const int64_t wg = hpw ? std::max(1, n_cus) : std::max<int64_t>(1, slots / Hkv);
+        // head per wave: a CU holds eight such waves, i.e. 8 / waves workgroups
+        const int64_t wg = hpw ? std::max<int64_t>(1, (int64_t)std::max(1, n_cus) * (8 / hpw_waves) / hpw_groups)
+                               : std::max<int64_t>(1, slots / Hkv);
         const int64_t piece_max = std::max(kChunkMin, env_int("SPD_CHUNK_MAX", kChunkMaxDefault)) / kChunkAlign;
         // group boundaries (cumulative step counts)
         std::vector<int64_t> ends;
@@ -138,7 +153,8 @@ inline void build_schedule(int Hkv, int n_users, const int32_t *lens, int n_cus,
     for (const auto &grp : groups) {
         if (grp.empty())
             continue;
-        for (int h = 0; h < (hpw ? 1 : Hkv); ++h) {
+        for (int hh = 0; hh < (hpw ? hpw_groups : Hkv); ++hh) {
+            const int h = hpw ? hh * hpw_waves : hh;  // head per wave: the first head of the group
             for (const Cut &c : grp) {
                 spd_work_item it;
                 it.user = c.user;

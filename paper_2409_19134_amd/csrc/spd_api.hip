@@ -111,7 +111,7 @@ void free_entry(CachedSchedule &e)
 // kernel: one wave per KV head, all waves on the same tokens.
 bool head_per_wave_layout(const spd_shape *s, const spd_kv_view *v)
 {
-    return s->dtype == SPD_BF16 && s->n_kv_heads > 1 && s->n_kv_heads <= 8 &&
+    return s->dtype == SPD_BF16 && head_per_wave_waves(s->n_kv_heads) > 1 &&
            !(v->head_strides && v->block_size == 0) && v->head_stride == s->head_dim &&
            v->token_stride >= (int64_t)s->n_kv_heads * s->head_dim;
 }
@@ -197,10 +197,11 @@ int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view
     // writes A = 0, lse = -inf), then the continuation segments, linked through `next`
     const int es = elt_size(s->dtype);
     const int Hkv = s->n_kv_heads;
+    const int hpw_waves = hpw ? head_per_wave_waves(Hkv) : 1;  // heads an item stands for
     const int64_t n_pieces = (int64_t)S.piece_first.size() - 1;
     int64_t n_empty_rows = 0;  // workgroups that only write A = 0, lse = -inf (head-per-wave: one per empty user)
     for (int u = 0; u < v->n_users; ++u)
-        n_empty_rows += v->lens[u] == 0 ? (hpw ? 1 : Hkv) : 0;
+        n_empty_rows += v->lens[u] == 0 ? (hpw ? Hkv / hpw_waves : Hkv) : 0;
     const int64_t n_groups = n_pieces + n_empty_rows;  // launched workgroups
     std::vector<DevItem> dev_items((size_t)n_groups);
     dev_items.reserve((size_t)n_groups + S.items.size());
@@ -208,7 +209,7 @@ int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view
         const char *base = (v->block_size || v->k_ptrs_dev) ? nullptr  // an offset: the kernel adds the pool / the user's pointer
                                          : static_cast<const char *>(is_v ? v->v_ptrs[u] : v->k_ptrs[u]);
         const int64_t hs = (v->head_strides && v->block_size == 0) ? v->head_strides[u] : v->head_stride;
-        return base + (hpw ? 0 : (int64_t)h * hs * es);  // head-per-wave: every wave adds its own head's offset
+        return base + (hpw ? 0 : (int64_t)h * hs * es);  // head-per-wave: every wave adds its own head's offset (from head 0)
     };
     auto to_dev = [&](const spd_work_item &w, int rot) {
         DevItem d;
@@ -248,11 +249,11 @@ int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view
         for (int u = 0; u < v->n_users; ++u) {
             if (v->lens[u] != 0)
                 continue;
-            for (int h = 0; h < (hpw ? 1 : Hkv); ++h) {
+            for (int hh = 0; hh < (hpw ? Hkv / hpw_waves : Hkv); ++hh) {
                 DevItem d;
                 d.k_base = d.v_base = nullptr;
                 d.user = u;
-                d.kv_head = h;
+                d.kv_head = hpw ? hh * hpw_waves : hh;
                 d.t_begin = d.t_end = 0;
                 d.slot = d.n_chunks = d.rot = 0;
                 d.next = -1;
@@ -264,13 +265,13 @@ int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view
     for (size_t i = 0; i < S.items.size(); ++i) {
         const spd_work_item &w = S.items[i];
         if (w.chunk == 0 && w.n_chunks > 1)
-            for (int h = 0; h < (hpw ? Hkv : 1); ++h)  // a head-per-wave item stands for all KV heads
+            for (int h = 0; h < hpw_waves; ++h)  // a head-per-wave item stands for the KV heads of its group
                 split_rows.push_back(CombineRow{w.slot + h * w.n_chunks, w.n_chunks, w.user, w.kv_head + h});
     }
     std::vector<RowInfo> row_info((size_t)v->n_users * Hkv, RowInfo{0, 0});
     for (const spd_work_item &w : S.items)
         if (w.chunk == 0)
-            for (int h = 0; h < (hpw ? Hkv : 1); ++h)
+            for (int h = 0; h < hpw_waves; ++h)
                 row_info[(size_t)w.user * Hkv + w.kv_head + h] = RowInfo{w.slot + h * w.n_chunks, w.n_chunks};
     const size_t b_items = dev_items.size() * sizeof(DevItem);
     const size_t b_rows = split_rows.size() * sizeof(CombineRow);
@@ -445,10 +446,10 @@ int launch_partial(spd_ctx *ctx, int which, const CachedSchedule *e0, const spd_
     if (s->dtype == SPD_BF16) {
         const uint16_t *qh = static_cast<const uint16_t *>(q);
         const bool hpw = e0->hpw;  // a two-owner launch needs the same mapping on both sides (checked by the caller)
-        const int waves = hpw ? s->n_kv_heads : spd::kWaves;
+        const int waves = hpw ? head_per_wave_waves(s->n_kv_heads) : spd::kWaves;
         // cross-wave staging; head-per-wave stages its per-wave results too if that fits (the kernel applies the same rule)
         const size_t lds = (hpw && !spd::staging_fits(waves, G)) ? 0 : spd::staging_bytes(waves, G);
-        const dim3 blk(hpw ? 64u * (unsigned)s->n_kv_heads : (unsigned)spd::kThreads);
+        const dim3 blk(hpw ? 64u * (unsigned)waves : (unsigned)spd::kThreads);
         // clearly more pieces than the three-per-CU kernel holds at once (a few left over just start a little
         // later): use the prefetching two-per-CU kernel.  Also when all pieces fit two per CU anyway: a wave then
         // needs half as many dependent memory round trips (short rows taken whole are latency-bound).

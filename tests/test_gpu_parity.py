@@ -158,7 +158,8 @@ def test_bf16_edge_lengths(ctx, mapping_of, lp, lo, layout, paged):
 
 
 @pytest.mark.parametrize("Hq,Hkv", [(8, 8), (16, 8), (64, 8), (16, 1), (12, 4), (32, 2), (48, 16),
-                                    (128, 8)])   # G = 16 with 8 waves: head-per-wave results too big for the LDS tiles
+                                    (128, 8),    # G = 16 with 8 waves: head-per-wave results too big for the LDS tiles
+                                    (24, 12), (27, 9), (32, 32)])   # head per wave in groups of 6, 3 and 8 heads
 @pytest.mark.parametrize("layout", ["nhd", "nhd_hpw", "hnd"])   # nhd_hpw: one wave per KV head where Hkv is in 2..8
 def test_bf16_head_groupings(ctx, mapping_of, Hq, Hkv, layout):
     layout = mapping_of(layout)
