@@ -23,15 +23,12 @@ inline int validate_shape(const spd_shape *s)
     if (s->n_kv_heads > 65535)  // a grid dimension of the closing kernel
         return SPD_ERR_SHAPE;
     const int G = s->n_q_heads / s->n_kv_heads;
-    if (s->dtype == SPD_BF16) {
-        if (s->head_dim != 128 || G > spd::kMaxGroup)
-            return SPD_ERR_SHAPE;
-    } else {
-        if (s->head_dim != 64 && s->head_dim != 128)
-            return SPD_ERR_SHAPE;
-        if (G != 1 && G != 2 && G != 4 && G != 8)
-            return SPD_ERR_SHAPE;
-    }
+    if (s->head_dim != 64 && s->head_dim != 128)
+        return SPD_ERR_SHAPE;
+    // bf16 with 128 channels runs on the matrix cores; everything else on the vector path, which keeps the group's
+    // state in registers
+    if (G > (s->dtype == SPD_BF16 && s->head_dim == 128 ? spd::kMaxGroup : 8))
+        return SPD_ERR_SHAPE;
     if (!std::isfinite(s->scale))
         return SPD_ERR_SHAPE;
     return SPD_OK;

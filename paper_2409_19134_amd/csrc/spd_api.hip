@@ -111,7 +111,7 @@ void free_entry(CachedSchedule &e)
 // kernel: one wave per KV head, all waves on the same tokens.
 bool head_per_wave_layout(const spd_shape *s, const spd_kv_view *v)
 {
-    return s->dtype == SPD_BF16 && head_per_wave_waves(s->n_kv_heads) > 1 &&
+    return s->dtype == SPD_BF16 && s->head_dim == 128 && head_per_wave_waves(s->n_kv_heads) > 1 &&
            !(v->head_strides && v->block_size == 0) && v->head_stride == s->head_dim &&
            v->token_stride >= (int64_t)s->n_kv_heads * s->head_dim;
 }
@@ -353,23 +353,27 @@ int ensure_scratch(spd_ctx *ctx, Owner &own, size_t o_floats, size_t lse_floats)
 }
 
 // ev0 / ev1 (both null unless timing is armed) receive the kernel's own start and stop time stamps.
-template <int D, int G>
-void launch_f32(dim3 grid, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1, const OwnerArgs &a0,
-                const OwnerArgs &a1, int n0, const void *q, int Hq, float c)
+template <bool BF16, int D, int G>
+void launch_valu(dim3 grid, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1, const OwnerArgs &a0,
+                 const OwnerArgs &a1, int n0, const void *q, int Hq, float c)
 {
-    hipExtLaunchKernelGGL((spd::partial_f32_kernel<D, G>), grid, dim3(spd::kThreads), 0, stream, ev0, ev1, 0, a0, a1, n0,
-                          static_cast<const float *>(q), Hq, c);
+    hipExtLaunchKernelGGL((spd::partial_valu_kernel<BF16, D, G>), grid, dim3(spd::kThreads), 0, stream, ev0, ev1, 0, a0,
+                          a1, n0, static_cast<const char *>(q), Hq, c);
 }
 
-template <int D>
-void launch_f32_g(int G, dim3 grid, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1, const OwnerArgs &a0,
-                  const OwnerArgs &a1, int n0, const void *q, int Hq, float c)
+template <bool BF16, int D>
+void launch_valu_g(int G, dim3 grid, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1, const OwnerArgs &a0,
+                   const OwnerArgs &a1, int n0, const void *q, int Hq, float c)
 {
-    switch (G) {
-    case 1: launch_f32<D, 1>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
-    case 2: launch_f32<D, 2>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
-    case 4: launch_f32<D, 4>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
-    default: launch_f32<D, 8>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
+    switch (G) {  // validate_shape admits 1..8
+    case 1: launch_valu<BF16, D, 1>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
+    case 2: launch_valu<BF16, D, 2>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
+    case 3: launch_valu<BF16, D, 3>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
+    case 4: launch_valu<BF16, D, 4>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
+    case 5: launch_valu<BF16, D, 5>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
+    case 6: launch_valu<BF16, D, 6>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
+    case 7: launch_valu<BF16, D, 7>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
+    default: launch_valu<BF16, D, 8>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
     }
 }
 
@@ -443,7 +447,7 @@ int launch_partial(spd_ctx *ctx, int which, const CachedSchedule *e0, const spd_
     const hipEvent_t ev0 = timed ? town.ev_start[town.ev_used] : nullptr;
     const hipEvent_t ev1 = timed ? town.ev_stop[town.ev_used] : nullptr;
     const dim3 grid((unsigned)(n0 + n1));
-    if (s->dtype == SPD_BF16) {
+    if (s->dtype == SPD_BF16 && s->head_dim == 128) {
         const uint16_t *qh = static_cast<const uint16_t *>(q);
         const bool hpw = e0->hpw;  // a two-owner launch needs the same mapping on both sides (checked by the caller)
         const int waves = hpw ? head_per_wave_waves(s->n_kv_heads) : spd::kWaves;
@@ -483,10 +487,12 @@ int launch_partial(spd_ctx *ctx, int which, const CachedSchedule *e0, const spd_
         }
 #undef SPD_LAUNCH_BF16_A
 #undef SPD_LAUNCH_BF16
+    } else if (s->dtype == SPD_BF16) {
+        launch_valu_g<true, 64>(G, grid, stream, ev0, ev1, a0, a1, (int)n0, q, s->n_q_heads, c);
     } else if (s->head_dim == 64) {
-        launch_f32_g<64>(G, grid, stream, ev0, ev1, a0, a1, (int)n0, q, s->n_q_heads, c);
+        launch_valu_g<false, 64>(G, grid, stream, ev0, ev1, a0, a1, (int)n0, q, s->n_q_heads, c);
     } else {
-        launch_f32_g<128>(G, grid, stream, ev0, ev1, a0, a1, (int)n0, q, s->n_q_heads, c);
+        launch_valu_g<false, 128>(G, grid, stream, ev0, ev1, a0, a1, (int)n0, q, s->n_q_heads, c);
     }
     SPD_HIP(ctx, hipGetLastError());
     if (timed)

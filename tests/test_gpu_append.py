@@ -69,6 +69,9 @@ CASES = [
     (torch.bfloat16, 32, 8, 128, [2000, 10, 0], [1500, 3000, 1], "nhd_hpw", "token_major"),
     (torch.float32, 8, 8, 64, [128, 5], [16, 1], "nhd", False),
     (torch.float32, 8, 2, 128, [128, 5, 9], [33, 1, 900], "nhd", True),
+    (torch.bfloat16, 32, 8, 64, [40, 1, 700, 33], [1, 16, 17, 250], "nhd", False),
+    (torch.bfloat16, 12, 2, 64, [2000, 10, 0], [1500, 3000, 1], "hnd", False),
+    (torch.bfloat16, 32, 8, 64, [128, 5, 9], [33, 1, 900], "nhd", "token_major"),
 ]
 
 

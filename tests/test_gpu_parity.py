@@ -261,6 +261,19 @@ def test_fp32_shapes(ctx, d, Hq, Hkv, paged):
     check_against_oracle(ctx, wl)
 
 
+@pytest.mark.parametrize("dtype,d,Hq,Hkv", [
+    (torch.bfloat16, 64, 32, 8), (torch.bfloat16, 64, 8, 8), (torch.bfloat16, 64, 12, 2), (torch.bfloat16, 64, 14, 2),
+    (torch.bfloat16, 64, 3, 1), (torch.bfloat16, 64, 40, 8),
+    (torch.float32, 64, 9, 3), (torch.float32, 128, 5, 1), (torch.float32, 64, 12, 2), (torch.float32, 128, 14, 2)])
+@pytest.mark.parametrize("storage", ["hnd", "nhd", "paged", "paged_tm"])
+def test_vector_path_shapes(ctx, dtype, d, Hq, Hkv, storage):
+    """bf16 with 64 channels and the head groups 3, 5, 6, 7: the shapes that take the vector kernel beside fp32's own."""
+    paged = {"paged": True, "paged_tm": "token_major"}.get(storage, False)
+    wl = workloads.random_case(108, dtype, 5, Hq, Hkv, d, [128, 0, 1000, 3, 2500], [16, 5, 0, 77, 300], device=DEV,
+                               layout="nhd" if paged else storage, paged=paged)
+    check_against_oracle(ctx, wl)
+
+
 def test_peaked_softmax_and_large_score_gap(ctx):
     """Scores spread far beyond the fp32 exp range between the two parts: weights saturate, nothing overflows."""
     wl = workloads.random_case(109, torch.bfloat16, 2, 32, 8, 128, [256, 256], [64, 64], device=DEV, scale=1.0)
