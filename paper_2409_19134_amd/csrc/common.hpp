@@ -10,6 +10,7 @@ namespace spd {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kWaves = 4;            // waves per workgroup in the partial-attention kernels
 constexpr int kThreads = kWaves * 64;
@@ -48,11 +49,13 @@ constexpr int kEndsRow = 0x100;
 // other lines in L2 (measured: plain streaming reads reach ~6.3 TB/s on this GPU, non-temporal ones ~7.1 TB/s).
 // The pointer is cast to the global address space: base pointers arrive through memory (the work items), where the
 // compiler cannot see the address space and would otherwise emit slower FLAT loads that also tie up the LDS counter.
-typedef const u32x4 __attribute__((address_space(1))) *global_u32x4_ptr;
-__device__ __forceinline__ u32x4 stream_load16(const char *p)
+template <typename V>  // V: u32x4 (16 bytes) or u32x2 (8 bytes)
+__device__ __forceinline__ V stream_load(const char *p)
 {
-    return __builtin_nontemporal_load((global_u32x4_ptr)(uintptr_t)p);
+    typedef const V __attribute__((address_space(1))) *global_ptr;
+    return __builtin_nontemporal_load((global_ptr)(uintptr_t)p);
 }
+__device__ __forceinline__ u32x4 stream_load16(const char *p) { return stream_load<u32x4>(p); }
 
 // Wave-uniform values (work item fields arrive through vector loads): tell the compiler, so that address arithmetic
 // and the block-table lookups go to the scalar unit.

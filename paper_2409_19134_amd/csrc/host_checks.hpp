@@ -25,9 +25,9 @@ inline int validate_shape(const spd_shape *s)
     const int G = s->n_q_heads / s->n_kv_heads;
     if (s->head_dim != 64 && s->head_dim != 128)
         return SPD_ERR_SHAPE;
-    // bf16 with 128 channels runs on the matrix cores; everything else on the vector path, which keeps the group's
-    // state in registers
-    if (G > (s->dtype == SPD_BF16 && s->head_dim == 128 ? spd::kMaxGroup : 8))
+    // bf16 runs on the matrix cores (a tile holds 16 heads); fp32 on the vector path, which keeps the group's state
+    // in registers
+    if (G > (s->dtype == SPD_BF16 ? spd::kMaxGroup : 8))
         return SPD_ERR_SHAPE;
     if (!std::isfinite(s->scale))
         return SPD_ERR_SHAPE;

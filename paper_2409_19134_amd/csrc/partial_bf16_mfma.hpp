@@ -1,4 +1,4 @@
-// Partial attention over one chunk of one (user, KV head): bf16 K/V, head_dim 128, MFMA path.
+// Partial attention over one chunk of one (user, KV head): bf16 K/V, head_dim D = 128 or 64, MFMA path.
 //
 // What it computes (paper section 4.2): for each of the G query heads that share this KV head,
 //   A = softmax(s) V and lse = ln sum exp(s) over the chunk's tokens, s_i = scale * <q, k_i>,
@@ -6,27 +6,40 @@
 // combined with the n-way form of the same theorem (combine.hpp).
 //
 // Mapping onto a 64-lane wave (r = lane % 16, grp = lane / 16), 32 tokens per step:
-//   S^T = K . Q^T   two v_mfma_f32_16x16x32_bf16 chains (4 MFMAs each, 128 channels):
+//   S^T = K . Q^T   two v_mfma_f32_16x16x32_bf16 chains (D/32 MFMAs each):
 //                   the A operand is K as loaded (lane reads 16 B = 8 channels of token row r),
 //                   the B operand is Q (head r, rows >= G are zero).  The result lands with
 //                   head = r and tokens tb + grp*8 + e (e = 0..7) in each lane.
 //   softmax         online (running max m, running sum l) per lane; the max is made uniform across the
 //                   four lane groups of a head with two cross-lane exchanges per step.
-//   O^T += V^T P^T  eight MFMA pairs (one per channel phase cc): the A operand V^T needs 8 tokens of one
-//                   channel per lane; the lane loaded 8 channels of 8 tokens (16 B each, full 256 B rows
-//                   per 16 lanes), so the operand is formed in registers with v_perm_b32 (no LDS).
+//   O^T += V^T P^T  D/16 MFMA pairs (one per channel phase cc): the A operand V^T needs 8 tokens of one
+//                   channel per lane; the lane loaded D/16 channels of 8 tokens (16 B each at D = 128, 8 B
+//                   at D = 64: 16 lanes read a full row either way), so the operand is formed in registers
+//                   with v_perm_b32 (no LDS).
 //                   P is split into bf16 hi + lo so the product keeps ~16 mantissa bits.
 //                   The B operand P^T is exactly the lane's own 8 probabilities.
-// Every K/V byte is read once per KV head (all G heads share the tile) with 16-byte loads.
+// Every K/V byte is read once per KV head (all G heads share the tile).
 // The four waves of a workgroup take interleaved 32-token steps and are combined through LDS.
 #pragma once
 #include "common.hpp"
 
 namespace spd {
 
+template <int D>
+struct VRow;  // a lane's share of one V row: D/16 channels
+template <>
+struct VRow<128> {
+    typedef u32x4 type;
+};
+template <>
+struct VRow<64> {
+    typedef u32x2 type;
+};
+
+template <int D>
 struct TileRegs {
-    u32x4 k[2][4];  // [S tile a][channel block kk]: token row r of tile a, channels kk*32 + grp*8 .. +8
-    u32x4 v[8];     // [e]: token tb + grp*8 + e, channels r*8 .. +8
+    u32x4 k[2][D / 32];          // [S tile a][channel block kk]: token row r of tile a, channels kk*32 + grp*8 .. +8
+    typename VRow<D>::type v[8];  // [e]: token tb + grp*8 + e, channels r*(D/16) .. +D/16
 };
 
 struct LaneConst {
@@ -58,8 +71,8 @@ __device__ __forceinline__ PagePair load_pages(const LaneConst &L, int tb, int t
 // Issues the 16 loads of the step at tb.  Paged: P holds that step's page ids on entry and the following step's
 // (tb + step) on return: the lookup is issued behind the data loads, one whole step before it is needed, so that no
 // wave ever waits for a block-table entry before it can ask for data.
-template <bool PAGED, bool APPEND>
-__device__ __forceinline__ void load_tile(TileRegs &T, const LaneConst &L, int tb, int t_last, PagePair &P, int step)
+template <int D, bool PAGED, bool APPEND>
+__device__ __forceinline__ void load_tile(TileRegs<D> &T, const LaneConst &L, int tb, int t_last, PagePair &P, int step)
 {
     const int gk = tb + (L.r >> 2) * 8;  // first token of the 8-token group this lane's K rows fall in
     const int gv = tb + L.grp * 8;       // first token of the group this lane's V rows fall in
@@ -75,30 +88,31 @@ __device__ __forceinline__ void load_tile(TileRegs &T, const LaneConst &L, int t
         if (APPEND && L.k_new_row && t == t_last)  // the appended token is read from the caller's buffer, not the cache
             p = L.k_new_row + L.grp * 16;
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk)
+        for (int kk = 0; kk < D / 32; ++kk)
             T.k[a][kk] = stream_load16(p + kk * 64);
     }
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         const int t = min(gv + e, t_last);
-        const char *p = vp + (int64_t)(PAGED ? (t & 15) : t) * L.token_stride + L.r * 16;
+        const char *p = vp + (int64_t)(PAGED ? (t & 15) : t) * L.token_stride + L.r * (D / 8);
         if (APPEND && L.v_new_row && t == t_last)
-            p = L.v_new_row + L.r * 16;
-        T.v[e] = stream_load16(p);
+            p = L.v_new_row + L.r * (D / 8);
+        T.v[e] = stream_load<typename VRow<D>::type>(p);
     }
     if (PAGED)
         P = load_pages(L, tb + step, t_last);
-    // all 16 loads of the step are issued before anything that follows: without this the compiler sinks the V loads
+    // all loads of the step are issued before anything that follows: without this the compiler sinks the V loads
     // below the K wait to shorten live ranges, which serialises two memory round trips per step
     __builtin_amdgcn_sched_barrier(0);
 }
 
-__device__ __forceinline__ void compute_tile(const TileRegs &T, const bf16x8 (&qB)[4], int tb, int grp, int t_end,
-                                             float c, float &m, float &l, f32x4 (&acc)[8])
+template <int D>
+__device__ __forceinline__ void compute_tile(const TileRegs<D> &T, const bf16x8 (&qB)[D / 32], int tb, int grp, int t_end,
+                                             float c, float &m, float &l, f32x4 (&acc)[D / 16])
 {
     f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
+    for (int kk = 0; kk < D / 32; ++kk) {
         s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, T.k[0][kk]), qB[kk], s0, 0, 0, 0);
         s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, T.k[1][kk]), qB[kk], s1, 0, 0, 0);
     }
@@ -125,7 +139,7 @@ __device__ __forceinline__ void compute_tile(const TileRegs &T, const bf16x8 (&q
     m = m_new;
     if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {  // wave-uniform: rescale only when some max moved
 #pragma unroll
-        for (int cc = 0; cc < 8; ++cc)
+        for (int cc = 0; cc < D / 16; ++cc)
             acc[cc] *= alpha;
     }
     bf16x8 ph, pl;
@@ -135,7 +149,7 @@ __device__ __forceinline__ void compute_tile(const TileRegs &T, const bf16x8 (&q
         pl[e] = (__bf16)(p[e] - (float)ph[e]);
     }
 #pragma unroll
-    for (int cc = 0; cc < 8; ++cc) {
+    for (int cc = 0; cc < D / 16; ++cc) {
         const int w = cc >> 1;
         const unsigned sel = (cc & 1) ? 0x07060302u : 0x05040100u;  // odd channel: high halves, even: low halves
         u32x4 vt;
@@ -148,16 +162,21 @@ __device__ __forceinline__ void compute_tile(const TileRegs &T, const bf16x8 (&q
     }
 }
 
-constexpr int kOStride = 132;  // LDS row stride (floats) of one head's 128 channels: bank = 4*r + grp, conflict free
+// LDS row stride (floats) of one head's D channels: the four extra floats spread the heads over the banks
+__host__ __device__ constexpr int o_stride(int D) { return D + 4; }
 
 // LDS bytes of the result staging tiles of a workgroup of `waves` waves, and whether the head-per-wave mapping can have
 // them (kernel and launch use the same rule; 64 KB is what a workgroup may ask for without special attributes).
-__host__ __device__ constexpr size_t staging_bytes(int waves, int G) { return sizeof(float) * (size_t)waves * G * kOStride; }
-__host__ __device__ constexpr bool staging_fits(int waves, int G) { return staging_bytes(waves, G) <= 64 * 1024; }
+__host__ __device__ constexpr size_t staging_bytes(int D, int waves, int G)
+{
+    return sizeof(float) * (size_t)waves * G * o_stride(D);
+}
+__host__ __device__ constexpr bool staging_fits(int D, int waves, int G) { return staging_bytes(D, waves, G) <= 64 * 1024; }
 
-// One workgroup per piece (see DevItem); q: [U][Hq][128] bf16.  A segment that is its row's only one writes out/lse
-// directly; otherwise it writes part_o[slot][G][128] / part_lse[slot][G], which combine_chunks_kernel then reduces.
+// One workgroup per piece (see DevItem); q: [U][Hq][D] bf16.  A segment that is its row's only one writes out/lse
+// directly; otherwise it writes part_o[slot][G][D] / part_lse[slot][G], which combine_chunks_kernel then reduces.
 //
+// (Register counts below are those of D = 128; D = 64 needs about half and always runs with PREFETCH.)
 // PREFETCH = true keeps two 32-token steps of loads in flight per wave (~245 VGPRs, two waves per SIMD): for launches
 // that run several rounds of workgroups, and for small ones that fit two per CU anyway (half as many dependent round
 // trips per wave).  PREFETCH = false holds one step (~160 VGPRs, three waves per SIMD): as fast when the private
@@ -172,8 +191,8 @@ __host__ __device__ constexpr bool staging_fits(int waves, int G) { return stagi
 // a token range of one (user, KV head) row and its four waves take interleaved steps.
 //
 // APPEND = true adds the KV append (the address substitution costs ~1 % when nothing is appended, hence a flag).
-template <bool PAGED, bool PREFETCH, bool HPW, bool APPEND>
-__global__ __launch_bounds__(HPW ? 512 : kThreads, PREFETCH ? 2 : 3) void partial_bf16_d128_kernel(
+template <int D, bool PAGED, bool PREFETCH, bool HPW, bool APPEND>
+__global__ __launch_bounds__(HPW ? 512 : kThreads, D == 128 && !PREFETCH ? 3 : 2 + (D == 64 && !HPW)) void partial_bf16_kernel(
     OwnerArgs a0, OwnerArgs a1, int n0, const uint16_t *__restrict__ q, int Hq, int G, float scale_log2e)
 {
     const bool second = (int)blockIdx.x >= n0;  // workgroup-uniform: which owner this workgroup serves
@@ -192,9 +211,12 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, PREFETCH ? 2 : 3) void partia
     __shared__ float sm_m[kWaves][16];
     __shared__ float sm_l[kWaves][16];
     extern __shared__ float sm_o[];  // [waves][G * kOStride], sized by the launch: only G heads are staged
+    constexpr int kOStride = o_stride(D);
+    constexpr int CP = D / 16;  // channel phases of the O^T tile: a lane holds CP consecutive channels per accumulator row
+    constexpr int kRowBytes = D * 2;
     const int o_wave_stride = G * kOStride;
     // head-per-wave results go through a wave-private tile if the launch gave the room
-    const bool staged = HPW && staging_fits((int)(blockDim.x >> 6), G);
+    const bool staged = HPW && staging_fits(D, (int)(blockDim.x >> 6), G);
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -203,7 +225,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, PREFETCH ? 2 : 3) void partia
     // Everything a segment needs before its first MFMA: addresses, the KV append copy, Q, and the loads of the wave's
     // first 32-token step.  Issued for the *next* segment before the current one's epilogue, so that the barriers
     // and the result stores of the epilogue overlap the memory round trip instead of preceding it.
-    auto begin_segment = [&](const DevItem &it, LaneConst &L, bf16x8 (&qB)[4], int &tb, TileRegs &T0, PagePair &P) {
+    auto begin_segment = [&](const DevItem &it, LaneConst &L, bf16x8 (&qB)[D / 32], int &tb, TileRegs<D> &T0, PagePair &P) {
         L.r = lane & 15;
         L.grp = lane >> 4;
         L.token_stride = kv.token_stride;
@@ -216,25 +238,26 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, PREFETCH ? 2 : 3) void partia
         L.k_new_row = L.v_new_row = nullptr;
         if (APPEND && k_new && (it.rot & kEndsRow)) {
             // KV append: this segment holds the row's last token, which is the new one.  Wave 0 copies its K and V
-            // rows into the cache (lanes 0-15: K, 16-31: V); every reader of that token takes it from the caller's
-            // buffer instead, so nothing waits for the copy.
-            const int64_t row = ((int64_t)it.user * (Hq / G) + kv_head) * 256;
+            // rows into the cache (16 bytes per lane, K in the first lanes, V in the next); every reader of that token
+            // takes it from the caller's buffer instead, so nothing waits for the copy.
+            constexpr int kRowLanes = kRowBytes / 16;
+            const int64_t row = ((int64_t)it.user * (Hq / G) + kv_head) * kRowBytes;
             L.k_new_row = k_new + row;
             L.v_new_row = v_new + row;
-            if ((HPW || wave == 0) && lane < 32) {
-                int64_t off = (int64_t)(PAGED ? (t_last & 15) : t_last) * kv.token_stride + (lane & 15) * 16;
+            if ((HPW || wave == 0) && lane < 2 * kRowLanes) {
+                int64_t off = (int64_t)(PAGED ? (t_last & 15) : t_last) * kv.token_stride + (lane % kRowLanes) * 16;
                 if (PAGED)
                     off += (int64_t)scalar_load_i32(L.bt_row, t_last >> 4) * kv.block_stride;
-                if (lane < 16)
+                if (lane < kRowLanes)
                     copy16(const_cast<char *>(L.k_base) + off, L.k_new_row + lane * 16);
                 else
-                    copy16(const_cast<char *>(L.v_base) + off, L.v_new_row + (lane - 16) * 16);
+                    copy16(const_cast<char *>(L.v_base) + off, L.v_new_row + (lane - kRowLanes) * 16);
             }
         }
         // Q as the B operand: head r (zero beyond G), channels kk*32 + grp*8 .. +8
-        const uint16_t *qrow = q + ((int64_t)it.user * Hq + (int64_t)kv_head * G + L.r) * 128 + L.grp * 8;
+        const uint16_t *qrow = q + ((int64_t)it.user * Hq + (int64_t)kv_head * G + L.r) * D + L.grp * 8;
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
+        for (int kk = 0; kk < D / 32; ++kk) {
             u32x4 w = {0u, 0u, 0u, 0u};
             if (L.r < G)
                 w = *reinterpret_cast<const u32x4 *>(qrow + kk * 32);
@@ -245,26 +268,26 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, PREFETCH ? 2 : 3) void partia
         if (PAGED)
             P = load_pages(L, tb, t_last);
         if (PREFETCH && tb < it.t_end)
-            load_tile<PAGED, APPEND>(T0, L, tb, t_last, P, kStep);
+            load_tile<D, PAGED, APPEND>(T0, L, tb, t_last, P, kStep);
     };
 
     DevItem it = scalar_load_item(items, second ? (int)blockIdx.x - n0 : (int)blockIdx.x);
     if (it.n_chunks == 0) {  // a row without tokens (head-per-wave: a user without tokens) is a piece of its own
         if (HPW) {
             const int64_t head0 = (int64_t)it.user * Hq + (int64_t)(it.kv_head + wave) * G;
-            for (int idx = lane; idx < G * 128; idx += 64)
-                out[head0 * 128 + idx] = 0.f;
+            for (int idx = lane; idx < G * D; idx += 64)
+                out[head0 * D + idx] = 0.f;
             if (lane < G)
                 lse[head0 + lane] = -INFINITY;
         } else {
-            write_empty_row<128>(it, G, Hq, out, lse);
+            write_empty_row<D>(it, G, Hq, out, lse);
         }
         return;
     }
     LaneConst L;
-    bf16x8 qB[4];
+    bf16x8 qB[D / 32];
     int tb;
-    TileRegs T0;
+    TileRegs<D> T0;
     PagePair P = {0, 0};
     begin_segment(it, L, qB, tb, T0, P);
     for (;;) {
@@ -276,20 +299,20 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, PREFETCH ? 2 : 3) void partia
         const int t_last = it.t_end - 1;
 
         float m = -INFINITY, l = 0.f;
-        f32x4 acc[8];
+        f32x4 acc[CP];
 #pragma unroll
-        for (int cc = 0; cc < 8; ++cc)
+        for (int cc = 0; cc < CP; ++cc)
             acc[cc] = f32x4{0.f, 0.f, 0.f, 0.f};
 
         if (!PREFETCH) {
             for (; tb < it.t_end; tb += kStep) {
-                TileRegs T;
-                load_tile<PAGED, APPEND>(T, L, tb, t_last, P, kStep);
-                compute_tile(T, qB, tb, L.grp, it.t_end, scale_log2e, m, l, acc);
+                TileRegs<D> T;
+                load_tile<D, PAGED, APPEND>(T, L, tb, t_last, P, kStep);
+                compute_tile<D>(T, qB, tb, L.grp, it.t_end, scale_log2e, m, l, acc);
             }
         } else if (tb < it.t_end) {  // T0 already holds (the loads of) step tb
             {
-                TileRegs T1;
+                TileRegs<D> T1;
                 for (;;) {
                     const int tb1 = tb + kStep;
                     const bool more1 = tb1 < it.t_end;
@@ -298,8 +321,8 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, PREFETCH ? 2 : 3) void partia
                     if (HPW)
                         __builtin_amdgcn_s_barrier();
                     if (more1)
-                        load_tile<PAGED, APPEND>(T1, L, tb1, t_last, P, kStep);
-                    compute_tile(T0, qB, tb, L.grp, it.t_end, scale_log2e, m, l, acc);
+                        load_tile<D, PAGED, APPEND>(T1, L, tb1, t_last, P, kStep);
+                    compute_tile<D>(T0, qB, tb, L.grp, it.t_end, scale_log2e, m, l, acc);
                     if (!more1)
                         break;
                     const int tb2 = tb1 + kStep;
@@ -307,8 +330,8 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, PREFETCH ? 2 : 3) void partia
                     if (HPW)
                         __builtin_amdgcn_s_barrier();
                     if (more2)
-                        load_tile<PAGED, APPEND>(T0, L, tb2, t_last, P, kStep);
-                    compute_tile(T1, qB, tb1, L.grp, it.t_end, scale_log2e, m, l, acc);
+                        load_tile<D, PAGED, APPEND>(T0, L, tb2, t_last, P, kStep);
+                    compute_tile<D>(T1, qB, tb1, L.grp, it.t_end, scale_log2e, m, l, acc);
                     if (!more2)
                         break;
                     tb = tb2;
@@ -327,42 +350,42 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, PREFETCH ? 2 : 3) void partia
         const bool direct = it.n_chunks == 1;
         if (HPW) {
             // ... and that is all: the wave owns head `wave` of this token range.  Lane (r < G, grp) holds channels
-            // (4*grp + v)*8 + cc of query head r: eight consecutive floats per v.
+            // (4*grp + v)*CP + cc of query head r: CP consecutive floats per v.
             const int kvh = it.kv_head + uniform(wave);
             const int64_t head0 = (int64_t)it.user * Hq + (int64_t)kvh * G;
             const int64_t slot = (int64_t)it.slot + (int64_t)uniform(wave) * it.n_chunks;  // it.slot: the group's first head
             const float inv = fast_rcp(l);  // l > 0: the segment holds at least one token
-            float *res = direct ? out + head0 * 128 : part_o + slot * G * 128;  // [G][128], contiguous
+            float *res = direct ? out + head0 * D : part_o + slot * G * D;  // [G][D], contiguous
             if (staged) {
                 // Through a wave-private LDS tile, so that the wave stores whole rows with consecutive lanes (storing
                 // straight from the accumulator layout puts 16 bytes per lane into 16 different cache lines per
                 // instruction; measured 2-3 % of the kernel on long token-major workloads).
                 float *stage = sm_o + wave * o_wave_stride;
                 if (r < G) {
-                    float *dst = stage + r * kOStride + grp * 32;
+                    float *dst = stage + r * kOStride + grp * 4 * CP;
 #pragma unroll
-                    for (int cc = 0; cc < 8; ++cc)
+                    for (int cc = 0; cc < CP; ++cc)
 #pragma unroll
                         for (int v = 0; v < 4; ++v)
-                            dst[v * 8 + cc] = acc[cc][v] * inv;  // channel (4*grp + v)*8 + cc
+                            dst[v * CP + cc] = acc[cc][v] * inv;  // channel (4*grp + v)*CP + cc
                 }
                 __builtin_amdgcn_wave_barrier();  // same wave: LDS executes its writes before its reads
-                for (int i = lane * 4; i < G * 128; i += 256) {
-                    const f32x4 w = *reinterpret_cast<const f32x4 *>(stage + (i >> 7) * kOStride + (i & 127));
+                for (int i = lane * 4; i < G * D; i += 256) {
+                    const f32x4 w = *reinterpret_cast<const f32x4 *>(stage + (i / D) * kOStride + (i % D));
                     *reinterpret_cast<f32x4 *>(res + i) = w;
                 }
                 __builtin_amdgcn_wave_barrier();
             }
             if (r < G) {
                 if (!staged) {
-                    float *dst = res + r * 128 + grp * 32;
+                    float *dst = res + r * D + grp * 4 * CP;
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        f32x4 lo = {acc[0][v] * inv, acc[1][v] * inv, acc[2][v] * inv, acc[3][v] * inv};
-                        f32x4 hi = {acc[4][v] * inv, acc[5][v] * inv, acc[6][v] * inv, acc[7][v] * inv};
-                        *reinterpret_cast<f32x4 *>(dst + v * 8) = lo;
-                        *reinterpret_cast<f32x4 *>(dst + v * 8 + 4) = hi;
-                    }
+                    for (int v = 0; v < 4; ++v)
+#pragma unroll
+                        for (int c4 = 0; c4 < CP; c4 += 4) {
+                            const f32x4 w = {acc[c4][v] * inv, acc[c4 + 1][v] * inv, acc[c4 + 2][v] * inv, acc[c4 + 3][v] * inv};
+                            *reinterpret_cast<f32x4 *>(dst + v * CP + c4) = w;
+                        }
                 }
                 if (grp == 0) {
                     const float ls = (m + fast_log2(l)) * kLn2;  // m is in log2 units
@@ -392,18 +415,18 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, PREFETCH ? 2 : 3) void partia
             M = fmaxf(M, sm_m[w][r]);
         const float f = fast_exp2(m - M);  // some wave holds tokens, so M is finite; an idle wave has m = -inf, f = 0
         if (r < G) {
-            float *dst = &sm_o[wave * o_wave_stride + r * kOStride + grp * 32];
+            float *dst = &sm_o[wave * o_wave_stride + r * kOStride + grp * 4 * CP];
 #pragma unroll
-            for (int cc = 0; cc < 8; ++cc)
+            for (int cc = 0; cc < CP; ++cc)
 #pragma unroll
                 for (int v = 0; v < 4; ++v)
-                    dst[v * 8 + cc] = acc[cc][v] * f;  // channel (4*grp + v)*8 + cc
+                    dst[v * CP + cc] = acc[cc][v] * f;  // channel (4*grp + v)*CP + cc
         }
         __syncthreads();
 
         const int64_t head0 = (int64_t)it.user * Hq + (int64_t)it.kv_head * G;
-        for (int idx = threadIdx.x; idx < G * 128; idx += kThreads) {
-            const int g = idx >> 7, ch = idx & 127;
+        for (int idx = threadIdx.x; idx < G * D; idx += kThreads) {
+            const int g = idx / D, ch = idx % D;
             float Mg = sm_m[0][g];
 #pragma unroll
             for (int w = 1; w < kWaves; ++w)
@@ -416,9 +439,9 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, PREFETCH ? 2 : 3) void partia
             }
             const float a = o * fast_rcp(lt);
             if (direct)
-                out[(head0 + g) * 128 + ch] = a;
+                out[(head0 + g) * D + ch] = a;
             else
-                part_o[((int64_t)it.slot * G + g) * 128 + ch] = a;
+                part_o[((int64_t)it.slot * G + g) * D + ch] = a;
             if (ch == 0) {
                 const float ls = (Mg + fast_log2(lt)) * kLn2;  // Mg is in log2 units
                 if (direct)

@@ -1,10 +1,8 @@
-// Partial attention over one chunk of one (user, KV head): vector-ALU path.  It serves fp32 inputs (head_dim 64 or
-// 128), whose products must be formed in fp32, and bf16 inputs of head_dim 64 (widened to fp32 on load, which is
-// exact); bf16 with head_dim 128 has the MFMA kernel.
+// Partial attention over one chunk of one (user, KV head): vector-ALU path for fp32 inputs
+// (head_dim 64 or 128) where products must be formed in fp32 and the tile is too thin for MFMA.
 //
 // Computes the same quantity as the MFMA kernel (paper section 4.2: A = softmax(s) V and
-// lse = ln sum exp(s) over a token range).  A row of D channels is covered by LPR lanes of 16 bytes each (EPL = 4
-// fp32 or 8 bf16 elements),
+// lse = ln sum exp(s) over a token range).  A row of D channels is covered by LPR = D/4 lanes (16 bytes each),
 // so one wave reads 64/LPR full rows per load; every lane group keeps its own online-softmax state
 // (m, l, acc) for the G query heads of the KV head and the groups are merged at the end with the
 // n-way form of Theorem 1 (first across lane groups by cross-lane exchanges, then across waves in LDS).
@@ -13,28 +11,9 @@
 
 namespace spd {
 
-// A 16-byte load widened to fp32: four floats as they are, or eight bf16 (an fp32's upper half each).
-template <bool BF16>
-__device__ __forceinline__ void load_row16(const char *p, float (&x)[BF16 ? 8 : 4])
-{
-    if constexpr (BF16) {
-        const u32x4 w = *reinterpret_cast<const u32x4 *>(p);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            x[2 * i] = __uint_as_float(w[i] << 16);
-            x[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
-        }
-    } else {
-        const f32x4 w = *reinterpret_cast<const f32x4 *>(p);
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            x[i] = w[i];
-    }
-}
-
-template <bool BF16, int D, int G>
-__global__ __launch_bounds__(kThreads) void partial_valu_kernel(
-    OwnerArgs a0, OwnerArgs a1, int n0, const char *__restrict__ q, int Hq, float scale_log2e)
+template <int D, int G>
+__global__ __launch_bounds__(kThreads) void partial_f32_kernel(
+    OwnerArgs a0, OwnerArgs a1, int n0, const float *__restrict__ q, int Hq, float scale_log2e)
 {
     const bool second = (int)blockIdx.x >= n0;  // workgroup-uniform: which owner this workgroup serves
     const DevItem *__restrict__ items = second ? a1.items : a0.items;
@@ -49,9 +28,8 @@ __global__ __launch_bounds__(kThreads) void partial_valu_kernel(
     float *__restrict__ lse = second ? a1.lse : a0.lse;
     const char *k_new = second ? a1.k_new : a0.k_new;
     const char *v_new = second ? a1.v_new : a0.v_new;
-    constexpr int ES = BF16 ? 2 : 4;  // bytes per element
-    constexpr int EPL = 16 / ES;    // elements per 16-byte lane load
-    constexpr int LPR = D / EPL;    // lanes per row: 8 (bf16, D=64), 16 or 32
+    constexpr int EPL = 4;          // fp32 elements per 16-byte lane load
+    constexpr int LPR = D / EPL;    // lanes per row: 16 (D=64) or 32 (D=128)
     constexpr int RPW = 64 / LPR;   // rows per wave per step
     __shared__ float sm_m[kWaves][G];
     __shared__ float sm_l[kWaves][G];
@@ -68,7 +46,7 @@ __global__ __launch_bounds__(kThreads) void partial_valu_kernel(
         }
         const int lane = threadIdx.x & 63;
         const int wave = threadIdx.x >> 6;
-        const int cl = lane % LPR;      // which 16-byte slice of the row
+        const int cl = lane % LPR;      // which 4-channel slice of the row
         const int rs = lane / LPR;      // which row of the step
 
         const bool paged = kv.block_table != nullptr;
@@ -78,8 +56,13 @@ __global__ __launch_bounds__(kThreads) void partial_valu_kernel(
 
         float qr[G][EPL];
 #pragma unroll
-        for (int g = 0; g < G; ++g)
-            load_row16<BF16>(q + (((int64_t)it.user * Hq + (int64_t)it.kv_head * G + g) * D + cl * EPL) * ES, qr[g]);
+        for (int g = 0; g < G; ++g) {
+            const f32x4 w = *reinterpret_cast<const f32x4 *>(
+                q + ((int64_t)it.user * Hq + (int64_t)it.kv_head * G + g) * D + cl * EPL);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e)
+                qr[g][e] = w[e];
+        }
 
         float m[G], l[G], acc[G][EPL];
 #pragma unroll
@@ -96,7 +79,7 @@ __global__ __launch_bounds__(kThreads) void partial_valu_kernel(
         // the cache (lanes [0, LPR): K, [LPR, 2*LPR): V; 2*LPR <= 64)
         const char *k_new_row = nullptr, *v_new_row = nullptr;
         if (k_new && (it.rot & kEndsRow)) {
-            const int64_t row = ((int64_t)it.user * (Hq / G) + it.kv_head) * D * ES;
+            const int64_t row = ((int64_t)it.user * (Hq / G) + it.kv_head) * D * 4;
             k_new_row = k_new + row;
             v_new_row = v_new + row;
             if (wave == 0 && lane < 2 * LPR) {
@@ -113,7 +96,7 @@ __global__ __launch_bounds__(kThreads) void partial_valu_kernel(
         // latency-bound, so what counts is the number of dependent memory round trips per wave
         constexpr int kUnroll = 4;
         for (int tb = it.t_begin + wave * RPW; tb < it.t_end; tb += RPW * kWaves * kUnroll) {
-            float kk[kUnroll][EPL], vv[kUnroll][EPL];
+            f32x4 kk[kUnroll], vv[kUnroll];
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
                 const int tc = min(tb + u * RPW * kWaves + rs, t_last);  // rows past the chunk re-read its last token
@@ -124,8 +107,8 @@ __global__ __launch_bounds__(kThreads) void partial_valu_kernel(
                     off = (int64_t)tc * kv.token_stride;
                 off += cl * 16;
                 const bool is_new = k_new_row && tc == t_last;
-                load_row16<BF16>(is_new ? k_new_row + cl * 16 : k_base + off, kk[u]);
-                load_row16<BF16>(is_new ? v_new_row + cl * 16 : v_base + off, vv[u]);
+                kk[u] = *reinterpret_cast<const f32x4 *>(is_new ? k_new_row + cl * 16 : k_base + off);
+                vv[u] = *reinterpret_cast<const f32x4 *>(is_new ? v_new_row + cl * 16 : v_base + off);
             }
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
@@ -133,9 +116,9 @@ __global__ __launch_bounds__(kThreads) void partial_valu_kernel(
 #pragma unroll
                 for (int g = 0; g < G; ++g) {
                     float s = qr[g][0] * kk[u][0];
-#pragma unroll
-                    for (int e = 1; e < EPL; ++e)
-                        s = fmaf(qr[g][e], kk[u][e], s);
+                    s = fmaf(qr[g][1], kk[u][1], s);
+                    s = fmaf(qr[g][2], kk[u][2], s);
+                    s = fmaf(qr[g][3], kk[u][3], s);
 #pragma unroll
                     for (int o = 1; o < LPR; o <<= 1)
                         s += __shfl_xor(s, o);          // all LPR lanes of the row end up with the full dot product

@@ -111,7 +111,7 @@ void free_entry(CachedSchedule &e)
 // kernel: one wave per KV head, all waves on the same tokens.
 bool head_per_wave_layout(const spd_shape *s, const spd_kv_view *v)
 {
-    return s->dtype == SPD_BF16 && s->head_dim == 128 && head_per_wave_waves(s->n_kv_heads) > 1 &&
+    return s->dtype == SPD_BF16 && head_per_wave_waves(s->n_kv_heads) > 1 &&
            !(v->head_strides && v->block_size == 0) && v->head_stride == s->head_dim &&
            v->token_stride >= (int64_t)s->n_kv_heads * s->head_dim;
 }
@@ -353,27 +353,27 @@ int ensure_scratch(spd_ctx *ctx, Owner &own, size_t o_floats, size_t lse_floats)
 }
 
 // ev0 / ev1 (both null unless timing is armed) receive the kernel's own start and stop time stamps.
-template <bool BF16, int D, int G>
-void launch_valu(dim3 grid, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1, const OwnerArgs &a0,
-                 const OwnerArgs &a1, int n0, const void *q, int Hq, float c)
+template <int D, int G>
+void launch_f32(dim3 grid, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1, const OwnerArgs &a0,
+                const OwnerArgs &a1, int n0, const void *q, int Hq, float c)
 {
-    hipExtLaunchKernelGGL((spd::partial_valu_kernel<BF16, D, G>), grid, dim3(spd::kThreads), 0, stream, ev0, ev1, 0, a0,
-                          a1, n0, static_cast<const char *>(q), Hq, c);
+    hipExtLaunchKernelGGL((spd::partial_f32_kernel<D, G>), grid, dim3(spd::kThreads), 0, stream, ev0, ev1, 0, a0, a1, n0,
+                          static_cast<const float *>(q), Hq, c);
 }
 
-template <bool BF16, int D>
-void launch_valu_g(int G, dim3 grid, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1, const OwnerArgs &a0,
-                   const OwnerArgs &a1, int n0, const void *q, int Hq, float c)
+template <int D>
+void launch_f32_g(int G, dim3 grid, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1, const OwnerArgs &a0,
+                  const OwnerArgs &a1, int n0, const void *q, int Hq, float c)
 {
     switch (G) {  // validate_shape admits 1..8
-    case 1: launch_valu<BF16, D, 1>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
-    case 2: launch_valu<BF16, D, 2>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
-    case 3: launch_valu<BF16, D, 3>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
-    case 4: launch_valu<BF16, D, 4>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
-    case 5: launch_valu<BF16, D, 5>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
-    case 6: launch_valu<BF16, D, 6>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
-    case 7: launch_valu<BF16, D, 7>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
-    default: launch_valu<BF16, D, 8>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
+    case 1: launch_f32<D, 1>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
+    case 2: launch_f32<D, 2>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
+    case 3: launch_f32<D, 3>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
+    case 4: launch_f32<D, 4>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
+    case 5: launch_f32<D, 5>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
+    case 6: launch_f32<D, 6>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
+    case 7: launch_f32<D, 7>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
+    default: launch_f32<D, 8>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
     }
 }
 
@@ -447,52 +447,58 @@ int launch_partial(spd_ctx *ctx, int which, const CachedSchedule *e0, const spd_
     const hipEvent_t ev0 = timed ? town.ev_start[town.ev_used] : nullptr;
     const hipEvent_t ev1 = timed ? town.ev_stop[town.ev_used] : nullptr;
     const dim3 grid((unsigned)(n0 + n1));
-    if (s->dtype == SPD_BF16 && s->head_dim == 128) {
+    if (s->dtype == SPD_BF16) {
         const uint16_t *qh = static_cast<const uint16_t *>(q);
         const bool hpw = e0->hpw;  // a two-owner launch needs the same mapping on both sides (checked by the caller)
         const int waves = hpw ? head_per_wave_waves(s->n_kv_heads) : spd::kWaves;
         // cross-wave staging; head-per-wave stages its per-wave results too if that fits (the kernel applies the same rule)
-        const size_t lds = (hpw && !spd::staging_fits(waves, G)) ? 0 : spd::staging_bytes(waves, G);
+        const int D = s->head_dim;
+        const size_t lds = (hpw && !spd::staging_fits(D, waves, G)) ? 0 : spd::staging_bytes(D, waves, G);
         const dim3 blk(hpw ? 64u * (unsigned)waves : (unsigned)spd::kThreads);
         // clearly more pieces than the three-per-CU kernel holds at once (a few left over just start a little
         // later): use the prefetching two-per-CU kernel.  Also when all pieces fit two per CU anyway: a wave then
         // needs half as many dependent memory round trips (short rows taken whole are latency-bound).
         // Head-per-wave workgroups fit one per CU either way.
         const int64_t cus = std::max(1, ctx->n_cus);
-        const bool prefetch = hpw || n0 + n1 > cus * 4 || n0 + n1 <= cus * 2;
-#define SPD_LAUNCH_BF16_A(PAGED, PREFETCH, HPW, APPEND)                                                              \
-    hipExtLaunchKernelGGL((spd::partial_bf16_d128_kernel<PAGED, PREFETCH, HPW, APPEND>), grid, blk, (uint32_t)lds,     \
+        // With 64 channels a step is half the bytes: always two in flight.
+        const bool prefetch = hpw || D == 64 || n0 + n1 > cus * 4 || n0 + n1 <= cus * 2;
+#define SPD_LAUNCH_BF16_A(D, PAGED, PREFETCH, HPW, APPEND)                                                           \
+    hipExtLaunchKernelGGL((spd::partial_bf16_kernel<D, PAGED, PREFETCH, HPW, APPEND>), grid, blk, (uint32_t)lds,      \
                           stream, ev0, ev1, 0, a0, a1, (int)n0, qh, s->n_q_heads, G, c)
-#define SPD_LAUNCH_BF16(PAGED, PREFETCH, HPW)                                                                         \
+#define SPD_LAUNCH_BF16(D, PAGED, PREFETCH, HPW)                                                                      \
     do {                                                                                                             \
         if (nt.k)                                                                                                    \
-            SPD_LAUNCH_BF16_A(PAGED, PREFETCH, HPW, true);                                                           \
+            SPD_LAUNCH_BF16_A(D, PAGED, PREFETCH, HPW, true);                                                        \
         else                                                                                                         \
-            SPD_LAUNCH_BF16_A(PAGED, PREFETCH, HPW, false);                                                          \
+            SPD_LAUNCH_BF16_A(D, PAGED, PREFETCH, HPW, false);                                                       \
     } while (0)
-        if (v0->block_size) {
-            if (hpw)
-                SPD_LAUNCH_BF16(true, true, true);
-            else if (prefetch)
-                SPD_LAUNCH_BF16(true, true, false);
+#define SPD_LAUNCH_BF16_P(D, PAGED)                                                                                  \
+    do {                                                                                                             \
+        if (hpw)                                                                                                     \
+            SPD_LAUNCH_BF16(D, PAGED, true, true);                                                                   \
+        else if (prefetch)                                                                                           \
+            SPD_LAUNCH_BF16(D, PAGED, true, false);                                                                  \
+        else if (D == 128)                                                                                           \
+            SPD_LAUNCH_BF16(128, PAGED, false, false);                                                               \
+    } while (0)
+        if (D == 128) {
+            if (v0->block_size)
+                SPD_LAUNCH_BF16_P(128, true);
             else
-                SPD_LAUNCH_BF16(true, false, false);
+                SPD_LAUNCH_BF16_P(128, false);
         } else {
-            if (hpw)
-                SPD_LAUNCH_BF16(false, true, true);
-            else if (prefetch)
-                SPD_LAUNCH_BF16(false, true, false);
+            if (v0->block_size)
+                SPD_LAUNCH_BF16_P(64, true);
             else
-                SPD_LAUNCH_BF16(false, false, false);
+                SPD_LAUNCH_BF16_P(64, false);
         }
 #undef SPD_LAUNCH_BF16_A
 #undef SPD_LAUNCH_BF16
-    } else if (s->dtype == SPD_BF16) {
-        launch_valu_g<true, 64>(G, grid, stream, ev0, ev1, a0, a1, (int)n0, q, s->n_q_heads, c);
+#undef SPD_LAUNCH_BF16_P
     } else if (s->head_dim == 64) {
-        launch_valu_g<false, 64>(G, grid, stream, ev0, ev1, a0, a1, (int)n0, q, s->n_q_heads, c);
+        launch_f32_g<64>(G, grid, stream, ev0, ev1, a0, a1, (int)n0, q, s->n_q_heads, c);
     } else {
-        launch_valu_g<false, 128>(G, grid, stream, ev0, ev1, a0, a1, (int)n0, q, s->n_q_heads, c);
+        launch_f32_g<128>(G, grid, stream, ev0, ev1, a0, a1, (int)n0, q, s->n_q_heads, c);
     }
     SPD_HIP(ctx, hipGetLastError());
     if (timed)

@@ -59,7 +59,7 @@ def test_validation_accepts_good_arguments():
     assert _check(sh, paged) == spd.SPD_OK
     assert _check(spd.make_shape(spd.SPD_F32, 8, 8, 64, 0.125), _view([128], token_stride=512, head_stride=64)) == spd.SPD_OK
     assert _check(spd.make_shape(spd.SPD_F32, 6, 2, 128, 0.1), _view([128])) == spd.SPD_OK          # group of 3 heads
-    assert _check(spd.make_shape(spd.SPD_BF16, 56, 8, 64, 0.125), _view([128], token_stride=512, head_stride=64)) == spd.SPD_OK
+    assert _check(spd.make_shape(spd.SPD_BF16, 128, 8, 64, 0.125), _view([128], token_stride=512, head_stride=64)) == spd.SPD_OK
 
 
 @pytest.mark.parametrize("args,code", [
@@ -67,7 +67,6 @@ def test_validation_accepts_good_arguments():
     (dict(Hq=30), spd.SPD_ERR_SHAPE),                   # Hq % Hkv != 0
     (dict(d=96), spd.SPD_ERR_SHAPE),
     (dict(Hq=256, Hkv=8), spd.SPD_ERR_SHAPE),           # group of 32 heads
-    (dict(Hq=128, Hkv=8, d=64), spd.SPD_ERR_SHAPE),     # group of 16 heads off the matrix-core path
     (dict(Hq=72, Hkv=8, dtype=spd.SPD_F32), spd.SPD_ERR_SHAPE),   # group of 9 heads in fp32
     (dict(scale=float("nan")), spd.SPD_ERR_SHAPE),
 ])

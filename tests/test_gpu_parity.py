@@ -263,13 +263,24 @@ def test_fp32_shapes(ctx, d, Hq, Hkv, paged):
 
 @pytest.mark.parametrize("dtype,d,Hq,Hkv", [
     (torch.bfloat16, 64, 32, 8), (torch.bfloat16, 64, 8, 8), (torch.bfloat16, 64, 12, 2), (torch.bfloat16, 64, 14, 2),
-    (torch.bfloat16, 64, 3, 1), (torch.bfloat16, 64, 40, 8),
+    (torch.bfloat16, 64, 3, 1), (torch.bfloat16, 64, 40, 8), (torch.bfloat16, 64, 64, 4), (torch.bfloat16, 64, 16, 16),
     (torch.float32, 64, 9, 3), (torch.float32, 128, 5, 1), (torch.float32, 64, 12, 2), (torch.float32, 128, 14, 2)])
-@pytest.mark.parametrize("storage", ["hnd", "nhd", "paged", "paged_tm"])
-def test_vector_path_shapes(ctx, dtype, d, Hq, Hkv, storage):
-    """bf16 with 64 channels and the head groups 3, 5, 6, 7: the shapes that take the vector kernel beside fp32's own."""
+@pytest.mark.parametrize("storage", ["hnd", "nhd", "nhd_hpw", "paged", "paged_tm", "paged_tm_hpw"])
+def test_small_head_dim_and_odd_groups(ctx, mapping_of, dtype, d, Hq, Hkv, storage):
+    """bf16 with 64 channels per head (every storage mode and mapping), and fp32 head groups of 3, 5, 6 and 7."""
+    storage = mapping_of(storage)
     paged = {"paged": True, "paged_tm": "token_major"}.get(storage, False)
     wl = workloads.random_case(108, dtype, 5, Hq, Hkv, d, [128, 0, 1000, 3, 2500], [16, 5, 0, 77, 300], device=DEV,
+                               layout="nhd" if paged else storage, paged=paged)
+    check_against_oracle(ctx, wl)
+
+
+@pytest.mark.parametrize("lp,lo", [(0, 0), (1, 0), (31, 33), (32, 64), (127, 129), (4097, 1), (20000, 700)])
+@pytest.mark.parametrize("storage", ["hnd", "nhd_hpw", "paged"])
+def test_bf16_d64_edge_lengths(ctx, mapping_of, lp, lo, storage):
+    storage = mapping_of(storage)
+    paged = storage == "paged"
+    wl = workloads.random_case(109, torch.bfloat16, 2, 32, 8, 64, [lp, 77], [lo, 5], device=DEV,
                                layout="nhd" if paged else storage, paged=paged)
     check_against_oracle(ctx, wl)
 
