@@ -27,7 +27,7 @@
  *   - a decode query attends to every cached token of both parts; no mask.
  *   - an empty part has A = 0, m = -inf, gamma = 0 and weight 0; if both parts
  *     are empty Y = 0 and lse = -inf.
- *   - inputs are the already-rounded bf16 / fp32 values, widened exactly to
+ *   - inputs are the already-rounded bf16 / fp16 / fp32 values, widened exactly to
  *     fp64; every sum, max and exponential is fp64.
  *
  * Parity pins live in tests/test_oracle_pins.py (brute force without the max
@@ -41,7 +41,7 @@
 #include <omp.h>
 #endif
 
-enum { ORC_F32 = 0, ORC_BF16 = 1 };
+enum { ORC_F32 = 0, ORC_BF16 = 1, ORC_F16 = 2 };
 
 /* One owner's cache for all users, in host memory. */
 typedef struct {
@@ -62,10 +62,26 @@ typedef struct {
     int64_t block_stride;         /* elements between consecutive pages                */
 } orc_view;
 
+/* IEEE binary16 (1 sign, 5 exponent, 10 fraction bits) to fp64, exactly. */
+double orc_half_to_double(uint16_t h)
+{
+    const int sign = h >> 15, e = (h >> 10) & 31, f = h & 1023;
+    double v;
+    if (e == 0)
+        v = ldexp((double)f, -24);                 /* zero and subnormals: f * 2^-10 * 2^-14 */
+    else if (e == 31)
+        v = f ? NAN : INFINITY;
+    else
+        v = ldexp(1.0 + (double)f / 1024.0, e - 15);
+    return sign ? -v : v;
+}
+
 static double widen(const void *base, int dtype, int64_t idx)
 {
     if (dtype == ORC_F32)
         return (double)((const float *)base)[idx];
+    if (dtype == ORC_F16)
+        return orc_half_to_double(((const uint16_t *)base)[idx]);
     uint32_t bits = (uint32_t)((const uint16_t *)base)[idx] << 16;  /* bf16 = top half of fp32 */
     float f;
     memcpy(&f, &bits, sizeof f);

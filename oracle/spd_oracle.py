@@ -19,7 +19,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "spd_oracle.c")
 _LIB = os.path.join(_HERE, "libspd_oracle.so")
 
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 
 
 def build(force: bool = False) -> str:
@@ -141,7 +141,7 @@ def from_workload(wl) -> HostWorkload:
         return HostView(s.lens, s.token_stride, s.head_stride, k=[host_array(t) for t in s.k],
                         v=[host_array(t) for t in s.v], head_strides=getattr(s, "head_strides", None))
 
-    dt = F32 if wl.dtype == torch.float32 else BF16
+    dt = {torch.float32: F32, torch.bfloat16: BF16, torch.float16: F16}[wl.dtype]
     return HostWorkload(dt, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.scale, host_array(wl.q),
                         side(wl.private), side(wl.public))
 

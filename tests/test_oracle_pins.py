@@ -452,6 +452,36 @@ def test_bf16_is_widened_exactly():
     assert g[0] == pytest.approx(w.sum(), rel=1e-15)
 
 
+def test_fp16_decoding_of_every_bit_pattern():
+    """The oracle's binary16 decoder against numpy's float16 on all 65536 patterns (zeros, subnormals, inf, NaN)."""
+    import ctypes as C
+    lib = orc._load()
+    lib.orc_half_to_double.restype = C.c_double
+    lib.orc_half_to_double.argtypes = [C.c_uint16]
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    want = bits.view(np.float16).astype(np.float64)
+    got = np.array([lib.orc_half_to_double(int(b)) for b in bits])
+    nan = np.isnan(want)
+    assert (np.isnan(got) == nan).all()
+    assert (got[~nan] == want[~nan]).all()
+    assert (np.signbit(got[~nan]) == np.signbit(want[~nan])).all()          # -0.0 keeps its sign
+
+
+def test_fp16_inputs_against_library_softmax():
+    """fp16 q, K, V (values torch rounded; widened by torch, not by the oracle) against scipy's softmax."""
+    from scipy.special import logsumexp, softmax
+    U, Hq, Hkv, d = 3, 4, 2, 16
+    wl, hw = _case(67, torch.float16, U, Hq, Hkv, d, [33, 1, 100], [16, 0, 31], layout="nhd", paged=True)
+    assert hw.dtype == orc.F16
+    Y, lse = orc.attention(hw)
+    for u in range(U):
+        for h in range(Hq):
+            K, V = _concat_rows(wl, u, h // (Hq // Hkv))
+            s = (K @ wl.q[u, h].double().numpy()) * wl.scale
+            np.testing.assert_allclose(Y[u * Hq + h], softmax(s) @ V, rtol=1e-11, atol=1e-12)
+            assert lse[u * Hq + h] == pytest.approx(logsumexp(s), rel=1e-12)
+
+
 def test_scale_is_applied_to_scores_not_outputs():
     wl, hw = _case(61, torch.float32, 1, 1, 1, 8, [5], [3], scale=0.0)
     Y, lse = orc.attention(hw)       # scale 0: uniform weights

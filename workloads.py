@@ -291,9 +291,9 @@ def random_case(seed: int, dtype, U: int, Hq: int, Hkv: int, d: int, lens_privat
 
 
 def host_array(t: torch.Tensor) -> np.ndarray:
-    """Host copy of a tensor with its exact bits: fp32 -> float32, bf16 -> uint16."""
+    """Host copy of a tensor with its exact bits: fp32 -> float32, bf16 and fp16 -> uint16."""
     t = t.detach().contiguous().cpu()
-    if t.dtype == torch.bfloat16:
+    if t.dtype in (torch.bfloat16, torch.float16):
         return t.view(torch.int16).numpy().view(np.uint16).copy()
     if t.dtype == torch.float32:
         return t.numpy().copy()
