@@ -48,16 +48,16 @@ extern "C" {
 #define SPD_ERR_HIP (-6)       /* a HIP runtime call failed; see spd_last_hip_error                  */
 #define SPD_ERR_NOMEM (-7)     /* host allocation failed                                             */
 
-enum { SPD_F32 = 0, SPD_BF16 = 1 };
+enum { SPD_F32 = 0, SPD_BF16 = 1, SPD_F16 = 2 };
 
 /* Opaque library context: device id, scratch memory for split partials, cached schedules. */
 typedef struct spd_ctx spd_ctx;
 
 /* Attention shape shared by q, K and V of one call. */
 typedef struct spd_shape {
-    int32_t dtype;      /* SPD_F32 or SPD_BF16: element type of q, K and V                            */
+    int32_t dtype;      /* SPD_F32, SPD_BF16 or SPD_F16: element type of q, K and V                   */
     int32_t n_q_heads;  /* Hq                                                                         */
-    int32_t n_kv_heads; /* Hkv, must divide Hq; Hq / Hkv in 1..16 (bf16) or 1..8 (fp32)               */
+    int32_t n_kv_heads; /* Hkv, must divide Hq; Hq / Hkv in 1..16 (bf16, fp16) or 1..8 (fp32)         */
     int32_t head_dim;   /* d: 64 or 128                                                               */
     float scale;        /* multiplies <q,k> before the softmax; 1/sqrt(d) in the usual case           */
 } spd_shape;

@@ -18,7 +18,7 @@ LIB_PATH = os.environ.get("SPD_HIP_LIBRARY") or os.path.join(_PKG, "libspd_hip.s
 SPD_OK = 0
 SPD_ERR_NULL, SPD_ERR_SHAPE, SPD_ERR_LEN, SPD_ERR_ALIGN = -1, -2, -3, -4
 SPD_ERR_WORKSPACE, SPD_ERR_HIP, SPD_ERR_NOMEM = -5, -6, -7
-SPD_F32, SPD_BF16 = 0, 1
+SPD_F32, SPD_BF16, SPD_F16 = 0, 1, 2
 
 EXPORTED_SYMBOLS = (
     "spd_create", "spd_destroy", "spd_strerror", "spd_last_hip_error",
@@ -112,7 +112,7 @@ def spd_strerror(code: int) -> str:
 
 def make_shape(dtype, n_q_heads: int, n_kv_heads: int, head_dim: int, scale: float) -> spd_shape:
     if isinstance(dtype, torch.dtype):
-        dtype = {torch.float32: SPD_F32, torch.bfloat16: SPD_BF16}[dtype]
+        dtype = {torch.float32: SPD_F32, torch.bfloat16: SPD_BF16, torch.float16: SPD_F16}[dtype]
     return spd_shape(int(dtype), int(n_q_heads), int(n_kv_heads), int(head_dim), float(scale))
 
 

@@ -16,7 +16,7 @@ inline int validate_shape(const spd_shape *s)
 {
     if (!s)
         return SPD_ERR_NULL;
-    if (s->dtype != SPD_F32 && s->dtype != SPD_BF16)
+    if (s->dtype != SPD_F32 && s->dtype != SPD_BF16 && s->dtype != SPD_F16)
         return SPD_ERR_SHAPE;
     if (s->n_q_heads <= 0 || s->n_kv_heads <= 0 || s->n_q_heads % s->n_kv_heads != 0)
         return SPD_ERR_SHAPE;
@@ -25,9 +25,9 @@ inline int validate_shape(const spd_shape *s)
     const int G = s->n_q_heads / s->n_kv_heads;
     if (s->head_dim != 64 && s->head_dim != 128)
         return SPD_ERR_SHAPE;
-    // bf16 runs on the matrix cores (a tile holds 16 heads); fp32 on the vector path, which keeps the group's state
-    // in registers
-    if (G > (s->dtype == SPD_BF16 ? spd::kMaxGroup : 8))
+    // the 16-bit types run on the matrix cores (a tile holds 16 heads); fp32 on the vector path, which keeps the
+    // group's state in registers
+    if (G > (s->dtype != SPD_F32 ? spd::kMaxGroup : 8))
         return SPD_ERR_SHAPE;
     if (!std::isfinite(s->scale))
         return SPD_ERR_SHAPE;

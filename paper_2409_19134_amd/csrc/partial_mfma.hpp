@@ -1,4 +1,4 @@
-// Partial attention over one chunk of one (user, KV head): bf16 K/V, head_dim D = 128 or 64, MFMA path.
+// Partial attention over one chunk of one (user, KV head): bf16 or fp16 K/V, head_dim D = 128 or 64, MFMA path.
 //
 // What it computes (paper section 4.2): for each of the G query heads that share this KV head,
 //   A = softmax(s) V and lse = ln sum exp(s) over the chunk's tokens, s_i = scale * <q, k_i>,
@@ -6,7 +6,7 @@
 // combined with the n-way form of the same theorem (combine.hpp).
 //
 // Mapping onto a 64-lane wave (r = lane % 16, grp = lane / 16), 32 tokens per step:
-//   S^T = K . Q^T   two v_mfma_f32_16x16x32_bf16 chains (D/32 MFMAs each):
+//   S^T = K . Q^T   two v_mfma_f32_16x16x32_{bf16,f16} chains (D/32 MFMAs each):
 //                   the A operand is K as loaded (lane reads 16 B = 8 channels of token row r),
 //                   the B operand is Q (head r, rows >= G are zero).  The result lands with
 //                   head = r and tokens tb + grp*8 + e (e = 0..7) in each lane.
@@ -16,7 +16,10 @@
 //                   channel per lane; the lane loaded D/16 channels of 8 tokens (16 B each at D = 128, 8 B
 //                   at D = 64: 16 lanes read a full row either way), so the operand is formed in registers
 //                   with v_perm_b32 (no LDS).
-//                   P is split into bf16 hi + lo so the product keeps ~16 mantissa bits.
+//                   P is split into hi + lo parts of the element type, so the product keeps ~16 (bf16) or ~22
+//                   (fp16) mantissa bits.  fp16 has a narrow exponent range: there P carries a factor 2^14 (the
+//                   running sum l carries it too, so it cancels in A; lse subtracts it), which keeps
+//                   probabilities down to 4e-9 of the row's largest out of the subnormal range.
 //                   The B operand P^T is exactly the lane's own 8 probabilities.
 // Every K/V byte is read once per KV head (all G heads share the tile).
 // The four waves of a workgroup take interleaved 32-token steps and are combined through LDS.
@@ -24,6 +27,28 @@
 #include "common.hpp"
 
 namespace spd {
+
+// The element type's MFMA and conversions.
+template <typename E>
+struct Elt;
+template <>
+struct Elt<__bf16> {
+    typedef __bf16 vec8 __attribute__((ext_vector_type(8)));
+    static constexpr float kPShift = 0.f;  // log2 of the factor P carries into the second MFMA
+    static __device__ __forceinline__ f32x4 mfma(vec8 a, vec8 b, f32x4 c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+    }
+};
+template <>
+struct Elt<_Float16> {
+    typedef _Float16 vec8 __attribute__((ext_vector_type(8)));
+    static constexpr float kPShift = 14.f;  // P <= 2^14 < 65504
+    static __device__ __forceinline__ f32x4 mfma(vec8 a, vec8 b, f32x4 c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+    }
+};
 
 template <int D>
 struct VRow;  // a lane's share of one V row: D/16 channels
@@ -106,15 +131,16 @@ __device__ __forceinline__ void load_tile(TileRegs<D> &T, const LaneConst &L, in
     __builtin_amdgcn_sched_barrier(0);
 }
 
-template <int D>
-__device__ __forceinline__ void compute_tile(const TileRegs<D> &T, const bf16x8 (&qB)[D / 32], int tb, int grp, int t_end,
-                                             float c, float &m, float &l, f32x4 (&acc)[D / 16])
+template <typename E, int D>
+__device__ __forceinline__ void compute_tile(const TileRegs<D> &T, const typename Elt<E>::vec8 (&qB)[D / 32], int tb,
+                                             int grp, int t_end, float c, float &m, float &l, f32x4 (&acc)[D / 16])
 {
+    typedef typename Elt<E>::vec8 vec8;
     f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int kk = 0; kk < D / 32; ++kk) {
-        s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, T.k[0][kk]), qB[kk], s0, 0, 0, 0);
-        s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, T.k[1][kk]), qB[kk], s1, 0, 0, 0);
+        s0 = Elt<E>::mfma(__builtin_bit_cast(vec8, T.k[0][kk]), qB[kk], s0);
+        s1 = Elt<E>::mfma(__builtin_bit_cast(vec8, T.k[1][kk]), qB[kk], s1);
     }
     // scores in log2 units; tokens past the chunk end get -inf
     const int t0 = tb + grp * 8;
@@ -129,10 +155,11 @@ __device__ __forceinline__ void compute_tile(const TileRegs<D> &T, const bf16x8 
     mt = wave_xor_max(mt, 32);
     const float m_new = fmaxf(m, mt);  // finite: every step holds at least one token of the chunk
     const float alpha = fast_exp2(m - m_new);
+    const float m_p = m_new - Elt<E>::kPShift;  // p (and with it l and acc) carries the factor 2^kPShift
     float p[8], ps = 0.f;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-        p[e] = fast_exp2(x[e] - m_new);
+        p[e] = fast_exp2(x[e] - m_p);
         ps += p[e];
     }
     l = l * alpha + ps;
@@ -142,11 +169,11 @@ __device__ __forceinline__ void compute_tile(const TileRegs<D> &T, const bf16x8 
         for (int cc = 0; cc < D / 16; ++cc)
             acc[cc] *= alpha;
     }
-    bf16x8 ph, pl;
+    vec8 ph, pl;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-        ph[e] = (__bf16)p[e];
-        pl[e] = (__bf16)(p[e] - (float)ph[e]);
+        ph[e] = (E)p[e];
+        pl[e] = (E)(p[e] - (float)ph[e]);
     }
 #pragma unroll
     for (int cc = 0; cc < D / 16; ++cc) {
@@ -156,9 +183,9 @@ __device__ __forceinline__ void compute_tile(const TileRegs<D> &T, const bf16x8 
 #pragma unroll
         for (int j = 0; j < 4; ++j)
             vt[j] = __builtin_amdgcn_perm(T.v[2 * j + 1][w], T.v[2 * j][w], sel);  // (token 2j, token 2j+1) of channel cc
-        const bf16x8 va = __builtin_bit_cast(bf16x8, vt);
-        acc[cc] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, ph, acc[cc], 0, 0, 0);
-        acc[cc] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pl, acc[cc], 0, 0, 0);
+        const vec8 va = __builtin_bit_cast(vec8, vt);
+        acc[cc] = Elt<E>::mfma(va, ph, acc[cc]);
+        acc[cc] = Elt<E>::mfma(va, pl, acc[cc]);
     }
 }
 
@@ -173,7 +200,7 @@ __host__ __device__ constexpr size_t staging_bytes(int D, int waves, int G)
 }
 __host__ __device__ constexpr bool staging_fits(int D, int waves, int G) { return staging_bytes(D, waves, G) <= 64 * 1024; }
 
-// One workgroup per piece (see DevItem); q: [U][Hq][D] bf16.  A segment that is its row's only one writes out/lse
+// One workgroup per piece (see DevItem); q: [U][Hq][D] of the element type E (__bf16 or _Float16).  A segment that is its row's only one writes out/lse
 // directly; otherwise it writes part_o[slot][G][D] / part_lse[slot][G], which combine_chunks_kernel then reduces.
 //
 // (Register counts below are those of D = 128; D = 64 needs about half and always runs with PREFETCH.)
@@ -191,8 +218,8 @@ __host__ __device__ constexpr bool staging_fits(int D, int waves, int G) { retur
 // a token range of one (user, KV head) row and its four waves take interleaved steps.
 //
 // APPEND = true adds the KV append (the address substitution costs ~1 % when nothing is appended, hence a flag).
-template <int D, bool PAGED, bool PREFETCH, bool HPW, bool APPEND>
-__global__ __launch_bounds__(HPW ? 512 : kThreads, D == 128 && !PREFETCH ? 3 : 2 + (D == 64 && !HPW)) void partial_bf16_kernel(
+template <typename E, int D, bool PAGED, bool PREFETCH, bool HPW, bool APPEND>
+__global__ __launch_bounds__(HPW ? 512 : kThreads, D == 128 && !PREFETCH ? 3 : 2 + (D == 64 && !HPW)) void partial_mfma_kernel(
     OwnerArgs a0, OwnerArgs a1, int n0, const uint16_t *__restrict__ q, int Hq, int G, float scale_log2e)
 {
     const bool second = (int)blockIdx.x >= n0;  // workgroup-uniform: which owner this workgroup serves
@@ -214,6 +241,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, D == 128 && !PREFETCH ? 3 : 2
     constexpr int kOStride = o_stride(D);
     constexpr int CP = D / 16;  // channel phases of the O^T tile: a lane holds CP consecutive channels per accumulator row
     constexpr int kRowBytes = D * 2;
+    typedef typename Elt<E>::vec8 vec8;
     const int o_wave_stride = G * kOStride;
     // head-per-wave results go through a wave-private tile if the launch gave the room
     const bool staged = HPW && staging_fits(D, (int)(blockDim.x >> 6), G);
@@ -225,7 +253,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, D == 128 && !PREFETCH ? 3 : 2
     // Everything a segment needs before its first MFMA: addresses, the KV append copy, Q, and the loads of the wave's
     // first 32-token step.  Issued for the *next* segment before the current one's epilogue, so that the barriers
     // and the result stores of the epilogue overlap the memory round trip instead of preceding it.
-    auto begin_segment = [&](const DevItem &it, LaneConst &L, bf16x8 (&qB)[D / 32], int &tb, TileRegs<D> &T0, PagePair &P) {
+    auto begin_segment = [&](const DevItem &it, LaneConst &L, vec8 (&qB)[D / 32], int &tb, TileRegs<D> &T0, PagePair &P) {
         L.r = lane & 15;
         L.grp = lane >> 4;
         L.token_stride = kv.token_stride;
@@ -261,7 +289,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, D == 128 && !PREFETCH ? 3 : 2
             u32x4 w = {0u, 0u, 0u, 0u};
             if (L.r < G)
                 w = *reinterpret_cast<const u32x4 *>(qrow + kk * 32);
-            qB[kk] = __builtin_bit_cast(bf16x8, w);
+            qB[kk] = __builtin_bit_cast(vec8, w);
         }
         // head-major: the four waves take interleaved 32-token steps; token-major: every wave takes every step
         tb = HPW ? it.t_begin : it.t_begin + ((uniform(wave) - (it.rot & 3)) & (kWaves - 1)) * 32;
@@ -285,7 +313,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, D == 128 && !PREFETCH ? 3 : 2
         return;
     }
     LaneConst L;
-    bf16x8 qB[D / 32];
+    vec8 qB[D / 32];
     int tb;
     TileRegs<D> T0;
     PagePair P = {0, 0};
@@ -308,7 +336,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, D == 128 && !PREFETCH ? 3 : 2
             for (; tb < it.t_end; tb += kStep) {
                 TileRegs<D> T;
                 load_tile<D, PAGED, APPEND>(T, L, tb, t_last, P, kStep);
-                compute_tile<D>(T, qB, tb, L.grp, it.t_end, scale_log2e, m, l, acc);
+                compute_tile<E, D>(T, qB, tb, L.grp, it.t_end, scale_log2e, m, l, acc);
             }
         } else if (tb < it.t_end) {  // T0 already holds (the loads of) step tb
             {
@@ -322,7 +350,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, D == 128 && !PREFETCH ? 3 : 2
                         __builtin_amdgcn_s_barrier();
                     if (more1)
                         load_tile<D, PAGED, APPEND>(T1, L, tb1, t_last, P, kStep);
-                    compute_tile<D>(T0, qB, tb, L.grp, it.t_end, scale_log2e, m, l, acc);
+                    compute_tile<E, D>(T0, qB, tb, L.grp, it.t_end, scale_log2e, m, l, acc);
                     if (!more1)
                         break;
                     const int tb2 = tb1 + kStep;
@@ -331,7 +359,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, D == 128 && !PREFETCH ? 3 : 2
                         __builtin_amdgcn_s_barrier();
                     if (more2)
                         load_tile<D, PAGED, APPEND>(T0, L, tb2, t_last, P, kStep);
-                    compute_tile<D>(T1, qB, tb1, L.grp, it.t_end, scale_log2e, m, l, acc);
+                    compute_tile<E, D>(T1, qB, tb1, L.grp, it.t_end, scale_log2e, m, l, acc);
                     if (!more2)
                         break;
                     tb = tb2;
@@ -388,7 +416,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, D == 128 && !PREFETCH ? 3 : 2
                         }
                 }
                 if (grp == 0) {
-                    const float ls = (m + fast_log2(l)) * kLn2;  // m is in log2 units
+                    const float ls = (m + fast_log2(l) - Elt<E>::kPShift) * kLn2;  // m is in log2 units
                     if (direct)
                         lse[head0 + r] = ls;
                     else
@@ -443,7 +471,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, D == 128 && !PREFETCH ? 3 : 2
             else
                 part_o[((int64_t)it.slot * G + g) * D + ch] = a;
             if (ch == 0) {
-                const float ls = (Mg + fast_log2(lt)) * kLn2;  // Mg is in log2 units
+                const float ls = (Mg + fast_log2(lt) - Elt<E>::kPShift) * kLn2;  // Mg is in log2 units
                 if (direct)
                     lse[head0 + g] = ls;
                 else

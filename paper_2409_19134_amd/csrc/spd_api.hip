@@ -14,7 +14,7 @@
 #include "combine.hpp"
 #include "common.hpp"
 #include "host_checks.hpp"
-#include "partial_bf16_mfma.hpp"
+#include "partial_mfma.hpp"
 #include "partial_generic.hpp"
 #include "schedule.hpp"
 
@@ -111,7 +111,7 @@ void free_entry(CachedSchedule &e)
 // kernel: one wave per KV head, all waves on the same tokens.
 bool head_per_wave_layout(const spd_shape *s, const spd_kv_view *v)
 {
-    return s->dtype == SPD_BF16 && head_per_wave_waves(s->n_kv_heads) > 1 &&
+    return s->dtype != SPD_F32 && head_per_wave_waves(s->n_kv_heads) > 1 &&
            !(v->head_strides && v->block_size == 0) && v->head_stride == s->head_dim &&
            v->token_stride >= (int64_t)s->n_kv_heads * s->head_dim;
 }
@@ -447,7 +447,7 @@ int launch_partial(spd_ctx *ctx, int which, const CachedSchedule *e0, const spd_
     const hipEvent_t ev0 = timed ? town.ev_start[town.ev_used] : nullptr;
     const hipEvent_t ev1 = timed ? town.ev_stop[town.ev_used] : nullptr;
     const dim3 grid((unsigned)(n0 + n1));
-    if (s->dtype == SPD_BF16) {
+    if (s->dtype != SPD_F32) {
         const uint16_t *qh = static_cast<const uint16_t *>(q);
         const bool hpw = e0->hpw;  // a two-owner launch needs the same mapping on both sides (checked by the caller)
         const int waves = hpw ? head_per_wave_waves(s->n_kv_heads) : spd::kWaves;
@@ -462,39 +462,47 @@ int launch_partial(spd_ctx *ctx, int which, const CachedSchedule *e0, const spd_
         const int64_t cus = std::max(1, ctx->n_cus);
         // With 64 channels a step is half the bytes: always two in flight.
         const bool prefetch = hpw || D == 64 || n0 + n1 > cus * 4 || n0 + n1 <= cus * 2;
-#define SPD_LAUNCH_BF16_A(D, PAGED, PREFETCH, HPW, APPEND)                                                           \
-    hipExtLaunchKernelGGL((spd::partial_bf16_kernel<D, PAGED, PREFETCH, HPW, APPEND>), grid, blk, (uint32_t)lds,      \
+#define SPD_LAUNCH_MFMA_A(E, D, PAGED, PREFETCH, HPW, APPEND)                                                        \
+    hipExtLaunchKernelGGL((spd::partial_mfma_kernel<E, D, PAGED, PREFETCH, HPW, APPEND>), grid, blk, (uint32_t)lds,   \
                           stream, ev0, ev1, 0, a0, a1, (int)n0, qh, s->n_q_heads, G, c)
-#define SPD_LAUNCH_BF16(D, PAGED, PREFETCH, HPW)                                                                      \
+#define SPD_LAUNCH_MFMA(E, D, PAGED, PREFETCH, HPW)                                                                   \
     do {                                                                                                             \
         if (nt.k)                                                                                                    \
-            SPD_LAUNCH_BF16_A(D, PAGED, PREFETCH, HPW, true);                                                        \
+            SPD_LAUNCH_MFMA_A(E, D, PAGED, PREFETCH, HPW, true);                                                     \
         else                                                                                                         \
-            SPD_LAUNCH_BF16_A(D, PAGED, PREFETCH, HPW, false);                                                       \
+            SPD_LAUNCH_MFMA_A(E, D, PAGED, PREFETCH, HPW, false);                                                    \
     } while (0)
-#define SPD_LAUNCH_BF16_P(D, PAGED)                                                                                  \
+#define SPD_LAUNCH_MFMA_P(E, D, PAGED)                                                                               \
     do {                                                                                                             \
         if (hpw)                                                                                                     \
-            SPD_LAUNCH_BF16(D, PAGED, true, true);                                                                   \
+            SPD_LAUNCH_MFMA(E, D, PAGED, true, true);                                                                \
         else if (prefetch)                                                                                           \
-            SPD_LAUNCH_BF16(D, PAGED, true, false);                                                                  \
+            SPD_LAUNCH_MFMA(E, D, PAGED, true, false);                                                               \
         else if (D == 128)                                                                                           \
-            SPD_LAUNCH_BF16(128, PAGED, false, false);                                                               \
+            SPD_LAUNCH_MFMA(E, 128, PAGED, false, false);                                                            \
     } while (0)
-        if (D == 128) {
-            if (v0->block_size)
-                SPD_LAUNCH_BF16_P(128, true);
-            else
-                SPD_LAUNCH_BF16_P(128, false);
-        } else {
-            if (v0->block_size)
-                SPD_LAUNCH_BF16_P(64, true);
-            else
-                SPD_LAUNCH_BF16_P(64, false);
-        }
-#undef SPD_LAUNCH_BF16_A
-#undef SPD_LAUNCH_BF16
-#undef SPD_LAUNCH_BF16_P
+#define SPD_LAUNCH_MFMA_D(E)                                                                                         \
+    do {                                                                                                             \
+        if (D == 128) {                                                                                              \
+            if (v0->block_size)                                                                                      \
+                SPD_LAUNCH_MFMA_P(E, 128, true);                                                                     \
+            else                                                                                                     \
+                SPD_LAUNCH_MFMA_P(E, 128, false);                                                                    \
+        } else {                                                                                                     \
+            if (v0->block_size)                                                                                      \
+                SPD_LAUNCH_MFMA_P(E, 64, true);                                                                      \
+            else                                                                                                     \
+                SPD_LAUNCH_MFMA_P(E, 64, false);                                                                     \
+        }                                                                                                            \
+    } while (0)
+        if (s->dtype == SPD_BF16)
+            SPD_LAUNCH_MFMA_D(__bf16);
+        else
+            SPD_LAUNCH_MFMA_D(_Float16);
+#undef SPD_LAUNCH_MFMA_A
+#undef SPD_LAUNCH_MFMA
+#undef SPD_LAUNCH_MFMA_P
+#undef SPD_LAUNCH_MFMA_D
     } else if (s->head_dim == 64) {
         launch_f32_g<64>(G, grid, stream, ev0, ev1, a0, a1, (int)n0, q, s->n_q_heads, c);
     } else {

@@ -60,6 +60,7 @@ def test_validation_accepts_good_arguments():
     assert _check(spd.make_shape(spd.SPD_F32, 8, 8, 64, 0.125), _view([128], token_stride=512, head_stride=64)) == spd.SPD_OK
     assert _check(spd.make_shape(spd.SPD_F32, 6, 2, 128, 0.1), _view([128])) == spd.SPD_OK          # group of 3 heads
     assert _check(spd.make_shape(spd.SPD_BF16, 128, 8, 64, 0.125), _view([128], token_stride=512, head_stride=64)) == spd.SPD_OK
+    assert _check(spd.make_shape(spd.SPD_F16, 128, 8, 128, 0.1), _view([128])) == spd.SPD_OK
 
 
 @pytest.mark.parametrize("args,code", [

@@ -11,7 +11,7 @@ from oracle import spd_oracle as orc
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
-TOL = {torch.float32: 1e-5, torch.bfloat16: 2e-3}
+TOL = {torch.float32: 1e-5, torch.bfloat16: 2e-3, torch.float16: 2e-3}
 
 
 @pytest.fixture(scope="module")
@@ -53,7 +53,7 @@ def _clone_side(side):
 
 def _all_bytes(side):
     ts = [side.k_pool, side.v_pool] if side.paged else list(side.k) + list(side.v)
-    return [t.view(torch.int16 if t.dtype == torch.bfloat16 else torch.int32).cpu() for t in ts]
+    return [t.view(torch.int32 if t.dtype == torch.float32 else torch.int16).cpu() for t in ts]
 
 
 CASES = [
@@ -75,6 +75,9 @@ CASES = [
     (torch.bfloat16, 32, 8, 64, [2000, 10, 0], [1500, 3000, 1], "nhd_hpw", False),
     (torch.bfloat16, 16, 4, 64, [2000, 10, 0], [1500, 3000, 1], "nhd_hpw", "token_major"),
     (torch.bfloat16, 64, 8, 64, [300, 0, 5000], [32, 1, 4097], "nhd", True),
+    (torch.float16, 32, 8, 128, [40, 1, 700, 33], [1, 16, 17, 250], "hnd", False),
+    (torch.float16, 32, 8, 128, [2000, 10, 0], [1500, 3000, 1], "nhd_hpw", "token_major"),
+    (torch.float16, 32, 8, 64, [2000, 10, 0], [1500, 3000, 1], "nhd", True),
 ]
 
 

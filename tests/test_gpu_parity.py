@@ -12,7 +12,9 @@ from oracle import spd_oracle as orc
 
 pytestmark = pytest.mark.gpu
 
-TOL = {torch.float32: 1e-5, torch.bfloat16: 2e-3}
+# fp16: fp32 accumulation of exact products, probabilities carried with ~22 bits: the fp32 bar with room for the
+# hardware exp2 / log2 over tens of thousands of tokens
+TOL = {torch.float32: 1e-5, torch.bfloat16: 2e-3, torch.float16: 1e-4}
 DEV = "cuda:0"
 
 
@@ -283,6 +285,39 @@ def test_bf16_d64_edge_lengths(ctx, mapping_of, lp, lo, storage):
     wl = workloads.random_case(109, torch.bfloat16, 2, 32, 8, 64, [lp, 77], [lo, 5], device=DEV,
                                layout="nhd" if paged else storage, paged=paged)
     check_against_oracle(ctx, wl)
+
+
+@pytest.mark.parametrize("d,Hq,Hkv", [(128, 32, 8), (128, 64, 4), (128, 6, 2), (64, 32, 8), (64, 16, 16), (64, 7, 1)])
+@pytest.mark.parametrize("storage", ["hnd", "nhd", "nhd_hpw", "paged", "paged_tm", "paged_tm_hpw"])
+def test_fp16_shapes(ctx, mapping_of, d, Hq, Hkv, storage):
+    storage = mapping_of(storage)
+    paged = {"paged": True, "paged_tm": "token_major"}.get(storage, False)
+    wl = workloads.random_case(110, torch.float16, 5, Hq, Hkv, d, [128, 0, 1000, 3, 2500], [16, 5, 0, 77, 300], device=DEV,
+                               layout="nhd" if paged else storage, paged=paged)
+    check_against_oracle(ctx, wl)
+
+
+@pytest.mark.parametrize("lp,lo", [(0, 0), (1, 0), (31, 33), (127, 129), (4097, 1), (40000, 700)])
+def test_fp16_edge_lengths(ctx, lp, lo):
+    wl = workloads.random_case(111, torch.float16, 2, 32, 8, 128, [lp, 77], [lo, 5], device=DEV, layout="hnd")
+    check_against_oracle(ctx, wl)
+
+
+def test_fp16_small_probabilities_are_kept(ctx):
+    """One dominant token and 30000 tokens whose probability (6e-8 of the largest) lies below fp16's smallest
+    subnormal, with large values: together they hold 0.2 % of the mass and move the result by 1.8.  The kernel's
+    probabilities therefore cannot be plain fp16 numbers."""
+    L, d = 30001, 128
+    wl = workloads.random_case(112, torch.float16, 1, 1, 1, d, [L], [0], device=DEV, layout="hnd")
+    wl.q.zero_()
+    wl.q[0, 0, 0] = 16.0
+    k, v = wl.private.k[0], wl.private.v[0]          # [Hkv, capacity, d]
+    k.zero_()
+    k[0, 1234, 0] = 11.75                              # score 16 * 11.75 / sqrt(128) = 16.62 above all others
+    v.fill_(1000.0)
+    v[0, 1234] = 0.0
+    step, errs = check_against_oracle(ctx, wl)
+    assert 1.5 < float(step.y[0, 0, 0]) < 2.1
 
 
 def test_peaked_softmax_and_large_score_gap(ctx):
