@@ -28,11 +28,13 @@
 
 namespace spd {
 
-// The element type's MFMA and conversions.
-template <typename E>
+// The element type's MFMA and conversions, by dtype code (SPD_BF16 / SPD_F16: an integer template argument keeps
+// the kernel's name readable in profiler output).
+template <int DT>
 struct Elt;
 template <>
-struct Elt<__bf16> {
+struct Elt<SPD_BF16> {
+    typedef __bf16 type;
     typedef __bf16 vec8 __attribute__((ext_vector_type(8)));
     static constexpr float kPShift = 0.f;  // log2 of the factor P carries into the second MFMA
     static __device__ __forceinline__ f32x4 mfma(vec8 a, vec8 b, f32x4 c)
@@ -41,7 +43,8 @@ struct Elt<__bf16> {
     }
 };
 template <>
-struct Elt<_Float16> {
+struct Elt<SPD_F16> {
+    typedef _Float16 type;
     typedef _Float16 vec8 __attribute__((ext_vector_type(8)));
     static constexpr float kPShift = 14.f;  // P <= 2^14 < 65504
     static __device__ __forceinline__ f32x4 mfma(vec8 a, vec8 b, f32x4 c)
@@ -131,16 +134,17 @@ __device__ __forceinline__ void load_tile(TileRegs<D> &T, const LaneConst &L, in
     __builtin_amdgcn_sched_barrier(0);
 }
 
-template <typename E, int D>
-__device__ __forceinline__ void compute_tile(const TileRegs<D> &T, const typename Elt<E>::vec8 (&qB)[D / 32], int tb,
+template <int DT, int D>
+__device__ __forceinline__ void compute_tile(const TileRegs<D> &T, const typename Elt<DT>::vec8 (&qB)[D / 32], int tb,
                                              int grp, int t_end, float c, float &m, float &l, f32x4 (&acc)[D / 16])
 {
-    typedef typename Elt<E>::vec8 vec8;
+    typedef typename Elt<DT>::vec8 vec8;
+    typedef typename Elt<DT>::type E;
     f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int kk = 0; kk < D / 32; ++kk) {
-        s0 = Elt<E>::mfma(__builtin_bit_cast(vec8, T.k[0][kk]), qB[kk], s0);
-        s1 = Elt<E>::mfma(__builtin_bit_cast(vec8, T.k[1][kk]), qB[kk], s1);
+        s0 = Elt<DT>::mfma(__builtin_bit_cast(vec8, T.k[0][kk]), qB[kk], s0);
+        s1 = Elt<DT>::mfma(__builtin_bit_cast(vec8, T.k[1][kk]), qB[kk], s1);
     }
     // scores in log2 units; tokens past the chunk end get -inf
     const int t0 = tb + grp * 8;
@@ -155,7 +159,7 @@ __device__ __forceinline__ void compute_tile(const TileRegs<D> &T, const typenam
     mt = wave_xor_max(mt, 32);
     const float m_new = fmaxf(m, mt);  // finite: every step holds at least one token of the chunk
     const float alpha = fast_exp2(m - m_new);
-    const float m_p = m_new - Elt<E>::kPShift;  // p (and with it l and acc) carries the factor 2^kPShift
+    const float m_p = m_new - Elt<DT>::kPShift;  // p (and with it l and acc) carries the factor 2^kPShift
     float p[8], ps = 0.f;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
@@ -184,8 +188,8 @@ __device__ __forceinline__ void compute_tile(const TileRegs<D> &T, const typenam
         for (int j = 0; j < 4; ++j)
             vt[j] = __builtin_amdgcn_perm(T.v[2 * j + 1][w], T.v[2 * j][w], sel);  // (token 2j, token 2j+1) of channel cc
         const vec8 va = __builtin_bit_cast(vec8, vt);
-        acc[cc] = Elt<E>::mfma(va, ph, acc[cc]);
-        acc[cc] = Elt<E>::mfma(va, pl, acc[cc]);
+        acc[cc] = Elt<DT>::mfma(va, ph, acc[cc]);
+        acc[cc] = Elt<DT>::mfma(va, pl, acc[cc]);
     }
 }
 
@@ -200,7 +204,7 @@ __host__ __device__ constexpr size_t staging_bytes(int D, int waves, int G)
 }
 __host__ __device__ constexpr bool staging_fits(int D, int waves, int G) { return staging_bytes(D, waves, G) <= 64 * 1024; }
 
-// One workgroup per piece (see DevItem); q: [U][Hq][D] of the element type E (__bf16 or _Float16).  A segment that is its row's only one writes out/lse
+// One workgroup per piece (see DevItem); q: [U][Hq][D] of the element type DT (SPD_BF16 or SPD_F16).  A segment that is its row's only one writes out/lse
 // directly; otherwise it writes part_o[slot][G][D] / part_lse[slot][G], which combine_chunks_kernel then reduces.
 //
 // (Register counts below are those of D = 128; D = 64 needs about half and always runs with PREFETCH.)
@@ -218,7 +222,7 @@ __host__ __device__ constexpr bool staging_fits(int D, int waves, int G) { retur
 // a token range of one (user, KV head) row and its four waves take interleaved steps.
 //
 // APPEND = true adds the KV append (the address substitution costs ~1 % when nothing is appended, hence a flag).
-template <typename E, int D, bool PAGED, bool PREFETCH, bool HPW, bool APPEND>
+template <int DT, int D, bool PAGED, bool PREFETCH, bool HPW, bool APPEND>
 __global__ __launch_bounds__(HPW ? 512 : kThreads, D == 128 && !PREFETCH ? 3 : 2 + (D == 64 && !HPW)) void partial_mfma_kernel(
     OwnerArgs a0, OwnerArgs a1, int n0, const uint16_t *__restrict__ q, int Hq, int G, float scale_log2e)
 {
@@ -241,7 +245,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, D == 128 && !PREFETCH ? 3 : 2
     constexpr int kOStride = o_stride(D);
     constexpr int CP = D / 16;  // channel phases of the O^T tile: a lane holds CP consecutive channels per accumulator row
     constexpr int kRowBytes = D * 2;
-    typedef typename Elt<E>::vec8 vec8;
+    typedef typename Elt<DT>::vec8 vec8;
     const int o_wave_stride = G * kOStride;
     // head-per-wave results go through a wave-private tile if the launch gave the room
     const bool staged = HPW && staging_fits(D, (int)(blockDim.x >> 6), G);
@@ -336,7 +340,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, D == 128 && !PREFETCH ? 3 : 2
             for (; tb < it.t_end; tb += kStep) {
                 TileRegs<D> T;
                 load_tile<D, PAGED, APPEND>(T, L, tb, t_last, P, kStep);
-                compute_tile<E, D>(T, qB, tb, L.grp, it.t_end, scale_log2e, m, l, acc);
+                compute_tile<DT, D>(T, qB, tb, L.grp, it.t_end, scale_log2e, m, l, acc);
             }
         } else if (tb < it.t_end) {  // T0 already holds (the loads of) step tb
             {
@@ -350,7 +354,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, D == 128 && !PREFETCH ? 3 : 2
                         __builtin_amdgcn_s_barrier();
                     if (more1)
                         load_tile<D, PAGED, APPEND>(T1, L, tb1, t_last, P, kStep);
-                    compute_tile<E, D>(T0, qB, tb, L.grp, it.t_end, scale_log2e, m, l, acc);
+                    compute_tile<DT, D>(T0, qB, tb, L.grp, it.t_end, scale_log2e, m, l, acc);
                     if (!more1)
                         break;
                     const int tb2 = tb1 + kStep;
@@ -359,7 +363,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, D == 128 && !PREFETCH ? 3 : 2
                         __builtin_amdgcn_s_barrier();
                     if (more2)
                         load_tile<D, PAGED, APPEND>(T0, L, tb2, t_last, P, kStep);
-                    compute_tile<E, D>(T1, qB, tb1, L.grp, it.t_end, scale_log2e, m, l, acc);
+                    compute_tile<DT, D>(T1, qB, tb1, L.grp, it.t_end, scale_log2e, m, l, acc);
                     if (!more2)
                         break;
                     tb = tb2;
@@ -416,7 +420,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, D == 128 && !PREFETCH ? 3 : 2
                         }
                 }
                 if (grp == 0) {
-                    const float ls = (m + fast_log2(l) - Elt<E>::kPShift) * kLn2;  // m is in log2 units
+                    const float ls = (m + fast_log2(l) - Elt<DT>::kPShift) * kLn2;  // m is in log2 units
                     if (direct)
                         lse[head0 + r] = ls;
                     else
@@ -471,7 +475,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, D == 128 && !PREFETCH ? 3 : 2
             else
                 part_o[((int64_t)it.slot * G + g) * D + ch] = a;
             if (ch == 0) {
-                const float ls = (Mg + fast_log2(lt) - Elt<E>::kPShift) * kLn2;  // Mg is in log2 units
+                const float ls = (Mg + fast_log2(lt) - Elt<DT>::kPShift) * kLn2;  // Mg is in log2 units
                 if (direct)
                     lse[head0 + g] = ls;
                 else

@@ -496,9 +496,9 @@ int launch_partial(spd_ctx *ctx, int which, const CachedSchedule *e0, const spd_
         }                                                                                                            \
     } while (0)
         if (s->dtype == SPD_BF16)
-            SPD_LAUNCH_MFMA_D(__bf16);
+            SPD_LAUNCH_MFMA_D(SPD_BF16);
         else
-            SPD_LAUNCH_MFMA_D(_Float16);
+            SPD_LAUNCH_MFMA_D(SPD_F16);
 #undef SPD_LAUNCH_MFMA_A
 #undef SPD_LAUNCH_MFMA
 #undef SPD_LAUNCH_MFMA_P
