@@ -29,6 +29,12 @@
  *   - Calls on one context that use the same entry point must not overlap in time (they share scratch memory);
  *     the private and the public call may run concurrently on two streams.  A context is not thread-safe: its
  *     calls must come from one host thread at a time (use a context per thread).
+ *   - A call whose view the context has seen before (same lengths, strides and - without device pointer arrays -
+ *     buffers) and whose scratch memory is large enough only launches kernels: it allocates nothing, copies nothing
+ *     and may be recorded into a HIP graph (stream capture).  A call that has to build a schedule or grow scratch
+ *     memory under capture fails with SPD_ERR_HIP and invalidates the capture, so run the step once eagerly first.
+ *     The context remembers 128 views per entry point (SPD_SCHEDULE_CACHE_ENTRIES in the environment, read by
+ *     spd_create, changes that), least recently used first out.
  */
 #ifndef SPD_H
 #define SPD_H

@@ -27,7 +27,10 @@ using spd::OwnerArgs;
 using spd::RowInfo;
 using namespace spd::host;
 
-constexpr int kCacheEntries = 16;    // remembered schedules per entry point
+// Remembered schedules per entry point.  Views without device pointer tables need one per set of buffers, i.e. one per
+// layer of a model: the default holds an 80-layer model with room to spare.  SPD_SCHEDULE_CACHE_ENTRIES (1..4096, read
+// when a context is created) changes it.
+constexpr int kCacheEntriesDefault = 128;
 
 // Hash of a schedule key, eight bytes at a time (keys grow with the number of users and are hashed on every call).
 // Only a filter: a hit is confirmed by comparing the keys themselves.
@@ -63,7 +66,7 @@ struct CachedSchedule {
 };
 
 struct Owner {
-    CachedSchedule cache[kCacheEntries];
+    std::vector<CachedSchedule> cache;
     float *part_o = nullptr;
     float *part_lse = nullptr;
     size_t part_o_cap = 0, part_lse_cap = 0;  // floats
@@ -613,6 +616,14 @@ int spd_create(spd_ctx **out, int hip_device)
     spd_ctx *ctx = new (std::nothrow) spd_ctx();
     if (!ctx)
         return SPD_ERR_NOMEM;
+    try {
+        const int entries = std::min(4096, std::max(1, env_int("SPD_SCHEDULE_CACHE_ENTRIES", kCacheEntriesDefault)));
+        for (auto &own : ctx->owner)
+            own.cache.resize((size_t)entries);
+    } catch (...) {
+        delete ctx;
+        return SPD_ERR_NOMEM;
+    }
     ctx->device = hip_device;
     hipError_t e = hipSetDevice(hip_device);
     if (e == hipSuccess)

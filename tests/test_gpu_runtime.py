@@ -18,10 +18,11 @@ def _err(step, Y):
     return float(np.abs(step.y.cpu().double().numpy().reshape(Y.shape) - Y).max())
 
 
-def test_more_views_than_cache_entries_and_scratch_growth():
-    """40 distinct views (the cache remembers 16 per entry point), sizes going up and down: every result stays right,
-    also when an evicted view comes back."""
+def test_more_views_than_cache_entries_and_scratch_growth(monkeypatch):
+    """40 distinct views with a cache of 16 schedules per entry point, sizes going up and down: every result stays
+    right, also when an evicted view comes back."""
     import paper_2409_19134_amd as spd
+    monkeypatch.setenv("SPD_SCHEDULE_CACHE_ENTRIES", "16")       # read when the context is created
     ctx = spd.Context(0)
     rng = np.random.default_rng(3)
     cases = []
@@ -329,4 +330,51 @@ def test_attention_mass_track_argument_errors():
     assert b.lib.spd_attention_mass_track(ctx.handle, 4, None, 0.5, None, None, None, None) == b.SPD_ERR_NULL
     assert b.lib.spd_attention_mass_track(None, 4, w.data_ptr(), 0.5, None, None, None, None) == b.SPD_ERR_NULL
     assert b.lib.spd_attention_mass_track(ctx.handle, 0, None, 0.5, None, None, None, None) == b.SPD_OK
+    ctx.close()
+
+
+@pytest.mark.parametrize("fused", [True, False])
+def test_layers_captured_in_one_hip_graph(fused):
+    """Four layers of a decode step (a set of buffers each, one shared schedule) recorded into one HIP graph after an
+    eager pass has built the schedules and sized the scratch memory: a call with warm caches only launches kernels,
+    so it can be captured.  Every replay - with eager work of the library and fresh inputs in between - must give
+    the bits of the eager run on the same inputs."""
+    import paper_2409_19134_amd as spd
+    ctx = spd.Context(0)
+    U, Hq, Hkv, d, n_layers = 3, 32, 8, 128, 4
+    layers = [workloads.random_case(540 + i, torch.bfloat16, U, Hq, Hkv, d, [700, 40, 2100], [30, 0, 200], device=DEV,
+                                    layout="hnd") for i in range(n_layers)]
+    q = [w.q for w in layers]                      # static input buffers of the graph
+    steps = [spd.DecodeStep.from_workload(ctx, w, device_pointer_tables=True) for w in layers]
+    run = (lambda s, x: s.run_fused(x)) if fused else (lambda s, x: s.run(x))
+
+    def eager():
+        for s, x in zip(steps, q):
+            run(s, x)
+        torch.cuda.synchronize()
+        return [s.y.clone() for s in steps]
+
+    eager()                                        # schedules built and uploaded, scratch allocated
+    builds0, _ = ctx.spd_get_schedule_stats()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        for s, x in zip(steps, q):
+            run(s, x)                              # stream=None: torch's current stream, here the capturing one
+    assert ctx.spd_get_schedule_stats()[0] == builds0      # nothing was built while capturing
+    g = torch.Generator(device=DEV).manual_seed(11)
+    for rep in range(4):
+        for x in q:
+            x.copy_(torch.randn(x.shape, generator=g, device=DEV).to(x.dtype))
+        want = eager()
+        for s in steps:
+            s.y.fill_(float("nan"))
+            s.a_in.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for s, y in zip(steps, want):
+            assert torch.equal(s.y, y), f"replay {rep}"
+    for w, s in zip(layers, steps):
+        assert _err(s, _oracle_y(w)) <= 2e-3
     ctx.close()
