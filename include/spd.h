@@ -239,9 +239,13 @@ typedef struct spd_work_item {
  * is covered by exactly one segment; segment boundaries inside a row are multiples of 32 tokens.
  * items may be NULL to query the count.  On return *n_items is the number of segments (written only if it fits
  * `capacity`, else SPD_ERR_WORKSPACE) and *chunk_tokens the tokens per piece (rounded up to 32).
+ * head_per_wave != 0 asks for the schedule of the token-major kernel mapping: a segment then stands for a group of
+ * w consecutive KV heads starting at `kv_head` (w = the largest divisor of n_kv_heads that is <= 8; one wave each),
+ * and head kv_head + j writes partial `slot + j * n_chunks`.
  */
 int spd_build_schedule(const spd_shape *shape, int32_t n_users, const int32_t *lens, int32_t n_compute_units,
-                       spd_work_item *items, int64_t capacity, int64_t *n_items, int32_t *chunk_tokens);
+                       int32_t head_per_wave, spd_work_item *items, int64_t capacity, int64_t *n_items,
+                       int32_t *chunk_tokens);
 
 #ifdef __cplusplus
 }

@@ -97,7 +97,7 @@ def _load() -> C.CDLL:
     lib.spd_validate_partial.restype = C.c_int
     lib.spd_validate_partial.argtypes = [C.POINTER(spd_shape), vp, C.POINTER(spd_kv_view), fp, fp]
     lib.spd_build_schedule.restype = C.c_int
-    lib.spd_build_schedule.argtypes = [C.POINTER(spd_shape), C.c_int32, C.POINTER(C.c_int32), C.c_int32,
+    lib.spd_build_schedule.argtypes = [C.POINTER(spd_shape), C.c_int32, C.POINTER(C.c_int32), C.c_int32, C.c_int32,
                                        C.POINTER(spd_work_item), C.c_int64, C.POINTER(C.c_int64),
                                        C.POINTER(C.c_int32)]
     return lib
@@ -305,17 +305,18 @@ def spd_validate_partial(shape: spd_shape, q_ptr, view: spd_kv_view, out_ptr, ls
     return int(lib.spd_validate_partial(C.byref(shape), q_ptr, C.byref(view), out_ptr, lse_ptr))
 
 
-def spd_build_schedule(shape: spd_shape, lens, n_compute_units: int):
+def spd_build_schedule(shape: spd_shape, lens, n_compute_units: int, head_per_wave: bool = False):
     """Host-only: the split schedule for `lens`.  Returns (list of item dicts, chunk_tokens)."""
     lens = np.ascontiguousarray(lens, dtype=np.int32)
     n = C.c_int64(0)
     chunk = C.c_int32(0)
     lp = lens.ctypes.data_as(C.POINTER(C.c_int32))
-    rc = lib.spd_build_schedule(C.byref(shape), len(lens), lp, n_compute_units, None, 0, C.byref(n), C.byref(chunk))
+    hpw = int(bool(head_per_wave))
+    rc = lib.spd_build_schedule(C.byref(shape), len(lens), lp, n_compute_units, hpw, None, 0, C.byref(n), C.byref(chunk))
     if rc != SPD_OK:
         raise SpdError(rc, "spd_build_schedule")
     items = (spd_work_item * max(1, n.value))()
-    rc = lib.spd_build_schedule(C.byref(shape), len(lens), lp, n_compute_units, items, n.value, C.byref(n),
+    rc = lib.spd_build_schedule(C.byref(shape), len(lens), lp, n_compute_units, hpw, items, n.value, C.byref(n),
                                 C.byref(chunk))
     if rc != SPD_OK:
         raise SpdError(rc, "spd_build_schedule")

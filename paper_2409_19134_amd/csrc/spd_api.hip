@@ -688,7 +688,8 @@ int spd_validate_partial(const spd_shape *shape, const void *q, const spd_kv_vie
 }
 
 int spd_build_schedule(const spd_shape *shape, int32_t n_users, const int32_t *lens, int32_t n_compute_units,
-                       spd_work_item *items, int64_t capacity, int64_t *n_items, int32_t *chunk_tokens)
+                       int32_t head_per_wave, spd_work_item *items, int64_t capacity, int64_t *n_items,
+                       int32_t *chunk_tokens)
 try {
     const int rc = validate_shape(shape);
     if (rc != SPD_OK)
@@ -701,7 +702,7 @@ try {
         if (lens[u] < 0)
             return SPD_ERR_LEN;
     Schedule S;
-    build_schedule(shape->n_kv_heads, n_users, lens, n_compute_units, false, S);
+    build_schedule(shape->n_kv_heads, n_users, lens, n_compute_units, head_per_wave != 0, S);
     *n_items = (int64_t)S.items.size();
     if (chunk_tokens)
         *chunk_tokens = S.chunk_tokens;

@@ -29,7 +29,7 @@ int main(void)
     if (spd_validate_partial(&shape, (const void *)0x1000, &view, (const float *)0x2000, (const float *)0x3000) !=
         SPD_ERR_LEN)
         return 2;
-    rc = spd_build_schedule(&shape, 3, lens, 256, items, 256, &n_items, &chunk);
+    rc = spd_build_schedule(&shape, 3, lens, 256, 0, items, 256, &n_items, &chunk);
     if (rc != SPD_OK || n_items <= 0)
         return 3;
     if (spd_partial_attn_private(NULL, &shape, NULL, &view, NULL, NULL, NULL) != SPD_ERR_NULL)
