@@ -48,7 +48,8 @@ extern "C" {
 #define SPD_OK 0
 #define SPD_ERR_NULL (-1)      /* a required pointer is NULL                                         */
 #define SPD_ERR_SHAPE (-2)     /* unsupported dtype / head counts / head_dim / block size            */
-#define SPD_ERR_LEN (-3)       /* negative count or length, or a paged length beyond max_blocks      */
+#define SPD_ERR_LEN (-3)       /* negative count or length, a length above 2^30, or a paged length
+                                  beyond max_blocks                                                   */
 #define SPD_ERR_ALIGN (-4)     /* a base pointer or stride breaks the 16-byte row alignment          */
 #define SPD_ERR_WORKSPACE (-5) /* scratch memory could not be (re)allocated                          */
 #define SPD_ERR_HIP (-6)       /* a HIP runtime call failed; see spd_last_hip_error                  */
@@ -82,7 +83,7 @@ typedef struct spd_shape {
  */
 typedef struct spd_kv_view {
     int32_t n_users;
-    const int32_t *lens;        /* HOST [n_users] tokens held per user, >= 0                              */
+    const int32_t *lens;        /* HOST [n_users] tokens held per user, 0 .. 2^30                         */
     const void *const *k_ptrs;  /* HOST array [n_users] of DEVICE pointers (contiguous mode)              */
     const void *const *v_ptrs;  /* HOST array [n_users] of DEVICE pointers (contiguous mode)              */
     int64_t token_stride;       /* elements, multiple of 16 bytes                                         */

@@ -10,6 +10,8 @@
 
 namespace spd::host {
 
+constexpr int32_t kMaxLen = 1 << 30;  // tokens per user: token indices and their 32-token steps stay inside int32
+
 inline int elt_size(int dtype) { return dtype == SPD_F32 ? 4 : 2; }
 
 inline int validate_shape(const spd_shape *s)
@@ -49,7 +51,7 @@ inline int validate_view(const spd_shape *s, const spd_kv_view *v)
         return SPD_ERR_SHAPE;
     bool any = false;
     for (int u = 0; u < v->n_users; ++u) {
-        if (v->lens[u] < 0)
+        if (v->lens[u] < 0 || v->lens[u] > kMaxLen)
             return SPD_ERR_LEN;
         any = any || v->lens[u] > 0;
     }

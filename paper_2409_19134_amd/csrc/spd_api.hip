@@ -699,7 +699,7 @@ try {
     if ((n_users > 0 && !lens) || !n_items)
         return SPD_ERR_NULL;
     for (int u = 0; u < n_users; ++u)
-        if (lens[u] < 0)
+        if (lens[u] < 0 || lens[u] > kMaxLen)
             return SPD_ERR_LEN;
     Schedule S;
     build_schedule(shape->n_kv_heads, n_users, lens, n_compute_units, head_per_wave != 0, S);

@@ -104,6 +104,18 @@ def test_validation_rejects_bad_views_and_pointers():
     assert spd.lib.spd_validate_partial(null_shape, Q, C.byref(_view([5])), OUT, LSE) == spd.SPD_ERR_NULL
 
 
+def test_lengths_beyond_two_to_the_thirty_are_rejected():
+    sh = spd.make_shape(spd.SPD_BF16, 32, 8, 128, 0.1)
+    assert _check(sh, _view([1 << 30])) == spd.SPD_OK
+    assert _check(sh, _view([5, (1 << 30) + 1])) == spd.SPD_ERR_LEN
+    assert _check(sh, _view([2 ** 31 - 1])) == spd.SPD_ERR_LEN
+    with pytest.raises(spd.SpdError) as ei:
+        spd.spd_build_schedule(sh, [2 ** 31 - 1], 256)
+    assert ei.value.code == spd.SPD_ERR_LEN
+    items, chunk = spd.spd_build_schedule(sh, [1 << 30], 256)       # the largest length still gets a schedule
+    assert sum(it["t_end"] - it["t_begin"] for it in items) == 8 * (1 << 30)
+
+
 def test_calls_reject_null_context_without_touching_the_gpu():
     sh = spd.make_shape(spd.SPD_BF16, 32, 8, 128, 0.1)
     v = _view([5])
