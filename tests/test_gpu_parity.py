@@ -201,6 +201,40 @@ def test_randomised_cases(ctx, mapping_of, block):
         check_against_oracle(ctx, wl)
 
 
+def _random_case_spec_wide(rng):
+    """Like _random_case_spec, over all three element types, both head sizes, every head group size and KV-head
+    counts that need head groups in the head-per-wave mapping."""
+    kind = rng.random()
+    dtype = torch.bfloat16 if kind < 0.45 else torch.float16 if kind < 0.8 else torch.float32
+    f32 = dtype == torch.float32
+    Hkv = int(rng.choice([1, 2, 3, 4, 8] if f32 else [1, 2, 3, 4, 8, 12, 16, 27]))
+    G = int(rng.choice([1, 2, 3, 4, 5, 6, 7, 8] if f32 else [1, 2, 3, 4, 8, 16]))
+    G = min(G, max(1, 128 // Hkv))
+    d = int(rng.choice([64, 128]))
+    U = int(rng.integers(1, 7))
+    kinds = [lambda: 0, lambda: int(rng.integers(1, 40)), lambda: int(rng.integers(40, 800)),
+             lambda: int(rng.integers(800, 6000)), lambda: int(rng.choice([32, 64, 128, 512, 1024]))]
+    weights = [0.1, 0.25, 0.3, 0.2, 0.15]
+    lens = lambda: [kinds[int(rng.choice(len(kinds), p=weights))]() for _ in range(U)]
+    storage = str(rng.choice(["nhd", "nhd_hpw", "hnd", "hnd_exact", "paged", "paged_tm", "paged_tm_hpw"]))
+    return dict(dtype=dtype, U=U, Hq=Hkv * G, Hkv=Hkv, d=d, lp=lens(), lo=lens(), storage=storage,
+                scale=float(rng.choice([d ** -0.5, 0.02, 0.3])))
+
+
+@pytest.mark.parametrize("block", range(4))
+def test_randomised_cases_all_dtypes_and_head_sizes(ctx, mapping_of, block):
+    rng = np.random.default_rng(9500 + block)
+    for i in range(10):
+        c = _random_case_spec_wide(rng)
+        print(f"randomised wide case {block}.{i}: {c}", flush=True)
+        storage = mapping_of(c["storage"])
+        paged = {"paged": True, "paged_tm": "token_major"}.get(storage, False)
+        layout = "nhd" if paged else storage
+        wl = workloads.random_case(9600 + 16 * block + i, c["dtype"], c["U"], c["Hq"], c["Hkv"], c["d"], c["lp"], c["lo"],
+                                   device=DEV, layout=layout, paged=paged, scale=c["scale"])
+        check_against_oracle(ctx, wl)
+
+
 def _pad_contiguous(side, Hkv, d, pad_tokens, pad_channels, token_major):
     """Re-house every user's K and V in buffers with unused channels after each row and unused rows after each head
     (head-major) or unused channels after each token's heads (token-major); fills the padding with a large value."""
