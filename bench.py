@@ -70,6 +70,11 @@ def main():
                     help="fused mode only: also append one new token per user to the public cache in the same launch "
                          "(its slot is the cache's last token, rewritten every step)")
     ap.add_argument("--layout", default=None, choices=["hnd", "hnd_exact", "nhd"], help="contiguous KV layout override")
+    ap.add_argument("--shape", default=None, metavar="HQ,HKV,D",
+                    help="replace the configuration's head counts and head size (same users, lengths and seeds): other "
+                         "model shapes, e.g. 32,8,64 or 32,32,128; not one of the five benchmark workloads")
+    ap.add_argument("--dtype", default=None, choices=["bf16", "f16", "f32"], help="replace the configuration's element type")
+    ap.add_argument("--users", type=int, default=None, help="replace the configuration's number of users (same length law)")
     ap.add_argument("--pointer-tables", action="store_true",
                     help="contiguous layouts: also pass the per-user pointers in device arrays (address-independent "
                          "schedules, shared by the layers of a model; one more dependent scalar load per segment)")
@@ -91,7 +96,11 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
-    wl = workloads.make_workload(args.config, dev, layout=args.layout)
+    shape = tuple(int(x) for x in args.shape.split(",")) if args.shape else None
+    assert shape is None or len(shape) == 3, "--shape wants Hq,Hkv,d"
+    dtype = {None: None, "bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}[args.dtype]
+    variant = shape is not None or dtype is not None or args.users is not None
+    wl = workloads.make_workload(args.config, dev, layout=args.layout, shape=shape, dtype=dtype, n_users=args.users)
     kv_bytes = wl.kv_bytes
     elt = 4 if wl.dtype == torch.float32 else 2
     per_token = 2 * wl.n_kv_heads * wl.head_dim * elt
@@ -198,7 +207,7 @@ def main():
         "us_per_step": round(ms_per_step * 1e3, 2),
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32" if wl.dtype == torch.float32 else "bf16",
+        "dtype": {torch.float32: "f32", torch.bfloat16: "bf16", torch.float16: "f16"}[wl.dtype],
         "data": "synthetic",
         "host": {"first_call_us_incl_schedule_build_and_upload": round(host_first_call_us, 1),
                  "enqueue_us_per_step_cached": round(host_enqueue_us, 2),
@@ -216,7 +225,7 @@ def main():
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": measured_traffic(args.config, "partial_mfma_kernel" if elt == 2 else "partial_f32_kernel")
-                                if fused else None,
+                                if fused and not variant else None,
                      "bytes_per_launch": launch_bytes, "launches_timed": n_priv,
                      "mean_us": round(priv_mean_us, 2), "min_us": round(priv_min_us, 2),
                      "p10_p50_p90_us": [round(v, 2) for v in priv_pct],
@@ -228,7 +237,7 @@ def main():
     if not args.no_check or not args.no_cpu_baseline:
         from oracle import spd_oracle as orc
         hw = orc.from_workload(wl)
-        full = args.config in (1, 2)
+        full = args.config in (1, 2) and not variant
         if full:
             rows = None
         else:   # big workloads: a bounded sample of output rows
@@ -240,7 +249,7 @@ def main():
             if rows is not None:
                 y = y[[u * wl.n_q_heads + h for u, h in rows]]
             err = float(np.abs(y - Y).max())
-            tol = 1e-5 if elt == 4 else 2e-3
+            tol = {torch.float32: 1e-5, torch.bfloat16: 2e-3, torch.float16: 1e-4}[wl.dtype]
             out["parity"] = {"max_abs_err_vs_fp64_oracle": err, "tolerance": tol, "ok": bool(err <= tol),
                              "rows_checked": "all" if rows is None else len(rows)}
         if not args.no_cpu_baseline:

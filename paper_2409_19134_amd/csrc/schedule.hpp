@@ -18,7 +18,7 @@ constexpr int kChunkMaxDefault = 16384;    // tokens per piece when the work exc
 constexpr int kNoSplitMaxDefault = 768;     // if no row is longer than this the work is latency-bound: every row
                                             // is cut into chunks of one step per wave
 constexpr int kTargetWgPerCuDefault = 2;   // workgroups of the MFMA kernel resident per CU (2 waves per SIMD)
-constexpr int kHeadPerWaveMinSteps = 8;    // 32-token steps per CU from which the head-per-wave mapping is used
+constexpr int kHeadPerWaveMinHeadSteps = 80;  // (32-token steps * KV heads) per CU from which the head-per-wave mapping is used
 
 inline int env_int(const char *name, int dflt)
 {

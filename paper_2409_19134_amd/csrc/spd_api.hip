@@ -128,15 +128,17 @@ int64_t total_steps(const spd_kv_view *v)
 }
 
 // The mapping pays once the launch is bandwidth-bound, i.e. every one-per-CU workgroup gets several 32-token steps;
-// below that the four interleaving waves of the head-major mapping finish a short piece sooner.
+// below that the four interleaving waves of the head-major mapping finish a short piece sooner.  Measured crossover
+// (256 CUs): ~2300 steps with 8 KV heads, between 600 and 1200 with 32, above 1200 with 16: about 330 MB of K/V in
+// each case, so the bound is on steps * KV heads.
 // SPD_HEAD_PER_WAVE=0 / 1 in the environment overrides the rule (never / whenever the layout allows): for tests and
 // measurements.
-bool head_per_wave_pays(const spd_ctx *ctx, int64_t steps)
+bool head_per_wave_pays(const spd_ctx *ctx, const spd_shape *s, int64_t steps)
 {
     const char *force = std::getenv("SPD_HEAD_PER_WAVE");
     if (force && (force[0] == '0' || force[0] == '1'))
         return force[0] == '1';
-    return steps >= (int64_t)std::max(1, ctx->n_cus) * kHeadPerWaveMinSteps;
+    return steps * std::max(8, s->n_kv_heads) >= (int64_t)std::max(1, ctx->n_cus) * kHeadPerWaveMinHeadSteps;
 }
 
 void make_key(const spd_shape *s, const spd_kv_view *v, bool hpw, std::vector<uint8_t> &key)
@@ -392,7 +394,7 @@ int prepare_partial(spd_ctx *ctx, int which, const spd_shape *s, const void *q, 
         return SPD_OK;
     Owner &own = ctx->owner[which];
     // mapping: 1 = head per wave, 0 = head-major, -1 = whatever suits this view on its own
-    const bool hpw = mapping >= 0 ? mapping != 0 : head_per_wave_layout(s, v) && head_per_wave_pays(ctx, total_steps(v));
+    const bool hpw = mapping >= 0 ? mapping != 0 : head_per_wave_layout(s, v) && head_per_wave_pays(ctx, s, total_steps(v));
     const int rs = get_schedule(ctx, own, s, v, hpw, stream, e);
     if (rs != SPD_OK)
         return rs;
@@ -840,7 +842,7 @@ try {
     // both owners share one launch, so they share the mapping: head per wave if both layouts allow it and the two
     // together are bandwidth-bound
     const int hpw = head_per_wave_layout(shape, priv) && head_per_wave_layout(shape, pub) &&
-                    head_per_wave_pays(ctx, total_steps(priv) + total_steps(pub));
+                    head_per_wave_pays(ctx, shape, total_steps(priv) + total_steps(pub));
     rc = prepare_partial(ctx, 0, shape, q, priv, a_in, lse_in, hpw, stream, &ep);
     if (rc != SPD_OK)
         return rc;

@@ -224,16 +224,20 @@ def _make_paged(lens, Hkv, d, dtype, device, seed_k, seed_v, seed_t, ch_scale, s
 
 
 def make_workload(cfg: int, device="cpu", len_div: int = 1, n_users: Optional[int] = None,
-                  layout: Optional[str] = None) -> Workload:
+                  layout: Optional[str] = None, shape=None, dtype=None) -> Workload:
     """Draw workload ``cfg`` on ``device``.
 
     ``len_div`` divides every drawn length (for CPU-sized parity cases);
     ``n_users`` overrides the user count; ``layout`` overrides the contiguous
     layout ("hnd" for configs 1-3, "hnd_exact" for config 4 by default; config 5 is paged).
+    ``shape`` = (Hq, Hkv, d) and ``dtype`` replace the configuration's own (same users, lengths and seeds): for
+    measurements on other model shapes, not part of the five configurations.
     """
     sh = _SHAPES[cfg]
     U = sh["U"] if n_users is None else n_users
-    Hq, Hkv, d, dtype = sh["Hq"], sh["Hkv"], sh["d"], sh["dtype"]
+    Hq, Hkv, d = shape if shape is not None else (sh["Hq"], sh["Hkv"], sh["d"])
+    name = sh["name"] if shape is None and dtype is None and n_users is None else f'{sh["name"]}-variant'
+    dtype = sh["dtype"] if dtype is None else dtype
     lp, lo = draw_lengths(cfg, U, len_div)
     seeds = {fam: seed_of(cfg, fam) for fam in SEED_FAMILIES}
 
@@ -260,7 +264,7 @@ def make_workload(cfg: int, device="cpu", len_div: int = 1, n_users: Optional[in
         priv = _make_contig(lp, Hkv, d, dtype, device, seeds["k_private"], seeds["v_private"], lay, ch_scale)
         pub = _make_contig(lo, Hkv, d, dtype, device, seeds["k_public"], seeds["v_public"], lay, ch_scale)
 
-    return Workload(cfg=cfg, name=sh["name"], dtype=dtype, n_users=U, n_q_heads=Hq,
+    return Workload(cfg=cfg, name=name, dtype=dtype, n_users=U, n_q_heads=Hq,
                     n_kv_heads=Hkv, head_dim=d, scale=1.0 / math.sqrt(d), q=q,
                     private=priv, public=pub, seeds=seeds, outlier_channels=outliers)
 
