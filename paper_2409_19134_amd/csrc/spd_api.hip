@@ -598,7 +598,7 @@ const char *spd_strerror(int code)
     case SPD_OK: return "ok";
     case SPD_ERR_NULL: return "a required pointer is NULL";
     case SPD_ERR_SHAPE: return "unsupported dtype, head counts, head_dim or block size";
-    case SPD_ERR_LEN: return "negative count or length, or a paged length beyond max_blocks";
+    case SPD_ERR_LEN: return "negative count or length, a length above 2^30, or a paged length beyond max_blocks";
     case SPD_ERR_ALIGN: return "pointer or stride breaks the 16-byte row alignment";
     case SPD_ERR_WORKSPACE: return "scratch memory could not be allocated or is too small";
     case SPD_ERR_HIP: return "a HIP runtime call failed";
