@@ -228,6 +228,35 @@ def lse_of(m, gamma):
     return np.where(gamma == 0.0, -np.inf, out)
 
 
+def merge_n(parts):
+    """Theorem 1 for n owners of disjoint token sets (the theorem applied n - 1 times; written out once):
+    with lse_i = m_i + ln gamma_i the merged output is Y = sum_i (e^{lse_i} / sum_j e^{lse_j}) A_i, the weight of
+    part i being its share of the softmax denominator, and lse = ln sum_j e^{lse_j}.
+
+    parts: sequence of (A_i [n_rows, d], lse_i [n_rows]); an empty part has lse_i = -inf and weight 0 (its A_i is
+    ignored).  Returns (Y [n_rows, d], lse [n_rows], w [n_parts, n_rows]); rows whose parts are all empty give
+    Y = 0, lse = -inf, w = 0.
+    """
+    A = [np.asarray(a, dtype=np.float64) for a, _ in parts]
+    L = [np.asarray(l, dtype=np.float64) for _, l in parts]
+    n_rows, d = A[0].shape
+    Y = np.zeros((n_rows, d))
+    lse = np.full(n_rows, -np.inf)
+    W = np.zeros((len(parts), n_rows))
+    for r in range(n_rows):
+        top = max(float(l[r]) for l in L)          # the largest log-sum-exp: shift so that no exponential overflows
+        if top == -np.inf:
+            continue
+        e = [np.exp(float(l[r]) - top) for l in L]
+        den = sum(e)
+        lse[r] = top + np.log(den)
+        for i in range(len(parts)):
+            W[i, r] = e[i] / den
+            if e[i] != 0.0:
+                Y[r] += W[i, r] * A[i][r]
+    return Y, lse, W
+
+
 def attention_mass_track(w_steps, threshold: float):
     """Running statistics of the private part's attention mass w_in = gamma_in / (gamma_in + gamma_out) (the weight
     of A_in in Theorem 1) over a sequence of decode steps: the quantity a user's process would watch to notice that

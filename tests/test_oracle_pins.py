@@ -360,6 +360,48 @@ def test_three_way_merge_any_bracketing():
 # 6. structure: GQA grouping, paging, batching, token order
 
 
+def test_n_way_merge_of_any_partition_equals_unsplit_attention():
+    """A row cut at random points into 1..7 ranges (some empty): the n-way merge of the ranges' partials equals the
+    unsplit attention (Theorem 1 applied repeatedly), and equals folding the two-way merge from the left."""
+    rng = np.random.default_rng(5)
+    wl, hw = _case(71, torch.float32, 3, 4, 2, 16, [57, 0, 120], [0, 0, 0])
+    Y, lse = orc.attention(hw)
+    for n in (1, 2, 3, 5, 7):
+        cuts = np.sort(rng.integers(0, np.maximum(hw.private.lens, 1)[None, :] + 1, size=(n - 1, hw.U)), axis=0)
+        cuts = np.minimum(cuts, hw.private.lens[None, :])
+        edges = np.concatenate([np.zeros((1, hw.U), dtype=np.int64), cuts, hw.private.lens[None, :].astype(np.int64)])
+        raw = [orc.partial(hw, hw.private, edges[i], edges[i + 1]) for i in range(n)]
+        parts = [(A, orc.lse_of(m, g)) for A, m, g in raw]
+        Yn, lse_n, W = orc.merge_n(parts)
+        np.testing.assert_allclose(Yn, Y, rtol=1e-12, atol=1e-13)
+        both_empty = np.isinf(lse)
+        np.testing.assert_allclose(lse_n[~both_empty], lse[~both_empty], rtol=1e-13)
+        assert (lse_n[both_empty] == -np.inf).all() and (Yn[both_empty] == 0).all()
+        np.testing.assert_allclose(W.sum(axis=0)[~both_empty], 1.0, rtol=1e-14)
+        # fold of the two-way form
+        A, m, g = raw[0]
+        for A2, m2, g2 in raw[1:]:
+            A, m, g, _ = orc.merge(A, m, g, A2, m2, g2)
+        np.testing.assert_allclose(Yn, A, rtol=1e-12, atol=1e-13)
+        # the order of the parts does not matter
+        perm = rng.permutation(n)
+        Yp, lse_p, Wp = orc.merge_n([parts[i] for i in perm])
+        np.testing.assert_allclose(Yp, Yn, rtol=1e-13, atol=1e-14)
+        np.testing.assert_allclose(Wp, W[perm], rtol=1e-13)
+
+
+def test_n_way_merge_weights_are_shares_of_the_denominator():
+    """Hand numbers: lse = ln 1, ln 2, ln 5, -inf: weights 1/8, 2/8, 5/8, 0 and lse = ln 8; a huge gap stays finite."""
+    A = [np.full((1, 2), v) for v in (8.0, 16.0, -8.0, 123.0)]
+    L = [np.array([np.log(1.0)]), np.array([np.log(2.0)]), np.array([np.log(5.0)]), np.array([-np.inf])]
+    Y, lse, W = orc.merge_n(list(zip(A, L)))
+    np.testing.assert_allclose(W[:, 0], [0.125, 0.25, 0.625, 0.0], rtol=1e-15)
+    np.testing.assert_allclose(Y[0], [1.0 + 4.0 - 5.0] * 2, rtol=1e-15, atol=1e-15)
+    assert lse[0] == pytest.approx(np.log(8.0), rel=1e-15)
+    Y, lse, W = orc.merge_n([(A[0], np.array([900.0])), (A[1], np.array([-900.0]))])
+    assert lse[0] == 900.0 and W[0, 0] == 1.0 and W[1, 0] == 0.0 and (Y[0] == 8.0).all()
+
+
 def test_gqa_equals_mha_on_replicated_kv_heads():
     U, Hq, Hkv, d = 2, 8, 2, 16
     wl, hw = _case(51, torch.bfloat16, U, Hq, Hkv, d, [19, 5], [4, 0], layout="nhd")
