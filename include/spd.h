@@ -170,6 +170,19 @@ int spd_lse_merge(spd_ctx *ctx, int32_t n_rows, int32_t head_dim, const float *a
                   const float *a1, const float *lse1, float *y, float *lse_out, float *w0_out, void *hip_stream);
 
 /*
+ * The same for n owners of disjoint token sets (Theorem 1 applied n - 1 times, in one launch): e.g. the partials of
+ * a cache that is sharded by sequence over several devices, gathered on one.
+ *   lse = logsumexp_i(lse_i);  w_i = exp(lse_i - lse);  y = sum_i w_i * a_i   (parts in the order given).
+ * a_parts, lse_parts: HOST arrays of n_parts DEVICE pointers ([n_rows][head_dim] and [n_rows] fp32 each), read during
+ * the call only; 1 <= n_parts <= SPD_MAX_MERGE_PARTS.  Parts with lse = -inf have weight 0 and their a_i is ignored;
+ * if all are, y = 0 and lse = -inf.  lse_out [n_rows] and w_out [n_parts][n_rows] (the weights) may be NULL.
+ * y may alias one of the a_i.  head_dim as for spd_lse_merge.
+ */
+#define SPD_MAX_MERGE_PARTS 16
+int spd_lse_merge_n(spd_ctx *ctx, int32_t n_parts, int32_t n_rows, int32_t head_dim, const float *const *a_parts,
+                    const float *const *lse_parts, float *y, float *lse_out, float *w_out, void *hip_stream);
+
+/*
  * One whole decode step of one layer for a caller that holds both owners' caches in one process (section 4, step 3).
  * The paper's prototype overlaps the users' private computation with the service's public one; here both owners'
  * work is placed in one launch (the public owner's short pieces run beside the private owner's long streams on the

@@ -25,7 +25,7 @@ EXPORTED_SYMBOLS = (
     "spd_partial_attn_private", "spd_partial_attn_public_batched", "spd_lse_merge",
     "spd_validate_partial", "spd_build_schedule", "spd_set_kernel_timing", "spd_get_kernel_timing",
     "spd_decode_step", "spd_partial_attn_public_batched_append", "spd_get_schedule_stats",
-    "spd_attention_mass_track", "spd_get_kernel_timing_samples",
+    "spd_attention_mass_track", "spd_get_kernel_timing_samples", "spd_lse_merge_n",
 )
 
 
@@ -77,6 +77,9 @@ def _load() -> C.CDLL:
         fn.argtypes = [vp, C.POINTER(spd_shape), vp, C.POINTER(spd_kv_view), fp, fp, vp]
     lib.spd_lse_merge.restype = C.c_int
     lib.spd_lse_merge.argtypes = [vp, C.c_int32, C.c_int32, fp, fp, fp, fp, fp, fp, fp, vp]
+    lib.spd_lse_merge_n.restype = C.c_int
+    lib.spd_lse_merge_n.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
+                                    fp, fp, fp, vp]
     lib.spd_attention_mass_track.restype = C.c_int
     lib.spd_attention_mass_track.argtypes = [vp, C.c_int32, fp, C.c_float, fp, fp, vp, vp]
     lib.spd_decode_step.restype = C.c_int
@@ -298,6 +301,27 @@ class Context:
                                y.data_ptr(), None if lse_out is None else lse_out.data_ptr(),
                                None if w0_out is None else w0_out.data_ptr(), _stream_ptr(stream))
         self._check(rc, "spd_lse_merge")
+        return y
+
+
+    def spd_lse_merge_n(self, a_parts, lse_parts, y=None, lse_out=None, w_out=None, stream=None):
+        """n-way merge of partials (lists of [n_rows..., d] and [n_rows...] fp32 tensors); w_out: [n_parts, n_rows]."""
+        n = len(a_parts)
+        assert n == len(lse_parts) and n >= 1
+        n_rows = lse_parts[0].numel()
+        d = a_parts[0].shape[-1]
+        if y is None:
+            y = torch.empty_like(a_parts[0])
+        for t in (*a_parts, *lse_parts, y):
+            assert t.is_contiguous() and t.dtype == torch.float32
+        assert all(a.numel() == n_rows * d for a in a_parts) and all(l.numel() == n_rows for l in lse_parts)
+        assert w_out is None or (w_out.is_contiguous() and w_out.dtype == torch.float32 and w_out.numel() == n * n_rows)
+        ap = (C.c_void_p * n)(*[a.data_ptr() for a in a_parts])
+        lp = (C.c_void_p * n)(*[l.data_ptr() for l in lse_parts])
+        rc = lib.spd_lse_merge_n(self.handle, n, n_rows, d, ap, lp, y.data_ptr(),
+                                 None if lse_out is None else lse_out.data_ptr(),
+                                 None if w_out is None else w_out.data_ptr(), _stream_ptr(stream))
+        self._check(rc, "spd_lse_merge_n")
         return y
 
 

@@ -303,6 +303,66 @@ __global__ __launch_bounds__(256) void lse_merge_kernel(int n_rows, int vec_per_
     }
 }
 
+// The merge for up to SPD_MAX_MERGE_PARTS owners; the part pointers travel in the kernel arguments.
+struct MergeParts {
+    const float *a[SPD_MAX_MERGE_PARTS];
+    const float *lse[SPD_MAX_MERGE_PARTS];
+};
+
+// one thread per 4 channels of one row; block (vec_per_row, rows per block).  Every part's row is loaded before y is
+// written, so y may alias a part.
+__global__ __launch_bounds__(256) void lse_merge_n_kernel(int n_parts, int n_rows, int vec_per_row, MergeParts p,
+                                                           float *y, float *__restrict__ lse_out,
+                                                           float *__restrict__ w_out)
+{
+    const int64_t row = (int64_t)blockIdx.x * blockDim.y + threadIdx.y;
+    if (row >= n_rows)
+        return;
+    const int64_t i = row * vec_per_row + threadIdx.x;
+    float l[SPD_MAX_MERGE_PARTS];
+    f32x4 x[SPD_MAX_MERGE_PARTS];
+    float top = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < SPD_MAX_MERGE_PARTS; ++k) {
+        if (k < n_parts) {  // n_parts is uniform: the loads of all parts are in flight together
+            l[k] = p.lse[k][row];
+            x[k] = reinterpret_cast<const f32x4 *>(p.a[k])[i];
+            top = fmaxf(top, l[k]);
+        }
+    }
+    float den = 0.f;
+    f32x4 r = {0.f, 0.f, 0.f, 0.f};
+    float w[SPD_MAX_MERGE_PARTS];
+#pragma unroll
+    for (int k = 0; k < SPD_MAX_MERGE_PARTS; ++k) {
+        if (k < n_parts) {
+            w[k] = top == -INFINITY ? 0.f : fast_exp(l[k] - top);  // exactly 0 for an empty part, exactly 1 for the largest
+            den += w[k];
+        }
+    }
+    const float inv = den > 0.f ? 1.f / den : 0.f;
+#pragma unroll
+    for (int k = 0; k < SPD_MAX_MERGE_PARTS; ++k) {
+        if (k < n_parts) {
+            w[k] *= inv;
+            if (w[k] != 0.f)  // a zero weight ignores its part entirely (it may hold anything)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    r[e] = fmaf(w[k], x[k][e], r[e]);
+        }
+    }
+    reinterpret_cast<f32x4 *>(y)[i] = r;
+    if (threadIdx.x == 0) {
+        if (lse_out)
+            lse_out[row] = den > 0.f ? top + fast_log(den) : -INFINITY;
+        if (w_out)
+#pragma unroll
+            for (int k = 0; k < SPD_MAX_MERGE_PARTS; ++k)
+                if (k < n_parts)
+                    w_out[(int64_t)k * n_rows + row] = w[k];
+    }
+}
+
 // Folds one decode step's private attention masses into running per-row statistics (minimum, sum, count below a
 // threshold); any of the three outputs may be null.
 __global__ __launch_bounds__(256) void mass_track_kernel(int n_rows, const float *__restrict__ w_in, float threshold,

@@ -926,4 +926,38 @@ int spd_lse_merge(spd_ctx *ctx, int32_t n_rows, int32_t head_dim, const float *a
     return SPD_OK;
 }
 
+int spd_lse_merge_n(spd_ctx *ctx, int32_t n_parts, int32_t n_rows, int32_t head_dim, const float *const *a_parts,
+                    const float *const *lse_parts, float *y, float *lse_out, float *w_out, void *hip_stream)
+{
+    if (!ctx)
+        return SPD_ERR_NULL;
+    if (n_rows < 0 || n_parts < 1 || n_parts > SPD_MAX_MERGE_PARTS)
+        return SPD_ERR_LEN;
+    if (head_dim <= 0 || head_dim % 4 != 0 || head_dim > 1024)
+        return SPD_ERR_SHAPE;
+    if (n_rows == 0)
+        return SPD_OK;
+    if (!a_parts || !lse_parts || !y)
+        return SPD_ERR_NULL;
+    spd::MergeParts parts = {};
+    for (int k = 0; k < n_parts; ++k) {
+        if (!a_parts[k] || !lse_parts[k])
+            return SPD_ERR_NULL;
+        if (!aligned16(a_parts[k]))
+            return SPD_ERR_ALIGN;
+        parts.a[k] = a_parts[k];
+        parts.lse[k] = lse_parts[k];
+    }
+    if (!aligned16(y))
+        return SPD_ERR_ALIGN;
+    SPD_HIP(ctx, hipSetDevice(ctx->device));
+    const int vpr = head_dim / 4;              // at most 256
+    const int rows_per_block = std::max(1, 256 / vpr);
+    const unsigned blocks = (unsigned)(((int64_t)n_rows + rows_per_block - 1) / rows_per_block);
+    hipLaunchKernelGGL(spd::lse_merge_n_kernel, dim3(blocks), dim3((unsigned)vpr, (unsigned)rows_per_block), 0,
+                       static_cast<hipStream_t>(hip_stream), (int)n_parts, (int)n_rows, vpr, parts, y, lse_out, w_out);
+    SPD_HIP(ctx, hipGetLastError());
+    return SPD_OK;
+}
+
 }  // extern "C"

@@ -449,6 +449,76 @@ def test_merge_standalone_against_oracle(ctx):
     assert torch.equal(a0c, y)
 
 
+@pytest.mark.parametrize("n_parts,d", [(1, 128), (2, 128), (3, 64), (8, 128), (16, 256), (5, 4)])
+def test_n_way_merge_against_oracle(ctx, n_parts, d):
+    rng = np.random.default_rng(100 + n_parts)
+    n = 259
+    A = [rng.standard_normal((n, d)) for _ in range(n_parts)]
+    L = [rng.normal(0, 30, n) for _ in range(n_parts)]
+    for k in range(n_parts):                       # empty parts hold garbage that must not leak into the result
+        rows = rng.choice(n, size=20, replace=False)
+        L[k][rows] = -np.inf
+        A[k][rows] = np.nan
+    for k in range(n_parts):
+        L[k][:3] = -np.inf                        # rows 0-2: every part empty
+        A[k][:3] = 7.0
+    L[0][3] = 3000.0                               # a gap far beyond the fp32 exponential range
+    if n_parts > 1:
+        L[1][3] = -3000.0
+    t = lambda a: torch.tensor(a, dtype=torch.float32, device=DEV)
+    a_t, l_t = [t(a) for a in A], [t(l) for l in L]
+    y = torch.full((n, d), float("nan"), device=DEV)
+    lse = torch.full((n,), float("nan"), device=DEV)
+    w = torch.full((n_parts, n), float("nan"), device=DEV)
+    ctx.spd_lse_merge_n(a_t, l_t, y, lse, w)
+    torch.cuda.synchronize()
+    # the oracle on the values the GPU saw (fp32-rounded inputs)
+    Y, lse_o, W = orc.merge_n([(a.cpu().double().numpy(), l.cpu().double().numpy()) for a, l in zip(a_t, l_t)])
+    assert maxerr(y, Y) <= 1e-5 * max(1.0, float(np.nanmax(np.abs(Y))))
+    assert maxerr(w, W) <= 1e-6
+    fin = np.isfinite(lse_o)
+    assert maxerr(lse[torch.as_tensor(fin, device=DEV)], lse_o[fin]) <= 1e-3     # |lse| up to 3000 in fp32
+    assert torch.isinf(lse[:3]).all() and (lse[:3] < 0).all() and (y[:3] == 0).all() and (w[:, :3] == 0).all()
+    # in place over one of the parts, and without the optional outputs
+    if n_parts > 1:
+        want = y.clone()
+        keep = a_t[1].clone()
+        ctx.spd_lse_merge_n(a_t, l_t, a_t[1])
+        torch.cuda.synchronize()
+        assert torch.equal(a_t[1], want)
+        a_t[1].copy_(keep)
+    if n_parts == 2:                                # the two-owner call gives the same bits
+        y2 = torch.empty_like(y)
+        a0 = torch.nan_to_num(a_t[0]); a1 = torch.nan_to_num(a_t[1])
+        ctx.spd_lse_merge(a0, l_t[0], a1, l_t[1], y2)
+        torch.cuda.synchronize()
+        assert (y2 - y).abs().max().item() <= 1e-5 * max(1.0, float(np.nanmax(np.abs(Y))))
+
+
+def test_sequence_sharded_cache_merges_to_the_whole(ctx):
+    """A user's cache cut into four consecutive token ranges, each attended to by its own call (what four devices
+    holding a sequence-sharded cache would compute), then one n-way merge: equals attention over the whole cache."""
+    import paper_2409_19134_amd as spd
+    U, Hq, Hkv, d, n_shards = 3, 32, 8, 128, 4
+    lens = [5000, 37, 1203]
+    wl = workloads.random_case(140, torch.bfloat16, U, Hq, Hkv, d, lens, [0, 0, 0], device=DEV, layout="nhd")
+    sh = spd.make_shape(wl.dtype, Hq, Hkv, d, wl.scale)
+    outs, lses = [], []
+    for s in range(n_shards):
+        lo = [L * s // n_shards for L in lens]
+        hi = [L * (s + 1) // n_shards for L in lens]
+        ks = [k[a:b] for k, a, b in zip(wl.private.k, lo, hi)]          # views into the same buffers: [tokens, Hkv, d]
+        vs = [v[a:b] for v, a, b in zip(wl.private.v, lo, hi)]
+        view = spd.KVView([b - a for a, b in zip(lo, hi)], token_stride=Hkv * d, head_stride=d, k=ks, v=vs)
+        o, l = ctx.spd_partial_attn_private(sh, wl.q, view)
+        outs.append(o)
+        lses.append(l)
+    y = ctx.spd_lse_merge_n(outs, lses)
+    torch.cuda.synchronize()
+    Y, _ = orc.attention(orc.from_workload(wl))
+    assert maxerr(y.reshape(U * Hq, d), Y) <= TOL[wl.dtype]
+
+
 def test_error_codes_from_device_calls(ctx):
     import paper_2409_19134_amd as spd
     wl = workloads.random_case(137, torch.bfloat16, 1, 32, 8, 128, [64], [8], device=DEV)
