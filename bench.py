@@ -271,9 +271,15 @@ def main():
                 orc.attention(hw, rows=sample_rows)
                 times.append(time.perf_counter() - a)
             med = float(np.median(times))
+            cpu_model = None
+            try:
+                with open("/proc/cpuinfo") as f:
+                    cpu_model = next((ln.split(":", 1)[1].strip() for ln in f if ln.startswith("model name")), None)
+            except OSError:
+                pass
             out["cpu_baseline"] = {"value": round(sample_bytes / med / 1e9, 4), "unit": "GB/s", "cores": orc.threads(),
                                    "kind": "oracle", "sample": f"{sample_desc}; median of {len(times)} passes",
-                                   "seconds_per_pass": round(med, 4)}
+                                   "seconds_per_pass": round(med, 4), "cpu_model": cpu_model}
     print(json.dumps(out))
     ctx.close()
 
