@@ -220,11 +220,11 @@ def main():
                    "device_pointer_tables": bool(args.pointer_tables and not wl.private.paged),
                    "seeds": wl.seeds},
         "roofline": {"bound": "hbm",
-                     "kernel": ("partial_mfma_kernel" if elt == 2 else "partial_f32_kernel")
+                     "kernel": "partial_mfma_kernel"
                                + (" (both owners, spd_decode_step)" if fused else " (private call)"),
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": measured_traffic(args.config, "partial_mfma_kernel" if elt == 2 else "partial_f32_kernel")
+                     "traffic": measured_traffic(args.config, "partial_mfma_kernel")
                                 if fused and not variant else None,
                      "bytes_per_launch": launch_bytes, "launches_timed": n_priv,
                      "mean_us": round(priv_mean_us, 2), "min_us": round(priv_min_us, 2),

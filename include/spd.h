@@ -64,7 +64,7 @@ typedef struct spd_ctx spd_ctx;
 typedef struct spd_shape {
     int32_t dtype;      /* SPD_F32, SPD_BF16 or SPD_F16: element type of q, K and V                   */
     int32_t n_q_heads;  /* Hq                                                                         */
-    int32_t n_kv_heads; /* Hkv, must divide Hq; Hq / Hkv in 1..16 (bf16, fp16) or 1..8 (fp32)         */
+    int32_t n_kv_heads; /* Hkv, must divide Hq; Hq / Hkv in 1..16                                      */
     int32_t head_dim;   /* d: 64 or 128                                                               */
     float scale;        /* multiplies <q,k> before the softmax; 1/sqrt(d) in the usual case           */
 } spd_shape;

@@ -27,9 +27,7 @@ inline int validate_shape(const spd_shape *s)
     const int G = s->n_q_heads / s->n_kv_heads;
     if (s->head_dim != 64 && s->head_dim != 128)
         return SPD_ERR_SHAPE;
-    // the 16-bit types run on the matrix cores (a tile holds 16 heads); fp32 on the vector path, which keeps the
-    // group's state in registers
-    if (G > (s->dtype != SPD_F32 ? spd::kMaxGroup : 8))
+    if (G > spd::kMaxGroup)  // an MFMA tile holds 16 heads
         return SPD_ERR_SHAPE;
     if (!std::isfinite(s->scale))
         return SPD_ERR_SHAPE;

@@ -1,4 +1,4 @@
-// Partial attention over one chunk of one (user, KV head): bf16 or fp16 K/V, head_dim D = 128 or 64, MFMA path.
+// Partial attention over one chunk of one (user, KV head): bf16, fp16 or fp32 K/V, head_dim D = 128 or 64, MFMA path.
 //
 // What it computes (paper section 4.2): for each of the G query heads that share this KV head,
 //   A = softmax(s) V and lse = ln sum exp(s) over the chunk's tokens, s_i = scale * <q, k_i>,
@@ -21,6 +21,10 @@
 //                   running sum l carries it too, so it cancels in A; lse subtracts it), which keeps
 //                   probabilities down to 4e-9 of the row's largest out of the subnormal range.
 //                   The B operand P^T is exactly the lane's own 8 probabilities.
+// fp32 inputs take the same route with v_mfma_f32_16x16x4_f32 (one k-value per lane instead of eight): the lane's
+// loads, the token each of its values belongs to and the layout of the results are the same as above, only the
+// number of MFMAs per step differs (D/4 for S^T, D/2 for O^T at fp32, against D/16 and D/8 at 16 bits); P needs no
+// split.
 // Every K/V byte is read once per KV head (all G heads share the tile).
 // The four waves of a workgroup take interleaved 32-token steps and are combined through LDS.
 #pragma once
@@ -34,6 +38,7 @@ template <int DT>
 struct Elt;
 template <>
 struct Elt<SPD_BF16> {
+    static constexpr int kBytes = 2;
     typedef __bf16 type;
     typedef __bf16 vec8 __attribute__((ext_vector_type(8)));
     static constexpr float kPShift = 0.f;  // log2 of the factor P carries into the second MFMA
@@ -44,6 +49,7 @@ struct Elt<SPD_BF16> {
 };
 template <>
 struct Elt<SPD_F16> {
+    static constexpr int kBytes = 2;
     typedef _Float16 type;
     typedef _Float16 vec8 __attribute__((ext_vector_type(8)));
     static constexpr float kPShift = 14.f;  // P <= 2^14 < 65504
@@ -53,21 +59,22 @@ struct Elt<SPD_F16> {
     }
 };
 
-template <int D>
-struct VRow;  // a lane's share of one V row: D/16 channels
 template <>
-struct VRow<128> {
-    typedef u32x4 type;
-};
-template <>
-struct VRow<64> {
-    typedef u32x2 type;
+struct Elt<SPD_F32> {
+    static constexpr int kBytes = 4;
+    static constexpr float kPShift = 0.f;
+    static __device__ __forceinline__ f32x4 mfma(float a, float b, f32x4 c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+    }
 };
 
-template <int D>
+// One step's loads of a lane, for rows of RB bytes (D channels of 2 or 4 bytes): RB/64 16-byte pieces of each of its
+// two K rows, and RB/16 bytes (D/16 channels) of each of its eight V rows.
+template <int RB>
 struct TileRegs {
-    u32x4 k[2][D / 32];          // [S tile a][channel block kk]: token row r of tile a, channels kk*32 + grp*8 .. +8
-    typename VRow<D>::type v[8];  // [e]: token tb + grp*8 + e, channels r*(D/16) .. +D/16
+    u32x4 k[2][RB / 64];     // [S tile a][piece kk]: token row r of tile a, bytes kk*64 + grp*16 .. +16
+    unsigned v[8][RB / 64];  // [e][dword]: token tb + grp*8 + e, bytes r*(RB/16) .. +RB/16
 };
 
 struct LaneConst {
@@ -99,8 +106,8 @@ __device__ __forceinline__ PagePair load_pages(const LaneConst &L, int tb, int t
 // Issues the 16 loads of the step at tb.  Paged: P holds that step's page ids on entry and the following step's
 // (tb + step) on return: the lookup is issued behind the data loads, one whole step before it is needed, so that no
 // wave ever waits for a block-table entry before it can ask for data.
-template <int D, bool PAGED, bool APPEND>
-__device__ __forceinline__ void load_tile(TileRegs<D> &T, const LaneConst &L, int tb, int t_last, PagePair &P, int step)
+template <int RB, bool PAGED, bool APPEND>
+__device__ __forceinline__ void load_tile(TileRegs<RB> &T, const LaneConst &L, int tb, int t_last, PagePair &P, int step)
 {
     const int gk = tb + (L.r >> 2) * 8;  // first token of the 8-token group this lane's K rows fall in
     const int gv = tb + L.grp * 8;       // first token of the group this lane's V rows fall in
@@ -116,16 +123,28 @@ __device__ __forceinline__ void load_tile(TileRegs<D> &T, const LaneConst &L, in
         if (APPEND && L.k_new_row && t == t_last)  // the appended token is read from the caller's buffer, not the cache
             p = L.k_new_row + L.grp * 16;
 #pragma unroll
-        for (int kk = 0; kk < D / 32; ++kk)
+        for (int kk = 0; kk < RB / 64; ++kk)
             T.k[a][kk] = stream_load16(p + kk * 64);
     }
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         const int t = min(gv + e, t_last);
-        const char *p = vp + (int64_t)(PAGED ? (t & 15) : t) * L.token_stride + L.r * (D / 8);
+        const char *p = vp + (int64_t)(PAGED ? (t & 15) : t) * L.token_stride + L.r * (RB / 16);
         if (APPEND && L.v_new_row && t == t_last)
-            p = L.v_new_row + L.r * (D / 8);
-        T.v[e] = stream_load<typename VRow<D>::type>(p);
+            p = L.v_new_row + L.r * (RB / 16);
+        if constexpr (RB == 128) {  // 8 bytes per lane and row
+            const u32x2 w = stream_load<u32x2>(p);
+            T.v[e][0] = w[0];
+            T.v[e][1] = w[1];
+        } else {
+#pragma unroll
+            for (int h = 0; h < RB / 256; ++h) {  // 16 or 32 bytes
+                const u32x4 w = stream_load16(p + h * 16);
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    T.v[e][h * 4 + j] = w[j];
+            }
+        }
     }
     if (PAGED)
         P = load_pages(L, tb + step, t_last);
@@ -134,17 +153,29 @@ __device__ __forceinline__ void load_tile(TileRegs<D> &T, const LaneConst &L, in
     __builtin_amdgcn_sched_barrier(0);
 }
 
+// qB: Q as the B operand, loaded like a K row (head r instead of token r): bytes kk*64 + grp*16 .. +16 of the row.
 template <int DT, int D>
-__device__ __forceinline__ void compute_tile(const TileRegs<D> &T, const typename Elt<DT>::vec8 (&qB)[D / 32], int tb,
-                                             int grp, int t_end, float c, float &m, float &l, f32x4 (&acc)[D / 16])
+__device__ __forceinline__ void compute_tile(const TileRegs<D * Elt<DT>::kBytes> &T,
+                                             const u32x4 (&qB)[D * Elt<DT>::kBytes / 64], int tb, int grp, int t_end,
+                                             float c, float &m, float &l, f32x4 (&acc)[D / 16])
 {
-    typedef typename Elt<DT>::vec8 vec8;
-    typedef typename Elt<DT>::type E;
+    constexpr int RB = D * Elt<DT>::kBytes;
     f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+    if constexpr (DT == SPD_F32) {
 #pragma unroll
-    for (int kk = 0; kk < D / 32; ++kk) {
-        s0 = Elt<DT>::mfma(__builtin_bit_cast(vec8, T.k[0][kk]), qB[kk], s0);
-        s1 = Elt<DT>::mfma(__builtin_bit_cast(vec8, T.k[1][kk]), qB[kk], s1);
+        for (int kk = 0; kk < RB / 64; ++kk)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {  // four channels per piece, one MFMA (k = 4: the lane groups) each
+                s0 = Elt<DT>::mfma(__uint_as_float(T.k[0][kk][e]), __uint_as_float(qB[kk][e]), s0);
+                s1 = Elt<DT>::mfma(__uint_as_float(T.k[1][kk][e]), __uint_as_float(qB[kk][e]), s1);
+            }
+    } else {
+        typedef typename Elt<DT>::vec8 vec8;
+#pragma unroll
+        for (int kk = 0; kk < RB / 64; ++kk) {
+            s0 = Elt<DT>::mfma(__builtin_bit_cast(vec8, T.k[0][kk]), __builtin_bit_cast(vec8, qB[kk]), s0);
+            s1 = Elt<DT>::mfma(__builtin_bit_cast(vec8, T.k[1][kk]), __builtin_bit_cast(vec8, qB[kk]), s1);
+        }
     }
     // scores in log2 units; tokens past the chunk end get -inf
     const int t0 = tb + grp * 8;
@@ -173,23 +204,35 @@ __device__ __forceinline__ void compute_tile(const TileRegs<D> &T, const typenam
         for (int cc = 0; cc < D / 16; ++cc)
             acc[cc] *= alpha;
     }
-    vec8 ph, pl;
+    if constexpr (DT == SPD_F32) {
+        // channel phase cc: the lane's dword cc of each of its eight tokens; the MFMA's four k-values are the four
+        // lane groups' tokens grp*8 + e, and the B operand is the lane's own probability of that token
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        ph[e] = (E)p[e];
-        pl[e] = (E)(p[e] - (float)ph[e]);
-    }
+        for (int cc = 0; cc < D / 16; ++cc)
 #pragma unroll
-    for (int cc = 0; cc < D / 16; ++cc) {
-        const int w = cc >> 1;
-        const unsigned sel = (cc & 1) ? 0x07060302u : 0x05040100u;  // odd channel: high halves, even: low halves
-        u32x4 vt;
+            for (int e = 0; e < 8; ++e)
+                acc[cc] = Elt<DT>::mfma(__uint_as_float(T.v[e][cc]), p[e], acc[cc]);
+    } else {
+        typedef typename Elt<DT>::vec8 vec8;
+        typedef typename Elt<DT>::type E;
+        vec8 ph, pl;
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            vt[j] = __builtin_amdgcn_perm(T.v[2 * j + 1][w], T.v[2 * j][w], sel);  // (token 2j, token 2j+1) of channel cc
-        const vec8 va = __builtin_bit_cast(vec8, vt);
-        acc[cc] = Elt<DT>::mfma(va, ph, acc[cc]);
-        acc[cc] = Elt<DT>::mfma(va, pl, acc[cc]);
+        for (int e = 0; e < 8; ++e) {
+            ph[e] = (E)p[e];
+            pl[e] = (E)(p[e] - (float)ph[e]);
+        }
+#pragma unroll
+        for (int cc = 0; cc < D / 16; ++cc) {
+            const int w = cc >> 1;
+            const unsigned sel = (cc & 1) ? 0x07060302u : 0x05040100u;  // odd channel: high halves, even: low halves
+            u32x4 vt;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                vt[j] = __builtin_amdgcn_perm(T.v[2 * j + 1][w], T.v[2 * j][w], sel);  // (token 2j, token 2j+1) of channel cc
+            const vec8 va = __builtin_bit_cast(vec8, vt);
+            acc[cc] = Elt<DT>::mfma(va, ph, acc[cc]);
+            acc[cc] = Elt<DT>::mfma(va, pl, acc[cc]);
+        }
     }
 }
 
@@ -204,7 +247,7 @@ __host__ __device__ constexpr size_t staging_bytes(int D, int waves, int G)
 }
 __host__ __device__ constexpr bool staging_fits(int D, int waves, int G) { return staging_bytes(D, waves, G) <= 64 * 1024; }
 
-// One workgroup per piece (see DevItem); q: [U][Hq][D] of the element type DT (SPD_BF16 or SPD_F16).  A segment that is its row's only one writes out/lse
+// One workgroup per piece (see DevItem); q: [U][Hq][D] of the element type DT (SPD_BF16, SPD_F16 or SPD_F32).  A segment that is its row's only one writes out/lse
 // directly; otherwise it writes part_o[slot][G][D] / part_lse[slot][G], which combine_chunks_kernel then reduces.
 //
 // (Register counts below are those of D = 128; D = 64 needs about half and always runs with PREFETCH.)
@@ -222,9 +265,15 @@ __host__ __device__ constexpr bool staging_fits(int D, int waves, int G) { retur
 // a token range of one (user, KV head) row and its four waves take interleaved steps.
 //
 // APPEND = true adds the KV append (the address substitution costs ~1 % when nothing is appended, hence a flag).
+// Waves per SIMD the kernel is compiled for: a step's loads take RB/4 registers per lane (twice that with PREFETCH).
+__host__ __device__ constexpr int mfma_waves_per_simd(int RB, bool prefetch, bool hpw)
+{
+    return RB == 512 ? 2 : RB == 256 ? (prefetch ? 2 : 3) : (hpw ? 2 : 3);
+}
+
 template <int DT, int D, bool PAGED, bool PREFETCH, bool HPW, bool APPEND>
-__global__ __launch_bounds__(HPW ? 512 : kThreads, D == 128 && !PREFETCH ? 3 : 2 + (D == 64 && !HPW)) void partial_mfma_kernel(
-    OwnerArgs a0, OwnerArgs a1, int n0, const uint16_t *__restrict__ q, int Hq, int G, float scale_log2e)
+__global__ __launch_bounds__(HPW ? 512 : kThreads, mfma_waves_per_simd(D *Elt<DT>::kBytes, PREFETCH, HPW)) void partial_mfma_kernel(
+    OwnerArgs a0, OwnerArgs a1, int n0, const char *__restrict__ q, int Hq, int G, float scale_log2e)
 {
     const bool second = (int)blockIdx.x >= n0;  // workgroup-uniform: which owner this workgroup serves
     const DevItem *__restrict__ items = second ? a1.items : a0.items;
@@ -244,8 +293,8 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, D == 128 && !PREFETCH ? 3 : 2
     extern __shared__ float sm_o[];  // [waves][G * kOStride], sized by the launch: only G heads are staged
     constexpr int kOStride = o_stride(D);
     constexpr int CP = D / 16;  // channel phases of the O^T tile: a lane holds CP consecutive channels per accumulator row
-    constexpr int kRowBytes = D * 2;
-    typedef typename Elt<DT>::vec8 vec8;
+    constexpr int kRowBytes = D * Elt<DT>::kBytes;
+    constexpr int RB = kRowBytes;
     const int o_wave_stride = G * kOStride;
     // head-per-wave results go through a wave-private tile if the launch gave the room
     const bool staged = HPW && staging_fits(D, (int)(blockDim.x >> 6), G);
@@ -257,7 +306,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, D == 128 && !PREFETCH ? 3 : 2
     // Everything a segment needs before its first MFMA: addresses, the KV append copy, Q, and the loads of the wave's
     // first 32-token step.  Issued for the *next* segment before the current one's epilogue, so that the barriers
     // and the result stores of the epilogue overlap the memory round trip instead of preceding it.
-    auto begin_segment = [&](const DevItem &it, LaneConst &L, vec8 (&qB)[D / 32], int &tb, TileRegs<D> &T0, PagePair &P) {
+    auto begin_segment = [&](const DevItem &it, LaneConst &L, u32x4 (&qB)[RB / 64], int &tb, TileRegs<RB> &T0, PagePair &P) {
         L.r = lane & 15;
         L.grp = lane >> 4;
         L.token_stride = kv.token_stride;
@@ -286,21 +335,20 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, D == 128 && !PREFETCH ? 3 : 2
                     copy16(const_cast<char *>(L.v_base) + off, L.v_new_row + (lane - kRowLanes) * 16);
             }
         }
-        // Q as the B operand: head r (zero beyond G), channels kk*32 + grp*8 .. +8
-        const uint16_t *qrow = q + ((int64_t)it.user * Hq + (int64_t)kv_head * G + L.r) * D + L.grp * 8;
+        // Q as the B operand: head r (zero beyond G), read like a K row: bytes kk*64 + grp*16 .. +16
+        const char *qrow = q + ((int64_t)it.user * Hq + (int64_t)kv_head * G + L.r) * kRowBytes + L.grp * 16;
 #pragma unroll
-        for (int kk = 0; kk < D / 32; ++kk) {
-            u32x4 w = {0u, 0u, 0u, 0u};
+        for (int kk = 0; kk < RB / 64; ++kk) {
+            qB[kk] = u32x4{0u, 0u, 0u, 0u};
             if (L.r < G)
-                w = *reinterpret_cast<const u32x4 *>(qrow + kk * 32);
-            qB[kk] = __builtin_bit_cast(vec8, w);
+                qB[kk] = *reinterpret_cast<const u32x4 *>(qrow + kk * 64);
         }
         // head-major: the four waves take interleaved 32-token steps; token-major: every wave takes every step
         tb = HPW ? it.t_begin : it.t_begin + ((uniform(wave) - (it.rot & 3)) & (kWaves - 1)) * 32;
         if (PAGED)
             P = load_pages(L, tb, t_last);
         if (PREFETCH && tb < it.t_end)
-            load_tile<D, PAGED, APPEND>(T0, L, tb, t_last, P, kStep);
+            load_tile<RB, PAGED, APPEND>(T0, L, tb, t_last, P, kStep);
     };
 
     DevItem it = scalar_load_item(items, second ? (int)blockIdx.x - n0 : (int)blockIdx.x);
@@ -317,9 +365,9 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, D == 128 && !PREFETCH ? 3 : 2
         return;
     }
     LaneConst L;
-    vec8 qB[D / 32];
+    u32x4 qB[RB / 64];
     int tb;
-    TileRegs<D> T0;
+    TileRegs<RB> T0;
     PagePair P = {0, 0};
     begin_segment(it, L, qB, tb, T0, P);
     for (;;) {
@@ -338,13 +386,13 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, D == 128 && !PREFETCH ? 3 : 2
 
         if (!PREFETCH) {
             for (; tb < it.t_end; tb += kStep) {
-                TileRegs<D> T;
-                load_tile<D, PAGED, APPEND>(T, L, tb, t_last, P, kStep);
+                TileRegs<RB> T;
+                load_tile<RB, PAGED, APPEND>(T, L, tb, t_last, P, kStep);
                 compute_tile<DT, D>(T, qB, tb, L.grp, it.t_end, scale_log2e, m, l, acc);
             }
         } else if (tb < it.t_end) {  // T0 already holds (the loads of) step tb
             {
-                TileRegs<D> T1;
+                TileRegs<RB> T1;
                 for (;;) {
                     const int tb1 = tb + kStep;
                     const bool more1 = tb1 < it.t_end;
@@ -353,7 +401,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, D == 128 && !PREFETCH ? 3 : 2
                     if (HPW)
                         __builtin_amdgcn_s_barrier();
                     if (more1)
-                        load_tile<D, PAGED, APPEND>(T1, L, tb1, t_last, P, kStep);
+                        load_tile<RB, PAGED, APPEND>(T1, L, tb1, t_last, P, kStep);
                     compute_tile<DT, D>(T0, qB, tb, L.grp, it.t_end, scale_log2e, m, l, acc);
                     if (!more1)
                         break;
@@ -362,7 +410,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, D == 128 && !PREFETCH ? 3 : 2
                     if (HPW)
                         __builtin_amdgcn_s_barrier();
                     if (more2)
-                        load_tile<D, PAGED, APPEND>(T0, L, tb2, t_last, P, kStep);
+                        load_tile<RB, PAGED, APPEND>(T0, L, tb2, t_last, P, kStep);
                     compute_tile<DT, D>(T1, qB, tb1, L.grp, it.t_end, scale_log2e, m, l, acc);
                     if (!more2)
                         break;

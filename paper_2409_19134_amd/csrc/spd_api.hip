@@ -15,7 +15,6 @@
 #include "common.hpp"
 #include "host_checks.hpp"
 #include "partial_mfma.hpp"
-#include "partial_generic.hpp"
 #include "schedule.hpp"
 
 namespace {
@@ -357,31 +356,6 @@ int ensure_scratch(spd_ctx *ctx, Owner &own, size_t o_floats, size_t lse_floats)
     return SPD_OK;
 }
 
-// ev0 / ev1 (both null unless timing is armed) receive the kernel's own start and stop time stamps.
-template <int D, int G>
-void launch_f32(dim3 grid, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1, const OwnerArgs &a0,
-                const OwnerArgs &a1, int n0, const void *q, int Hq, float c)
-{
-    hipExtLaunchKernelGGL((spd::partial_f32_kernel<D, G>), grid, dim3(spd::kThreads), 0, stream, ev0, ev1, 0, a0, a1, n0,
-                          static_cast<const float *>(q), Hq, c);
-}
-
-template <int D>
-void launch_f32_g(int G, dim3 grid, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1, const OwnerArgs &a0,
-                  const OwnerArgs &a1, int n0, const void *q, int Hq, float c)
-{
-    switch (G) {  // validate_shape admits 1..8
-    case 1: launch_f32<D, 1>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
-    case 2: launch_f32<D, 2>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
-    case 3: launch_f32<D, 3>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
-    case 4: launch_f32<D, 4>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
-    case 5: launch_f32<D, 5>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
-    case 6: launch_f32<D, 6>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
-    case 7: launch_f32<D, 7>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
-    default: launch_f32<D, 8>(grid, stream, ev0, ev1, a0, a1, n0, q, Hq, c); break;
-    }
-}
-
 // Validation, schedule lookup and scratch growth of one partial-attention call.
 int prepare_partial(spd_ctx *ctx, int which, const spd_shape *s, const void *q, const spd_kv_view *v, float *out,
                     float *lse, int mapping, hipStream_t stream, CachedSchedule **e)
@@ -452,8 +426,18 @@ int launch_partial(spd_ctx *ctx, int which, const CachedSchedule *e0, const spd_
     const hipEvent_t ev0 = timed ? town.ev_start[town.ev_used] : nullptr;
     const hipEvent_t ev1 = timed ? town.ev_stop[town.ev_used] : nullptr;
     const dim3 grid((unsigned)(n0 + n1));
+    const char *qh = static_cast<const char *>(q);
+#define SPD_LAUNCH_MFMA_A(E, D, PAGED, PREFETCH, HPW, APPEND)                                                        \
+    hipExtLaunchKernelGGL((spd::partial_mfma_kernel<E, D, PAGED, PREFETCH, HPW, APPEND>), grid, blk, (uint32_t)lds,   \
+                          stream, ev0, ev1, 0, a0, a1, (int)n0, qh, s->n_q_heads, G, c)
+#define SPD_LAUNCH_MFMA(E, D, PAGED, PREFETCH, HPW)                                                                   \
+    do {                                                                                                             \
+        if (nt.k)                                                                                                    \
+            SPD_LAUNCH_MFMA_A(E, D, PAGED, PREFETCH, HPW, true);                                                     \
+        else                                                                                                         \
+            SPD_LAUNCH_MFMA_A(E, D, PAGED, PREFETCH, HPW, false);                                                    \
+    } while (0)
     if (s->dtype != SPD_F32) {
-        const uint16_t *qh = static_cast<const uint16_t *>(q);
         const bool hpw = e0->hpw;  // a two-owner launch needs the same mapping on both sides (checked by the caller)
         const int waves = hpw ? head_per_wave_waves(s->n_kv_heads) : spd::kWaves;
         // cross-wave staging; head-per-wave stages its per-wave results too if that fits (the kernel applies the same rule)
@@ -467,16 +451,6 @@ int launch_partial(spd_ctx *ctx, int which, const CachedSchedule *e0, const spd_
         const int64_t cus = std::max(1, ctx->n_cus);
         // With 64 channels a step is half the bytes: always two in flight.
         const bool prefetch = hpw || D == 64 || n0 + n1 > cus * 4 || n0 + n1 <= cus * 2;
-#define SPD_LAUNCH_MFMA_A(E, D, PAGED, PREFETCH, HPW, APPEND)                                                        \
-    hipExtLaunchKernelGGL((spd::partial_mfma_kernel<E, D, PAGED, PREFETCH, HPW, APPEND>), grid, blk, (uint32_t)lds,   \
-                          stream, ev0, ev1, 0, a0, a1, (int)n0, qh, s->n_q_heads, G, c)
-#define SPD_LAUNCH_MFMA(E, D, PAGED, PREFETCH, HPW)                                                                   \
-    do {                                                                                                             \
-        if (nt.k)                                                                                                    \
-            SPD_LAUNCH_MFMA_A(E, D, PAGED, PREFETCH, HPW, true);                                                     \
-        else                                                                                                         \
-            SPD_LAUNCH_MFMA_A(E, D, PAGED, PREFETCH, HPW, false);                                                    \
-    } while (0)
 #define SPD_LAUNCH_MFMA_P(E, D, PAGED)                                                                               \
     do {                                                                                                             \
         if (hpw)                                                                                                     \
@@ -504,15 +478,26 @@ int launch_partial(spd_ctx *ctx, int which, const CachedSchedule *e0, const spd_
             SPD_LAUNCH_MFMA_D(SPD_BF16);
         else
             SPD_LAUNCH_MFMA_D(SPD_F16);
-#undef SPD_LAUNCH_MFMA_A
-#undef SPD_LAUNCH_MFMA
 #undef SPD_LAUNCH_MFMA_P
 #undef SPD_LAUNCH_MFMA_D
-    } else if (s->head_dim == 64) {
-        launch_f32_g<64>(G, grid, stream, ev0, ev1, a0, a1, (int)n0, q, s->n_q_heads, c);
     } else {
-        launch_f32_g<128>(G, grid, stream, ev0, ev1, a0, a1, (int)n0, q, s->n_q_heads, c);
+        // fp32: one step in flight per wave (at 128 channels a step is already 32 KB per wave)
+        const size_t lds = spd::staging_bytes(s->head_dim, spd::kWaves, G);
+        const dim3 blk((unsigned)spd::kThreads);
+        if (s->head_dim == 128) {
+            if (v0->block_size)
+                SPD_LAUNCH_MFMA(SPD_F32, 128, true, false, false);
+            else
+                SPD_LAUNCH_MFMA(SPD_F32, 128, false, false, false);
+        } else {
+            if (v0->block_size)
+                SPD_LAUNCH_MFMA(SPD_F32, 64, true, false, false);
+            else
+                SPD_LAUNCH_MFMA(SPD_F32, 64, false, false, false);
+        }
     }
+#undef SPD_LAUNCH_MFMA_A
+#undef SPD_LAUNCH_MFMA
     SPD_HIP(ctx, hipGetLastError());
     if (timed)
         ++town.ev_used;

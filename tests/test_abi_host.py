@@ -68,7 +68,7 @@ def test_validation_accepts_good_arguments():
     (dict(Hq=30), spd.SPD_ERR_SHAPE),                   # Hq % Hkv != 0
     (dict(d=96), spd.SPD_ERR_SHAPE),
     (dict(Hq=256, Hkv=8), spd.SPD_ERR_SHAPE),           # group of 32 heads
-    (dict(Hq=72, Hkv=8, dtype=spd.SPD_F32), spd.SPD_ERR_SHAPE),   # group of 9 heads in fp32
+    (dict(Hq=136, Hkv=8, dtype=spd.SPD_F32), spd.SPD_ERR_SHAPE),  # group of 17 heads
     (dict(scale=float("nan")), spd.SPD_ERR_SHAPE),
 ])
 def test_validation_rejects_bad_shapes(args, code):

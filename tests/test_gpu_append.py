@@ -75,6 +75,9 @@ CASES = [
     (torch.bfloat16, 32, 8, 64, [2000, 10, 0], [1500, 3000, 1], "nhd_hpw", False),
     (torch.bfloat16, 16, 4, 64, [2000, 10, 0], [1500, 3000, 1], "nhd_hpw", "token_major"),
     (torch.bfloat16, 64, 8, 64, [300, 0, 5000], [32, 1, 4097], "nhd", True),
+    (torch.float32, 8, 8, 64, [128, 5], [16, 1], "nhd", False),
+    (torch.float32, 8, 2, 128, [128, 5, 9], [33, 1, 900], "nhd", True),
+    (torch.float32, 16, 4, 128, [2000, 10, 0], [1500, 3000, 1], "hnd", False),
     (torch.float16, 32, 8, 128, [40, 1, 700, 33], [1, 16, 17, 250], "hnd", False),
     (torch.float16, 32, 8, 128, [2000, 10, 0], [1500, 3000, 1], "nhd_hpw", "token_major"),
     (torch.float16, 32, 8, 64, [2000, 10, 0], [1500, 3000, 1], "nhd", True),

@@ -208,7 +208,7 @@ def _random_case_spec_wide(rng):
     dtype = torch.bfloat16 if kind < 0.45 else torch.float16 if kind < 0.8 else torch.float32
     f32 = dtype == torch.float32
     Hkv = int(rng.choice([1, 2, 3, 4, 8] if f32 else [1, 2, 3, 4, 8, 12, 16, 27]))
-    G = int(rng.choice([1, 2, 3, 4, 5, 6, 7, 8] if f32 else [1, 2, 3, 4, 8, 16]))
+    G = int(rng.choice([1, 2, 3, 4, 5, 6, 7, 8, 16] if f32 else [1, 2, 3, 4, 8, 16]))
     G = min(G, max(1, 128 // Hkv))
     d = int(rng.choice([64, 128]))
     U = int(rng.integers(1, 7))
@@ -352,6 +352,29 @@ def test_fp16_small_probabilities_are_kept(ctx):
     v[0, 1234] = 0.0
     step, errs = check_against_oracle(ctx, wl)
     assert 1.5 < float(step.y[0, 0, 0]) < 2.1
+
+
+@pytest.mark.parametrize("d,Hq,Hkv", [(64, 8, 8), (64, 8, 2), (128, 8, 1), (128, 4, 4), (64, 16, 2), (128, 32, 8), (128, 14, 2),
+                                      (64, 9, 3), (128, 32, 2), (64, 64, 4)])
+@pytest.mark.parametrize("storage", ["hnd", "nhd", "hnd_exact", "paged", "paged_tm"])
+def test_fp32_shapes_and_storage_modes(ctx, d, Hq, Hkv, storage):
+    paged = {"paged": True, "paged_tm": "token_major"}.get(storage, False)
+    wl = workloads.random_case(113, torch.float32, 5, Hq, Hkv, d, [128, 0, 1000, 3, 2500], [16, 5, 0, 77, 300], device=DEV,
+                               layout="nhd" if paged else storage, paged=paged)
+    check_against_oracle(ctx, wl)
+
+
+@pytest.mark.parametrize("lp,lo", [(0, 0), (1, 0), (31, 33), (32, 64), (127, 129), (4097, 1), (40000, 700)])
+@pytest.mark.parametrize("d", [64, 128])
+def test_fp32_edge_lengths(ctx, lp, lo, d):
+    wl = workloads.random_case(114, torch.float32, 2, 8, 2, d, [lp, 77], [lo, 5], device=DEV, layout="hnd")
+    check_against_oracle(ctx, wl)
+
+
+def test_fp32_large_launch(ctx):
+    """64 users x 8 KV heads x 3000 tokens in fp32 (1.6 GB): several resident rounds of pieces; sampled rows."""
+    wl = workloads.random_case(115, torch.float32, 64, 16, 8, 128, [3000] * 64, [100] * 64, device=DEV, layout="hnd")
+    check_against_oracle(ctx, wl, rows=[(0, 0), (63, 15), (31, 7), (17, 9)])
 
 
 def test_peaked_softmax_and_large_score_gap(ctx):
