@@ -247,10 +247,18 @@ __host__ __device__ constexpr size_t staging_bytes(int D, int waves, int G)
 }
 __host__ __device__ constexpr bool staging_fits(int D, int waves, int G) { return staging_bytes(D, waves, G) <= 64 * 1024; }
 
-// One workgroup per piece (see DevItem); q: [U][Hq][D] of the element type DT (SPD_BF16, SPD_F16 or SPD_F32).  A segment that is its row's only one writes out/lse
-// directly; otherwise it writes part_o[slot][G][D] / part_lse[slot][G], which combine_chunks_kernel then reduces.
+// Waves per SIMD the kernel is compiled for: a step's loads take RB/4 registers per lane (twice that with PREFETCH).
+__host__ __device__ constexpr int mfma_waves_per_simd(int RB, bool prefetch, bool hpw)
+{
+    return RB == 512 ? 2 : RB == 256 ? (prefetch ? 2 : 3) : (hpw ? 2 : 3);
+}
+
+// One workgroup per piece (see DevItem); q: [U][Hq][D] of the element type DT (SPD_BF16, SPD_F16 or SPD_F32).  A
+// segment that is its row's only one writes out/lse directly; otherwise it writes part_o[slot][G][D] /
+// part_lse[slot][G], which combine_chunks_kernel then reduces.
 //
-// (Register counts below are those of D = 128; D = 64 needs about half and always runs with PREFETCH.)
+// (Register counts below are those of 256-byte rows: 16-bit elements with D = 128.  Rows of 128 bytes need about half
+// and always run with PREFETCH; fp32 rows of 512 bytes need ~245 with one step in flight and never run with it.)
 // PREFETCH = true keeps two 32-token steps of loads in flight per wave (~245 VGPRs, two waves per SIMD): for launches
 // that run several rounds of workgroups, and for small ones that fit two per CU anyway (half as many dependent round
 // trips per wave).  PREFETCH = false holds one step (~160 VGPRs, three waves per SIMD): as fast when the private
@@ -258,19 +266,13 @@ __host__ __device__ constexpr bool staging_fits(int D, int waves, int G) { retur
 //
 // HPW ("head per wave") is the mapping for contiguous token-major storage, where the KV heads of a token are adjacent
 // in memory ([token][head][d]).  A piece is then a token range of a *user* for a group of up to eight KV heads (all
-// of them if Hkv <= 8), the workgroup has one wave per KV head of the group, and all waves walk the same tokens: together they read whole, consecutive DRAM pages,
-// where one workgroup per head would touch every page eight times at different moments (a barrier per step keeps
-// the waves together).  Each wave owns its head's result, so there is no cross-wave combine; the wave stores its
+// of them if Hkv <= 8), the workgroup has one wave per KV head of the group, and all waves walk the same tokens:
+// together they read whole, consecutive DRAM pages, where one workgroup per head would touch every page eight times
+// at different moments (a barrier per step keeps the waves together).  Each wave owns its head's result, so there is no cross-wave combine; the wave stores its
 // result through an LDS tile of its own.  Without HPW (head-major storage: one contiguous stream per head) a piece is
 // a token range of one (user, KV head) row and its four waves take interleaved steps.
 //
 // APPEND = true adds the KV append (the address substitution costs ~1 % when nothing is appended, hence a flag).
-// Waves per SIMD the kernel is compiled for: a step's loads take RB/4 registers per lane (twice that with PREFETCH).
-__host__ __device__ constexpr int mfma_waves_per_simd(int RB, bool prefetch, bool hpw)
-{
-    return RB == 512 ? 2 : RB == 256 ? (prefetch ? 2 : 3) : (hpw ? 2 : 3);
-}
-
 template <int DT, int D, bool PAGED, bool PREFETCH, bool HPW, bool APPEND>
 __global__ __launch_bounds__(HPW ? 512 : kThreads, mfma_waves_per_simd(D *Elt<DT>::kBytes, PREFETCH, HPW)) void partial_mfma_kernel(
     OwnerArgs a0, OwnerArgs a1, int n0, const char *__restrict__ q, int Hq, int G, float scale_log2e)
