@@ -78,8 +78,9 @@ def main():
     ap.add_argument("--pointer-tables", action="store_true",
                     help="contiguous layouts: also pass the per-user pointers in device arrays (address-independent "
                          "schedules, shared by the layers of a model; one more dependent scalar load per segment)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-check", action="store_true", help="skip the parity check against the oracle")
+    ap.add_argument("--no-cpu-baseline", action="store_true",
+                    help="skip the oracle leg altogether (its timing and the parity check made on its output)")
+    ap.add_argument("--no-check", action="store_true", help="skip the comparison of the GPU result with the oracle's")
     ap.add_argument("--cpu-seconds", type=float, default=1.5,
                     help="wall-clock seconds of oracle passes in the cpu_baseline leg (times the cores it uses: CPU work)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -234,17 +235,40 @@ def main():
                      "us_per_step_while_timed": round(ms_per_step_timed * 1e3, 2)},
     }
 
-    if not args.no_check or not args.no_cpu_baseline:
+    if not args.no_cpu_baseline:
+        # The cpu_baseline leg: the oracle as it stands, on the host cores of this machine, on a bounded sample of the same
+        # workload.  Its output doubles as the parity check of the GPU result (--no-check skips the comparison).
         from oracle import spd_oracle as orc
         hw = orc.from_workload(wl)
         full = args.config in (1, 2) and not variant
         if full:
-            rows = None
+            rows, sample_desc = None, "whole workload, all rows"
+            sample_bytes = kv_bytes
         else:   # big workloads: a bounded sample of output rows
             rng = np.random.default_rng(args.config)
             rows = [(int(rng.integers(wl.n_users)), int(rng.integers(wl.n_q_heads))) for _ in range(4)]
-        if not args.no_check:
+            # a row's share of the algorithmic bytes: its (user, kv head) K/V stream divided among the G query
+            # heads that share it (the whole job is U*Hq rows and reads every stream once)
+            toks = sum(int(wl.private.lens[u]) + int(wl.public.lens[u]) for u, _ in rows)
+            sample_bytes = toks * 2 * wl.head_dim * elt // (wl.n_q_heads // wl.n_kv_heads)
+            sample_desc = f"{len(rows)} sampled (user, head) rows; bytes = their share of the K/V streams"
+        times = []
+        t_begin = time.perf_counter()
+        while len(times) < 5 or (time.perf_counter() - t_begin) < args.cpu_seconds:
+            a = time.perf_counter()
             Y, _ = orc.attention(hw, rows=rows)
+            times.append(time.perf_counter() - a)
+        med = float(np.median(times))
+        cpu_model = None
+        try:
+            with open("/proc/cpuinfo") as f:
+                cpu_model = next((ln.split(":", 1)[1].strip() for ln in f if ln.startswith("model name")), None)
+        except OSError:
+            pass
+        out["cpu_baseline"] = {"value": round(sample_bytes / med / 1e9, 4), "unit": "GB/s", "cores": orc.threads(),
+                               "kind": "oracle", "sample": f"{sample_desc}; median of {len(times)} passes",
+                               "seconds_per_pass": round(med, 4), "cpu_model": cpu_model}
+        if not args.no_check:
             y = steps_objs[0].y.cpu().double().numpy().reshape(wl.n_users * wl.n_q_heads, -1)
             if rows is not None:
                 y = y[[u * wl.n_q_heads + h for u, h in rows]]
@@ -252,34 +276,6 @@ def main():
             tol = {torch.float32: 1e-5, torch.bfloat16: 2e-3, torch.float16: 1e-4}[wl.dtype]
             out["parity"] = {"max_abs_err_vs_fp64_oracle": err, "tolerance": tol, "ok": bool(err <= tol),
                              "rows_checked": "all" if rows is None else len(rows)}
-        if not args.no_cpu_baseline:
-            # the oracle as it stands, on the host cores of this machine, on a bounded sample of the same workload
-            if full:
-                sample_rows, sample_desc = None, "whole workload, all rows"
-                sample_bytes = kv_bytes
-            else:
-                sample_rows = rows
-                # a row's share of the algorithmic bytes: its (user, kv head) K/V stream divided among the G query
-                # heads that share it (the whole job is U*Hq rows and reads every stream once)
-                toks = sum(int(wl.private.lens[u]) + int(wl.public.lens[u]) for u, _ in rows)
-                sample_bytes = toks * 2 * wl.head_dim * elt // (wl.n_q_heads // wl.n_kv_heads)
-                sample_desc = f"{len(rows)} sampled (user, head) rows; bytes = their share of the K/V streams"
-            times = []
-            t_begin = time.perf_counter()
-            while len(times) < 5 or (time.perf_counter() - t_begin) < args.cpu_seconds:
-                a = time.perf_counter()
-                orc.attention(hw, rows=sample_rows)
-                times.append(time.perf_counter() - a)
-            med = float(np.median(times))
-            cpu_model = None
-            try:
-                with open("/proc/cpuinfo") as f:
-                    cpu_model = next((ln.split(":", 1)[1].strip() for ln in f if ln.startswith("model name")), None)
-            except OSError:
-                pass
-            out["cpu_baseline"] = {"value": round(sample_bytes / med / 1e9, 4), "unit": "GB/s", "cores": orc.threads(),
-                                   "kind": "oracle", "sample": f"{sample_desc}; median of {len(times)} passes",
-                                   "seconds_per_pass": round(med, 4), "cpu_model": cpu_model}
     print(json.dumps(out))
     ctx.close()
 

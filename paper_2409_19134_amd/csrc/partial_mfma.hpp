@@ -71,10 +71,36 @@ struct Elt<SPD_F32> {
 
 // One step's loads of a lane, for rows of RB bytes (D channels of 2 or 4 bytes): RB/64 16-byte pieces of each of its
 // two K rows, and RB/16 bytes (D/16 channels) of each of its eight V rows.
+// A lane's share of one V row (RB/16 bytes), kept in the registers its loads deliver it in.
+template <int RB>
+struct VRow;
+template <>
+struct VRow<128> {
+    u32x2 w;
+    __device__ __forceinline__ void load(const char *p) { w = stream_load<u32x2>(p); }
+    __device__ __forceinline__ unsigned dword(int i) const { return w[i]; }
+};
+template <>
+struct VRow<256> {
+    u32x4 w;
+    __device__ __forceinline__ void load(const char *p) { w = stream_load16(p); }
+    __device__ __forceinline__ unsigned dword(int i) const { return w[i]; }
+};
+template <>
+struct VRow<512> {
+    u32x4 w0, w1;
+    __device__ __forceinline__ void load(const char *p)
+    {
+        w0 = stream_load16(p);
+        w1 = stream_load16(p + 16);
+    }
+    __device__ __forceinline__ unsigned dword(int i) const { return i < 4 ? w0[i] : w1[i - 4]; }  // i is a constant
+};
+
 template <int RB>
 struct TileRegs {
-    u32x4 k[2][RB / 64];     // [S tile a][piece kk]: token row r of tile a, bytes kk*64 + grp*16 .. +16
-    unsigned v[8][RB / 64];  // [e][dword]: token tb + grp*8 + e, bytes r*(RB/16) .. +RB/16
+    u32x4 k[2][RB / 64];  // [S tile a][piece kk]: token row r of tile a, bytes kk*64 + grp*16 .. +16
+    VRow<RB> v[8];        // [e]: token tb + grp*8 + e, bytes r*(RB/16) .. +RB/16
 };
 
 struct LaneConst {
@@ -132,19 +158,7 @@ __device__ __forceinline__ void load_tile(TileRegs<RB> &T, const LaneConst &L, i
         const char *p = vp + (int64_t)(PAGED ? (t & 15) : t) * L.token_stride + L.r * (RB / 16);
         if (APPEND && L.v_new_row && t == t_last)
             p = L.v_new_row + L.r * (RB / 16);
-        if constexpr (RB == 128) {  // 8 bytes per lane and row
-            const u32x2 w = stream_load<u32x2>(p);
-            T.v[e][0] = w[0];
-            T.v[e][1] = w[1];
-        } else {
-#pragma unroll
-            for (int h = 0; h < RB / 256; ++h) {  // 16 or 32 bytes
-                const u32x4 w = stream_load16(p + h * 16);
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    T.v[e][h * 4 + j] = w[j];
-            }
-        }
+        T.v[e].load(p);
     }
     if (PAGED)
         P = load_pages(L, tb + step, t_last);
@@ -211,7 +225,7 @@ __device__ __forceinline__ void compute_tile(const TileRegs<D * Elt<DT>::kBytes>
         for (int cc = 0; cc < D / 16; ++cc)
 #pragma unroll
             for (int e = 0; e < 8; ++e)
-                acc[cc] = Elt<DT>::mfma(__uint_as_float(T.v[e][cc]), p[e], acc[cc]);
+                acc[cc] = Elt<DT>::mfma(__uint_as_float(T.v[e].dword(cc)), p[e], acc[cc]);
     } else {
         typedef typename Elt<DT>::vec8 vec8;
         typedef typename Elt<DT>::type E;
@@ -228,7 +242,7 @@ __device__ __forceinline__ void compute_tile(const TileRegs<D * Elt<DT>::kBytes>
             u32x4 vt;
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                vt[j] = __builtin_amdgcn_perm(T.v[2 * j + 1][w], T.v[2 * j][w], sel);  // (token 2j, token 2j+1) of channel cc
+                vt[j] = __builtin_amdgcn_perm(T.v[2 * j + 1].dword(w), T.v[2 * j].dword(w), sel);  // (token 2j, token 2j+1) of channel cc
             const vec8 va = __builtin_bit_cast(vec8, vt);
             acc[cc] = Elt<DT>::mfma(va, ph, acc[cc]);
             acc[cc] = Elt<DT>::mfma(va, pl, acc[cc]);
