@@ -35,3 +35,22 @@ def test_oracle_under_asan_ubsan(tmp_path):
     env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1", OMP_NUM_THREADS="4")
     run = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, env=env, timeout=300)
     assert run.returncode == 0 and run.stdout.strip().endswith("ok 60"), run.stdout[-3000:]
+
+
+@pytest.mark.skipif(not os.path.exists(HIPCC), reason="hipcc not found")
+def test_no_kernel_spills_registers(tmp_path):
+    """Every kernel instance fits its register budget: a spill in the streaming kernel (which has happened after an
+    innocent-looking refactoring) costs several percent of bandwidth without failing any parity test."""
+    import importlib.util
+    import re
+    spec = importlib.util.spec_from_file_location("spd_build", os.path.join(ROOT, "paper_2409_19134_amd", "build.py"))
+    build = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(build)
+    cmd = [HIPCC, *build.HIPCC_FLAGS, "-Rpass-analysis=kernel-resource-usage", "-o", str(tmp_path / "lib.so"),
+           os.path.join(ROOT, "paper_2409_19134_amd", "csrc", "spd_api.hip")]
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    assert res.returncode == 0, res.stdout[-3000:]
+    spills = [int(x) for x in re.findall(r"VGPRs Spill: (\d+)", res.stdout)]
+    scratch = [int(x) for x in re.findall(r"ScratchSize \[bytes/lane\]: (\d+)", res.stdout)]
+    assert len(spills) >= 40 and len(scratch) == len(spills)          # every kernel instance reported
+    assert max(spills) == 0 and max(scratch) == 0
