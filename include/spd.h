@@ -121,7 +121,8 @@ int spd_last_hip_error(const spd_ctx *ctx);
  * those it remembers (`hits`).  A schedule is determined by the lengths, the storage mode and strides and, in
  * contiguous mode without device pointer arrays, the per-user base pointers - not by q, the outputs, the block table
  * or the pools; so the layers of a model that share lengths (and a block table, or pass k_ptrs_dev / v_ptrs_dev) share
- * one schedule per decode step.
+ * one schedule.  A view whose lengths have all grown by the same 1..64 tokens since its schedule was built (a decode
+ * loop that appends a token per user and step) is served by that schedule too and counts as a hit.
  */
 int spd_get_schedule_stats(const spd_ctx *ctx, int64_t *builds, int64_t *hits);
 

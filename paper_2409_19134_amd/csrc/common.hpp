@@ -162,7 +162,18 @@ struct OwnerArgs {
     // (position lens[u] - 1) is then taken from here, and the segment that ends the row also writes it to the cache.
     const char *k_new;
     const char *v_new;
+    // Tokens every row has gained since the schedule was built (a decode loop appends one token per user and step):
+    // added to t_end of the segments that end their row, so that a schedule serves several consecutive steps.
+    int32_t grow;
 };
+
+// A work item with the row's growth applied.
+__device__ __forceinline__ DevItem scalar_load_item(const DevItem *items, int idx, int grow)
+{
+    DevItem it = scalar_load_item(items, idx);
+    it.t_end += (it.rot & kEndsRow) ? grow : 0;
+    return it;
+}
 
 // A row (user, KV head) whose tokens were split into several chunks.
 struct CombineRow {

@@ -304,6 +304,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, mfma_waves_per_simd(D *Elt<DT
     float *__restrict__ lse = second ? a1.lse : a0.lse;
     const char *k_new = second ? a1.k_new : a0.k_new;
     const char *v_new = second ? a1.v_new : a0.v_new;
+    const int grow = second ? a1.grow : a0.grow;
     __shared__ float sm_m[kWaves][16];
     __shared__ float sm_l[kWaves][16];
     extern __shared__ float sm_o[];  // [waves][G * kOStride], sized by the launch: only G heads are staged
@@ -367,7 +368,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, mfma_waves_per_simd(D *Elt<DT
             load_tile<RB, PAGED, APPEND>(T0, L, tb, t_last, P, kStep);
     };
 
-    DevItem it = scalar_load_item(items, second ? (int)blockIdx.x - n0 : (int)blockIdx.x);
+    DevItem it = scalar_load_item(items, second ? (int)blockIdx.x - n0 : (int)blockIdx.x, grow);
     if (it.n_chunks == 0) {  // a row without tokens (head-per-wave: a user without tokens) is a piece of its own
         if (HPW) {
             const int64_t head0 = (int64_t)it.user * Hq + (int64_t)(it.kv_head + wave) * G;
@@ -391,7 +392,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, mfma_waves_per_simd(D *Elt<DT
         // flight a dependent round trip costs microseconds, so none may sit between two segments
         DevItem nx = it;
         if (it.next >= 0)
-            nx = scalar_load_item(items, it.next);
+            nx = scalar_load_item(items, it.next, grow);
         const int t_last = it.t_end - 1;
 
         float m = -INFINITY, l = 0.f;

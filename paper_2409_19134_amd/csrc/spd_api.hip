@@ -52,6 +52,9 @@ uint64_t hash_key(const uint8_t *p, size_t n)
 struct CachedSchedule {
     bool valid = false;
     uint64_t hash = 0, last_use = 0;
+    uint64_t hash_but_lens = 0;  // of the key without the lengths: finds the schedule of a view that has grown since
+    bool growable = false;       // no user without tokens (a row that only writes A = 0 cannot gain tokens)
+    int32_t grow = 0;            // set by every lookup: tokens each row has gained over the lengths in `key`
     std::vector<uint8_t> key;
     int64_t n_items = 0, n_slots = 0;
     bool hpw = false;        // pieces are for the head-per-wave kernel
@@ -140,6 +143,40 @@ bool head_per_wave_pays(const spd_ctx *ctx, const spd_shape *s, int64_t steps)
     return steps * std::max(8, s->n_kv_heads) >= (int64_t)std::max(1, ctx->n_cus) * kHeadPerWaveMinHeadSteps;
 }
 
+// A decode loop appends one token per user and step: a schedule built for the lengths L serves L + g for
+// 1 <= g <= kMaxGrow as well (the kernels add g to the end of every row's last segment), which spares the loop a
+// rebuild and an upload per step.  Beyond that the pieces would drift out of balance and a new schedule is built.
+constexpr int32_t kMaxGrow = 64;
+constexpr size_t kKeyLensOffset = 6 * sizeof(int32_t);  // the lengths follow the key's six-integer head
+
+uint64_t hash_key_but_lens(const std::vector<uint8_t> &key, int n_users)
+{
+    const size_t tail = kKeyLensOffset + sizeof(int32_t) * (size_t)n_users;
+    return hash_key(key.data(), kKeyLensOffset) ^ (hash_key(key.data() + tail, key.size() - tail) * 0x9E3779B97F4A7C15ull);
+}
+
+// g if `key` is `e`'s key with every length g larger (1 <= g <= kMaxGrow), else 0.
+int32_t uniform_growth(const CachedSchedule &e, const std::vector<uint8_t> &key, int n_users)
+{
+    if (!e.growable || n_users == 0 || e.key.size() != key.size())
+        return 0;
+    const size_t tail = kKeyLensOffset + sizeof(int32_t) * (size_t)n_users;
+    if (std::memcmp(e.key.data(), key.data(), kKeyLensOffset) != 0 ||
+        std::memcmp(e.key.data() + tail, key.data() + tail, key.size() - tail) != 0)
+        return 0;
+    int32_t g = 0;
+    for (int u = 0; u < n_users; ++u) {
+        int32_t was, now;
+        std::memcpy(&was, e.key.data() + kKeyLensOffset + sizeof(int32_t) * (size_t)u, sizeof was);
+        std::memcpy(&now, key.data() + kKeyLensOffset + sizeof(int32_t) * (size_t)u, sizeof now);
+        if (u == 0)
+            g = now - was;
+        if (now - was != g || g < 1 || g > kMaxGrow)
+            return 0;
+    }
+    return g;
+}
+
 void make_key(const spd_shape *s, const spd_kv_view *v, bool hpw, std::vector<uint8_t> &key)
 {
     key.clear();
@@ -149,6 +186,7 @@ void make_key(const spd_shape *s, const spd_kv_view *v, bool hpw, std::vector<ui
     };
     const int32_t head[6] = {s->dtype, s->n_q_heads, s->n_kv_heads, v->n_users, v->block_size,
                              hpw ? 1 : 0};
+    static_assert(sizeof head == kKeyLensOffset, "the lengths follow the head");
     put(head, sizeof head);
     put(v->lens, sizeof(int32_t) * (size_t)v->n_users);
     // the items carry row base addresses (contiguous mode) or row offsets inside the pools (paged mode): the key holds
@@ -177,15 +215,26 @@ int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view
     std::vector<uint8_t> &key = ctx->key_scratch;  // reused from call to call: no allocation on the hit path
     make_key(s, v, hpw, key);
     const uint64_t h = hash_key(key.data(), key.size());
+    const uint64_t h_but_lens = hash_key_but_lens(key, v->n_users);
     ++ctx->tick;
     CachedSchedule *victim = &own.cache[0];
+    CachedSchedule *grown = nullptr;  // a schedule of the same view with uniformly shorter lengths
+    int32_t grown_by = 0;
     for (auto &e : own.cache) {
         if (e.valid && e.hash == h && e.key == key) {
             e.last_use = ctx->tick;
             e.last_stream = stream;
+            e.grow = 0;
             ++ctx->schedule_hits;
             *out = &e;
             return SPD_OK;
+        }
+        if (e.valid && e.hash_but_lens == h_but_lens) {
+            const int32_t g = uniform_growth(e, key, v->n_users);
+            if (g > 0 && (!grown || g < grown_by)) {
+                grown = &e;
+                grown_by = g;
+            }
         }
         if (!e.valid) {
             if (victim->valid)
@@ -193,6 +242,14 @@ int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view
         } else if (victim->valid && e.last_use < victim->last_use) {
             victim = &e;
         }
+    }
+    if (grown) {
+        grown->last_use = ctx->tick;
+        grown->last_stream = stream;
+        grown->grow = grown_by;
+        ++ctx->schedule_hits;
+        *out = grown;
+        return SPD_OK;
     }
     Schedule S;
     build_schedule(s->n_kv_heads, v->n_users, v->lens, ctx->n_cus, hpw, S);
@@ -315,6 +372,11 @@ int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view
     e.last_stream = stream;
     e.valid = true;
     e.hash = h;
+    e.hash_but_lens = h_but_lens;
+    e.growable = true;
+    for (int u = 0; u < v->n_users; ++u)
+        e.growable = e.growable && v->lens[u] > 0;
+    e.grow = 0;
     e.key = key;
     e.last_use = ctx->tick;
     e.n_items = n_groups;
@@ -397,6 +459,7 @@ OwnerArgs owner_args(const Owner &own, const CachedSchedule *e, const spd_shape 
     a.lse = lse;
     a.k_new = static_cast<const char *>(k_new);
     a.v_new = static_cast<const char *>(v_new);
+    a.grow = e->grow;
     return a;
 }
 

@@ -203,11 +203,11 @@ def test_layers_share_one_schedule_per_step_in_paged_mode():
             outs.append(step)
         torch.cuda.synchronize()
         builds, hits = ctx.spd_get_schedule_stats()
-        # the private schedule is built once (step 0), the public one once per step; every other call is a hit
-        assert builds - builds0 == (s + 1) + 1
+        # both schedules are built once (step 0): the public one also serves the lengths of the following steps
+        assert builds - builds0 == 2
         for w, step in zip(layers, outs):
             assert _err(step, _oracle_y(w)) <= 2e-3
-    assert hits == 2 * n_layers * n_steps - (n_steps + 1)
+    assert hits == 2 * n_layers * n_steps - 2
     ctx.close()
 
 
@@ -244,11 +244,11 @@ def test_layers_share_one_schedule_with_device_pointer_tables(layout):
             for w, step in zip(layers, outs):
                 assert _err(step, _oracle_y(w)) <= 2e-3
         builds, hits = ctx.spd_get_schedule_stats()
-        if tables:   # private: one build in all; public: one per step
-            assert builds - builds0 == 1 + n_steps
-            assert hits - hits0 == 2 * n_layers * n_steps - (1 + n_steps)
-        else:        # private: one per layer; public: one per layer and step
-            assert builds - builds0 == n_layers + n_layers * n_steps
+        if tables:   # one build per owner in all (the public one also serves the grown lengths of the later steps)
+            assert builds - builds0 == 2
+            assert hits - hits0 == 2 * n_layers * n_steps - 2
+        else:        # one per owner and layer
+            assert builds - builds0 == 2 * n_layers
     ctx.close()
 
 
@@ -377,4 +377,53 @@ def test_layers_captured_in_one_hip_graph(fused):
             assert torch.equal(s.y, y), f"replay {rep}"
     for w, s in zip(layers, steps):
         assert _err(s, _oracle_y(w)) <= 2e-3
+    ctx.close()
+
+
+@pytest.mark.parametrize("storage", ["hnd", "nhd_hpw", "paged", "paged_tm_hpw"])
+@pytest.mark.parametrize("fused", [True, False])
+def test_decode_loop_reuses_the_public_schedule_while_the_cache_grows(storage, fused, monkeypatch):
+    """150 decode steps, one token appended per user and step: the public schedule is rebuilt only every 65th step
+    (a schedule serves lengths up to 64 tokens beyond those it was built for), rows cross 32-token steps and pages on
+    the way, and every step's result is right."""
+    import paper_2409_19134_amd as spd
+    hpw = storage.endswith("_hpw")
+    monkeypatch.setenv("SPD_HEAD_PER_WAVE", "1" if hpw else "0")
+    storage = storage[:-4] if hpw else storage
+    paged = {"paged": True, "paged_tm": "token_major"}.get(storage, False)
+    ctx = spd.Context(0)
+    U, Hq, Hkv, d, n_steps = 4, 16, 4, 128, 150
+    lp, lo0 = [300, 33, 1500, 64], [1, 30, 700, 95]
+    cap = [x + n_steps for x in lo0]
+    wl = workloads.random_case(560, torch.bfloat16, U, Hq, Hkv, d, lp, cap, device=DEV,
+                               layout="nhd" if paged else storage, paged=paged)
+    sh = spd.make_shape(wl.dtype, Hq, Hkv, d, wl.scale)
+    g = torch.Generator(device=DEV).manual_seed(9)
+    builds0, hits0 = ctx.spd_get_schedule_stats()
+    check_at = {0, 1, 2, 31, 63, 64, 65, 66, 100, 129, 130, 149}
+    for s in range(n_steps):
+        wl.public.lens = np.asarray([x + s for x in lo0], dtype=np.int32)        # step 0: the lengths as built
+        if s > 0:        # the token of this step goes in with the call
+            kn = torch.randn((U, Hkv, d), generator=g, device=DEV).to(torch.bfloat16)
+            vn = torch.randn((U, Hkv, d), generator=g, device=DEV).to(torch.bfloat16)
+        else:
+            kn = vn = None
+        wl.q = torch.randn((U, Hq, d), generator=g, device=DEV).to(torch.bfloat16)
+        step = spd.DecodeStep.from_workload(ctx, wl)
+        if fused:
+            step.run_fused(wl.q, k_new=kn, v_new=vn)
+        else:
+            step.ctx.spd_partial_attn_private(sh, wl.q, step.private, step.a_in, step.lse_in)
+            if kn is None:
+                step.ctx.spd_partial_attn_public_batched(sh, wl.q, step.public, step.a_out, step.lse_out)
+            else:
+                step.ctx.spd_partial_attn_public_batched_append(sh, wl.q, kn, vn, step.public, step.a_out, step.lse_out)
+            step.ctx.spd_lse_merge(step.a_in, step.lse_in, step.a_out, step.lse_out, step.y)
+        if s in check_at:
+            torch.cuda.synchronize()
+            assert _err(step, _oracle_y(wl)) <= 2e-3, f"step {s}"
+    torch.cuda.synchronize()
+    builds, hits = ctx.spd_get_schedule_stats()
+    assert builds - builds0 == 1 + 3           # private once; public at steps 0, 65 and 130
+    assert hits - hits0 == 2 * n_steps - 4
     ctx.close()
