@@ -427,3 +427,15 @@ def test_decode_loop_reuses_the_public_schedule_while_the_cache_grows(storage, f
     assert builds - builds0 == 1 + 3           # private once; public at steps 0, 65 and 130
     assert hits - hits0 == 2 * n_steps - 4
     ctx.close()
+
+
+def test_c_program_runs_the_path_without_python():
+    """tests/host/abi_gpu_program.cpp knows only include/spd.h and the HIP runtime: the three calls and the fused step
+    from a plain program, against a closed form (zero keys: the result is the mean of V)."""
+    import os
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    exe = os.path.join(root, "tests", "host", "abi_gpu_program")
+    assert os.path.exists(exe), "build it first: python -c 'import __graft_entry__ as g; g.build()'"
+    run = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=120)
+    assert run.returncode == 0 and run.stdout.strip().endswith("c abi gpu ok"), run.stdout[-2000:]
