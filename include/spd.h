@@ -74,7 +74,8 @@ typedef struct spd_shape {
  *
  * Contiguous mode (block_size == 0): user u's K and V start at k_ptrs[u] / v_ptrs[u]; element (token i, KV head j,
  * channel c) is at offset i*token_stride + j*head_stride + c (in elements; head_strides[u] instead of head_stride if
- * that array is given).  Buffers of different users may be separate allocations.  A user with lens[u] == 0 may have NULL pointers.
+ * that array is given).  Buffers of different users may be separate allocations.  A user with lens[u] == 0 may
+ * have NULL pointers.
  *
  * Paged mode (block_size == 16): element (token i, head j, channel c) of user u is at
  * pool + block_table[u*max_blocks + i/16]*block_stride + j*head_stride + (i%16)*token_stride + c.
