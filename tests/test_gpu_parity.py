@@ -542,6 +542,18 @@ def test_sequence_sharded_cache_merges_to_the_whole(ctx):
     assert maxerr(y.reshape(U * Hq, d), Y) <= TOL[wl.dtype]
 
 
+@pytest.mark.parametrize("dtype,scale", [
+    (torch.bfloat16, 0.0), (torch.float16, 0.0), (torch.float32, 0.0),
+    (torch.bfloat16, -0.25), (torch.float16, -0.25), (torch.float32, -0.25),
+    (torch.bfloat16, 4.0), (torch.float16, 4.0),
+    (torch.float32, 0.5)])   # fp32's 1e-5 bar is below half an fp32 ulp of scores (and log-sum-exps) of several hundred
+def test_unusual_scales(ctx, dtype, scale):
+    """scale = 0 (uniform weights: the mean of V), a negative scale (the least similar key wins) and a large one
+    (scores of several hundred for the 16-bit types: nearly one-hot rows)."""
+    wl = workloads.random_case(150, dtype, 3, 8, 2, 128, [700, 0, 65], [40, 3, 0], device=DEV, layout="hnd", scale=scale)
+    check_against_oracle(ctx, wl)
+
+
 def test_error_codes_from_device_calls(ctx):
     import paper_2409_19134_amd as spd
     wl = workloads.random_case(137, torch.bfloat16, 1, 32, 8, 128, [64], [8], device=DEV)
