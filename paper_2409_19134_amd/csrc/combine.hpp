@@ -363,6 +363,14 @@ __global__ __launch_bounds__(256) void lse_merge_n_kernel(int n_parts, int n_row
     }
 }
 
+// Copies a freshly built schedule from its pinned host staging buffer to device memory (n16 16-byte words).
+__global__ __launch_bounds__(256) void upload_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, unsigned n16)
+{
+    const unsigned i = blockIdx.x * 256u + threadIdx.x;
+    if (i < n16)
+        dst[i] = src[i];
+}
+
 // Folds one decode step's private attention masses into running per-row statistics (minimum, sum, count below a
 // threshold); any of the three outputs may be null.
 __global__ __launch_bounds__(256) void mass_track_kernel(int n_rows, const float *__restrict__ w_in, float threshold,

@@ -63,12 +63,20 @@ struct CachedSchedule {
     char *dev = nullptr;     // DevItem[n_items] | CombineRow[n_split_rows] | RowInfo[n_users * Hkv]
     char *pinned = nullptr;  // host staging copy of the same blob
     size_t capacity = 0;
+    bool in_slab = false;    // dev / pinned are slots of the owner's slab, not allocations of their own
     hipStream_t last_stream = nullptr;  // stream of the latest call that used this entry
     hipEvent_t uploaded = nullptr;      // completes when the latest upload has left the staging copy
 };
 
+// Most schedules are a few tens of KB: the first kSlabEntries entries of an owner share one device and one pinned
+// allocation of kSlabSlot bytes each (made when the first schedule is built), so that a run of new views - a serving
+// loop whose batch keeps changing - does not pay two allocations per view.  Larger schedules get storage of their own.
+constexpr size_t kSlabSlot = 64 * 1024;
+constexpr size_t kSlabEntries = 128;
+
 struct Owner {
     std::vector<CachedSchedule> cache;
+    char *slab_dev = nullptr, *slab_pinned = nullptr;
     float *part_o = nullptr;
     float *part_lse = nullptr;
     size_t part_o_cap = 0, part_lse_cap = 0;  // floats
@@ -103,9 +111,9 @@ namespace {
 
 void free_entry(CachedSchedule &e)
 {
-    if (e.dev)
+    if (e.dev && !e.in_slab)
         (void)hipFree(e.dev);
-    if (e.pinned)
+    if (e.pinned && !e.in_slab)
         (void)hipHostFree(e.pinned);
     if (e.uploaded)
         (void)hipEventDestroy(e.uploaded);
@@ -352,10 +360,27 @@ int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view
         SPD_HIP(ctx, hipEventSynchronize(e.uploaded));
     }
     if (e.capacity < total) {
-        const size_t cap = std::max(total, e.capacity);
-        free_entry(e);  // hipFree waits for the device
-        SPD_HIP(ctx, hipMalloc(reinterpret_cast<void **>(&e.dev), cap));
-        SPD_HIP(ctx, hipHostMalloc(reinterpret_cast<void **>(&e.pinned), cap, hipHostMallocDefault));
+        // Rounded up to a power of two (at least 64 KB): a serving loop whose batch changes a little every step builds
+        // schedules of slightly different sizes, and growing an entry costs a hipFree (which waits for the device)
+        // and two allocations.
+        size_t cap = kSlabSlot;
+        while (cap < total)
+            cap *= 2;
+        const size_t idx = (size_t)(&e - own.cache.data());
+        free_entry(e);  // hipFree (storage of its own only) waits for the device
+        if (cap == kSlabSlot && idx < kSlabEntries) {
+            if (!own.slab_dev) {
+                const size_t bytes = kSlabSlot * std::min(kSlabEntries, own.cache.size());
+                SPD_HIP(ctx, hipMalloc(reinterpret_cast<void **>(&own.slab_dev), bytes));
+                SPD_HIP(ctx, hipHostMalloc(reinterpret_cast<void **>(&own.slab_pinned), bytes, hipHostMallocDefault));
+            }
+            e.dev = own.slab_dev + idx * kSlabSlot;
+            e.pinned = own.slab_pinned + idx * kSlabSlot;
+            e.in_slab = true;
+        } else {
+            SPD_HIP(ctx, hipMalloc(reinterpret_cast<void **>(&e.dev), cap));
+            SPD_HIP(ctx, hipHostMalloc(reinterpret_cast<void **>(&e.pinned), cap, hipHostMallocDefault));
+        }
         e.capacity = cap;
     }
     if (!e.uploaded)
@@ -367,7 +392,14 @@ int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view
         std::memcpy(e.pinned + off_rows, split_rows.data(), b_rows);
     if (b_info)
         std::memcpy(e.pinned + off_info, row_info.data(), b_info);
-    SPD_HIP(ctx, hipMemcpyAsync(e.dev, e.pinned, total, hipMemcpyHostToDevice, stream));
+    // The upload is a kernel that reads the pinned staging copy over the bus: a copy command would leave the compute
+    // queue for a DMA engine and back, which costs the stream tens of microseconds per schedule.
+    {
+        const unsigned n16 = (unsigned)(total / 16);  // total is a multiple of 256
+        hipLaunchKernelGGL(spd::upload_kernel, dim3((n16 + 255) / 256), dim3(256), 0, stream,
+                           reinterpret_cast<const spd::u32x4 *>(e.pinned), reinterpret_cast<spd::u32x4 *>(e.dev), n16);
+        SPD_HIP(ctx, hipGetLastError());
+    }
     SPD_HIP(ctx, hipEventRecord(e.uploaded, stream));
     e.last_stream = stream;
     e.valid = true;
@@ -695,6 +727,10 @@ int spd_destroy(spd_ctx *ctx)
     for (auto &own : ctx->owner) {
         for (auto &e : own.cache)
             free_entry(e);
+        if (own.slab_dev)
+            (void)hipFree(own.slab_dev);
+        if (own.slab_pinned)
+            (void)hipHostFree(own.slab_pinned);
         if (own.part_o)
             (void)hipFree(own.part_o);
         if (own.part_lse)
