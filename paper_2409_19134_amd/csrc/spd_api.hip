@@ -223,11 +223,8 @@ int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view
     std::vector<uint8_t> &key = ctx->key_scratch;  // reused from call to call: no allocation on the hit path
     make_key(s, v, hpw, key);
     const uint64_t h = hash_key(key.data(), key.size());
-    const uint64_t h_but_lens = hash_key_but_lens(key, v->n_users);
     ++ctx->tick;
     CachedSchedule *victim = &own.cache[0];
-    CachedSchedule *grown = nullptr;  // a schedule of the same view with uniformly shorter lengths
-    int32_t grown_by = 0;
     for (auto &e : own.cache) {
         if (e.valid && e.hash == h && e.key == key) {
             e.last_use = ctx->tick;
@@ -237,18 +234,24 @@ int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view
             *out = &e;
             return SPD_OK;
         }
+        if (!e.valid) {
+            if (victim->valid)
+                victim = &e;
+        } else if (victim->valid && e.last_use < victim->last_use) {
+            victim = &e;
+        }
+    }
+    // no schedule for exactly these lengths: one of the same view with uniformly shorter lengths will do
+    const uint64_t h_but_lens = hash_key_but_lens(key, v->n_users);
+    CachedSchedule *grown = nullptr;
+    int32_t grown_by = 0;
+    for (auto &e : own.cache) {
         if (e.valid && e.hash_but_lens == h_but_lens) {
             const int32_t g = uniform_growth(e, key, v->n_users);
             if (g > 0 && (!grown || g < grown_by)) {
                 grown = &e;
                 grown_by = g;
             }
-        }
-        if (!e.valid) {
-            if (victim->valid)
-                victim = &e;
-        } else if (victim->valid && e.last_use < victim->last_use) {
-            victim = &e;
         }
     }
     if (grown) {
