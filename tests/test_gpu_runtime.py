@@ -439,3 +439,42 @@ def test_c_program_runs_the_path_without_python():
     assert os.path.exists(exe), "build it first: python -c 'import __graft_entry__ as g; g.build()'"
     run = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=120)
     assert run.returncode == 0 and run.stdout.strip().endswith("c abi gpu ok"), run.stdout[-2000:]
+
+
+def test_two_host_threads_with_a_context_each():
+    """A context is for one host thread at a time; two threads with a context and a stream each run side by side."""
+    import threading
+    import paper_2409_19134_amd as spd
+    cases = [workloads.random_case(570 + i, torch.bfloat16, 3, 32, 8, 128, [900 + 100 * i, 40, 2100], [30, 0, 200],
+                                   device=DEV, layout=("hnd", "nhd")[i]) for i in range(2)]
+    want = [_oracle_y(w) for w in cases]
+    errors = [None, None]
+
+    def work(i):
+        try:
+            torch.cuda.set_device(0)
+            ctx = spd.Context(0)
+            stream = torch.cuda.Stream()
+            step = spd.DecodeStep.from_workload(ctx, cases[i])
+            worst = 0.0
+            for rep in range(40):
+                with torch.cuda.stream(stream):
+                    if rep % 2:
+                        step.run_fused(cases[i].q)
+                    else:
+                        step.run(cases[i].q)
+                if rep % 10 == 9:
+                    stream.synchronize()
+                    worst = max(worst, _err(step, want[i]))
+            stream.synchronize()
+            ctx.close()
+            errors[i] = worst
+        except Exception as exc:        # surfaces in the main thread's assertion
+            errors[i] = exc
+
+    threads = [threading.Thread(target=work, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=100)
+    assert all(isinstance(e, float) and e <= 2e-3 for e in errors), errors
