@@ -86,7 +86,14 @@ inline void build_schedule(int Hkv, int n_users, const int32_t *lens, int n_cus,
         int64_t s0, s1;
     };
     std::vector<std::vector<Cut>> groups;
-    if (max_len <= env_int("SPD_NO_SPLIT_MAX", kNoSplitMaxDefault)) {
+    // Short rows are cut into chunks of one step per wave - unless that makes more workgroups than fit the machine
+    // at once: many users with short rows are bandwidth-bound like any large launch and get equal pieces instead
+    // (measured, 64 users x <= 512 + 256 tokens, 117 MB: 31.7 us against 35.6 us per fused step).
+    int64_t short_chunks = 0;
+    for (int u = 0; u < n_users; ++u)
+        short_chunks += ((lens[u] + kChunkAlign - 1) / kChunkAlign + spd::kWaves - 1) / spd::kWaves;
+    const int64_t resident = (int64_t)std::max(1, n_cus) * env_int("SPD_TARGET_WG_PER_CU", kTargetWgPerCuDefault);
+    if (max_len <= env_int("SPD_NO_SPLIT_MAX", kNoSplitMaxDefault) && short_chunks * (hpw ? hpw_groups : Hkv) <= resident) {
         const int64_t per = spd::kWaves;  // steps per chunk
         for (int u = 0; u < n_users; ++u) {
             const int64_t steps = (lens[u] + kChunkAlign - 1) / kChunkAlign;
