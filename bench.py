@@ -60,12 +60,13 @@ def main():
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (2 = Llama-3-8B shape, 16 users: the headline)")
     ap.add_argument("--copies", type=int, default=0, help="KV set copies cycled through (0 = enough for > 1 GB, at most 8)")
-    ap.add_argument("--mode", default="fused", choices=["fused", "calls", "calls_public_first", "streams"],
+    ap.add_argument("--mode", default="fused", choices=["fused", "calls", "calls_public_first", "streams", "two_parties"],
                     help="fused: spd_decode_step (both owners' pieces in one launch, one closing kernel); "
                          "calls: the three entry points in sequence on one stream (private, public, merge); "
                          "calls_public_first: the same with the public call first; "
                          "streams: private and public calls on two streams of equal priority, joined before the merge "
-                         "(the last three are the orderings of the paper's overlap study, section 5)")
+                         "(these three are the orderings of the paper's overlap study, section 5); "
+                         "two_parties: the users' call (private partials) and the service's call (public partial + merge)")
     ap.add_argument("--append", action="store_true",
                     help="fused mode only: also append one new token per user to the public cache in the same launch "
                          "(its slot is the cache's last token, rewritten every step)")
@@ -141,6 +142,8 @@ def main():
                 so.run_prepared_fused()
             elif side is not None:
                 so.run_streams(q, side)
+            elif args.mode == "two_parties":
+                so.run_two_parties(q)
             else:
                 so.run_prepared(public_first=args.mode == "calls_public_first")
 

@@ -202,6 +202,18 @@ int spd_decode_step(spd_ctx *ctx, const spd_shape *shape, const void *q, const s
                     float *a_out, float *lse_out, float *y, float *lse, float *w_in, void *hip_stream);
 
 /*
+ * The service's half of a decode step in one call (section 4, step 3c): the public batched partial attention (with the
+ * KV append if k_new / v_new are given, else pass NULL for both) and the merge with the private partials
+ * (a_in, lse_in) that the users' processes have delivered.  Equivalent to spd_partial_attn_public_batched[_append]
+ * followed by spd_lse_merge, with one launch less: the kernel that closes the public call also merges.
+ * a_in, lse_in are inputs here (DEVICE, complete on `hip_stream` before the call's work runs); a_out, lse_out, y, lse
+ * and w_in are outputs as in spd_decode_step.
+ */
+int spd_public_attn_merge(spd_ctx *ctx, const spd_shape *shape, const void *q, const spd_kv_view *pub,
+                          const void *k_new, const void *v_new, const float *a_in, const float *lse_in, float *a_out,
+                          float *lse_out, float *y, float *lse, float *w_in, void *hip_stream);
+
+/*
  * Running statistics of the private part's attention mass (sections 2.4 and 7.1: a user's process can notice a
  * prompt-leakage injection by watching how much attention its prompt still receives; Theorem 1's weight of A_in,
  * w_in = gamma_in / (gamma_in + gamma_out), is that share, and spd_lse_merge / spd_decode_step emit it).

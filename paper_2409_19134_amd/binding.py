@@ -25,7 +25,7 @@ EXPORTED_SYMBOLS = (
     "spd_partial_attn_private", "spd_partial_attn_public_batched", "spd_lse_merge",
     "spd_validate_partial", "spd_build_schedule", "spd_set_kernel_timing", "spd_get_kernel_timing",
     "spd_decode_step", "spd_partial_attn_public_batched_append", "spd_get_schedule_stats",
-    "spd_attention_mass_track", "spd_get_kernel_timing_samples", "spd_lse_merge_n",
+    "spd_attention_mass_track", "spd_get_kernel_timing_samples", "spd_lse_merge_n", "spd_public_attn_merge",
 )
 
 
@@ -77,6 +77,9 @@ def _load() -> C.CDLL:
         fn.argtypes = [vp, C.POINTER(spd_shape), vp, C.POINTER(spd_kv_view), fp, fp, vp]
     lib.spd_lse_merge.restype = C.c_int
     lib.spd_lse_merge.argtypes = [vp, C.c_int32, C.c_int32, fp, fp, fp, fp, fp, fp, fp, vp]
+    lib.spd_public_attn_merge.restype = C.c_int
+    lib.spd_public_attn_merge.argtypes = [vp, C.POINTER(spd_shape), vp, C.POINTER(spd_kv_view), vp, vp, fp, fp, fp, fp,
+                                          fp, fp, fp, vp]
     lib.spd_lse_merge_n.restype = C.c_int
     lib.spd_lse_merge_n.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
                                     fp, fp, fp, vp]
@@ -303,6 +306,26 @@ class Context:
         self._check(rc, "spd_lse_merge")
         return y
 
+
+    def spd_public_attn_merge(self, shape, q, public, a_in, lse_in, a_out, lse_out, y, lse, w_in, stream=None,
+                              k_new=None, v_new=None):
+        """The service's half of a step: public partial (+ append) and the merge with delivered private partials."""
+        n, Hq, d = public.struct.n_users, shape.n_q_heads, shape.head_dim
+        for t in (a_in, a_out, y):
+            assert t.is_contiguous() and t.dtype == torch.float32 and tuple(t.shape) == (n, Hq, d)
+        for t in (lse_in, lse_out, lse, w_in):
+            assert t.is_contiguous() and t.dtype == torch.float32 and tuple(t.shape) == (n, Hq)
+        assert q.is_contiguous() and tuple(q.shape) == (n, Hq, d)
+        assert (k_new is None) == (v_new is None)
+        for t in (k_new, v_new):
+            assert t is None or (t.is_contiguous() and t.dtype == q.dtype and tuple(t.shape) == (n, shape.n_kv_heads, d))
+        rc = lib.spd_public_attn_merge(self.handle, C.byref(shape), q.data_ptr(), C.byref(public.struct),
+                                       None if k_new is None else k_new.data_ptr(),
+                                       None if v_new is None else v_new.data_ptr(), a_in.data_ptr(), lse_in.data_ptr(),
+                                       a_out.data_ptr(), lse_out.data_ptr(), y.data_ptr(), lse.data_ptr(),
+                                       w_in.data_ptr(), _stream_ptr(stream))
+        self._check(rc, "spd_public_attn_merge")
+        return y
 
     def spd_lse_merge_n(self, a_parts, lse_parts, y=None, lse_out=None, w_out=None, stream=None):
         """n-way merge of partials (lists of [n_rows..., d] and [n_rows...] fp32 tensors); w_out: [n_parts, n_rows]."""

@@ -224,7 +224,8 @@ __global__ __launch_bounds__(D) void finalize_step_kernel(const RowInfo *__restr
     const int user = blockIdx.x, kvh = blockIdx.y, g = blockIdx.z;
     const int64_t row = (int64_t)user * Hq + kvh * G + g;
     const int tid = threadIdx.x;
-    const RowInfo ri = rows_in[user * Hkv + kvh], ro = rows_out[user * Hkv + kvh];
+    // rows_in == nullptr: the first owner's partials are finished results handed in by the caller
+    const RowInfo ri = rows_in ? rows_in[user * Hkv + kvh] : RowInfo{0, 1}, ro = rows_out[user * Hkv + kvh];
     // Measured on this kernel (4 us, pure latency): the 8-wide straight-line form is the fastest for rows of up to 8
     // chunks; loading both owners' pairs in one go, or 16-wide for everything, made it 1.3-2.3 us slower.
     constexpr int kSmall = 8, kMedium = 16;

@@ -970,6 +970,56 @@ try {
     return SPD_ERR_NOMEM;
 }
 
+int spd_public_attn_merge(spd_ctx *ctx, const spd_shape *shape, const void *q, const spd_kv_view *pub, const void *k_new,
+                          const void *v_new, const float *a_in, const float *lse_in, float *a_out, float *lse_out,
+                          float *y, float *lse, float *w_in, void *hip_stream)
+try {
+    NewToken nt;
+    nt.k = k_new;
+    nt.v = v_new;
+    if (!ctx || !pub)
+        return SPD_ERR_NULL;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    SPD_HIP(ctx, hipSetDevice(ctx->device));
+    int rc = spd_validate_partial(shape, q, pub, a_out, lse_out);
+    if (rc == SPD_OK)
+        rc = validate_new_token(pub, nt);
+    if (rc != SPD_OK)
+        return rc;
+    if (pub->n_users == 0)
+        return SPD_OK;
+    if (!a_in || !lse_in || !y || !lse || !w_in)
+        return SPD_ERR_NULL;
+    if (!aligned16(a_in) || !aligned16(y))
+        return SPD_ERR_ALIGN;
+    CachedSchedule *eo = nullptr;
+    rc = prepare_partial(ctx, 1, shape, q, pub, a_out, lse_out, -1, stream, &eo);
+    if (rc != SPD_OK)
+        return rc;
+    rc = launch_partial(ctx, 1, eo, pub, a_out, lse_out, nullptr, nullptr, nullptr, nullptr, shape, q, nt, stream);
+    if (rc != SPD_OK)
+        return rc;
+    // the closing kernel: combines the public rows that were split and merges; the private side arrives finished
+    const int G = shape->n_q_heads / shape->n_kv_heads;
+    const RowInfo *ro = reinterpret_cast<const RowInfo *>(eo->dev + eo->off_info);
+    const dim3 grid((unsigned)pub->n_users, (unsigned)shape->n_kv_heads, (unsigned)G);
+    const Owner &oo = ctx->owner[1];
+    float *a_in_rw = const_cast<float *>(a_in);  // only read: the kernel writes them for rows it combined itself
+    float *lse_in_rw = const_cast<float *>(lse_in);
+    if (shape->head_dim == 64)
+        hipLaunchKernelGGL((spd::finalize_step_kernel<64>), grid, dim3(64), 0, stream, (const RowInfo *)nullptr, ro,
+                           shape->n_kv_heads, shape->n_q_heads, G, (const float *)nullptr, (const float *)nullptr,
+                           oo.part_o, oo.part_lse, a_in_rw, lse_in_rw, a_out, lse_out, y, lse, w_in);
+    else
+        hipLaunchKernelGGL((spd::finalize_step_kernel<128>), grid, dim3(128), 0, stream, (const RowInfo *)nullptr, ro,
+                           shape->n_kv_heads, shape->n_q_heads, G, (const float *)nullptr, (const float *)nullptr,
+                           oo.part_o, oo.part_lse, a_in_rw, lse_in_rw, a_out, lse_out, y, lse, w_in);
+    SPD_HIP(ctx, hipGetLastError());
+    return SPD_OK;
+} catch (...) {  // a failed host allocation (std::vector): no C++ exception leaves the library
+    return SPD_ERR_NOMEM;
+}
+
 int spd_attention_mass_track(spd_ctx *ctx, int32_t n_rows, const float *w_in, float threshold, float *mass_min,
                              float *mass_sum, int32_t *n_below, void *hip_stream)
 {

@@ -40,6 +40,14 @@ class DecodeStep:
         c.spd_lse_merge(self.a_in, self.lse_in, self.a_out, self.lse_out, self.y, self.lse, self.w_in, stream)
         return self.y
 
+    def run_two_parties(self, q: torch.Tensor, stream=None, k_new=None, v_new=None):
+        """The deployment of the paper in two calls: the users' side (private partials) and the service's side
+        (public partial, optional append, and the merge) - spd_public_attn_merge closes the step."""
+        c = self.ctx
+        c.spd_partial_attn_private(self.shape, q, self.private, self.a_in, self.lse_in, stream)
+        return c.spd_public_attn_merge(self.shape, q, self.public, self.a_in, self.lse_in, self.a_out, self.lse_out,
+                                       self.y, self.lse, self.w_in, stream, k_new, v_new)
+
     def run_fused(self, q: torch.Tensor, stream=None, k_new=None, v_new=None):
         """The same step through spd_decode_step: one launch for both owners, one closing kernel.  With k_new / v_new
         the new token is appended to the public cache in the same launch (the view's lengths already count it)."""

@@ -85,7 +85,7 @@ CASES = [
 
 
 @pytest.mark.parametrize("dtype,Hq,Hkv,d,lp,lo,layout,paged", CASES)
-@pytest.mark.parametrize("fused", [False, True])
+@pytest.mark.parametrize("fused", [False, True, "two_parties"])
 def test_append_then_attend(ctx, mapping_of, dtype, Hq, Hkv, d, lp, lo, layout, paged, fused):
     layout = mapping_of(layout)
     import paper_2409_19134_amd as spd
@@ -108,7 +108,9 @@ def test_append_then_attend(ctx, mapping_of, dtype, Hq, Hkv, d, lp, lo, layout, 
     tol = TOL[dtype]
 
     step = spd.DecodeStep.from_workload(ctx, wl)
-    if fused:
+    if fused == "two_parties":       # the users' call, then the service's call with the append
+        step.run_two_parties(wl.q, k_new=k_new, v_new=v_new)
+    elif fused:
         step.run_fused(wl.q, k_new=k_new, v_new=v_new)
     else:
         ctx.spd_partial_attn_public_batched_append(step.shape, wl.q, k_new, v_new, step.public, step.a_out, step.lse_out)
@@ -127,7 +129,7 @@ def test_append_then_attend(ctx, mapping_of, dtype, Hq, Hkv, d, lp, lo, layout, 
     # a plain call on the updated cache now gives the same partial
     a2, l2 = ctx.spd_partial_attn_public_batched(step.shape, wl.q, step.public)
     torch.cuda.synchronize()
-    assert (a2 - step.a_out).abs().max().item() <= (1e-5 if fused else 0.0)
+    assert (a2 - step.a_out).abs().max().item() <= (1e-5 if fused is True else 0.0)
 
 
 def test_append_argument_errors(ctx):

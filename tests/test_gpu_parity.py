@@ -29,12 +29,15 @@ def ctx():
 
 
 def run_step(ctx, wl, fused=False):
-    """One decode step: the three C-ABI calls in sequence, or the fused spd_decode_step."""
+    """One decode step: the three C-ABI calls in sequence, the fused spd_decode_step (fused=True), or the users' call
+    followed by the service's spd_public_attn_merge (fused="two_parties")."""
     import paper_2409_19134_amd as spd
     step = spd.DecodeStep.from_workload(ctx, wl)
     for t in (step.a_in, step.a_out, step.y, step.lse_in, step.lse_out, step.lse, step.w_in):
         t.fill_(float("nan"))          # every output must be overwritten
-    if fused:
+    if fused == "two_parties":
+        step.run_two_parties(wl.q)
+    elif fused:
         step.run_fused(wl.q)
     else:
         step.run(wl.q)
@@ -52,10 +55,11 @@ def maxerr(got: torch.Tensor, want: np.ndarray) -> float:
 
 
 def check_against_oracle(ctx, wl, rows=None, tol=None):
-    """Both ways of running a step (three calls; fused call) against the oracle.  Returns the three-call step."""
+    """All three ways of running a step (three calls; fused call; users' call + service's call) against the oracle.
+    Returns the three-call step."""
     hw = orc.from_workload(wl)
     first = None
-    for fused in (False, True):
+    for fused in (False, True, "two_parties"):
         step, errs = _check_one(ctx, wl, hw, rows, tol, fused)
         first = first or (step, errs)
     return first

@@ -429,6 +429,27 @@ def test_decode_loop_reuses_the_public_schedule_while_the_cache_grows(storage, f
     ctx.close()
 
 
+def test_service_call_argument_errors_and_zero_users():
+    import paper_2409_19134_amd as spd
+    ctx = spd.Context(0)
+    wl = workloads.random_case(580, torch.bfloat16, 2, 32, 8, 128, [100, 0], [5, 300], device=DEV)
+    step = spd.DecodeStep.from_workload(ctx, wl)
+    sh, pub = step.shape, step.public
+    args = lambda **kw: [kw.get(k, getattr(step, k).data_ptr()) for k in ("a_in", "lse_in", "a_out", "lse_out", "y", "lse", "w_in")]
+    call = lambda a, k_new=None, v_new=None: spd.lib.spd_public_attn_merge(ctx.handle, sh, wl.q.data_ptr(), pub.struct, k_new, v_new, *a, None)
+    assert call(args(a_in=None)) == spd.SPD_ERR_NULL
+    assert call(args(y=None)) == spd.SPD_ERR_NULL
+    assert call(args(a_in=step.a_in.data_ptr() + 4)) == spd.SPD_ERR_ALIGN
+    kn = torch.zeros((2, 8, 128), device=DEV, dtype=torch.bfloat16)
+    assert call(args(), kn.data_ptr(), None) == spd.SPD_ERR_NULL          # the new token needs both rows
+    empty = spd.KVView([], token_stride=128, head_stride=128, k=[], v=[])
+    assert spd.lib.spd_public_attn_merge(ctx.handle, sh, None, empty.struct, None, None, *([None] * 7), None) == spd.SPD_OK
+    step.run_two_parties(wl.q)
+    torch.cuda.synchronize()
+    assert _err(step, _oracle_y(wl)) <= 2e-3
+    ctx.close()
+
+
 def test_c_program_runs_the_path_without_python():
     """tests/host/abi_gpu_program.cpp knows only include/spd.h and the HIP runtime: the three calls and the fused step
     from a plain program, against a closed form (zero keys: the result is the mean of V)."""
