@@ -1,5 +1,5 @@
 // The whole path from a program that knows only include/spd.h and the HIP runtime (no Python, no PyTorch): the three
-// calls of the protocol (paper section 4, step 3) and the fused step, checked against a closed form.
+// calls of the protocol (paper section 4, step 3), the fused step and the two-party form, checked against a closed form.
 // All keys are zero, so every score is 0, the softmax is uniform and the result is the mean of the user's V rows
 // over both caches, with lse = ln(number of tokens).  Built by paper_2409_19134_amd/build.py, run by a GPU test.
 #include <hip/hip_runtime.h>
@@ -108,16 +108,20 @@ int main()
     spd_ctx *ctx = nullptr;
     SPD_CALL(spd_create(&ctx, 0));
     std::vector<float> hy(n_rows * d), hl(n_rows), hw(n_rows);
-    for (int variant = 0; variant < 2; ++variant) {
+    for (int variant = 0; variant < 3; ++variant) {
         HIP_OK(hipMemsetAsync(y, 0xff, n_rows * d * 4, stream));  // NaN bits: every output must be overwritten
         HIP_OK(hipMemsetAsync(lse, 0xff, n_rows * 4, stream));
         if (variant == 0) {  // the three calls of the protocol
             SPD_CALL(spd_partial_attn_private(ctx, &shape, q, &priv, a_in, lse_in, stream));
             SPD_CALL(spd_partial_attn_public_batched(ctx, &shape, q, &pub, a_out, lse_out, stream));
             SPD_CALL(spd_lse_merge(ctx, (int32_t)n_rows, d, a_in, lse_in, a_out, lse_out, y, lse, w_in, stream));
-        } else {  // one call
+        } else if (variant == 1) {  // one call
             SPD_CALL(spd_decode_step(ctx, &shape, q, &priv, &pub, nullptr, nullptr, a_in, lse_in, a_out, lse_out, y, lse,
                                      w_in, stream));
+        } else {  // the users' call, then the service's call
+            SPD_CALL(spd_partial_attn_private(ctx, &shape, q, &priv, a_in, lse_in, stream));
+            SPD_CALL(spd_public_attn_merge(ctx, &shape, q, &pub, nullptr, nullptr, a_in, lse_in, a_out, lse_out, y, lse,
+                                           w_in, stream));
         }
         HIP_OK(hipStreamSynchronize(stream));
         HIP_OK(hipMemcpy(hy.data(), y, hy.size() * 4, hipMemcpyDeviceToHost));
