@@ -76,6 +76,8 @@ def main():
                          "model shapes, e.g. 32,8,64 or 32,32,128; not one of the five benchmark workloads")
     ap.add_argument("--dtype", default=None, choices=["bf16", "f16", "f32"], help="replace the configuration's element type")
     ap.add_argument("--users", type=int, default=None, help="replace the configuration's number of users (same length law)")
+    ap.add_argument("--page-tokens", type=int, default=16, choices=[16, 32, 64, 128, 256],
+                    help="tokens per page of the paged workload (config 5; 16 is the benchmark's)")
     ap.add_argument("--pointer-tables", action="store_true",
                     help="contiguous layouts: also pass the per-user pointers in device arrays (address-independent "
                          "schedules, shared by the layers of a model; one more dependent scalar load per segment)")
@@ -101,8 +103,9 @@ def main():
     shape = tuple(int(x) for x in args.shape.split(",")) if args.shape else None
     assert shape is None or len(shape) == 3, "--shape wants Hq,Hkv,d"
     dtype = {None: None, "bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}[args.dtype]
-    variant = shape is not None or dtype is not None or args.users is not None
-    wl = workloads.make_workload(args.config, dev, layout=args.layout, shape=shape, dtype=dtype, n_users=args.users)
+    variant = shape is not None or dtype is not None or args.users is not None or args.page_tokens != 16
+    wl = workloads.make_workload(args.config, dev, layout=args.layout, shape=shape, dtype=dtype, n_users=args.users,
+                                 page_tokens=args.page_tokens)
     kv_bytes = wl.kv_bytes
     elt = 4 if wl.dtype == torch.float32 else 2
     per_token = 2 * wl.n_kv_heads * wl.head_dim * elt
@@ -220,7 +223,7 @@ def main():
                    "n_kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim,
                    "private_tokens": wl.private.n_tokens, "public_tokens": wl.public.n_tokens,
                    "kv_bytes_per_step": kv_bytes, "kv_copies_cycled": copies, "mode": args.mode, "kv_append": bool(args.append),
-                   "layout": "paged16" if wl.private.paged else wl.private.layout,
+                   "layout": f"paged{wl.private.page_tokens}" if wl.private.paged else wl.private.layout,
                    "device_pointer_tables": bool(args.pointer_tables and not wl.private.paged),
                    "seeds": wl.seeds},
         "roofline": {"bound": "hbm",

@@ -77,9 +77,9 @@ typedef struct spd_shape {
  * that array is given).  Buffers of different users may be separate allocations.  A user with lens[u] == 0 may
  * have NULL pointers.
  *
- * Paged mode (block_size == 16): element (token i, head j, channel c) of user u is at
- * pool + block_table[u*max_blocks + i/16]*block_stride + j*head_stride + (i%16)*token_stride + c.
- * The table lives on the device and only entries [0, ceil(lens[u]/16)) of each row are read; they must name
+ * Paged mode (block_size B = 16, 32, 64, 128 or 256 tokens per page): element (token i, head j, channel c) of user u is
+ * at pool + block_table[u*max_blocks + i/B]*block_stride + j*head_stride + (i%B)*token_stride + c.
+ * The table lives on the device and only entries [0, ceil(lens[u]/B)) of each row are read; they must name
  * pages inside the pool (the library cannot check device-resident entries).
  */
 typedef struct spd_kv_view {
@@ -94,7 +94,7 @@ typedef struct spd_kv_view {
                                     lengths share one view                                                   */
     const void *k_pool;         /* DEVICE (paged mode)                                                    */
     const void *v_pool;         /* DEVICE (paged mode)                                                    */
-    int32_t block_size;         /* 0 = contiguous, 16 = paged                                             */
+    int32_t block_size;         /* 0 = contiguous; paged: tokens per page, 16 / 32 / 64 / 128 / 256       */
     const int32_t *block_table; /* DEVICE [n_users][max_blocks] (paged mode)                              */
     int32_t max_blocks;
     int64_t block_stride;       /* elements between pages, multiple of 16 bytes                           */

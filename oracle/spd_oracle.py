@@ -131,12 +131,12 @@ class HostWorkload:
 def from_workload(wl) -> HostWorkload:
     """Copy a workloads.Workload (tensors on any device) to the host, bit for bit."""
     import torch
-    from workloads import host_array, PAGE_TOKENS
+    from workloads import host_array
 
     def side(s) -> HostView:
         if s.paged:
             return HostView(s.lens, s.token_stride, s.head_stride, k_pool=host_array(s.k_pool),
-                            v_pool=host_array(s.v_pool), block_size=PAGE_TOKENS,
+                            v_pool=host_array(s.v_pool), block_size=s.page_tokens,
                             block_table=s.block_table.cpu().numpy(), block_stride=s.block_stride)
         return HostView(s.lens, s.token_stride, s.head_stride, k=[host_array(t) for t in s.k],
                         v=[host_array(t) for t in s.v], head_strides=getattr(s, "head_strides", None))

@@ -166,7 +166,7 @@ class KVView:
         """From a workloads.KVSide (tensors already on the GPU)."""
         if side.paged:
             return cls(side.lens, side.token_stride, side.head_stride, k_pool=side.k_pool, v_pool=side.v_pool,
-                       block_table=side.block_table, block_size=16, block_stride=side.block_stride)
+                       block_table=side.block_table, block_size=side.page_tokens, block_stride=side.block_stride)
         return cls(side.lens, side.token_stride, side.head_stride, k=side.k, v=side.v,
                    head_strides=getattr(side, "head_strides", None), device_pointer_tables=device_pointer_tables)
 

@@ -22,6 +22,7 @@ constexpr float kLn2 = 0.6931471805599453f;
 struct KvAddr {
     const int32_t *block_table;  // paged mode only, else nullptr
     int32_t max_blocks;
+    int32_t page_shift;  // paged mode: a page holds 1 << page_shift tokens (16 .. 256)
     int64_t block_stride;
     int64_t token_stride;
     int64_t head_stride;  // used by the head-per-wave kernel only (token-major storage: the same for every user)

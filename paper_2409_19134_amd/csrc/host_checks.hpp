@@ -12,6 +12,15 @@ namespace spd::host {
 
 constexpr int32_t kMaxLen = 1 << 30;  // tokens per user: token indices and their 32-token steps stay inside int32
 
+// log2 of a page size the kernels take (16, 32, 64, 128 or 256 tokens), else -1.
+inline int page_shift(int block_size)
+{
+    for (int s = 4; s <= 8; ++s)
+        if (block_size == (1 << s))
+            return s;
+    return -1;
+}
+
 inline int elt_size(int dtype) { return dtype == SPD_F32 ? 4 : 2; }
 
 inline int validate_shape(const spd_shape *s)
@@ -45,7 +54,7 @@ inline int validate_view(const spd_shape *s, const spd_kv_view *v)
     if (v->n_users > 0 && !v->lens)
         return SPD_ERR_NULL;
     const int es = elt_size(s->dtype);
-    if (v->block_size != 0 && v->block_size != 16)
+    if (v->block_size != 0 && page_shift(v->block_size) < 0)
         return SPD_ERR_SHAPE;
     bool any = false;
     for (int u = 0; u < v->n_users; ++u) {
@@ -81,7 +90,7 @@ inline int validate_view(const spd_shape *s, const spd_kv_view *v)
         if (v->max_blocks < 0)
             return SPD_ERR_LEN;
         for (int u = 0; u < v->n_users; ++u)
-            if (((int64_t)v->lens[u] + 15) / 16 > v->max_blocks)
+            if (((int64_t)v->lens[u] + v->block_size - 1) / v->block_size > v->max_blocks)
                 return SPD_ERR_LEN;
         if (any) {
             if (!v->k_pool || !v->v_pool || !v->block_table)

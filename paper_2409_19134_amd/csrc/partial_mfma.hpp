@@ -108,14 +108,16 @@ struct LaneConst {
     const char *k_base;  // contiguous: user's K + head offset; paged: pool + head offset
     const char *v_base;
     const int32_t *bt_row;
+    int page_shift, page_mask;  // paged: token t lies in the row's page t >> page_shift at place t & page_mask
     int64_t token_stride, block_stride;
     const char *k_new_row;  // KV append: this (user, KV head)'s new K / V row if the segment ends its row, else nullptr
     const char *v_new_row;
 };
 
-// The two 16-token pages a 32-token step at tb touches.  The ids are wave-uniform and come through the scalar cache.
-// Clamping keeps the lookups inside the user's pages; rows past the chunk re-read its last token, which lies in the
-// page the clamped lookup names (an 8-token group never straddles a page).
+// The pages that hold the two 16-token halves of the 32-token step at tb (the same page twice if pages hold 32 tokens
+// or more).  The ids are wave-uniform and come through the scalar cache.  Clamping keeps the lookups inside the
+// user's pages; rows past the chunk re-read its last token, which lies in the page the clamped lookup names (an
+// 8-token group never straddles a page).
 struct PagePair {
     int p0, p1;
 };
@@ -124,8 +126,8 @@ __device__ __forceinline__ PagePair load_pages(const LaneConst &L, int tb, int t
 {
     const int tbu = uniform(tb);
     PagePair P;
-    P.p0 = scalar_load_i32(L.bt_row, min(tbu, t_last) >> 4);
-    P.p1 = scalar_load_i32(L.bt_row, min(tbu + 16, t_last) >> 4);
+    P.p0 = scalar_load_i32(L.bt_row, min(tbu, t_last) >> L.page_shift);
+    P.p1 = scalar_load_i32(L.bt_row, min(tbu + 16, t_last) >> L.page_shift);
     return P;
 }
 
@@ -145,7 +147,7 @@ __device__ __forceinline__ void load_tile(TileRegs<RB> &T, const LaneConst &L, i
 #pragma unroll
     for (int a = 0; a < 2; ++a) {
         const int t = min(gk + a * 4 + (L.r & 3), t_last);  // rows past the chunk re-read its last token (masked later)
-        const char *p = kp + (int64_t)(PAGED ? (t & 15) : t) * L.token_stride + L.grp * 16;
+        const char *p = kp + (int64_t)(PAGED ? (t & L.page_mask) : t) * L.token_stride + L.grp * 16;
         if (APPEND && L.k_new_row && t == t_last)  // the appended token is read from the caller's buffer, not the cache
             p = L.k_new_row + L.grp * 16;
 #pragma unroll
@@ -155,7 +157,7 @@ __device__ __forceinline__ void load_tile(TileRegs<RB> &T, const LaneConst &L, i
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         const int t = min(gv + e, t_last);
-        const char *p = vp + (int64_t)(PAGED ? (t & 15) : t) * L.token_stride + L.r * (RB / 16);
+        const char *p = vp + (int64_t)(PAGED ? (t & L.page_mask) : t) * L.token_stride + L.r * (RB / 16);
         if (APPEND && L.v_new_row && t == t_last)
             p = L.v_new_row + L.r * (RB / 16);
         T.v[e].load(p);
@@ -328,6 +330,8 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, mfma_waves_per_simd(D *Elt<DT
         L.grp = lane >> 4;
         L.token_stride = kv.token_stride;
         L.block_stride = kv.block_stride;
+        L.page_shift = kv.page_shift;
+        L.page_mask = (1 << kv.page_shift) - 1;
         const int kv_head = HPW ? it.kv_head + uniform(wave) : it.kv_head;  // head per wave: the group's first head + wave
         L.k_base = it.k_base + k_pool + (PAGED ? 0 : user_base(k_ptrs, it.user)) + (HPW ? (int64_t)kv_head * kv.head_stride : 0);
         L.v_base = it.v_base + v_pool + (PAGED ? 0 : user_base(v_ptrs, it.user)) + (HPW ? (int64_t)kv_head * kv.head_stride : 0);
@@ -343,9 +347,9 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, mfma_waves_per_simd(D *Elt<DT
             L.k_new_row = k_new + row;
             L.v_new_row = v_new + row;
             if ((HPW || wave == 0) && lane < 2 * kRowLanes) {
-                int64_t off = (int64_t)(PAGED ? (t_last & 15) : t_last) * kv.token_stride + (lane % kRowLanes) * 16;
+                int64_t off = (int64_t)(PAGED ? (t_last & L.page_mask) : t_last) * kv.token_stride + (lane % kRowLanes) * 16;
                 if (PAGED)
-                    off += (int64_t)scalar_load_i32(L.bt_row, t_last >> 4) * kv.block_stride;
+                    off += (int64_t)scalar_load_i32(L.bt_row, t_last >> L.page_shift) * kv.block_stride;
                 if (lane < kRowLanes)
                     copy16(const_cast<char *>(L.k_base) + off, L.k_new_row + lane * 16);
                 else

@@ -485,6 +485,7 @@ OwnerArgs owner_args(const Owner &own, const CachedSchedule *e, const spd_shape 
     a.v_ptrs = v->block_size ? nullptr : reinterpret_cast<const char *const *>(v->v_ptrs_dev);
     a.kv.block_table = v->block_size ? v->block_table : nullptr;
     a.kv.max_blocks = v->max_blocks;
+    a.kv.page_shift = v->block_size ? page_shift(v->block_size) : 0;
     a.kv.block_stride = v->block_stride * es;
     a.kv.token_stride = v->token_stride * es;
     a.kv.head_stride = v->head_stride * es;

@@ -94,7 +94,9 @@ def test_validation_rejects_bad_views_and_pointers():
     assert _check(sh, _view([5, 9], token_stride=128, head_stride=0, head_strides=hs)) == spd.SPD_ERR_ALIGN
     hs = (C.c_int64 * 2)(640, 1152)
     assert _check(sh, _view([5, 9], token_stride=128, head_stride=0, head_strides=hs)) == spd.SPD_OK
-    assert _check(sh, _view([5], block_size=32)) == spd.SPD_ERR_SHAPE
+    assert _check(sh, _view([5], block_size=24)) == spd.SPD_ERR_SHAPE           # pages hold 16, 32, 64, 128 or 256 tokens
+    assert _check(sh, _view([5], block_size=8)) == spd.SPD_ERR_SHAPE
+    assert _check(sh, _view([5], block_size=512)) == spd.SPD_ERR_SHAPE
     paged = dict(token_stride=128, head_stride=2048, block_size=16, k_pool=0x100000, v_pool=0x200000,
                  block_table=0x300000, max_blocks=3, block_stride=16384)
     assert _check(sh, _view([49], **paged)) == spd.SPD_ERR_LEN                   # needs 4 pages, table has 3

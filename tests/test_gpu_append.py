@@ -27,13 +27,13 @@ def _set_last_token(side, u, k_row, v_row):
     """Plain copy of one token's rows ([Hkv, d]) into position lens[u]-1 of user u (torch indexing only)."""
     t = int(side.lens[u]) - 1
     if side.paged:
-        page = int(side.block_table[u, t // workloads.PAGE_TOKENS])
+        page = int(side.block_table[u, t // side.page_tokens])
         if side.page_token_major:
-            side.k_pool[page, t % workloads.PAGE_TOKENS] = k_row
-            side.v_pool[page, t % workloads.PAGE_TOKENS] = v_row
+            side.k_pool[page, t % side.page_tokens] = k_row
+            side.v_pool[page, t % side.page_tokens] = v_row
         else:
-            side.k_pool[page, :, t % workloads.PAGE_TOKENS] = k_row
-            side.v_pool[page, :, t % workloads.PAGE_TOKENS] = v_row
+            side.k_pool[page, :, t % side.page_tokens] = k_row
+            side.v_pool[page, :, t % side.page_tokens] = v_row
     elif side.layout == "nhd":
         side.k[u][t] = k_row
         side.v[u][t] = v_row
@@ -82,6 +82,36 @@ CASES = [
     (torch.float16, 32, 8, 128, [2000, 10, 0], [1500, 3000, 1], "nhd_hpw", "token_major"),
     (torch.float16, 32, 8, 64, [2000, 10, 0], [1500, 3000, 1], "nhd", True),
 ]
+
+
+@pytest.mark.parametrize("page_tokens", [32, 128])
+@pytest.mark.parametrize("paged", [True, "token_major"])
+@pytest.mark.parametrize("fused", [False, True])
+def test_append_with_larger_pages(ctx, page_tokens, paged, fused):
+    """The new token lands in the right place of a 32- or 128-token page: first slot of a fresh page, last slot of a
+    full one, somewhere in between."""
+    import paper_2409_19134_amd as spd
+    U, Hq, Hkv, d, dtype = 4, 16, 4, 128, torch.bfloat16
+    lo = [page_tokens + 1, page_tokens, 5, 3 * page_tokens - 1]
+    wl = workloads.random_case(212, dtype, U, Hq, Hkv, d, [40, 1, 700, 33], lo, device=DEV, paged=paged,
+                               page_tokens=page_tokens)
+    g = torch.Generator(device=DEV).manual_seed(978)
+    k_new = torch.randn((U, Hkv, d), generator=g, device=DEV).to(dtype)
+    v_new = torch.randn((U, Hkv, d), generator=g, device=DEV).to(dtype)
+    want = copy.copy(wl)
+    want.public = _clone_side(wl.public)
+    for u in range(U):
+        _set_last_token(want.public, u, k_new[u], v_new[u])
+    step = spd.DecodeStep.from_workload(ctx, wl)
+    if fused:
+        step.run_fused(wl.q, k_new=k_new, v_new=v_new)
+    else:
+        step.run_two_parties(wl.q, k_new=k_new, v_new=v_new)
+    torch.cuda.synchronize()
+    Y, _ = orc.attention(orc.from_workload(want))
+    assert np.abs(step.y.cpu().double().numpy().reshape(Y.shape) - Y).max() <= TOL[dtype]
+    for a, b in zip(_all_bytes(wl.public), _all_bytes(want.public)):
+        assert torch.equal(a, b)
 
 
 @pytest.mark.parametrize("dtype,Hq,Hkv,d,lp,lo,layout,paged", CASES)

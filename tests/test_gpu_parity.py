@@ -558,6 +558,32 @@ def test_unusual_scales(ctx, dtype, scale):
     check_against_oracle(ctx, wl)
 
 
+@pytest.mark.parametrize("page_tokens", [32, 64, 128, 256])
+@pytest.mark.parametrize("dtype,d", [(torch.bfloat16, 128), (torch.float16, 64), (torch.float32, 128)])
+@pytest.mark.parametrize("storage", ["paged", "paged_tm", "paged_tm_hpw"])
+def test_page_sizes(ctx, mapping_of, page_tokens, dtype, d, storage):
+    """Pages of 32 to 256 tokens (16 is what every other paged test uses), rows that end inside, at the end of and
+    one token into a page."""
+    storage = mapping_of(storage)
+    paged = {"paged": True, "paged_tm": "token_major"}[storage]
+    lp = [page_tokens * 3, 1, 2500, page_tokens + 1, 0]
+    lo = [page_tokens - 1, 5, 0, 777, page_tokens]
+    wl = workloads.random_case(160, dtype, 5, 16, 4, d, lp, lo, device=DEV, paged=paged, page_tokens=page_tokens)
+    check_against_oracle(ctx, wl)
+
+
+def test_owners_with_different_page_sizes(ctx):
+    """The fused step with 64-token pages on the private side and 16-token pages on the public side."""
+    import copy
+    a = workloads.random_case(161, torch.bfloat16, 3, 32, 8, 128, [3000, 70, 0], [40, 0, 500], device=DEV, paged=True,
+                              page_tokens=64)
+    b = workloads.random_case(161, torch.bfloat16, 3, 32, 8, 128, [3000, 70, 0], [40, 0, 500], device=DEV, paged=True,
+                              page_tokens=16)
+    wl = copy.copy(a)
+    wl.public = b.public
+    check_against_oracle(ctx, wl)
+
+
 def test_error_codes_from_device_calls(ctx):
     import paper_2409_19134_amd as spd
     wl = workloads.random_case(137, torch.bfloat16, 1, 32, 8, 128, [64], [8], device=DEV)

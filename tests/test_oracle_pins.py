@@ -26,7 +26,7 @@ def _rows_as_float64(wl, side, u, kv):
     """[L, d] float64 K and V rows of one (user, kv head), gathered with torch indexing only."""
     if side.paged:
         L = int(side.lens[u])
-        n = -(-L // workloads.PAGE_TOKENS)
+        n = -(-L // side.page_tokens)
         pages = side.block_table[u, :n].long()
         if side.page_token_major:
             k = side.k_pool[pages][:, :, kv].reshape(-1, wl.head_dim)[:L]
@@ -430,7 +430,7 @@ def test_paged_equals_contiguous_and_layouts_agree():
             cap = 64
             for u in range(U):
                 L = int(side.lens[u])
-                n = -(-L // workloads.PAGE_TOKENS)
+                n = -(-L // side.page_tokens)
                 pg = side.block_table[u, :n].long()
                 k = side.k_pool[pg].permute(1, 0, 2, 3).reshape(Hkv, -1, d)[:, :L]   # [Hkv, L, d]
                 v = side.v_pool[pg].permute(1, 0, 2, 3).reshape(Hkv, -1, d)[:, :L]
@@ -447,6 +447,25 @@ def test_paged_equals_contiguous_and_layouts_agree():
         Y2, lse2 = orc.attention(hw2)
         np.testing.assert_array_equal(Y, Y2)
         np.testing.assert_array_equal(lse, lse2)
+
+
+@pytest.mark.parametrize("page_tokens", [32, 64, 256])
+@pytest.mark.parametrize("token_major", [False, True])
+def test_larger_pages_hold_the_same_attention(page_tokens, token_major):
+    """The oracle on pages of 32, 64 and 256 tokens against the library softmax on rows gathered with torch indexing."""
+    from scipy.special import softmax
+    U, Hq, Hkv, d = 3, 4, 2, 16
+    wl, hw = _case(73, torch.float32, U, Hq, Hkv, d, [300, 1, 64], [65, 0, 257],
+                   paged="token_major" if token_major else True, page_tokens=page_tokens)
+    assert hw.private.block_size == page_tokens
+    Y, _ = orc.attention(hw)
+    for u in range(U):
+        for h in range(Hq):
+            K, V = _concat_rows(wl, u, h // (Hq // Hkv))
+            if K.shape[0] == 0:
+                continue
+            s = (K @ wl.q[u, h].double().numpy()) * wl.scale
+            np.testing.assert_allclose(Y[u * Hq + h], softmax(s) @ V, rtol=1e-11, atol=1e-12)
 
 
 def test_users_are_independent_and_rows_subset():

@@ -26,7 +26,7 @@ def cases(draw):
 def _rows(wl, side, u, kv):
     L = int(side.lens[u])
     if side.paged:
-        n = -(-L // workloads.PAGE_TOKENS)
+        n = -(-L // side.page_tokens)
         pg = side.block_table[u, :n].long()
         if side.page_token_major:
             k = side.k_pool[pg][:, :, kv].reshape(-1, wl.head_dim)[:L]

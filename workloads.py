@@ -71,6 +71,7 @@ class KVSide:
     max_blocks: int = 0
     head_strides: Optional[np.ndarray] = None   # per-user head stride (layout "hnd_exact"), else None
     page_token_major: bool = False              # paged pools are [block, token, head, d] instead of [block, head, token, d]
+    page_tokens: int = PAGE_TOKENS              # tokens per page (paged mode)
     layout: str = "nhd"      # contiguous mode: "nhd" or "hnd"; paged pools are [block, head, token, d]
 
     @property
@@ -190,12 +191,13 @@ def _make_contig(lens, Hkv, d, dtype, device, seed_k, seed_v, layout, ch_scale):
                   layout=layout, head_strides=hs)
 
 
-def _make_paged(lens, Hkv, d, dtype, device, seed_k, seed_v, seed_t, ch_scale, spare_blocks=3, token_major=False):
+def _make_paged(lens, Hkv, d, dtype, device, seed_k, seed_v, seed_t, ch_scale, spare_blocks=3, token_major=False,
+                page_tokens=PAGE_TOKENS):
     """One pool per tensor; each user's pages are drawn from a seeded shuffle of the pool.  Pages are
-    [Hkv, PAGE_TOKENS, d] (head-major) or, with token_major, [PAGE_TOKENS, Hkv, d]."""
+    [Hkv, page_tokens, d] (head-major) or, with token_major, [page_tokens, Hkv, d]."""
     gk = torch.Generator(device=device).manual_seed(seed_k)
     gv = torch.Generator(device=device).manual_seed(seed_v)
-    n_pages = [-(-int(L) // PAGE_TOKENS) for L in lens.tolist()]
+    n_pages = [-(-int(L) // page_tokens) for L in lens.tolist()]
     n_blocks = sum(n_pages) + spare_blocks
     max_blocks = max(1, max(n_pages, default=0))
     perm = np.random.default_rng(seed_t).permutation(n_blocks).astype(np.int32)
@@ -204,7 +206,7 @@ def _make_paged(lens, Hkv, d, dtype, device, seed_k, seed_v, seed_t, ch_scale, s
     for u, n in enumerate(n_pages):
         table[u, :n] = perm[at:at + n]
         at += n
-    shape = (n_blocks, PAGE_TOKENS, Hkv, d) if token_major else (n_blocks, Hkv, PAGE_TOKENS, d)
+    shape = (n_blocks, page_tokens, Hkv, d) if token_major else (n_blocks, Hkv, page_tokens, d)
     k_pool = torch.empty(shape, device=device, dtype=dtype)
     v_pool = torch.empty(shape, device=device, dtype=dtype)
     step = 4096  # pages per draw, bounds the fp32 staging buffer
@@ -217,14 +219,15 @@ def _make_paged(lens, Hkv, d, dtype, device, seed_k, seed_v, seed_t, ch_scale, s
         k_pool[b0:b1] = kk
         v_pool[b0:b1] = _randn((b1 - b0,) + shape[1:], gv, device, dtype)
     return KVSide(lens=lens, paged=True, token_stride=Hkv * d if token_major else d,
-                  head_stride=d if token_major else PAGE_TOKENS * d,
+                  head_stride=d if token_major else page_tokens * d,
                   k_pool=k_pool, v_pool=v_pool,
                   block_table=torch.from_numpy(table).to(device),
-                  block_stride=Hkv * PAGE_TOKENS * d, max_blocks=max_blocks, page_token_major=token_major)
+                  block_stride=Hkv * page_tokens * d, max_blocks=max_blocks, page_token_major=token_major,
+                  page_tokens=page_tokens)
 
 
 def make_workload(cfg: int, device="cpu", len_div: int = 1, n_users: Optional[int] = None,
-                  layout: Optional[str] = None, shape=None, dtype=None) -> Workload:
+                  layout: Optional[str] = None, shape=None, dtype=None, page_tokens: int = PAGE_TOKENS) -> Workload:
     """Draw workload ``cfg`` on ``device``.
 
     ``len_div`` divides every drawn length (for CPU-sized parity cases);
@@ -236,7 +239,8 @@ def make_workload(cfg: int, device="cpu", len_div: int = 1, n_users: Optional[in
     sh = _SHAPES[cfg]
     U = sh["U"] if n_users is None else n_users
     Hq, Hkv, d = shape if shape is not None else (sh["Hq"], sh["Hkv"], sh["d"])
-    name = sh["name"] if shape is None and dtype is None and n_users is None else f'{sh["name"]}-variant'
+    plain = shape is None and dtype is None and n_users is None and page_tokens == PAGE_TOKENS
+    name = sh["name"] if plain else f'{sh["name"]}-variant'
     dtype = sh["dtype"] if dtype is None else dtype
     lp, lo = draw_lengths(cfg, U, len_div)
     seeds = {fam: seed_of(cfg, fam) for fam in SEED_FAMILIES}
@@ -256,9 +260,9 @@ def make_workload(cfg: int, device="cpu", len_div: int = 1, n_users: Optional[in
     if cfg == 5:
         tm = layout == "nhd"      # token-major pages [block, token, head, d]
         priv = _make_paged(lp, Hkv, d, dtype, device, seeds["k_private"], seeds["v_private"],
-                           seeds["table_private"], ch_scale, token_major=tm)
+                           seeds["table_private"], ch_scale, token_major=tm, page_tokens=page_tokens)
         pub = _make_paged(lo, Hkv, d, dtype, device, seeds["k_public"], seeds["v_public"],
-                          seeds["table_public"], ch_scale, token_major=tm)
+                          seeds["table_public"], ch_scale, token_major=tm, page_tokens=page_tokens)
     else:
         lay = layout or ("hnd_exact" if cfg == 4 else "hnd")
         priv = _make_contig(lp, Hkv, d, dtype, device, seeds["k_private"], seeds["v_private"], lay, ch_scale)
@@ -270,9 +274,10 @@ def make_workload(cfg: int, device="cpu", len_div: int = 1, n_users: Optional[in
 
 
 def random_case(seed: int, dtype, U: int, Hq: int, Hkv: int, d: int, lens_private, lens_public,
-                device="cpu", layout: str = "nhd", paged=False, scale: Optional[float] = None) -> Workload:
+                device="cpu", layout: str = "nhd", paged=False, scale: Optional[float] = None,
+                page_tokens: int = PAGE_TOKENS) -> Workload:
     """A free-form seeded case for edge-case tests (explicit shapes and lengths).  paged: False, True
-    (head-major pages) or "token_major"."""
+    (head-major pages) or "token_major"; page_tokens: tokens per page."""
     lp = np.asarray(lens_private, dtype=np.int32)
     lo = np.asarray(lens_public, dtype=np.int32)
     assert lp.shape == (U,) and lo.shape == (U,)
@@ -280,8 +285,10 @@ def random_case(seed: int, dtype, U: int, Hq: int, Hkv: int, d: int, lens_privat
     q = _randn((U, Hq, d), gq, device, dtype)
     if paged:
         tm = paged == "token_major"
-        priv = _make_paged(lp, Hkv, d, dtype, device, seed + 1, seed + 2, seed + 5, None, token_major=tm)
-        pub = _make_paged(lo, Hkv, d, dtype, device, seed + 3, seed + 4, seed + 6, None, token_major=tm)
+        priv = _make_paged(lp, Hkv, d, dtype, device, seed + 1, seed + 2, seed + 5, None, token_major=tm,
+                           page_tokens=page_tokens)
+        pub = _make_paged(lo, Hkv, d, dtype, device, seed + 3, seed + 4, seed + 6, None, token_major=tm,
+                          page_tokens=page_tokens)
     else:
         priv = _make_contig(lp, Hkv, d, dtype, device, seed + 1, seed + 2, layout, None)
         pub = _make_contig(lo, Hkv, d, dtype, device, seed + 3, seed + 4, layout, None)
