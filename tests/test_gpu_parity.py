@@ -222,7 +222,7 @@ def _random_case_spec_wide(rng):
     lens = lambda: [kinds[int(rng.choice(len(kinds), p=weights))]() for _ in range(U)]
     storage = str(rng.choice(["nhd", "nhd_hpw", "hnd", "hnd_exact", "paged", "paged_tm", "paged_tm_hpw"]))
     return dict(dtype=dtype, U=U, Hq=Hkv * G, Hkv=Hkv, d=d, lp=lens(), lo=lens(), storage=storage,
-                scale=float(rng.choice([d ** -0.5, 0.02, 0.3])))
+                scale=float(rng.choice([d ** -0.5, 0.02, 0.3])), page_tokens=int(rng.choice([16, 32, 64, 128, 256])))
 
 
 @pytest.mark.parametrize("block", range(4))
@@ -235,7 +235,7 @@ def test_randomised_cases_all_dtypes_and_head_sizes(ctx, mapping_of, block):
         paged = {"paged": True, "paged_tm": "token_major"}.get(storage, False)
         layout = "nhd" if paged else storage
         wl = workloads.random_case(9600 + 16 * block + i, c["dtype"], c["U"], c["Hq"], c["Hkv"], c["d"], c["lp"], c["lo"],
-                                   device=DEV, layout=layout, paged=paged, scale=c["scale"])
+                                   device=DEV, layout=layout, paged=paged, scale=c["scale"], page_tokens=c["page_tokens"])
         check_against_oracle(ctx, wl)
 
 
