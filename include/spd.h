@@ -105,6 +105,11 @@ typedef struct spd_kv_view {
                                       pointer from these arrays.  k_ptrs / v_ptrs are still required (validation) */
 } spd_kv_view;
 
+/* Bumped whenever a struct layout or a signature of this header changes; spd_abi_version() returns the value the
+ * library was built with, so a program can check that header and library belong together. */
+#define SPD_ABI_VERSION 3
+int spd_abi_version(void);
+
 /* Create a context on HIP device `hip_device` (host call; allocates a small amount of device memory). */
 int spd_create(spd_ctx **out, int hip_device);
 

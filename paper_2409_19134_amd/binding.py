@@ -26,7 +26,10 @@ EXPORTED_SYMBOLS = (
     "spd_validate_partial", "spd_build_schedule", "spd_set_kernel_timing", "spd_get_kernel_timing",
     "spd_decode_step", "spd_partial_attn_public_batched_append", "spd_get_schedule_stats",
     "spd_attention_mass_track", "spd_get_kernel_timing_samples", "spd_lse_merge_n", "spd_public_attn_merge",
+    "spd_abi_version",
 )
+
+SPD_ABI_VERSION = 3      # include/spd.h's; checked against the loaded library below
 
 
 class SpdError(RuntimeError):
@@ -62,6 +65,8 @@ def _load() -> C.CDLL:
         raise ImportError(f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'` "
                           "(the SPD path has no fallback)")
     lib = C.CDLL(LIB_PATH)
+    if not hasattr(lib, "spd_abi_version") or lib.spd_abi_version() != SPD_ABI_VERSION:
+        raise ImportError(f"{LIB_PATH} was built from another version of include/spd.h; build it again")
     vp, fp = C.c_void_p, C.c_void_p
     lib.spd_create.restype = C.c_int
     lib.spd_create.argtypes = [C.POINTER(vp), C.c_int]

@@ -676,6 +676,8 @@ int no_throw(F &&body)
 
 extern "C" {
 
+int spd_abi_version(void) { return SPD_ABI_VERSION; }
+
 const char *spd_strerror(int code)
 {
     switch (code) {

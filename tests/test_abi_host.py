@@ -20,6 +20,16 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(spd.lib, name), name
 
 
+def test_abi_version_of_header_binding_and_library_agree():
+    import os
+    import re
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    header = open(os.path.join(root, "include", "spd.h")).read()
+    in_header = int(re.search(r"#define SPD_ABI_VERSION (\d+)", header).group(1))
+    from paper_2409_19134_amd import binding
+    assert in_header == binding.SPD_ABI_VERSION == spd.lib.spd_abi_version()
+
+
 def test_strerror_is_distinct_per_code():
     msgs = {spd.spd_strerror(c) for c in range(0, -8, -1)}
     assert len(msgs) == 8 and spd.spd_strerror(-99) == "unknown error code"
