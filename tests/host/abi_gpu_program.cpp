@@ -105,6 +105,10 @@ int main()
     hipStream_t stream;
     HIP_OK(hipStreamCreate(&stream));
 
+    if (spd_abi_version() != SPD_ABI_VERSION) {
+        std::printf("library built from another version of spd.h\n");
+        return 4;
+    }
     spd_ctx *ctx = nullptr;
     SPD_CALL(spd_create(&ctx, 0));
     std::vector<float> hy(n_rows * d), hl(n_rows), hw(n_rows);
