@@ -9,6 +9,8 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
+#include <type_traits>
+#include <utility>
 #include <vector>
 
 #include "combine.hpp"
@@ -499,6 +501,56 @@ OwnerArgs owner_args(const Owner &own, const CachedSchedule *e, const spd_shape 
     return a;
 }
 
+// Run-time values to template arguments: f is called with a std::integral_constant of the matching candidate.
+template <int V, int... Rest, class F>
+bool with_value(int v, F &&f)
+{
+    if (v == V)
+        return f(std::integral_constant<int, V>());
+    if constexpr (sizeof...(Rest) > 0)
+        return with_value<Rest...>(v, std::forward<F>(f));
+    else
+        return false;
+}
+template <class F>
+bool with_bool(bool b, F &&f)
+{
+    return b ? f(std::true_type()) : f(std::false_type());
+}
+
+struct MfmaLaunch {
+    dim3 grid, block;
+    uint32_t lds;
+    hipStream_t stream;
+    hipEvent_t ev0, ev1;  // both null unless timing is armed: receive the kernel's own start and stop time stamps
+    const OwnerArgs *a0, *a1;
+    int n0;
+    const char *q;
+    int Hq, G;
+    float c;
+};
+
+// The kernel instances that exist: the head-per-wave mapping always keeps two steps in flight, fp32 rows of 512 bytes
+// always one (and have no head-per-wave mapping), rows of 128 bytes always two.
+template <int DT, int D, bool PREFETCH, bool HPW>
+constexpr bool mfma_instance_exists()
+{
+    constexpr int RB = D * (DT == SPD_F32 ? 4 : 2);
+    return !(HPW && !PREFETCH) && !(DT == SPD_F32 && (HPW || PREFETCH)) && !(RB == 128 && !PREFETCH);
+}
+
+template <int DT, int D, bool PAGED, bool PREFETCH, bool HPW, bool APPEND>
+bool launch_mfma(const MfmaLaunch &L)
+{
+    if constexpr (mfma_instance_exists<DT, D, PREFETCH, HPW>()) {
+        hipExtLaunchKernelGGL((spd::partial_mfma_kernel<DT, D, PAGED, PREFETCH, HPW, APPEND>), L.grid, L.block, L.lds,
+                              L.stream, L.ev0, L.ev1, 0, *L.a0, *L.a1, L.n0, L.q, L.Hq, L.G, L.c);
+        return true;
+    } else {
+        return false;
+    }
+}
+
 // The partial kernel: every piece's workgroup writes final rows or chunk partials.  One owner per launch
 // (e1 == nullptr), or both owners' pieces in one grid (the fused step; both views in the same storage mode).
 struct NewToken {  // KV append for the public owner (protocol step 3a); both null if none
@@ -524,79 +576,49 @@ int launch_partial(spd_ctx *ctx, int which, const CachedSchedule *e0, const spd_
     const bool timed = ctx->timing && town.ev_used < (int)town.ev_start.size();
     const hipEvent_t ev0 = timed ? town.ev_start[town.ev_used] : nullptr;
     const hipEvent_t ev1 = timed ? town.ev_stop[town.ev_used] : nullptr;
-    const dim3 grid((unsigned)(n0 + n1));
-    const char *qh = static_cast<const char *>(q);
-#define SPD_LAUNCH_MFMA_A(E, D, PAGED, PREFETCH, HPW, APPEND)                                                        \
-    hipExtLaunchKernelGGL((spd::partial_mfma_kernel<E, D, PAGED, PREFETCH, HPW, APPEND>), grid, blk, (uint32_t)lds,   \
-                          stream, ev0, ev1, 0, a0, a1, (int)n0, qh, s->n_q_heads, G, c)
-#define SPD_LAUNCH_MFMA(E, D, PAGED, PREFETCH, HPW)                                                                   \
-    do {                                                                                                             \
-        if (nt.k)                                                                                                    \
-            SPD_LAUNCH_MFMA_A(E, D, PAGED, PREFETCH, HPW, true);                                                     \
-        else                                                                                                         \
-            SPD_LAUNCH_MFMA_A(E, D, PAGED, PREFETCH, HPW, false);                                                    \
-    } while (0)
-    if (s->dtype != SPD_F32) {
-        const bool hpw = e0->hpw;  // a two-owner launch needs the same mapping on both sides (checked by the caller)
-        const int waves = hpw ? head_per_wave_waves(s->n_kv_heads) : spd::kWaves;
-        // cross-wave staging; head-per-wave stages its per-wave results too if that fits (the kernel applies the same rule)
-        const int D = s->head_dim;
-        const size_t lds = (hpw && !spd::staging_fits(D, waves, G)) ? 0 : spd::staging_bytes(D, waves, G);
-        const dim3 blk(hpw ? 64u * (unsigned)waves : (unsigned)spd::kThreads);
-        // clearly more pieces than the three-per-CU kernel holds at once (a few left over just start a little
-        // later): use the prefetching two-per-CU kernel.  Also when all pieces fit two per CU anyway: a wave then
-        // needs half as many dependent memory round trips (short rows taken whole are latency-bound).
-        // Head-per-wave workgroups fit one per CU either way.
-        const int64_t cus = std::max(1, ctx->n_cus);
-        // With 64 channels a step is half the bytes: always two in flight.
-        const bool prefetch = hpw || D == 64 || n0 + n1 > cus * 4 || n0 + n1 <= cus * 2;
-#define SPD_LAUNCH_MFMA_P(E, D, PAGED)                                                                               \
-    do {                                                                                                             \
-        if (hpw)                                                                                                     \
-            SPD_LAUNCH_MFMA(E, D, PAGED, true, true);                                                                \
-        else if (prefetch)                                                                                           \
-            SPD_LAUNCH_MFMA(E, D, PAGED, true, false);                                                               \
-        else if (D == 128)                                                                                           \
-            SPD_LAUNCH_MFMA(E, 128, PAGED, false, false);                                                            \
-    } while (0)
-#define SPD_LAUNCH_MFMA_D(E)                                                                                         \
-    do {                                                                                                             \
-        if (D == 128) {                                                                                              \
-            if (v0->block_size)                                                                                      \
-                SPD_LAUNCH_MFMA_P(E, 128, true);                                                                     \
-            else                                                                                                     \
-                SPD_LAUNCH_MFMA_P(E, 128, false);                                                                    \
-        } else {                                                                                                     \
-            if (v0->block_size)                                                                                      \
-                SPD_LAUNCH_MFMA_P(E, 64, true);                                                                      \
-            else                                                                                                     \
-                SPD_LAUNCH_MFMA_P(E, 64, false);                                                                     \
-        }                                                                                                            \
-    } while (0)
-        if (s->dtype == SPD_BF16)
-            SPD_LAUNCH_MFMA_D(SPD_BF16);
-        else
-            SPD_LAUNCH_MFMA_D(SPD_F16);
-#undef SPD_LAUNCH_MFMA_P
-#undef SPD_LAUNCH_MFMA_D
-    } else {
-        // fp32: one step in flight per wave (at 128 channels a step is already 32 KB per wave)
-        const size_t lds = spd::staging_bytes(s->head_dim, spd::kWaves, G);
-        const dim3 blk((unsigned)spd::kThreads);
-        if (s->head_dim == 128) {
-            if (v0->block_size)
-                SPD_LAUNCH_MFMA(SPD_F32, 128, true, false, false);
-            else
-                SPD_LAUNCH_MFMA(SPD_F32, 128, false, false, false);
-        } else {
-            if (v0->block_size)
-                SPD_LAUNCH_MFMA(SPD_F32, 64, true, false, false);
-            else
-                SPD_LAUNCH_MFMA(SPD_F32, 64, false, false, false);
-        }
-    }
-#undef SPD_LAUNCH_MFMA_A
-#undef SPD_LAUNCH_MFMA
+    const bool f32 = s->dtype == SPD_F32;
+    const bool hpw = e0->hpw;  // a two-owner launch needs the same mapping on both sides (checked by the caller)
+    const int waves = hpw ? head_per_wave_waves(s->n_kv_heads) : spd::kWaves;
+    const int D = s->head_dim;
+    MfmaLaunch L;
+    L.grid = dim3((unsigned)(n0 + n1));
+    L.block = dim3(64u * (unsigned)waves);
+    // cross-wave staging; head-per-wave stages its per-wave results too if that fits (the kernel applies the same rule)
+    L.lds = (hpw && !spd::staging_fits(D, waves, G)) ? 0 : (uint32_t)spd::staging_bytes(D, waves, G);
+    L.stream = stream;
+    L.ev0 = ev0;
+    L.ev1 = ev1;
+    L.a0 = &a0;
+    L.a1 = &a1;
+    L.n0 = (int)n0;
+    L.q = static_cast<const char *>(q);
+    L.Hq = s->n_q_heads;
+    L.G = G;
+    L.c = c;
+    // Two steps in flight (PREFETCH) or one: clearly more pieces than the one-step kernel holds at once, three per CU
+    // (a few left over just start a little later), run on the two-step kernel, two per CU; so do launches whose pieces
+    // fit two per CU anyway (a wave then needs half as many dependent memory round trips).  Head-per-wave workgroups
+    // fit one per CU either way; with 128-byte rows a step is half the bytes, always two in flight; fp32 keeps one
+    // (at 128 channels a step is already 32 KB per wave and fills the registers).
+    const int64_t cus = std::max(1, ctx->n_cus);
+    const int row_bytes = D * elt_size(s->dtype);
+    const bool prefetch = !f32 && (hpw || row_bytes == 128 || n0 + n1 > cus * 4 || n0 + n1 <= cus * 2);
+    const bool ok = with_value<SPD_F32, SPD_BF16, SPD_F16>(s->dtype, [&](auto dt) {
+        return with_value<64, 128>(D, [&](auto d) {
+            return with_bool(v0->block_size != 0, [&](auto paged) {
+                return with_bool(prefetch, [&](auto pf) {
+                    return with_bool(hpw, [&](auto hp) {
+                        return with_bool(nt.k != nullptr, [&](auto app) {
+                            return launch_mfma<decltype(dt)::value, decltype(d)::value, decltype(paged)::value,
+                                               decltype(pf)::value, decltype(hp)::value, decltype(app)::value>(L);
+                        });
+                    });
+                });
+            });
+        });
+    });
+    if (!ok)
+        return SPD_ERR_SHAPE;  // no kernel instance for this combination: a bug in the rules above
     SPD_HIP(ctx, hipGetLastError());
     if (timed)
         ++town.ev_used;
