@@ -267,86 +267,12 @@ int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view
     Schedule S;
     build_schedule(s->n_kv_heads, v->n_users, v->lens, ctx->n_cus, hpw, S);
 
-    // device items: the first segment of every piece (index = workgroup id), then one per row without tokens (it only
-    // writes A = 0, lse = -inf), then the continuation segments, linked through `next`
-    const int es = elt_size(s->dtype);
-    const int Hkv = s->n_kv_heads;
-    const int hpw_waves = hpw ? head_per_wave_waves(Hkv) : 1;  // heads an item stands for
-    const int64_t n_pieces = (int64_t)S.piece_first.size() - 1;
-    int64_t n_empty_rows = 0;  // workgroups that only write A = 0, lse = -inf (head-per-wave: one per empty user)
-    for (int u = 0; u < v->n_users; ++u)
-        n_empty_rows += v->lens[u] == 0 ? (hpw ? Hkv / hpw_waves : Hkv) : 0;
-    const int64_t n_groups = n_pieces + n_empty_rows;  // launched workgroups
-    std::vector<DevItem> dev_items((size_t)n_groups);
-    dev_items.reserve((size_t)n_groups + S.items.size());
-    auto row_base = [&](int u, int h, bool is_v) -> const char * {
-        const char *base = (v->block_size || v->k_ptrs_dev) ? nullptr  // an offset: the kernel adds the pool / the user's pointer
-                                         : static_cast<const char *>(is_v ? v->v_ptrs[u] : v->k_ptrs[u]);
-        const int64_t hs = (v->head_strides && v->block_size == 0) ? v->head_strides[u] : v->head_stride;
-        return base + (hpw ? 0 : (int64_t)h * hs * es);  // head-per-wave: every wave adds its own head's offset (from head 0)
-    };
-    auto to_dev = [&](const spd_work_item &w, int rot) {
-        DevItem d;
-        d.k_base = row_base(w.user, w.kv_head, false);
-        d.v_base = row_base(w.user, w.kv_head, true);
-        d.user = w.user;
-        d.kv_head = w.kv_head;
-        d.t_begin = w.t_begin;
-        d.t_end = w.t_end;
-        d.slot = w.slot;
-        d.n_chunks = w.n_chunks;
-        d.next = -1;
-        d.rot = (rot & (spd::kWaves - 1)) | (w.t_end == v->lens[w.user] ? spd::kEndsRow : 0);
-        return d;
-    };
-    for (int64_t pc = 0; pc < n_pieces; ++pc) {
-        int rot = 0;
-        size_t prev = 0;
-        for (int32_t i = S.piece_first[(size_t)pc]; i < S.piece_first[(size_t)pc + 1]; ++i) {
-            const spd_work_item &w = S.items[(size_t)i];
-            const DevItem d = to_dev(w, rot);
-            size_t at;
-            if (i == S.piece_first[(size_t)pc]) {
-                at = (size_t)pc;
-                dev_items[at] = d;
-            } else {
-                at = dev_items.size();
-                dev_items.push_back(d);
-                dev_items[prev].next = (int32_t)at;
-            }
-            prev = at;
-            rot += (w.t_end - w.t_begin + kChunkAlign - 1) / kChunkAlign;
-        }
-    }
-    {
-        size_t at = (size_t)n_pieces;
-        for (int u = 0; u < v->n_users; ++u) {
-            if (v->lens[u] != 0)
-                continue;
-            for (int hh = 0; hh < (hpw ? Hkv / hpw_waves : Hkv); ++hh) {
-                DevItem d;
-                d.k_base = d.v_base = nullptr;
-                d.user = u;
-                d.kv_head = hpw ? hh * hpw_waves : hh;
-                d.t_begin = d.t_end = 0;
-                d.slot = d.n_chunks = d.rot = 0;
-                d.next = -1;
-                dev_items[at++] = d;
-            }
-        }
-    }
-    std::vector<CombineRow> split_rows;
-    for (size_t i = 0; i < S.items.size(); ++i) {
-        const spd_work_item &w = S.items[i];
-        if (w.chunk == 0 && w.n_chunks > 1)
-            for (int h = 0; h < hpw_waves; ++h)  // a head-per-wave item stands for the KV heads of its group
-                split_rows.push_back(CombineRow{w.slot + h * w.n_chunks, w.n_chunks, w.user, w.kv_head + h});
-    }
-    std::vector<RowInfo> row_info((size_t)v->n_users * Hkv, RowInfo{0, 0});
-    for (const spd_work_item &w : S.items)
-        if (w.chunk == 0)
-            for (int h = 0; h < hpw_waves; ++h)
-                row_info[(size_t)w.user * Hkv + w.kv_head + h] = RowInfo{w.slot + h * w.n_chunks, w.n_chunks};
+    DeviceTables T;
+    build_device_tables(S, s->n_kv_heads, elt_size(s->dtype), v, hpw, T);
+    const std::vector<DevItem> &dev_items = T.items;
+    const std::vector<CombineRow> &split_rows = T.split_rows;
+    const std::vector<RowInfo> &row_info = T.row_info;
+    const int64_t n_groups = (int64_t)T.items_launched;
     const size_t b_items = dev_items.size() * sizeof(DevItem);
     const size_t b_rows = split_rows.size() * sizeof(CombineRow);
     const size_t b_info = row_info.size() * sizeof(RowInfo);

@@ -25,6 +25,23 @@ def test_schedule_and_validation_under_asan_ubsan(tmp_path):
     assert run.returncode == 0 and run.stdout.strip().endswith("ok 400"), run.stdout[-3000:]
 
 
+@pytest.mark.skipif(not os.path.exists(HIPCC), reason="hipcc not found")
+def test_device_tables_under_asan_ubsan(tmp_path):
+    """What the kernels read of a schedule (items linked into pieces, split rows, slot bookkeeping), built on the host
+    for random views in both mappings: every item reached once, every token and slot covered once, flags and row
+    addresses as the kernels expect them."""
+    exe = str(tmp_path / "device_tables_fuzz")
+    cmd = [HIPCC, "--offload-arch=gfx950", "-O1", "-g", "-std=c++17", "-x", "hip",
+           "-Xarch_host", "-fsanitize=address,undefined", "-Xarch_host", "-fno-sanitize-recover=undefined",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-o", exe, os.path.join(ROOT, "tests", "host", "device_tables_fuzz.cpp")]
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    assert res.returncode == 0, res.stdout[-3000:]
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    run = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, env=env, timeout=300)
+    assert run.returncode == 0 and run.stdout.strip().endswith("ok 600"), run.stdout[-3000:]
+
+
 def test_oracle_under_asan_ubsan(tmp_path):
     """The C oracle itself: small random inputs in every storage mode, with AddressSanitizer and UBSan."""
     exe = str(tmp_path / "oracle_sanitize")
