@@ -53,6 +53,28 @@ def measured_traffic(config: int, kernel_prefix: str):
     return int(total) if found == 2 else None
 
 
+def masked_stream(torch, n_cus, wanted):
+    """A HIP stream (default priority) whose kernels run only on the compute units cu with wanted(cu)."""
+    import ctypes
+    # the HIP runtime this process already uses (loading another copy by name would start a second runtime)
+    with open("/proc/self/maps") as f:
+        paths = {line.split()[-1] for line in f if "libamdhip64" in line}
+    assert len(paths) == 1, f"expected one HIP runtime in the process, found {sorted(paths)}"
+    hip = ctypes.CDLL(paths.pop())
+    words = (n_cus + 31) // 32
+    mask = (ctypes.c_uint32 * words)()
+    for cu in range(n_cus):
+        if wanted(cu):
+            mask[cu // 32] |= 1 << (cu % 32)
+    handle = ctypes.c_void_p()
+    hip.hipExtStreamCreateWithCUMask.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_uint32,
+                                                 ctypes.POINTER(ctypes.c_uint32)]
+    hip.hipExtStreamCreateWithCUMask.restype = ctypes.c_int
+    rc = hip.hipExtStreamCreateWithCUMask(ctypes.byref(handle), words, mask)
+    assert rc == 0 and handle.value, f"hipExtStreamCreateWithCUMask failed ({rc})"
+    return torch.cuda.ExternalStream(handle.value)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -67,6 +89,9 @@ def main():
                          "streams: private and public calls on two streams of equal priority, joined before the merge "
                          "(these three are the orderings of the paper's overlap study, section 5); "
                          "two_parties: the users' call (private partials) and the service's call (public partial + merge)")
+    ap.add_argument("--public-cus", type=int, default=0, metavar="N",
+                    help="streams mode only: give the public call's stream N compute units and the private call's "
+                         "stream the others (HIP compute-unit masks; 0 = both streams may use every unit)")
     ap.add_argument("--append", action="store_true",
                     help="fused mode only: also append one new token per user to the public cache in the same launch "
                          "(its slot is the cache's last token, rewritten every step)")
@@ -137,6 +162,13 @@ def main():
     fused = args.mode == "fused"
 
     side = torch.cuda.Stream() if args.mode == "streams" else None     # default priority
+    if args.public_cus:
+        # the owners on disjoint sets of compute units: the nearest a single process comes to the paper's separate
+        # processes sharing a GPU (section 5)
+        n_cus = torch.cuda.get_device_properties(0).multi_processor_count
+        assert args.mode == "streams" and 0 < args.public_cus < n_cus, "--public-cus wants --mode streams and 0 < N < the GPU's units"
+        side = masked_stream(torch, n_cus, lambda cu: cu < args.public_cus)
+        torch.cuda.set_stream(masked_stream(torch, n_cus, lambda cu: cu >= args.public_cus))
 
     def run(n, start=0):
         for i in range(n):
@@ -222,7 +254,7 @@ def main():
         "config": {"workload": f"config{args.config}:{wl.name}", "n_users": wl.n_users, "n_q_heads": wl.n_q_heads,
                    "n_kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim,
                    "private_tokens": wl.private.n_tokens, "public_tokens": wl.public.n_tokens,
-                   "kv_bytes_per_step": kv_bytes, "kv_copies_cycled": copies, "mode": args.mode, "kv_append": bool(args.append),
+                   "kv_bytes_per_step": kv_bytes, "kv_copies_cycled": copies, "mode": args.mode, "public_cus": args.public_cus or None, "kv_append": bool(args.append),
                    "layout": f"paged{wl.private.page_tokens}" if wl.private.paged else wl.private.layout,
                    "device_pointer_tables": bool(args.pointer_tables and not wl.private.paged),
                    "seeds": wl.seeds},
