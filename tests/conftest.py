@@ -6,6 +6,10 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
+# tests/test_oracle_pin_strength.py runs the pin tests against copies of the oracle with a planted mistake: the copy's
+# parent directory comes first on the path, so that `import oracle` finds the copy
+if os.environ.get("SPD_ORACLE_PACKAGE_ROOT"):
+    sys.path.insert(0, os.environ["SPD_ORACLE_PACKAGE_ROOT"])
 
 
 def pytest_configure(config):
