@@ -92,6 +92,10 @@ def main():
     ap.add_argument("--public-cus", type=int, default=0, metavar="N",
                     help="streams mode only: give the public call's stream N compute units and the private call's "
                          "stream the others (HIP compute-unit masks; 0 = both streams may use every unit)")
+    ap.add_argument("--graph", action="store_true",
+                    help="fused mode only: record one step on every KV copy (think: the layers of a model, --copies N) "
+                         "into one HIP graph after the warm-up and time replays of it; --steps must be a multiple of "
+                         "the number of copies")
     ap.add_argument("--append", action="store_true",
                     help="fused mode only: also append one new token per user to the public cache in the same launch "
                          "(its slot is the cache's last token, rewritten every step)")
@@ -208,6 +212,21 @@ def main():
     torch.cuda.synchronize()
     builds, hits = ctx.spd_get_schedule_stats()
 
+    run_eager = run
+    if args.graph:
+        # every schedule exists by now, so the calls only launch kernels and can be captured
+        assert fused and not args.append and args.steps % copies == 0, "--graph wants --mode fused and --steps a multiple of the copies"
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=torch.cuda.Stream()):
+            for so in steps_objs:
+                so.run_fused(q)
+
+        def run(n, start=0):
+            for _ in range(n // copies):
+                graph.replay()
+        run(copies)
+        torch.cuda.synchronize()
+
     # ---- timed region: exactly K steps between two synchronisations ----
     K = args.steps
     torch.cuda.synchronize()
@@ -222,7 +241,7 @@ def main():
     ctx.spd_set_kernel_timing(K)
     torch.cuda.synchronize()
     t2 = time.perf_counter()
-    run(K)
+    run_eager(K)          # the events ride on the dispatches themselves, which a graph replay does not make anew
     torch.cuda.synchronize()
     t3 = time.perf_counter()
     def stats(samples):
@@ -254,7 +273,7 @@ def main():
         "config": {"workload": f"config{args.config}:{wl.name}", "n_users": wl.n_users, "n_q_heads": wl.n_q_heads,
                    "n_kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim,
                    "private_tokens": wl.private.n_tokens, "public_tokens": wl.public.n_tokens,
-                   "kv_bytes_per_step": kv_bytes, "kv_copies_cycled": copies, "mode": args.mode, "public_cus": args.public_cus or None, "kv_append": bool(args.append),
+                   "kv_bytes_per_step": kv_bytes, "kv_copies_cycled": copies, "mode": args.mode, "public_cus": args.public_cus or None, "hip_graph": bool(args.graph), "kv_append": bool(args.append),
                    "layout": f"paged{wl.private.page_tokens}" if wl.private.paged else wl.private.layout,
                    "device_pointer_tables": bool(args.pointer_tables and not wl.private.paged),
                    "seeds": wl.seeds},
