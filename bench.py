@@ -105,6 +105,9 @@ def main():
                          "model shapes, e.g. 32,8,64 or 32,32,128; not one of the five benchmark workloads")
     ap.add_argument("--dtype", default=None, choices=["bf16", "f16", "f32"], help="replace the configuration's element type")
     ap.add_argument("--users", type=int, default=None, help="replace the configuration's number of users (same length law)")
+    ap.add_argument("--lens", default=None, metavar="PLO,PHI,OLO,OHI",
+                    help="replace the configuration's length law: private lengths uniform in [PLO, PHI], public in "
+                         "[OLO, OHI] (e.g. 64,512,1,256 with --users 32: the paper's own prompt lengths and batch size)")
     ap.add_argument("--page-tokens", type=int, default=16, choices=[16, 32, 64, 128, 256],
                     help="tokens per page of the paged workload (config 5; 16 is the benchmark's)")
     ap.add_argument("--pointer-tables", action="store_true",
@@ -132,9 +135,12 @@ def main():
     shape = tuple(int(x) for x in args.shape.split(",")) if args.shape else None
     assert shape is None or len(shape) == 3, "--shape wants Hq,Hkv,d"
     dtype = {None: None, "bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}[args.dtype]
-    variant = shape is not None or dtype is not None or args.users is not None or args.page_tokens != 16
+    len_ranges = tuple(int(x) for x in args.lens.split(",")) if args.lens else None
+    assert len_ranges is None or len(len_ranges) == 4, "--lens wants four integers"
+    variant = (shape is not None or dtype is not None or args.users is not None or args.page_tokens != 16
+               or len_ranges is not None)
     wl = workloads.make_workload(args.config, dev, layout=args.layout, shape=shape, dtype=dtype, n_users=args.users,
-                                 page_tokens=args.page_tokens)
+                                 page_tokens=args.page_tokens, len_ranges=len_ranges)
     kv_bytes = wl.kv_bytes
     elt = 4 if wl.dtype == torch.float32 else 2
     per_token = 2 * wl.n_kv_heads * wl.head_dim * elt

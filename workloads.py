@@ -112,11 +112,17 @@ _SHAPES = {
 }
 
 
-def draw_lengths(cfg: int, n_users: int, len_div: int = 1):
-    """Private and public token counts per user (int32), both ends inclusive."""
+def draw_lengths(cfg: int, n_users: int, len_div: int = 1, len_ranges=None):
+    """Private and public token counts per user (int32), both ends inclusive.  len_ranges = (private low, private
+    high, public low, public high) replaces the configuration's length law by uniform draws (same seeds)."""
     rp = np.random.default_rng(seed_of(cfg, "len_private"))
     ro = np.random.default_rng(seed_of(cfg, "len_public"))
-    if cfg == 1:
+    if len_ranges is not None:
+        plo, phi, olo, ohi = (int(x) for x in len_ranges)
+        assert 0 <= plo <= phi and 0 <= olo <= ohi
+        lp = rp.integers(plo, phi, size=n_users, endpoint=True)
+        lo = ro.integers(olo, ohi, size=n_users, endpoint=True)
+    elif cfg == 1:
         lp = np.full(n_users, 128)
         lo = np.full(n_users, 16)
     elif cfg == 2:
@@ -227,22 +233,24 @@ def _make_paged(lens, Hkv, d, dtype, device, seed_k, seed_v, seed_t, ch_scale, s
 
 
 def make_workload(cfg: int, device="cpu", len_div: int = 1, n_users: Optional[int] = None,
-                  layout: Optional[str] = None, shape=None, dtype=None, page_tokens: int = PAGE_TOKENS) -> Workload:
+                  layout: Optional[str] = None, shape=None, dtype=None, page_tokens: int = PAGE_TOKENS,
+                  len_ranges=None) -> Workload:
     """Draw workload ``cfg`` on ``device``.
 
     ``len_div`` divides every drawn length (for CPU-sized parity cases);
     ``n_users`` overrides the user count; ``layout`` overrides the contiguous
     layout ("hnd" for configs 1-3, "hnd_exact" for config 4 by default; config 5 is paged).
     ``shape`` = (Hq, Hkv, d) and ``dtype`` replace the configuration's own (same users, lengths and seeds): for
-    measurements on other model shapes, not part of the five configurations.
+    measurements on other model shapes, not part of the five configurations.  ``len_ranges`` likewise replaces the
+    length law (see draw_lengths).
     """
     sh = _SHAPES[cfg]
     U = sh["U"] if n_users is None else n_users
     Hq, Hkv, d = shape if shape is not None else (sh["Hq"], sh["Hkv"], sh["d"])
-    plain = shape is None and dtype is None and n_users is None and page_tokens == PAGE_TOKENS
+    plain = shape is None and dtype is None and n_users is None and page_tokens == PAGE_TOKENS and len_ranges is None
     name = sh["name"] if plain else f'{sh["name"]}-variant'
     dtype = sh["dtype"] if dtype is None else dtype
-    lp, lo = draw_lengths(cfg, U, len_div)
+    lp, lo = draw_lengths(cfg, U, len_div, len_ranges)
     seeds = {fam: seed_of(cfg, fam) for fam in SEED_FAMILIES}
 
     gq = torch.Generator(device=device).manual_seed(seeds["q"])
