@@ -96,6 +96,11 @@ def main():
                     help="fused mode only: record one step on every KV copy (think: the layers of a model, --copies N) "
                          "into one HIP graph after the warm-up and time replays of it; --steps must be a multiple of "
                          "the number of copies")
+    ap.add_argument("--decode-loop", type=int, default=0, metavar="N",
+                    help="fused mode only: a decode loop instead of one repeated step - every step appends a token per "
+                         "user to the public cache (as --append) and the public lengths grow by one per step; after N "
+                         "steps (at most 32) the loop starts over on the next KV copy.  Shows what a growing cache costs "
+                         "(nothing, when the schedule of the first step serves the following ones); no oracle leg")
     ap.add_argument("--append", action="store_true",
                     help="fused mode only: also append one new token per user to the public cache in the same launch "
                          "(its slot is the cache's last token, rewritten every step)")
@@ -138,9 +143,10 @@ def main():
     len_ranges = tuple(int(x) for x in args.lens.split(",")) if args.lens else None
     assert len_ranges is None or len(len_ranges) == 4, "--lens wants four integers"
     variant = (shape is not None or dtype is not None or args.users is not None or args.page_tokens != 16
-               or len_ranges is not None)
+               or len_ranges is not None or args.decode_loop > 0)
     wl = workloads.make_workload(args.config, dev, layout=args.layout, shape=shape, dtype=dtype, n_users=args.users,
-                                 page_tokens=args.page_tokens, len_ranges=len_ranges)
+                                 page_tokens=args.page_tokens, len_ranges=len_ranges,
+                                 min_public_len=args.decode_loop)   # the loop grows every public cache up to its drawn length
     kv_bytes = wl.kv_bytes
     elt = 4 if wl.dtype == torch.float32 else 2
     per_token = 2 * wl.n_kv_heads * wl.head_dim * elt
@@ -157,6 +163,7 @@ def main():
             w = copy.copy(wl)
             w.private, w.public = clone_side(wl.private), clone_side(wl.public)
         steps_objs.append(spd.DecodeStep.from_workload(ctx, w, device_pointer_tables=args.pointer_tables))
+        steps_objs[-1].workload = w
     q = wl.q
 
     stream_ptr = torch.cuda.current_stream().cuda_stream
@@ -168,6 +175,32 @@ def main():
         v_new = torch.randn((wl.n_users, wl.n_kv_heads, wl.head_dim), generator=gen, device=dev).to(wl.dtype)
     for so in steps_objs:
         so.prepare(q, stream_ptr, k_new, v_new)
+
+    loops = None
+    if args.decode_loop:
+        # per KV copy, N views of the same buffers whose public lengths grow by one token from step to step
+        import copy
+        N = args.decode_loop
+        assert args.mode == "fused" and 1 <= N <= 32 and not args.append and not args.graph, \
+            "--decode-loop wants --mode fused, 1 <= N <= 32, and neither --append nor --graph"
+        gen = torch.Generator(device=dev).manual_seed(1000 * args.config + 10)
+        k_new = torch.randn((wl.n_users, wl.n_kv_heads, wl.head_dim), generator=gen, device=dev).to(wl.dtype)
+        v_new = torch.randn((wl.n_users, wl.n_kv_heads, wl.head_dim), generator=gen, device=dev).to(wl.dtype)
+        # the buffers and block tables were made for the drawn lengths (all >= N): the loop's N steps end there, so that
+        # no step reads or writes past what is allocated, whatever the layout
+        first = wl.public.lens.astype(np.int64) - N
+        assert int(first.min()) >= 0 and int((first + N).max()) <= int(wl.public.lens.max())
+        assert all(int(first[u]) + N <= int(wl.public.lens[u]) for u in range(wl.n_users))
+        loops = []
+        for so in steps_objs:
+            views = []
+            for step in range(N):
+                w = copy.copy(so.workload)
+                w.public = copy.copy(so.workload.public)
+                w.public.lens = (first + step + 1).astype(np.int32)
+                views.append(spd.DecodeStep.from_workload(ctx, w, device_pointer_tables=args.pointer_tables))
+            loops.append(views)
+        kv_bytes = int(priv_bytes + (first + (N + 1) / 2).sum() * per_token)    # mean over the loop's steps
 
     fused = args.mode == "fused"
 
@@ -182,6 +215,10 @@ def main():
 
     def run(n, start=0):
         for i in range(n):
+            if loops is not None:
+                N = args.decode_loop
+                loops[((start + i) // N) % copies][(start + i) % N].run_fused(q, k_new=k_new, v_new=v_new)
+                continue
             so = steps_objs[(start + i) % copies]
             if fused:
                 so.run_prepared_fused()
@@ -279,7 +316,7 @@ def main():
         "config": {"workload": f"config{args.config}:{wl.name}", "n_users": wl.n_users, "n_q_heads": wl.n_q_heads,
                    "n_kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim,
                    "private_tokens": wl.private.n_tokens, "public_tokens": wl.public.n_tokens,
-                   "kv_bytes_per_step": kv_bytes, "kv_copies_cycled": copies, "mode": args.mode, "public_cus": args.public_cus or None, "hip_graph": bool(args.graph), "kv_append": bool(args.append),
+                   "kv_bytes_per_step": kv_bytes, "kv_copies_cycled": copies, "mode": args.mode, "public_cus": args.public_cus or None, "hip_graph": bool(args.graph), "decode_loop_steps": args.decode_loop or None, "kv_append": bool(args.append),
                    "layout": f"paged{wl.private.page_tokens}" if wl.private.paged else wl.private.layout,
                    "device_pointer_tables": bool(args.pointer_tables and not wl.private.paged),
                    "seeds": wl.seeds},
@@ -298,7 +335,7 @@ def main():
                      "us_per_step_while_timed": round(ms_per_step_timed * 1e3, 2)},
     }
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.decode_loop:   # (the loop's caches differ from step to step)
         # The cpu_baseline leg: the oracle as it stands, on the host cores of this machine, on a bounded sample of the same
         # workload.  Its output doubles as the parity check of the GPU result (--no-check skips the comparison).
         from oracle import spd_oracle as orc

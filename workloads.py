@@ -112,9 +112,10 @@ _SHAPES = {
 }
 
 
-def draw_lengths(cfg: int, n_users: int, len_div: int = 1, len_ranges=None):
+def draw_lengths(cfg: int, n_users: int, len_div: int = 1, len_ranges=None, min_public_len: int = 0):
     """Private and public token counts per user (int32), both ends inclusive.  len_ranges = (private low, private
-    high, public low, public high) replaces the configuration's length law by uniform draws (same seeds)."""
+    high, public low, public high) replaces the configuration's length law by uniform draws (same seeds);
+    min_public_len raises every public length to at least that many tokens."""
     rp = np.random.default_rng(seed_of(cfg, "len_private"))
     ro = np.random.default_rng(seed_of(cfg, "len_public"))
     if len_ranges is not None:
@@ -144,6 +145,7 @@ def draw_lengths(cfg: int, n_users: int, len_div: int = 1, len_ranges=None):
         # shrink for CPU-sized tests; a length that was >= 1 stays >= 1, zeros stay zero
         lp = np.where(lp > 0, np.maximum(1, lp // len_div), 0)
         lo = np.where(lo > 0, np.maximum(1, lo // len_div), 0)
+    lo = np.maximum(lo, min_public_len)
     return lp.astype(np.int32), lo.astype(np.int32)
 
 
@@ -234,7 +236,7 @@ def _make_paged(lens, Hkv, d, dtype, device, seed_k, seed_v, seed_t, ch_scale, s
 
 def make_workload(cfg: int, device="cpu", len_div: int = 1, n_users: Optional[int] = None,
                   layout: Optional[str] = None, shape=None, dtype=None, page_tokens: int = PAGE_TOKENS,
-                  len_ranges=None) -> Workload:
+                  len_ranges=None, min_public_len: int = 0) -> Workload:
     """Draw workload ``cfg`` on ``device``.
 
     ``len_div`` divides every drawn length (for CPU-sized parity cases);
@@ -242,15 +244,16 @@ def make_workload(cfg: int, device="cpu", len_div: int = 1, n_users: Optional[in
     layout ("hnd" for configs 1-3, "hnd_exact" for config 4 by default; config 5 is paged).
     ``shape`` = (Hq, Hkv, d) and ``dtype`` replace the configuration's own (same users, lengths and seeds): for
     measurements on other model shapes, not part of the five configurations.  ``len_ranges`` likewise replaces the
-    length law (see draw_lengths).
+    length law and ``min_public_len`` bounds the public lengths from below (see draw_lengths).
     """
     sh = _SHAPES[cfg]
     U = sh["U"] if n_users is None else n_users
     Hq, Hkv, d = shape if shape is not None else (sh["Hq"], sh["Hkv"], sh["d"])
-    plain = shape is None and dtype is None and n_users is None and page_tokens == PAGE_TOKENS and len_ranges is None
+    plain = shape is None and dtype is None and n_users is None and page_tokens == PAGE_TOKENS and len_ranges is None \
+        and min_public_len == 0
     name = sh["name"] if plain else f'{sh["name"]}-variant'
     dtype = sh["dtype"] if dtype is None else dtype
-    lp, lo = draw_lengths(cfg, U, len_div, len_ranges)
+    lp, lo = draw_lengths(cfg, U, len_div, len_ranges, min_public_len)
     seeds = {fam: seed_of(cfg, fam) for fam in SEED_FAMILIES}
 
     gq = torch.Generator(device=device).manual_seed(seeds["q"])
