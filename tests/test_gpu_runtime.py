@@ -380,7 +380,7 @@ def test_layers_captured_in_one_hip_graph(fused):
     ctx.close()
 
 
-@pytest.mark.parametrize("storage", ["hnd", "nhd_hpw", "paged", "paged_tm_hpw"])
+@pytest.mark.parametrize("storage", ["hnd", "hnd_exact", "nhd_hpw", "paged", "paged_tm_hpw"])
 @pytest.mark.parametrize("fused", [True, False])
 def test_decode_loop_reuses_the_public_schedule_while_the_cache_grows(storage, fused, monkeypatch):
     """150 decode steps, one token appended per user and step: the public schedule is rebuilt only every 65th step
