@@ -499,3 +499,35 @@ def test_two_host_threads_with_a_context_each():
     for t in threads:
         t.join(timeout=100)
     assert all(isinstance(e, float) and e <= 2e-3 for e in errors), errors
+
+
+def test_contexts_give_their_memory_back():
+    """Forty contexts created, used (both storage for small schedules and a schedule too large for it, scratch for
+    split rows) and destroyed: the device's free memory ends where it began, so spd_destroy frees what a context
+    allocated."""
+    import paper_2409_19134_amd as spd
+    wl_small = workloads.random_case(811, torch.bfloat16, 3, 8, 2, 128, [700, 40, 5000], [10, 0, 300], device=DEV, layout="hnd")
+    wl_big = workloads.random_case(812, torch.bfloat16, 600, 8, 2, 64, [40] * 600, [7] * 600, device=DEV, layout="nhd")
+    want = _oracle_y(wl_small)
+    torch.cuda.synchronize()
+
+    def one_context():
+        ctx = spd.Context(0)
+        for wl in (wl_small, wl_big):
+            step = spd.DecodeStep.from_workload(ctx, wl)
+            step.run_fused(wl.q)
+            step.run(wl.q)
+            if wl is wl_small:
+                torch.cuda.synchronize()
+                assert _err(step, want) <= 2e-3
+        torch.cuda.synchronize()
+        ctx.close()
+
+    one_context()                     # whatever the first use of the library itself keeps is allocated now
+    torch.cuda.synchronize()
+    free0, _ = torch.cuda.mem_get_info()
+    for _ in range(40):
+        one_context()
+    torch.cuda.synchronize()
+    free1, _ = torch.cuda.mem_get_info()
+    assert free0 - free1 < 32 << 20, f"{(free0 - free1) >> 20} MiB not returned after 40 contexts"
