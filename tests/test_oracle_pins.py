@@ -564,6 +564,15 @@ def test_workload_configs_are_seeded_and_shaped():
     assert lp.min() >= 16 and lp.max() <= 32768 and 700 < np.median(lp) < 1500 and lo.max() <= 2048
     lp, lo = workloads.draw_lengths(5, 32)
     assert lp.min() >= 32768 and lp.max() <= 131072 and lo.min() >= 1 and lo.max() <= 4096
+    # the overrides the benchmark offers: another length law, a floor under the public lengths (buffers and block
+    # tables are then made for the raised lengths, which is what lets a decode loop grow a cache up to them)
+    lp, lo = workloads.draw_lengths(2, 200, len_ranges=(64, 512, 0, 256))
+    assert lp.min() >= 64 and lp.max() <= 512 and lo.min() >= 0 and lo.max() <= 256 and lo.min() < 32
+    lp2, lo2 = workloads.draw_lengths(2, 200, len_ranges=(64, 512, 0, 256), min_public_len=32)
+    assert np.array_equal(lp, lp2) and np.array_equal(lo2, np.maximum(lo, 32))
+    w4 = workloads.make_workload(4, n_users=12, len_div=4, min_public_len=32)
+    assert w4.name.endswith("-variant") and int(w4.public.lens.min()) >= 32
+    assert all(k.shape[1] == L for k, L in zip(w4.public.k, w4.public.lens))      # exactly sized per-user buffers
     w3 = workloads.make_workload(3, len_div=256, n_users=4)
     assert len(w3.outlier_channels) == 21
     kv, ch = divmod(int(w3.outlier_channels[0]), 128)
