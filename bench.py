@@ -82,18 +82,20 @@ def main():
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (2 = Llama-3-8B shape, 16 users: the headline)")
     ap.add_argument("--copies", type=int, default=0, help="KV set copies cycled through (0 = enough for > 1 GB, at most 8)")
-    ap.add_argument("--mode", default="fused", choices=["fused", "calls", "calls_public_first", "streams", "two_parties"],
+    ap.add_argument("--mode", default="fused", choices=["fused", "calls", "calls_public_first", "streams", "two_parties", "per_user_streams"],
                     help="fused: spd_decode_step (both owners' pieces in one launch, one closing kernel); "
                          "calls: the three entry points in sequence on one stream (private, public, merge); "
                          "calls_public_first: the same with the public call first; "
                          "streams: private and public calls on two streams of equal priority, joined before the merge "
                          "(these three are the orderings of the paper's overlap study, section 5); "
-                         "two_parties: the users' call (private partials) and the service's call (public partial + merge)")
+                         "two_parties: the users' call (private partials) and the service's call (public partial + merge); "
+                         "per_user_streams: as two_parties, but every user's private call is made on its own (one user, "
+                         "own context, own stream, as the paper's per-user processes would), joined before the service's call")
     ap.add_argument("--public-cus", type=int, default=0, metavar="N",
                     help="streams mode only: give the public call's stream N compute units and the private call's "
                          "stream the others (HIP compute-unit masks; 0 = both streams may use every unit)")
     ap.add_argument("--graph", action="store_true",
-                    help="fused mode only: record one step on every KV copy (think: the layers of a model, --copies N) "
+                    help="fused and per_user_streams modes: record one step on every KV copy (think: the layers of a model, --copies N) "
                          "into one HIP graph after the warm-up and time replays of it; --steps must be a multiple of "
                          "the number of copies")
     ap.add_argument("--decode-loop", type=int, default=0, metavar="N",
@@ -213,8 +215,38 @@ def main():
         side = masked_stream(torch, n_cus, lambda cu: cu < args.public_cus)
         torch.cuda.set_stream(masked_stream(torch, n_cus, lambda cu: cu >= args.public_cus))
 
+    per_user = None
+    if args.mode == "per_user_streams":
+        U = wl.n_users
+        assert not wl.private.paged and U <= 32, "per_user_streams wants a contiguous workload of at most 32 users"
+        user_ctx = [spd.Context(0) for _ in range(U)]           # calls that overlap in time need a context each
+        user_stream = [torch.cuda.Stream() for _ in range(U)]   # default priority
+        per_user = []
+        for so in steps_objs:
+            side = so.workload.private
+            per_user.append([spd.KVView(side.lens[u:u + 1], side.token_stride, side.head_stride, k=[side.k[u]], v=[side.v[u]],
+                                        head_strides=None if side.head_strides is None else side.head_strides[u:u + 1])
+                             for u in range(U)])
+
+    def run_per_user(so, views):
+        main = torch.cuda.current_stream()
+        fork = torch.cuda.Event()
+        fork.record(main)
+        for u, view in enumerate(views):
+            st = user_stream[u]
+            st.wait_event(fork)
+            user_ctx[u].spd_partial_attn_private(so.shape, q[u:u + 1], view, so.a_in[u:u + 1], so.lse_in[u:u + 1], st)
+            done = torch.cuda.Event()
+            done.record(st)
+            main.wait_event(done)
+        so.ctx.spd_public_attn_merge(so.shape, q, so.public, so.a_in, so.lse_in, so.a_out, so.lse_out, so.y, so.lse,
+                                     so.w_in, main)
+
     def run(n, start=0):
         for i in range(n):
+            if per_user is not None:
+                run_per_user(steps_objs[(start + i) % copies], per_user[(start + i) % copies])
+                continue
             if loops is not None:
                 N = args.decode_loop
                 loops[((start + i) // N) % copies][(start + i) % N].run_fused(q, k_new=k_new, v_new=v_new)
@@ -258,11 +290,15 @@ def main():
     run_eager = run
     if args.graph:
         # every schedule exists by now, so the calls only launch kernels and can be captured
-        assert fused and not args.append and args.steps % copies == 0, "--graph wants --mode fused and --steps a multiple of the copies"
+        assert (fused or per_user is not None) and not args.append and args.steps % copies == 0, \
+            "--graph wants --mode fused or per_user_streams, and --steps a multiple of the copies"
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=torch.cuda.Stream()):
-            for so in steps_objs:
-                so.run_fused(q)
+            for i, so in enumerate(steps_objs):
+                if per_user is not None:
+                    run_per_user(so, per_user[i])       # the users' streams fork from and rejoin the captured stream
+                else:
+                    so.run_fused(q)
 
         def run(n, start=0):
             for _ in range(n // copies):
@@ -284,7 +320,8 @@ def main():
     ctx.spd_set_kernel_timing(K)
     torch.cuda.synchronize()
     t2 = time.perf_counter()
-    run_eager(K)          # the events ride on the dispatches themselves, which a graph replay does not make anew
+    if per_user is None:
+        run_eager(K)      # the events ride on the dispatches themselves, which a graph replay does not make anew
     torch.cuda.synchronize()
     t3 = time.perf_counter()
     def stats(samples):
