@@ -42,6 +42,19 @@ def test_device_tables_under_asan_ubsan(tmp_path):
     assert run.returncode == 0 and run.stdout.strip().endswith("ok 600"), run.stdout[-3000:]
 
 
+def test_schedule_key_and_growth_rule_under_asan_ubsan(tmp_path):
+    """The key a schedule is remembered by (what is part of it, what is not) and the rule by which a schedule serves
+    a view whose lengths have all grown by the same 1..64 tokens: plain C++, no GPU."""
+    exe = str(tmp_path / "schedule_key_fuzz")
+    cmd = ["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+           "-o", exe, os.path.join(ROOT, "tests", "host", "schedule_key_fuzz.cpp")]
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    assert res.returncode == 0, res.stdout[-3000:]
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    run = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, env=env, timeout=300)
+    assert run.returncode == 0 and run.stdout.strip().endswith("ok 2000"), run.stdout[-3000:]
+
+
 def test_oracle_under_asan_ubsan(tmp_path):
     """The C oracle itself: small random inputs in every storage mode, with AddressSanitizer and UBSan."""
     exe = str(tmp_path / "oracle_sanitize")
