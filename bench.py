@@ -36,21 +36,32 @@ def clone_side(side):
     return c
 
 
-def measured_traffic(config: int, kernel_prefix: str):
-    """HBM bytes per launch of the streaming kernel from the committed rocprofv3 --pmc summary of this workload
-    (scaled FETCH_SIZE + WRITE_SIZE), or None if no summary is there.  The summary names the command that made it."""
+def measured_traffic(config: int, kernel_name: str):
+    """(bytes, source): HBM bytes per launch of the streaming kernel from the committed rocprofv3 --pmc summary of this
+    workload (scaled FETCH_SIZE + WRITE_SIZE) and where that figure comes from.  bytes is None, and source says why, if
+    there is no summary or it was made with another kernel instance than `kernel_name`, the one that just ran: the
+    summary is a stored measurement, not one made by this run."""
     import re
-    path = os.path.join(ROOT, "profiles", f"partial_kernel_config{config}_pmc_traffic.txt")
+    rel = os.path.join("profiles", f"partial_kernel_config{config}_pmc_traffic.txt")
+    path = os.path.join(ROOT, rel)
+    source = {"file": rel, "kind": "stored rocprofv3 --pmc summary (FETCH_SIZE + WRITE_SIZE, scaled by a 256 MiB copy)",
+              "kernel_that_ran": kernel_name}
     if not os.path.exists(path):
-        return None
-    total = 0.0
-    found = 0
+        source["why_null"] = "no summary for this workload"
+        return None, source
+    total, found, seen = 0.0, 0, set()
     for line in open(path):
-        m = re.search(r"^\s+spd::(\S+).*->\s+([0-9.]+) MB scaled", line)
-        if m and m.group(1).startswith(kernel_prefix):
-            total += float(m.group(2)) * 1e6
-            found += 1
-    return int(total) if found == 2 else None
+        m = re.search(r"^\s+spd::(partial_mfma_kernel<[^>]*>).*->\s+([0-9.]+) MB scaled", line)
+        if m:
+            seen.add(m.group(1))
+            if m.group(1) == kernel_name:
+                total += float(m.group(2)) * 1e6
+                found += 1
+    source["kernel_in_summary"] = sorted(seen)
+    if found != 2:
+        source["why_null"] = "the summary was made with another kernel instance"
+        return None, source
+    return int(total), source
 
 
 def masked_stream(torch, n_cus, wanted):
@@ -125,6 +136,9 @@ def main():
     ap.add_argument("--no-check", action="store_true", help="skip the comparison of the GPU result with the oracle's")
     ap.add_argument("--cpu-seconds", type=float, default=1.5,
                     help="wall-clock seconds of oracle passes in the cpu_baseline leg (times the cores it uses: CPU work)")
+    ap.add_argument("--no-sub-records", action="store_true",
+                    help="default workload only: skip the three_calls / two_parties legs (the same step through the "
+                         "three named entry points, and as the users' call plus the service's call)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy, so that a rocprofv3 --pmc run has a dispatch of known "
                          "traffic to scale FETCH_SIZE / WRITE_SIZE by")
@@ -316,6 +330,48 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / K
     value = kv_bytes / (ms_per_step * 1e-3) / 1e9
 
+    # ---- distribution of the step time: the same steps in short chunks between event pairs on the launch stream ----
+    chunk = max(1, min(10, K // 10))
+    n_chunks = max(1, K // chunk)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_chunks)]
+    torch.cuda.synchronize()
+    for c, (e0, e1) in enumerate(ev):
+        e0.record()
+        run(chunk, start=c * chunk)
+        e1.record()
+    torch.cuda.synchronize()
+    chunk_us = np.asarray([e0.elapsed_time(e1) * 1e3 / chunk for e0, e1 in ev], dtype=np.float64)
+    step_dist = {"median": round(float(np.median(chunk_us)), 2), "p10": round(float(np.percentile(chunk_us, 10)), 2),
+                 "p90": round(float(np.percentile(chunk_us, 90)), 2), "samples": n_chunks, "steps_per_sample": chunk,
+                 "clock": "HIP events on the launch stream around each sample"}
+
+    # ---- the same workload through the calls the paper's deployment makes (same K, same clock as `value`) ----
+    sub_records = {}
+    plain_default = (fused and not args.graph and not args.append and not args.decode_loop and not args.public_cus
+                     and per_user is None)
+    if plain_default and not args.no_sub_records:
+        def timed(fn):
+            fn(max(args.warmup, copies))
+            torch.cuda.synchronize()
+            a = time.perf_counter()
+            fn(K)
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - a) * 1e3 / K
+            return {"us_per_step": round(ms * 1e3, 2), "GBps": round(kv_bytes / (ms * 1e-3) / 1e9, 1),
+                    "pct_of_hbm_peak": round(100.0 * kv_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2)}
+
+        def three_calls(n, start=0):
+            for i in range(n):
+                steps_objs[(start + i) % copies].run_prepared()
+
+        def two_parties(n, start=0):
+            for i in range(n):
+                steps_objs[(start + i) % copies].run_prepared_two_parties()
+        sub_records["three_calls"] = dict(timed(three_calls), calls="spd_partial_attn_private, "
+                                          "spd_partial_attn_public_batched, spd_lse_merge")
+        sub_records["two_parties"] = dict(timed(two_parties), calls="spd_partial_attn_private (users), "
+                                          "spd_public_attn_merge (service)")
+
     # ---- the same K steps again with HIP events around the partial kernels (on the launch stream) ----
     ctx.spd_set_kernel_timing(K)
     torch.cuda.synchronize()
@@ -324,6 +380,7 @@ def main():
         run_eager(K)      # the events ride on the dispatches themselves, which a graph replay does not make anew
     torch.cuda.synchronize()
     t3 = time.perf_counter()
+    kernel_name = ctx.spd_last_kernel_name()
     def stats(samples):
         a = np.asarray(samples, dtype=np.float64)
         return (len(a), float(a.mean()), float(a.min()), [float(np.percentile(a, p)) for p in (10, 50, 90)]) if len(a) \
@@ -343,6 +400,7 @@ def main():
         "n_gpus": 1, "steps": K, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 6),
         "us_per_step": round(ms_per_step * 1e3, 2),
+        "us_per_step_distribution": step_dist,
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": {torch.float32: "f32", torch.bfloat16: "bf16", torch.float16: "f16"}[wl.dtype],
@@ -358,12 +416,10 @@ def main():
                    "device_pointer_tables": bool(args.pointer_tables and not wl.private.paged),
                    "seeds": wl.seeds},
         "roofline": {"bound": "hbm",
-                     "kernel": "partial_mfma_kernel"
-                               + (" (both owners, spd_decode_step)" if fused else " (private call)"),
+                     "kernel": kernel_name + (" (both owners, spd_decode_step)" if fused else " (private call)"),
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": measured_traffic(args.config, "partial_mfma_kernel")
-                                if fused and not variant else None,
+                     "traffic": None, "traffic_source": None,
                      "bytes_per_launch": launch_bytes, "launches_timed": n_priv,
                      "mean_us": round(priv_mean_us, 2), "min_us": round(priv_min_us, 2),
                      "p10_p50_p90_us": [round(v, 2) for v in priv_pct],
@@ -372,6 +428,11 @@ def main():
                      "us_per_step_while_timed": round(ms_per_step_timed * 1e3, 2)},
     }
 
+    if fused and not variant:
+        out["roofline"]["traffic"], out["roofline"]["traffic_source"] = measured_traffic(args.config, kernel_name)
+    out.update(sub_records)
+
+    parity_failed = False
     if not args.no_cpu_baseline and not args.decode_loop:   # (the loop's caches differ from step to step)
         # The cpu_baseline leg: the oracle as it stands, on the host cores of this machine, on a bounded sample of the same
         # workload.  Its output doubles as the parity check of the GPU result (--no-check skips the comparison).
@@ -381,17 +442,18 @@ def main():
         if full:
             rows, sample_desc = None, "whole workload, all rows"
             sample_bytes = kv_bytes
-        else:   # big workloads: a bounded sample of output rows
-            rng = np.random.default_rng(args.config)
-            rows = [(int(rng.integers(wl.n_users)), int(rng.integers(wl.n_q_heads))) for _ in range(4)]
+        else:   # big workloads: one query head of every (user, KV head) stream, the head rotating with the user
+            G = wl.n_q_heads // wl.n_kv_heads
+            rows = [(u, kvh * G + (u + kvh) % G) for u in range(wl.n_users) for kvh in range(wl.n_kv_heads)]
             # a row's share of the algorithmic bytes: its (user, kv head) K/V stream divided among the G query
             # heads that share it (the whole job is U*Hq rows and reads every stream once)
             toks = sum(int(wl.private.lens[u]) + int(wl.public.lens[u]) for u, _ in rows)
-            sample_bytes = toks * 2 * wl.head_dim * elt // (wl.n_q_heads // wl.n_kv_heads)
-            sample_desc = f"{len(rows)} sampled (user, head) rows; bytes = their share of the K/V streams"
+            sample_bytes = toks * 2 * wl.head_dim * elt // G
+            sample_desc = (f"{len(rows)} (user, head) rows: one query head of every (user, KV head) stream; "
+                           "bytes = their share of the K/V streams")
         times = []
         t_begin = time.perf_counter()
-        while len(times) < 5 or (time.perf_counter() - t_begin) < args.cpu_seconds:
+        while len(times) < (5 if full else 1) or (time.perf_counter() - t_begin) < args.cpu_seconds:
             a = time.perf_counter()
             Y, _ = orc.attention(hw, rows=rows)
             times.append(time.perf_counter() - a)
@@ -413,8 +475,11 @@ def main():
             tol = {torch.float32: 1e-5, torch.bfloat16: 2e-3, torch.float16: 1e-4}[wl.dtype]
             out["parity"] = {"max_abs_err_vs_fp64_oracle": err, "tolerance": tol, "ok": bool(err <= tol),
                              "rows_checked": "all" if rows is None else len(rows)}
+            parity_failed = not err <= tol
     print(json.dumps(out))
     ctx.close()
+    if parity_failed:
+        sys.exit("bench.py: the GPU result is beyond the tolerance against the fp64 oracle (see \"parity\")")
 
 
 if __name__ == "__main__":

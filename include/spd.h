@@ -107,7 +107,7 @@ typedef struct spd_kv_view {
 
 /* Bumped whenever a struct layout or a signature of this header changes; spd_abi_version() returns the value the
  * library was built with, so a program can check that header and library belong together. */
-#define SPD_ABI_VERSION 3
+#define SPD_ABI_VERSION 4
 int spd_abi_version(void);
 
 /* Create a context on HIP device `hip_device` (host call; allocates a small amount of device memory). */
@@ -121,6 +121,27 @@ const char *spd_strerror(int code);
 
 /* hipError_t of the last failed HIP call made through this context (0 if none). */
 int spd_last_hip_error(const spd_ctx *ctx);
+
+/*
+ * Options of a context: what shapes its split schedules, and the choice of kernel mapping.  spd_create takes each
+ * option's default or, if set, the value of the environment variable of the same name with the prefix SPD_ (e.g.
+ * SPD_CHUNK_MAX=4096), read once at that moment; spd_set_option changes it for later calls of this context.  The
+ * schedule-shaping options are part of the key a cached schedule is found by, so a change never reuses a schedule
+ * built under other options.  Out-of-range values are refused with SPD_ERR_LEN, unknown options with SPD_ERR_SHAPE.
+ */
+enum {
+    SPD_OPT_HEAD_PER_WAVE = 0,    /* -1 (default): head-per-wave mapping for large token-major views; 0 never; 1 whenever
+                                     the layout allows it                                                          */
+    SPD_OPT_TARGET_WG_PER_CU = 1, /* pieces per compute unit that count as one resident round (default 2)              */
+    SPD_OPT_NO_SPLIT_MAX = 2,     /* rows up to this many tokens are cut into one-step-per-wave chunks if all of them
+                                     fit the device at once (default 768)                                          */
+    SPD_OPT_CHUNK_MAX = 3,        /* tokens per piece when the work exceeds one resident round (default 16384)       */
+    SPD_OPT_SEG_COST = 4,         /* 32-token steps a piece gives up for every further row it reaches into (default 2) */
+    SPD_OPT_HALF_SKEW = 5         /* one resident round of pieces: per cent by which the half dispatched first is made
+                                     longer and the other half shorter (default 12, 0..90)                          */
+};
+int spd_set_option(spd_ctx *ctx, int32_t option, int32_t value);
+int spd_get_option(spd_ctx *ctx, int32_t option, int32_t *value);
 
 /*
  * How often a call had to build and upload a split schedule (`builds`) and how often it found the one it needed among
@@ -241,6 +262,10 @@ int spd_attention_mass_track(spd_ctx *ctx, int32_t n_rows, const float *w_in, fl
  * launch is booked under entry point 0.
  */
 int spd_set_kernel_timing(spd_ctx *ctx, int32_t max_launches);
+/* Which instance of the partial kernel the context launched last, as its template arguments
+ * {dtype, head_dim, paged, two steps in flight, head per wave, append} (all -1 before the first launch): lets a
+ * measurement say which kernel it timed, e.g. partial_mfma_kernel<1, 128, false, false, false, false>. */
+int spd_get_last_kernel_instance(const spd_ctx *ctx, int32_t instance[6]);
 int spd_get_kernel_timing(spd_ctx *ctx, int32_t entry_point, int32_t *n_launches, double *mean_us, double *min_us);
 /* The same, handing out every recorded duration (microseconds, in launch order) instead of their mean and minimum:
  * the first min(*n_launches, capacity) of them are written to us (HOST [capacity]); also clears the record. */
@@ -267,7 +292,8 @@ typedef struct spd_work_item {
 } spd_work_item;
 
 /*
- * Build the split schedule for `lens` (HOST, [n_users]) on a device with `n_compute_units` CUs.  The 32-token steps
+ * Build the split schedule for `lens` (HOST, [n_users]) on a device with `n_compute_units` CUs, under the default
+ * options (see spd_set_option) or what the SPD_* environment variables say at the time of the call.  The 32-token steps
  * of all rows, laid end to end, are cut into pieces of equal length (+-1 step).  Every token of every (user, KV head)
  * is covered by exactly one segment; segment boundaries inside a row are multiples of 32 tokens.
  * items may be NULL to query the count.  On return *n_items is the number of segments (written only if it fits

@@ -19,6 +19,8 @@ SPD_OK = 0
 SPD_ERR_NULL, SPD_ERR_SHAPE, SPD_ERR_LEN, SPD_ERR_ALIGN = -1, -2, -3, -4
 SPD_ERR_WORKSPACE, SPD_ERR_HIP, SPD_ERR_NOMEM = -5, -6, -7
 SPD_F32, SPD_BF16, SPD_F16 = 0, 1, 2
+(SPD_OPT_HEAD_PER_WAVE, SPD_OPT_TARGET_WG_PER_CU, SPD_OPT_NO_SPLIT_MAX, SPD_OPT_CHUNK_MAX, SPD_OPT_SEG_COST,
+ SPD_OPT_HALF_SKEW) = range(6)
 
 EXPORTED_SYMBOLS = (
     "spd_create", "spd_destroy", "spd_strerror", "spd_last_hip_error",
@@ -26,10 +28,11 @@ EXPORTED_SYMBOLS = (
     "spd_validate_partial", "spd_build_schedule", "spd_set_kernel_timing", "spd_get_kernel_timing",
     "spd_decode_step", "spd_partial_attn_public_batched_append", "spd_get_schedule_stats",
     "spd_attention_mass_track", "spd_get_kernel_timing_samples", "spd_lse_merge_n", "spd_public_attn_merge",
-    "spd_abi_version",
+    "spd_abi_version", "spd_set_option", "spd_get_option",
+    "spd_get_last_kernel_instance",
 )
 
-SPD_ABI_VERSION = 3      # include/spd.h's; checked against the loaded library below
+SPD_ABI_VERSION = 4      # include/spd.h's; checked against the loaded library below
 
 
 class SpdError(RuntimeError):
@@ -105,6 +108,12 @@ def _load() -> C.CDLL:
                                           C.POINTER(C.c_double)]
     lib.spd_get_kernel_timing_samples.restype = C.c_int
     lib.spd_get_kernel_timing_samples.argtypes = [vp, C.c_int32, C.c_int32, C.POINTER(C.c_float), C.POINTER(C.c_int32)]
+    lib.spd_get_last_kernel_instance.restype = C.c_int
+    lib.spd_get_last_kernel_instance.argtypes = [vp, C.POINTER(C.c_int32)]
+    lib.spd_set_option.restype = C.c_int
+    lib.spd_set_option.argtypes = [vp, C.c_int32, C.c_int32]
+    lib.spd_get_option.restype = C.c_int
+    lib.spd_get_option.argtypes = [vp, C.c_int32, C.POINTER(C.c_int32)]
     lib.spd_validate_partial.restype = C.c_int
     lib.spd_validate_partial.argtypes = [C.POINTER(spd_shape), vp, C.POINTER(spd_kv_view), fp, fp]
     lib.spd_build_schedule.restype = C.c_int
@@ -221,6 +230,21 @@ class Context:
                 _stream_ptr(stream))
         self._check(rc, name)
         return out, lse
+
+    def spd_last_kernel_name(self) -> str:
+        """The partial kernel instance launched last, as a profiler prints it."""
+        a = (C.c_int32 * 6)()
+        self._check(lib.spd_get_last_kernel_instance(self.handle, a), "spd_get_last_kernel_instance")
+        b = lambda x: "true" if x else "false"
+        return f"partial_mfma_kernel<{a[0]}, {a[1]}, {b(a[2])}, {b(a[3])}, {b(a[4])}, {b(a[5])}>"
+
+    def spd_set_option(self, option: int, value: int):
+        self._check(lib.spd_set_option(self.handle, int(option), int(value)), "spd_set_option")
+
+    def spd_get_option(self, option: int) -> int:
+        v = C.c_int32(0)
+        self._check(lib.spd_get_option(self.handle, int(option), C.byref(v)), "spd_get_option")
+        return int(v.value)
 
     def spd_get_schedule_stats(self):
         """(builds, hits) of the split-schedule cache."""

@@ -206,16 +206,19 @@ __device__ __forceinline__ void merge_weights(float l0, float l1, float &w0, flo
 // Last kernel of a fused decode step: one workgroup of D threads per (user, query head), grid (users, Hkv, G).  For each owner, a row
 // that was split is combined here (and its A / lse written, so the caller still gets both partials); unsplit and
 // empty rows were already written by the partial kernels and are read back.  Then the two owners are merged.
+// The first owner's partials are read through a_in_r / lse_in_r and, for the rows combined here, written through
+// a_in_w / lse_in_w (the same arrays for a fused step).  rows_in == nullptr says that the first owner's partials are
+// finished results handed in by the caller: they are only read, and the write pointers may be null.
 template <int D>
 __global__ __launch_bounds__(D) void finalize_step_kernel(const RowInfo *__restrict__ rows_in,
                                                           const RowInfo *__restrict__ rows_out, int Hkv, int Hq, int G,
                                                           const float *__restrict__ part_o_in,
                                                           const float *__restrict__ part_lse_in,
                                                           const float *__restrict__ part_o_out,
-                                                          const float *__restrict__ part_lse_out, float *a_in,
-                                                          float *lse_in, float *a_out, float *lse_out,
-                                                          float *__restrict__ y, float *__restrict__ lse,
-                                                          float *__restrict__ w_in)
+                                                          const float *__restrict__ part_lse_out, const float *a_in_r,
+                                                          const float *lse_in_r, float *a_in, float *lse_in,
+                                                          float *a_out, float *lse_out, float *__restrict__ y,
+                                                          float *__restrict__ lse, float *__restrict__ w_in)
 {
     __shared__ float sm_w[kCombineStage];
     __shared__ float sm_red[D];
@@ -224,7 +227,6 @@ __global__ __launch_bounds__(D) void finalize_step_kernel(const RowInfo *__restr
     const int user = blockIdx.x, kvh = blockIdx.y, g = blockIdx.z;
     const int64_t row = (int64_t)user * Hq + kvh * G + g;
     const int tid = threadIdx.x;
-    // rows_in == nullptr: the first owner's partials are finished results handed in by the caller
     const RowInfo ri = rows_in ? rows_in[user * Hkv + kvh] : RowInfo{0, 1}, ro = rows_out[user * Hkv + kvh];
     // Measured on this kernel (4 us, pure latency): the 8-wide straight-line form is the fastest for rows of up to 8
     // chunks; loading both owners' pairs in one go, or 16-wide for everything, made it 1.3-2.3 us slower.
@@ -249,8 +251,8 @@ __global__ __launch_bounds__(D) void finalize_step_kernel(const RowInfo *__restr
         if (tid == 0)
             lse_in[row] = l0;
     } else {
-        x0 = a_in[row * D + tid];
-        l0 = lse_in[row];
+        x0 = a_in_r[row * D + tid];
+        l0 = lse_in_r[row];
     }
     if (ro.n_chunks > 1 && ro.n_chunks <= kSmall) {
         combine_row_small<D, kSmall>(part_lse_out + (int64_t)ro.first_slot * G + g,

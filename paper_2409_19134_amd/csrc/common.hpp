@@ -131,7 +131,39 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
 __device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
 
-__device__ __forceinline__ float wave_xor_max(float v, int mask) { return fmaxf(v, __shfl_xor(v, mask)); }
+// Exchanges between the four 16-lane groups of a wave (lane ^ 16, lane ^ 32) without a trip through the LDS crossbar:
+// v_permlane16_swap trades the odd 16-lane rows of its first operand for the even rows of its second, v_permlane32_swap
+// the upper half of the first for the lower half of the second.  Fed the same value twice, the two results hold, in
+// every lane, the lane's own value and its partner's (in one order or the other), which is all a max or a sum needs.
+template <int MASK>
+__device__ __forceinline__ void wave_xor_pair(float v, float &a, float &b)
+{
+    static_assert(MASK == 16 || MASK == 32, "lane groups are 16 lanes wide");
+    const unsigned u = __float_as_uint(v);
+    if constexpr (MASK == 16) {
+        const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+        a = __uint_as_float(r[0]);
+        b = __uint_as_float(r[1]);
+    } else {
+        const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+        a = __uint_as_float(r[0]);
+        b = __uint_as_float(r[1]);
+    }
+}
+template <int MASK>
+__device__ __forceinline__ float wave_xor_max(float v)
+{
+    float a, b;
+    wave_xor_pair<MASK>(v, a, b);
+    return fmaxf(a, b);
+}
+template <int MASK>
+__device__ __forceinline__ float wave_xor_sum(float v)
+{
+    float a, b;
+    wave_xor_pair<MASK>(v, a, b);
+    return a + b;
+}
 
 // Rows without tokens (Theorem 1 with an empty part): A = 0, lse = -inf for the G heads of the row.
 template <int D>
@@ -186,4 +218,12 @@ struct RowInfo {
     int32_t first_slot, n_chunks;
 };
 
+// The partial kernel's arguments.
+struct PartialArgs {
+    OwnerArgs a0, a1;
+    int32_t n0;             // workgroups [0, n0) serve a0, the rest a1
+    const char *q;          // [U][Hq][D]
+    int32_t Hq, G;
+    float scale_log2e;
+};
 }  // namespace spd

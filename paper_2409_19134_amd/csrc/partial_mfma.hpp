@@ -202,8 +202,8 @@ __device__ __forceinline__ void compute_tile(const TileRegs<D * Elt<DT>::kBytes>
         x[4 + e] = (t0 + 4 + e < t_end) ? s1[e] * c : -INFINITY;
     }
     float mt = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-    mt = wave_xor_max(mt, 16);
-    mt = wave_xor_max(mt, 32);
+    mt = wave_xor_max<16>(mt);
+    mt = wave_xor_max<32>(mt);
     const float m_new = fmaxf(m, mt);  // finite: every step holds at least one token of the chunk
     const float alpha = fast_exp2(m - m_new);
     const float m_p = m_new - Elt<DT>::kPShift;  // p (and with it l and acc) carries the factor 2^kPShift
@@ -291,8 +291,12 @@ __host__ __device__ constexpr int mfma_waves_per_simd(int RB, bool prefetch, boo
 // APPEND = true adds the KV append (the address substitution costs ~1 % when nothing is appended, hence a flag).
 template <int DT, int D, bool PAGED, bool PREFETCH, bool HPW, bool APPEND>
 __global__ __launch_bounds__(HPW ? 512 : kThreads, mfma_waves_per_simd(D *Elt<DT>::kBytes, PREFETCH, HPW)) void partial_mfma_kernel(
-    OwnerArgs a0, OwnerArgs a1, int n0, const char *__restrict__ q, int Hq, int G, float scale_log2e)
+    PartialArgs A)
 {
+    const OwnerArgs &a0 = A.a0, &a1 = A.a1;
+    const int n0 = A.n0, Hq = A.Hq, G = A.G;
+    const char *__restrict__ q = A.q;
+    const float scale_log2e = A.scale_log2e;
     const bool second = (int)blockIdx.x >= n0;  // workgroup-uniform: which owner this workgroup serves
     const DevItem *__restrict__ items = second ? a1.items : a0.items;
     const KvAddr kv = second ? a1.kv : a0.kv;
@@ -446,8 +450,8 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, mfma_waves_per_simd(D *Elt<DT
             begin_segment(nx, L, qB, tb, T0, P);
 
         // ---- combine the lane groups (sum of l) ... ----
-        l += __shfl_xor(l, 16);
-        l += __shfl_xor(l, 32);
+        l = wave_xor_sum<16>(l);
+        l = wave_xor_sum<32>(l);
         const bool direct = it.n_chunks == 1;
         if (HPW) {
             // ... and that is all: the wave owns head `wave` of this token range.  Lane (r < G, grp) holds channels

@@ -12,21 +12,51 @@ namespace spd::host {
 
 constexpr int kChunkAlign = 32;      // chunk boundaries are multiples of the MFMA kernel's 32-token step
 constexpr int kChunkMin = 128;       // one 32-token step for each of the four waves
-constexpr int kChunkMaxDefault = 16384;    // tokens per piece when the work exceeds one resident wave: a new
-                                            // workgroup costs a few microseconds of an idle slot, more than the longer
-                                            // tail of bigger pieces (4096: 3 % slower on the longest workload)
-constexpr int kNoSplitMaxDefault = 768;     // if no row is longer than this the work is latency-bound: every row
-                                            // is cut into chunks of one step per wave
-constexpr int kTargetWgPerCuDefault = 2;   // workgroups of the MFMA kernel resident per CU (2 waves per SIMD)
 constexpr int kHeadPerWaveMinHeadSteps = 80;  // (32-token steps * KV heads) per CU from which the head-per-wave mapping is used
 
-inline int env_int(const char *name, int dflt)
+// What shapes a schedule besides the lengths.  A context starts from the defaults below, replaced by SPD_* variables
+// of the environment that spd_create finds set (tuning_from_env), and spd_set_option changes them per context; all
+// of them are part of the key a cached schedule is remembered by.
+struct Tuning {
+    // workgroups of the MFMA kernel resident per CU (2 waves per SIMD)                        SPD_TARGET_WG_PER_CU
+    int32_t target_wg_per_cu = 2;
+    // if no row is longer than this the work is latency-bound: every row is cut into chunks of one step per wave
+    //                                                                                          SPD_NO_SPLIT_MAX
+    int32_t no_split_max = 768;
+    // tokens per piece when the work exceeds one resident round: a new workgroup costs a few microseconds of an idle
+    // slot, more than the longer tail of bigger pieces (4096: 3 % slower on the longest workload)  SPD_CHUNK_MAX
+    int32_t chunk_max = 16384;
+    // 32-token steps a piece gives up for every further row it reaches into (a second segment costs an epilogue and a
+    // memory round trip before the new row's first tile; measured on the headline workload: 0 -> 2 steps takes
+    // 0.45 us off a 32.5 us step, 4 and more give it back)                                      SPD_SEG_COST
+    int32_t seg_cost = 2;
+    // When the pieces are exactly one resident round, the half dispatched first gets (100 + s) % of the mean piece and
+    // the other half (100 - s) %: every workgroup asks for its first tile in the same microsecond, the memory system
+    // serves those ~35 MB in launch order, and the half served last stays ~4 us behind to the end (measured with
+    // in-kernel time stamps); unequal shares let both halves finish together (0 -> 12 %: -0.35 us)  SPD_HALF_SKEW
+    int32_t half_skew = 12;
+};
+constexpr int kTuningInts = 5;
+static_assert(sizeof(Tuning) == kTuningInts * sizeof(int32_t), "the key takes the struct as kTuningInts integers");
+
+inline int env_int(const char *name, int dflt, int least = 1)
 {
     const char *s = std::getenv(name);
     if (!s || !*s)
         return dflt;
     const long v = std::strtol(s, nullptr, 10);
-    return v > 0 ? (int)v : dflt;
+    return v >= least && v <= (1 << 30) ? (int)v : dflt;
+}
+
+inline Tuning tuning_from_env()
+{
+    Tuning t;
+    t.target_wg_per_cu = env_int("SPD_TARGET_WG_PER_CU", t.target_wg_per_cu);
+    t.no_split_max = env_int("SPD_NO_SPLIT_MAX", t.no_split_max);
+    t.chunk_max = env_int("SPD_CHUNK_MAX", t.chunk_max);
+    t.seg_cost = env_int("SPD_SEG_COST", t.seg_cost, 0);
+    t.half_skew = std::min(90, env_int("SPD_HALF_SKEW", t.half_skew, 0));
+    return t;
 }
 
 // The split schedule ("stream-K" over tokens).  All KV heads of a user hold the same tokens, so the schedule is laid
@@ -63,7 +93,7 @@ inline int head_per_wave_waves(int Hkv)
     return 1;
 }
 
-inline void build_schedule(int Hkv, int n_users, const int32_t *lens, int n_cus, bool hpw, Schedule &S)
+inline void build_schedule(int Hkv, int n_users, const int32_t *lens, int n_cus, bool hpw, const Tuning &tune, Schedule &S)
 {
     const int hpw_waves = hpw ? head_per_wave_waves(Hkv) : 1;
     const int hpw_groups = hpw ? Hkv / hpw_waves : 1;
@@ -92,8 +122,8 @@ inline void build_schedule(int Hkv, int n_users, const int32_t *lens, int n_cus,
     int64_t short_chunks = 0;
     for (int u = 0; u < n_users; ++u)
         short_chunks += ((lens[u] + kChunkAlign - 1) / kChunkAlign + spd::kWaves - 1) / spd::kWaves;
-    const int64_t resident = (int64_t)std::max(1, n_cus) * env_int("SPD_TARGET_WG_PER_CU", kTargetWgPerCuDefault);
-    if (max_len <= env_int("SPD_NO_SPLIT_MAX", kNoSplitMaxDefault) && short_chunks * (hpw ? hpw_groups : Hkv) <= resident) {
+    const int64_t resident = (int64_t)std::max(1, n_cus) * tune.target_wg_per_cu;
+    if (max_len <= tune.no_split_max && short_chunks * (hpw ? hpw_groups : Hkv) <= resident) {
         const int64_t per = spd::kWaves;  // steps per chunk
         for (int u = 0; u < n_users; ++u) {
             const int64_t steps = (lens[u] + kChunkAlign - 1) / kChunkAlign;
@@ -102,27 +132,75 @@ inline void build_schedule(int Hkv, int n_users, const int32_t *lens, int n_cus,
         }
         S.chunk_tokens = (int)std::min<int64_t>(per, (max_len + kChunkAlign - 1) / kChunkAlign) * kChunkAlign;
     } else {
-        const int64_t slots = (int64_t)std::max(1, n_cus) * env_int("SPD_TARGET_WG_PER_CU", kTargetWgPerCuDefault);
+        const int64_t slots = resident;
         // groups per resident wave of workgroups
         // head per wave: a CU holds eight such waves, i.e. 8 / waves workgroups
         const int64_t wg = hpw ? std::max<int64_t>(1, (int64_t)std::max(1, n_cus) * (8 / hpw_waves) / hpw_groups)
                                : std::max<int64_t>(1, slots / Hkv);
-        const int64_t piece_max = std::max(kChunkMin, env_int("SPD_CHUNK_MAX", kChunkMaxDefault)) / kChunkAlign;
+        const int64_t piece_max = std::max(kChunkMin, (int)tune.chunk_max) / kChunkAlign;
         // group boundaries (cumulative step counts)
         std::vector<int64_t> ends;
+        std::vector<int64_t> cut_num;  // group i ends at the fraction cut_num[i] / cut_den of the line
+        int64_t cut_den = 1;
         if (T <= wg * piece_max) {
             // at least one step per wave
             // (measured on the headline workload: fewer, round-aligned pieces or more pieces than fit at once are
             // both slower - 55 groups of 20 steps +2 us, 80 groups +1.5 us against 64 groups of 17-18 steps)
             const int64_t W = std::min<int64_t>(wg, hpw ? T : (T + spd::kWaves - 1) / spd::kWaves);
-            for (int64_t i = 0; i < W; ++i)
-                ends.push_back(T * (i + 1) / W);
+            // exactly one resident round of head-major pieces with several steps per wave: unequal halves (see Tuning)
+            const int64_t skew = (!hpw && W == wg && W >= 2 && T >= 8 * W) ? tune.half_skew : 0;
+            for (int64_t i = 0; i < W; ++i) {
+                const int64_t h = W / 2;
+                // cumulative weight up to group i (inclusive), in percent-groups
+                const int64_t cum = (i + 1 <= h) ? (i + 1) * (100 + skew) : h * (100 + skew) + (i + 1 - h) * (100 - skew);
+                const int64_t tot = h * (100 + skew) + (W - h) * (100 - skew);
+                ends.push_back(T * cum / tot);
+                cut_num.push_back(cum);
+                cut_den = tot;
+            }
         } else {
             // several resident waves of equal pieces; the hardware hands them out in launch order.  (Cutting the last
             // wave's share finer to shorten the tail was measured and lost 1-3 %: short pieces cost more than the tail.)
             const int64_t W = wg * ((T + wg * piece_max - 1) / (wg * piece_max));
-            for (int64_t i = 0; i < W; ++i)
+            for (int64_t i = 0; i < W; ++i) {
                 ends.push_back(T * (i + 1) / W);
+                cut_num.push_back(i + 1);
+            }
+            cut_den = W;
+        }
+        // A piece that crosses into another user's row pays for a second segment (an epilogue, and a memory round
+        // trip before the new row's first tile): such pieces get `seg_cost` steps fewer.  The cuts are made on a line
+        // that holds seg_cost extra steps in front of every user but the first; a cut that lands in such a gap moves
+        // to the user's boundary.
+        const int64_t seg_cost = tune.seg_cost;
+        if (seg_cost > 0) {
+            int64_t n_rows_with_tokens = 0;
+            for (int u = 0; u < n_users; ++u)
+                n_rows_with_tokens += lens[u] > 0;
+            const int64_t Tv = T + seg_cost * std::max<int64_t>(0, n_rows_with_tokens - 1);
+            size_t i = 0;
+            int64_t real0 = 0, virt0 = 0;  // the current user's first step on the real and on the stretched line
+            bool first = true;
+            for (int u = 0; u < n_users && i < ends.size(); ++u) {
+                const int64_t steps = (lens[u] + kChunkAlign - 1) / kChunkAlign;
+                if (steps == 0)
+                    continue;
+                if (!first)
+                    virt0 += seg_cost;
+                first = false;
+                // cuts (on the stretched line) up to the end of this user's steps
+                while (i < ends.size()) {
+                    const int64_t cut = Tv * cut_num[i] / cut_den;
+                    if (cut > virt0 + steps)
+                        break;
+                    ends[i++] = real0 + std::max<int64_t>(0, cut - virt0);
+                }
+                real0 += steps;
+                virt0 += steps;
+            }
+            for (; i < ends.size(); ++i)
+                ends[i] = T;
+            ends.back() = T;
         }
         const int64_t W = (int64_t)ends.size();
         int64_t longest = ends[0];

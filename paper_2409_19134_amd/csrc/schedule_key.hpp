@@ -59,7 +59,9 @@ inline int32_t uniform_growth(const std::vector<uint8_t> &old_key, const std::ve
     return g;
 }
 
-inline void make_key(const spd_shape *s, const spd_kv_view *v, bool hpw, std::vector<uint8_t> &key)
+// tuning: the kTuningInts integers of the context's Tuning (they shape the schedule like the lengths do).
+inline void make_key(const spd_shape *s, const spd_kv_view *v, bool hpw, const int32_t *tuning, int n_tuning,
+                     std::vector<uint8_t> &key)
 {
     key.clear();
     auto put = [&key](const void *p, size_t n) {
@@ -76,6 +78,7 @@ inline void make_key(const spd_shape *s, const spd_kv_view *v, bool hpw, std::ve
     // lengths and block table but have a pool each, share one schedule.
     const int32_t tables = (v->block_size == 0 && v->k_ptrs_dev) ? 1 : 0;  // the items then hold offsets, not addresses
     put(&tables, sizeof tables);
+    put(tuning, sizeof(int32_t) * (size_t)n_tuning);
     put(&v->head_stride, sizeof v->head_stride);
     if (v->head_strides && v->block_size == 0)
         put(v->head_strides, sizeof(int64_t) * (size_t)v->n_users);

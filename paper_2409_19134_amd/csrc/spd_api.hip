@@ -80,6 +80,9 @@ struct spd_ctx {
     uint64_t tick = 0;
     int64_t schedule_builds = 0, schedule_hits = 0;
     bool timing = false;
+    int32_t last_instance[6] = {-1, -1, -1, -1, -1, -1};  // template arguments of the partial kernel launched last
+    Tuning tuning;           // what shapes the split schedules (SPD_OPT_*)
+    int head_per_wave = -1;  // SPD_OPT_HEAD_PER_WAVE: 0 never, 1 whenever the layout allows, -1 by the size rule
     std::vector<uint8_t> key_scratch;
     Owner owner[2];
 };
@@ -127,14 +130,46 @@ int64_t total_steps(const spd_kv_view *v)
 // below that the four interleaving waves of the head-major mapping finish a short piece sooner.  Measured crossover
 // (256 CUs): ~2300 steps with 8 KV heads, between 600 and 1200 with 32, above 1200 with 16: about 330 MB of K/V in
 // each case, so the bound is on steps * KV heads.
-// SPD_HEAD_PER_WAVE=0 / 1 in the environment overrides the rule (never / whenever the layout allows): for tests and
+// The option SPD_OPT_HEAD_PER_WAVE (0 / 1) overrides the rule (never / whenever the layout allows): for tests and
 // measurements.
 bool head_per_wave_pays(const spd_ctx *ctx, const spd_shape *s, int64_t steps)
 {
-    const char *force = std::getenv("SPD_HEAD_PER_WAVE");
-    if (force && (force[0] == '0' || force[0] == '1'))
-        return force[0] == '1';
+    if (ctx->head_per_wave == 0 || ctx->head_per_wave == 1)
+        return ctx->head_per_wave == 1;
     return steps * std::max(8, s->n_kv_heads) >= (int64_t)std::max(1, ctx->n_cus) * kHeadPerWaveMinHeadSteps;
+}
+
+// A schedule as the kernels read it, laid out for device memory:
+// DevItem[items] | CombineRow[split rows] | RowInfo[n_users * Hkv], each part 256-byte aligned.
+struct ScheduleBlob {
+    std::vector<char> bytes;  // a multiple of 256
+    size_t off_rows = 0, off_info = 0;
+    int64_t n_items = 0;      // workgroups of the launch
+    int64_t n_slots = 0;      // chunk partials
+    int n_split_rows = 0;
+};
+
+void build_blob(const spd_shape *s, const spd_kv_view *v, bool hpw, int n_cus, const Tuning &tune, ScheduleBlob &B)
+{
+    Schedule S;
+    build_schedule(s->n_kv_heads, v->n_users, v->lens, n_cus, hpw, tune, S);
+    DeviceTables T;
+    build_device_tables(S, s->n_kv_heads, elt_size(s->dtype), v, hpw, T);
+    const size_t b_items = T.items.size() * sizeof(DevItem);
+    const size_t b_rows = T.split_rows.size() * sizeof(CombineRow);
+    const size_t b_info = T.row_info.size() * sizeof(RowInfo);
+    B.off_rows = (b_items + 255) / 256 * 256;
+    B.off_info = B.off_rows + (b_rows + 255) / 256 * 256;
+    B.bytes.assign(B.off_info + (b_info + 255) / 256 * 256 + 256, 0);
+    if (b_items)
+        std::memcpy(B.bytes.data(), T.items.data(), b_items);
+    if (b_rows)
+        std::memcpy(B.bytes.data() + B.off_rows, T.split_rows.data(), b_rows);
+    if (b_info)
+        std::memcpy(B.bytes.data() + B.off_info, T.row_info.data(), b_info);
+    B.n_items = T.items_launched;
+    B.n_slots = S.n_slots;
+    B.n_split_rows = (int)T.split_rows.size();
 }
 
 // Find or build the device-resident schedule for this view (hpw: pieces for the head-per-wave kernel).  Uploads are
@@ -143,7 +178,7 @@ int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view
                  hipStream_t stream, CachedSchedule **out)
 {
     std::vector<uint8_t> &key = ctx->key_scratch;  // reused from call to call: no allocation on the hit path
-    make_key(s, v, hpw, key);
+    make_key(s, v, hpw, &ctx->tuning.target_wg_per_cu, kTuningInts, key);
     const uint64_t h = hash_key(key.data(), key.size());
     ++ctx->tick;
     CachedSchedule *victim = &own.cache[0];
@@ -184,30 +219,21 @@ int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view
         *out = grown;
         return SPD_OK;
     }
-    Schedule S;
-    build_schedule(s->n_kv_heads, v->n_users, v->lens, ctx->n_cus, hpw, S);
-
-    DeviceTables T;
-    build_device_tables(S, s->n_kv_heads, elt_size(s->dtype), v, hpw, T);
-    const std::vector<DevItem> &dev_items = T.items;
-    const std::vector<CombineRow> &split_rows = T.split_rows;
-    const std::vector<RowInfo> &row_info = T.row_info;
-    const int64_t n_groups = (int64_t)T.items_launched;
-    const size_t b_items = dev_items.size() * sizeof(DevItem);
-    const size_t b_rows = split_rows.size() * sizeof(CombineRow);
-    const size_t b_info = row_info.size() * sizeof(RowInfo);
-    const size_t off_rows = (b_items + 255) / 256 * 256;
-    const size_t off_info = off_rows + (b_rows + 255) / 256 * 256;
-    const size_t total = off_info + (b_info + 255) / 256 * 256 + 256;
+    ScheduleBlob B;
+    build_blob(s, v, hpw, ctx->n_cus, ctx->tuning, B);
+    const size_t total = B.bytes.size();
 
     CachedSchedule &e = *victim;
     ++ctx->schedule_builds;
     if (e.valid) {
         // Reusing an entry: work in flight may still read its device blob, and its last upload may still read the
-        // staging copy.  On the same stream the new upload is ordered behind that work anyway; another stream is
-        // waited for.  The staging copy is only rewritten once its last upload has completed.
+        // staging copy.  On the same stream the new upload is ordered behind that work anyway.  If the entry was last
+        // used on another stream, the whole device is waited for: that stream belongs to the caller and may be gone by
+        // now, so it is never touched again (evictions are rare; recording an event per call to wait on instead would
+        // put a marker between the kernels of every step).  The staging copy is only rewritten once its last upload
+        // has completed.
         if (e.last_stream != stream)
-            SPD_HIP(ctx, hipStreamSynchronize(e.last_stream));
+            SPD_HIP(ctx, hipDeviceSynchronize());
         SPD_HIP(ctx, hipEventSynchronize(e.uploaded));
     }
     if (e.capacity < total) {
@@ -236,13 +262,7 @@ int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view
     }
     if (!e.uploaded)
         SPD_HIP(ctx, hipEventCreateWithFlags(&e.uploaded, hipEventDisableTiming));
-    std::memset(e.pinned, 0, total);
-    if (b_items)
-        std::memcpy(e.pinned, dev_items.data(), b_items);
-    if (b_rows)
-        std::memcpy(e.pinned + off_rows, split_rows.data(), b_rows);
-    if (b_info)
-        std::memcpy(e.pinned + off_info, row_info.data(), b_info);
+    std::memcpy(e.pinned, B.bytes.data(), total);
     // The upload is a kernel that reads the pinned staging copy over the bus: a copy command would leave the compute
     // queue for a DMA engine and back, which costs the stream tens of microseconds per schedule.
     {
@@ -262,12 +282,12 @@ int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view
     e.grow = 0;
     e.key = key;
     e.last_use = ctx->tick;
-    e.n_items = n_groups;
+    e.n_items = B.n_items;
     e.hpw = hpw;
-    e.n_slots = S.n_slots;
-    e.n_split_rows = (int)split_rows.size();
-    e.off_rows = off_rows;
-    e.off_info = off_info;
+    e.n_slots = B.n_slots;
+    e.n_split_rows = B.n_split_rows;
+    e.off_rows = B.off_rows;
+    e.off_info = B.off_info;
     *out = &e;
     return SPD_OK;
 }
@@ -275,10 +295,11 @@ int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view
 int ensure_scratch(spd_ctx *ctx, Owner &own, size_t o_floats, size_t lse_floats)
 {
     if (own.part_o_cap < o_floats) {
-        if (own.part_o)
-            SPD_HIP(ctx, hipFree(own.part_o));  // hipFree waits for work that may still use the old buffer
+        float *old = own.part_o;  // forgotten before it is freed: a failing hipFree must not leave it behind in use
         own.part_o = nullptr;
         own.part_o_cap = 0;
+        if (old)
+            SPD_HIP(ctx, hipFree(old));  // hipFree waits for work that may still use the old buffer
         const size_t cap = o_floats + o_floats / 4;
         if (hipMalloc(reinterpret_cast<void **>(&own.part_o), cap * sizeof(float)) != hipSuccess) {
             own.part_o = nullptr;
@@ -287,10 +308,11 @@ int ensure_scratch(spd_ctx *ctx, Owner &own, size_t o_floats, size_t lse_floats)
         own.part_o_cap = cap;
     }
     if (own.part_lse_cap < lse_floats) {
-        if (own.part_lse)
-            SPD_HIP(ctx, hipFree(own.part_lse));
+        float *old = own.part_lse;
         own.part_lse = nullptr;
         own.part_lse_cap = 0;
+        if (old)
+            SPD_HIP(ctx, hipFree(old));
         const size_t cap = lse_floats + lse_floats / 4;
         if (hipMalloc(reinterpret_cast<void **>(&own.part_lse), cap * sizeof(float)) != hipSuccess) {
             own.part_lse = nullptr;
@@ -321,7 +343,20 @@ int prepare_partial(spd_ctx *ctx, int which, const spd_shape *s, const void *q, 
     return ensure_scratch(ctx, own, (size_t)(*e)->n_slots * G * s->head_dim + 4, (size_t)(*e)->n_slots * G + 4);
 }
 
-OwnerArgs owner_args(const Owner &own, const CachedSchedule *e, const spd_shape *s, const spd_kv_view *v, float *out,
+// Where one owner's chunk partials go: the context's own scratch memory, or a part of the library's fixed array.
+struct ScratchPtrs {
+    float *part_o = nullptr;      // [slots][G][D]
+    float *part_lse = nullptr;    // [slots][G]
+};
+ScratchPtrs scratch_of(const Owner &own)
+{
+    ScratchPtrs sp;
+    sp.part_o = own.part_o;
+    sp.part_lse = own.part_lse;
+    return sp;
+}
+
+OwnerArgs owner_args(const ScratchPtrs &own, const CachedSchedule *e, const spd_shape *s, const spd_kv_view *v, float *out,
                      float *lse, const void *k_new, const void *v_new)
 {
     const int es = elt_size(s->dtype);
@@ -369,11 +404,7 @@ struct MfmaLaunch {
     uint32_t lds;
     hipStream_t stream;
     hipEvent_t ev0, ev1;  // both null unless timing is armed: receive the kernel's own start and stop time stamps
-    const OwnerArgs *a0, *a1;
-    int n0;
-    const char *q;
-    int Hq, G;
-    float c;
+    spd::PartialArgs args;
 };
 
 // The kernel instances that exist: the head-per-wave mapping always keeps two steps in flight, fp32 rows of 512 bytes
@@ -390,7 +421,7 @@ bool launch_mfma(const MfmaLaunch &L)
 {
     if constexpr (mfma_instance_exists<DT, D, PREFETCH, HPW>()) {
         hipExtLaunchKernelGGL((spd::partial_mfma_kernel<DT, D, PAGED, PREFETCH, HPW, APPEND>), L.grid, L.block, L.lds,
-                              L.stream, L.ev0, L.ev1, 0, *L.a0, *L.a1, L.n0, L.q, L.Hq, L.G, L.c);
+                              L.stream, L.ev0, L.ev1, 0, L.args);
         return true;
     } else {
         return false;
@@ -403,17 +434,17 @@ struct NewToken {  // KV append for the public owner (protocol step 3a); both nu
     const void *k = nullptr, *v = nullptr;
 };
 
+// sp0 / sp1: where the two owners' chunk partials go.
 int launch_partial(spd_ctx *ctx, int which, const CachedSchedule *e0, const spd_kv_view *v0, float *out0, float *lse0,
-                   const CachedSchedule *e1, const spd_kv_view *v1, float *out1, float *lse1, const spd_shape *s,
-                   const void *q, NewToken nt, hipStream_t stream)
+                   const ScratchPtrs &sp0, const CachedSchedule *e1, const spd_kv_view *v1, float *out1, float *lse1,
+                   const ScratchPtrs &sp1, const spd_shape *s, const void *q, NewToken nt, hipStream_t stream)
 {
     const int64_t n0 = e0->n_items, n1 = e1 ? e1->n_items : 0;
     if (n0 + n1 == 0)
         return SPD_OK;
-    Owner &own0 = ctx->owner[which];
     // the public owner is entry point 1: the new token, if any, belongs to whichever of the two that is
-    const OwnerArgs a0 = owner_args(own0, e0, s, v0, out0, lse0, which == 1 ? nt.k : nullptr, which == 1 ? nt.v : nullptr);
-    const OwnerArgs a1 = e1 ? owner_args(ctx->owner[1 - which], e1, s, v1, out1, lse1, which == 0 ? nt.k : nullptr,
+    const OwnerArgs a0 = owner_args(sp0, e0, s, v0, out0, lse0, which == 1 ? nt.k : nullptr, which == 1 ? nt.v : nullptr);
+    const OwnerArgs a1 = e1 ? owner_args(sp1, e1, s, v1, out1, lse1, which == 0 ? nt.k : nullptr,
                                          which == 0 ? nt.v : nullptr)
                             : a0;
     const int G = s->n_q_heads / s->n_kv_heads;
@@ -434,13 +465,13 @@ int launch_partial(spd_ctx *ctx, int which, const CachedSchedule *e0, const spd_
     L.stream = stream;
     L.ev0 = ev0;
     L.ev1 = ev1;
-    L.a0 = &a0;
-    L.a1 = &a1;
-    L.n0 = (int)n0;
-    L.q = static_cast<const char *>(q);
-    L.Hq = s->n_q_heads;
-    L.G = G;
-    L.c = c;
+    L.args.a0 = a0;
+    L.args.a1 = a1;
+    L.args.n0 = (int)n0;
+    L.args.q = static_cast<const char *>(q);
+    L.args.Hq = s->n_q_heads;
+    L.args.G = G;
+    L.args.scale_log2e = c;
     // Two steps in flight (PREFETCH) or one: clearly more pieces than the one-step kernel holds at once, three per CU
     // (a few left over just start a little later), run on the two-step kernel, two per CU; so do launches whose pieces
     // fit two per CU anyway (a wave then needs half as many dependent memory round trips).  Head-per-wave workgroups
@@ -465,6 +496,8 @@ int launch_partial(spd_ctx *ctx, int which, const CachedSchedule *e0, const spd_
     });
     if (!ok)
         return SPD_ERR_SHAPE;  // no kernel instance for this combination: a bug in the rules above
+    const int32_t inst[6] = {s->dtype, D, v0->block_size != 0, prefetch, hpw, nt.k != nullptr};
+    std::memcpy(ctx->last_instance, inst, sizeof inst);
     SPD_HIP(ctx, hipGetLastError());
     if (timed)
         ++town.ev_used;
@@ -522,10 +555,99 @@ int partial_attention(spd_ctx *ctx, int which, const spd_shape *s, const void *q
     rc = prepare_partial(ctx, which, s, q, v, out, lse, -1, stream, &e);
     if (rc != SPD_OK || !e)
         return rc;
-    rc = launch_partial(ctx, which, e, v, out, lse, nullptr, nullptr, nullptr, nullptr, s, q, nt, stream);
+    rc = launch_partial(ctx, which, e, v, out, lse, scratch_of(ctx->owner[which]), nullptr, nullptr, nullptr, nullptr,
+                        ScratchPtrs(), s, q, nt, stream);
     if (rc != SPD_OK)
         return rc;
     return launch_combine(ctx, which, e, s, out, lse, stream);
+}
+
+// The closing kernel of a step: combines whichever rows either owner had to split and merges the owners.
+// ep == nullptr: the first owner's partials (a_in_r, lse_in_r) are finished results delivered by the caller; they are
+// only read, and a_in_w / lse_in_w may be null.
+int launch_finalize(spd_ctx *ctx, const spd_shape *shape, int n_users, const CachedSchedule *ep, const CachedSchedule *eo,
+                    const ScratchPtrs &sp_in, const ScratchPtrs &sp_out, const float *a_in_r, const float *lse_in_r,
+                    float *a_in_w, float *lse_in_w, float *a_out, float *lse_out, float *y, float *lse, float *w_in,
+                    hipStream_t stream)
+{
+    const int G = shape->n_q_heads / shape->n_kv_heads;
+    const RowInfo *ri = ep ? reinterpret_cast<const RowInfo *>(ep->dev + ep->off_info) : nullptr;
+    const RowInfo *ro = reinterpret_cast<const RowInfo *>(eo->dev + eo->off_info);
+    const dim3 grid((unsigned)n_users, (unsigned)shape->n_kv_heads, (unsigned)G);
+    if (shape->head_dim == 64)
+        hipLaunchKernelGGL((spd::finalize_step_kernel<64>), grid, dim3(64), 0, stream, ri, ro, shape->n_kv_heads,
+                           shape->n_q_heads, G, (const float *)sp_in.part_o, (const float *)sp_in.part_lse,
+                           (const float *)sp_out.part_o, (const float *)sp_out.part_lse, a_in_r, lse_in_r, a_in_w, lse_in_w,
+                           a_out, lse_out, y, lse, w_in);
+    else
+        hipLaunchKernelGGL((spd::finalize_step_kernel<128>), grid, dim3(128), 0, stream, ri, ro, shape->n_kv_heads,
+                           shape->n_q_heads, G, (const float *)sp_in.part_o, (const float *)sp_in.part_lse,
+                           (const float *)sp_out.part_o, (const float *)sp_out.part_lse, a_in_r, lse_in_r, a_in_w, lse_in_w,
+                           a_out, lse_out, y, lse, w_in);
+    SPD_HIP(ctx, hipGetLastError());
+    return SPD_OK;
+}
+
+// Everything spd_decode_step checks before anything is enqueued (also makes the context's device current).
+int validate_decode_step(spd_ctx *ctx, const spd_shape *shape, const void *q, const spd_kv_view *priv,
+                         const spd_kv_view *pub, NewToken nt, const float *a_in, const float *lse_in, const float *a_out,
+                         const float *lse_out, const float *y, const float *lse, const float *w_in)
+{
+    if (!priv || !pub)
+        return SPD_ERR_NULL;
+    if (priv->n_users != pub->n_users)
+        return SPD_ERR_LEN;
+    SPD_HIP(ctx, hipSetDevice(ctx->device));
+    int rc = spd_validate_partial(shape, q, priv, a_in, lse_in);
+    if (rc == SPD_OK)
+        rc = spd_validate_partial(shape, q, pub, a_out, lse_out);
+    if (rc == SPD_OK)
+        rc = validate_new_token(pub, nt);
+    if (rc != SPD_OK)
+        return rc;
+    if (priv->n_users == 0)
+        return SPD_OK;
+    if (!y || !lse || !w_in)
+        return SPD_ERR_NULL;
+    if (!aligned16(y))
+        return SPD_ERR_ALIGN;
+    return SPD_OK;
+}
+
+// Both owners of a fused step share one launch, so they share the mapping: head per wave if both layouts allow it and
+// the two together are bandwidth-bound.
+bool fused_step_mapping(const spd_ctx *ctx, const spd_shape *shape, const spd_kv_view *priv, const spd_kv_view *pub)
+{
+    return head_per_wave_layout(shape, priv) && head_per_wave_layout(shape, pub) &&
+           head_per_wave_pays(ctx, shape, total_steps(priv) + total_steps(pub));
+}
+
+// The launches of a fused step, given both owners' schedules (device resident) and where their chunk partials go.
+int launch_decode_step(spd_ctx *ctx, const spd_shape *shape, const void *q, const spd_kv_view *priv, const spd_kv_view *pub,
+                       NewToken nt, const CachedSchedule *ep, const CachedSchedule *eo, const ScratchPtrs &sp_in,
+                       const ScratchPtrs &sp_out, float *a_in, float *lse_in, float *a_out, float *lse_out, float *y,
+                       float *lse, float *w_in, hipStream_t stream)
+{
+    int rc;
+    // one grid for both owners, the private owner's long streams first (measured faster than public first): the
+    // public owner's short, latency-bound pieces then run beside them on the workgroup slots that remain
+    if ((priv->block_size != 0) == (pub->block_size != 0)) {
+        rc = launch_partial(ctx, 0, ep, priv, a_in, lse_in, sp_in, eo, pub, a_out, lse_out, sp_out, shape, q, nt, stream);
+        if (rc != SPD_OK)
+            return rc;
+    } else {  // different storage modes need different kernel instances
+        rc = launch_partial(ctx, 1, eo, pub, a_out, lse_out, sp_out, nullptr, nullptr, nullptr, nullptr, ScratchPtrs(), shape, q,
+                            nt, stream);
+        if (rc != SPD_OK)
+            return rc;
+        rc = launch_partial(ctx, 0, ep, priv, a_in, lse_in, sp_in, nullptr, nullptr, nullptr, nullptr, ScratchPtrs(), shape, q,
+                            NewToken(), stream);
+        if (rc != SPD_OK)
+            return rc;
+    }
+    // join: one kernel combines whichever rows were split and merges the owners
+    return launch_finalize(ctx, shape, priv->n_users, ep, eo, sp_in, sp_out, a_in, lse_in, a_in, lse_in, a_out, lse_out, y, lse,
+                           w_in, stream);
 }
 
 // No C++ exception leaves the library: a failed host allocation (the schedule builder and the cache use std::vector)
@@ -581,6 +703,10 @@ int spd_create(spd_ctx **out, int hip_device)
         return SPD_ERR_NOMEM;
     }
     ctx->device = hip_device;
+    ctx->tuning = tuning_from_env();
+    ctx->head_per_wave = env_int("SPD_HEAD_PER_WAVE", -1, 0);
+    if (ctx->head_per_wave > 1)
+        ctx->head_per_wave = -1;
     hipError_t e = hipSetDevice(hip_device);
     if (e == hipSuccess)
         e = hipDeviceGetAttribute(&ctx->n_cus, hipDeviceAttributeMultiprocessorCount, hip_device);
@@ -619,6 +745,60 @@ int spd_destroy(spd_ctx *ctx)
 }
 
 int spd_last_hip_error(const spd_ctx *ctx) { return ctx ? ctx->last_hip : 0; }
+
+namespace {
+int32_t *option_slot(spd_ctx *ctx, int32_t option)
+{
+    switch (option) {
+    case SPD_OPT_HEAD_PER_WAVE: return &ctx->head_per_wave;
+    case SPD_OPT_TARGET_WG_PER_CU: return &ctx->tuning.target_wg_per_cu;
+    case SPD_OPT_NO_SPLIT_MAX: return &ctx->tuning.no_split_max;
+    case SPD_OPT_CHUNK_MAX: return &ctx->tuning.chunk_max;
+    case SPD_OPT_SEG_COST: return &ctx->tuning.seg_cost;
+    case SPD_OPT_HALF_SKEW: return &ctx->tuning.half_skew;
+    default: return nullptr;
+    }
+}
+}  // namespace
+
+int spd_set_option(spd_ctx *ctx, int32_t option, int32_t value)
+{
+    if (!ctx)
+        return SPD_ERR_NULL;
+    int32_t *slot = option_slot(ctx, option);
+    if (!slot)
+        return SPD_ERR_SHAPE;
+    bool ok;
+    switch (option) {
+    case SPD_OPT_HEAD_PER_WAVE: ok = value >= -1 && value <= 1; break;
+    case SPD_OPT_SEG_COST: ok = value >= 0 && value <= (1 << 20); break;
+    case SPD_OPT_HALF_SKEW: ok = value >= 0 && value <= 90; break;
+    default: ok = value >= 1 && value <= (1 << 30); break;
+    }
+    if (!ok)
+        return SPD_ERR_LEN;
+    *slot = value;
+    return SPD_OK;
+}
+
+int spd_get_option(spd_ctx *ctx, int32_t option, int32_t *value)
+{
+    if (!ctx || !value)
+        return SPD_ERR_NULL;
+    const int32_t *slot = option_slot(ctx, option);
+    if (!slot)
+        return SPD_ERR_SHAPE;
+    *value = *slot;
+    return SPD_OK;
+}
+
+int spd_get_last_kernel_instance(const spd_ctx *ctx, int32_t instance[6])
+{
+    if (!ctx || !instance)
+        return SPD_ERR_NULL;
+    std::memcpy(instance, ctx->last_instance, sizeof ctx->last_instance);
+    return SPD_OK;
+}
 
 int spd_get_schedule_stats(const spd_ctx *ctx, int64_t *builds, int64_t *hits)
 {
@@ -662,7 +842,7 @@ try {
         if (lens[u] < 0 || lens[u] > kMaxLen)
             return SPD_ERR_LEN;
     Schedule S;
-    build_schedule(shape->n_kv_heads, n_users, lens, n_compute_units, head_per_wave != 0, S);
+    build_schedule(shape->n_kv_heads, n_users, lens, n_compute_units, head_per_wave != 0, tuning_from_env(), S);
     *n_items = (int64_t)S.items.size();
     if (chunk_tokens)
         *chunk_tokens = S.chunk_tokens;
@@ -776,67 +956,20 @@ try {
     nt.v = v_new;
     if (!ctx)
         return SPD_ERR_NULL;
-    if (!priv || !pub)
-        return SPD_ERR_NULL;
-    if (priv->n_users != pub->n_users)
-        return SPD_ERR_LEN;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    SPD_HIP(ctx, hipSetDevice(ctx->device));
-    // validate everything before anything is enqueued
-    int rc = spd_validate_partial(shape, q, priv, a_in, lse_in);
-    if (rc == SPD_OK)
-        rc = spd_validate_partial(shape, q, pub, a_out, lse_out);
-    if (rc == SPD_OK)
-        rc = validate_new_token(pub, nt);
-    if (rc != SPD_OK)
+    int rc = validate_decode_step(ctx, shape, q, priv, pub, nt, a_in, lse_in, a_out, lse_out, y, lse, w_in);
+    if (rc != SPD_OK || priv->n_users == 0)
         return rc;
-    if (priv->n_users == 0)
-        return SPD_OK;
-    if (!y || !lse || !w_in)
-        return SPD_ERR_NULL;
-    if (!aligned16(y))
-        return SPD_ERR_ALIGN;
     CachedSchedule *ep = nullptr, *eo = nullptr;
-    // both owners share one launch, so they share the mapping: head per wave if both layouts allow it and the two
-    // together are bandwidth-bound
-    const int hpw = head_per_wave_layout(shape, priv) && head_per_wave_layout(shape, pub) &&
-                    head_per_wave_pays(ctx, shape, total_steps(priv) + total_steps(pub));
+    const int hpw = fused_step_mapping(ctx, shape, priv, pub);
     rc = prepare_partial(ctx, 0, shape, q, priv, a_in, lse_in, hpw, stream, &ep);
     if (rc != SPD_OK)
         return rc;
     rc = prepare_partial(ctx, 1, shape, q, pub, a_out, lse_out, hpw, stream, &eo);  // an upload, if any, stays on `stream`
     if (rc != SPD_OK)
         return rc;
-    // one grid for both owners, the private owner's long streams first (measured faster than public first): the
-    // public owner's short, latency-bound pieces then run beside them on the workgroup slots that remain
-    if ((priv->block_size != 0) == (pub->block_size != 0)) {
-        rc = launch_partial(ctx, 0, ep, priv, a_in, lse_in, eo, pub, a_out, lse_out, shape, q, nt, stream);
-        if (rc != SPD_OK)
-            return rc;
-    } else {  // different storage modes need different kernel instances
-        rc = launch_partial(ctx, 1, eo, pub, a_out, lse_out, nullptr, nullptr, nullptr, nullptr, shape, q, nt, stream);
-        if (rc != SPD_OK)
-            return rc;
-        rc = launch_partial(ctx, 0, ep, priv, a_in, lse_in, nullptr, nullptr, nullptr, nullptr, shape, q, NewToken(), stream);
-        if (rc != SPD_OK)
-            return rc;
-    }
-    // join: one kernel combines whichever rows were split and merges the owners
-    const int G = shape->n_q_heads / shape->n_kv_heads;
-    const RowInfo *ri = reinterpret_cast<const RowInfo *>(ep->dev + ep->off_info);
-    const RowInfo *ro = reinterpret_cast<const RowInfo *>(eo->dev + eo->off_info);
-    const dim3 grid((unsigned)priv->n_users, (unsigned)shape->n_kv_heads, (unsigned)G);
-    const Owner &op = ctx->owner[0], &oo = ctx->owner[1];
-    if (shape->head_dim == 64)
-        hipLaunchKernelGGL((spd::finalize_step_kernel<64>), grid, dim3(64), 0, stream, ri, ro, shape->n_kv_heads,
-                           shape->n_q_heads, G, op.part_o, op.part_lse, oo.part_o, oo.part_lse, a_in, lse_in, a_out,
-                           lse_out, y, lse, w_in);
-    else
-        hipLaunchKernelGGL((spd::finalize_step_kernel<128>), grid, dim3(128), 0, stream, ri, ro,
-                           shape->n_kv_heads, shape->n_q_heads, G, op.part_o, op.part_lse, oo.part_o, oo.part_lse, a_in,
-                           lse_in, a_out, lse_out, y, lse, w_in);
-    SPD_HIP(ctx, hipGetLastError());
-    return SPD_OK;
+    return launch_decode_step(ctx, shape, q, priv, pub, nt, ep, eo, scratch_of(ctx->owner[0]), scratch_of(ctx->owner[1]), a_in,
+                              lse_in, a_out, lse_out, y, lse, w_in, stream);
 } catch (...) {  // a failed host allocation (std::vector): no C++ exception leaves the library
     return SPD_ERR_NOMEM;
 }
@@ -867,26 +1000,13 @@ try {
     rc = prepare_partial(ctx, 1, shape, q, pub, a_out, lse_out, -1, stream, &eo);
     if (rc != SPD_OK)
         return rc;
-    rc = launch_partial(ctx, 1, eo, pub, a_out, lse_out, nullptr, nullptr, nullptr, nullptr, shape, q, nt, stream);
+    rc = launch_partial(ctx, 1, eo, pub, a_out, lse_out, scratch_of(ctx->owner[1]), nullptr, nullptr, nullptr, nullptr,
+                        ScratchPtrs(), shape, q, nt, stream);
     if (rc != SPD_OK)
         return rc;
     // the closing kernel: combines the public rows that were split and merges; the private side arrives finished
-    const int G = shape->n_q_heads / shape->n_kv_heads;
-    const RowInfo *ro = reinterpret_cast<const RowInfo *>(eo->dev + eo->off_info);
-    const dim3 grid((unsigned)pub->n_users, (unsigned)shape->n_kv_heads, (unsigned)G);
-    const Owner &oo = ctx->owner[1];
-    float *a_in_rw = const_cast<float *>(a_in);  // only read: the kernel writes them for rows it combined itself
-    float *lse_in_rw = const_cast<float *>(lse_in);
-    if (shape->head_dim == 64)
-        hipLaunchKernelGGL((spd::finalize_step_kernel<64>), grid, dim3(64), 0, stream, (const RowInfo *)nullptr, ro,
-                           shape->n_kv_heads, shape->n_q_heads, G, (const float *)nullptr, (const float *)nullptr,
-                           oo.part_o, oo.part_lse, a_in_rw, lse_in_rw, a_out, lse_out, y, lse, w_in);
-    else
-        hipLaunchKernelGGL((spd::finalize_step_kernel<128>), grid, dim3(128), 0, stream, (const RowInfo *)nullptr, ro,
-                           shape->n_kv_heads, shape->n_q_heads, G, (const float *)nullptr, (const float *)nullptr,
-                           oo.part_o, oo.part_lse, a_in_rw, lse_in_rw, a_out, lse_out, y, lse, w_in);
-    SPD_HIP(ctx, hipGetLastError());
-    return SPD_OK;
+    return launch_finalize(ctx, shape, pub->n_users, nullptr, eo, ScratchPtrs(), scratch_of(ctx->owner[1]), a_in, lse_in, nullptr,
+                           nullptr, a_out, lse_out, y, lse, w_in, stream);
 } catch (...) {  // a failed host allocation (std::vector): no C++ exception leaves the library
     return SPD_ERR_NOMEM;
 }

@@ -80,6 +80,23 @@ class DecodeStep:
                                              self.lse_in.data_ptr(), self.a_out.data_ptr(), self.lse_out.data_ptr(),
                                              self.y.data_ptr(), self.lse.data_ptr(), self.w_in.data_ptr(), st))
 
+        self._two_parties = (
+            self._calls[0],
+            (lib.spd_public_attn_merge, (h, sp, q.data_ptr(), C.byref(self.public.struct),
+                                         None if k_new is None else k_new.data_ptr(),
+                                         None if v_new is None else v_new.data_ptr(), self.a_in.data_ptr(),
+                                         self.lse_in.data_ptr(), self.a_out.data_ptr(), self.lse_out.data_ptr(),
+                                         self.y.data_ptr(), self.lse.data_ptr(), self.w_in.data_ptr(), st)),
+        )
+
+    def run_prepared_two_parties(self):
+        """The users' call (private partials) and the service's call (public partial and merge), arguments prepared."""
+        for fn, args in self._two_parties:
+            rc = fn(*args)
+            if rc != 0:
+                self.ctx._check(rc, fn.__name__)
+        return self.y
+
     def run_prepared_fused(self):
         fn, args = self._fused
         rc = fn(*args)

@@ -17,13 +17,17 @@ def pytest_configure(config):
 
 
 @pytest.fixture
-def mapping_of(monkeypatch):
+def mapping_of(ctx):
     """Layout names ending in "_hpw" force the library's head-per-wave kernel mapping (it is otherwise chosen only for
-    large token-major inputs) through its SPD_HEAD_PER_WAVE override; returns the plain layout name."""
+    large token-major inputs) through the option SPD_OPT_HEAD_PER_WAVE of the test module's context `ctx`; returns the
+    plain layout name."""
+    import paper_2409_19134_amd as spd
+
     def apply(layout):
         if layout is not None and layout.endswith("_hpw"):
-            monkeypatch.setenv("SPD_HEAD_PER_WAVE", "1")
+            ctx.spd_set_option(spd.SPD_OPT_HEAD_PER_WAVE, 1)
             return layout[:-4]
-        monkeypatch.delenv("SPD_HEAD_PER_WAVE", raising=False)
+        ctx.spd_set_option(spd.SPD_OPT_HEAD_PER_WAVE, -1)
         return layout
-    return apply
+    yield apply
+    ctx.spd_set_option(spd.SPD_OPT_HEAD_PER_WAVE, -1)

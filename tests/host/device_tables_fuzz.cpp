@@ -59,8 +59,16 @@ int main()
         v.token_stride = hpw ? (int64_t)d * Hkv : d;
         v.head_stride = hpw ? d : (int64_t)d * 100000;
 
+        Tuning tune;  // the defaults, or anything a context's options allow
+        if (rnd() % 2) {
+            tune.target_wg_per_cu = 1 + (int)(rnd() % 4);
+            tune.no_split_max = 1 + (int)(rnd() % 2000);
+            tune.chunk_max = 1 + (int)(rnd() % 40000);
+            tune.seg_cost = (int)(rnd() % 9);
+            tune.half_skew = (int)(rnd() % 91);
+        }
         Schedule S;
-        build_schedule(Hkv, n_users, lens.data(), n_cus, hpw, S);
+        build_schedule(Hkv, n_users, lens.data(), n_cus, hpw, tune, S);
         DeviceTables T;
         build_device_tables(S, Hkv, es, &v, hpw, T);
 

@@ -38,11 +38,13 @@ struct View {
     }
 };
 
+static int32_t g_tuning[5] = {2, 768, 16384, 2, 12};  // the schedule-shaping options of a context
+
 static std::vector<uint8_t> key_of(const spd_shape &s, View &w, int mapping)
 {
     w.bind();
     std::vector<uint8_t> k;
-    make_key(&s, &w.v, mapping != 0, k);
+    make_key(&s, &w.v, mapping != 0, g_tuning, 5, k);
     return k;
 }
 
@@ -77,6 +79,15 @@ int main()
         b.v.head_stride += 16;
         if (key_of(s, b, 0) == ka)
             FAIL("the head stride is not part of the key");
+        // every schedule-shaping option of the context is part of the key
+        for (int opt = 0; opt < 5; ++opt) {
+            b = a;
+            g_tuning[opt] += 1;
+            const bool same = key_of(s, b, 0) == ka;
+            g_tuning[opt] -= 1;
+            if (same)
+                FAIL("option %d is not part of the key", opt);
+        }
         b = a;
         const int pick = (int)(rnd() % n);
         b.lens[(size_t)pick] += 1;

@@ -142,8 +142,14 @@ def test_calls_reject_null_context_without_touching_the_gpu():
     [131072, 5, 40000], [2304] * 16, [100000] * 64,
 ])
 @pytest.mark.parametrize("n_cus", [1, 256])
-def test_schedule_covers_every_token_once(lens, n_cus):
+@pytest.mark.parametrize("plain", [True, False])
+def test_schedule_covers_every_token_once(lens, n_cus, plain, monkeypatch):
+    """plain: equal pieces (the options that make pieces unequal on purpose switched off); else the default options."""
     Hkv = 8
+    seg_cost, skew = (0, 0) if plain else (2, 12)
+    if plain:                                            # the host-only helper reads the SPD_* variables at every call
+        monkeypatch.setenv("SPD_SEG_COST", "0")
+        monkeypatch.setenv("SPD_HALF_SKEW", "0")
     sh = spd.make_shape(spd.SPD_BF16, 32, Hkv, 128, 0.1)
     items, chunk = spd.spd_build_schedule(sh, lens, n_cus)
     assert chunk % 32 == 0
@@ -184,9 +190,28 @@ def test_schedule_covers_every_token_once(lens, n_cus):
             assert len(steps) == len(items)
             return
         sizes = [steps[i] for i in range(len(steps))]
-        assert max(sizes) * 32 <= max(chunk, 128) and max(sizes) * 32 <= 16384
-        assert max(sizes) - min(sizes) <= 1                    # equal pieces
+        assert max(sizes) * 32 <= max(chunk, 128)
         resident = max(8, 2 * n_cus // 8 * 8)
+        if plain:
+            assert max(sizes) * 32 <= 16384
+            assert max(sizes) - min(sizes) <= 1                    # equal pieces
+        else:
+            # a piece gives up seg_cost steps for every further row it reaches into (a cut that would land inside
+            # that allowance moves to the row boundary, so a piece may come out up to seg_cost steps short or long)
+            segs = {}
+            for it in items:
+                segs[it["piece"]] = segs.get(it["piece"], 0) + 1
+            cost = [steps[i] + seg_cost * (segs[i] - 1) for i in range(len(steps))]
+            halves = [cost]
+            n_groups = len(sizes) // Hkv
+            total_steps = sum(-(-L // 32) for L in lens)
+            if len(sizes) == resident and n_groups >= 2 and total_steps >= 8 * n_groups:   # one resident round: unequal halves
+                h = n_groups // 2 * Hkv
+                halves = [cost[:h], cost[h:]]
+                m0, m1 = sum(halves[0]) / len(halves[0]), sum(halves[1]) / len(halves[1])
+                assert abs(m0 / m1 - (100 + skew) / (100 - skew)) <= 0.12, (m0, m1)
+            for part in halves:
+                assert max(part) - min(part) <= 2 * seg_cost + 2, (min(part), max(part))
         if len(sizes) > resident:                              # several resident waves: a whole number of them
             assert len(sizes) % resident == 0
 

@@ -11,7 +11,7 @@ from oracle import spd_oracle as orc
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
-TOL = {torch.float32: 1e-5, torch.bfloat16: 2e-3, torch.float16: 2e-3}
+TOL = {torch.float32: 1e-5, torch.bfloat16: 2e-3, torch.float16: 1e-4}    # as in test_gpu_parity.py
 
 
 @pytest.fixture(scope="module")

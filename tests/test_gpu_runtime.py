@@ -382,16 +382,16 @@ def test_layers_captured_in_one_hip_graph(fused):
 
 @pytest.mark.parametrize("storage", ["hnd", "hnd_exact", "nhd_hpw", "paged", "paged_tm_hpw"])
 @pytest.mark.parametrize("fused", [True, False])
-def test_decode_loop_reuses_the_public_schedule_while_the_cache_grows(storage, fused, monkeypatch):
+def test_decode_loop_reuses_the_public_schedule_while_the_cache_grows(storage, fused):
     """150 decode steps, one token appended per user and step: the public schedule is rebuilt only every 65th step
     (a schedule serves lengths up to 64 tokens beyond those it was built for), rows cross 32-token steps and pages on
     the way, and every step's result is right."""
     import paper_2409_19134_amd as spd
     hpw = storage.endswith("_hpw")
-    monkeypatch.setenv("SPD_HEAD_PER_WAVE", "1" if hpw else "0")
     storage = storage[:-4] if hpw else storage
     paged = {"paged": True, "paged_tm": "token_major"}.get(storage, False)
     ctx = spd.Context(0)
+    ctx.spd_set_option(spd.SPD_OPT_HEAD_PER_WAVE, 1 if hpw else 0)
     U, Hq, Hkv, d, n_steps = 4, 16, 4, 128, 150
     lp, lo0 = [300, 33, 1500, 64], [1, 30, 700, 95]
     cap = [x + n_steps for x in lo0]
