@@ -51,7 +51,8 @@ extern "C" {
 #define SPD_ERR_LEN (-3)       /* negative count or length, a length above 2^30, or a paged length
                                   beyond max_blocks                                                   */
 #define SPD_ERR_ALIGN (-4)     /* a base pointer or stride breaks the 16-byte row alignment          */
-#define SPD_ERR_WORKSPACE (-5) /* scratch memory could not be (re)allocated                          */
+#define SPD_ERR_WORKSPACE (-5) /* scratch memory could not be (re)allocated, or the step exceeds the
+                                  fixed scratch array of spd_decode_step_static                       */
 #define SPD_ERR_HIP (-6)       /* a HIP runtime call failed; see spd_last_hip_error                  */
 #define SPD_ERR_NOMEM (-7)     /* host allocation failed                                             */
 
@@ -226,6 +227,25 @@ int spd_lse_merge_n(spd_ctx *ctx, int32_t n_parts, int32_t n_rows, int32_t head_
 int spd_decode_step(spd_ctx *ctx, const spd_shape *shape, const void *q, const spd_kv_view *priv,
                     const spd_kv_view *pub, const void *k_new, const void *v_new, float *a_in, float *lse_in,
                     float *a_out, float *lse_out, float *y, float *lse, float *w_in, void *hip_stream);
+
+/*
+ * spd_decode_step for callers that cannot allocate device memory: code that is being recorded into a HIP graph,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same results; but the split schedules, the
+ * chunk partials live in one fixed array of SPD_STATIC_SCRATCH_BYTES of device memory that
+ * belongs to the library (one copy per GPU, held until the process ends), the schedules reach it through kernel
+ * arguments, and the call makes no hipMalloc, hipFree, hipHostMalloc or copy command - it only launches kernels.
+ * A step that does not fit the array fails with SPD_ERR_WORKSPACE before anything is enqueued.  It fits if, for each
+ * owner, the schedule takes at most 512 KiB (about 10 000 work items) and the chunk partials number at most
+ * 65 536 / G and take at most ~7.2 MiB (slots * G * head_dim fp32): all five benchmark workloads do.
+ * Every call on a GPU, from any context, uses that GPU's one array and keeps the previous call's contents in it:
+ * calls that overlap in time on one GPU race (run them on one stream, or order them with events).  The call may be
+ * recorded into a HIP graph without a warm-up call; once any call has been recorded, later calls send their schedules
+ * every time (the library cannot know what replays have left in the array).  Devices 0..63.
+ */
+#define SPD_STATIC_SCRATCH_BYTES (16u << 20)
+int spd_decode_step_static(spd_ctx *ctx, const spd_shape *shape, const void *q, const spd_kv_view *priv,
+                           const spd_kv_view *pub, const void *k_new, const void *v_new, float *a_in, float *lse_in,
+                           float *a_out, float *lse_out, float *y, float *lse, float *w_in, void *hip_stream);
 
 /*
  * The service's half of a decode step in one call (section 4, step 3c): the public batched partial attention (with the

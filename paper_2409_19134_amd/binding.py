@@ -28,7 +28,7 @@ EXPORTED_SYMBOLS = (
     "spd_validate_partial", "spd_build_schedule", "spd_set_kernel_timing", "spd_get_kernel_timing",
     "spd_decode_step", "spd_partial_attn_public_batched_append", "spd_get_schedule_stats",
     "spd_attention_mass_track", "spd_get_kernel_timing_samples", "spd_lse_merge_n", "spd_public_attn_merge",
-    "spd_abi_version", "spd_set_option", "spd_get_option",
+    "spd_abi_version", "spd_decode_step_static", "spd_set_option", "spd_get_option",
     "spd_get_last_kernel_instance",
 )
 
@@ -96,6 +96,8 @@ def _load() -> C.CDLL:
     lib.spd_decode_step.restype = C.c_int
     lib.spd_decode_step.argtypes = [vp, C.POINTER(spd_shape), vp, C.POINTER(spd_kv_view), C.POINTER(spd_kv_view),
                                     vp, vp, fp, fp, fp, fp, fp, fp, fp, vp]
+    lib.spd_decode_step_static.restype = C.c_int
+    lib.spd_decode_step_static.argtypes = lib.spd_decode_step.argtypes
     lib.spd_partial_attn_public_batched_append.restype = C.c_int
     lib.spd_partial_attn_public_batched_append.argtypes = [vp, C.POINTER(spd_shape), vp, vp, vp,
                                                            C.POINTER(spd_kv_view), fp, fp, vp]
@@ -308,6 +310,25 @@ class Context:
                                  a_in.data_ptr(), lse_in.data_ptr(), a_out.data_ptr(),
                                  lse_out.data_ptr(), y.data_ptr(), lse.data_ptr(), w_in.data_ptr(), _stream_ptr(stream))
         self._check(rc, "spd_decode_step")
+        return y
+
+    def spd_decode_step_static(self, shape, q, private, public, a_in, lse_in, a_out, lse_out, y, lse, w_in, stream=None,
+                               k_new=None, v_new=None):
+        """spd_decode_step on the library's fixed scratch array (allocates nothing)."""
+        n, Hq, d = private.struct.n_users, shape.n_q_heads, shape.head_dim
+        for t in (a_in, a_out, y):
+            assert t.is_contiguous() and t.dtype == torch.float32 and tuple(t.shape) == (n, Hq, d)
+        for t in (lse_in, lse_out, lse, w_in):
+            assert t.is_contiguous() and t.dtype == torch.float32 and tuple(t.shape) == (n, Hq)
+        assert q.is_contiguous() and tuple(q.shape) == (n, Hq, d)
+        for t in (k_new, v_new):
+            assert t is None or (t.is_contiguous() and t.dtype == q.dtype and tuple(t.shape) == (n, shape.n_kv_heads, d))
+        rc = lib.spd_decode_step_static(self.handle, C.byref(shape), q.data_ptr(), C.byref(private.struct),
+                                        C.byref(public.struct), None if k_new is None else k_new.data_ptr(),
+                                        None if v_new is None else v_new.data_ptr(),
+                                        a_in.data_ptr(), lse_in.data_ptr(), a_out.data_ptr(),
+                                        lse_out.data_ptr(), y.data_ptr(), lse.data_ptr(), w_in.data_ptr(), _stream_ptr(stream))
+        self._check(rc, "spd_decode_step_static")
         return y
 
     def spd_attention_mass_track(self, w_in, threshold, mass_min=None, mass_sum=None, n_below=None, stream=None):

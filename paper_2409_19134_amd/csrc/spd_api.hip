@@ -5,7 +5,9 @@
 #include <hip/hip_ext.h>
 
 #include <algorithm>
+#include <array>
 #include <cmath>
+#include <mutex>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -650,6 +652,68 @@ int launch_decode_step(spd_ctx *ctx, const spd_shape *shape, const void *q, cons
                            w_in, stream);
 }
 
+// ---- the fixed scratch array of spd_decode_step_static ------------------------------------------------------
+// One array per GPU, resident from the moment the library's code object is loaded until the process ends.  `scratch`
+// is only a host-side handle of the symbol: host code uses the device address that hipGetSymbolAddress returned for
+// the GPU in question (static_scratch_of), never the name.
+constexpr size_t kStaticSchedBytes = 512u << 10;   // per owner: its schedule as the kernels read it
+constexpr size_t kStaticLseFloats = 64u << 10;     // per owner: chunk log-sum-exps (slots * G)
+constexpr size_t kStaticOffLse = 2 * kStaticSchedBytes;
+constexpr size_t kStaticOffPartO = kStaticOffLse + 2 * kStaticLseFloats * sizeof(float);
+constexpr size_t kStaticPartOFloats = (SPD_STATIC_SCRATCH_BYTES - kStaticOffPartO) / 2 / sizeof(float) / 64 * 64;  // per owner
+static_assert(kStaticOffPartO + 2 * kStaticPartOFloats * sizeof(float) <= SPD_STATIC_SCRATCH_BYTES, "layout exceeds the array");
+
+static __device__ __align__(256) unsigned char scratch[SPD_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+struct StaticScratch {
+    char *ptr = nullptr;          // this GPU's copy of `scratch`
+    std::vector<uint8_t> key[2];  // the view whose schedule each owner's part holds (empty: unknown)
+    bool replayed = false;        // a call has been recorded into a HIP graph: replays rewrite the array behind the
+                                  // host's back, so its contents are no longer known here
+};
+std::mutex g_static_mutex;
+std::array<StaticScratch, kMaxDevices> g_static;
+
+// Looks up this GPU's address of the array (once per device, with that device current).
+int static_scratch_init(spd_ctx *ctx)
+{
+    if (ctx->device >= kMaxDevices)
+        return SPD_OK;  // spd_decode_step_static will refuse; everything else works
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    StaticScratch &st = g_static[(size_t)ctx->device];
+    if (st.ptr)
+        return SPD_OK;
+    void *p = nullptr;
+    SPD_HIP(ctx, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    st.ptr = static_cast<char *>(p);
+    return SPD_OK;
+}
+
+// A piece of a schedule handed to the GPU inside the kernel arguments (no staging memory, no copy command).
+constexpr unsigned kUploadWords = 224;  // 16-byte words per launch (3.5 KB of the 4 KB a launch may carry)
+struct UploadChunk {
+    spd::u32x4 w[kUploadWords];
+};
+__global__ __launch_bounds__(256) void upload_args_kernel(UploadChunk c, spd::u32x4 *dst, unsigned n16)
+{
+    if (threadIdx.x < n16)
+        dst[threadIdx.x] = c.w[threadIdx.x];
+}
+
+int upload_through_args(spd_ctx *ctx, const std::vector<char> &bytes, char *dst, hipStream_t stream)
+{
+    const size_t n16 = bytes.size() / 16;  // a multiple of 16 words
+    for (size_t at = 0; at < n16; at += kUploadWords) {
+        const unsigned n = (unsigned)std::min<size_t>(kUploadWords, n16 - at);
+        UploadChunk c;
+        std::memcpy(c.w, bytes.data() + at * 16, (size_t)n * 16);
+        hipLaunchKernelGGL(upload_args_kernel, dim3(1), dim3(256), 0, stream, c, reinterpret_cast<spd::u32x4 *>(dst) + at, n);
+        SPD_HIP(ctx, hipGetLastError());
+    }
+    return SPD_OK;
+}
+
 // No C++ exception leaves the library: a failed host allocation (the schedule builder and the cache use std::vector)
 // becomes SPD_ERR_NOMEM.
 template <class F>
@@ -676,7 +740,7 @@ const char *spd_strerror(int code)
     case SPD_ERR_SHAPE: return "unsupported dtype, head counts, head_dim or block size";
     case SPD_ERR_LEN: return "negative count or length, a length above 2^30, or a paged length beyond max_blocks";
     case SPD_ERR_ALIGN: return "pointer or stride breaks the 16-byte row alignment";
-    case SPD_ERR_WORKSPACE: return "scratch memory could not be allocated or is too small";
+    case SPD_ERR_WORKSPACE: return "scratch memory could not be allocated, or the step exceeds the fixed scratch array of spd_decode_step_static";
     case SPD_ERR_HIP: return "a HIP runtime call failed";
     case SPD_ERR_NOMEM: return "host allocation failed";
     default: return "unknown error code";
@@ -711,6 +775,10 @@ int spd_create(spd_ctx **out, int hip_device)
     if (e == hipSuccess)
         e = hipDeviceGetAttribute(&ctx->n_cus, hipDeviceAttributeMultiprocessorCount, hip_device);
     if (e != hipSuccess) {
+        delete ctx;
+        return SPD_ERR_HIP;
+    }
+    if (static_scratch_init(ctx) != SPD_OK) {
         delete ctx;
         return SPD_ERR_HIP;
     }
@@ -970,6 +1038,72 @@ try {
         return rc;
     return launch_decode_step(ctx, shape, q, priv, pub, nt, ep, eo, scratch_of(ctx->owner[0]), scratch_of(ctx->owner[1]), a_in,
                               lse_in, a_out, lse_out, y, lse, w_in, stream);
+} catch (...) {  // a failed host allocation (std::vector): no C++ exception leaves the library
+    return SPD_ERR_NOMEM;
+}
+
+int spd_decode_step_static(spd_ctx *ctx, const spd_shape *shape, const void *q, const spd_kv_view *priv,
+                           const spd_kv_view *pub, const void *k_new, const void *v_new, float *a_in, float *lse_in,
+                           float *a_out, float *lse_out, float *y, float *lse, float *w_in, void *hip_stream)
+try {
+    NewToken nt;
+    nt.k = k_new;
+    nt.v = v_new;
+    if (!ctx)
+        return SPD_ERR_NULL;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    int rc = validate_decode_step(ctx, shape, q, priv, pub, nt, a_in, lse_in, a_out, lse_out, y, lse, w_in);
+    if (rc != SPD_OK || priv->n_users == 0)
+        return rc;
+    if (ctx->device >= kMaxDevices)
+        return SPD_ERR_WORKSPACE;
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    StaticScratch &st = g_static[(size_t)ctx->device];
+    if (!st.ptr)
+        return SPD_ERR_WORKSPACE;
+    const bool hpw = fused_step_mapping(ctx, shape, priv, pub);
+    const int G = shape->n_q_heads / shape->n_kv_heads;
+    // both schedules are built and checked against the array's limits before anything is enqueued
+    ScheduleBlob B[2];
+    const spd_kv_view *views[2] = {priv, pub};
+    std::vector<uint8_t> key[2];
+    for (int w = 0; w < 2; ++w) {
+        build_blob(shape, views[w], hpw, ctx->n_cus, ctx->tuning, B[w]);
+        make_key(shape, views[w], hpw, &ctx->tuning.target_wg_per_cu, kTuningInts, key[w]);
+        if (B[w].bytes.size() > kStaticSchedBytes || (size_t)B[w].n_slots * G + 4 > kStaticLseFloats ||
+            (size_t)B[w].n_slots * G * shape->head_dim + 4 > kStaticPartOFloats)
+            return SPD_ERR_WORKSPACE;
+    }
+    hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+    SPD_HIP(ctx, hipStreamIsCapturing(stream, &capture));
+    if (capture != hipStreamCaptureStatusNone)
+        st.replayed = true;
+    CachedSchedule e[2];
+    ScratchPtrs sp[2];
+    for (int w = 0; w < 2; ++w) {
+        char *dst = st.ptr + (size_t)w * kStaticSchedBytes;
+        // a schedule that the array already holds is not sent again - unless graph replays may have replaced it since
+        if (st.replayed || st.key[w] != key[w]) {
+            st.key[w].clear();
+            rc = upload_through_args(ctx, B[w].bytes, dst, stream);
+            if (rc != SPD_OK)
+                return rc;
+            if (!st.replayed)
+                st.key[w] = key[w];
+        }
+        e[w].valid = true;
+        e[w].dev = dst;
+        e[w].n_items = B[w].n_items;
+        e[w].n_slots = B[w].n_slots;
+        e[w].hpw = hpw;
+        e[w].n_split_rows = B[w].n_split_rows;
+        e[w].off_rows = B[w].off_rows;
+        e[w].off_info = B[w].off_info;
+        sp[w].part_lse = reinterpret_cast<float *>(st.ptr + kStaticOffLse) + (size_t)w * kStaticLseFloats;
+        sp[w].part_o = reinterpret_cast<float *>(st.ptr + kStaticOffPartO) + (size_t)w * kStaticPartOFloats;
+    }
+    return launch_decode_step(ctx, shape, q, priv, pub, nt, &e[0], &e[1], sp[0], sp[1], a_in, lse_in, a_out, lse_out, y, lse,
+                              w_in, stream);
 } catch (...) {  // a failed host allocation (std::vector): no C++ exception leaves the library
     return SPD_ERR_NOMEM;
 }
