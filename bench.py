@@ -86,6 +86,91 @@ def masked_stream(torch, n_cus, wanted):
     return torch.cuda.ExternalStream(handle.value)
 
 
+# ---- the users' side of --mode two_processes -------------------------------------------------------------------
+# Host handshake between the service process and the users' processes: a few 64-bit counters in shared host memory.
+FLAG_GO, FLAG_STOP, FLAG_DONE0 = 0, 1, 8      # done[i] / ready[i] of worker i at FLAG_DONE0 + 2 i, + 2 i + 1
+SPIN_LIMIT_S = 120.0                           # every wait on a counter gives up after this long
+
+
+def spin_until(flags, idx, value, also_stop=False):
+    """Waits until flags[idx] >= value (or, with also_stop, the stop flag is up); False on time-out."""
+    t0 = time.perf_counter()
+    n = 0
+    while flags[idx] < value:
+        if also_stop and flags[FLAG_STOP]:
+            return True
+        n += 1
+        if (n & 0x3fff) == 0 and time.perf_counter() - t0 > SPIN_LIMIT_S:
+            return False
+    return True
+
+
+def worker_main(args):
+    """One users' process (section 4, step 3b): holds the private caches of its share of the users, maps the service's
+    q / A_in / lse_in buffers, and answers every step with spd_partial_attn_private written in place."""
+    import json as js
+    import numpy as np
+    import torch
+    import paper_2409_19134_amd as spd
+    import workloads
+    from paper_2409_19134_amd import ipc
+
+    idx, n_workers = (int(x) for x in args.worker.split("/"))
+    flags = np.memmap(args.shm, dtype=np.int64, mode="r+", shape=(64,))     # the service's counters (a file in /dev/shm)
+    dev = "cuda:0"
+    shape = tuple(int(x) for x in args.shape.split(",")) if args.shape else None
+    dtype = {None: None, "bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}[args.dtype]
+    len_ranges = tuple(int(x) for x in args.lens.split(",")) if args.lens else None
+    wl = workloads.make_workload(args.config, dev, layout=args.layout, shape=shape, dtype=dtype, n_users=args.users,
+                                 page_tokens=args.page_tokens, len_ranges=len_ranges)
+    wl.public = None                               # the service's, not ours
+    msg = js.loads(sys.stdin.readline())           # what the service shares
+    copies = int(msg["copies"])
+    U = wl.n_users
+    u0, u1 = U * idx // n_workers, U * (idx + 1) // n_workers
+    sides = [wl.private] + [clone_side(wl.private) for _ in range(copies - 1)]
+
+    def view_of(side):
+        if side.paged:
+            return spd.KVView(side.lens[u0:u1], side.token_stride, side.head_stride, k_pool=side.k_pool, v_pool=side.v_pool,
+                              block_table=side.block_table[u0:u1], block_size=side.page_tokens,
+                              block_stride=side.block_stride)
+        return spd.KVView(side.lens[u0:u1], side.token_stride, side.head_stride, k=side.k[u0:u1], v=side.v[u0:u1],
+                          head_strides=None if side.head_strides is None else side.head_strides[u0:u1])
+    views = [view_of(s) for s in sides]
+    sh = spd.make_shape(wl.dtype, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.scale)
+    q = ipc.MappedBuffer(bytes.fromhex(msg["q"]), (U, wl.n_q_heads, wl.head_dim), wl.dtype, dev)
+    a_in = ipc.MappedBuffer(bytes.fromhex(msg["a_in"]), (U, wl.n_q_heads, wl.head_dim), torch.float32, dev)
+    lse_in = ipc.MappedBuffer(bytes.fromhex(msg["lse_in"]), (U, wl.n_q_heads), torch.float32, dev)
+    use_events = msg["sync"] == "events"
+    ev_q = ipc.SharedEvent(bytes.fromhex(msg["ev_q"])) if use_events else None
+    ev_done = ipc.SharedEvent() if use_events else None
+    ctx = spd.Context(0)
+    stream = torch.cuda.current_stream()
+    qs, As, Ls = q.tensor[u0:u1], a_in.tensor[u0:u1], lse_in.tensor[u0:u1]
+    scratch_a, scratch_l = torch.empty_like(As), torch.empty_like(Ls)
+    for v in views:                                # every view's schedule is built before the first timed step
+        ctx.spd_partial_attn_private(sh, qs, v, scratch_a, scratch_l, stream)
+    torch.cuda.synchronize()
+    print(js.dumps({"ev_done": ev_done.handle.hex() if use_events else None, "users": [u0, u1]}), flush=True)
+    k = 1
+    while True:
+        if not spin_until(flags, FLAG_GO, k, also_stop=True) or flags[FLAG_STOP]:
+            break
+        if u1 > u0:
+            if use_events:
+                ev_q.wait(stream)                  # the service's previous merge has read A_in; q is in place
+            ctx.spd_partial_attn_private(sh, qs, views[(k - 1) % copies], As, Ls, stream)
+            if use_events:
+                ev_done.record(stream)
+            else:
+                stream.synchronize()
+        flags[FLAG_DONE0 + 2 * idx] = k            # enqueued (events) or finished (host)
+        k += 1
+    torch.cuda.synchronize()
+    ctx.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -93,7 +178,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (2 = Llama-3-8B shape, 16 users: the headline)")
     ap.add_argument("--copies", type=int, default=0, help="KV set copies cycled through (0 = enough for > 1 GB, at most 8)")
-    ap.add_argument("--mode", default="fused", choices=["fused", "calls", "calls_public_first", "streams", "two_parties", "per_user_streams"],
+    ap.add_argument("--mode", default="fused", choices=["fused", "calls", "calls_public_first", "streams", "two_parties", "per_user_streams",
+                                                        "two_processes"],
                     help="fused: spd_decode_step (both owners' pieces in one launch, one closing kernel); "
                          "calls: the three entry points in sequence on one stream (private, public, merge); "
                          "calls_public_first: the same with the public call first; "
@@ -101,7 +187,20 @@ def main():
                          "(these three are the orderings of the paper's overlap study, section 5); "
                          "two_parties: the users' call (private partials) and the service's call (public partial + merge); "
                          "per_user_streams: as two_parties, but every user's private call is made on its own (one user, "
-                         "own context, own stream, as the paper's per-user processes would), joined before the service's call")
+                         "own context, own stream, as the paper's per-user processes would), joined before the service's call; "
+                         "two_processes: the paper's deployment on one GPU - the private partials are computed by "
+                         "--user-procs other processes that hold the private caches and write (A_in, lse_in) into "
+                         "buffers of this (the service's) process through HIP IPC memory handles; this process runs "
+                         "the public partial beside them and merges")
+    ap.add_argument("--user-procs", type=int, default=1, metavar="N",
+                    help="two_processes mode: users' processes (each takes an equal share of the users; at most 8)")
+    ap.add_argument("--ipc-sync", default="host", choices=["host", "events"],
+                    help="two_processes mode: how the two sides' streams are ordered - host synchronisation of each "
+                         "side's stream before the other side goes on (default), or IPC events recorded and waited for "
+                         "on the GPU, the host only saying when they have been enqueued (the HIP runtime of this image "
+                         "hands out IPC event handles but refuses to record such an event, so this form fails here)")
+    ap.add_argument("--worker", default=None, help=argparse.SUPPRESS)     # i/N: this process is users' process i of N
+    ap.add_argument("--shm", default=None, help=argparse.SUPPRESS)
     ap.add_argument("--public-cus", type=int, default=0, metavar="N",
                     help="streams mode only: give the public call's stream N compute units and the private call's "
                          "stream the others (HIP compute-unit masks; 0 = both streams may use every unit)")
@@ -145,6 +244,29 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+    if args.worker:
+        return worker_main(args)
+
+    two_proc = None
+    if args.mode == "two_processes":
+        # the users' processes are started before this process touches the GPU; each initialises the GPU itself
+        import subprocess
+        import tempfile
+        assert 1 <= args.user_procs <= 8 and not (args.graph or args.append or args.decode_loop or args.public_cus), \
+            "two_processes wants 1..8 users' processes and none of --graph / --append / --decode-loop / --public-cus"
+        shm_dir = "/dev/shm" if os.path.isdir("/dev/shm") else None
+        fd, shm_path = tempfile.mkstemp(prefix="spd_bench_", dir=shm_dir)
+        os.write(fd, bytes(64 * 8))
+        os.close(fd)
+        passed = ["--config", str(args.config), "--page-tokens", str(args.page_tokens)]
+        for flag, val in (("--layout", args.layout), ("--shape", args.shape), ("--dtype", args.dtype),
+                          ("--users", args.users), ("--lens", args.lens)):
+            if val is not None:
+                passed += [flag, str(val)]
+        procs = [subprocess.Popen([sys.executable, os.path.abspath(__file__), "--worker", f"{i}/{args.user_procs}",
+                                   "--shm", shm_path, *passed], stdin=subprocess.PIPE, stdout=subprocess.PIPE, text=True)
+                 for i in range(args.user_procs)]
+        two_proc = {"shm_path": shm_path, "procs": procs}
 
     import numpy as np
     import torch
@@ -181,6 +303,35 @@ def main():
         steps_objs.append(spd.DecodeStep.from_workload(ctx, w, device_pointer_tables=args.pointer_tables))
         steps_objs[-1].workload = w
     q = wl.q
+
+    if two_proc is not None:
+        # q, A_in and lse_in live in allocations of their own that the users' processes map; every KV copy's step
+        # writes the same A_in / lse_in (steps run one after the other)
+        from paper_2409_19134_amd import ipc
+        U, Hq, D = wl.n_users, wl.n_q_heads, wl.head_dim
+        sq = ipc.SharedBuffer((U, Hq, D), wl.dtype, dev)
+        sa = ipc.SharedBuffer((U, Hq, D), torch.float32, dev)
+        sl = ipc.SharedBuffer((U, Hq), torch.float32, dev)
+        sq.tensor.copy_(wl.q)
+        q = sq.tensor
+        for so in steps_objs:
+            so.a_in, so.lse_in = sa.tensor, sl.tensor
+        use_events = args.ipc_sync == "events"
+        ev_q = ipc.SharedEvent() if use_events else None
+        torch.cuda.synchronize()
+        flags = np.memmap(two_proc["shm_path"], dtype=np.int64, mode="r+", shape=(64,))
+        hello = json.dumps({"q": sq.handle.hex(), "a_in": sa.handle.hex(), "lse_in": sl.handle.hex(), "copies": copies,
+                            "sync": args.ipc_sync, "ev_q": ev_q.handle.hex() if use_events else None})
+        ev_done = []
+        for p in two_proc["procs"]:
+            p.stdin.write(hello + "\n")
+            p.stdin.flush()
+        for p in two_proc["procs"]:
+            line = p.stdout.readline()
+            assert line, "a users' process ended before it was ready"
+            reply = json.loads(line)
+            ev_done.append(ipc.SharedEvent(bytes.fromhex(reply["ev_done"])) if use_events else None)
+        two_proc.update(flags=flags, ev_q=ev_q, ev_done=ev_done, step=0, bufs=(sq, sa, sl))
 
     stream_ptr = torch.cuda.current_stream().cuda_stream
     k_new = v_new = None
@@ -256,8 +407,31 @@ def main():
         so.ctx.spd_public_attn_merge(so.shape, q, so.public, so.a_in, so.lse_in, so.a_out, so.lse_out, so.y, so.lse,
                                      so.w_in, main)
 
+    def run_two_processes(so):
+        """One step with the users' processes: they are told to enqueue their private calls, this process runs the
+        public partial beside them, waits (on the GPU) for their partials and merges (section 4, step 3b / 3c)."""
+        main = torch.cuda.current_stream()
+        tp = two_proc
+        tp["step"] += 1
+        k = tp["step"]
+        if tp["ev_q"] is not None:
+            tp["ev_q"].record(main)        # behind the previous step's merge, which reads A_in
+        else:
+            main.synchronize()
+        tp["flags"][FLAG_GO] = k
+        so.ctx.spd_partial_attn_public_batched(so.shape, q, so.public, so.a_out, so.lse_out, main)
+        for i, ev in enumerate(tp["ev_done"]):
+            if not spin_until(tp["flags"], FLAG_DONE0 + 2 * i, k):
+                raise RuntimeError(f"users' process {i} did not answer step {k}")
+            if ev is not None:
+                ev.wait(main)
+        so.ctx.spd_lse_merge(so.a_in, so.lse_in, so.a_out, so.lse_out, so.y, so.lse, so.w_in, main)
+
     def run(n, start=0):
         for i in range(n):
+            if two_proc is not None:
+                run_two_processes(steps_objs[(start + i) % copies])
+                continue
             if per_user is not None:
                 run_per_user(steps_objs[(start + i) % copies], per_user[(start + i) % copies])
                 continue
@@ -386,11 +560,15 @@ def main():
         return (len(a), float(a.mean()), float(a.min()), [float(np.percentile(a, p)) for p in (10, 50, 90)]) if len(a) \
             else (0, 0.0, 0.0, [0.0, 0.0, 0.0])
     n_priv, priv_mean_us, priv_min_us, priv_pct = stats(ctx.spd_get_kernel_timing_samples(0))
-    n_pub, pub_mean_us, pub_min_us, _ = stats(ctx.spd_get_kernel_timing_samples(1))
+    pub_samples = ctx.spd_get_kernel_timing_samples(1)
+    n_pub, pub_mean_us, pub_min_us, _ = stats(pub_samples)
     ctx.spd_set_kernel_timing(0)
     ms_per_step_timed = (t3 - t2) * 1e3 / K
     # fused mode: one launch streams both owners' caches; calls mode: the private call's kernel is the dominant one
     launch_bytes = kv_bytes if fused else priv_bytes
+    if two_proc is not None:    # the private kernel runs in the users' processes: this process can time its own only
+        n_priv, priv_mean_us, priv_min_us, priv_pct = stats(pub_samples)
+        launch_bytes = pub_bytes
     achieved = launch_bytes / (priv_mean_us * 1e-6) / 1e9 if n_priv else 0.0
 
     out = {
@@ -416,7 +594,9 @@ def main():
                    "device_pointer_tables": bool(args.pointer_tables and not wl.private.paged),
                    "seeds": wl.seeds},
         "roofline": {"bound": "hbm",
-                     "kernel": kernel_name + (" (both owners, spd_decode_step)" if fused else " (private call)"),
+                     "kernel": kernel_name + (" (both owners, spd_decode_step)" if fused else
+                                              " (public call; the private kernel runs in the users' processes)"
+                                              if two_proc is not None else " (private call)"),
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": None, "traffic_source": None,
@@ -476,6 +656,18 @@ def main():
             out["parity"] = {"max_abs_err_vs_fp64_oracle": err, "tolerance": tol, "ok": bool(err <= tol),
                              "rows_checked": "all" if rows is None else len(rows)}
             parity_failed = not err <= tol
+    if two_proc is not None:
+        out["config"]["user_processes"] = args.user_procs
+        out["config"]["ipc_sync"] = args.ipc_sync
+        torch.cuda.synchronize()
+        two_proc["flags"][FLAG_STOP] = 1
+        for p in two_proc["procs"]:
+            try:
+                p.wait(timeout=60)
+            except Exception:
+                p.kill()
+        del two_proc["flags"]
+        os.unlink(two_proc["shm_path"])
     print(json.dumps(out))
     ctx.close()
     if parity_failed:

@@ -12,7 +12,7 @@ namespace spd::host {
 
 constexpr int kChunkAlign = 32;      // chunk boundaries are multiples of the MFMA kernel's 32-token step
 constexpr int kChunkMin = 128;       // one 32-token step for each of the four waves
-constexpr int kSegCostMaxPiece = 64;  // 32-token steps per piece up to which Tuning::seg_cost applies
+constexpr int kShortPieceSteps = 64;  // 32-token steps per piece up to which Tuning::seg_cost and half_skew apply
 constexpr int kHeadPerWaveMinHeadSteps = 80;  // (32-token steps * KV heads) per CU from which the head-per-wave mapping is used
 
 // What shapes a schedule besides the lengths.  A context starts from the defaults below, replaced by SPD_* variables
@@ -148,8 +148,9 @@ inline void build_schedule(int Hkv, int n_users, const int32_t *lens, int n_cus,
             // (measured on the headline workload: fewer, round-aligned pieces or more pieces than fit at once are
             // both slower - 55 groups of 20 steps +2 us, 80 groups +1.5 us against 64 groups of 17-18 steps)
             const int64_t W = std::min<int64_t>(wg, hpw ? T : (T + spd::kWaves - 1) / spd::kWaves);
-            // exactly one resident round of head-major pieces with several steps per wave: unequal halves (see Tuning)
-            const int64_t skew = (!hpw && W == wg && W >= 2 && T >= 8 * W) ? tune.half_skew : 0;
+            // exactly one resident round of head-major pieces of 8 to kShortPieceSteps steps: unequal halves (see Tuning;
+            // the ~4 us by which the second half trails do not matter to longer pieces: workload 4, 214 steps, +0.2 %)
+            const int64_t skew = (!hpw && W == wg && W >= 2 && T >= 8 * W && T <= kShortPieceSteps * W) ? tune.half_skew : 0;
             for (int64_t i = 0; i < W; ++i) {
                 const int64_t h = W / 2;
                 // cumulative weight up to group i (inclusive), in percent-groups
@@ -173,10 +174,10 @@ inline void build_schedule(int Hkv, int n_users, const int32_t *lens, int n_cus,
         // trip before the new row's first tile): such pieces get `seg_cost` steps fewer.  The cuts are made on a line
         // that holds seg_cost extra steps in front of every user but the first; a cut that lands in such a gap moves
         // to the user's boundary.
-        // Only for pieces of up to kSegCostMaxPiece steps: measured, 2 steps take 1.4 % off the headline workload's step
+        // Only for pieces of up to kShortPieceSteps steps: measured, 2 steps take 1.4 % off the headline workload's step
         // (pieces of 17 steps) and 3 % off 256 users with 64-512-token rows (36 steps), but add 0.9 % to workload 4
         // (pieces of 214 steps over four rows each), where the unequal lengths cost more than the segments.
-        const int64_t seg_cost = T <= kSegCostMaxPiece * (int64_t)ends.size() ? tune.seg_cost : 0;
+        const int64_t seg_cost = T <= kShortPieceSteps * (int64_t)ends.size() ? tune.seg_cost : 0;
         if (seg_cost > 0) {
             int64_t n_rows_with_tokens = 0;
             for (int u = 0; u < n_users; ++u)

@@ -201,11 +201,13 @@ def test_schedule_covers_every_token_once(lens, n_cus, plain, monkeypatch):
             segs = {}
             for it in items:
                 segs[it["piece"]] = segs.get(it["piece"], 0) + 1
-            cost = [steps[i] + seg_cost * (segs[i] - 1) for i in range(len(steps))]
-            halves = [cost]
             n_groups = len(sizes) // Hkv
             total_steps = sum(-(-L // 32) for L in lens)
-            if len(sizes) == resident and n_groups >= 2 and total_steps >= 8 * n_groups:   # one resident round: unequal halves
+            if total_steps > 64 * n_groups:                        # long pieces stay equal
+                seg_cost = 0
+            cost = [steps[i] + seg_cost * (segs[i] - 1) for i in range(len(steps))]
+            halves = [cost]
+            if len(sizes) == resident and n_groups >= 2 and 8 * n_groups <= total_steps <= 64 * n_groups:   # one resident round of short pieces: unequal halves
                 h = n_groups // 2 * Hkv
                 halves = [cost[:h], cost[h:]]
                 m0, m1 = sum(halves[0]) / len(halves[0]), sum(halves[1]) / len(halves[1])

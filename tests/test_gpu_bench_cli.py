@@ -31,6 +31,8 @@ def run_bench(*args):
     ["--graph", "--copies", "4"],
     ["--decode-loop", "8"],
     ["--mode", "per_user_streams", "--graph", "--copies", "2"],
+    ["--mode", "two_processes", "--user-procs", "2"],
+    ["--mode", "two_processes", "--user-procs", "1"],
 ], ids=lambda e: "_".join(x.strip("-") for x in e) or "fused")
 def test_bench_modes_on_a_small_workload(extra):
     d = run_bench(*SMALL, *extra)
