@@ -241,12 +241,48 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy, so that a rocprofv3 --pmc run has a dispatch of known "
                          "traffic to scale FETCH_SIZE / WRITE_SIZE by")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="default workload only: skip the short runs of workloads 1, 3, 4 and 5 whose figures the JSON "
+                         "line carries under \"other_workloads\"")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
     if args.worker:
         return worker_main(args)
 
+    out, parity_failed = run_once(args)
+    plain_default = (args.config == 2 and args.mode == "fused" and not any(
+        (args.graph, args.append, args.decode_loop, args.public_cus, args.layout, args.shape, args.dtype, args.users,
+         args.lens, args.pointer_tables, args.copies)) and args.page_tokens == 16)
+    if plain_default and not args.no_other_workloads and not parity_failed:
+        # The other benchmark workloads, after the timed region of the headline one and in the same process: fewer
+        # steps (their steps are 15 to 55 times longer), the same fused step, the same clocks, the same parity check
+        # (one query head of every (user, KV head) stream against the oracle).  Not part of `value`.
+        import copy
+        others = []
+        for cfg in (1, 3, 4, 5):
+            a = copy.copy(args)
+            a.config = cfg
+            a.steps = max(10, min(args.steps, 100 if cfg != 1 else 1000))
+            a.warmup = max(2, min(args.warmup, 10))
+            a.no_sub_records = True
+            o, failed = run_once(a)
+            parity_failed = parity_failed or failed
+            r = o["roofline"]
+            others.append({"workload": o["config"]["workload"], "layout": o["config"]["layout"], "dtype": o["dtype"],
+                           "kv_bytes_per_step": o["config"]["kv_bytes_per_step"], "steps": o["steps"],
+                           "us_per_step": o["us_per_step"], "us_per_step_median": o["us_per_step_distribution"]["median"],
+                           "GBps": o["value"], "pct_of_hbm_peak": o["pct_of_hbm_peak"],
+                           "kernel": r["kernel"], "kernel_mean_us": r["mean_us"], "roofline_frac": r["frac"],
+                           "traffic": r["traffic"], "parity": o.get("parity")})
+        out["other_workloads"] = others
+    print(json.dumps(out))
+    if parity_failed:
+        sys.exit("bench.py: the GPU result is beyond the tolerance against the fp64 oracle (see \"parity\")")
+
+
+def run_once(args):
+    """One measurement as the arguments describe it: returns the JSON record and whether its parity check failed."""
     two_proc = None
     if args.mode == "two_processes":
         # the users' processes are started before this process touches the GPU; each initialises the GPU itself
@@ -668,10 +704,8 @@ def main():
                 p.kill()
         del two_proc["flags"]
         os.unlink(two_proc["shm_path"])
-    print(json.dumps(out))
     ctx.close()
-    if parity_failed:
-        sys.exit("bench.py: the GPU result is beyond the tolerance against the fp64 oracle (see \"parity\")")
+    return out, parity_failed
 
 
 if __name__ == "__main__":

@@ -132,7 +132,7 @@ int spd_last_hip_error(const spd_ctx *ctx);
  */
 enum {
     SPD_OPT_HEAD_PER_WAVE = 0,    /* -1 (default): head-per-wave mapping for large token-major views; 0 never; 1 whenever
-                                     the layout allows it                                                          */
+                                     the layout allows it; 2..8 the same, with at most that many KV heads per workgroup */
     SPD_OPT_TARGET_WG_PER_CU = 1, /* pieces per compute unit that count as one resident round (default 2)              */
     SPD_OPT_NO_SPLIT_MAX = 2,     /* rows up to this many tokens are cut into one-step-per-wave chunks if all of them
                                      fit the device at once (default 768)                                          */
@@ -319,8 +319,9 @@ typedef struct spd_work_item {
  * items may be NULL to query the count.  On return *n_items is the number of segments (written only if it fits
  * `capacity`, else SPD_ERR_WORKSPACE) and *chunk_tokens the tokens per piece (rounded up to 32).
  * head_per_wave != 0 asks for the schedule of the token-major kernel mapping: a segment then stands for a group of
- * w consecutive KV heads starting at `kv_head` (w = the largest divisor of n_kv_heads that is <= 8; one wave each),
- * and head kv_head + j writes partial `slot + j * n_chunks`.
+ * w consecutive KV heads starting at `kv_head` (one wave each), and head kv_head + j writes partial
+ * `slot + j * n_chunks`; w = the largest divisor of n_kv_heads that is <= 8 (head_per_wave = 1) or <= head_per_wave
+ * (2..8; other values are refused with SPD_ERR_SHAPE).
  */
 int spd_build_schedule(const spd_shape *shape, int32_t n_users, const int32_t *lens, int32_t n_compute_units,
                        int32_t head_per_wave, spd_work_item *items, int64_t capacity, int64_t *n_items,

@@ -281,8 +281,8 @@ __host__ __device__ constexpr int mfma_waves_per_simd(int RB, bool prefetch, boo
 // owner's pieces are one resident round, and it leaves room on every CU for the other owner's pieces.
 //
 // HPW ("head per wave") is the mapping for contiguous token-major storage, where the KV heads of a token are adjacent
-// in memory ([token][head][d]).  A piece is then a token range of a *user* for a group of up to eight KV heads (all
-// of them if Hkv <= 8), the workgroup has one wave per KV head of the group, and all waves walk the same tokens:
+// in memory ([token][head][d]).  A piece is then a token range of a *user* for a group of two to eight KV heads (the
+// host picks the group size by the size of the launch), the workgroup has one wave per KV head of the group, and all waves walk the same tokens:
 // together they read whole, consecutive DRAM pages, where one workgroup per head would touch every page eight times
 // at different moments (a barrier per step keeps the waves together).  Each wave owns its head's result, so there is no cross-wave combine; the wave stores its
 // result through an LDS tile of its own.  Without HPW (head-major storage: one contiguous stream per head) a piece is

@@ -13,7 +13,10 @@ namespace spd::host {
 constexpr int kChunkAlign = 32;      // chunk boundaries are multiples of the MFMA kernel's 32-token step
 constexpr int kChunkMin = 128;       // one 32-token step for each of the four waves
 constexpr int kShortPieceSteps = 64;  // 32-token steps per piece up to which Tuning::seg_cost and half_skew apply
-constexpr int kHeadPerWaveMinHeadSteps = 80;  // (32-token steps * KV heads) per CU from which the head-per-wave mapping is used
+// (32-token steps * KV heads) per CU from which the head-per-wave mapping is used, and from which its workgroups take
+// eight heads instead of four (see head_per_wave_choice in spd_api.hip)
+constexpr int kHeadPerWaveMinHeadSteps = 65;
+constexpr int kHeadPerWaveWideHeadSteps = 900;
 
 // What shapes a schedule besides the lengths.  A context starts from the defaults below, replaced by SPD_* variables
 // of the environment that spd_create finds set (tuning_from_env), and spd_set_option changes them per context; all
@@ -84,19 +87,21 @@ struct Schedule {
 // those of the group's first head) and one resident workgroup per CU.  The same
 // token limit per piece serves both mappings (smaller pieces measured slower here too), although every wave now
 // walks the whole range instead of a quarter of it.
-// Waves (KV heads) per workgroup of the head-per-wave mapping: the largest divisor of Hkv that is at most 8 (two waves
-// per SIMD is what the kernel's registers allow); Hkv / that many head groups share a token range.
-inline int head_per_wave_waves(int Hkv)
+// Waves (KV heads) per workgroup of the head-per-wave mapping: the largest divisor of Hkv that is at most `most`
+// (8: two waves per SIMD is what the kernel's registers allow); Hkv / that many head groups share a token range.
+inline int head_per_wave_waves(int Hkv, int most = 8)
 {
-    for (int w = std::min(Hkv, 8); w >= 1; --w)
+    for (int w = std::min(Hkv, std::min(most, 8)); w >= 1; --w)
         if (Hkv % w == 0)
             return w;
     return 1;
 }
 
-inline void build_schedule(int Hkv, int n_users, const int32_t *lens, int n_cus, bool hpw, const Tuning &tune, Schedule &S)
+// hpw: 0 for the head-major mapping, else the KV heads (waves) per workgroup of the head-per-wave mapping, a divisor
+// of Hkv that is at most 8.
+inline void build_schedule(int Hkv, int n_users, const int32_t *lens, int n_cus, int hpw, const Tuning &tune, Schedule &S)
 {
-    const int hpw_waves = hpw ? head_per_wave_waves(Hkv) : 1;
+    const int hpw_waves = hpw ? hpw : 1;
     const int hpw_groups = hpw ? Hkv / hpw_waves : 1;
     S.items.clear();
     S.piece_first.assign(1, 0);
@@ -275,14 +280,14 @@ struct DeviceTables {
 
 // es: bytes per K/V element.  Row addresses come from the view's host pointer arrays (contiguous mode without device
 // pointer tables); in the other modes the items hold offsets and the kernel adds the pool or the user's pointer.
-inline void build_device_tables(const Schedule &S, int Hkv, int es, const spd_kv_view *v, bool hpw, DeviceTables &T)
+inline void build_device_tables(const Schedule &S, int Hkv, int es, const spd_kv_view *v, int hpw, DeviceTables &T)
 {
     using spd::CombineRow;
     using spd::DevItem;
     using spd::RowInfo;
     // device items: the first segment of every piece (index = workgroup id), then one per row without tokens (it only
     // writes A = 0, lse = -inf), then the continuation segments, linked through `next`
-    const int hpw_waves = hpw ? head_per_wave_waves(Hkv) : 1;  // heads an item stands for
+    const int hpw_waves = hpw ? hpw : 1;  // heads an item stands for
     const int64_t n_pieces = (int64_t)S.piece_first.size() - 1;
     int64_t n_empty_rows = 0;  // workgroups that only write A = 0, lse = -inf (head-per-wave: one per empty user)
     for (int u = 0; u < v->n_users; ++u)

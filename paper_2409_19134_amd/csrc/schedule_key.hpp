@@ -60,7 +60,7 @@ inline int32_t uniform_growth(const std::vector<uint8_t> &old_key, const std::ve
 }
 
 // tuning: the kTuningInts integers of the context's Tuning (they shape the schedule like the lengths do).
-inline void make_key(const spd_shape *s, const spd_kv_view *v, bool hpw, const int32_t *tuning, int n_tuning,
+inline void make_key(const spd_shape *s, const spd_kv_view *v, int hpw, const int32_t *tuning, int n_tuning,
                      std::vector<uint8_t> &key)
 {
     key.clear();
@@ -69,7 +69,7 @@ inline void make_key(const spd_shape *s, const spd_kv_view *v, bool hpw, const i
         key.insert(key.end(), b, b + n);
     };
     const int32_t head[6] = {s->dtype, s->n_q_heads, s->n_kv_heads, v->n_users, v->block_size,
-                             hpw ? 1 : 0};
+                             hpw};
     static_assert(sizeof head == kKeyLensOffset, "the lengths follow the head");
     put(head, sizeof head);
     put(v->lens, sizeof(int32_t) * (size_t)v->n_users);

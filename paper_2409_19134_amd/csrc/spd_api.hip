@@ -45,7 +45,7 @@ struct CachedSchedule {
     int32_t grow = 0;            // set by every lookup: tokens each row has gained over the lengths in `key`
     std::vector<uint8_t> key;
     int64_t n_items = 0, n_slots = 0;
-    bool hpw = false;        // pieces are for the head-per-wave kernel
+    int hpw = 0;             // 0, or the KV heads per workgroup of the head-per-wave kernel the pieces are for
     int n_split_rows = 0;    // rows with several chunks: CombineRow[n_split_rows] follows the items
     size_t off_rows = 0, off_info = 0;
     char *dev = nullptr;     // DevItem[n_items] | CombineRow[n_split_rows] | RowInfo[n_users * Hkv]
@@ -84,7 +84,7 @@ struct spd_ctx {
     bool timing = false;
     int32_t last_instance[6] = {-1, -1, -1, -1, -1, -1};  // template arguments of the partial kernel launched last
     Tuning tuning;           // what shapes the split schedules (SPD_OPT_*)
-    int head_per_wave = -1;  // SPD_OPT_HEAD_PER_WAVE: 0 never, 1 whenever the layout allows, -1 by the size rule
+    int head_per_wave = -1;  // SPD_OPT_HEAD_PER_WAVE: 0 never, 1 whenever the layout allows, 2..8 the same with that many heads per workgroup, -1 by the size rule
     std::vector<uint8_t> key_scratch;
     Owner owner[2];
 };
@@ -128,17 +128,32 @@ int64_t total_steps(const spd_kv_view *v)
     return T;
 }
 
-// The mapping pays once the launch is bandwidth-bound, i.e. every one-per-CU workgroup gets several 32-token steps;
-// below that the four interleaving waves of the head-major mapping finish a short piece sooner.  Measured crossover
-// (256 CUs): ~2300 steps with 8 KV heads, between 600 and 1200 with 32, above 1200 with 16: about 330 MB of K/V in
-// each case, so the bound is on steps * KV heads.
-// The option SPD_OPT_HEAD_PER_WAVE (0 / 1) overrides the rule (never / whenever the layout allows): for tests and
-// measurements.
-bool head_per_wave_pays(const spd_ctx *ctx, const spd_shape *s, int64_t steps)
+// KV heads (waves) per workgroup of the head-per-wave mapping for a launch of `steps` 32-token steps per KV head, or 0
+// for the head-major mapping.  The mapping pays once the launch is bandwidth-bound, i.e. every workgroup gets several
+// steps; below that the four interleaving waves of the head-major mapping finish a short piece sooner.  Workgroups of
+// four heads (two or three per CU, 1 KB of every token) take over from ~280 MB of K/V; workgroups of eight (one per
+// CU, a token's whole 2 KB with eight KV heads) are ahead from a few GB of long rows (workload 3: 1.2 %), and for more
+// than eight KV heads.  Measured (256 CUs, 8 KV heads, token-major, us per fused step; head-major / four / eight):
+// workload 2's lengths with 16 users 35.5 / 40.2 / 48.1, 24 users 46.8 / 50.0 / -, 32 users 63.2 / 59.5 / 66.5,
+// 64 users 115.7 / 102.5 / 110.0; workload 4 - / 445.5 / 452.9; workload 3 - / 783 / 774.  The bounds are on
+// steps * KV heads per CU, which is what fixed the earlier crossovers for 16 and 32 KV heads (~330 MB each).
+// The option SPD_OPT_HEAD_PER_WAVE overrides the rule: 0 never, 1 whenever the layout allows (group size by the rule),
+// 2..8 that many heads per workgroup (the largest divisor of the KV head count up to it): for tests and measurements.
+int head_per_wave_choice(const spd_ctx *ctx, const spd_shape *s, int64_t steps)
 {
-    if (ctx->head_per_wave == 0 || ctx->head_per_wave == 1)
-        return ctx->head_per_wave == 1;
-    return steps * std::max(8, s->n_kv_heads) >= (int64_t)std::max(1, ctx->n_cus) * kHeadPerWaveMinHeadSteps;
+    const int opt = ctx->head_per_wave;
+    if (opt == 0)
+        return 0;
+    const int64_t head_steps = steps * std::max(8, s->n_kv_heads) / std::max(1, ctx->n_cus);
+    if (opt < 0 && head_steps < kHeadPerWaveMinHeadSteps)
+        return 0;
+    int most = 8;
+    if (opt >= 2)
+        most = opt;
+    else if (head_steps < kHeadPerWaveWideHeadSteps && s->n_kv_heads <= 8)
+        most = 4;
+    const int w = head_per_wave_waves(s->n_kv_heads, most);
+    return w >= 2 ? w : 0;
 }
 
 // A schedule as the kernels read it, laid out for device memory:
@@ -151,7 +166,7 @@ struct ScheduleBlob {
     int n_split_rows = 0;
 };
 
-void build_blob(const spd_shape *s, const spd_kv_view *v, bool hpw, int n_cus, const Tuning &tune, ScheduleBlob &B)
+void build_blob(const spd_shape *s, const spd_kv_view *v, int hpw, int n_cus, const Tuning &tune, ScheduleBlob &B)
 {
     Schedule S;
     build_schedule(s->n_kv_heads, v->n_users, v->lens, n_cus, hpw, tune, S);
@@ -176,7 +191,7 @@ void build_blob(const spd_shape *s, const spd_kv_view *v, bool hpw, int n_cus, c
 
 // Find or build the device-resident schedule for this view (hpw: pieces for the head-per-wave kernel).  Uploads are
 // enqueued on `stream`.
-int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view *v, bool hpw,
+int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view *v, int hpw,
                  hipStream_t stream, CachedSchedule **out)
 {
     std::vector<uint8_t> &key = ctx->key_scratch;  // reused from call to call: no allocation on the hit path
@@ -336,8 +351,8 @@ int prepare_partial(spd_ctx *ctx, int which, const spd_shape *s, const void *q, 
     if (v->n_users == 0)
         return SPD_OK;
     Owner &own = ctx->owner[which];
-    // mapping: 1 = head per wave, 0 = head-major, -1 = whatever suits this view on its own
-    const bool hpw = mapping >= 0 ? mapping != 0 : head_per_wave_layout(s, v) && head_per_wave_pays(ctx, s, total_steps(v));
+    // mapping: KV heads per workgroup of the head-per-wave mapping, 0 = head-major, -1 = whatever suits this view on its own
+    const int hpw = mapping >= 0 ? mapping : head_per_wave_layout(s, v) ? head_per_wave_choice(ctx, s, total_steps(v)) : 0;
     const int rs = get_schedule(ctx, own, s, v, hpw, stream, e);
     if (rs != SPD_OK)
         return rs;
@@ -456,8 +471,8 @@ int launch_partial(spd_ctx *ctx, int which, const CachedSchedule *e0, const spd_
     const hipEvent_t ev0 = timed ? town.ev_start[town.ev_used] : nullptr;
     const hipEvent_t ev1 = timed ? town.ev_stop[town.ev_used] : nullptr;
     const bool f32 = s->dtype == SPD_F32;
-    const bool hpw = e0->hpw;  // a two-owner launch needs the same mapping on both sides (checked by the caller)
-    const int waves = hpw ? head_per_wave_waves(s->n_kv_heads) : spd::kWaves;
+    const bool hpw = e0->hpw != 0;  // a two-owner launch needs the same mapping on both sides (checked by the caller)
+    const int waves = hpw ? e0->hpw : spd::kWaves;
     const int D = s->head_dim;
     MfmaLaunch L;
     L.grid = dim3((unsigned)(n0 + n1));
@@ -617,11 +632,12 @@ int validate_decode_step(spd_ctx *ctx, const spd_shape *shape, const void *q, co
 }
 
 // Both owners of a fused step share one launch, so they share the mapping: head per wave if both layouts allow it and
-// the two together are bandwidth-bound.
-bool fused_step_mapping(const spd_ctx *ctx, const spd_shape *shape, const spd_kv_view *priv, const spd_kv_view *pub)
+// the two together are bandwidth-bound (the value is the KV heads per workgroup, 0 for the head-major mapping).
+int fused_step_mapping(const spd_ctx *ctx, const spd_shape *shape, const spd_kv_view *priv, const spd_kv_view *pub)
 {
-    return head_per_wave_layout(shape, priv) && head_per_wave_layout(shape, pub) &&
-           head_per_wave_pays(ctx, shape, total_steps(priv) + total_steps(pub));
+    if (!head_per_wave_layout(shape, priv) || !head_per_wave_layout(shape, pub))
+        return 0;
+    return head_per_wave_choice(ctx, shape, total_steps(priv) + total_steps(pub));
 }
 
 // The launches of a fused step, given both owners' schedules (device resident) and where their chunk partials go.
@@ -769,7 +785,7 @@ int spd_create(spd_ctx **out, int hip_device)
     ctx->device = hip_device;
     ctx->tuning = tuning_from_env();
     ctx->head_per_wave = env_int("SPD_HEAD_PER_WAVE", -1, 0);
-    if (ctx->head_per_wave > 1)
+    if (ctx->head_per_wave > 8)
         ctx->head_per_wave = -1;
     hipError_t e = hipSetDevice(hip_device);
     if (e == hipSuccess)
@@ -838,7 +854,7 @@ int spd_set_option(spd_ctx *ctx, int32_t option, int32_t value)
         return SPD_ERR_SHAPE;
     bool ok;
     switch (option) {
-    case SPD_OPT_HEAD_PER_WAVE: ok = value >= -1 && value <= 1; break;
+    case SPD_OPT_HEAD_PER_WAVE: ok = value >= -1 && value <= 8; break;
     case SPD_OPT_SEG_COST: ok = value >= 0 && value <= (1 << 20); break;
     case SPD_OPT_HALF_SKEW: ok = value >= 0 && value <= 90; break;
     default: ok = value >= 1 && value <= (1 << 30); break;
@@ -909,8 +925,12 @@ try {
     for (int u = 0; u < n_users; ++u)
         if (lens[u] < 0 || lens[u] > kMaxLen)
             return SPD_ERR_LEN;
+    if (head_per_wave < 0 || head_per_wave > 8)
+        return SPD_ERR_SHAPE;
+    // 1: the widest group; 2..8: the largest divisor of the KV head count up to that
+    const int hpw = head_per_wave == 0 ? 0 : head_per_wave_waves(shape->n_kv_heads, head_per_wave == 1 ? 8 : head_per_wave);
     Schedule S;
-    build_schedule(shape->n_kv_heads, n_users, lens, n_compute_units, head_per_wave != 0, tuning_from_env(), S);
+    build_schedule(shape->n_kv_heads, n_users, lens, n_compute_units, hpw, tuning_from_env(), S);
     *n_items = (int64_t)S.items.size();
     if (chunk_tokens)
         *chunk_tokens = S.chunk_tokens;
@@ -1061,7 +1081,7 @@ try {
     StaticScratch &st = g_static[(size_t)ctx->device];
     if (!st.ptr)
         return SPD_ERR_WORKSPACE;
-    const bool hpw = fused_step_mapping(ctx, shape, priv, pub);
+    const int hpw = fused_step_mapping(ctx, shape, priv, pub);
     const int G = shape->n_q_heads / shape->n_kv_heads;
     // both schedules are built and checked against the array's limits before anything is enqueued
     ScheduleBlob B[2];

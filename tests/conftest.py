@@ -19,14 +19,17 @@ def pytest_configure(config):
 @pytest.fixture
 def mapping_of(ctx):
     """Layout names ending in "_hpw" force the library's head-per-wave kernel mapping (it is otherwise chosen only for
-    large token-major inputs) through the option SPD_OPT_HEAD_PER_WAVE of the test module's context `ctx`; returns the
-    plain layout name."""
+    large token-major inputs) through the option SPD_OPT_HEAD_PER_WAVE of the test module's context `ctx`, with
+    workgroups of up to eight KV heads; "_hpw4" and "_hpw2" the same with up to four and two.  Returns the plain
+    layout name."""
+    import re
     import paper_2409_19134_amd as spd
 
     def apply(layout):
-        if layout is not None and layout.endswith("_hpw"):
-            ctx.spd_set_option(spd.SPD_OPT_HEAD_PER_WAVE, 1)
-            return layout[:-4]
+        m = re.search(r"_hpw([2-8]?)$", layout or "")
+        if m:
+            ctx.spd_set_option(spd.SPD_OPT_HEAD_PER_WAVE, int(m.group(1) or 8))
+            return layout[:m.start()]
         ctx.spd_set_option(spd.SPD_OPT_HEAD_PER_WAVE, -1)
         return layout
     yield apply

@@ -32,8 +32,9 @@ int main()
         const int n_users = (int)(rnd() % 24);
         static const int kv_choices[] = {1, 2, 4, 8, 3, 12, 16, 7};
         const int Hkv = kv_choices[rnd() % 8];
-        const bool hpw = rnd() % 2;
-        const int waves = hpw ? head_per_wave_waves(Hkv) : 1;
+        // 0: head-major mapping; else the KV heads per workgroup of the head-per-wave mapping (any divisor up to 8)
+        const int hpw = rnd() % 2 ? head_per_wave_waves(Hkv, 1 + (int)(rnd() % 8)) : 0;
+        const int waves = hpw ? hpw : 1;
         const int es = rnd() % 2 ? 2 : 4;
         const int d = rnd() % 2 ? 64 : 128;
         const bool offsets = rnd() % 3 == 0;  // paged mode: the items hold offsets from head 0, no addresses

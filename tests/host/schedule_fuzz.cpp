@@ -26,10 +26,11 @@ int main()
         const int hkv = kv_choices[rnd() % 10];
         const int G = 1 << (rnd() % 4);
         // head-per-wave schedules: an item stands for `waves` consecutive KV heads
-        const int hpw = (int)(rnd() % 2);
+        // 0 head-major, 1 the widest group (up to 8 heads), 2..8 the widest group up to that many
+        const int hpw = rnd() % 2 ? 1 + (int)(rnd() % 8) : 0;
         int waves = 1;
         if (hpw)
-            for (int w = hkv < 8 ? hkv : 8; w >= 1; --w)
+            for (int w = std::min(hkv, hpw == 1 ? 8 : hpw); w >= 1; --w)
                 if (hkv % w == 0) {
                     waves = w;
                     break;

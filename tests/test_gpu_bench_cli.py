@@ -50,3 +50,19 @@ def test_bench_refuses_more_than_one_gpu():
     res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], cwd=ROOT,
                          stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True, timeout=120)
     assert res.returncode != 0 and "one GPU" in res.stderr
+
+
+def test_default_line_carries_the_call_forms_and_the_other_workloads():
+    """The command the benchmark is run with (fewer steps): the headline workload's record, the same step through the
+    three named calls and as two parties, and short runs of workloads 1, 3, 4 and 5 with their own parity checks."""
+    d = run_bench("--steps", "40", "--warmup", "8", "--cpu-seconds", "0.2")
+    assert d["config"]["workload"].startswith("config2") and d["config"]["mode"] == "fused" and d["parity"]["ok"]
+    assert d["roofline"]["traffic_source"] is None or "profiles/" in d["roofline"]["traffic_source"]
+    for key in ("three_calls", "two_parties"):
+        assert d[key]["us_per_step"] > 0 and d[key]["GBps"] > 0
+    others = d["other_workloads"]
+    assert [o["workload"].split(":")[0] for o in others] == ["config1", "config3", "config4", "config5"]
+    for o in others:
+        assert o["us_per_step"] > 0 and 0 < o["roofline_frac"] < 1 and o["parity"]["ok"], o
+    # the sub-records are the default workload's only
+    assert "other_workloads" not in run_bench(*SMALL)

@@ -109,7 +109,9 @@ def test_config1_fp32_full_size(ctx):
                                                         (4, 8, 48, "nhd"), (2, 8, None, "nhd"), (5, 128, 6, None),
                                                         (5, 128, 6, "nhd"), (3, 64, 12, "nhd"),
                                                         (4, 8, 48, "nhd_hpw"), (2, 8, None, "nhd_hpw"),
-                                                        (3, 64, 12, "nhd_hpw"), (5, 128, 6, "nhd_hpw")])
+                                                        (3, 64, 12, "nhd_hpw"), (5, 128, 6, "nhd_hpw"),
+                                                        (4, 8, 48, "nhd_hpw4"), (2, 8, None, "nhd_hpw4"),
+                                                        (3, 64, 12, "nhd_hpw2"), (5, 128, 6, "nhd_hpw4")])
 def test_configs_reduced_lengths(ctx, mapping_of, cfg, len_div, n_users, layout):
     layout = mapping_of(layout)
     check_against_oracle(ctx, workloads.make_workload(cfg, DEV, len_div=len_div, n_users=n_users, layout=layout))
@@ -152,7 +154,8 @@ def test_full_size_one_row_per_stream(ctx, cfg, layout):
     ([0, 0, 700], [5, 0, 0]), ([513, 1025, 2049], [95, 96, 97]),
 ])
 @pytest.mark.parametrize("layout,paged", [("nhd", False), ("nhd_hpw", False), ("hnd", False), ("hnd_exact", False),
-                                          ("nhd", True), ("nhd", "token_major"), ("nhd_hpw", "token_major")])
+                                          ("nhd", True), ("nhd", "token_major"), ("nhd_hpw", "token_major"),
+                                          ("nhd_hpw4", False), ("nhd_hpw2", "token_major")])
 def test_bf16_edge_lengths(ctx, mapping_of, lp, lo, layout, paged):
     layout = mapping_of(layout)
     wl = workloads.random_case(101, torch.bfloat16, len(lp), 32, 8, 128, lp, lo, device=DEV, layout=layout, paged=paged)
@@ -174,7 +177,7 @@ def test_bf16_edge_lengths(ctx, mapping_of, lp, lo, layout, paged):
 @pytest.mark.parametrize("Hq,Hkv", [(8, 8), (16, 8), (64, 8), (16, 1), (12, 4), (32, 2), (48, 16),
                                     (128, 8),    # G = 16 with 8 waves: head-per-wave results too big for the LDS tiles
                                     (24, 12), (27, 9), (32, 32)])   # head per wave in groups of 6, 3 and 8 heads
-@pytest.mark.parametrize("layout", ["nhd", "nhd_hpw", "hnd"])   # nhd_hpw: one wave per KV head where Hkv is in 2..8
+@pytest.mark.parametrize("layout", ["nhd", "nhd_hpw", "nhd_hpw4", "hnd"])   # nhd_hpw: one wave per KV head where Hkv is in 2..8; nhd_hpw4: groups of up to four heads
 def test_bf16_head_groupings(ctx, mapping_of, Hq, Hkv, layout):
     layout = mapping_of(layout)
     wl = workloads.random_case(103, torch.bfloat16, 3, Hq, Hkv, 128, [300, 77, 1500], [40, 0, 65], device=DEV,
@@ -193,7 +196,7 @@ def _random_case_spec(rng):
              lambda: int(rng.integers(800, 6000)), lambda: int(rng.choice([32, 64, 128, 512, 1024]))]
     weights = [0.1, 0.25, 0.3, 0.2, 0.15]
     lens = lambda: [kinds[int(rng.choice(len(kinds), p=weights))]() for _ in range(U)]
-    storage = str(rng.choice(["nhd", "nhd_hpw", "hnd", "hnd_exact", "paged", "paged_tm", "paged_tm_hpw"]))
+    storage = str(rng.choice(["nhd", "nhd_hpw", "nhd_hpw4", "hnd", "hnd_exact", "paged", "paged_tm", "paged_tm_hpw", "paged_tm_hpw2"]))
     return dict(dtype=torch.bfloat16 if bf16 else torch.float32, U=U, Hq=Hkv * G, Hkv=Hkv, d=d, lp=lens(), lo=lens(),
                 storage=storage, scale=float(rng.choice([d ** -0.5, 0.02, 0.3])))
 
@@ -228,7 +231,7 @@ def _random_case_spec_wide(rng):
              lambda: int(rng.integers(800, 6000)), lambda: int(rng.choice([32, 64, 128, 512, 1024]))]
     weights = [0.1, 0.25, 0.3, 0.2, 0.15]
     lens = lambda: [kinds[int(rng.choice(len(kinds), p=weights))]() for _ in range(U)]
-    storage = str(rng.choice(["nhd", "nhd_hpw", "hnd", "hnd_exact", "paged", "paged_tm", "paged_tm_hpw"]))
+    storage = str(rng.choice(["nhd", "nhd_hpw", "nhd_hpw4", "nhd_hpw3", "hnd", "hnd_exact", "paged", "paged_tm", "paged_tm_hpw", "paged_tm_hpw4"]))
     return dict(dtype=dtype, U=U, Hq=Hkv * G, Hkv=Hkv, d=d, lp=lens(), lo=lens(), storage=storage,
                 scale=float(rng.choice([d ** -0.5, 0.02, 0.3])), page_tokens=int(rng.choice([16, 32, 64, 128, 256])))
 
