@@ -237,13 +237,11 @@ def main():
                     help="wall-clock seconds of oracle passes in the cpu_baseline leg (times the cores it uses: CPU work)")
     ap.add_argument("--no-sub-records", action="store_true",
                     help="default workload only: skip the three_calls / two_parties legs (the same step through the "
-                         "three named entry points, and as the users' call plus the service's call)")
+                         "three named entry points, and as the users' call plus the service's call) and the short runs "
+                         "of workloads 1, 3, 4 and 5 (\"other_workloads\")")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy, so that a rocprofv3 --pmc run has a dispatch of known "
                          "traffic to scale FETCH_SIZE / WRITE_SIZE by")
-    ap.add_argument("--no-other-workloads", action="store_true",
-                    help="default workload only: skip the short runs of workloads 1, 3, 4 and 5 whose figures the JSON "
-                         "line carries under \"other_workloads\"")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -254,7 +252,7 @@ def main():
     plain_default = (args.config == 2 and args.mode == "fused" and not any(
         (args.graph, args.append, args.decode_loop, args.public_cus, args.layout, args.shape, args.dtype, args.users,
          args.lens, args.pointer_tables, args.copies)) and args.page_tokens == 16)
-    if plain_default and not args.no_other_workloads and not parity_failed:
+    if plain_default and not args.no_sub_records and not parity_failed:
         # The other benchmark workloads, after the timed region of the headline one and in the same process: fewer
         # steps (their steps are 15 to 55 times longer), the same fused step, the same clocks, the same parity check
         # (one query head of every (user, KV head) stream against the oracle).  Not part of `value`.
