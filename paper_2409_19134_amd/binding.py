@@ -402,13 +402,15 @@ def spd_validate_partial(shape: spd_shape, q_ptr, view: spd_kv_view, out_ptr, ls
     return int(lib.spd_validate_partial(C.byref(shape), q_ptr, C.byref(view), out_ptr, lse_ptr))
 
 
-def spd_build_schedule(shape: spd_shape, lens, n_compute_units: int, head_per_wave: bool = False):
-    """Host-only: the split schedule for `lens`.  Returns (list of item dicts, chunk_tokens)."""
+def spd_build_schedule(shape: spd_shape, lens, n_compute_units: int, head_per_wave=False):
+    """Host-only: the split schedule for `lens`.  Returns (list of item dicts, chunk_tokens).
+    head_per_wave: False / 0 the head-major mapping; True / 1 the head-per-wave mapping with the widest head groups
+    (up to 8 KV heads); 2..8 the same with at most that many heads per group."""
     lens = np.ascontiguousarray(lens, dtype=np.int32)
     n = C.c_int64(0)
     chunk = C.c_int32(0)
     lp = lens.ctypes.data_as(C.POINTER(C.c_int32))
-    hpw = int(bool(head_per_wave))
+    hpw = int(head_per_wave)
     rc = lib.spd_build_schedule(C.byref(shape), len(lens), lp, n_compute_units, hpw, None, 0, C.byref(n), C.byref(chunk))
     if rc != SPD_OK:
         raise SpdError(rc, "spd_build_schedule")

@@ -279,3 +279,31 @@ def test_header_is_c99_and_library_links_from_c(tmp_path):
     res = subprocess.run([exe], capture_output=True, text=True)
     assert res.returncode == 0, (res.returncode, res.stdout, res.stderr)
     assert "c99 ok" in res.stdout
+
+
+@pytest.mark.parametrize("hpw,Hkv,w", [(1, 8, 8), (4, 8, 4), (2, 8, 2), (1, 12, 6), (4, 12, 4), (5, 12, 4), (8, 32, 8), (3, 9, 3)])
+def test_head_per_wave_schedule_in_head_groups(hpw, Hkv, w):
+    """Head-per-wave schedules: an item stands for w consecutive KV heads (w = the largest divisor of the KV head count
+    up to the group size asked for); every token of every head is covered once and every head of every chunk has a
+    partial slot of its own."""
+    lens = [5000, 0, 33, 70000, 129]
+    sh = spd.make_shape(spd.SPD_BF16, Hkv * 2, Hkv, 128, 0.1)
+    items, _ = spd.spd_build_schedule(sh, lens, 256, head_per_wave=hpw)
+    slots = set()
+    cover = {}
+    for it in items:
+        assert it["kv_head"] % w == 0 and it["kv_head"] + w <= Hkv
+        for j in range(w):
+            slot = it["slot"] + j * it["n_chunks"]
+            assert slot not in slots
+            slots.add(slot)
+            cover.setdefault((it["user"], it["kv_head"] + j), []).append((it["t_begin"], it["t_end"]))
+    for u, L in enumerate(lens):
+        for h in range(Hkv):
+            row = sorted(cover.get((u, h), []))
+            if L == 0:
+                assert not row
+                continue
+            assert row[0][0] == 0 and row[-1][1] == L and all(a[1] == b[0] for a, b in zip(row, row[1:]))
+    with pytest.raises(spd.SpdError):
+        spd.spd_build_schedule(sh, lens, 256, head_per_wave=9)
