@@ -138,8 +138,11 @@ enum {
                                      fit the device at once (default 768)                                          */
     SPD_OPT_CHUNK_MAX = 3,        /* tokens per piece when the work exceeds one resident round (default 16384)       */
     SPD_OPT_SEG_COST = 4,         /* 32-token steps a piece gives up for every further row it reaches into (default 2) */
-    SPD_OPT_HALF_SKEW = 5         /* one resident round of pieces: per cent by which the half dispatched first is made
+    SPD_OPT_HALF_SKEW = 5,        /* one resident round of pieces: per cent by which the half dispatched first is made
                                      longer and the other half shorter (default 12, 0..90)                          */
+    SPD_OPT_RESULT_ROWS = 6       /* result rows a workgroup of the head-major mapping may hold back in on-chip memory
+                                     and store together at the end of its piece (default 16, 0..16; fewer if they do
+                                     not fit); not part of the schedule: changing it rebuilds nothing               */
 };
 int spd_set_option(spd_ctx *ctx, int32_t option, int32_t value);
 int spd_get_option(spd_ctx *ctx, int32_t option, int32_t *value);

@@ -225,5 +225,6 @@ struct PartialArgs {
     const char *q;          // [U][Hq][D]
     int32_t Hq, G;
     float scale_log2e;
+    int32_t ring_rows;      // result rows a workgroup may hold back in LDS (see the result ring in partial_mfma.hpp); 0: none
 };
 }  // namespace spd

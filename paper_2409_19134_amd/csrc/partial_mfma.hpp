@@ -263,6 +263,26 @@ __host__ __device__ constexpr size_t staging_bytes(int D, int waves, int G)
 }
 __host__ __device__ constexpr bool staging_fits(int D, int waves, int G) { return staging_bytes(D, waves, G) <= 64 * 1024; }
 
+// The result ring.  A piece that crosses rows produces a result row ([G][D] values and G log-sum-exps, final or a chunk
+// partial) at every segment end.  Written where they arise, those rows reach HBM as single lines scattered over the
+// read stream, and each costs the memory system far more than its bytes: a plain streaming read of 2.8 GB at 768
+// workgroups takes 414 us, 444 us with 8 MB of such rows written along the way, and 418 us with the same rows written
+// when a workgroup is done (measured on this GPU; workload 4 writes 8 MB of them in 443 us).  So a head-major
+// workgroup keeps its rows in LDS, up to `ring_rows` of them, and stores them together when the ring is full or the
+// piece ends.  A row of the ring: G * D values, then G log-sum-exps, padded to a multiple of four floats.
+constexpr int kRingMaxRows = 32;
+__host__ __device__ constexpr int ring_row_floats(int D, int G) { return G * D + ((G + 3) & ~3); }
+// LDS bytes a head-major workgroup may use for staging and ring together: three workgroups (one step in flight) or two
+// (two steps) share a CU's 160 KB, and a workgroup may ask for 64 KB in all.
+__host__ __device__ constexpr size_t ring_lds_budget(bool prefetch) { return (prefetch ? 60 : 40) * 1024; }
+__host__ __device__ constexpr int ring_rows_that_fit(int D, int G, bool prefetch)
+{
+    const size_t staging = sizeof(float) * (size_t)kWaves * G * o_stride(D);
+    const size_t row = sizeof(float) * (size_t)ring_row_floats(D, G);
+    const size_t n = staging >= ring_lds_budget(prefetch) ? 0 : (ring_lds_budget(prefetch) - staging) / row;
+    return n < 2 ? 0 : n > (size_t)kRingMaxRows ? kRingMaxRows : (int)n;  // a ring of one row holds nothing back
+}
+
 // Waves per SIMD the kernel is compiled for: a step's loads take RB/4 registers per lane (twice that with PREFETCH).
 __host__ __device__ constexpr int mfma_waves_per_simd(int RB, bool prefetch, bool hpw)
 {
@@ -313,7 +333,8 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, mfma_waves_per_simd(D *Elt<DT
     const int grow = second ? a1.grow : a0.grow;
     __shared__ float sm_m[kWaves][16];
     __shared__ float sm_l[kWaves][16];
-    extern __shared__ float sm_o[];  // [waves][G * kOStride], sized by the launch: only G heads are staged
+    __shared__ float *ring_dst_o[kRingMaxRows], *ring_dst_l[kRingMaxRows];  // where the ring's rows go
+    extern __shared__ float sm_o[];  // [waves][G * kOStride], sized by the launch: only G heads are staged; then the ring
     constexpr int kOStride = o_stride(D);
     constexpr int CP = D / 16;  // channel phases of the O^T tile: a lane holds CP consecutive channels per accumulator row
     constexpr int kRowBytes = D * Elt<DT>::kBytes;
@@ -394,6 +415,7 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, mfma_waves_per_simd(D *Elt<DT
     int tb;
     TileRegs<RB> T0;
     PagePair P = {0, 0};
+    int n_ring = 0;  // rows held in the result ring (head-major mapping only)
     begin_segment(it, L, qB, tb, T0, P);
     for (;;) {
         // the piece's next segment is fetched (scalar cache) long before it is looked at: with tens of MB of loads in
@@ -530,32 +552,59 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, mfma_waves_per_simd(D *Elt<DT
         __syncthreads();
 
         const int64_t head0 = (int64_t)it.user * Hq + (int64_t)it.kv_head * G;
-        for (int idx = threadIdx.x; idx < G * D; idx += kThreads) {
-            const int g = idx / D, ch = idx % D;
-            float Mg = sm_m[0][g];
+        // the row goes to the ring - unless the piece ends here with an empty ring, or there is no ring
+        const bool last = it.next < 0;
+        const bool to_ring = A.ring_rows > 0 && !(last && n_ring == 0);
+        const int GD = G * D, ring_stride = ring_row_floats(D, G);
+        float *const ring = sm_o + kWaves * o_wave_stride;
+        float *const dst_o = direct ? out + head0 * D : part_o + (int64_t)it.slot * GD;
+        float *const dst_l = direct ? lse + head0 : part_lse + (int64_t)it.slot * G;
+        // (two copies of the loop, so that each stores through pointers of one kind, LDS or global memory: a pointer
+        // that may be either makes every store a flat one)
+        typedef __attribute__((address_space(1))) float *global_f32;
+        typedef __attribute__((address_space(3))) float *lds_f32;
+        auto reduce_waves = [&](auto row_o, auto row_l) {
+            for (int idx = threadIdx.x; idx < GD; idx += kThreads) {
+                const int g = idx / D, ch = idx % D;
+                float Mg = sm_m[0][g];
 #pragma unroll
-            for (int w = 1; w < kWaves; ++w)
-                Mg = fmaxf(Mg, sm_m[w][g]);
-            float o = 0.f, lt = 0.f;
+                for (int w = 1; w < kWaves; ++w)
+                    Mg = fmaxf(Mg, sm_m[w][g]);
+                float o = 0.f, lt = 0.f;
 #pragma unroll
-            for (int w = 0; w < kWaves; ++w) {
-                o += sm_o[w * o_wave_stride + g * kOStride + ch];
-                lt += sm_l[w][g] * fast_exp2(sm_m[w][g] - Mg);
+                for (int w = 0; w < kWaves; ++w) {
+                    o += sm_o[w * o_wave_stride + g * kOStride + ch];
+                    lt += sm_l[w][g] * fast_exp2(sm_m[w][g] - Mg);
+                }
+                row_o[idx] = o * fast_rcp(lt);
+                if (ch == 0)
+                    row_l[g] = (Mg + fast_log2(lt) - Elt<DT>::kPShift) * kLn2;  // Mg is in log2 units
             }
-            const float a = o * fast_rcp(lt);
-            if (direct)
-                out[(head0 + g) * D + ch] = a;
-            else
-                part_o[((int64_t)it.slot * G + g) * D + ch] = a;
-            if (ch == 0) {
-                const float ls = (Mg + fast_log2(lt) - Elt<DT>::kPShift) * kLn2;  // Mg is in log2 units
-                if (direct)
-                    lse[head0 + g] = ls;
-                else
-                    part_lse[(int64_t)it.slot * G + g] = ls;
+        };
+        if (to_ring)
+            reduce_waves((lds_f32)(ring + n_ring * ring_stride), (lds_f32)(ring + n_ring * ring_stride + GD));
+        else
+            reduce_waves((global_f32)dst_o, (global_f32)dst_l);
+        if (to_ring) {
+            if (threadIdx.x == 0) {
+                ring_dst_o[n_ring] = dst_o;
+                ring_dst_l[n_ring] = dst_l;
+            }
+            ++n_ring;
+            if (last || n_ring == A.ring_rows) {
+                __syncthreads();
+                for (int i = 0; i < n_ring; ++i) {
+                    const lds_f32 src = (lds_f32)(ring + i * ring_stride);
+                    const global_f32 o = (global_f32)ring_dst_o[i];
+                    for (int idx = threadIdx.x; idx < GD; idx += kThreads)
+                        o[idx] = src[idx];
+                    if ((int)threadIdx.x < G)
+                        ((global_f32)ring_dst_l[i])[threadIdx.x] = src[GD + threadIdx.x];
+                }
+                n_ring = 0;
             }
         }
-        if (it.next < 0)
+        if (last)
             return;
         if (!PREFETCH)
             begin_segment(nx, L, qB, tb, T0, P);

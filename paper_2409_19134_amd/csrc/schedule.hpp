@@ -97,6 +97,32 @@ inline int head_per_wave_waves(int Hkv, int most = 8)
     return 1;
 }
 
+// The number of pieces build_schedule makes for the head-major mapping if they are exactly one resident round of
+// equal pieces (target_wg_per_cu per CU), else 0 (short rows cut into one-step chunks, less work than a round, or
+// several rounds).  Costs a pass over the lengths: the fused step asks before it looks its schedules up.
+// *rows: the (user, KV head) rows that hold tokens.
+inline int64_t single_round_pieces(int Hkv, int n_users, const int32_t *lens, int n_cus, const Tuning &tune, int64_t *rows)
+{
+    int64_t T = 0, short_chunks = 0;
+    int max_len = 0;
+    *rows = 0;
+    for (int u = 0; u < n_users; ++u) {
+        const int64_t steps = (lens[u] + kChunkAlign - 1) / kChunkAlign;
+        T += steps;
+        short_chunks += (steps + spd::kWaves - 1) / spd::kWaves;
+        max_len = std::max(max_len, lens[u]);
+        *rows += lens[u] > 0 ? Hkv : 0;
+    }
+    const int64_t resident = (int64_t)std::max(1, n_cus) * tune.target_wg_per_cu;
+    if (T == 0 || (max_len <= tune.no_split_max && short_chunks * Hkv <= resident))
+        return 0;
+    const int64_t wg = std::max<int64_t>(1, resident / Hkv);
+    const int64_t piece_max = std::max(kChunkMin, (int)tune.chunk_max) / kChunkAlign;
+    if (T > wg * piece_max || (T + spd::kWaves - 1) / spd::kWaves < wg)
+        return 0;
+    return wg * Hkv;
+}
+
 // hpw: 0 for the head-major mapping, else the KV heads (waves) per workgroup of the head-per-wave mapping, a divisor
 // of Hkv that is at most 8.
 inline void build_schedule(int Hkv, int n_users, const int32_t *lens, int n_cus, int hpw, const Tuning &tune, Schedule &S)
@@ -276,6 +302,7 @@ struct DeviceTables {
     std::vector<spd::CombineRow> split_rows;  // rows held in more than one partial slot
     std::vector<spd::RowInfo> row_info;       // [n_users * Hkv] first slot and slot count of every row
     int64_t items_launched = 0;               // workgroups of the launch
+    int64_t n_segments = 0;                   // segments with tokens, all pieces together
 };
 
 // es: bytes per K/V element.  Row addresses come from the view's host pointer arrays (contiguous mode without device
@@ -368,6 +395,7 @@ inline void build_device_tables(const Schedule &S, int Hkv, int es, const spd_kv
             for (int h = 0; h < hpw_waves; ++h)
                 row_info[(size_t)w.user * Hkv + w.kv_head + h] = RowInfo{w.slot + h * w.n_chunks, w.n_chunks};
     T.items_launched = n_groups;
+    T.n_segments = (int64_t)S.items.size();
 }
 
 }  // namespace spd::host

@@ -44,7 +44,7 @@ struct CachedSchedule {
     bool growable = false;       // no user without tokens (a row that only writes A = 0 cannot gain tokens)
     int32_t grow = 0;            // set by every lookup: tokens each row has gained over the lengths in `key`
     std::vector<uint8_t> key;
-    int64_t n_items = 0, n_slots = 0;
+    int64_t n_items = 0, n_slots = 0, n_segments = 0;
     int hpw = 0;             // 0, or the KV heads per workgroup of the head-per-wave kernel the pieces are for
     int n_split_rows = 0;    // rows with several chunks: CombineRow[n_split_rows] follows the items
     size_t off_rows = 0, off_info = 0;
@@ -84,6 +84,7 @@ struct spd_ctx {
     bool timing = false;
     int32_t last_instance[6] = {-1, -1, -1, -1, -1, -1};  // template arguments of the partial kernel launched last
     Tuning tuning;           // what shapes the split schedules (SPD_OPT_*)
+    int result_rows = spd::kRingMaxRows;  // SPD_OPT_RESULT_ROWS: result rows a workgroup holds back in LDS at most (0: none)
     int head_per_wave = -1;  // SPD_OPT_HEAD_PER_WAVE: 0 never, 1 whenever the layout allows, 2..8 the same with that many heads per workgroup, -1 by the size rule
     std::vector<uint8_t> key_scratch;
     Owner owner[2];
@@ -163,6 +164,7 @@ struct ScheduleBlob {
     size_t off_rows = 0, off_info = 0;
     int64_t n_items = 0;      // workgroups of the launch
     int64_t n_slots = 0;      // chunk partials
+    int64_t n_segments = 0;   // segments with tokens
     int n_split_rows = 0;
 };
 
@@ -186,16 +188,17 @@ void build_blob(const spd_shape *s, const spd_kv_view *v, int hpw, int n_cus, co
         std::memcpy(B.bytes.data() + B.off_info, T.row_info.data(), b_info);
     B.n_items = T.items_launched;
     B.n_slots = S.n_slots;
+    B.n_segments = T.n_segments;
     B.n_split_rows = (int)T.split_rows.size();
 }
 
 // Find or build the device-resident schedule for this view (hpw: pieces for the head-per-wave kernel).  Uploads are
 // enqueued on `stream`.
-int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view *v, int hpw,
+int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view *v, int hpw, const Tuning &tune,
                  hipStream_t stream, CachedSchedule **out)
 {
     std::vector<uint8_t> &key = ctx->key_scratch;  // reused from call to call: no allocation on the hit path
-    make_key(s, v, hpw, &ctx->tuning.target_wg_per_cu, kTuningInts, key);
+    make_key(s, v, hpw, &tune.target_wg_per_cu, kTuningInts, key);
     const uint64_t h = hash_key(key.data(), key.size());
     ++ctx->tick;
     CachedSchedule *victim = &own.cache[0];
@@ -237,7 +240,7 @@ int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view
         return SPD_OK;
     }
     ScheduleBlob B;
-    build_blob(s, v, hpw, ctx->n_cus, ctx->tuning, B);
+    build_blob(s, v, hpw, ctx->n_cus, tune, B);
     const size_t total = B.bytes.size();
 
     CachedSchedule &e = *victim;
@@ -302,6 +305,7 @@ int get_schedule(spd_ctx *ctx, Owner &own, const spd_shape *s, const spd_kv_view
     e.n_items = B.n_items;
     e.hpw = hpw;
     e.n_slots = B.n_slots;
+    e.n_segments = B.n_segments;
     e.n_split_rows = B.n_split_rows;
     e.off_rows = B.off_rows;
     e.off_info = B.off_info;
@@ -342,7 +346,7 @@ int ensure_scratch(spd_ctx *ctx, Owner &own, size_t o_floats, size_t lse_floats)
 
 // Validation, schedule lookup and scratch growth of one partial-attention call.
 int prepare_partial(spd_ctx *ctx, int which, const spd_shape *s, const void *q, const spd_kv_view *v, float *out,
-                    float *lse, int mapping, hipStream_t stream, CachedSchedule **e)
+                    float *lse, int mapping, const Tuning &tune, hipStream_t stream, CachedSchedule **e)
 {
     const int rc = spd_validate_partial(s, q, v, out, lse);
     if (rc != SPD_OK)
@@ -353,7 +357,7 @@ int prepare_partial(spd_ctx *ctx, int which, const spd_shape *s, const void *q, 
     Owner &own = ctx->owner[which];
     // mapping: KV heads per workgroup of the head-per-wave mapping, 0 = head-major, -1 = whatever suits this view on its own
     const int hpw = mapping >= 0 ? mapping : head_per_wave_layout(s, v) ? head_per_wave_choice(ctx, s, total_steps(v)) : 0;
-    const int rs = get_schedule(ctx, own, s, v, hpw, stream, e);
+    const int rs = get_schedule(ctx, own, s, v, hpw, tune, stream, e);
     if (rs != SPD_OK)
         return rs;
     const int G = s->n_q_heads / s->n_kv_heads;
@@ -479,6 +483,7 @@ int launch_partial(spd_ctx *ctx, int which, const CachedSchedule *e0, const spd_
     L.block = dim3(64u * (unsigned)waves);
     // cross-wave staging; head-per-wave stages its per-wave results too if that fits (the kernel applies the same rule)
     L.lds = (hpw && !spd::staging_fits(D, waves, G)) ? 0 : (uint32_t)spd::staging_bytes(D, waves, G);
+
     L.stream = stream;
     L.ev0 = ev0;
     L.ev1 = ev1;
@@ -497,6 +502,13 @@ int launch_partial(spd_ctx *ctx, int which, const CachedSchedule *e0, const spd_
     const int64_t cus = std::max(1, ctx->n_cus);
     const int row_bytes = D * elt_size(s->dtype);
     const bool prefetch = !f32 && (hpw || row_bytes == 128 || n0 + n1 > cus * 4 || n0 + n1 <= cus * 2);
+    // Head-major mapping: result rows wait in LDS for the end of their piece (see the result ring in
+    // partial_mfma.hpp) - where a piece has rows to wait for: with fewer than three segments per piece on average the
+    // ring only adds its copy (the headline workload, 1.3 segments per piece: +0.4 us).
+    const int64_t segments = e0->n_segments + (e1 ? e1->n_segments : 0);
+    const int ring_rows = (hpw || segments < 3 * (n0 + n1)) ? 0 : std::min(ctx->result_rows, spd::ring_rows_that_fit(D, G, prefetch));
+    L.lds += (uint32_t)(ring_rows * spd::ring_row_floats(D, G) * sizeof(float));
+    L.args.ring_rows = ring_rows;
     const bool ok = with_value<SPD_F32, SPD_BF16, SPD_F16>(s->dtype, [&](auto dt) {
         return with_value<64, 128>(D, [&](auto d) {
             return with_bool(v0->block_size != 0, [&](auto paged) {
@@ -569,7 +581,7 @@ int partial_attention(spd_ctx *ctx, int which, const spd_shape *s, const void *q
         rc = validate_new_token(v, nt);
     if (rc != SPD_OK)
         return rc;
-    rc = prepare_partial(ctx, which, s, q, v, out, lse, -1, stream, &e);
+    rc = prepare_partial(ctx, which, s, q, v, out, lse, -1, ctx->tuning, stream, &e);
     if (rc != SPD_OK || !e)
         return rc;
     rc = launch_partial(ctx, which, e, v, out, lse, scratch_of(ctx->owner[which]), nullptr, nullptr, nullptr, nullptr,
@@ -638,6 +650,26 @@ int fused_step_mapping(const spd_ctx *ctx, const spd_shape *shape, const spd_kv_
     if (!head_per_wave_layout(shape, priv) || !head_per_wave_layout(shape, pub))
         return 0;
     return head_per_wave_choice(ctx, shape, total_steps(priv) + total_steps(pub));
+}
+
+// Both owners of a fused step also share the device: if each would cut its rows into a full resident round of equal
+// pieces, the two rounds together are more than fit at once, the second owner's pieces start when the first's end, and
+// result rows are written all along (see the result ring in partial_mfma.hpp).  Where the pieces cross many rows -
+// two rows per piece or more - each owner then gets half as many pieces, twice as long, all resident from the start
+// and with more rows to hold back each (with the ring; us per fused step, 512 + 512 pieces against 256 + 256:
+// workload 4 444.3 / 434.4, its length law with 128 users 230.7 / 227.0, 256 users of 64-512 tokens 92.7 / 91.3).
+// With few, long rows the shorter pieces stay (workload 2's length law with 64 users: 103.9 / 107.2).
+Tuning fused_step_tuning(const spd_ctx *ctx, const spd_shape *shape, const spd_kv_view *priv, const spd_kv_view *pub, int hpw)
+{
+    Tuning t = ctx->tuning;
+    if (hpw || t.target_wg_per_cu < 2)
+        return t;
+    int64_t rows_p = 0, rows_o = 0;
+    const int64_t np = single_round_pieces(shape->n_kv_heads, priv->n_users, priv->lens, ctx->n_cus, t, &rows_p);
+    const int64_t no = single_round_pieces(shape->n_kv_heads, pub->n_users, pub->lens, ctx->n_cus, t, &rows_o);
+    if (np > 0 && no > 0 && rows_p + rows_o >= 2 * (np + no))
+        t.target_wg_per_cu /= 2;
+    return t;
 }
 
 // The launches of a fused step, given both owners' schedules (device resident) and where their chunk partials go.
@@ -784,6 +816,7 @@ int spd_create(spd_ctx **out, int hip_device)
     }
     ctx->device = hip_device;
     ctx->tuning = tuning_from_env();
+    ctx->result_rows = std::min(spd::kRingMaxRows, env_int("SPD_RESULT_ROWS", spd::kRingMaxRows, 0));
     ctx->head_per_wave = env_int("SPD_HEAD_PER_WAVE", -1, 0);
     if (ctx->head_per_wave > 8)
         ctx->head_per_wave = -1;
@@ -835,6 +868,7 @@ int32_t *option_slot(spd_ctx *ctx, int32_t option)
 {
     switch (option) {
     case SPD_OPT_HEAD_PER_WAVE: return &ctx->head_per_wave;
+    case SPD_OPT_RESULT_ROWS: return &ctx->result_rows;
     case SPD_OPT_TARGET_WG_PER_CU: return &ctx->tuning.target_wg_per_cu;
     case SPD_OPT_NO_SPLIT_MAX: return &ctx->tuning.no_split_max;
     case SPD_OPT_CHUNK_MAX: return &ctx->tuning.chunk_max;
@@ -855,6 +889,7 @@ int spd_set_option(spd_ctx *ctx, int32_t option, int32_t value)
     bool ok;
     switch (option) {
     case SPD_OPT_HEAD_PER_WAVE: ok = value >= -1 && value <= 8; break;
+    case SPD_OPT_RESULT_ROWS: ok = value >= 0 && value <= spd::kRingMaxRows; break;
     case SPD_OPT_SEG_COST: ok = value >= 0 && value <= (1 << 20); break;
     case SPD_OPT_HALF_SKEW: ok = value >= 0 && value <= 90; break;
     default: ok = value >= 1 && value <= (1 << 30); break;
@@ -1050,10 +1085,11 @@ try {
         return rc;
     CachedSchedule *ep = nullptr, *eo = nullptr;
     const int hpw = fused_step_mapping(ctx, shape, priv, pub);
-    rc = prepare_partial(ctx, 0, shape, q, priv, a_in, lse_in, hpw, stream, &ep);
+    const Tuning tune = fused_step_tuning(ctx, shape, priv, pub, hpw);
+    rc = prepare_partial(ctx, 0, shape, q, priv, a_in, lse_in, hpw, tune, stream, &ep);
     if (rc != SPD_OK)
         return rc;
-    rc = prepare_partial(ctx, 1, shape, q, pub, a_out, lse_out, hpw, stream, &eo);  // an upload, if any, stays on `stream`
+    rc = prepare_partial(ctx, 1, shape, q, pub, a_out, lse_out, hpw, tune, stream, &eo);  // an upload, if any, stays on `stream`
     if (rc != SPD_OK)
         return rc;
     return launch_decode_step(ctx, shape, q, priv, pub, nt, ep, eo, scratch_of(ctx->owner[0]), scratch_of(ctx->owner[1]), a_in,
@@ -1082,14 +1118,15 @@ try {
     if (!st.ptr)
         return SPD_ERR_WORKSPACE;
     const int hpw = fused_step_mapping(ctx, shape, priv, pub);
+    const Tuning tune = fused_step_tuning(ctx, shape, priv, pub, hpw);
     const int G = shape->n_q_heads / shape->n_kv_heads;
     // both schedules are built and checked against the array's limits before anything is enqueued
     ScheduleBlob B[2];
     const spd_kv_view *views[2] = {priv, pub};
     std::vector<uint8_t> key[2];
     for (int w = 0; w < 2; ++w) {
-        build_blob(shape, views[w], hpw, ctx->n_cus, ctx->tuning, B[w]);
-        make_key(shape, views[w], hpw, &ctx->tuning.target_wg_per_cu, kTuningInts, key[w]);
+        build_blob(shape, views[w], hpw, ctx->n_cus, tune, B[w]);
+        make_key(shape, views[w], hpw, &tune.target_wg_per_cu, kTuningInts, key[w]);
         if (B[w].bytes.size() > kStaticSchedBytes || (size_t)B[w].n_slots * G + 4 > kStaticLseFloats ||
             (size_t)B[w].n_slots * G * shape->head_dim + 4 > kStaticPartOFloats)
             return SPD_ERR_WORKSPACE;
@@ -1115,6 +1152,7 @@ try {
         e[w].dev = dst;
         e[w].n_items = B[w].n_items;
         e[w].n_slots = B[w].n_slots;
+        e[w].n_segments = B[w].n_segments;
         e[w].hpw = hpw;
         e[w].n_split_rows = B[w].n_split_rows;
         e[w].off_rows = B[w].off_rows;
@@ -1151,7 +1189,7 @@ try {
     if (!aligned16(a_in) || !aligned16(y))
         return SPD_ERR_ALIGN;
     CachedSchedule *eo = nullptr;
-    rc = prepare_partial(ctx, 1, shape, q, pub, a_out, lse_out, -1, stream, &eo);
+    rc = prepare_partial(ctx, 1, shape, q, pub, a_out, lse_out, -1, ctx->tuning, stream, &eo);
     if (rc != SPD_OK)
         return rc;
     rc = launch_partial(ctx, 1, eo, pub, a_out, lse_out, scratch_of(ctx->owner[1]), nullptr, nullptr, nullptr, nullptr,
