@@ -283,6 +283,18 @@ __host__ __device__ constexpr int ring_rows_that_fit(int D, int G, bool prefetch
     return n < 2 ? 0 : n > (size_t)kRingMaxRows ? kRingMaxRows : (int)n;  // a ring of one row holds nothing back
 }
 
+// The same for the head-per-wave mapping, where every wave owns a row per segment: a ring per wave, its rows in the
+// layout of the wave's staging tile ([G][o_stride]), then G log-sum-exps (padded to four floats) and the two pointers
+// the row goes to.
+__host__ __device__ constexpr int hpw_ring_row_floats(int D, int G) { return G * o_stride(D) + ((G + 3) & ~3) + 4; }
+__host__ __device__ constexpr int hpw_ring_rows_that_fit(int D, int G, int waves)
+{
+    const size_t staging = sizeof(float) * (size_t)waves * G * o_stride(D);
+    const size_t row = sizeof(float) * (size_t)hpw_ring_row_floats(D, G) * waves;
+    const size_t n = staging >= ring_lds_budget(true) ? 0 : (ring_lds_budget(true) - staging) / row;
+    return n < 2 ? 0 : n > (size_t)kRingMaxRows ? kRingMaxRows : (int)n;
+}
+
 // Waves per SIMD the kernel is compiled for: a step's loads take RB/4 registers per lane (twice that with PREFETCH).
 __host__ __device__ constexpr int mfma_waves_per_simd(int RB, bool prefetch, bool hpw)
 {
@@ -483,11 +495,17 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, mfma_waves_per_simd(D *Elt<DT
             const int64_t slot = (int64_t)it.slot + (int64_t)uniform(wave) * it.n_chunks;  // it.slot: the group's first head
             const float inv = fast_rcp(l);  // l > 0: the segment holds at least one token
             float *res = direct ? out + head0 * D : part_o + slot * G * D;  // [G][D], contiguous
+            float *res_l = direct ? lse + head0 : part_lse + slot * G;
+            // the row waits in the wave's ring - unless the piece ends here with an empty ring, or there is no ring
+            const bool last = it.next < 0;
+            const bool to_ring = staged && A.ring_rows > 0 && !(last && n_ring == 0);
+            const int hrow = hpw_ring_row_floats(D, G);
+            float *const ring_w = sm_o + (int)(blockDim.x >> 6) * o_wave_stride + wave * A.ring_rows * hrow;
             if (staged) {
                 // Through a wave-private LDS tile, so that the wave stores whole rows with consecutive lanes (storing
                 // straight from the accumulator layout puts 16 bytes per lane into 16 different cache lines per
                 // instruction; measured 2-3 % of the kernel on long token-major workloads).
-                float *stage = sm_o + wave * o_wave_stride;
+                float *stage = to_ring ? ring_w + n_ring * hrow : sm_o + wave * o_wave_stride;
                 if (r < G) {
                     float *dst = stage + r * kOStride + grp * 4 * CP;
 #pragma unroll
@@ -496,10 +514,36 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, mfma_waves_per_simd(D *Elt<DT
                         for (int v = 0; v < 4; ++v)
                             dst[v * CP + cc] = acc[cc][v] * inv;  // channel (4*grp + v)*CP + cc
                 }
+                if (to_ring) {
+                    if (r < G && grp == 0)
+                        stage[o_wave_stride + r] = (m + fast_log2(l) - Elt<DT>::kPShift) * kLn2;  // m is in log2 units
+                    if (lane == 0) {
+                        float **dst = reinterpret_cast<float **>(stage + o_wave_stride + ((G + 3) & ~3));
+                        dst[0] = res;
+                        dst[1] = res_l;
+                    }
+                    ++n_ring;
+                }
                 __builtin_amdgcn_wave_barrier();  // same wave: LDS executes its writes before its reads
-                for (int i = lane * 4; i < G * D; i += 256) {
-                    const f32x4 w = *reinterpret_cast<const f32x4 *>(stage + (i / D) * kOStride + (i % D));
-                    *reinterpret_cast<f32x4 *>(res + i) = w;
+                if (!to_ring) {
+                    for (int i = lane * 4; i < G * D; i += 256) {
+                        const f32x4 w = *reinterpret_cast<const f32x4 *>(stage + (i / D) * kOStride + (i % D));
+                        *reinterpret_cast<f32x4 *>(res + i) = w;
+                    }
+                } else if (last || n_ring == A.ring_rows) {
+                    typedef __attribute__((address_space(1))) float *global_f32;
+                    for (int k = 0; k < n_ring; ++k) {
+                        const float *row = ring_w + k * hrow;
+                        float *const *dst = reinterpret_cast<float *const *>(row + o_wave_stride + ((G + 3) & ~3));
+                        const global_f32 o = (global_f32)dst[0];
+                        for (int i = lane * 4; i < G * D; i += 256) {
+                            const f32x4 w = *reinterpret_cast<const f32x4 *>(row + (i / D) * kOStride + (i % D));
+                            *reinterpret_cast<__attribute__((address_space(1))) f32x4 *>(o + i) = w;
+                        }
+                        if (lane < G)
+                            ((global_f32)dst[1])[lane] = row[o_wave_stride + lane];
+                    }
+                    n_ring = 0;
                 }
                 __builtin_amdgcn_wave_barrier();
             }
@@ -514,15 +558,10 @@ __global__ __launch_bounds__(HPW ? 512 : kThreads, mfma_waves_per_simd(D *Elt<DT
                             *reinterpret_cast<f32x4 *>(dst + v * CP + c4) = w;
                         }
                 }
-                if (grp == 0) {
-                    const float ls = (m + fast_log2(l) - Elt<DT>::kPShift) * kLn2;  // m is in log2 units
-                    if (direct)
-                        lse[head0 + r] = ls;
-                    else
-                        part_lse[slot * G + r] = ls;
-                }
+                if (grp == 0 && !to_ring)
+                    res_l[r] = (m + fast_log2(l) - Elt<DT>::kPShift) * kLn2;  // m is in log2 units
             }
-            if (it.next < 0)
+            if (last)
                 return;
             if (!PREFETCH)
                 begin_segment(nx, L, qB, tb, T0, P);

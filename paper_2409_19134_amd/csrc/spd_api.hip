@@ -502,12 +502,16 @@ int launch_partial(spd_ctx *ctx, int which, const CachedSchedule *e0, const spd_
     const int64_t cus = std::max(1, ctx->n_cus);
     const int row_bytes = D * elt_size(s->dtype);
     const bool prefetch = !f32 && (hpw || row_bytes == 128 || n0 + n1 > cus * 4 || n0 + n1 <= cus * 2);
-    // Head-major mapping: result rows wait in LDS for the end of their piece (see the result ring in
-    // partial_mfma.hpp) - where a piece has rows to wait for: with fewer than three segments per piece on average the
-    // ring only adds its copy (the headline workload, 1.3 segments per piece: +0.4 us).
+    // Result rows wait in LDS for the end of their piece (see the result ring in partial_mfma.hpp) - where a piece
+    // has rows to wait for: with fewer than three segments per piece on average the ring only adds its copy (the
+    // headline workload, 1.3 segments per piece: +0.4 us).  The head-per-wave mapping has fewer, wider segments and
+    // takes it from 1.5 (workload 4 token-major, 2 segments per piece: 446 -> 442 us).
     const int64_t segments = e0->n_segments + (e1 ? e1->n_segments : 0);
-    const int ring_rows = (hpw || segments < 3 * (n0 + n1)) ? 0 : std::min(ctx->result_rows, spd::ring_rows_that_fit(D, G, prefetch));
-    L.lds += (uint32_t)(ring_rows * spd::ring_row_floats(D, G) * sizeof(float));
+    int ring_rows = 0;
+    const int min_x2 = hpw ? 3 : 6;  // twice the segments per piece
+    if (2 * segments >= min_x2 * (n0 + n1) && L.lds > 0)  // (head per wave without its staging tiles has no ring either)
+        ring_rows = std::min(ctx->result_rows, hpw ? spd::hpw_ring_rows_that_fit(D, G, waves) : spd::ring_rows_that_fit(D, G, prefetch));
+    L.lds += (uint32_t)(ring_rows * sizeof(float) * (hpw ? (size_t)spd::hpw_ring_row_floats(D, G) * waves : (size_t)spd::ring_row_floats(D, G)));
     L.args.ring_rows = ring_rows;
     const bool ok = with_value<SPD_F32, SPD_BF16, SPD_F16>(s->dtype, [&](auto dt) {
         return with_value<64, 128>(D, [&](auto d) {

@@ -319,8 +319,9 @@ def test_one_very_long_row(chunk_max, monkeypatch):
     own.close()
 
 
-@pytest.mark.parametrize("rows_opt", [None, 0, 3])
-def test_many_rows_per_piece_fused_step_and_result_ring(rows_opt):
+@pytest.mark.parametrize("rows_opt,layout,group", [(None, "hnd", 0), (0, "hnd", 0), (3, "hnd", 0), (None, "nhd", 4),
+                                                  (2, "nhd", 4), (None, "nhd", 8), (None, "nhd", 2)])
+def test_many_rows_per_piece_fused_step_and_result_ring(rows_opt, layout, group):
     """Many users with rows of a few hundred tokens on both sides: every piece crosses several rows, so the pieces hold
     their result rows back and store them together (the ring is filled and emptied several times per piece with
     rows_opt = 3, never used with 0), and the fused step - both owners would each fill the device - builds schedules of
@@ -329,17 +330,19 @@ def test_many_rows_per_piece_fused_step_and_result_ring(rows_opt):
     own = spd.Context(0)
     if rows_opt is not None:
         own.spd_set_option(spd.SPD_OPT_RESULT_ROWS, rows_opt)
+    own.spd_set_option(spd.SPD_OPT_HEAD_PER_WAVE, group)     # token-major: a ring per wave, `group` KV heads per workgroup
     rng = np.random.default_rng(77)
     U = 300
     lp = rng.integers(0, 700, size=U).tolist()
     lo = rng.integers(0, 500, size=U).tolist()
     lp[3] = lo[3] = 0
     lp[7], lo[8] = 5000, 3000                       # rows longer than the short-row rule allows
-    wl = workloads.random_case(108, torch.bfloat16, U, 16, 8, 128, lp, lo, device=DEV, layout="hnd")
+    wl = workloads.random_case(108, torch.bfloat16, U, 16, 8, 128, lp, lo, device=DEV, layout=layout)
     builds0, _ = own.spd_get_schedule_stats()
     check_against_oracle(own, wl)
     builds1, _ = own.spd_get_schedule_stats()
-    assert builds1 - builds0 == 4          # the separate calls' schedules and the fused step's
+    # the separate calls' schedules and, in the head-major mapping, the fused step's own
+    assert builds1 - builds0 == (4 if group == 0 else 2)
     own.close()
 
 
