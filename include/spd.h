@@ -133,7 +133,8 @@ int spd_last_hip_error(const spd_ctx *ctx);
 enum {
     SPD_OPT_HEAD_PER_WAVE = 0,    /* -1 (default): head-per-wave mapping for large token-major views; 0 never; 1 whenever
                                      the layout allows it; 2..8 the same, with at most that many KV heads per workgroup */
-    SPD_OPT_TARGET_WG_PER_CU = 1, /* pieces per compute unit that count as one resident round (default 2)              */
+    SPD_OPT_TARGET_WG_PER_CU = 1, /* pieces per compute unit that count as one resident round for an owner of a fused
+                                     step (default 2); a call for one owner alone takes half as many again          */
     SPD_OPT_NO_SPLIT_MAX = 2,     /* rows up to this many tokens are cut into one-step-per-wave chunks if all of them
                                      fit the device at once (default 768)                                          */
     SPD_OPT_CHUNK_MAX = 3,        /* tokens per piece when the work exceeds one resident round (default 16384)       */

@@ -344,6 +344,17 @@ int ensure_scratch(spd_ctx *ctx, Owner &own, size_t o_floats, size_t lse_floats)
     return SPD_OK;
 }
 
+// A call for one owner has the device to itself: its resident round is half as many pieces again as an owner's share of
+// a fused step (three per CU with the default two: the one-step-in-flight kernel then holds them all at once).
+// Measured as two parties, us per step, 2 against 3 per CU: workload 2's length law with 8 / 16 / 24 / 32 users
+// 26.6 / 39.7 / 50.5 / 64.1 against 26.0 / 39.2 / 49.8 / 62.2; 64 users and workloads 3, 4 and 5 the same either way.
+Tuning standalone_tuning(const spd_ctx *ctx)
+{
+    Tuning t = ctx->tuning;
+    t.target_wg_per_cu += t.target_wg_per_cu / 2;
+    return t;
+}
+
 // Validation, schedule lookup and scratch growth of one partial-attention call.
 int prepare_partial(spd_ctx *ctx, int which, const spd_shape *s, const void *q, const spd_kv_view *v, float *out,
                     float *lse, int mapping, const Tuning &tune, hipStream_t stream, CachedSchedule **e)
@@ -585,7 +596,7 @@ int partial_attention(spd_ctx *ctx, int which, const spd_shape *s, const void *q
         rc = validate_new_token(v, nt);
     if (rc != SPD_OK)
         return rc;
-    rc = prepare_partial(ctx, which, s, q, v, out, lse, -1, ctx->tuning, stream, &e);
+    rc = prepare_partial(ctx, which, s, q, v, out, lse, -1, standalone_tuning(ctx), stream, &e);
     if (rc != SPD_OK || !e)
         return rc;
     rc = launch_partial(ctx, which, e, v, out, lse, scratch_of(ctx->owner[which]), nullptr, nullptr, nullptr, nullptr,
@@ -1193,7 +1204,7 @@ try {
     if (!aligned16(a_in) || !aligned16(y))
         return SPD_ERR_ALIGN;
     CachedSchedule *eo = nullptr;
-    rc = prepare_partial(ctx, 1, shape, q, pub, a_out, lse_out, -1, ctx->tuning, stream, &eo);
+    rc = prepare_partial(ctx, 1, shape, q, pub, a_out, lse_out, -1, standalone_tuning(ctx), stream, &eo);
     if (rc != SPD_OK)
         return rc;
     rc = launch_partial(ctx, 1, eo, pub, a_out, lse_out, scratch_of(ctx->owner[1]), nullptr, nullptr, nullptr, nullptr,
