@@ -26,7 +26,8 @@
 // number of MFMAs per step differs (D/4 for S^T, D/2 for O^T at fp32, against D/16 and D/8 at 16 bits); P needs no
 // split.
 // Every K/V byte is read once per KV head (all G heads share the tile).
-// The four waves of a workgroup take interleaved 32-token steps and are combined through LDS.
+// The four waves of a workgroup take interleaved 32-token steps and are combined through LDS; the result rows of a
+// workgroup that crosses many rows wait in LDS too and are stored together (the result ring, below).
 #pragma once
 #include "common.hpp"
 
