@@ -81,6 +81,9 @@ CASES = [
     (torch.float16, 32, 8, 128, [40, 1, 700, 33], [1, 16, 17, 250], "hnd", False),
     (torch.float16, 32, 8, 128, [2000, 10, 0], [1500, 3000, 1], "nhd_hpw", "token_major"),
     (torch.float16, 32, 8, 64, [2000, 10, 0], [1500, 3000, 1], "nhd", True),
+    # many short rows: the pieces hold their result rows back (the result ring) while they append
+    (torch.bfloat16, 16, 8, 128, [(37 * u) % 400 for u in range(220)], [1 + (53 * u) % 300 for u in range(220)], "hnd", False),
+    (torch.bfloat16, 16, 8, 128, [(37 * u) % 400 for u in range(220)], [1 + (53 * u) % 300 for u in range(220)], "nhd_hpw4", "token_major"),
 ]
 
 

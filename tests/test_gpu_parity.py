@@ -347,6 +347,29 @@ def test_many_rows_per_piece_fused_step_and_result_ring(rows_opt, layout, group)
     own.close()
 
 
+@pytest.mark.parametrize("dtype,Hq,Hkv,d,layout,paged,group", [
+    (torch.float32, 8, 8, 64, "hnd", False, 0), (torch.float32, 12, 4, 128, "hnd", True, 0),
+    (torch.float16, 24, 8, 64, "hnd_exact", False, 0), (torch.bfloat16, 40, 8, 128, "hnd", True, 0),
+    (torch.bfloat16, 64, 8, 128, "hnd", False, 0),            # G = 8: fewer rows fit the ring
+    (torch.bfloat16, 128, 8, 128, "hnd", False, 0),           # G = 16: no room for a ring beside the staging tiles
+    (torch.float16, 12, 4, 64, "nhd", "token_major", 4), (torch.bfloat16, 48, 16, 128, "nhd", False, 8),
+])
+def test_result_ring_shapes(dtype, Hq, Hkv, d, layout, paged, group):
+    """The result ring over element types, head sizes, group sizes, storage modes and both mappings, with the KV
+    append in the fused step: many users with short rows, so that every piece holds rows back."""
+    import paper_2409_19134_amd as spd
+    own = spd.Context(0)
+    own.spd_set_option(spd.SPD_OPT_HEAD_PER_WAVE, group)
+    rng = np.random.default_rng(79)
+    U = 200
+    lp = rng.integers(0, 400, size=U).tolist()
+    lo = rng.integers(1, 300, size=U).tolist()
+    lp[5], lo[6] = 3000, 2000
+    wl = workloads.random_case(109, dtype, U, Hq, Hkv, d, lp, lo, device=DEV, layout=layout, paged=paged)
+    check_against_oracle(own, wl)
+    own.close()
+
+
 @pytest.mark.parametrize("d,Hq,Hkv", [(64, 8, 8), (64, 8, 2), (128, 8, 1), (128, 4, 4), (64, 16, 2)])
 @pytest.mark.parametrize("paged", [False, True])
 def test_fp32_shapes(ctx, d, Hq, Hkv, paged):
