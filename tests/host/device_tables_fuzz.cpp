@@ -77,6 +77,24 @@ int main()
         const int64_t n_pieces = (int64_t)S.piece_first.size() - 1;
         if (n_launched < n_pieces || n_launched > (int64_t)T.items.size())
             FAIL("launched %lld of %zu items, %lld pieces", (long long)n_launched, T.items.size(), (long long)n_pieces);
+        if (T.n_segments != (int64_t)S.items.size())
+            FAIL("segment count %lld of %zu", (long long)T.n_segments, S.items.size());
+        if (!hpw) {
+            // what the fused step asks before it looks a schedule up: one resident round of equal pieces, or not
+            int64_t rows = -1;
+            const int64_t round = single_round_pieces(Hkv, n_users, lens.data(), n_cus, tune, &rows);
+            int64_t rows_with_tokens = 0;
+            for (int u = 0; u < n_users; ++u)
+                rows_with_tokens += lens[(size_t)u] > 0 ? Hkv : 0;
+            if (rows != rows_with_tokens)
+                FAIL("rows %lld, expected %lld", (long long)rows, (long long)rows_with_tokens);
+            const int64_t resident = (int64_t)n_cus * tune.target_wg_per_cu;
+            if (round < 0 || round > std::max<int64_t>(resident, Hkv) || round % Hkv)
+                FAIL("round of %lld pieces with %lld resident", (long long)round, (long long)resident);
+            // (a cut moved to a row boundary can leave a piece without steps, so the schedule may hold fewer)
+            if (round > 0 && (n_pieces > round || (tune.seg_cost == 0 && n_pieces != round)))
+                FAIL("%lld pieces where a round of %lld was announced", (long long)n_pieces, (long long)round);
+        }
 
         // every item is reached exactly once: launched ones by their index, the others through one `next` link
         std::vector<int> reached(T.items.size(), 0);
