@@ -92,16 +92,20 @@ FLAG_GO, FLAG_STOP, FLAG_DONE0 = 0, 1, 8      # done[i] / ready[i] of worker i a
 SPIN_LIMIT_S = 120.0                           # every wait on a counter gives up after this long
 
 
-def spin_until(flags, idx, value, also_stop=False):
-    """Waits until flags[idx] >= value (or, with also_stop, the stop flag is up); False on time-out."""
+def spin_until(flags, idx, value, also_stop=False, proc=None):
+    """Waits until flags[idx] >= value (or, with also_stop, the stop flag is up); False on time-out, or when the
+    process `proc` that should raise the counter has ended."""
     t0 = time.perf_counter()
     n = 0
     while flags[idx] < value:
         if also_stop and flags[FLAG_STOP]:
             return True
         n += 1
-        if (n & 0x3fff) == 0 and time.perf_counter() - t0 > SPIN_LIMIT_S:
-            return False
+        if (n & 0x3fff) == 0:
+            if time.perf_counter() - t0 > SPIN_LIMIT_S:
+                return False
+            if proc is not None and proc.poll() is not None:
+                return bool(flags[idx] >= value)
     return True
 
 
@@ -455,8 +459,10 @@ def run_once(args):
         tp["flags"][FLAG_GO] = k
         so.ctx.spd_partial_attn_public_batched(so.shape, q, so.public, so.a_out, so.lse_out, main)
         for i, ev in enumerate(tp["ev_done"]):
-            if not spin_until(tp["flags"], FLAG_DONE0 + 2 * i, k):
-                raise RuntimeError(f"users' process {i} did not answer step {k}")
+            if not spin_until(tp["flags"], FLAG_DONE0 + 2 * i, k, proc=tp["procs"][i]):
+                raise RuntimeError(f"users' process {i} did not answer step {k}"
+                                   + (f" (it ended with status {tp['procs'][i].poll()})"
+                                      if tp["procs"][i].poll() is not None else ""))
             if ev is not None:
                 ev.wait(main)
         so.ctx.spd_lse_merge(so.a_in, so.lse_in, so.a_out, so.lse_out, so.y, so.lse, so.w_in, main)
