@@ -3,8 +3,10 @@
 The paper's deployment (section 4, step 3; section 5) runs each user's private attention in a process of its own and
 moves Q to it and (A_in, lse_in) back through the host (GLOO), which section 6.2 names as the dominant cost; section 5
 mentions device IPC as the alternative.  This module is that alternative for HIP: the service allocates q, A_in and
-lse_in once, exports them as IPC memory handles, the users' processes map them and write their partials in place, and
-IPC events order the two sides' streams - no byte of the message crosses the host.
+lse_in once, exports them as IPC memory handles, and the users' processes map them and write their partials in place:
+no byte of the message crosses the host.  What orders the two sides' streams is the caller's choice: IPC events
+(SharedEvent; some HIP runtimes hand out the handles and then refuse to record such an event - the error names the
+call), or a host-side handshake after each side has synchronised its own stream.
 
 Only marshalling: HIP runtime calls through ctypes on the runtime library the process already has loaded.
 """
