@@ -141,9 +141,9 @@ enum {
     SPD_OPT_SEG_COST = 4,         /* 32-token steps a piece gives up for every further row it reaches into (default 2) */
     SPD_OPT_HALF_SKEW = 5,        /* one resident round of pieces: per cent by which the half dispatched first is made
                                      longer and the other half shorter (default 12, 0..90)                          */
-    SPD_OPT_RESULT_ROWS = 6       /* result rows a workgroup of the head-major mapping may hold back in on-chip memory
-                                     and store together at the end of its piece (default 16, 0..16; fewer if they do
-                                     not fit); not part of the schedule: changing it rebuilds nothing               */
+    SPD_OPT_RESULT_ROWS = 6       /* result rows a workgroup (head-per-wave mapping: each of its waves) may hold back
+                                     in on-chip memory and store together at the end of its piece (default 32, 0..32;
+                                     fewer if they do not fit); not part of the schedule: changing it rebuilds nothing */
 };
 int spd_set_option(spd_ctx *ctx, int32_t option, int32_t value);
 int spd_get_option(spd_ctx *ctx, int32_t option, int32_t *value);
@@ -234,7 +234,7 @@ int spd_decode_step(spd_ctx *ctx, const spd_shape *shape, const void *q, const s
 
 /*
  * spd_decode_step for callers that cannot allocate device memory: code that is being recorded into a HIP graph,
- * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same results; but the split schedules, the
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same results; but the split schedules and the
  * chunk partials live in one fixed array of SPD_STATIC_SCRATCH_BYTES of device memory that
  * belongs to the library (one copy per GPU, held until the process ends), the schedules reach it through kernel
  * arguments, and the call makes no hipMalloc, hipFree, hipHostMalloc or copy command - it only launches kernels.
@@ -317,8 +317,10 @@ typedef struct spd_work_item {
 
 /*
  * Build the split schedule for `lens` (HOST, [n_users]) on a device with `n_compute_units` CUs, under the default
- * options (see spd_set_option) or what the SPD_* environment variables say at the time of the call.  The 32-token steps
- * of all rows, laid end to end, are cut into pieces of equal length (+-1 step).  Every token of every (user, KV head)
+ * options (see spd_set_option) or what the SPD_* environment variables say at the time of the call, as an owner of a
+ * fused step gets it (a call for one owner alone takes half as many pieces per compute unit again).  The 32-token steps
+ * of all rows, laid end to end, are cut into pieces of equal length (+-1 step, apart from what SPD_OPT_SEG_COST and
+ * SPD_OPT_HALF_SKEW take from or add to a piece).  Every token of every (user, KV head)
  * is covered by exactly one segment; segment boundaries inside a row are multiples of 32 tokens.
  * items may be NULL to query the count.  On return *n_items is the number of segments (written only if it fits
  * `capacity`, else SPD_ERR_WORKSPACE) and *chunk_tokens the tokens per piece (rounded up to 32).
