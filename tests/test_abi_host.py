@@ -236,6 +236,31 @@ def test_bench_refuses_more_than_one_gpu():
     assert "one GPU" in res.stderr
 
 
+def test_bench_traffic_figure_names_its_source_and_its_kernel():
+    """roofline.traffic is a stored measurement: the benchmark hands it out only for the kernel instance the stored
+    summary was made with, and says which file it read."""
+    import importlib.util
+    import re
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    spec = importlib.util.spec_from_file_location("bench_under_test", os.path.join(root, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    algorithmic = {2: 157405184, 3: 5299486720, 4: 2810568704, 5: 11444723712}   # 4096 B x the workload's tokens
+    for config, want in algorithmic.items():
+        rel = os.path.join("profiles", f"partial_kernel_config{config}_pmc_traffic.txt")
+        names = set(re.findall(r"spd::(partial_mfma_kernel<[^>]*>)", open(os.path.join(root, rel)).read()))
+        assert len(names) == 1, names
+        name = names.pop()
+        got, src = bench.measured_traffic(config, name)
+        assert src["file"] == rel and src["kernel_that_ran"] == name and src["kernel_in_summary"] == [name]
+        assert want <= got <= 1.05 * want, (config, got)          # every byte read once, little else
+        other = name.replace("<1,", "<2,")
+        got, src = bench.measured_traffic(config, other)
+        assert got is None and "another kernel instance" in src["why_null"]
+    got, src = bench.measured_traffic(1, "partial_mfma_kernel<0, 64, false, false, false, false>")
+    assert got is None and "no summary" in src["why_null"]
+
+
 def test_product_package_does_not_reach_the_oracle():
     """The oracle is test infrastructure: nothing under the package imports or loads it."""
     pkg = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "paper_2409_19134_amd")
