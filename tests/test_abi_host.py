@@ -261,6 +261,30 @@ def test_bench_traffic_figure_names_its_source_and_its_kernel():
     assert got is None and "no summary" in src["why_null"]
 
 
+def test_bench_handshake_wait_ends_when_the_other_process_has_ended():
+    """The two-process benchmark's host handshake: a wait on a counter gives up as soon as the process that should
+    raise it is gone (and not only at its time limit), and sees a counter that is already there."""
+    import importlib.util
+    import subprocess
+    import sys
+    import time
+    import numpy as np
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    spec = importlib.util.spec_from_file_location("bench_under_test", os.path.join(root, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    flags = np.zeros(64, dtype=np.int64)
+    gone = subprocess.Popen([sys.executable, "-c", "pass"])
+    gone.wait()
+    t0 = time.perf_counter()
+    assert bench.spin_until(flags, bench.FLAG_DONE0, 1, proc=gone) is False
+    assert time.perf_counter() - t0 < 10.0 < bench.SPIN_LIMIT_S
+    flags[bench.FLAG_DONE0] = 1
+    assert bench.spin_until(flags, bench.FLAG_DONE0, 1, proc=gone) is True
+    flags[bench.FLAG_STOP] = 1
+    assert bench.spin_until(flags, bench.FLAG_GO, 5, also_stop=True) is True      # the stop flag ends a worker's wait
+
+
 def test_product_package_does_not_reach_the_oracle():
     """The oracle is test infrastructure: nothing under the package imports or loads it."""
     pkg = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "paper_2409_19134_amd")
