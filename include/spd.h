@@ -134,16 +134,21 @@ enum {
     SPD_OPT_HEAD_PER_WAVE = 0,    /* -1 (default): head-per-wave mapping for large token-major views; 0 never; 1 whenever
                                      the layout allows it; 2..8 the same, with at most that many KV heads per workgroup */
     SPD_OPT_TARGET_WG_PER_CU = 1, /* pieces per compute unit that count as one resident round for an owner of a fused
-                                     step (default 2); a call for one owner alone takes half as many again          */
+                                     step (default 2); a call for one owner alone takes half as many again, unless
+                                     its round would then be made of pieces of 64 steps (2048 tokens) or less       */
     SPD_OPT_NO_SPLIT_MAX = 2,     /* rows up to this many tokens are cut into one-step-per-wave chunks if all of them
                                      fit the device at once (default 768)                                          */
     SPD_OPT_CHUNK_MAX = 3,        /* tokens per piece when the work exceeds one resident round (default 16384)       */
     SPD_OPT_SEG_COST = 4,         /* 32-token steps a piece gives up for every further row it reaches into (default 2) */
     SPD_OPT_HALF_SKEW = 5,        /* one resident round of pieces: per cent by which the half dispatched first is made
                                      longer and the other half shorter (default 12, 0..90)                          */
-    SPD_OPT_RESULT_ROWS = 6       /* result rows a workgroup (head-per-wave mapping: each of its waves) may hold back
+    SPD_OPT_RESULT_ROWS = 6,      /* result rows a workgroup (head-per-wave mapping: each of its waves) may hold back
                                      in on-chip memory and store together at the end of its piece (default 32, 0..32;
                                      fewer if they do not fit); not part of the schedule: changing it rebuilds nothing */
+    SPD_OPT_STEPS_IN_FLIGHT = 7   /* 32-token steps a wave of the streaming kernel has in flight: -1 (default) by the
+                                     size of the launch (two where the pieces outnumber the workgroup slots), 1 or 2
+                                     always - where the kernel has both forms: fp32 always takes one, 128-byte rows
+                                     and the head-per-wave mapping always two; not part of the schedule either       */
 };
 int spd_set_option(spd_ctx *ctx, int32_t option, int32_t value);
 int spd_get_option(spd_ctx *ctx, int32_t option, int32_t *value);

@@ -20,7 +20,7 @@ SPD_ERR_NULL, SPD_ERR_SHAPE, SPD_ERR_LEN, SPD_ERR_ALIGN = -1, -2, -3, -4
 SPD_ERR_WORKSPACE, SPD_ERR_HIP, SPD_ERR_NOMEM = -5, -6, -7
 SPD_F32, SPD_BF16, SPD_F16 = 0, 1, 2
 (SPD_OPT_HEAD_PER_WAVE, SPD_OPT_TARGET_WG_PER_CU, SPD_OPT_NO_SPLIT_MAX, SPD_OPT_CHUNK_MAX, SPD_OPT_SEG_COST,
- SPD_OPT_HALF_SKEW, SPD_OPT_RESULT_ROWS) = range(7)
+ SPD_OPT_HALF_SKEW, SPD_OPT_RESULT_ROWS, SPD_OPT_STEPS_IN_FLIGHT) = range(8)
 
 EXPORTED_SYMBOLS = (
     "spd_create", "spd_destroy", "spd_strerror", "spd_last_hip_error",

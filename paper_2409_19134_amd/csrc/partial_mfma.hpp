@@ -273,14 +273,15 @@ __host__ __device__ constexpr bool staging_fits(int D, int waves, int G) { retur
 // piece ends.  A row of the ring: G * D values, then G log-sum-exps, padded to a multiple of four floats.
 constexpr int kRingMaxRows = 32;
 __host__ __device__ constexpr int ring_row_floats(int D, int G) { return G * D + ((G + 3) & ~3); }
-// LDS bytes a head-major workgroup may use for staging and ring together: three workgroups (one step in flight) or two
-// (two steps) share a CU's 160 KB, and a workgroup may ask for 64 KB in all.
-__host__ __device__ constexpr size_t ring_lds_budget(bool prefetch) { return (prefetch ? 60 : 40) * 1024; }
-__host__ __device__ constexpr int ring_rows_that_fit(int D, int G, bool prefetch)
+// LDS bytes a head-major workgroup may use for staging and ring together: a CU's 160 KB are shared by the three
+// workgroups that the one-step kernel's registers allow, or by two (the two-step kernel, or a launch of no more than
+// two workgroups per CU), and a workgroup may ask for 64 KB in all.
+__host__ __device__ constexpr size_t ring_lds_budget(bool two_per_cu) { return (two_per_cu ? 60 : 40) * 1024; }
+__host__ __device__ constexpr int ring_rows_that_fit(int D, int G, bool two_per_cu)
 {
     const size_t staging = sizeof(float) * (size_t)kWaves * G * o_stride(D);
     const size_t row = sizeof(float) * (size_t)ring_row_floats(D, G);
-    const size_t n = staging >= ring_lds_budget(prefetch) ? 0 : (ring_lds_budget(prefetch) - staging) / row;
+    const size_t n = staging >= ring_lds_budget(two_per_cu) ? 0 : (ring_lds_budget(two_per_cu) - staging) / row;
     return n < 2 ? 0 : n > (size_t)kRingMaxRows ? kRingMaxRows : (int)n;  // a ring of one row holds nothing back
 }
 

@@ -100,8 +100,9 @@ inline int head_per_wave_waves(int Hkv, int most = 8)
 // The number of pieces build_schedule makes for the head-major mapping if they are exactly one resident round of
 // equal pieces (target_wg_per_cu per CU), else 0 (short rows cut into one-step chunks, less work than a round, or
 // several rounds).  Costs a pass over the lengths: the fused step asks before it looks its schedules up.
-// *rows: the (user, KV head) rows that hold tokens.
-inline int64_t single_round_pieces(int Hkv, int n_users, const int32_t *lens, int n_cus, const Tuning &tune, int64_t *rows)
+// *rows: the (user, KV head) rows that hold tokens; *steps (if asked for): the 32-token steps of one KV head.
+inline int64_t single_round_pieces(int Hkv, int n_users, const int32_t *lens, int n_cus, const Tuning &tune, int64_t *rows,
+                                   int64_t *steps_out = nullptr)
 {
     int64_t T = 0, short_chunks = 0;
     int max_len = 0;
@@ -113,6 +114,8 @@ inline int64_t single_round_pieces(int Hkv, int n_users, const int32_t *lens, in
         max_len = std::max(max_len, lens[u]);
         *rows += lens[u] > 0 ? Hkv : 0;
     }
+    if (steps_out)
+        *steps_out = T;
     const int64_t resident = (int64_t)std::max(1, n_cus) * tune.target_wg_per_cu;
     if (T == 0 || (max_len <= tune.no_split_max && short_chunks * Hkv <= resident))
         return 0;

@@ -85,6 +85,7 @@ struct spd_ctx {
     int32_t last_instance[6] = {-1, -1, -1, -1, -1, -1};  // template arguments of the partial kernel launched last
     Tuning tuning;           // what shapes the split schedules (SPD_OPT_*)
     int result_rows = spd::kRingMaxRows;  // SPD_OPT_RESULT_ROWS: result rows a workgroup holds back in LDS at most (0: none)
+    int steps_in_flight = -1;  // SPD_OPT_STEPS_IN_FLIGHT: 1 or 2 where the kernel has both forms, -1 by the size of the launch
     int head_per_wave = -1;  // SPD_OPT_HEAD_PER_WAVE: 0 never, 1 whenever the layout allows, 2..8 the same with that many heads per workgroup, -1 by the size rule
     std::vector<uint8_t> key_scratch;
     Owner owner[2];
@@ -345,19 +346,29 @@ int ensure_scratch(spd_ctx *ctx, Owner &own, size_t o_floats, size_t lse_floats)
 }
 
 // A call for one owner has the device to itself: its resident round is half as many pieces again as an owner's share of
-// a fused step (three per CU with the default two: the one-step-in-flight kernel then holds them all at once).
-// Measured as two parties, us per step, 2 against 3 per CU: workload 2's length law with 8 / 16 / 24 / 32 users
-// 26.6 / 39.7 / 50.5 / 64.1 against 26.0 / 39.2 / 49.8 / 62.2; 64 users and workloads 3, 4 and 5 the same either way.
-Tuning standalone_tuning(const spd_ctx *ctx)
+// a fused step (three per CU with the default two: the one-step-in-flight kernel then holds them all at once) - unless
+// that round would be made of short pieces (up to kShortPieceSteps steps at two per CU): those run faster as two per
+// CU.  Measured as two parties, us per step, 3 against 2 per CU (both on the one-step kernel): workload 2's length law
+// with 8 / 16 / 24 / 32 users 25.4 / 38.7 / 49.6 / 62.2 against 25.2 / 38.1 / 49.2 / 61.8; with 64 users (72 steps per
+// piece) 109.5 against 109.7, workloads 3 and 4 781.6 / 453.2 against 782.8 / 454.8.
+Tuning standalone_tuning(const spd_ctx *ctx, const spd_shape *s, const spd_kv_view *v, int hpw)
 {
-    Tuning t = ctx->tuning;
+    const Tuning base = ctx->tuning;
+    Tuning t = base;
     t.target_wg_per_cu += t.target_wg_per_cu / 2;
+    if (hpw || base.target_wg_per_cu < 2)
+        return t;
+    int64_t rows = 0, steps = 0;
+    const int64_t wide = single_round_pieces(s->n_kv_heads, v->n_users, v->lens, ctx->n_cus, t, &rows);
+    const int64_t narrow = single_round_pieces(s->n_kv_heads, v->n_users, v->lens, ctx->n_cus, base, &rows, &steps);
+    if (wide > 0 && narrow > 0 && steps <= (int64_t)kShortPieceSteps * (narrow / s->n_kv_heads))
+        return base;
     return t;
 }
 
 // Validation, schedule lookup and scratch growth of one partial-attention call.
 int prepare_partial(spd_ctx *ctx, int which, const spd_shape *s, const void *q, const spd_kv_view *v, float *out,
-                    float *lse, int mapping, const Tuning &tune, hipStream_t stream, CachedSchedule **e)
+                    float *lse, int mapping, const Tuning *tune, hipStream_t stream, CachedSchedule **e)
 {
     const int rc = spd_validate_partial(s, q, v, out, lse);
     if (rc != SPD_OK)
@@ -368,7 +379,8 @@ int prepare_partial(spd_ctx *ctx, int which, const spd_shape *s, const void *q, 
     Owner &own = ctx->owner[which];
     // mapping: KV heads per workgroup of the head-per-wave mapping, 0 = head-major, -1 = whatever suits this view on its own
     const int hpw = mapping >= 0 ? mapping : head_per_wave_layout(s, v) ? head_per_wave_choice(ctx, s, total_steps(v)) : 0;
-    const int rs = get_schedule(ctx, own, s, v, hpw, tune, stream, e);
+    // tune: the fused step's; none for a call that serves one owner alone
+    const int rs = get_schedule(ctx, own, s, v, hpw, tune ? *tune : standalone_tuning(ctx, s, v, hpw), stream, e);
     if (rs != SPD_OK)
         return rs;
     const int G = s->n_q_heads / s->n_kv_heads;
@@ -505,14 +517,22 @@ int launch_partial(spd_ctx *ctx, int which, const CachedSchedule *e0, const spd_
     L.args.Hq = s->n_q_heads;
     L.args.G = G;
     L.args.scale_log2e = c;
-    // Two steps in flight (PREFETCH) or one: clearly more pieces than the one-step kernel holds at once, three per CU
-    // (a few left over just start a little later), run on the two-step kernel, two per CU; so do launches whose pieces
-    // fit two per CU anyway (a wave then needs half as many dependent memory round trips).  Head-per-wave workgroups
-    // fit one per CU either way; with 128-byte rows a step is half the bytes, always two in flight; fp32 keeps one
-    // (at 128 channels a step is already 32 KB per wave and fills the registers).
+    // Two steps in flight (PREFETCH) or one.  Clearly more pieces than the one-step kernel holds at once, three per CU
+    // (a few left over just start a little later), run on the two-step kernel, two per CU: fewer workgroup starts and
+    // half as many dependent memory round trips per wave.  Everything that is resident at once runs on the one-step
+    // kernel, also what fits two per CU (us per fused step, two steps / one: 1 and 2 users of workload 2's length law
+    // 9.0 / 8.7 and 13.3 / 12.8; 16 users of 64-512 tokens 11.9 / 11.6; workload 4, 256 + 256 pieces, 433.3 / 430.8, with
+    // 128 users 225.7 / 222.0, with 8 query heads per KV head 452.0 / 446.2; 128 users of 64-512 tokens 50.8 / 50.0; 256
+    // such users 88.9 / 89.7; the standalone public call of workload 2 -0.3 us).  Head-per-wave workgroups fit one per
+    // CU either way; with 128-byte rows a step is half the bytes, always two in flight; fp32 keeps one (at 128
+    // channels a step is already 32 KB per wave and fills the registers).  SPD_OPT_STEPS_IN_FLIGHT overrides the size
+    // rule (tests run both kernels on the same small inputs).
     const int64_t cus = std::max(1, ctx->n_cus);
     const int row_bytes = D * elt_size(s->dtype);
-    const bool prefetch = !f32 && (hpw || row_bytes == 128 || n0 + n1 > cus * 4 || n0 + n1 <= cus * 2);
+    const bool by_size = ctx->steps_in_flight < 0 ? n0 + n1 > cus * 4 : ctx->steps_in_flight == 2;
+    const bool prefetch = !f32 && (hpw || row_bytes == 128 || by_size);
+    // no more than two workgroups on a CU, whether the registers or the launch see to that: the larger LDS share
+    const bool two_per_cu = prefetch || n0 + n1 <= cus * 2;
     // Result rows wait in LDS for the end of their piece (see the result ring in partial_mfma.hpp) - where a piece
     // has rows to wait for: with fewer than three segments per piece on average the ring only adds its copy (the
     // headline workload, 1.3 segments per piece: +0.4 us).  The head-per-wave mapping has fewer, wider segments and
@@ -521,7 +541,7 @@ int launch_partial(spd_ctx *ctx, int which, const CachedSchedule *e0, const spd_
     int ring_rows = 0;
     const int min_x2 = hpw ? 3 : 6;  // twice the segments per piece
     if (2 * segments >= min_x2 * (n0 + n1) && L.lds > 0)  // (head per wave without its staging tiles has no ring either)
-        ring_rows = std::min(ctx->result_rows, hpw ? spd::hpw_ring_rows_that_fit(D, G, waves) : spd::ring_rows_that_fit(D, G, prefetch));
+        ring_rows = std::min(ctx->result_rows, hpw ? spd::hpw_ring_rows_that_fit(D, G, waves) : spd::ring_rows_that_fit(D, G, two_per_cu));
     L.lds += (uint32_t)(ring_rows * sizeof(float) * (hpw ? (size_t)spd::hpw_ring_row_floats(D, G) * waves : (size_t)spd::ring_row_floats(D, G)));
     L.args.ring_rows = ring_rows;
     const bool ok = with_value<SPD_F32, SPD_BF16, SPD_F16>(s->dtype, [&](auto dt) {
@@ -596,7 +616,7 @@ int partial_attention(spd_ctx *ctx, int which, const spd_shape *s, const void *q
         rc = validate_new_token(v, nt);
     if (rc != SPD_OK)
         return rc;
-    rc = prepare_partial(ctx, which, s, q, v, out, lse, -1, standalone_tuning(ctx), stream, &e);
+    rc = prepare_partial(ctx, which, s, q, v, out, lse, -1, nullptr, stream, &e);
     if (rc != SPD_OK || !e)
         return rc;
     rc = launch_partial(ctx, which, e, v, out, lse, scratch_of(ctx->owner[which]), nullptr, nullptr, nullptr, nullptr,
@@ -832,6 +852,9 @@ int spd_create(spd_ctx **out, int hip_device)
     ctx->device = hip_device;
     ctx->tuning = tuning_from_env();
     ctx->result_rows = std::min(spd::kRingMaxRows, env_int("SPD_RESULT_ROWS", spd::kRingMaxRows, 0));
+    ctx->steps_in_flight = env_int("SPD_STEPS_IN_FLIGHT", -1, 1);
+    if (ctx->steps_in_flight > 2)
+        ctx->steps_in_flight = -1;
     ctx->head_per_wave = env_int("SPD_HEAD_PER_WAVE", -1, 0);
     if (ctx->head_per_wave > 8)
         ctx->head_per_wave = -1;
@@ -884,6 +907,7 @@ int32_t *option_slot(spd_ctx *ctx, int32_t option)
     switch (option) {
     case SPD_OPT_HEAD_PER_WAVE: return &ctx->head_per_wave;
     case SPD_OPT_RESULT_ROWS: return &ctx->result_rows;
+    case SPD_OPT_STEPS_IN_FLIGHT: return &ctx->steps_in_flight;
     case SPD_OPT_TARGET_WG_PER_CU: return &ctx->tuning.target_wg_per_cu;
     case SPD_OPT_NO_SPLIT_MAX: return &ctx->tuning.no_split_max;
     case SPD_OPT_CHUNK_MAX: return &ctx->tuning.chunk_max;
@@ -905,6 +929,7 @@ int spd_set_option(spd_ctx *ctx, int32_t option, int32_t value)
     switch (option) {
     case SPD_OPT_HEAD_PER_WAVE: ok = value >= -1 && value <= 8; break;
     case SPD_OPT_RESULT_ROWS: ok = value >= 0 && value <= spd::kRingMaxRows; break;
+    case SPD_OPT_STEPS_IN_FLIGHT: ok = value == -1 || value == 1 || value == 2; break;
     case SPD_OPT_SEG_COST: ok = value >= 0 && value <= (1 << 20); break;
     case SPD_OPT_HALF_SKEW: ok = value >= 0 && value <= 90; break;
     default: ok = value >= 1 && value <= (1 << 30); break;
@@ -1101,10 +1126,10 @@ try {
     CachedSchedule *ep = nullptr, *eo = nullptr;
     const int hpw = fused_step_mapping(ctx, shape, priv, pub);
     const Tuning tune = fused_step_tuning(ctx, shape, priv, pub, hpw);
-    rc = prepare_partial(ctx, 0, shape, q, priv, a_in, lse_in, hpw, tune, stream, &ep);
+    rc = prepare_partial(ctx, 0, shape, q, priv, a_in, lse_in, hpw, &tune, stream, &ep);
     if (rc != SPD_OK)
         return rc;
-    rc = prepare_partial(ctx, 1, shape, q, pub, a_out, lse_out, hpw, tune, stream, &eo);  // an upload, if any, stays on `stream`
+    rc = prepare_partial(ctx, 1, shape, q, pub, a_out, lse_out, hpw, &tune, stream, &eo);  // an upload, if any, stays on `stream`
     if (rc != SPD_OK)
         return rc;
     return launch_decode_step(ctx, shape, q, priv, pub, nt, ep, eo, scratch_of(ctx->owner[0]), scratch_of(ctx->owner[1]), a_in,
@@ -1204,7 +1229,7 @@ try {
     if (!aligned16(a_in) || !aligned16(y))
         return SPD_ERR_ALIGN;
     CachedSchedule *eo = nullptr;
-    rc = prepare_partial(ctx, 1, shape, q, pub, a_out, lse_out, -1, standalone_tuning(ctx), stream, &eo);
+    rc = prepare_partial(ctx, 1, shape, q, pub, a_out, lse_out, -1, nullptr, stream, &eo);
     if (rc != SPD_OK)
         return rc;
     rc = launch_partial(ctx, 1, eo, pub, a_out, lse_out, scratch_of(ctx->owner[1]), nullptr, nullptr, nullptr, nullptr,

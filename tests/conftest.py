@@ -34,3 +34,19 @@ def mapping_of(ctx):
         return layout
     yield apply
     ctx.spd_set_option(spd.SPD_OPT_HEAD_PER_WAVE, -1)
+
+
+@pytest.fixture
+def in_flight(ctx):
+    """The streaming kernel exists with one and with two 32-token steps in flight per wave, and the library picks by
+    the size of the launch (small test inputs get the one-step form): in_flight(2) / in_flight(1) force a form through
+    the option SPD_OPT_STEPS_IN_FLIGHT of the test module's context `ctx` - where the kernel has both (fp32 always
+    takes one, 128-byte rows and the head-per-wave mapping always two) - and in_flight(None) leaves the choice to the
+    library."""
+    import paper_2409_19134_amd as spd
+
+    def apply(steps):
+        ctx.spd_set_option(spd.SPD_OPT_STEPS_IN_FLIGHT, -1 if steps is None else steps)
+    yield apply
+    ctx.spd_set_option(spd.SPD_OPT_STEPS_IN_FLIGHT, -1)
+

@@ -119,8 +119,10 @@ def test_append_with_larger_pages(ctx, page_tokens, paged, fused):
 
 @pytest.mark.parametrize("dtype,Hq,Hkv,d,lp,lo,layout,paged", CASES)
 @pytest.mark.parametrize("fused", [False, True, "two_parties"])
-def test_append_then_attend(ctx, mapping_of, dtype, Hq, Hkv, d, lp, lo, layout, paged, fused):
+@pytest.mark.parametrize("steps", [None, 2])
+def test_append_then_attend(ctx, mapping_of, in_flight, dtype, Hq, Hkv, d, lp, lo, layout, paged, fused, steps):
     layout = mapping_of(layout)
+    in_flight(steps)
     import paper_2409_19134_amd as spd
     U = len(lp)
     wl = workloads.random_case(211, dtype, U, Hq, Hkv, d, lp, lo, device=DEV, layout=layout, paged=paged)

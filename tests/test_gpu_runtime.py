@@ -531,3 +531,56 @@ def test_contexts_give_their_memory_back():
     torch.cuda.synchronize()
     free1, _ = torch.cuda.mem_get_info()
     assert free0 - free1 < 32 << 20, f"{(free0 - free1) >> 20} MiB not returned after 40 contexts"
+
+
+def test_steps_in_flight_option_picks_the_kernel_form():
+    """SPD_OPT_STEPS_IN_FLIGHT: the library picks the streaming kernel's form by the size of the launch (a small input
+    runs with one step in flight, a launch of many more pieces than workgroup slots with two), the option forces either
+    where the kernel has both, and the results agree with the oracle every time."""
+    import paper_2409_19134_amd as spd
+    ctx = spd.Context(0)
+    small = workloads.random_case(821, torch.bfloat16, 3, 32, 8, 128, [700, 33, 1500], [40, 0, 129], device=DEV, layout="hnd")
+    want = _oracle_y(small)
+
+    def form(wl, expect_two):
+        step = spd.DecodeStep.from_workload(ctx, wl)
+        step.run_fused(wl.q)
+        torch.cuda.synchronize()
+        name = ctx.spd_last_kernel_name()
+        assert name.split(", ")[3] == ("true" if expect_two else "false"), name
+        return step
+
+    assert ctx.spd_get_option(spd.SPD_OPT_STEPS_IN_FLIGHT) == -1
+    assert _err(form(small, False), want) <= 2e-3
+    ctx.spd_set_option(spd.SPD_OPT_STEPS_IN_FLIGHT, 2)
+    assert ctx.spd_get_option(spd.SPD_OPT_STEPS_IN_FLIGHT) == 2
+    assert _err(form(small, True), want) <= 2e-3
+    ctx.spd_set_option(spd.SPD_OPT_STEPS_IN_FLIGHT, 1)
+    assert _err(form(small, False), want) <= 2e-3
+    for bad in (0, 3, -2):
+        with pytest.raises(spd.binding.SpdError) as e:
+            ctx.spd_set_option(spd.SPD_OPT_STEPS_IN_FLIGHT, bad)
+        assert e.value.code == spd.binding.SPD_ERR_LEN
+    assert ctx.spd_get_option(spd.SPD_OPT_STEPS_IN_FLIGHT) == 1
+
+    # forms the option cannot change: fp32 has one step in flight, 128-byte rows always two
+    f32 = workloads.random_case(822, torch.float32, 2, 8, 4, 128, [300, 77], [40, 5], device=DEV, layout="hnd")
+    ctx.spd_set_option(spd.SPD_OPT_STEPS_IN_FLIGHT, 2)
+    assert _err(form(f32, False), _oracle_y(f32)) <= 1e-5
+    d64 = workloads.random_case(823, torch.bfloat16, 2, 16, 4, 64, [300, 77], [40, 5], device=DEV, layout="hnd")
+    ctx.spd_set_option(spd.SPD_OPT_STEPS_IN_FLIGHT, 1)
+    assert _err(form(d64, True), _oracle_y(d64)) <= 2e-3
+
+    # by size: with pieces of at most 128 tokens, many users with short rows make several rounds of pieces, which take
+    # the two-step form; forced to one step the same launch gives the same answer
+    ctx.spd_set_option(spd.SPD_OPT_STEPS_IN_FLIGHT, -1)
+    ctx.spd_set_option(spd.SPD_OPT_CHUNK_MAX, 128)
+    rng = np.random.default_rng(5)
+    U = 300
+    big = workloads.random_case(824, torch.bfloat16, U, 16, 8, 128, rng.integers(1, 300, U).tolist(),
+                                rng.integers(0, 40, U).tolist(), device=DEV, layout="hnd_exact")
+    want_big = _oracle_y(big)
+    assert _err(form(big, True), want_big) <= 2e-3
+    ctx.spd_set_option(spd.SPD_OPT_STEPS_IN_FLIGHT, 1)
+    assert _err(form(big, False), want_big) <= 2e-3
+    ctx.close()
