@@ -81,13 +81,16 @@ int main()
             FAIL("segment count %lld of %zu", (long long)T.n_segments, S.items.size());
         if (!hpw) {
             // what the fused step asks before it looks a schedule up: one resident round of equal pieces, or not
-            int64_t rows = -1;
-            const int64_t round = single_round_pieces(Hkv, n_users, lens.data(), n_cus, tune, &rows);
-            int64_t rows_with_tokens = 0;
-            for (int u = 0; u < n_users; ++u)
+            int64_t rows = -1, steps = -1;
+            const int64_t round = single_round_pieces(Hkv, n_users, lens.data(), n_cus, tune, &rows, &steps);
+            int64_t rows_with_tokens = 0, steps_per_head = 0;
+            for (int u = 0; u < n_users; ++u) {
                 rows_with_tokens += lens[(size_t)u] > 0 ? Hkv : 0;
-            if (rows != rows_with_tokens)
-                FAIL("rows %lld, expected %lld", (long long)rows, (long long)rows_with_tokens);
+                steps_per_head += (lens[(size_t)u] + 31) / 32;
+            }
+            if (rows != rows_with_tokens || steps != steps_per_head)
+                FAIL("rows %lld, expected %lld; steps %lld, expected %lld", (long long)rows, (long long)rows_with_tokens,
+                     (long long)steps, (long long)steps_per_head);
             const int64_t resident = (int64_t)n_cus * tune.target_wg_per_cu;
             if (round < 0 || round > std::max<int64_t>(resident, Hkv) || round % Hkv)
                 FAIL("round of %lld pieces with %lld resident", (long long)round, (long long)resident);
